@@ -1,0 +1,346 @@
+"""Float64 CPU oracle for one token-sharded transformer layer (Cascade, Section 5).
+
+TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition that the HIP
+library is checked against.  It shares no code with the HIP path, is never
+imported by the product package, and may be used only from tests/, the smoke
+check and the benchmark's cpu_baseline leg.
+
+Two independent routes to the same result are written out:
+
+* layer_direct   -- the ordinary, unsharded pre-norm transformer layer.  Section 5
+                    (the exactness statement after the method's introduction, and
+                    the merge derivation of the Post-Pass subsection) says the
+                    sharded pipeline reproduces exactly this, so it is the
+                    definition of the result.
+* layer_sharded  -- Algorithm 1 step by step: Algorithm 2 (pre-pass) on every hidden
+                    shard, Algorithm 3 (attention-pass) on every (query-shard,
+                    key/value-shard) pair, Algorithm 4 (post-pass) on every hidden
+                    shard, then the residual and MLP.
+
+All arithmetic is float64 numpy; matmul (@) is the only library contraction used.
+
+Readings taken where the paper is silent or inconsistent (each is also listed in
+the design notes):
+  * a = scale * q k^T + s with an explicit scale (the paper prints none; scale=1
+    gives its formula literally, 1/sqrt(d) gives the standard layer).
+  * A query row that sees no key of S_k has m = -inf, e = 0, u = 0 and weight 0 in
+    the merge; exp(-inf - (-inf)) is never evaluated.
+  * The post-pass maximum n depends on the row only (Algorithm 4 line 3), not on k.
+  * u has shape (H, rows, d) (Appendix D), not (H, N, |S_k|) as Table 2 prints.
+  * mlp(h + o) is the rest of a pre-norm block: h1 = h + o, out = h1 + FFN(norm2(h1)).
+  * The causal mask compares original token positions: s[x, y] = 0 if pos[y] <= pos[x]
+    else -inf; it is the same for every head.
+  * Rows inside a shard are in ascending original index (Attention-Pass subsection).
+  * Query head h reads key/value head h // (H / H_KV) (repeat_kv of Algorithm 3).
+  * R = S (the option named at the start of the AttnNode security subsection).
+"""
+import numpy as np
+from scipy.special import erf
+
+F64 = np.float64
+
+
+# --------------------------------------------------------------------------- sharding
+def shard_index_lists(token_to_shard, n_shards):
+    """Section 5.1: the partition {S_j}; each list ascending (Attention-Pass subsection)."""
+    a = np.asarray(token_to_shard)
+    if a.ndim != 1 or (a.size and (a.min() < 0 or a.max() >= n_shards)):
+        raise ValueError("token_to_shard must be 1-D with values in [0, n_shards)")
+    return [np.flatnonzero(a == j) for j in range(n_shards)]
+
+
+def shard_plan(token_to_shard, n_shards):
+    """Packed order: shards in shard-id order, rows ascending inside a shard.
+
+    Returns offsets[n_shards+1], perm[N] (packed row -> original index) and
+    inv_perm[N] (original index -> packed row).
+    """
+    lists = shard_index_lists(token_to_shard, n_shards)
+    sizes = np.array([len(x) for x in lists], dtype=np.int64)
+    offsets = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    perm = (np.concatenate(lists) if lists else np.zeros(0)).astype(np.int32)
+    inv_perm = np.empty_like(perm)
+    inv_perm[perm] = np.arange(perm.size, dtype=np.int32)
+    return offsets, perm, inv_perm
+
+
+def cdelta_assignment(seq_len, c, delta):
+    """(c, delta)-sharding (Definition in Section 6): 0-based token t belongs to the
+    shard (t mod delta) div c; alpha = ceil(delta / c) shards."""
+    t = np.arange(seq_len)
+    return ((t % delta) // c).astype(np.int32)
+
+
+def m_split(index_list, m):
+    """m-split of a sorted hidden shard R_i into R_{i,1..m} (AttnNode security
+    subsection).  The worked N=18 example takes every m-th element of sorted R_i
+    starting at x, which is what is done here (the prose's stride 'delta' is in
+    token positions, not list indices, when m = c)."""
+    r = np.sort(np.asarray(index_list))
+    return [r[x::m] for x in range(m)]
+
+
+# --------------------------------------------------------------------------- per-token pieces
+def layer_norm(x, gain, bias, eps):
+    mu = x.mean(axis=-1, keepdims=True)
+    var = ((x - mu) ** 2).mean(axis=-1, keepdims=True)
+    y = (x - mu) / np.sqrt(var + eps) * gain
+    return y + bias if bias is not None else y
+
+
+def rms_norm(x, gain, eps):
+    ms = (x * x).mean(axis=-1, keepdims=True)
+    return x / np.sqrt(ms + eps) * gain
+
+
+def norm(x, kind, gain, bias, eps):
+    if kind == "layernorm":
+        return layer_norm(x, gain, bias, eps)
+    if kind == "rmsnorm":
+        return rms_norm(x, gain, eps)
+    raise ValueError(kind)
+
+
+def gelu_erf(x):
+    return 0.5 * x * (1.0 + erf(x / np.sqrt(2.0)))
+
+
+def gelu_tanh(x):
+    return 0.5 * x * (1.0 + np.tanh(np.sqrt(2.0 / np.pi) * (x + 0.044715 * x ** 3)))
+
+
+def silu(x):
+    return x / (1.0 + np.exp(-x))
+
+
+def linear(x, w, b=None):
+    y = x @ w.T
+    return y + b if b is not None else y
+
+
+def rope(x, pos, theta):
+    """Rotary embedding, half-split pairing: element i pairs with i + d/2 and is
+    rotated by pos * theta**(-2i/d).  x is (..., rows, d); pos is (rows,), the
+    ORIGINAL token positions of those rows (Pre-Pass subsection: p^{R_i} depends
+    only on the index set R_i)."""
+    d = x.shape[-1]
+    half = d // 2
+    inv_freq = theta ** (-2.0 * np.arange(half, dtype=F64) / d)
+    ang = np.asarray(pos, dtype=F64)[:, None] * inv_freq[None, :]
+    c, s = np.cos(ang), np.sin(ang)
+    x1, x2 = x[..., :half], x[..., half:]
+    return np.concatenate([x1 * c - x2 * s, x2 * c + x1 * s], axis=-1)
+
+
+def ffn(x, w, act):
+    if act == "swiglu":
+        return linear(silu(linear(x, w["w_gate"])) * linear(x, w["w_up"]), w["w_down"])
+    g = gelu_erf if act == "gelu" else gelu_tanh
+    return linear(g(linear(x, w["w_up"], w.get("b_up"))), w["w_down"], w.get("b_down"))
+
+
+def mask_block(pos_q, pos_k, mask_kind):
+    """Additive mask s[x, y] for query positions pos_q and key positions pos_k."""
+    if mask_kind == "none":
+        return np.zeros((len(pos_q), len(pos_k)), dtype=F64)
+    vis = np.asarray(pos_k)[None, :] <= np.asarray(pos_q)[:, None]
+    return np.where(vis, 0.0, -np.inf)
+
+
+def _f64_weights(w):
+    return {k: np.asarray(v, dtype=F64) for k, v in w.items()}
+
+
+def _split_heads(x, n_heads, d):
+    # (rows, n_heads*d) -> (n_heads, rows, d)
+    return x.reshape(x.shape[0], n_heads, d).transpose(1, 0, 2)
+
+
+# --------------------------------------------------------------------------- Algorithm 2
+def pre_pass(h_rows, pos_rows, w, cfg):
+    """Algorithm 2 on one hidden shard: norm, q/k/v projection, rotary embedding."""
+    x = norm(h_rows, cfg.norm, w["norm1_g"], w.get("norm1_b"), cfg.eps)
+    q = _split_heads(linear(x, w["wq"], w.get("bq")), cfg.n_heads, cfg.head_dim)
+    k = _split_heads(linear(x, w["wk"], w.get("bk")), cfg.n_kv_heads, cfg.head_dim)
+    v = _split_heads(linear(x, w["wv"], w.get("bv")), cfg.n_kv_heads, cfg.head_dim)
+    if cfg.rope:
+        q = rope(q, pos_rows, cfg.rope_theta)
+        k = rope(k, pos_rows, cfg.rope_theta)
+    return q, k, v
+
+
+# --------------------------------------------------------------------------- Algorithm 3
+def attn_pass(q, k, v, s, scale=1.0):
+    """Algorithm 3 for one (query-shard, key/value-shard) pair.
+
+    q (H, nq, d); k, v (H_KV, nk, d); s (nq, nk) additive mask.
+    Returns m (H, nq), e (H, nq), u (H, nq, d) with u the NORMALISED partial output.
+    """
+    H, nq, d = q.shape
+    Hkv, nk, _ = k.shape
+    if nk == 0:
+        return np.full((H, nq), -np.inf), np.zeros((H, nq)), np.zeros((H, nq, d))
+    rep = H // Hkv
+    k = np.repeat(k, rep, axis=0)                       # line 1: repeat_kv
+    v = np.repeat(v, rep, axis=0)                       # line 2
+    a = scale * (q @ k.transpose(0, 2, 1)) + s[None]    # line 3
+    m = a.max(axis=-1)                                  # line 4
+    m_sub = np.where(np.isfinite(m), m, 0.0)            # rows with no visible key: exp(-inf - 0) = 0
+    a = np.exp(a - m_sub[..., None])                    # line 5
+    e = a.sum(axis=-1)                                  # line 6
+    e_div = np.where(e > 0.0, e, 1.0)
+    a = a / e_div[..., None]                            # line 7
+    u = a @ v                                           # line 8
+    return m, e, u
+
+
+# --------------------------------------------------------------------------- Algorithm 4 (lines 1-8)
+def post_pass_merge(ms, es, us):
+    """Combine beta partials of the same query rows (Algorithm 4 before o_proj).
+
+    ms, es: sequences of (H, rows); us: sequence of (H, rows, d), normalised u.
+    Returns o (H, rows, d) = sum_k exp(m_k - n) e_k u_k / sum_k exp(m_k - n) e_k.
+    """
+    o = np.zeros_like(us[0])
+    w = np.zeros_like(es[0])
+    n = ms[0]
+    for m in ms[1:]:
+        n = np.maximum(n, m)
+    n_sub = np.where(np.isfinite(n), n, 0.0)
+    for m, e, u in zip(ms, es, us):
+        coef = np.where(np.isfinite(m), np.exp(m - n_sub), 0.0) * e
+        w = w + coef
+        o = o + coef[..., None] * u
+    w_div = np.where(w > 0.0, w, 1.0)
+    return o / w_div[..., None]
+
+
+# --------------------------------------------------------------------------- all pairs on given q, k, v
+def partial_attention_all_pairs(q, k, v, token_to_shard, n_shards, positions=None,
+                                scale=1.0, mask_kind="causal"):
+    """Algorithm 3 on every (j, k) pair for one sequence.
+
+    q (H, N, d), k, v (H_KV, N, d) in ORIGINAL token order.  Outputs are in packed
+    row order: m, e (H, beta, N) indexed [head, kv-shard, packed query row];
+    u (beta, H, N, d) normalised.
+    """
+    q, k, v = (np.asarray(t, dtype=F64) for t in (q, k, v))
+    H, N, d = q.shape
+    pos = np.arange(N) if positions is None else np.asarray(positions)
+    lists = shard_index_lists(token_to_shard, n_shards)
+    offsets, _, _ = shard_plan(token_to_shard, n_shards)
+    m = np.full((H, n_shards, N), -np.inf)
+    e = np.zeros((H, n_shards, N))
+    u = np.zeros((n_shards, H, N, d))
+    for j, Sj in enumerate(lists):
+        r0, r1 = offsets[j], offsets[j + 1]
+        for kk, Sk in enumerate(lists):
+            s = mask_block(pos[Sj], pos[Sk], mask_kind)
+            mj, ej, uj = attn_pass(q[:, Sj], k[:, Sk], v[:, Sk], s, scale)
+            m[:, kk, r0:r1], e[:, kk, r0:r1], u[kk, :, r0:r1] = mj, ej, uj
+    return m, e, u
+
+
+def lse_merge_all(m, e, u):
+    """Algorithm 4 lines 1-8 over the kv-shard axis of packed partials.
+    m, e (H, beta, N); u (beta, H, N, d) normalised.  Returns o (N, H*d), packed rows."""
+    beta = m.shape[1]
+    o = post_pass_merge([m[:, kk] for kk in range(beta)], [e[:, kk] for kk in range(beta)],
+                        [u[kk] for kk in range(beta)])
+    H, N, d = o.shape
+    return o.transpose(1, 0, 2).reshape(N, H * d)
+
+
+# --------------------------------------------------------------------------- the two layer routes
+def layer_direct(h, w, cfg, positions=None, mask_kind="causal", scale=None, rows=None):
+    """The unsharded layer, one sequence h (N, D).  With rows given, only those
+    output rows are computed (keys and values still come from every token)."""
+    w = _f64_weights(w)
+    h = np.asarray(h, dtype=F64)
+    N = h.shape[0]
+    pos = np.arange(N) if positions is None else np.asarray(positions)
+    scale = cfg.scale if scale is None else scale
+    rows = np.arange(N) if rows is None else np.asarray(rows)
+    H, Hkv, d = cfg.n_heads, cfg.n_kv_heads, cfg.head_dim
+
+    x = norm(h, cfg.norm, w["norm1_g"], w.get("norm1_b"), cfg.eps)
+    k = _split_heads(linear(x, w["wk"], w.get("bk")), Hkv, d)
+    v = _split_heads(linear(x, w["wv"], w.get("bv")), Hkv, d)
+    q = _split_heads(linear(x[rows], w["wq"], w.get("bq")), H, d)
+    if cfg.rope:
+        q = rope(q, pos[rows], cfg.rope_theta)
+        k = rope(k, pos, cfg.rope_theta)
+    s = mask_block(pos[rows], pos, mask_kind)
+    o = np.empty((len(rows), H * d))
+    rep = H // Hkv
+    for hh in range(H):
+        a = scale * (q[hh] @ k[hh // rep].T) + s
+        a = a - a.max(axis=-1, keepdims=True)
+        p = np.exp(a)
+        p = p / p.sum(axis=-1, keepdims=True)
+        o[:, hh * d:(hh + 1) * d] = p @ v[hh // rep]
+    h1 = h[rows] + linear(o, w["wo"], w.get("bo"))
+    x2 = norm(h1, cfg.norm, w["norm2_g"], w.get("norm2_b"), cfg.eps)
+    return h1 + ffn(x2, w, cfg.act)
+
+
+def layer_sharded(h, w, cfg, token_to_shard, n_shards, positions=None, mask_kind="causal",
+                  scale=None, return_partials=False):
+    """Algorithm 1 for one sequence h (N, D); output in original token order."""
+    w = _f64_weights(w)
+    h = np.asarray(h, dtype=F64)
+    N = h.shape[0]
+    pos = np.arange(N) if positions is None else np.asarray(positions)
+    scale = cfg.scale if scale is None else scale
+    lists = shard_index_lists(token_to_shard, n_shards)
+
+    # pre-pass on every hidden shard (Algorithm 1 lines 1-2)
+    qkv = [pre_pass(h[R], pos[R], w, cfg) for R in lists]
+
+    # attention-pass on every pair (Algorithm 1 lines 8-9); with R = S the routing of
+    # Algorithm 1 line 4 hands AttnNode_jk the whole of shard j's q and shard k's k, v.
+    partial = {}
+    for j, Sj in enumerate(lists):
+        for kk, Sk in enumerate(lists):
+            s = mask_block(pos[Sj], pos[Sk], mask_kind)
+            partial[(j, kk)] = attn_pass(qkv[j][0], qkv[kk][1], qkv[kk][2], s, scale)
+
+    # post-pass, residual and MLP on every hidden shard (Algorithm 1 lines 15-17)
+    out = np.empty_like(h)
+    for i, R in enumerate(lists):
+        if len(R) == 0:
+            continue
+        ms = [partial[(i, kk)][0] for kk in range(n_shards)]
+        es = [partial[(i, kk)][1] for kk in range(n_shards)]
+        us = [partial[(i, kk)][2] for kk in range(n_shards)]
+        o = post_pass_merge(ms, es, us)                               # Algorithm 4 lines 1-8
+        o = o.transpose(1, 0, 2).reshape(len(R), -1)
+        h1 = h[R] + linear(o, w["wo"], w.get("bo"))                   # line 9 + residual
+        x2 = norm(h1, cfg.norm, w["norm2_g"], w.get("norm2_b"), cfg.eps)
+        out[R] = h1 + ffn(x2, w, cfg.act)
+    if return_partials:
+        return out, partial
+    return out
+
+
+def layer_direct_batch(h, w, cfg, **kw):
+    return np.stack([layer_direct(h[b], w, cfg, **kw) for b in range(h.shape[0])])
+
+
+def layer_sharded_batch(h, w, cfg, token_to_shard, n_shards, **kw):
+    return np.stack([layer_sharded(h[b], w, cfg, token_to_shard, n_shards, **kw)
+                     for b in range(h.shape[0])])
+
+
+# --------------------------------------------------------------------------- cost model
+def comm_bytes(beta, F, d, H, Hkv, N):
+    """Equation 1 and its two halves (Appendix D): stage A ships q, k, v rows to the
+    AttnNodes, stage B ships m, e, u rows back."""
+    stage_a = beta * F * d * (H + 2 * Hkv) * N
+    stage_b = beta * F * (d + 2) * H * N
+    return stage_a + stage_b, stage_a, stage_b
+
+
+def overhead_ops(H, N, d):
+    """Appendix C: extra operations over the vanilla pass: (a) merge ~ H N d, (b) expsums ~ H N^2."""
+    return H * N * d, H * N * N
