@@ -1,0 +1,231 @@
+/*
+ * libcascade: one token-sharded transformer layer on one MI355X (gfx950).
+ *
+ * The library computes the single-layer forward pass of Cascade (Section 5,
+ * Algorithm 1) with every shard resident on one GPU: per-shard linear layers
+ * (Algorithm 2, Algorithm 4 line 9, the MLP of Algorithm 1 line 17), partial
+ * attention for every (query-shard, key/value-shard) pair with row maxima m and
+ * subtract-max exponential sums e (Algorithm 3), and the log-sum-exp merge of
+ * the partials (Algorithm 4 lines 1-8).  This build uses R = S (one token to
+ * shard assignment for hiddens, queries and keys/values).
+ *
+ * Conventions
+ *  - Every function returns an int32 status (CASCADE_OK = 0).  Nothing aborts,
+ *    throws or prints.  After CASCADE_EHIP, cascade_last_hip_error() returns the
+ *    HIP runtime code.
+ *  - Pointers are DEVICE pointers unless the name ends in _host.  The library
+ *    borrows them: the caller allocates and frees.  Tensor memory is never
+ *    allocated here; scratch comes from the caller's workspace.  Only
+ *    cascade_plan_create allocates (the index maps it owns).
+ *  - All work is enqueued on the caller's HIP stream (void* = hipStream_t) and
+ *    is asynchronous; there are no hidden synchronisations.
+ *  - Row-major everywhere; a weight matrix is [out_features, in_features].
+ *  - "Packed" row order: shards in shard-id order, rows inside a shard in
+ *    ascending original token index (the concatenation rule of the
+ *    Attention-Pass subsection).  perm[r] = original index of packed row r.
+ *  - dtype CASCADE_BF16: tensors are bf16, accumulation and m, e, u are fp32.
+ *    dtype CASCADE_F32: everything fp32.
+ *  - Empty shards are legal.  A query row that sees no key of a shard gets
+ *    m = -inf, e = 0, u = 0 and weight 0 in the merge.
+ */
+#ifndef CASCADE_H
+#define CASCADE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#if defined(__GNUC__)
+#define CASCADE_API __attribute__((visibility("default")))
+#else
+#define CASCADE_API
+#endif
+
+/* status codes */
+#define CASCADE_OK            0
+#define CASCADE_EINVAL        1   /* null pointer or negative / zero size               */
+#define CASCADE_ESHAPE        2   /* dimensions inconsistent with each other / the plan */
+#define CASCADE_EASSIGN       3   /* shard id outside [0, n_shards)                     */
+#define CASCADE_EUNSUPPORTED  4   /* dtype / head_dim / option not built                */
+#define CASCADE_EWORKSPACE    5   /* workspace missing or too small                     */
+#define CASCADE_EHIP          6   /* HIP runtime error                                  */
+
+#define CASCADE_F32   0
+#define CASCADE_BF16  1
+
+#define CASCADE_MASK_NONE    0
+#define CASCADE_MASK_CAUSAL  1   /* key visible iff position[key] <= position[query]   */
+
+#define CASCADE_ROWS_ORIGINAL  0 /* row t of a sequence is token t                     */
+#define CASCADE_ROWS_PACKED    1 /* row r of a sequence is token perm[r]               */
+
+#define CASCADE_U_UNNORMALISED 0 /* u~ = sum_s exp(a - m) v_s  (= e * u)               */
+#define CASCADE_U_NORMALISED   1 /* u  = softmax(a^{S_j S_k}) v^{S_k} (Algorithm 3)    */
+
+#define CASCADE_NORM_NONE      0
+#define CASCADE_NORM_LAYERNORM 1
+#define CASCADE_NORM_RMSNORM   2
+
+#define CASCADE_ACT_GELU_ERF   0
+#define CASCADE_ACT_GELU_TANH  1
+#define CASCADE_ACT_SWIGLU     2
+
+#define CASCADE_ATTN_FUSED        0 /* running merge in registers, no partials written */
+#define CASCADE_ATTN_MATERIALISED 1 /* partial_attn -> m, e, u~ in HBM -> lse_merge     */
+
+/* epilogue flags of cascade_shard_gemm (bit mask) */
+#define CASCADE_EPI_BIAS       1
+#define CASCADE_EPI_GELU_ERF   2
+#define CASCADE_EPI_GELU_TANH  4
+#define CASCADE_EPI_SWIGLU     8   /* Y = silu(X W^T) * (X W_up^T)                      */
+#define CASCADE_EPI_ROPE       16  /* rotate the first rope_cols columns head by head   */
+#define CASCADE_EPI_RESIDUAL   32  /* Y += residual                                     */
+
+/* ------------------------------------------------------------------ shard plan
+ * Section 5.1: the partition of [N] into shards, as index maps.  Built on the
+ * host from token_to_shard_host[seq_len] (values in [0, n_shards)), copied to
+ * the current device.  positions_host[seq_len] gives each token's position for
+ * the causal mask and the rotary embedding (NULL: position t = t).  The same
+ * assignment is shared by all `batch` sequences.
+ * Errors: EINVAL (null out / host array, sizes <= 0, unknown mask kind),
+ * EASSIGN (shard id out of range), EHIP.                                       */
+typedef struct cascade_plan cascade_plan;
+
+CASCADE_API int32_t cascade_plan_create(cascade_plan **out, int32_t batch, int32_t seq_len, int32_t n_shards,
+                            const int32_t *token_to_shard_host, const int32_t *positions_host,
+                            int32_t mask_kind);
+
+/* Device pointers to perm[seq_len], inv_perm[seq_len], offsets[n_shards + 1]
+ * (int32, owned by the plan); any out pointer may be NULL.                     */
+CASCADE_API int32_t cascade_plan_maps(const cascade_plan *plan, const int32_t **perm_dev,
+                          const int32_t **inv_perm_dev, const int32_t **offsets_dev);
+
+/* Host copies of the same maps (owned by the plan).                            */
+CASCADE_API int32_t cascade_plan_maps_host(const cascade_plan *plan, const int32_t **perm_host,
+                               const int32_t **inv_perm_host, const int32_t **offsets_host);
+
+CASCADE_API void cascade_plan_destroy(cascade_plan *plan);
+
+/* HIP error code of the last CASCADE_EHIP on this thread (0 if none).          */
+CASCADE_API int32_t cascade_last_hip_error(void);
+
+/* ------------------------------------------------------------------ shard GEMM
+ * The token-as-batch linear layers (Section 5 overview; Appendix C): for every
+ * shard, Y[rows of the shard] = epilogue(X[rows of the shard] W^T).  Weights are
+ * shared by all shards, so the groups are row-index lists; one launch covers
+ * all shards.  rows must be batch * seq_len of the plan when any row map is
+ * CASCADE_ROWS_ORIGINAL-to-packed (see x_rows / y_rows / res_rows).
+ *
+ * Row maps: the GEMM's own row r (0 <= r < rows) is a PACKED row.  With
+ * x_rows = CASCADE_ROWS_ORIGINAL the kernel reads X row b*N + perm[r mod N]
+ * (gather); with CASCADE_ROWS_PACKED it reads row r.  y_rows and res_rows do the
+ * same for the store of Y (scatter) and the read of the residual.               */
+typedef struct cascade_gemm_desc {
+    int32_t dtype;      /* element type of X, W, W_up, bias, residual, Y             */
+    int32_t rows;       /* M                                                          */
+    int32_t k;          /* in_features                                                */
+    int32_t n_out;      /* out_features = columns of Y                                */
+    int32_t epilogue;   /* CASCADE_EPI_* mask; order: +bias, activation / swiglu,
+                           rope, +residual                                            */
+    int32_t x_rows;     /* CASCADE_ROWS_*                                             */
+    int32_t y_rows;
+    int32_t res_rows;
+    int32_t rope_cols;  /* EPI_ROPE: columns [0, rope_cols) are rotated, in heads of
+                           head_dim columns, half-split pairing (i, i + head_dim/2),
+                           angle position * theta^(-2i/head_dim)                      */
+    int32_t head_dim;
+    float   rope_theta;
+} cascade_gemm_desc;
+
+/* X [rows, k]; W [n_out, k]; W_up [n_out, k] (EPI_SWIGLU only, else NULL);
+ * bias [n_out] (EPI_BIAS; with SWIGLU unsupported); residual [rows, n_out];
+ * Y [rows, n_out].  Y must not alias X.  Y may alias residual only when
+ * y_rows == res_rows.
+ * Errors: EINVAL, ESHAPE (rows != batch*seq_len with a map), EUNSUPPORTED
+ * (bf16 needs k % 8 == 0; rope needs head_dim even and rope_cols % head_dim == 0).*/
+CASCADE_API int32_t cascade_shard_gemm(const cascade_plan *plan, const cascade_gemm_desc *desc,
+                           const void *X, const void *W, const void *W_up, const void *bias,
+                           const void *residual, void *Y, void *stream);
+
+/* ------------------------------------------------------------------ attention
+ * Strides are in elements; the head_dim axis is contiguous.  A stride of 0
+ * means "dense [B, heads, N, d]".                                               */
+typedef struct cascade_attn_desc {
+    int32_t dtype;        /* of q, k, v and of o                                      */
+    int32_t n_heads;      /* H                                                        */
+    int32_t n_kv_heads;   /* H_KV, divides H; query head h reads kv head h/(H/H_KV)   */
+    int32_t head_dim;     /* d: bf16 path 64 or 128; f32 path any d <= 256            */
+    float   scale;        /* a = scale * q k^T + s                                    */
+    int32_t row_layout;   /* rows of q, k, v (partial_attn) and of o (lse_merge)      */
+    int32_t u_mode;       /* CASCADE_U_*                                              */
+    int64_t q_stride_b, q_stride_h, q_stride_n;
+    int64_t kv_stride_b, kv_stride_h, kv_stride_n;   /* shared by k and v             */
+} cascade_attn_desc;
+
+/* Bytes of workspace cascade_partial_attn needs (0 is possible).                */
+CASCADE_API size_t cascade_partial_attn_workspace_bytes(const cascade_plan *plan, const cascade_attn_desc *desc);
+
+/* Algorithm 3 for every pair (j, k).  Outputs are fp32 and in PACKED row order:
+ *   m, e [B, H, n_shards, N]   m[b,h,k,r], e[b,h,k,r]: packed query row r against shard k
+ *   u    [B, n_shards, H, N, d]
+ * m is in the units of a (natural-log domain).
+ * Errors: EINVAL, ESHAPE (H % H_KV), EUNSUPPORTED (head_dim), EWORKSPACE.       */
+CASCADE_API int32_t cascade_partial_attn(const cascade_plan *plan, const cascade_attn_desc *desc,
+                             const void *q, const void *k, const void *v,
+                             float *m, float *e, float *u,
+                             void *workspace, size_t workspace_bytes, void *stream);
+
+/* Algorithm 4 lines 1-8: n = max_k m_k; w = sum_k exp(m_k - n) e_k;
+ * o = sum_k exp(m_k - n) e_k u_k / w (u~ form: sum_k exp(m_k - n) u~_k / w).
+ * o [B, N, H*d] in desc->dtype, rows per desc->row_layout; lse_out (optional,
+ * may be NULL) [B, H, N] fp32 = n + log w, packed rows.                         */
+CASCADE_API int32_t cascade_lse_merge(const cascade_plan *plan, const cascade_attn_desc *desc,
+                          const float *m, const float *e, const float *u,
+                          void *o, float *lse_out, void *stream);
+
+/* ------------------------------------------------------------------ whole layer
+ * Algorithm 1 on one GPU: h1 = h + o_proj(attention(norm1(h))),
+ * h_out = h1 + FFN(norm2(h1)); pre-norm block.                                  */
+typedef struct cascade_layer_desc {
+    int32_t dtype;
+    int32_t d_model, n_heads, n_kv_heads, head_dim, d_ff;
+    int32_t norm_kind;    /* CASCADE_NORM_LAYERNORM | CASCADE_NORM_RMSNORM            */
+    float   norm_eps;
+    int32_t act;          /* CASCADE_ACT_*                                            */
+    int32_t rope;         /* 0: none, 1: half-split rotary on q and k                 */
+    float   rope_theta;
+    float   scale;
+    int32_t attn_mode;    /* CASCADE_ATTN_*                                           */
+    int32_t io_rows;      /* row order of h_in and h_out: CASCADE_ROWS_*              */
+} cascade_layer_desc;
+
+/* Device pointers, borrowed.  Matrices [out, in].  NULL = absent (biases, norm
+ * biases, w_gate unless SWIGLU).                                                */
+typedef struct cascade_layer_weights {
+    const void *wq, *wk, *wv, *wo;          /* [H d, D] [Hkv d, D] [Hkv d, D] [D, H d] */
+    const void *w_gate, *w_up, *w_down;     /* [f, D] [f, D] [D, f]                    */
+    const void *bq, *bk, *bv, *bo, *b_up, *b_down;
+    const void *norm1_g, *norm1_b, *norm2_g, *norm2_b;   /* [D]                        */
+} cascade_layer_weights;
+
+CASCADE_API size_t cascade_layer_workspace_bytes(const cascade_plan *plan, const cascade_layer_desc *desc);
+
+/* h_in, h_out [B, N, D]; must not alias.
+ * Errors: EINVAL, ESHAPE, EUNSUPPORTED, EWORKSPACE, EHIP.                       */
+CASCADE_API int32_t cascade_layer_forward(const cascade_plan *plan, const cascade_layer_desc *desc,
+                              const cascade_layer_weights *weights,
+                              const void *h_in, void *h_out,
+                              void *workspace, size_t workspace_bytes, void *stream);
+
+/* After a MATERIALISED cascade_layer_forward: device pointers into the workspace
+ * it used, holding m, e [B,H,n_shards,N] and u~ [B,n_shards,H,N,d] (fp32).      */
+CASCADE_API int32_t cascade_layer_partials(const cascade_plan *plan, const cascade_layer_desc *desc,
+                               void *workspace, float **m, float **e, float **u);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CASCADE_H */

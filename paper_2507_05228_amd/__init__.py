@@ -1,0 +1,316 @@
+"""Thin Python binding of libcascade (argument marshalling only).
+
+Every step of the path runs in the HIP library; PyTorch supplies device memory and
+streams.  The functions carry the names of the C entry points declared in
+include/cascade.h.  If the shared library has not been built, loading fails loudly:
+there is no CPU fallback.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libcascade.so")
+
+OK, EINVAL, ESHAPE, EASSIGN, EUNSUPPORTED, EWORKSPACE, EHIP = range(7)
+STATUS_NAMES = ["OK", "EINVAL", "ESHAPE", "EASSIGN", "EUNSUPPORTED", "EWORKSPACE", "EHIP"]
+F32, BF16 = 0, 1
+MASK_NONE, MASK_CAUSAL = 0, 1
+ROWS_ORIGINAL, ROWS_PACKED = 0, 1
+U_UNNORMALISED, U_NORMALISED = 0, 1
+NORM_NONE, NORM_LAYERNORM, NORM_RMSNORM = 0, 1, 2
+ACT_GELU_ERF, ACT_GELU_TANH, ACT_SWIGLU = 0, 1, 2
+ATTN_FUSED, ATTN_MATERIALISED = 0, 1
+EPI_BIAS, EPI_GELU_ERF, EPI_GELU_TANH, EPI_SWIGLU, EPI_ROPE, EPI_RESIDUAL = 1, 2, 4, 8, 16, 32
+
+EXPORTS = ["cascade_plan_create", "cascade_plan_maps", "cascade_plan_maps_host", "cascade_plan_destroy",
+           "cascade_last_hip_error", "cascade_shard_gemm", "cascade_partial_attn_workspace_bytes",
+           "cascade_partial_attn", "cascade_lse_merge", "cascade_layer_workspace_bytes",
+           "cascade_layer_forward", "cascade_layer_partials"]
+
+
+class CascadeError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        name = STATUS_NAMES[status] if 0 <= status < len(STATUS_NAMES) else str(status)
+        super().__init__(f"{where}: CASCADE_{name}")
+
+
+class GemmDesc(C.Structure):
+    _fields_ = [("dtype", C.c_int32), ("rows", C.c_int32), ("k", C.c_int32), ("n_out", C.c_int32),
+                ("epilogue", C.c_int32), ("x_rows", C.c_int32), ("y_rows", C.c_int32), ("res_rows", C.c_int32),
+                ("rope_cols", C.c_int32), ("head_dim", C.c_int32), ("rope_theta", C.c_float)]
+
+
+class AttnDesc(C.Structure):
+    _fields_ = [("dtype", C.c_int32), ("n_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+                ("scale", C.c_float), ("row_layout", C.c_int32), ("u_mode", C.c_int32),
+                ("q_stride_b", C.c_int64), ("q_stride_h", C.c_int64), ("q_stride_n", C.c_int64),
+                ("kv_stride_b", C.c_int64), ("kv_stride_h", C.c_int64), ("kv_stride_n", C.c_int64)]
+
+
+class LayerDesc(C.Structure):
+    _fields_ = [("dtype", C.c_int32), ("d_model", C.c_int32), ("n_heads", C.c_int32), ("n_kv_heads", C.c_int32),
+                ("head_dim", C.c_int32), ("d_ff", C.c_int32), ("norm_kind", C.c_int32), ("norm_eps", C.c_float),
+                ("act", C.c_int32), ("rope", C.c_int32), ("rope_theta", C.c_float), ("scale", C.c_float),
+                ("attn_mode", C.c_int32), ("io_rows", C.c_int32)]
+
+
+_WEIGHT_FIELDS = ["wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down", "bq", "bk", "bv", "bo", "b_up", "b_down",
+                  "norm1_g", "norm1_b", "norm2_g", "norm2_b"]
+
+
+class LayerWeights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in _WEIGHT_FIELDS]
+
+
+_lib = None
+
+
+def load_library():
+    """dlopen libcascade.so and declare the signatures.  Raises if it was not built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: run `python __graft_entry__.py` (build()) first; "
+                           "there is no fallback path")
+    lib = C.CDLL(LIB_PATH)
+    P, I32, VP = C.POINTER, C.c_int32, C.c_void_p
+    lib.cascade_plan_create.argtypes = [P(VP), I32, I32, I32, P(I32), P(I32), I32]
+    lib.cascade_plan_create.restype = I32
+    lib.cascade_plan_maps.argtypes = [VP, P(VP), P(VP), P(VP)]
+    lib.cascade_plan_maps.restype = I32
+    lib.cascade_plan_maps_host.argtypes = [VP, P(P(I32)), P(P(I32)), P(P(I32))]
+    lib.cascade_plan_maps_host.restype = I32
+    lib.cascade_plan_destroy.argtypes = [VP]
+    lib.cascade_plan_destroy.restype = None
+    lib.cascade_last_hip_error.argtypes = []
+    lib.cascade_last_hip_error.restype = I32
+    lib.cascade_shard_gemm.argtypes = [VP, P(GemmDesc), VP, VP, VP, VP, VP, VP, VP]
+    lib.cascade_shard_gemm.restype = I32
+    lib.cascade_partial_attn_workspace_bytes.argtypes = [VP, P(AttnDesc)]
+    lib.cascade_partial_attn_workspace_bytes.restype = C.c_size_t
+    lib.cascade_partial_attn.argtypes = [VP, P(AttnDesc), VP, VP, VP, VP, VP, VP, VP, C.c_size_t, VP]
+    lib.cascade_partial_attn.restype = I32
+    lib.cascade_lse_merge.argtypes = [VP, P(AttnDesc), VP, VP, VP, VP, VP, VP]
+    lib.cascade_lse_merge.restype = I32
+    lib.cascade_layer_workspace_bytes.argtypes = [VP, P(LayerDesc)]
+    lib.cascade_layer_workspace_bytes.restype = C.c_size_t
+    lib.cascade_layer_forward.argtypes = [VP, P(LayerDesc), P(LayerWeights), VP, VP, VP, C.c_size_t, VP]
+    lib.cascade_layer_forward.restype = I32
+    lib.cascade_layer_partials.argtypes = [VP, P(LayerDesc), VP, P(VP), P(VP), P(VP)]
+    lib.cascade_layer_partials.restype = I32
+    _lib = lib
+    return lib
+
+
+def _check(status, where):
+    if status != OK:
+        raise CascadeError(status, where)
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return C.c_void_p(s.cuda_stream)
+
+
+def _dtype_code(t):
+    import torch
+    if t.dtype == torch.bfloat16:
+        return BF16
+    if t.dtype == torch.float32:
+        return F32
+    raise CascadeError(EUNSUPPORTED, f"dtype {t.dtype}")
+
+
+class Plan:
+    """Owner of a cascade_plan handle."""
+
+    def __init__(self, handle, batch, seq_len, n_shards, mask_kind):
+        self.handle, self.batch, self.seq_len, self.n_shards, self.mask_kind = handle, batch, seq_len, n_shards, mask_kind
+
+    def __del__(self):
+        if getattr(self, "handle", None) and _lib is not None:
+            _lib.cascade_plan_destroy(self.handle)
+            self.handle = None
+
+
+def cascade_plan_create(batch, seq_len, n_shards, token_to_shard, positions=None, mask_kind=MASK_CAUSAL):
+    lib = load_library()
+    a = None if token_to_shard is None else np.ascontiguousarray(token_to_shard, dtype=np.int32)
+    if a is not None and a.shape != (max(seq_len, 0),):
+        raise CascadeError(ESHAPE, "cascade_plan_create: token_to_shard length")
+    pos = None if positions is None else np.ascontiguousarray(positions, dtype=np.int32)
+    if pos is not None and pos.shape != (seq_len,):
+        raise CascadeError(ESHAPE, "cascade_plan_create: positions length")
+    h = C.c_void_p()
+    I32P = C.POINTER(C.c_int32)
+    st = lib.cascade_plan_create(C.byref(h), batch, seq_len, n_shards,
+                                 None if a is None else a.ctypes.data_as(I32P),
+                                 None if pos is None else pos.ctypes.data_as(I32P), mask_kind)
+    _check(st, "cascade_plan_create")
+    return Plan(h, batch, seq_len, n_shards, mask_kind)
+
+
+def cascade_plan_maps(plan):
+    """Device copies of perm, inv_perm, offsets as torch int32 tensors (copied out)."""
+    import torch
+    lib = load_library()
+    p, ip, off = C.c_void_p(), C.c_void_p(), C.c_void_p()
+    _check(lib.cascade_plan_maps(plan.handle, C.byref(p), C.byref(ip), C.byref(off)), "cascade_plan_maps")
+    out = []
+    for ptr, n in ((p, plan.seq_len), (ip, plan.seq_len), (off, plan.n_shards + 1)):
+        out.append(torch.as_tensor(_DeviceInt32(ptr.value, n), device="cuda").clone())
+    return tuple(out)
+
+
+class _DeviceInt32:
+    """Borrowed view of n int32 values in device memory (for torch.as_tensor)."""
+
+    def __init__(self, ptr, n):
+        self.__cuda_array_interface__ = {"shape": (n,), "typestr": "<i4", "data": (ptr, True), "version": 2}
+
+
+def cascade_plan_maps_host(plan):
+    lib = load_library()
+    I32P = C.POINTER(C.c_int32)
+    p, ip, off = I32P(), I32P(), I32P()
+    _check(lib.cascade_plan_maps_host(plan.handle, C.byref(p), C.byref(ip), C.byref(off)), "cascade_plan_maps_host")
+    return (np.ctypeslib.as_array(p, (plan.seq_len,)).copy(), np.ctypeslib.as_array(ip, (plan.seq_len,)).copy(),
+            np.ctypeslib.as_array(off, (plan.n_shards + 1,)).copy())
+
+
+def cascade_shard_gemm(plan, X, W, Y, W_up=None, bias=None, residual=None, epilogue=0,
+                       x_rows=ROWS_PACKED, y_rows=ROWS_PACKED, res_rows=ROWS_PACKED,
+                       rope_cols=0, head_dim=0, rope_theta=0.0, stream=None):
+    lib = load_library()
+    d = GemmDesc(_dtype_code(X), X.shape[0], X.shape[1], W.shape[0], epilogue, x_rows, y_rows, res_rows,
+                 rope_cols, head_dim, rope_theta)
+    st = lib.cascade_shard_gemm(plan.handle if plan is not None else None, C.byref(d), _ptr(X), _ptr(W), _ptr(W_up),
+                                _ptr(bias), _ptr(residual), _ptr(Y), _stream(stream))
+    _check(st, "cascade_shard_gemm")
+
+
+def _attn_desc(q, n_heads, n_kv_heads, head_dim, scale, row_layout, u_mode, q_strides=None, kv_strides=None):
+    d = AttnDesc(_dtype_code(q), n_heads, n_kv_heads, head_dim, scale, row_layout, u_mode, 0, 0, 0, 0, 0, 0)
+    if q_strides:
+        d.q_stride_b, d.q_stride_h, d.q_stride_n = q_strides
+    if kv_strides:
+        d.kv_stride_b, d.kv_stride_h, d.kv_stride_n = kv_strides
+    return d
+
+
+def cascade_partial_attn_workspace_bytes(plan, q, n_heads, n_kv_heads, head_dim):
+    lib = load_library()
+    d = _attn_desc(q, n_heads, n_kv_heads, head_dim, 1.0, ROWS_PACKED, U_UNNORMALISED)
+    return lib.cascade_partial_attn_workspace_bytes(plan.handle, C.byref(d))
+
+
+def cascade_partial_attn(plan, q, k, v, m, e, u, n_heads, n_kv_heads, head_dim, scale,
+                         row_layout=ROWS_ORIGINAL, u_mode=U_UNNORMALISED, workspace=None,
+                         q_strides=None, kv_strides=None, stream=None):
+    lib = load_library()
+    d = _attn_desc(q, n_heads, n_kv_heads, head_dim, scale, row_layout, u_mode, q_strides, kv_strides)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    st = lib.cascade_partial_attn(plan.handle, C.byref(d), _ptr(q), _ptr(k), _ptr(v), _ptr(m), _ptr(e), _ptr(u),
+                                  _ptr(workspace), ws_bytes, _stream(stream))
+    _check(st, "cascade_partial_attn")
+
+
+def cascade_lse_merge(plan, m, e, u, o, n_heads, n_kv_heads, head_dim, row_layout=ROWS_PACKED,
+                      u_mode=U_UNNORMALISED, lse_out=None, stream=None):
+    lib = load_library()
+    d = _attn_desc(o, n_heads, n_kv_heads, head_dim, 1.0, row_layout, u_mode)
+    st = lib.cascade_lse_merge(plan.handle, C.byref(d), _ptr(m), _ptr(e), _ptr(u), _ptr(o), _ptr(lse_out),
+                               _stream(stream))
+    _check(st, "cascade_lse_merge")
+
+
+def make_layer_desc(cfg, attn_mode=ATTN_FUSED, io_rows=ROWS_ORIGINAL, scale=None):
+    """LayerDesc from a cascade_inputs.LayerConfig-like object (field copy only)."""
+    act = {"gelu": ACT_GELU_ERF, "gelu_tanh": ACT_GELU_TANH, "swiglu": ACT_SWIGLU}[cfg.act]
+    nk = {"layernorm": NORM_LAYERNORM, "rmsnorm": NORM_RMSNORM}[cfg.norm]
+    return LayerDesc(BF16 if cfg.dtype == "bf16" else F32, cfg.d_model, cfg.n_heads, cfg.n_kv_heads, cfg.head_dim,
+                     cfg.d_ff, nk, cfg.eps, act, 1 if cfg.rope else 0, cfg.rope_theta,
+                     cfg.scale if scale is None else scale, attn_mode, io_rows)
+
+
+def make_layer_weights(tensors):
+    """LayerWeights from a dict of device tensors (absent keys -> NULL).  Keep `tensors` alive."""
+    w = LayerWeights()
+    for n in _WEIGHT_FIELDS:
+        t = tensors.get(n)
+        setattr(w, n, None if t is None else t.data_ptr())
+    return w
+
+
+def cascade_layer_workspace_bytes(plan, desc):
+    return load_library().cascade_layer_workspace_bytes(plan.handle, C.byref(desc))
+
+
+def cascade_layer_forward(plan, desc, weights, h_in, h_out, workspace, stream=None):
+    lib = load_library()
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    st = lib.cascade_layer_forward(plan.handle, C.byref(desc), C.byref(weights), _ptr(h_in), _ptr(h_out),
+                                   _ptr(workspace), ws_bytes, _stream(stream))
+    _check(st, "cascade_layer_forward")
+
+
+def cascade_layer_partials(plan, desc, workspace, batch, n_heads, head_dim):
+    """Views (torch tensors over the workspace) of m, e, u~ after a MATERIALISED layer forward."""
+    import torch
+    lib = load_library()
+    m, e, u = C.c_void_p(), C.c_void_p(), C.c_void_p()
+    _check(lib.cascade_layer_partials(plan.handle, C.byref(desc), _ptr(workspace), C.byref(m), C.byref(e), C.byref(u)),
+           "cascade_layer_partials")
+    base = workspace.data_ptr()
+    f = workspace.view(torch.uint8)
+    S, N = plan.n_shards, plan.seq_len
+    n_me = batch * n_heads * S * N
+
+    def view(ptr, n, shape):
+        off = ptr.value - base
+        return f[off:off + 4 * n].view(torch.float32).view(*shape)
+
+    return (view(m, n_me, (batch, n_heads, S, N)), view(e, n_me, (batch, n_heads, S, N)),
+            view(u, n_me * head_dim, (batch, S, n_heads, N, head_dim)))
+
+
+# ------------------------------------------------------------------ numpy <-> device marshalling helpers
+def to_device(x, dtype_name):
+    import torch
+    t = torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).cuda()
+    return t.to(torch.bfloat16) if dtype_name == "bf16" else t
+
+
+def new_workspace(nbytes):
+    import torch
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device="cuda")
+
+
+def layer_forward_numpy(cfg, weights_np, h_np, token_to_shard, positions=None, attn_mode=ATTN_FUSED,
+                        io_rows=ROWS_ORIGINAL, mask_kind=MASK_CAUSAL, return_partials=False):
+    """Upload numpy inputs, run cascade_layer_forward once, download the output as float64."""
+    import torch
+    plan = cascade_plan_create(cfg.batch, cfg.seq_len, int(np.max(token_to_shard)) + 1 if cfg.n_shards is None
+                               else cfg.n_shards, token_to_shard, positions, mask_kind)
+    desc = make_layer_desc(cfg, attn_mode, io_rows)
+    tensors = {k: to_device(v, cfg.dtype) for k, v in weights_np.items()}
+    w = make_layer_weights(tensors)
+    h_in = to_device(h_np, cfg.dtype)
+    h_out = torch.empty_like(h_in)
+    ws = new_workspace(cascade_layer_workspace_bytes(plan, desc))
+    cascade_layer_forward(plan, desc, w, h_in, h_out, ws)
+    torch.cuda.synchronize()
+    out = h_out.float().cpu().numpy().astype(np.float64)
+    if return_partials:
+        m, e, u = cascade_layer_partials(plan, desc, ws, cfg.batch, cfg.n_heads, cfg.head_dim)
+        return out, tuple(t.cpu().numpy().astype(np.float64) for t in (m, e, u))
+    return out

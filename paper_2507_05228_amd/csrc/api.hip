@@ -1,0 +1,294 @@
+// C-ABI entry points: argument checks, then the kernels.  No compute happens here.
+#include "common.h"
+
+static inline int esize(int dtype) { return dtype == CASCADE_BF16 ? 2 : 4; }
+static inline bool dtype_ok(int dtype) { return dtype == CASCADE_BF16 || dtype == CASCADE_F32; }
+static inline bool rows_ok(int v) { return v == CASCADE_ROWS_ORIGINAL || v == CASCADE_ROWS_PACKED; }
+
+static RowMap rowmap_for(const cascade_plan *plan, int rows_kind) {
+    RowMap m;
+    m.map = (rows_kind == CASCADE_ROWS_ORIGINAL && plan) ? plan->perm_d : nullptr;
+    m.seq_len = plan ? plan->seq_len : 1;
+    return m;
+}
+
+static int32_t run_gemm(const GemmArgs &g, hipStream_t s) {
+    return g.dtype == CASCADE_BF16 ? launch_gemm_bf16(g, s) : launch_gemm_f32(g, s);
+}
+
+// ---------------------------------------------------------------------------- cascade_shard_gemm
+extern "C" int32_t cascade_shard_gemm(const cascade_plan *plan, const cascade_gemm_desc *d, const void *X,
+                                      const void *W, const void *W_up, const void *bias, const void *residual,
+                                      void *Y, void *stream) {
+    if (!d || !X || !W || !Y) return CASCADE_EINVAL;
+    if (d->rows < 0 || d->k <= 0 || d->n_out <= 0) return CASCADE_EINVAL;
+    if (!dtype_ok(d->dtype)) return CASCADE_EUNSUPPORTED;
+    if (!rows_ok(d->x_rows) || !rows_ok(d->y_rows) || !rows_ok(d->res_rows)) return CASCADE_EINVAL;
+    const int ep = d->epilogue;
+    const bool any_map = d->x_rows == CASCADE_ROWS_ORIGINAL || d->y_rows == CASCADE_ROWS_ORIGINAL ||
+                         ((ep & CASCADE_EPI_RESIDUAL) && d->res_rows == CASCADE_ROWS_ORIGINAL);
+    if ((any_map || (ep & CASCADE_EPI_ROPE)) && !plan) return CASCADE_EINVAL;
+    if ((any_map || (ep & CASCADE_EPI_ROPE)) && (int64_t)plan->batch * plan->seq_len != d->rows) return CASCADE_ESHAPE;
+    if ((ep & CASCADE_EPI_SWIGLU) && !W_up) return CASCADE_EINVAL;
+    if ((ep & CASCADE_EPI_SWIGLU) && (ep & (CASCADE_EPI_BIAS | CASCADE_EPI_GELU_ERF | CASCADE_EPI_GELU_TANH)))
+        return CASCADE_EUNSUPPORTED;
+    if ((ep & CASCADE_EPI_GELU_ERF) && (ep & CASCADE_EPI_GELU_TANH)) return CASCADE_EINVAL;
+    if ((ep & CASCADE_EPI_BIAS) && !bias) return CASCADE_EINVAL;
+    if ((ep & CASCADE_EPI_RESIDUAL) && !residual) return CASCADE_EINVAL;
+    if (ep & CASCADE_EPI_ROPE) {
+        if (ep & (CASCADE_EPI_RESIDUAL | CASCADE_EPI_GELU_ERF | CASCADE_EPI_GELU_TANH | CASCADE_EPI_SWIGLU))
+            return CASCADE_EUNSUPPORTED;
+        if (d->y_rows != CASCADE_ROWS_PACKED) return CASCADE_EUNSUPPORTED;
+        if (d->head_dim <= 0 || d->head_dim % 2 || d->rope_cols < 0 || d->rope_cols % d->head_dim ||
+            d->rope_cols > d->n_out || d->rope_theta <= 0.f)
+            return CASCADE_EUNSUPPORTED;
+    }
+    if (X == Y) return CASCADE_EINVAL;
+    if (residual == Y && d->y_rows != d->res_rows) return CASCADE_EINVAL;
+    hipStream_t s = (hipStream_t)stream;
+    GemmArgs g = {};
+    g.dtype = d->dtype; g.M = d->rows; g.N = d->n_out; g.K = d->k;
+    g.X = X; g.W[0] = W; g.W[1] = g.W[2] = nullptr;
+    g.seg_end[0] = g.seg_end[1] = g.seg_end[2] = d->n_out;
+    g.bias[0] = (ep & CASCADE_EPI_BIAS) ? bias : nullptr;
+    g.W_up = W_up; g.residual = residual; g.Y = Y;
+    g.ldx = d->k; g.ldy = d->n_out; g.ldres = d->n_out;
+    g.xmap = rowmap_for(plan, d->x_rows); g.ymap = rowmap_for(plan, d->y_rows); g.rmap = rowmap_for(plan, d->res_rows);
+    g.epilogue = ep & ~CASCADE_EPI_ROPE;
+    int32_t st = run_gemm(g, s);
+    if (st != CASCADE_OK) return st;
+    if ((ep & CASCADE_EPI_ROPE) && d->rope_cols > 0) {
+        RopeArgs r = {};
+        r.dtype = d->dtype; r.rows = d->rows; r.seq_len = plan->seq_len;
+        r.n_rope_heads = d->rope_cols / d->head_dim; r.head_dim = d->head_dim; r.ld = d->n_out;
+        r.theta = d->rope_theta; r.pos_packed = plan->pos_packed_d; r.x = Y;
+        st = launch_rope(r, s);
+    }
+    return st;
+}
+
+// ---------------------------------------------------------------------------- attention ops
+static int32_t check_attn_desc(const cascade_plan *plan, const cascade_attn_desc *d) {
+    if (!plan || !d) return CASCADE_EINVAL;
+    if (!dtype_ok(d->dtype)) return CASCADE_EUNSUPPORTED;
+    if (d->n_heads <= 0 || d->n_kv_heads <= 0 || d->head_dim <= 0) return CASCADE_EINVAL;
+    if (d->n_heads % d->n_kv_heads) return CASCADE_ESHAPE;
+    if (!rows_ok(d->row_layout)) return CASCADE_EINVAL;
+    if (d->u_mode != CASCADE_U_NORMALISED && d->u_mode != CASCADE_U_UNNORMALISED) return CASCADE_EINVAL;
+    if (d->dtype == CASCADE_BF16 && d->head_dim != 64 && d->head_dim != 128) return CASCADE_EUNSUPPORTED;
+    if (d->dtype == CASCADE_F32 && d->head_dim > 256) return CASCADE_EUNSUPPORTED;
+    return CASCADE_OK;
+}
+
+extern "C" size_t cascade_partial_attn_workspace_bytes(const cascade_plan *plan, const cascade_attn_desc *d) {
+    if (check_attn_desc(plan, d) != CASCADE_OK) return 0;
+    if (d->dtype != CASCADE_BF16) return 0;
+    return attn_bf16_workspace_bytes(plan, plan->batch, d->n_kv_heads, d->head_dim);
+}
+
+static void fill_strides(const cascade_plan *plan, const cascade_attn_desc *d, AttnArgs &a) {
+    const int64_t N = plan->seq_len, dd = d->head_dim;
+    a.qs_n = d->q_stride_n ? d->q_stride_n : dd;
+    a.qs_h = d->q_stride_h ? d->q_stride_h : N * dd;
+    a.qs_b = d->q_stride_b ? d->q_stride_b : (int64_t)d->n_heads * N * dd;
+    a.ks_n = d->kv_stride_n ? d->kv_stride_n : dd;
+    a.ks_h = d->kv_stride_h ? d->kv_stride_h : N * dd;
+    a.ks_b = d->kv_stride_b ? d->kv_stride_b : (int64_t)d->n_kv_heads * N * dd;
+}
+
+extern "C" int32_t cascade_partial_attn(const cascade_plan *plan, const cascade_attn_desc *d, const void *q,
+                                        const void *k, const void *v, float *m, float *e, float *u, void *workspace,
+                                        size_t workspace_bytes, void *stream) {
+    int32_t st = check_attn_desc(plan, d);
+    if (st != CASCADE_OK) return st;
+    if (!q || !k || !v || !m || !e || !u) return CASCADE_EINVAL;
+    AttnArgs a = {};
+    a.dtype = d->dtype; a.B = plan->batch; a.H = d->n_heads; a.Hkv = d->n_kv_heads; a.d = d->head_dim;
+    a.scale = d->scale; a.mask_kind = plan->mask_kind;
+    a.q = q; a.k = k; a.v = v;
+    fill_strides(plan, d, a);
+    a.q_rowmap = a.kv_rowmap = d->row_layout == CASCADE_ROWS_ORIGINAL ? plan->perm_d : nullptr;
+    a.fused = 0; a.u_mode = d->u_mode; a.m = m; a.e = e; a.u = u;
+    a.workspace = workspace; a.workspace_bytes = workspace_bytes;
+    hipStream_t s = (hipStream_t)stream;
+    return d->dtype == CASCADE_BF16 ? launch_attn_bf16(plan, a, s) : launch_attn_f32(plan, a, s);
+}
+
+extern "C" int32_t cascade_lse_merge(const cascade_plan *plan, const cascade_attn_desc *d, const float *m,
+                                     const float *e, const float *u, void *o, float *lse_out, void *stream) {
+    int32_t st = check_attn_desc(plan, d);
+    if (st != CASCADE_OK) return st;
+    if (!m || !e || !u || !o) return CASCADE_EINVAL;
+    MergeArgs a = {};
+    a.dtype = d->dtype; a.B = plan->batch; a.H = d->n_heads; a.d = d->head_dim; a.n_shards = plan->n_shards;
+    a.N = plan->seq_len; a.u_mode = d->u_mode; a.m = m; a.e = e; a.u = u; a.o = o;
+    a.o_ld = (int64_t)d->n_heads * d->head_dim;
+    a.o_rowmap = d->row_layout == CASCADE_ROWS_ORIGINAL ? plan->perm_d : nullptr;
+    a.lse = lse_out;
+    return launch_merge(a, (hipStream_t)stream);
+}
+
+// ---------------------------------------------------------------------------- whole layer
+struct LayerWs {
+    size_t x, qkv, ao, h1, act, attn_ws, m, e, u, total;
+    size_t attn_ws_bytes;
+};
+
+static LayerWs layer_ws(const cascade_plan *plan, const cascade_layer_desc *d) {
+    LayerWs w = {};
+    const size_t es = esize(d->dtype);
+    const size_t T = (size_t)plan->batch * plan->seq_len;
+    const size_t QW = (size_t)(d->n_heads + 2 * d->n_kv_heads) * d->head_dim;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes, 256); return o; };
+    w.x = take(T * d->d_model * es);
+    w.qkv = take(T * QW * es);
+    w.ao = take(T * (size_t)d->n_heads * d->head_dim * es);
+    w.h1 = take(T * d->d_model * es);
+    w.act = take(T * (size_t)d->d_ff * es);
+    w.attn_ws_bytes = d->dtype == CASCADE_BF16 ? attn_bf16_workspace_bytes(plan, plan->batch, d->n_kv_heads, d->head_dim) : 0;
+    w.attn_ws = take(w.attn_ws_bytes);
+    if (d->attn_mode == CASCADE_ATTN_MATERIALISED) {
+        const size_t me = (size_t)plan->batch * d->n_heads * plan->n_shards * plan->seq_len * 4;
+        w.m = take(me);
+        w.e = take(me);
+        w.u = take(me * d->head_dim);
+    }
+    w.total = off;
+    return w;
+}
+
+static int32_t check_layer_desc(const cascade_plan *plan, const cascade_layer_desc *d) {
+    if (!plan || !d) return CASCADE_EINVAL;
+    if (!dtype_ok(d->dtype)) return CASCADE_EUNSUPPORTED;
+    if (d->d_model <= 0 || d->n_heads <= 0 || d->n_kv_heads <= 0 || d->head_dim <= 0 || d->d_ff <= 0)
+        return CASCADE_EINVAL;
+    if (d->n_heads % d->n_kv_heads) return CASCADE_ESHAPE;
+    if (d->norm_kind != CASCADE_NORM_LAYERNORM && d->norm_kind != CASCADE_NORM_RMSNORM) return CASCADE_EINVAL;
+    if (d->act != CASCADE_ACT_GELU_ERF && d->act != CASCADE_ACT_GELU_TANH && d->act != CASCADE_ACT_SWIGLU)
+        return CASCADE_EINVAL;
+    if (d->attn_mode != CASCADE_ATTN_FUSED && d->attn_mode != CASCADE_ATTN_MATERIALISED) return CASCADE_EINVAL;
+    if (!rows_ok(d->io_rows)) return CASCADE_EINVAL;
+    if (d->rope != 0 && d->rope != 1) return CASCADE_EUNSUPPORTED;
+    if (d->rope && (d->head_dim % 2 || d->rope_theta <= 0.f)) return CASCADE_EUNSUPPORTED;
+    if (d->dtype == CASCADE_BF16) {
+        if (d->head_dim != 64 && d->head_dim != 128) return CASCADE_EUNSUPPORTED;
+        if (d->d_model % 8 || d->d_ff % 8) return CASCADE_EUNSUPPORTED;
+    } else if (d->head_dim > 256) return CASCADE_EUNSUPPORTED;
+    return CASCADE_OK;
+}
+
+extern "C" size_t cascade_layer_workspace_bytes(const cascade_plan *plan, const cascade_layer_desc *d) {
+    if (check_layer_desc(plan, d) != CASCADE_OK) return 0;
+    return layer_ws(plan, d).total;
+}
+
+extern "C" int32_t cascade_layer_partials(const cascade_plan *plan, const cascade_layer_desc *d, void *workspace,
+                                          float **m, float **e, float **u) {
+    int32_t st = check_layer_desc(plan, d);
+    if (st != CASCADE_OK) return st;
+    if (!workspace || d->attn_mode != CASCADE_ATTN_MATERIALISED) return CASCADE_EINVAL;
+    LayerWs w = layer_ws(plan, d);
+    char *base = (char *)workspace;
+    if (m) *m = (float *)(base + w.m);
+    if (e) *e = (float *)(base + w.e);
+    if (u) *u = (float *)(base + w.u);
+    return CASCADE_OK;
+}
+
+extern "C" int32_t cascade_layer_forward(const cascade_plan *plan, const cascade_layer_desc *d,
+                                         const cascade_layer_weights *w, const void *h_in, void *h_out,
+                                         void *workspace, size_t workspace_bytes, void *stream) {
+    int32_t st = check_layer_desc(plan, d);
+    if (st != CASCADE_OK) return st;
+    if (!w || !h_in || !h_out || h_in == h_out) return CASCADE_EINVAL;
+    if (!w->wq || !w->wk || !w->wv || !w->wo || !w->w_up || !w->w_down || !w->norm1_g || !w->norm2_g)
+        return CASCADE_EINVAL;
+    if (d->act == CASCADE_ACT_SWIGLU && !w->w_gate) return CASCADE_EINVAL;
+    const LayerWs ws = layer_ws(plan, d);
+    if (!workspace || workspace_bytes < ws.total) return CASCADE_EWORKSPACE;
+    if ((uintptr_t)workspace % 256) return CASCADE_EWORKSPACE;
+
+    hipStream_t s = (hipStream_t)stream;
+    char *base = (char *)workspace;
+    const int T = plan->batch * plan->seq_len, N = plan->seq_len;
+    const int D = d->d_model, H = d->n_heads, Hkv = d->n_kv_heads, hd = d->head_dim, f = d->d_ff;
+    const int QW = (H + 2 * Hkv) * hd;
+    const int es = esize(d->dtype);
+    void *x = base + ws.x, *qkv = base + ws.qkv, *ao = base + ws.ao, *h1 = base + ws.h1, *act = base + ws.act;
+    const RowMap io_map = rowmap_for(plan, d->io_rows), packed = rowmap_for(plan, CASCADE_ROWS_PACKED);
+
+    // 1. pre-pass: norm (with the gather into packed order), q/k/v projection, rotary embedding (Algorithm 2)
+    NormArgs n1 = {d->dtype, T, D, d->norm_kind, d->norm_eps, h_in, w->norm1_g, w->norm1_b, x, io_map};
+    if ((st = launch_norm(n1, s)) != CASCADE_OK) return st;
+    GemmArgs g = {};
+    g.dtype = d->dtype; g.M = T; g.N = QW; g.K = D; g.X = x;
+    g.W[0] = w->wq; g.W[1] = w->wk; g.W[2] = w->wv;
+    g.seg_end[0] = H * hd; g.seg_end[1] = (H + Hkv) * hd; g.seg_end[2] = QW;
+    g.bias[0] = w->bq; g.bias[1] = w->bk; g.bias[2] = w->bv;
+    g.epilogue = (w->bq || w->bk || w->bv) ? CASCADE_EPI_BIAS : 0;
+    g.Y = qkv; g.ldx = D; g.ldy = QW; g.xmap = g.ymap = g.rmap = packed;
+    if ((st = run_gemm(g, s)) != CASCADE_OK) return st;
+    if (d->rope) {
+        RopeArgs r = {d->dtype, T, N, H + Hkv, hd, QW, d->rope_theta, plan->pos_packed_d, qkv};
+        if ((st = launch_rope(r, s)) != CASCADE_OK) return st;
+    }
+
+    // 2. attention-pass on every (j, k) pair and post-pass merge (Algorithms 3 and 4)
+    AttnArgs a = {};
+    a.dtype = d->dtype; a.B = plan->batch; a.H = H; a.Hkv = Hkv; a.d = hd; a.scale = d->scale;
+    a.mask_kind = plan->mask_kind;
+    a.q = qkv; a.k = (char *)qkv + (size_t)H * hd * es; a.v = (char *)qkv + (size_t)(H + Hkv) * hd * es;
+    a.qs_b = a.ks_b = (int64_t)N * QW; a.qs_h = a.ks_h = hd; a.qs_n = a.ks_n = QW;
+    a.u_mode = CASCADE_U_UNNORMALISED;
+    a.workspace = base + ws.attn_ws; a.workspace_bytes = ws.attn_ws_bytes;
+    a.o = ao; a.o_ld = (int64_t)H * hd;
+    if (d->attn_mode == CASCADE_ATTN_FUSED) {
+        a.fused = 1;
+        st = d->dtype == CASCADE_BF16 ? launch_attn_bf16(plan, a, s) : launch_attn_f32(plan, a, s);
+        if (st != CASCADE_OK) return st;
+    } else {
+        a.fused = 0;
+        a.m = (float *)(base + ws.m); a.e = (float *)(base + ws.e); a.u = (float *)(base + ws.u);
+        st = d->dtype == CASCADE_BF16 ? launch_attn_bf16(plan, a, s) : launch_attn_f32(plan, a, s);
+        if (st != CASCADE_OK) return st;
+        MergeArgs mg = {d->dtype, plan->batch, H, hd, plan->n_shards, N, CASCADE_U_UNNORMALISED,
+                        a.m, a.e, a.u, ao, (int64_t)H * hd, nullptr, nullptr};
+        if ((st = launch_merge(mg, s)) != CASCADE_OK) return st;
+    }
+
+    // 3. o projection + residual (Algorithm 4 line 9, Algorithm 1 line 17)
+    g = {};
+    g.dtype = d->dtype; g.M = T; g.N = D; g.K = H * hd; g.X = ao; g.W[0] = w->wo;
+    g.seg_end[0] = g.seg_end[1] = g.seg_end[2] = D;
+    g.bias[0] = w->bo; g.residual = h_in; g.Y = h1;
+    g.ldx = H * hd; g.ldy = D; g.ldres = D;
+    g.xmap = g.ymap = packed; g.rmap = io_map;
+    g.epilogue = CASCADE_EPI_RESIDUAL | (w->bo ? CASCADE_EPI_BIAS : 0);
+    if ((st = run_gemm(g, s)) != CASCADE_OK) return st;
+
+    // 4. MLP: norm2, up (+ gate) projection with the activation, down projection + residual,
+    //    scattered back to the caller's row order
+    NormArgs n2 = {d->dtype, T, D, d->norm_kind, d->norm_eps, h1, w->norm2_g, w->norm2_b, x, packed};
+    if ((st = launch_norm(n2, s)) != CASCADE_OK) return st;
+    g = {};
+    g.dtype = d->dtype; g.M = T; g.N = f; g.K = D; g.X = x;
+    g.seg_end[0] = g.seg_end[1] = g.seg_end[2] = f;
+    g.Y = act; g.ldx = D; g.ldy = f; g.xmap = g.ymap = g.rmap = packed;
+    if (d->act == CASCADE_ACT_SWIGLU) {
+        g.W[0] = w->w_gate; g.W_up = w->w_up; g.epilogue = CASCADE_EPI_SWIGLU;
+    } else {
+        g.W[0] = w->w_up; g.bias[0] = w->b_up;
+        g.epilogue = (d->act == CASCADE_ACT_GELU_ERF ? CASCADE_EPI_GELU_ERF : CASCADE_EPI_GELU_TANH) |
+                     (w->b_up ? CASCADE_EPI_BIAS : 0);
+    }
+    if ((st = run_gemm(g, s)) != CASCADE_OK) return st;
+    g = {};
+    g.dtype = d->dtype; g.M = T; g.N = D; g.K = f; g.X = act; g.W[0] = w->w_down;
+    g.seg_end[0] = g.seg_end[1] = g.seg_end[2] = D;
+    g.bias[0] = w->b_down; g.residual = h1; g.Y = h_out;
+    g.ldx = f; g.ldy = D; g.ldres = D;
+    g.xmap = g.rmap = packed; g.ymap = io_map;
+    g.epilogue = CASCADE_EPI_RESIDUAL | (w->b_down ? CASCADE_EPI_BIAS : 0);
+    return run_gemm(g, s);
+}

@@ -1,0 +1,130 @@
+// Internal declarations shared by the library's translation units (host side).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include "../../include/cascade.h"
+
+// One tile of packed rows that never straddles a shard boundary.  sub_min/sub_max hold
+// the smallest / largest token position of each 32-row granule of the tile (granules
+// beyond n_rows hold min = INT_MAX, max = INT_MIN).
+struct CascadeTile {
+    int32_t row_start;   // first packed row
+    int32_t n_rows;      // rows in this tile (<= granule)
+    int32_t shard;       // shard id
+    int32_t pmin;        // min position over the tile
+    int32_t pmax;        // max position over the tile
+    int32_t pad[3];
+    int32_t sub_min[8];
+    int32_t sub_max[8];
+};
+
+struct CascadeTileList {
+    int32_t granule = 0;
+    int32_t count = 0;
+    CascadeTile *dev = nullptr;
+    int32_t *shard_first = nullptr;   // device: [n_shards + 1] first tile index of each shard
+    int32_t *shard_first_host = nullptr;
+};
+
+struct cascade_plan {
+    int32_t batch, seq_len, n_shards, mask_kind;
+    int device;
+    // host copies
+    int32_t *perm_h, *inv_perm_h, *offsets_h, *pos_packed_h;
+    // device copies
+    int32_t *perm_d, *inv_perm_d, *offsets_d, *pos_packed_d;
+    CascadeTileList tiles[4];   // granules 32, 64, 128, 256
+};
+
+static inline const CascadeTileList &plan_tiles(const cascade_plan *p, int granule) {
+    return p->tiles[granule == 32 ? 0 : granule == 64 ? 1 : granule == 128 ? 2 : 3];
+}
+
+void cascade_set_hip_error(hipError_t e);
+
+#define CASCADE_HIP_TRY(expr)                                   \
+    do {                                                        \
+        hipError_t _e = (expr);                                 \
+        if (_e != hipSuccess) { cascade_set_hip_error(_e); return CASCADE_EHIP; } \
+    } while (0)
+
+static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// ---------------------------------------------------------------------------- internal launchers
+// Row map convention: map == nullptr -> identity; else global row = b * seq_len + map[r % seq_len].
+struct RowMap {
+    const int32_t *map;
+    int32_t seq_len;
+};
+
+struct GemmArgs {
+    int32_t dtype;
+    int32_t M, N, K;                 // N: output columns (SWIGLU: of the product)
+    const void *X;
+    const void *W[3];                // weight segments stacked along the output axis
+    int32_t seg_end[3];              // exclusive end column of each segment (unused segments: N)
+    const void *bias[3];             // per segment, may be null
+    const void *W_up;                // SWIGLU second operand
+    const void *residual;
+    void *Y;
+    int64_t ldx, ldy, ldres;         // row strides in elements
+    RowMap xmap, ymap, rmap;
+    int32_t epilogue;
+};
+
+int32_t launch_gemm_bf16(const GemmArgs &a, hipStream_t s);
+int32_t launch_gemm_f32(const GemmArgs &a, hipStream_t s);
+
+struct NormArgs {
+    int32_t dtype, rows, D, kind;
+    float eps;
+    const void *x; const void *gain; const void *bias; void *y;
+    RowMap xmap;                     // gather on the read
+};
+int32_t launch_norm(const NormArgs &a, hipStream_t s);
+
+struct RopeArgs {
+    int32_t dtype, rows, seq_len;    // rows = B * N packed rows
+    int32_t n_rope_heads, head_dim;  // heads [0, n_rope_heads) of each row are rotated
+    int64_t ld;                      // row stride (elements)
+    float theta;
+    const int32_t *pos_packed;       // [seq_len]
+    void *x;                         // in place
+};
+int32_t launch_rope(const RopeArgs &a, hipStream_t s);
+
+struct CopyRowsArgs {                // y[ymap(r)] = x[xmap(r)], rows of `width` elements
+    int32_t dtype, rows, width;
+    int64_t ldx, ldy;
+    const void *x; void *y;
+    RowMap xmap, ymap;
+};
+int32_t launch_copy_rows(const CopyRowsArgs &a, hipStream_t s);
+
+struct AttnArgs {
+    int32_t dtype, B, H, Hkv, d;
+    float scale;
+    int32_t mask_kind;
+    const void *q, *k, *v;
+    int64_t qs_b, qs_h, qs_n, ks_b, ks_h, ks_n, vs_b, vs_h, vs_n;
+    const int32_t *q_rowmap, *kv_rowmap;   // packed row -> row in q / k,v (nullptr: identity)
+    int32_t fused;                   // 1: running merge over all shards, write o; 0: per-shard partials
+    int32_t u_mode;
+    float *m, *e, *u;                // partials (fused == 0)
+    void *o; int64_t o_ld;           // fused output [B, N, H*d], row map below
+    const int32_t *o_rowmap;
+    void *workspace; size_t workspace_bytes;
+};
+size_t attn_bf16_workspace_bytes(const cascade_plan *p, int32_t B, int32_t Hkv, int32_t d);
+int32_t launch_attn_bf16(const cascade_plan *p, const AttnArgs &a, hipStream_t s);
+int32_t launch_attn_f32(const cascade_plan *p, const AttnArgs &a, hipStream_t s);
+
+struct MergeArgs {
+    int32_t dtype, B, H, d, n_shards, N, u_mode;
+    const float *m, *e, *u;
+    void *o; int64_t o_ld;
+    const int32_t *o_rowmap;         // packed row -> output row (nullptr: identity)
+    float *lse;
+};
+int32_t launch_merge(const MergeArgs &a, hipStream_t s);

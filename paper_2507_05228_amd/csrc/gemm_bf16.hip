@@ -1,0 +1,264 @@
+// bf16 shard GEMM on the gfx950 matrix cores: Y[rows] = epilogue(X[rows] W^T), fp32 accumulation.
+// These are the token-as-batch linear layers of the method (q/k/v projection of Algorithm 2,
+// o projection of Algorithm 4 line 9, the MLP of Algorithm 1 line 17).  Weights are shared by
+// all shards, so the shard structure shows up only as row maps (gather on the X read, gather on
+// the residual read, scatter on the Y store).
+//
+// Tiling: a workgroup of WM x WN wavefronts owns a BM x BN tile; each wavefront owns
+// (BM/WM) x (BN/WN), built from 32x32x16 bf16 MFMA blocks.  K is walked in steps of 64; tiles are
+// staged through LDS (rows padded to 72 elements so that 16-lane groups of a ds_read_b128 hit 64
+// distinct banks) and double-buffered: the global loads of step t+1 are in flight while step t is
+// multiplied.  Global loads are buffer loads, so out-of-range rows / columns read as zero.
+//
+// Weight segments: the output axis may be the concatenation of up to three matrices (q | k | v);
+// tiles never straddle a segment, so the buffer resource of the W tile is workgroup-uniform.
+// SWIGLU: the B tile interleaves BN/WN/2 gate rows with the BN/WN/2 up rows of the same output
+// columns per wavefront column, so gate and up of one output element live in the same lane.
+#include "common.h"
+#include "device_utils.h"
+#include "epilogue.h"
+
+#define BK 64
+#define LDS_LD 72              // padded row length in elements (144 bytes)
+#define OOB_OFF 0x80000000u    // byte offset beyond any buffer we accept (< 2 GiB)
+
+struct GemmBf16Params {
+    const bf16_t *X;
+    const bf16_t *W[3];
+    const bf16_t *bias[3];
+    int32_t seg_rows[3];        // output columns in each segment
+    int32_t seg_col0[3];        // first output column of each segment
+    int32_t seg_tile0[3];       // first n-tile of each segment
+    const bf16_t *Wup;
+    const bf16_t *residual;
+    bf16_t *Y;
+    int32_t M, K;
+    int32_t tiles_m, tiles_n;
+    int64_t ldx, ldy, ldres;
+    const int32_t *xmap, *ymap, *rmap;
+    int32_t seq_len;
+    int32_t flags;
+    uint32_t x_bytes;
+};
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *p, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, bytes, 0x00020000);
+}
+
+__device__ __forceinline__ u32x4 buf_load16(__amdgpu_buffer_rsrc_t r, uint32_t off) {
+    return __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, 0));
+}
+
+template <int BM, int BN, int WM, int WN, bool SWIGLU>
+__global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_kernel(GemmBf16Params p) {
+    constexpr int NT = WM * WN * 64;
+    constexpr int WTM = BM / WM, WTN = BN / WN;
+    constexpr int TM = WTM / 32, TN = WTN / 32;
+    constexpr int A_PER = BM * 8 / NT, B_PER = BN * 8 / NT;
+    constexpr int ROWS_PER_PASS = NT / 8;
+    static_assert(BM * 8 % NT == 0 && BN * 8 % NT == 0, "tile / thread mismatch");
+    static_assert(!SWIGLU || (WTN / 2) % ROWS_PER_PASS == 0 || ROWS_PER_PASS % (WTN / 2) == 0, "swiglu interleave");
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    bf16_t *As = (bf16_t *)smem;                 // [2][BM][LDS_LD]
+    bf16_t *Bs = As + 2 * BM * LDS_LD;           // [2][BN][LDS_LD]
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm0 = (wave / WN) * WTM, wn0 = (wave % WN) * WTN;
+
+    // ---- workgroup -> tile.  Consecutive workgroup ids go round-robin over the 8 XCDs; give each
+    // XCD a contiguous run of tiles (m fastest) so the tiles resident on one XCD share W panels in
+    // that XCD's L2.
+    const int total = p.tiles_m * p.tiles_n;
+    int tile;
+    {
+        const int pid = blockIdx.x, xcd = pid & 7, idx = pid >> 3;
+        const int base = total >> 3, rem = total & 7;
+        tile = xcd * base + min(xcd, rem) + idx;
+    }
+    const int tile_m = tile % p.tiles_m, tile_n = tile / p.tiles_m;
+    const int seg = tile_n >= p.seg_tile0[2] ? 2 : tile_n >= p.seg_tile0[1] ? 1 : 0;
+    const int m0 = tile_m * BM;
+    constexpr int BN_OUT = SWIGLU ? BN / 2 : BN;
+    const int nloc0 = (tile_n - p.seg_tile0[seg]) * BN_OUT;      // first column inside the segment
+    const int seg_rows = p.seg_rows[seg];
+    const int K = p.K;
+
+    const __amdgpu_buffer_rsrc_t rx = make_rsrc(p.X, p.x_bytes);
+    const uint32_t w_bytes = (uint32_t)((int64_t)seg_rows * K * 2);
+    const __amdgpu_buffer_rsrc_t rw = make_rsrc(p.W[seg], w_bytes);
+    const __amdgpu_buffer_rsrc_t ru = make_rsrc(SWIGLU ? p.Wup : p.W[seg], w_bytes);
+
+    // ---- per-thread load slots: chunk id = tid + NT * i -> row id / 8, 16-byte chunk id % 8
+    const int ch = tid & 7;
+    uint32_t a_off[A_PER], b_off[B_PER];
+#pragma unroll
+    for (int i = 0; i < A_PER; ++i) {
+        int gm = m0 + (tid >> 3) + ROWS_PER_PASS * i;
+        a_off[i] = gm < p.M ? (uint32_t)(map_row(p.xmap, p.seq_len, gm) * p.ldx * 2) + ch * 16 : OOB_OFF;
+    }
+#pragma unroll
+    for (int i = 0; i < B_PER; ++i) {
+        int t = (tid >> 3) + ROWS_PER_PASS * i;       // row of the B tile
+        int col;
+        if (SWIGLU) col = nloc0 + (t / WTN) * (WTN / 2) + (t % (WTN / 2));
+        else col = nloc0 + t;
+        b_off[i] = col < seg_rows ? (uint32_t)((int64_t)col * K * 2) + ch * 16 : OOB_OFF;
+    }
+
+    u32x4 ra[A_PER], rb[B_PER];
+    auto issue_loads = [&](int kt) {
+        const int koff = kt * BK + ch * 8;
+        const uint32_t kb = (uint32_t)koff * 2;
+        const bool kin = koff < K;
+#pragma unroll
+        for (int i = 0; i < A_PER; ++i) ra[i] = buf_load16(rx, kin ? a_off[i] + (kb - ch * 16) : OOB_OFF);
+#pragma unroll
+        for (int i = 0; i < B_PER; ++i) {
+            const int t = (tid >> 3) + ROWS_PER_PASS * i;
+            const bool up = SWIGLU && ((t % WTN) >= WTN / 2);
+            const uint32_t off = kin ? b_off[i] + (kb - ch * 16) : OOB_OFF;
+            rb[i] = up ? buf_load16(ru, off) : buf_load16(rw, off);
+        }
+    };
+    auto store_lds = [&](int buf) {
+        bf16_t *a = As + buf * BM * LDS_LD, *b = Bs + buf * BN * LDS_LD;
+#pragma unroll
+        for (int i = 0; i < A_PER; ++i)
+            *(u32x4 *)(a + ((tid >> 3) + ROWS_PER_PASS * i) * LDS_LD + ch * 8) = ra[i];
+#pragma unroll
+        for (int i = 0; i < B_PER; ++i)
+            *(u32x4 *)(b + ((tid >> 3) + ROWS_PER_PASS * i) * LDS_LD + ch * 8) = rb[i];
+    };
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    const int KT = (K + BK - 1) / BK;
+    issue_loads(0);
+    store_lds(0);
+    __syncthreads();
+    const int frag_row = lane & 31, frag_k = (lane >> 5) * 8;
+    for (int kt = 0; kt < KT; ++kt) {
+        const int cur = kt & 1;
+        if (kt + 1 < KT) issue_loads(kt + 1);
+        const bf16_t *a = As + cur * BM * LDS_LD + (wm0 + frag_row) * LDS_LD + frag_k;
+        const bf16_t *b = Bs + cur * BN * LDS_LD + (wn0 + frag_row) * LDS_LD + frag_k;
+#pragma unroll
+        for (int kk = 0; kk < BK / 16; ++kk) {
+            bf16x8 af[TM], bfr[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) af[i] = *(const bf16x8 *)(a + i * 32 * LDS_LD + kk * 16);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) bfr[j] = *(const bf16x8 *)(b + j * 32 * LDS_LD + kk * 16);
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+        }
+        if (kt + 1 < KT) store_lds(cur ^ 1);
+        __syncthreads();
+    }
+
+    // ---- epilogue.  acc[i][j][r]: row 32i + 8(r/4) + 4(lane/32) + r%4, column 32j + lane%32.
+    const int flags = p.flags;
+    const int col_lane = lane & 31, row_lane = (lane >> 5) * 4;
+    constexpr int TN_OUT = SWIGLU ? TN / 2 : TN;
+    const int wcol0 = SWIGLU ? nloc0 + (wn0 / WTN) * (WTN / 2) : nloc0 + wn0;
+    const int gcol0 = p.seg_col0[seg];
+    float bias_v[TN_OUT];
+#pragma unroll
+    for (int j = 0; j < TN_OUT; ++j) {
+        int c = wcol0 + 32 * j + col_lane;
+        bias_v[j] = ((flags & CASCADE_EPI_BIAS) && p.bias[seg] && c < seg_rows) ? (float)p.bias[seg][c] : 0.f;
+    }
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int gm = m0 + wm0 + 32 * i + 8 * (r / 4) + row_lane + (r % 4);
+            if (gm >= p.M) continue;
+            bf16_t *yrow = p.Y + map_row(p.ymap, p.seq_len, gm) * p.ldy + gcol0;
+            const bf16_t *rrow = (flags & CASCADE_EPI_RESIDUAL)
+                                     ? p.residual + map_row(p.rmap, p.seq_len, gm) * p.ldres + gcol0 : nullptr;
+#pragma unroll
+            for (int j = 0; j < TN_OUT; ++j) {
+                const int c = wcol0 + 32 * j + col_lane;
+                if (c >= seg_rows) continue;
+                float v = acc[i][j][r] + bias_v[j];
+                if (SWIGLU) v = silu_f(v) * acc[i][j + TN_OUT][r];
+                else v = apply_act(v, flags);
+                if (rrow) v += (float)rrow[c];
+                yrow[c] = (bf16_t)v;
+            }
+        }
+    }
+}
+
+template <int BM, int BN, int WM, int WN, bool SWIGLU>
+static int32_t launch_cfg(const GemmArgs &a, hipStream_t s) {
+    GemmBf16Params p;
+    constexpr int BN_OUT = SWIGLU ? BN / 2 : BN;
+    int col0 = 0, tile0 = 0;
+    for (int i = 0; i < 3; ++i) {
+        int end = a.seg_end[i];
+        int rows = std::max(0, end - col0);
+        p.W[i] = (const bf16_t *)a.W[i];
+        p.bias[i] = (const bf16_t *)a.bias[i];
+        p.seg_rows[i] = rows;
+        p.seg_col0[i] = col0;
+        p.seg_tile0[i] = tile0;
+        tile0 += (rows + BN_OUT - 1) / BN_OUT;
+        col0 = std::max(col0, end);
+        if (rows == 0) p.seg_tile0[i] = INT32_MAX;            // never selected
+        if ((int64_t)rows * a.K * 2 >= (int64_t)OOB_OFF) return CASCADE_EUNSUPPORTED;
+    }
+    if (p.seg_tile0[0] == INT32_MAX) return CASCADE_ESHAPE;
+    p.seg_tile0[0] = 0;
+    p.X = (const bf16_t *)a.X; p.Wup = (const bf16_t *)a.W_up; p.residual = (const bf16_t *)a.residual;
+    p.Y = (bf16_t *)a.Y;
+    p.M = a.M; p.K = a.K;
+    p.tiles_m = (a.M + BM - 1) / BM; p.tiles_n = tile0;
+    p.ldx = a.ldx; p.ldy = a.ldy; p.ldres = a.ldres;
+    p.xmap = a.xmap.map; p.ymap = a.ymap.map; p.rmap = a.rmap.map;
+    p.seq_len = a.xmap.map ? a.xmap.seq_len : a.ymap.map ? a.ymap.seq_len : a.rmap.map ? a.rmap.seq_len : 1;
+    p.flags = a.epilogue;
+    int64_t xb = (int64_t)a.M * a.ldx * 2;                     // rows of X are a permutation of [0, M)
+    if (xb >= (int64_t)OOB_OFF) return CASCADE_EUNSUPPORTED;
+    p.x_bytes = (uint32_t)xb;
+    constexpr size_t lds = (size_t)2 * (BM + BN) * LDS_LD * sizeof(bf16_t);
+    auto kern = gemm_bf16_kernel<BM, BN, WM, WN, SWIGLU>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        CASCADE_HIP_TRY(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        attr_set = true;
+    }
+    int64_t total = (int64_t)p.tiles_m * p.tiles_n;
+    if (total > INT32_MAX) return CASCADE_EUNSUPPORTED;
+    hipLaunchKernelGGL(kern, dim3((unsigned)total), dim3(WM * WN * 64), lds, s, p);
+    CASCADE_HIP_TRY(hipGetLastError());
+    return CASCADE_OK;
+}
+
+int32_t launch_gemm_bf16(const GemmArgs &a, hipStream_t s) {
+    if (a.M == 0 || a.N == 0) return CASCADE_OK;
+    if (a.K % 8 != 0 || a.ldx % 8 != 0) return CASCADE_EUNSUPPORTED;
+    if (((uintptr_t)a.X | (uintptr_t)a.W[0] | (uintptr_t)a.W[1] | (uintptr_t)a.W[2] | (uintptr_t)a.W_up) % 16)
+        return CASCADE_EUNSUPPORTED;
+    const bool swiglu = a.epilogue & CASCADE_EPI_SWIGLU;
+    // Tile choice: the large tile when it still yields at least ~one workgroup per CU.
+    const int64_t big_tiles = (int64_t)((a.M + 255) / 256) * ((a.N + (swiglu ? 127 : 255)) / (swiglu ? 128 : 256));
+    if (swiglu) {
+        if (big_tiles >= 200) return launch_cfg<256, 256, 2, 2, true>(a, s);
+        return launch_cfg<128, 256, 2, 2, true>(a, s);
+    }
+    if (big_tiles >= 200) return launch_cfg<256, 256, 2, 2, false>(a, s);
+    if (a.M > 64) return launch_cfg<128, 256, 2, 2, false>(a, s);
+    return launch_cfg<64, 256, 1, 4, false>(a, s);
+}

@@ -1,0 +1,141 @@
+// Log-sum-exp merge of the per-shard partials (Algorithm 4 lines 1-8; derivation in the
+// Post-Pass subsection):  n = max_k m_k,  w = sum_k exp(m_k - n) e_k,
+// o = sum_k exp(m_k - n) e_k u_k / w   (with u~ = e u stored: o = sum_k exp(m_k - n) u~_k / w).
+// HBM-bound: one pass over n_shards rows of d floats per (batch, head, query row).
+//
+// Layout: m, e [B, H, S, N]; u [B, S, H, N, d]; o [B, N, H*d].
+// A group of G = d/4 lanes owns one (b, h, r): lane s of the group holds columns 4s..4s+3.
+// A wavefront therefore covers 64/G consecutive rows r of the same (b, h); the statistics of a
+// row are split over the group's lanes (lane s reads shards s, s+G, ...) and combined with
+// xor-shuffles inside the group.
+#include "common.h"
+#include "device_utils.h"
+
+template <typename T, int G>
+__global__ __launch_bounds__(256) void merge_vec_kernel(const float *__restrict__ m, const float *__restrict__ e,
+                                                        const float *__restrict__ u, T *__restrict__ o,
+                                                        float *__restrict__ lse, int B, int H, int S, int N,
+                                                        int64_t o_ld, const int32_t *__restrict__ omap, int u_mode) {
+    constexpr int d = G * 4;
+    constexpr int RW = 64 / G;                  // rows per wavefront
+    constexpr int RB = RW * 4;                  // rows per block
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int s = lane % G;
+    const int r = blockIdx.x * RB + wave * RW + lane / G;
+    const int h = blockIdx.y, b = blockIdx.z;
+    const bool live = r < N;
+    const int rr = live ? r : N - 1;            // clamp: dead lanes repeat the last row and do not store
+    const float *mrow = m + ((int64_t)(b * H + h) * S) * N + rr;
+    const float *erow = e + ((int64_t)(b * H + h) * S) * N + rr;
+
+    float n = -INFINITY;
+    for (int k = s; k < S; k += G) n = fmaxf(n, mrow[(int64_t)k * N]);
+#pragma unroll
+    for (int off = G / 2; off > 0; off >>= 1) n = fmaxf(n, __shfl_xor(n, off, WAVE));
+    const float n_sub = (n == -INFINITY) ? 0.f : n;
+
+    float w = 0.f;
+    for (int k = s; k < S; k += G) {
+        float mk = mrow[(int64_t)k * N];
+        float c = (mk == -INFINITY) ? 0.f : expf(mk - n_sub);
+        w += c * erow[(int64_t)k * N];
+    }
+#pragma unroll
+    for (int off = G / 2; off > 0; off >>= 1) w += __shfl_xor(w, off, WAVE);
+
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    const float *ub = u + (((int64_t)b * S * H + h) * N + rr) * d + 4 * s;
+    const int64_t ustep = (int64_t)H * N * d;
+#pragma unroll 4
+    for (int k = 0; k < S; ++k) {
+        float mk = mrow[(int64_t)k * N];
+        float c = (mk == -INFINITY) ? 0.f : expf(mk - n_sub);
+        if (u_mode == CASCADE_U_NORMALISED) c *= erow[(int64_t)k * N];
+        f32x4 uv = *(const f32x4 *)(ub + k * ustep);
+        acc += c * uv;
+    }
+    const float inv = w > 0.f ? 1.0f / w : 0.f;
+    acc *= inv;
+    if (live) {
+        int64_t orow = (int64_t)b * N + (omap ? omap[r] : r);
+        T *op = o + orow * o_ld + (int64_t)h * d + 4 * s;
+        if constexpr (sizeof(T) == 2) {
+            bf16x4 v = {(bf16_t)acc[0], (bf16_t)acc[1], (bf16_t)acc[2], (bf16_t)acc[3]};
+            *(bf16x4 *)op = v;
+        } else {
+            *(f32x4 *)op = acc;
+        }
+        if (lse && s == 0) lse[((int64_t)b * H + h) * N + r] = w > 0.f ? n + logf(w) : -INFINITY;
+    }
+}
+
+// Any d: one wavefront per (b, h, r), lanes stride over the columns.
+template <typename T>
+__global__ __launch_bounds__(256) void merge_scalar_kernel(const float *__restrict__ m, const float *__restrict__ e,
+                                                           const float *__restrict__ u, T *__restrict__ o,
+                                                           float *__restrict__ lse, int B, int H, int S, int N, int d,
+                                                           int64_t o_ld, const int32_t *__restrict__ omap, int u_mode) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int r = blockIdx.x * 4 + wave;
+    const int h = blockIdx.y, b = blockIdx.z;
+    if (r >= N) return;
+    const float *mrow = m + ((int64_t)(b * H + h) * S) * N + r;
+    const float *erow = e + ((int64_t)(b * H + h) * S) * N + r;
+    float n = -INFINITY;
+    for (int k = lane; k < S; k += 64) n = fmaxf(n, mrow[(int64_t)k * N]);
+    n = wave_max(n);
+    const float n_sub = (n == -INFINITY) ? 0.f : n;
+    float w = 0.f;
+    for (int k = lane; k < S; k += 64) {
+        float mk = mrow[(int64_t)k * N];
+        w += ((mk == -INFINITY) ? 0.f : expf(mk - n_sub)) * erow[(int64_t)k * N];
+    }
+    w = wave_sum(w);
+    const float inv = w > 0.f ? 1.0f / w : 0.f;
+    int64_t orow = (int64_t)b * N + (omap ? omap[r] : r);
+    for (int c = lane; c < d; c += 64) {
+        float acc = 0.f;
+        for (int k = 0; k < S; ++k) {
+            float mk = mrow[(int64_t)k * N];
+            float cf = (mk == -INFINITY) ? 0.f : expf(mk - n_sub);
+            if (u_mode == CASCADE_U_NORMALISED) cf *= erow[(int64_t)k * N];
+            acc += cf * u[((((int64_t)b * S + k) * H + h) * N + r) * d + c];
+        }
+        Elem<T>::store(o + orow * o_ld + (int64_t)h * d + c, acc * inv);
+    }
+    if (lse && lane == 0) lse[((int64_t)b * H + h) * N + r] = w > 0.f ? n + logf(w) : -INFINITY;
+}
+
+template <typename T>
+static int32_t launch_merge_t(const MergeArgs &a, hipStream_t s) {
+    const int G = a.d / 4;
+    const bool vec = a.d % 4 == 0 && (G == 4 || G == 8 || G == 16 || G == 32 || G == 64) &&
+                     ((uintptr_t)a.u % 16 == 0) && ((uintptr_t)a.o % (4 * sizeof(T)) == 0) &&
+                     (a.o_ld * sizeof(T)) % (4 * sizeof(T)) == 0;
+#define MERGE_CASE(GG)                                                                                          \
+    case GG: {                                                                                                  \
+        constexpr int RB = (64 / GG) * 4;                                                                       \
+        dim3 grid((a.N + RB - 1) / RB, a.H, a.B);                                                               \
+        hipLaunchKernelGGL((merge_vec_kernel<T, GG>), grid, dim3(256), 0, s, a.m, a.e, a.u, (T *)a.o, a.lse,    \
+                           a.B, a.H, a.n_shards, a.N, a.o_ld, a.o_rowmap, a.u_mode);                            \
+        break;                                                                                                  \
+    }
+    if (vec) {
+        switch (G) {
+            MERGE_CASE(4) MERGE_CASE(8) MERGE_CASE(16) MERGE_CASE(32) MERGE_CASE(64)
+        }
+    } else {
+        dim3 grid((a.N + 3) / 4, a.H, a.B);
+        hipLaunchKernelGGL(merge_scalar_kernel<T>, grid, dim3(256), 0, s, a.m, a.e, a.u, (T *)a.o, a.lse, a.B, a.H,
+                           a.n_shards, a.N, a.d, a.o_ld, a.o_rowmap, a.u_mode);
+    }
+#undef MERGE_CASE
+    CASCADE_HIP_TRY(hipGetLastError());
+    return CASCADE_OK;
+}
+
+int32_t launch_merge(const MergeArgs &a, hipStream_t s) {
+    if (a.B == 0 || a.N == 0 || a.H == 0) return CASCADE_OK;
+    if (a.H > 65535 || a.B > 65535) return CASCADE_EUNSUPPORTED;
+    return a.dtype == CASCADE_BF16 ? launch_merge_t<bf16_t>(a, s) : launch_merge_t<float>(a, s);
+}

@@ -1,0 +1,144 @@
+// Shard plan: the partition of [N] (Section 5.1) as index maps and tile lists.
+// Host integer work only; the results are copied to the device once.
+#include <climits>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+#include "common.h"
+
+static thread_local int32_t g_last_hip_error = 0;
+
+void cascade_set_hip_error(hipError_t e) { g_last_hip_error = (int32_t)e; }
+
+extern "C" int32_t cascade_last_hip_error(void) { return g_last_hip_error; }
+
+static void free_plan(cascade_plan *p) {
+    if (!p) return;
+    free(p->perm_h); free(p->inv_perm_h); free(p->offsets_h); free(p->pos_packed_h);
+    if (p->perm_d) (void)hipFree(p->perm_d);
+    if (p->inv_perm_d) (void)hipFree(p->inv_perm_d);
+    if (p->offsets_d) (void)hipFree(p->offsets_d);
+    if (p->pos_packed_d) (void)hipFree(p->pos_packed_d);
+    for (auto &t : p->tiles) {
+        if (t.dev) (void)hipFree(t.dev);
+        if (t.shard_first) (void)hipFree(t.shard_first);
+        free(t.shard_first_host);
+    }
+    delete p;
+}
+
+template <typename T>
+static hipError_t to_device(T **dst, const T *src, size_t n) {
+    *dst = nullptr;
+    size_t bytes = (n ? n : 1) * sizeof(T);
+    hipError_t e = hipMalloc((void **)dst, bytes);
+    if (e != hipSuccess) return e;
+    if (n) e = hipMemcpy(*dst, src, n * sizeof(T), hipMemcpyHostToDevice);
+    return e;
+}
+
+// Tiles of at most `granule` packed rows, each inside one shard, in packed order.
+static hipError_t build_tiles(cascade_plan *p, CascadeTileList &out, int granule) {
+    std::vector<CascadeTile> tiles;
+    std::vector<int32_t> first(p->n_shards + 1, 0);
+    for (int j = 0; j < p->n_shards; ++j) {
+        first[j] = (int32_t)tiles.size();
+        for (int r = p->offsets_h[j]; r < p->offsets_h[j + 1]; r += granule) {
+            CascadeTile t;
+            memset(&t, 0, sizeof(t));
+            t.row_start = r;
+            t.n_rows = std::min(granule, p->offsets_h[j + 1] - r);
+            t.shard = j;
+            t.pmin = INT_MAX;
+            t.pmax = INT_MIN;
+            for (int g = 0; g < 8; ++g) { t.sub_min[g] = INT_MAX; t.sub_max[g] = INT_MIN; }
+            for (int i = 0; i < t.n_rows; ++i) {
+                int pos = p->pos_packed_h[r + i];
+                int g = i / 32;
+                t.sub_min[g] = std::min(t.sub_min[g], pos);
+                t.sub_max[g] = std::max(t.sub_max[g], pos);
+                t.pmin = std::min(t.pmin, pos);
+                t.pmax = std::max(t.pmax, pos);
+            }
+            tiles.push_back(t);
+        }
+    }
+    first[p->n_shards] = (int32_t)tiles.size();
+    out.granule = granule;
+    out.count = (int32_t)tiles.size();
+    out.shard_first_host = (int32_t *)malloc(first.size() * sizeof(int32_t));
+    if (!out.shard_first_host) return hipErrorOutOfMemory;
+    memcpy(out.shard_first_host, first.data(), first.size() * sizeof(int32_t));
+    hipError_t e = to_device(&out.dev, tiles.data(), tiles.size());
+    if (e != hipSuccess) return e;
+    return to_device(&out.shard_first, first.data(), first.size());
+}
+
+extern "C" int32_t cascade_plan_create(cascade_plan **out, int32_t batch, int32_t seq_len, int32_t n_shards,
+                                       const int32_t *token_to_shard_host, const int32_t *positions_host,
+                                       int32_t mask_kind) {
+    if (!out) return CASCADE_EINVAL;
+    *out = nullptr;
+    if (!token_to_shard_host || batch <= 0 || seq_len <= 0 || n_shards <= 0) return CASCADE_EINVAL;
+    if (mask_kind != CASCADE_MASK_NONE && mask_kind != CASCADE_MASK_CAUSAL) return CASCADE_EINVAL;
+    if ((int64_t)batch * seq_len > INT32_MAX / 2) return CASCADE_EUNSUPPORTED;
+    for (int t = 0; t < seq_len; ++t)
+        if (token_to_shard_host[t] < 0 || token_to_shard_host[t] >= n_shards) return CASCADE_EASSIGN;
+
+    cascade_plan *p = new (std::nothrow) cascade_plan();
+    if (!p) return CASCADE_EINVAL;
+    memset(p, 0, sizeof(*p));
+    p->batch = batch; p->seq_len = seq_len; p->n_shards = n_shards; p->mask_kind = mask_kind;
+    p->perm_h = (int32_t *)malloc(sizeof(int32_t) * seq_len);
+    p->inv_perm_h = (int32_t *)malloc(sizeof(int32_t) * seq_len);
+    p->offsets_h = (int32_t *)malloc(sizeof(int32_t) * (n_shards + 1));
+    p->pos_packed_h = (int32_t *)malloc(sizeof(int32_t) * seq_len);
+    if (!p->perm_h || !p->inv_perm_h || !p->offsets_h || !p->pos_packed_h) { free_plan(p); return CASCADE_EINVAL; }
+
+    // Counting sort by shard id: stable, so rows inside a shard stay in ascending token index.
+    memset(p->offsets_h, 0, sizeof(int32_t) * (n_shards + 1));
+    for (int t = 0; t < seq_len; ++t) p->offsets_h[token_to_shard_host[t] + 1]++;
+    for (int j = 0; j < n_shards; ++j) p->offsets_h[j + 1] += p->offsets_h[j];
+    {
+        std::vector<int32_t> cursor(p->offsets_h, p->offsets_h + n_shards);
+        for (int t = 0; t < seq_len; ++t) {
+            int r = cursor[token_to_shard_host[t]]++;
+            p->perm_h[r] = t;
+            p->inv_perm_h[t] = r;
+        }
+    }
+    for (int r = 0; r < seq_len; ++r)
+        p->pos_packed_h[r] = positions_host ? positions_host[p->perm_h[r]] : p->perm_h[r];
+
+    hipError_t e = hipGetDevice(&p->device);
+    if (e == hipSuccess) e = to_device(&p->perm_d, p->perm_h, seq_len);
+    if (e == hipSuccess) e = to_device(&p->inv_perm_d, p->inv_perm_h, seq_len);
+    if (e == hipSuccess) e = to_device(&p->offsets_d, p->offsets_h, n_shards + 1);
+    if (e == hipSuccess) e = to_device(&p->pos_packed_d, p->pos_packed_h, seq_len);
+    static const int granules[4] = {32, 64, 128, 256};
+    for (int g = 0; g < 4 && e == hipSuccess; ++g) e = build_tiles(p, p->tiles[g], granules[g]);
+    if (e != hipSuccess) { cascade_set_hip_error(e); free_plan(p); return CASCADE_EHIP; }
+    *out = p;
+    return CASCADE_OK;
+}
+
+extern "C" int32_t cascade_plan_maps(const cascade_plan *plan, const int32_t **perm_dev,
+                                     const int32_t **inv_perm_dev, const int32_t **offsets_dev) {
+    if (!plan) return CASCADE_EINVAL;
+    if (perm_dev) *perm_dev = plan->perm_d;
+    if (inv_perm_dev) *inv_perm_dev = plan->inv_perm_d;
+    if (offsets_dev) *offsets_dev = plan->offsets_d;
+    return CASCADE_OK;
+}
+
+extern "C" int32_t cascade_plan_maps_host(const cascade_plan *plan, const int32_t **perm_host,
+                                          const int32_t **inv_perm_host, const int32_t **offsets_host) {
+    if (!plan) return CASCADE_EINVAL;
+    if (perm_host) *perm_host = plan->perm_h;
+    if (inv_perm_host) *inv_perm_host = plan->inv_perm_h;
+    if (offsets_host) *offsets_host = plan->offsets_h;
+    return CASCADE_OK;
+}
+
+extern "C" void cascade_plan_destroy(cascade_plan *plan) { free_plan(plan); }

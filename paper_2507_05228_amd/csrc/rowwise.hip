@@ -1,0 +1,143 @@
+// HBM-bound per-token kernels: normalisation with row gather (Pre-Pass subsection: "applies
+// layer normalization if necessary"), rotary embedding at original token positions
+// (Algorithm 2 lines 4-5), and row gather / scatter between original and packed order.
+#include "common.h"
+#include "device_utils.h"
+
+// ---------------------------------------------------------------------------- norm
+// One 256-thread block per row; the row is staged in LDS as fp32 (D * 4 bytes).
+template <typename T>
+__global__ __launch_bounds__(256) void norm_kernel(const T *__restrict__ x, const T *__restrict__ gain,
+                                                   const T *__restrict__ bias, T *__restrict__ y, int D, int kind,
+                                                   float eps, const int32_t *xmap, int seq_len) {
+    extern __shared__ float row[];
+    __shared__ float red[4];
+    const int r = blockIdx.x;
+    const T *xr = x + map_row(xmap, seq_len, r) * (int64_t)D;
+    float s = 0.f;
+    for (int i = threadIdx.x; i < D; i += 256) {
+        float v = Elem<T>::load(xr + i);
+        row[i] = v;
+        s += v;
+    }
+    float mu = 0.f;
+    if (kind == CASCADE_NORM_LAYERNORM) mu = block_sum_256(s, red) / D;
+    float q = 0.f;
+    for (int i = threadIdx.x; i < D; i += 256) {
+        float c = row[i] - mu;
+        q += c * c;
+    }
+    float var = block_sum_256(q, red) / D;
+    float rstd = 1.0f / sqrtf(var + eps);
+    T *yr = y + (int64_t)r * D;
+    for (int i = threadIdx.x; i < D; i += 256) {
+        float v = (row[i] - mu) * rstd * Elem<T>::load(gain + i);
+        if (bias) v += Elem<T>::load(bias + i);
+        Elem<T>::store(yr + i, v);
+    }
+}
+
+int32_t launch_norm(const NormArgs &a, hipStream_t s) {
+    if (a.rows == 0) return CASCADE_OK;
+    size_t lds = (size_t)a.D * sizeof(float);
+    if (lds > 64 * 1024) return CASCADE_EUNSUPPORTED;
+    if (a.dtype == CASCADE_BF16)
+        hipLaunchKernelGGL(norm_kernel<bf16_t>, dim3(a.rows), dim3(256), lds, s, (const bf16_t *)a.x,
+                           (const bf16_t *)a.gain, (const bf16_t *)a.bias, (bf16_t *)a.y, a.D, a.kind, a.eps,
+                           a.xmap.map, a.xmap.seq_len);
+    else
+        hipLaunchKernelGGL(norm_kernel<float>, dim3(a.rows), dim3(256), lds, s, (const float *)a.x,
+                           (const float *)a.gain, (const float *)a.bias, (float *)a.y, a.D, a.kind, a.eps,
+                           a.xmap.map, a.xmap.seq_len);
+    CASCADE_HIP_TRY(hipGetLastError());
+    return CASCADE_OK;
+}
+
+// ---------------------------------------------------------------------------- rotary embedding
+// Half-split pairing (i, i + d/2), angle = position * theta^(-2i/d); position = the token's own
+// position (pos_packed[r mod N]), never the shard-local row number.  One thread per pair.
+template <typename T, typename ANG>
+__global__ __launch_bounds__(256) void rope_kernel(T *__restrict__ x, int64_t total_pairs, int n_rope_heads,
+                                                   int head_dim, int64_t ld, float theta,
+                                                   const int32_t *__restrict__ pos_packed, int seq_len) {
+    const int half = head_dim >> 1;
+    const int64_t pairs_per_row = (int64_t)n_rope_heads * half;
+    for (int64_t id = blockIdx.x * 256ll + threadIdx.x; id < total_pairs; id += (int64_t)gridDim.x * 256) {
+        int64_t r = id / pairs_per_row;
+        int rem = (int)(id - r * pairs_per_row);
+        int h = rem / half, i = rem - h * half;
+        int pos = pos_packed[(int)(r % seq_len)];
+        ANG inv_freq = (ANG)exp2((ANG)(-2.0 * i / head_dim) * (ANG)log2((ANG)theta));
+        ANG ang = (ANG)pos * inv_freq;
+        ANG sn = sin(ang), cs = cos(ang);
+        T *p = x + r * ld + (int64_t)h * head_dim + i;
+        ANG a = (ANG)Elem<T>::load(p), b = (ANG)Elem<T>::load(p + half);
+        Elem<T>::store(p, (float)(a * cs - b * sn));
+        Elem<T>::store(p + half, (float)(b * cs + a * sn));
+    }
+}
+
+int32_t launch_rope(const RopeArgs &a, hipStream_t s) {
+    int64_t total = (int64_t)a.rows * a.n_rope_heads * (a.head_dim / 2);
+    if (total == 0) return CASCADE_OK;
+    int grid = (int)std::min<int64_t>((total + 255) / 256, 65536);
+    if (a.dtype == CASCADE_BF16)
+        hipLaunchKernelGGL((rope_kernel<bf16_t, float>), dim3(grid), dim3(256), 0, s, (bf16_t *)a.x, total,
+                           a.n_rope_heads, a.head_dim, a.ld, a.theta, a.pos_packed, a.seq_len);
+    else
+        hipLaunchKernelGGL((rope_kernel<float, double>), dim3(grid), dim3(256), 0, s, (float *)a.x, total,
+                           a.n_rope_heads, a.head_dim, a.ld, a.theta, a.pos_packed, a.seq_len);
+    CASCADE_HIP_TRY(hipGetLastError());
+    return CASCADE_OK;
+}
+
+// ---------------------------------------------------------------------------- gather / scatter of rows
+// y[ymap(r)] = x[xmap(r)] in 16-byte pieces (width_bytes % 16 == 0) or element by element.
+__global__ __launch_bounds__(256) void copy_rows16_kernel(const uint4 *__restrict__ x, uint4 *__restrict__ y,
+                                                          int rows, int vec_per_row, int64_t ldx_v, int64_t ldy_v,
+                                                          const int32_t *xmap, const int32_t *ymap, int seq_len) {
+    int64_t total = (int64_t)rows * vec_per_row;
+    for (int64_t id = blockIdx.x * 256ll + threadIdx.x; id < total; id += (int64_t)gridDim.x * 256) {
+        int r = (int)(id / vec_per_row);
+        int c = (int)(id - (int64_t)r * vec_per_row);
+        y[map_row(ymap, seq_len, r) * ldy_v + c] = x[map_row(xmap, seq_len, r) * ldx_v + c];
+    }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void copy_rows_kernel(const T *__restrict__ x, T *__restrict__ y, int rows,
+                                                        int width, int64_t ldx, int64_t ldy, const int32_t *xmap,
+                                                        const int32_t *ymap, int seq_len) {
+    int64_t total = (int64_t)rows * width;
+    for (int64_t id = blockIdx.x * 256ll + threadIdx.x; id < total; id += (int64_t)gridDim.x * 256) {
+        int r = (int)(id / width);
+        int c = (int)(id - (int64_t)r * width);
+        y[map_row(ymap, seq_len, r) * ldy + c] = x[map_row(xmap, seq_len, r) * ldx + c];
+    }
+}
+
+int32_t launch_copy_rows(const CopyRowsArgs &a, hipStream_t s) {
+    if (a.rows == 0 || a.width == 0) return CASCADE_OK;
+    const int es = a.dtype == CASCADE_BF16 ? 2 : 4;
+    const int seq = a.xmap.map ? a.xmap.seq_len : a.ymap.seq_len;
+    const bool vec = ((int64_t)a.width * es) % 16 == 0 && (a.ldx * es) % 16 == 0 && (a.ldy * es) % 16 == 0 &&
+                     ((uintptr_t)a.x % 16 == 0) && ((uintptr_t)a.y % 16 == 0);
+    if (vec) {
+        int vpr = a.width * es / 16;
+        int64_t total = (int64_t)a.rows * vpr;
+        int grid = (int)std::min<int64_t>((total + 255) / 256, 1 << 20);
+        hipLaunchKernelGGL(copy_rows16_kernel, dim3(grid), dim3(256), 0, s, (const uint4 *)a.x, (uint4 *)a.y, a.rows,
+                           vpr, a.ldx * es / 16, a.ldy * es / 16, a.xmap.map, a.ymap.map, seq);
+    } else {
+        int64_t total = (int64_t)a.rows * a.width;
+        int grid = (int)std::min<int64_t>((total + 255) / 256, 1 << 20);
+        if (es == 2)
+            hipLaunchKernelGGL(copy_rows_kernel<uint16_t>, dim3(grid), dim3(256), 0, s, (const uint16_t *)a.x,
+                               (uint16_t *)a.y, a.rows, a.width, a.ldx, a.ldy, a.xmap.map, a.ymap.map, seq);
+        else
+            hipLaunchKernelGGL(copy_rows_kernel<uint32_t>, dim3(grid), dim3(256), 0, s, (const uint32_t *)a.x,
+                               (uint32_t *)a.y, a.rows, a.width, a.ldx, a.ldy, a.xmap.map, a.ymap.map, seq);
+    }
+    CASCADE_HIP_TRY(hipGetLastError());
+    return CASCADE_OK;
+}

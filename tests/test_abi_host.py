@@ -1,0 +1,85 @@
+"""CPU-side checks of the boundary: the shared library loads, exports every symbol the header
+declares, and the ctypes mirrors of the descriptor structs have the header's layout.
+No compute call is made here (there is no GPU in this environment)."""
+import ctypes as C
+import os
+import re
+import subprocess
+
+import pytest
+
+import paper_2507_05228_amd as cas
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "cascade.h")
+
+
+def declared_symbols():
+    text = open(HEADER).read()
+    return sorted(set(re.findall(r"CASCADE_API\s+[\w\s\*]+?\b(cascade_\w+)\s*\(", text)))
+
+
+@pytest.fixture(scope="module")
+def lib_path():
+    if not os.path.exists(cas.LIB_PATH):
+        import __graft_entry__
+        __graft_entry__.build()
+    return cas.LIB_PATH
+
+
+def test_header_declares_the_four_ops():
+    names = declared_symbols()
+    for op in ("cascade_shard_gemm", "cascade_partial_attn", "cascade_lse_merge", "cascade_layer_forward"):
+        assert op in names
+
+
+def test_library_exports_every_declared_symbol(lib_path):
+    lib = C.CDLL(lib_path)
+    for name in declared_symbols():
+        assert hasattr(lib, name), name
+    assert sorted(cas.EXPORTS) == declared_symbols()
+
+
+def test_binding_has_the_same_names():
+    for name in ("cascade_plan_create", "cascade_plan_maps", "cascade_shard_gemm", "cascade_partial_attn",
+                 "cascade_lse_merge", "cascade_layer_forward", "cascade_layer_workspace_bytes"):
+        assert callable(getattr(cas, name))
+
+
+def test_struct_layouts_match_the_header(tmp_path):
+    """Compile a tiny C program against the header and compare sizeof / offsetof with ctypes."""
+    src = tmp_path / "layout.c"
+    src.write_text(
+        '#include <stdio.h>\n#include <stddef.h>\n#include "cascade.h"\n'
+        "int main(void){\n"
+        'printf("%zu %zu %zu %zu\\n", sizeof(cascade_gemm_desc), sizeof(cascade_attn_desc),'
+        " sizeof(cascade_layer_desc), sizeof(cascade_layer_weights));\n"
+        'printf("%zu %zu %zu\\n", offsetof(cascade_attn_desc, q_stride_b), offsetof(cascade_layer_desc, io_rows),'
+        " offsetof(cascade_layer_weights, norm2_b));\n"
+        'printf("%zu\\n", offsetof(cascade_gemm_desc, rope_theta));\n'
+        "return 0;}\n")
+    exe = tmp_path / "layout"
+    subprocess.run(["gcc", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()
+    got = [int(t) for t in out]
+    want = [C.sizeof(cas.GemmDesc), C.sizeof(cas.AttnDesc), C.sizeof(cas.LayerDesc), C.sizeof(cas.LayerWeights),
+            cas.AttnDesc.q_stride_b.offset, cas.LayerDesc.io_rows.offset, cas.LayerWeights.norm2_b.offset,
+            cas.GemmDesc.rope_theta.offset]
+    assert got == want
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    monkeypatch.setattr(cas, "_lib", None)
+    monkeypatch.setattr(cas, "LIB_PATH", str(tmp_path / "nope.so"))
+    with pytest.raises(RuntimeError, match="no fallback"):
+        cas.load_library()
+
+
+def test_product_package_does_not_import_the_oracle():
+    for dirpath, _, files in os.walk(os.path.join(ROOT, "paper_2507_05228_amd")):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text.lower().replace("no cpu fallback", ""), f
+    text = open(os.path.join(ROOT, "oracle", "cascade_oracle.py")).read()
+    assert "paper_2507_05228_amd" not in text and "ctypes" not in text

@@ -1,0 +1,426 @@
+"""Parity of the HIP library (through the C-ABI binding) against the float64 CPU oracle on the same
+seeded inputs.  Tolerances: max|gpu - ref| / max|ref| per tensor <= 1e-5 (fp32) or 2e-2 (bf16 with
+fp32 accumulation); shard maps bit-exact."""
+import numpy as np
+import pytest
+
+from cascade_inputs import CONFIGS, make_assignment, make_hidden, make_layer_weights, round_to_bf16
+from oracle import cascade_oracle as orc
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-5, "bf16": 2e-2}
+
+
+@pytest.fixture(scope="module")
+def cas():
+    import torch
+    assert torch.cuda.is_available()
+    import paper_2507_05228_amd as cas
+    cas.load_library()          # raises if the HIP library is missing: no fallback
+    return cas
+
+
+def rel_err(g, r):
+    return float(np.abs(np.asarray(g, dtype=np.float64) - r).max() / max(np.abs(r).max(), 1e-300))
+
+
+def dev(cas, x, dtype):
+    return cas.to_device(x, dtype)
+
+
+def host(t):
+    return t.float().cpu().numpy().astype(np.float64)
+
+
+def rand(rng, shape, dtype, std=1.0):
+    x = (rng.standard_normal(shape) * std).astype(np.float32)
+    return round_to_bf16(x) if dtype == "bf16" else x
+
+
+# ---------------------------------------------------------------------------- plan
+@pytest.mark.parametrize("kind,N,beta", [("perm", 128, 4), ("contiguous", 1024, 8), ("roundrobin", 512, 64),
+                                         ("ragged", 333, 7), ("ragged", 40, 16), ("perm", 2048, 16)])
+def test_plan_maps_bit_exact(cas, kind, N, beta):
+    a = make_assignment(kind, N, beta, 5)
+    plan = cas.cascade_plan_create(2, N, beta, a)
+    off_r, perm_r, inv_r = orc.shard_plan(a, beta)
+    perm_h, inv_h, off_h = cas.cascade_plan_maps_host(plan)
+    perm_d, inv_d, off_d = (t.cpu().numpy() for t in cas.cascade_plan_maps(plan))
+    for got in (perm_h, perm_d):
+        assert got.dtype == np.int32 and np.array_equal(got, perm_r)
+    for got in (inv_h, inv_d):
+        assert np.array_equal(got, inv_r)
+    for got in (off_h, off_d):
+        assert np.array_equal(got, off_r)
+
+
+def test_plan_error_paths(cas):
+    a = np.zeros(16, dtype=np.int32)
+    with pytest.raises(cas.CascadeError) as ei:
+        bad = a.copy(); bad[3] = 4
+        cas.cascade_plan_create(1, 16, 4, bad)
+    assert ei.value.status == cas.EASSIGN
+    with pytest.raises(cas.CascadeError) as ei:
+        bad = a.copy(); bad[0] = -1
+        cas.cascade_plan_create(1, 16, 4, bad)
+    assert ei.value.status == cas.EASSIGN
+    for args in ((0, 16, 4), (1, 16, 0)):
+        with pytest.raises(cas.CascadeError) as ei:
+            cas.cascade_plan_create(*args, a)
+        assert ei.value.status == cas.EINVAL
+    with pytest.raises(cas.CascadeError) as ei:
+        cas.cascade_plan_create(1, 16, 4, a, mask_kind=7)
+    assert ei.value.status == cas.EINVAL
+
+
+# ---------------------------------------------------------------------------- shard GEMM
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("M_N_K", [(128, 192, 64), (300, 200, 136), (512, 1000, 264), (40, 24, 8)])
+def test_shard_gemm_plain(cas, dtype, M_N_K):
+    import torch
+    M, N, K = M_N_K
+    rng = np.random.default_rng(M + N + K)
+    x, w = rand(rng, (M, K), dtype), rand(rng, (N, K), dtype, 0.1)
+    X, W = dev(cas, x, dtype), dev(cas, w, dtype)
+    Y = torch.empty(M, N, dtype=X.dtype, device="cuda")
+    cas.cascade_shard_gemm(None, X, W, Y)
+    ref = orc.linear(x.astype(np.float64), w.astype(np.float64))
+    assert rel_err(host(Y), ref) < TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_shard_gemm_gather_bias_gelu_and_scatter_residual(cas, dtype):
+    import torch
+    B, N, beta, K, F = 2, 200, 5, 72, 328
+    rng = np.random.default_rng(3)
+    a = make_assignment("ragged", N, beta, 11)
+    plan = cas.cascade_plan_create(B, N, beta, a)
+    _, perm, _ = orc.shard_plan(a, beta)
+    x = rand(rng, (B * N, K), dtype)
+    w1, b1 = rand(rng, (F, K), dtype, 0.2), rand(rng, (F,), dtype, 0.2)
+    w2, b2 = rand(rng, (K, F), dtype, 0.1), rand(rng, (K,), dtype, 0.2)
+    X, W1, B1, W2, B2 = (dev(cas, t, dtype) for t in (x, w1, b1, w2, b2))
+    # gather original rows into packed order, bias + GELU
+    H1 = torch.empty(B * N, F, dtype=X.dtype, device="cuda")
+    cas.cascade_shard_gemm(plan, X, W1, H1, bias=B1, epilogue=cas.EPI_BIAS | cas.EPI_GELU_ERF,
+                           x_rows=cas.ROWS_ORIGINAL)
+    rows = np.concatenate([b * N + perm for b in range(B)])
+    x64 = x.astype(np.float64)
+    ref1 = orc.gelu_erf(orc.linear(x64[rows], w1.astype(np.float64), b1.astype(np.float64)))
+    assert rel_err(host(H1), ref1) < TOL[dtype]
+    # packed rows in, residual gathered from original order, result scattered back to original order
+    Y = torch.zeros(B * N, K, dtype=X.dtype, device="cuda")
+    cas.cascade_shard_gemm(plan, H1, W2, Y, bias=B2, residual=X, epilogue=cas.EPI_BIAS | cas.EPI_RESIDUAL,
+                           y_rows=cas.ROWS_ORIGINAL, res_rows=cas.ROWS_ORIGINAL)
+    h1 = host(H1)
+    ref2 = np.empty((B * N, K))
+    ref2[rows] = x64[rows] + orc.linear(h1, w2.astype(np.float64), b2.astype(np.float64))
+    assert rel_err(host(Y), ref2) < TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_shard_gemm_swiglu_and_tanh(cas, dtype):
+    import torch
+    M, K, F = 260, 136, 200
+    rng = np.random.default_rng(4)
+    x, wg, wu = rand(rng, (M, K), dtype), rand(rng, (F, K), dtype, 0.2), rand(rng, (F, K), dtype, 0.2)
+    X, WG, WU = (dev(cas, t, dtype) for t in (x, wg, wu))
+    Y = torch.empty(M, F, dtype=X.dtype, device="cuda")
+    cas.cascade_shard_gemm(None, X, WG, Y, W_up=WU, epilogue=cas.EPI_SWIGLU)
+    x64 = x.astype(np.float64)
+    ref = orc.silu(orc.linear(x64, wg.astype(np.float64))) * orc.linear(x64, wu.astype(np.float64))
+    assert rel_err(host(Y), ref) < TOL[dtype]
+    cas.cascade_shard_gemm(None, X, WG, Y, epilogue=cas.EPI_GELU_TANH)
+    assert rel_err(host(Y), orc.gelu_tanh(orc.linear(x64, wg.astype(np.float64)))) < TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_shard_gemm_rope_uses_original_positions(cas, dtype):
+    import torch
+    B, N, beta, K, H, d = 1, 96, 3, 64, 3, 32
+    rng = np.random.default_rng(5)
+    a = make_assignment("perm", N, beta, 2)
+    pos = rng.permutation(4 * N)[:N].astype(np.int32)         # arbitrary positions
+    plan = cas.cascade_plan_create(B, N, beta, a, positions=pos)
+    _, perm, _ = orc.shard_plan(a, beta)
+    x, w = rand(rng, (N, K), dtype), rand(rng, ((H + 1) * d, K), dtype, 0.2)
+    X, W = dev(cas, x, dtype), dev(cas, w, dtype)
+    Y = torch.empty(N, (H + 1) * d, dtype=X.dtype, device="cuda")
+    cas.cascade_shard_gemm(plan, X, W, Y, epilogue=cas.EPI_ROPE, x_rows=cas.ROWS_ORIGINAL, rope_cols=H * d,
+                           head_dim=d, rope_theta=10000.0)
+    y = orc.linear(x.astype(np.float64)[perm], w.astype(np.float64))
+    ref = y.copy()
+    for h in range(H):
+        ref[:, h * d:(h + 1) * d] = orc.rope(y[:, h * d:(h + 1) * d], pos[perm], 10000.0)
+    assert rel_err(host(Y), ref) < TOL[dtype]
+    assert rel_err(host(Y)[:, :H * d], y[:, :H * d]) > 0.05       # the rotation did happen
+
+
+def test_shard_gemm_error_paths(cas):
+    import torch
+    X = torch.zeros(8, 12, dtype=torch.bfloat16, device="cuda")      # k = 12 is not a multiple of 8
+    W = torch.zeros(4, 12, dtype=torch.bfloat16, device="cuda")
+    Y = torch.zeros(8, 4, dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(cas.CascadeError) as ei:
+        cas.cascade_shard_gemm(None, X, W, Y)
+    assert ei.value.status == cas.EUNSUPPORTED
+    with pytest.raises(cas.CascadeError) as ei:
+        cas.cascade_shard_gemm(None, X, W, Y, x_rows=cas.ROWS_ORIGINAL)     # a map needs a plan
+    assert ei.value.status == cas.EINVAL
+    plan = cas.cascade_plan_create(1, 16, 2, np.zeros(16, dtype=np.int32))
+    with pytest.raises(cas.CascadeError) as ei:
+        cas.cascade_shard_gemm(plan, X.float(), W.float(), Y.float(), x_rows=cas.ROWS_ORIGINAL)   # 8 rows != 16
+    assert ei.value.status == cas.ESHAPE
+    with pytest.raises(cas.CascadeError) as ei:
+        cas.cascade_shard_gemm(None, X.float(), W.float(), Y.float(), epilogue=cas.EPI_BIAS)       # bias missing
+    assert ei.value.status == cas.EINVAL
+
+
+# ---------------------------------------------------------------------------- partial attention + merge
+def attn_case(cas, dtype, B, H, Hkv, N, d, beta, kind, layout, mask_kind="causal", seed=0, positions=None, amp=1.0):
+    import torch
+    rng = np.random.default_rng(seed)
+    q, k, v = (rand(rng, (B, H, N, d), dtype, amp), rand(rng, (B, Hkv, N, d), dtype, amp),
+               rand(rng, (B, Hkv, N, d), dtype))
+    a = make_assignment(kind, N, beta, seed + 1)
+    plan = cas.cascade_plan_create(B, N, beta, a, positions=positions,
+                                   mask_kind=cas.MASK_CAUSAL if mask_kind == "causal" else cas.MASK_NONE)
+    _, perm, _ = orc.shard_plan(a, beta)
+    scale = d ** -0.5
+    if layout == "packed":
+        qd, kd, vd = (dev(cas, t[:, :, perm], dtype) for t in (q, k, v))
+        row_layout = cas.ROWS_PACKED
+    else:
+        qd, kd, vd = (dev(cas, t, dtype) for t in (q, k, v))
+        row_layout = cas.ROWS_ORIGINAL
+    m = torch.full((B, H, beta, N), 7.0, dtype=torch.float32, device="cuda")
+    e = torch.full((B, H, beta, N), 7.0, dtype=torch.float32, device="cuda")
+    u = torch.full((B, beta, H, N, d), 7.0, dtype=torch.float32, device="cuda")
+    ws = cas.new_workspace(cas.cascade_partial_attn_workspace_bytes(plan, qd, H, Hkv, d))
+    cas.cascade_partial_attn(plan, qd, kd, vd, m, e, u, H, Hkv, d, scale, row_layout=row_layout, workspace=ws)
+    refs = [orc.partial_attention_all_pairs(q[b], k[b], v[b], a, beta, positions=positions, scale=scale,
+                                            mask_kind=mask_kind) for b in range(B)]
+    m_r = np.stack([r[0] for r in refs]); e_r = np.stack([r[1] for r in refs]); u_r = np.stack([r[2] for r in refs])
+    return plan, (m, e, u), (m_r, e_r, u_r), perm
+
+
+def check_partials(dtype, got, ref):
+    m, e, u = (host(t) for t in got)
+    m_r, e_r, u_r = ref
+    dead = ~np.isfinite(m_r)
+    assert np.array_equal(~np.isfinite(m), dead)
+    assert (m[dead] == -np.inf).all() and (e[dead] == 0).all()
+    tol_stat = 1e-5 if dtype == "f32" else 1e-4            # m, e are fp32 functions of exact bf16 inputs
+    assert (np.abs(m[~dead] - m_r[~dead]) / np.maximum(1.0, np.abs(m_r[~dead]))).max() < tol_stat
+    assert (np.abs(e - e_r) / np.maximum(1.0, e_r)).max() < tol_stat
+    lse, lse_r = m[~dead] + np.log(e[~dead]), m_r[~dead] + np.log(e_r[~dead])
+    assert (np.abs(lse - lse_r) / np.maximum(1.0, np.abs(lse_r))).max() < tol_stat
+    ut_r = e_r.transpose(0, 2, 1, 3)[..., None] * u_r        # u~ = e * u, [B, beta, H, N, d]
+    assert rel_err(u, ut_r) < TOL[dtype]
+    assert (u[dead.transpose(0, 2, 1, 3)] == 0).all()
+    assert (e[~dead] >= 1.0 - 1e-6).all()                     # corrected bound: 1 <= e <= |S_k|
+
+
+@pytest.mark.parametrize("dtype,H,Hkv,N,d,beta,kind,layout", [
+    ("f32", 4, 4, 128, 16, 4, "perm", "original"),
+    ("f32", 4, 2, 100, 24, 5, "ragged", "packed"),
+    ("f32", 2, 1, 70, 8, 16, "ragged", "original"),            # some shards empty
+    ("bf16", 4, 4, 256, 64, 4, "perm", "original"),
+    ("bf16", 8, 2, 384, 128, 3, "perm", "original"),           # GQA 4:1, 128-row shards
+    ("bf16", 8, 1, 200, 128, 4, "ragged", "packed"),           # GQA 8:1, ragged tiles
+    ("bf16", 2, 1, 300, 64, 7, "ragged", "original"),          # GQA 2:1
+    ("bf16", 3, 3, 330, 64, 2, "contiguous", "packed"),        # MHA, shards larger than a tile
+    ("bf16", 4, 1, 96, 128, 24, "ragged", "original"),         # tiny shards, some empty
+    ("bf16", 4, 2, 512, 128, 8, "roundrobin", "original"),
+])
+def test_partial_attn_matches_oracle(cas, dtype, H, Hkv, N, d, beta, kind, layout):
+    B = 2
+    plan, got, ref, _ = attn_case(cas, dtype, B, H, Hkv, N, d, beta, kind, layout, seed=N + d)
+    check_partials(dtype, got, ref)
+
+
+@pytest.mark.parametrize("dtype,d", [("f32", 16), ("bf16", 64), ("bf16", 128)])
+def test_partial_attn_no_mask_and_custom_positions(cas, dtype, d):
+    plan, got, ref, _ = attn_case(cas, dtype, 1, 4, 2, 160, d, 5, "perm", "original", mask_kind="none", seed=1)
+    check_partials(dtype, got, ref)
+    pos = np.random.default_rng(9).permutation(1000)[:160].astype(np.int32)
+    plan, got, ref, _ = attn_case(cas, dtype, 1, 4, 2, 160, d, 5, "perm", "original", seed=2, positions=pos)
+    check_partials(dtype, got, ref)
+
+
+@pytest.mark.parametrize("dtype,d", [("f32", 32), ("bf16", 128)])
+def test_partial_attn_large_logits_are_stable(cas, dtype, d):
+    plan, got, ref, _ = attn_case(cas, dtype, 1, 2, 2, 128, d, 4, "perm", "original", seed=3, amp=6.0)
+    assert np.abs(ref[0][np.isfinite(ref[0])]).max() > 100
+    check_partials(dtype, got, ref)
+
+
+@pytest.mark.parametrize("dtype,d,u_mode", [("f32", 16, "norm"), ("bf16", 128, "norm"), ("f32", 20, "unnorm"),
+                                            ("bf16", 64, "unnorm")])
+def test_lse_merge_matches_oracle_on_oracle_partials(cas, dtype, d, u_mode):
+    """The merge alone: its inputs are the ORACLE's partials (fp32-rounded), its output is
+    compared with the oracle's merge of the same numbers."""
+    import torch
+    B, H, Hkv, N, beta = 2, 4, 2, 150, 6
+    rng = np.random.default_rng(12)
+    q, k, v = rng.standard_normal((B, H, N, d)) * 2, rng.standard_normal((B, Hkv, N, d)) * 2, rng.standard_normal((B, Hkv, N, d))
+    a = make_assignment("ragged", N, beta, 4)
+    plan = cas.cascade_plan_create(B, N, beta, a)
+    _, perm, _ = orc.shard_plan(a, beta)
+    parts = [orc.partial_attention_all_pairs(q[b], k[b], v[b], a, beta, scale=d ** -0.5) for b in range(B)]
+    m32, e32, u32 = (np.stack([p[i] for p in parts]).astype(np.float32) for i in range(3))
+    ref = np.stack([orc.lse_merge_all(m32[b].astype(np.float64), e32[b].astype(np.float64), u32[b].astype(np.float64))
+                    for b in range(B)])                                        # [B, N, H*d], packed rows
+    u_in = u32 if u_mode == "norm" else (e32.transpose(0, 2, 1, 3)[..., None] * u32).astype(np.float32)
+    md, ed, ud = (torch.from_numpy(t).cuda() for t in (m32, e32, u_in))
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    mode = cas.U_NORMALISED if u_mode == "norm" else cas.U_UNNORMALISED
+    o = torch.empty(B, N, H * d, dtype=tdt, device="cuda")
+    lse = torch.empty(B, H, N, dtype=torch.float32, device="cuda")
+    cas.cascade_lse_merge(plan, md, ed, ud, o, H, Hkv, d, row_layout=cas.ROWS_PACKED, u_mode=mode, lse_out=lse)
+    tol = 1e-5 if dtype == "f32" else 4e-3          # bf16 here only rounds the output
+    assert rel_err(host(o), ref) < tol
+    o2 = torch.empty_like(o)
+    cas.cascade_lse_merge(plan, md, ed, ud, o2, H, Hkv, d, row_layout=cas.ROWS_ORIGINAL, u_mode=mode)
+    assert np.array_equal(host(o2)[:, perm], host(o))                         # scatter is a pure row move
+    n = m32.astype(np.float64).max(axis=2)
+    wsum = (np.exp(m32.astype(np.float64) - n[:, :, None]) * e32).sum(axis=2)
+    assert rel_err(host(lse), n + np.log(wsum)) < 1e-5
+
+
+def test_partial_then_merge_equals_direct_attention(cas):
+    """GPU partials merged on the GPU equal unsharded softmax attention (oracle brute route)."""
+    import torch
+    for dtype, d in (("f32", 16), ("bf16", 128)):
+        B, H, Hkv, N, beta = 1, 4, 2, 192, 6
+        plan, got, ref, perm = attn_case(cas, dtype, B, H, Hkv, N, d, beta, "perm", "original", seed=21)
+        tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+        o = torch.empty(B, N, H * d, dtype=tdt, device="cuda")
+        cas.cascade_lse_merge(plan, *got, o, H, Hkv, d, row_layout=cas.ROWS_ORIGINAL)
+        ref_o = orc.lse_merge_all(*[r[0] for r in ref])                      # packed rows
+        want = np.empty_like(ref_o)
+        want[perm] = ref_o
+        assert rel_err(host(o)[0], want) < TOL[dtype]
+
+
+def test_attention_error_paths(cas):
+    import torch
+    plan = cas.cascade_plan_create(1, 64, 2, np.zeros(64, dtype=np.int32))
+    q = torch.zeros(1, 4, 64, 64, dtype=torch.bfloat16, device="cuda")
+    kv = torch.zeros(1, 3, 64, 64, dtype=torch.bfloat16, device="cuda")
+    m = torch.zeros(1, 4, 2, 64, device="cuda"); u = torch.zeros(1, 2, 4, 64, 64, device="cuda")
+    with pytest.raises(cas.CascadeError) as ei:                              # H % H_KV != 0
+        cas.cascade_partial_attn(plan, q, kv, kv, m, m.clone(), u, 4, 3, 64, 0.125)
+    assert ei.value.status == cas.ESHAPE
+    kv = torch.zeros(1, 2, 64, 64, dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(cas.CascadeError) as ei:                              # bf16 path needs its workspace
+        cas.cascade_partial_attn(plan, q, kv, kv, m, m.clone(), u, 4, 2, 64, 0.125, workspace=None)
+    assert ei.value.status == cas.EWORKSPACE
+    q48 = torch.zeros(1, 4, 64, 48, dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(cas.CascadeError) as ei:                              # head_dim 48 not built for bf16
+        cas.cascade_partial_attn(plan, q48, q48, q48, m, m.clone(), u, 4, 4, 48, 0.125)
+    assert ei.value.status == cas.EUNSUPPORTED
+
+
+# ---------------------------------------------------------------------------- whole layer
+SMALL_LLAMA = CONFIGS["C3"].with_(name="small-llama", d_model=512, n_heads=8, n_kv_heads=2, head_dim=128,
+                                  d_ff=1024, seq_len=640, n_shards=5, index=31)
+SMALL_LLAMA64 = CONFIGS["C3"].with_(name="small-llama64", d_model=256, n_heads=4, n_kv_heads=4, head_dim=64,
+                                    d_ff=520, seq_len=300, n_shards=4, index=32, assignment="ragged")
+SMALL_GPT = CONFIGS["C2"].with_(name="small-gpt", d_model=256, n_heads=4, n_kv_heads=4, head_dim=64, d_ff=1024,
+                                batch=2, seq_len=384, n_shards=3, index=33)
+F32_LLAMA = CONFIGS["C3"].with_(name="f32-llama", dtype="f32", d_model=96, n_heads=6, n_kv_heads=2, head_dim=16,
+                                d_ff=200, seq_len=150, n_shards=6, index=34, assignment="ragged")
+
+
+def layer_case(cas, cfg, attn_mode, io_rows=None, seed=None):
+    a = make_assignment(cfg.assignment, cfg.seq_len, cfg.n_shards, 77 if seed is None else seed)
+    w, h = make_layer_weights(cfg), make_hidden(cfg)
+    io = cas.ROWS_ORIGINAL if io_rows is None else io_rows
+    out = cas.layer_forward_numpy(cfg, w, h, a, attn_mode=attn_mode, io_rows=io)
+    return a, w, h, out
+
+
+@pytest.mark.parametrize("cfg", [CONFIGS["C1"], F32_LLAMA, SMALL_LLAMA, SMALL_LLAMA64, SMALL_GPT],
+                         ids=lambda c: c.name)
+@pytest.mark.parametrize("mode", ["fused", "materialised"])
+def test_layer_forward_matches_oracle(cas, cfg, mode):
+    attn_mode = cas.ATTN_FUSED if mode == "fused" else cas.ATTN_MATERIALISED
+    a, w, h, out = layer_case(cas, cfg, attn_mode)
+    ref = orc.layer_sharded_batch(h, w, cfg, a, cfg.n_shards)
+    assert rel_err(out, ref) < TOL[cfg.dtype]
+    direct = orc.layer_direct_batch(h, w, cfg)
+    assert rel_err(out, direct) < TOL[cfg.dtype]
+
+
+@pytest.mark.parametrize("cfg", [CONFIGS["C1"], SMALL_LLAMA], ids=lambda c: c.name)
+def test_layer_partials_match_oracle(cas, cfg):
+    a = make_assignment(cfg.assignment, cfg.seq_len, cfg.n_shards, 5)
+    w, h = make_layer_weights(cfg), make_hidden(cfg)
+    out, (m, e, u) = cas.layer_forward_numpy(cfg, w, h, a, attn_mode=cas.ATTN_MATERIALISED, return_partials=True)
+    w64 = {k: v.astype(np.float64) for k, v in w.items()}
+    q, k, v = orc.pre_pass(h[0].astype(np.float64), np.arange(cfg.seq_len), w64, cfg)
+    m_r, e_r, u_r = orc.partial_attention_all_pairs(q, k, v, a, cfg.n_shards, scale=cfg.scale)
+    dead = ~np.isfinite(m_r)
+    assert np.array_equal(~np.isfinite(m[0]), dead)
+    tol = TOL[cfg.dtype]                      # q, k, v themselves carry the dtype's rounding here
+    assert (np.abs(m[0][~dead] - m_r[~dead]) / np.maximum(1.0, np.abs(m_r[~dead]))).max() < tol
+    assert (np.abs(e[0] - e_r) / np.maximum(1.0, e_r)).max() < tol
+    assert rel_err(u[0], e_r.transpose(1, 0, 2)[..., None] * u_r) < tol
+
+
+@pytest.mark.parametrize("cfg", [F32_LLAMA, SMALL_LLAMA], ids=lambda c: c.name)
+def test_layer_output_invariant_under_resharding_and_io_layout(cas, cfg):
+    import torch
+    base = layer_case(cas, cfg, cas.ATTN_FUSED, seed=1)[3]
+    for seed, beta, kind in [(2, cfg.n_shards, "perm"), (3, 3, "roundrobin"), (4, 1, "contiguous")]:
+        c2 = cfg.with_(n_shards=beta, assignment=kind)
+        other = layer_case(cas, c2, cas.ATTN_FUSED, seed=seed)[3]
+        assert rel_err(other, base) < TOL[cfg.dtype]
+    # packed io: feed packed rows, get packed rows
+    a = make_assignment(cfg.assignment, cfg.seq_len, cfg.n_shards, 1)
+    _, perm, _ = orc.shard_plan(a, cfg.n_shards)
+    w, h = make_layer_weights(cfg), make_hidden(cfg)
+    out_p = cas.layer_forward_numpy(cfg, w, h[:, perm], a, io_rows=cas.ROWS_PACKED)
+    assert np.array_equal(out_p, base[:, perm])
+
+
+def test_layer_forward_is_deterministic(cas):
+    cfg = SMALL_LLAMA
+    o1 = layer_case(cas, cfg, cas.ATTN_FUSED)[3]
+    o2 = layer_case(cas, cfg, cas.ATTN_FUSED)[3]
+    assert np.array_equal(o1, o2)
+
+
+def test_layer_error_paths(cas):
+    import torch
+    cfg = SMALL_LLAMA64
+    a = make_assignment("perm", cfg.seq_len, cfg.n_shards, 1)
+    plan = cas.cascade_plan_create(cfg.batch, cfg.seq_len, cfg.n_shards, a)
+    desc = cas.make_layer_desc(cfg)
+    tensors = {k: cas.to_device(v, cfg.dtype) for k, v in make_layer_weights(cfg).items()}
+    w = cas.make_layer_weights(tensors)
+    h = cas.to_device(make_hidden(cfg), cfg.dtype)
+    out = torch.empty_like(h)
+    need = cas.cascade_layer_workspace_bytes(plan, desc)
+    assert need > 0
+    with pytest.raises(cas.CascadeError) as ei:
+        cas.cascade_layer_forward(plan, desc, w, h, out, cas.new_workspace(need // 2))
+    assert ei.value.status == cas.EWORKSPACE
+    with pytest.raises(cas.CascadeError) as ei:
+        cas.cascade_layer_forward(plan, desc, w, h, h, cas.new_workspace(need))       # in-place not allowed
+    assert ei.value.status == cas.EINVAL
+    bad = cas.make_layer_desc(cfg.with_(n_heads=5, n_kv_heads=2))
+    assert cas.cascade_layer_workspace_bytes(plan, bad) == 0
+    with pytest.raises(cas.CascadeError) as ei:
+        cas.cascade_layer_forward(plan, bad, w, h, out, cas.new_workspace(need))
+    assert ei.value.status == cas.ESHAPE
+    bad = cas.make_layer_desc(cfg.with_(head_dim=48))
+    with pytest.raises(cas.CascadeError) as ei:
+        cas.cascade_layer_forward(plan, bad, w, h, out, cas.new_workspace(need))
+    assert ei.value.status == cas.EUNSUPPORTED
+    tensors2 = dict(tensors); tensors2.pop("w_gate")
+    with pytest.raises(cas.CascadeError) as ei:
+        cas.cascade_layer_forward(plan, desc, cas.make_layer_weights(tensors2), h, out, cas.new_workspace(need))
+    assert ei.value.status == cas.EINVAL
