@@ -1,0 +1,222 @@
+#!/usr/bin/env python3
+"""Benchmark of the token-sharded layer forward (one MI355X).
+
+A step is one pass of the whole hot path (gather + norm, q/k/v shard GEMM, rotary, partial
+attention over every (query-shard, kv-shard) pair with the running log-sum-exp merge, o projection,
+norm, FFN shard GEMMs, scatter) over one batch of synthetic input that is already resident in HBM.
+Prints ONE JSON line.  The float64 CPU oracle is timed next to it (cpu_baseline) on the host cores.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0      # MI355X dense bf16
+FP32_VECTOR_PEAK_TFLOPS = 157.3
+HBM_PEAK_GBS = 8000.0
+
+
+def layer_flops(cfg):
+    T = cfg.batch * cfg.seq_len
+    D, H, Hkv, d, f = cfg.d_model, cfg.n_heads, cfg.n_kv_heads, cfg.head_dim, cfg.d_ff
+    qkv = 2.0 * T * D * (H + 2 * Hkv) * d
+    o = 2.0 * T * (H * d) * D
+    up = 2.0 * T * D * f * (2 if cfg.act == "swiglu" else 1)
+    down = 2.0 * T * f * D
+    attn = 4.0 * d * H * cfg.batch * cfg.seq_len * (cfg.seq_len + 1) / 2      # causal-useful pairs only
+    return {"qkv_gemm": qkv, "o_proj": o, "ffn_up": up, "ffn_down": down, "attention": attn,
+            "total": qkv + o + up + down + attn}
+
+
+def device_inputs(cfg, seed):
+    """Random-init weights and hidden states drawn on the device (bf16 grid for bf16 configs)."""
+    import torch
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+    D, H, Hkv, d, f, s = cfg.d_model, cfg.n_heads, cfg.n_kv_heads, cfg.head_dim, cfg.d_ff, cfg.sigma
+
+    def normal(shape, std):
+        return (torch.randn(shape, device="cuda", generator=g, dtype=torch.float32) * std).to(tdt)
+
+    w = {"wq": normal((H * d, D), s), "wk": normal((Hkv * d, D), s), "wv": normal((Hkv * d, D), s),
+         "wo": normal((D, H * d), s), "w_up": normal((f, D), s), "w_down": normal((D, f), s),
+         "norm1_g": (1.0 + normal((D,), s).float()).to(tdt), "norm2_g": (1.0 + normal((D,), s).float()).to(tdt)}
+    if cfg.act == "swiglu":
+        w["w_gate"] = normal((f, D), s)
+    if cfg.norm == "layernorm":
+        w["norm1_b"], w["norm2_b"] = normal((D,), s), normal((D,), s)
+    if cfg.bias:
+        w.update(bq=normal((H * d,), s), bk=normal((Hkv * d,), s), bv=normal((Hkv * d,), s), bo=normal((D,), s),
+                 b_up=normal((f,), s), b_down=normal((D,), s))
+    h = normal((cfg.batch, cfg.seq_len, D), 1.0)
+    return w, h
+
+
+def time_steps(fn, steps):
+    import torch
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / steps
+
+
+def run_config(cas, cfg, steps, warmup, staged=True, check=False):
+    import numpy as np
+    import torch
+    from cascade_inputs import config_seed, make_assignment
+    seed = config_seed(cfg)
+    a = make_assignment(cfg.assignment, cfg.seq_len, cfg.n_shards, seed)
+    w, h = device_inputs(cfg, seed)
+    plan = cas.cascade_plan_create(cfg.batch, cfg.seq_len, cfg.n_shards, a)
+    wts = cas.make_layer_weights(w)
+    h_out = torch.empty_like(h)
+    res = {"flops": layer_flops(cfg)}
+
+    desc = cas.make_layer_desc(cfg, cas.ATTN_FUSED, cas.ROWS_ORIGINAL)
+    ws = cas.new_workspace(cas.cascade_layer_workspace_bytes(plan, desc))
+    step = lambda: cas.cascade_layer_forward(plan, desc, wts, h, h_out, ws)
+    for _ in range(warmup):
+        step()
+    sec = time_steps(step, steps)
+    res["sec_per_step"] = sec
+    res["tokens_per_s"] = cfg.batch * cfg.seq_len / sec
+    res["tflops"] = res["flops"]["total"] / sec / 1e12
+
+    if staged:
+        res["stages_ms"] = staged_times(cas, plan, desc, wts, h, h_out, ws, steps)
+        # materialised mode: partial attention writes m, e, u~ to HBM, the merge reads them back
+        desc_m = cas.make_layer_desc(cfg, cas.ATTN_MATERIALISED, cas.ROWS_ORIGINAL)
+        ws_m = cas.new_workspace(cas.cascade_layer_workspace_bytes(plan, desc_m))
+        cas.cascade_layer_forward(plan, desc_m, wts, h, h_out, ws_m)
+        res["stages_ms_materialised"] = staged_times(cas, plan, desc_m, wts, h, h_out, ws_m, max(3, steps // 4))
+        res["sec_per_step_materialised"] = time_steps(
+            lambda: cas.cascade_layer_forward(plan, desc_m, wts, h, h_out, ws_m), max(3, steps // 4))
+        del ws_m
+        step()                                     # leave the fused result in h_out
+        torch.cuda.synchronize()
+    if check:
+        res["_host"] = ({k: v.float().cpu().numpy() for k, v in w.items()}, h.float().cpu().numpy(),
+                        h_out.float().cpu().numpy(), a)
+    return res
+
+
+def staged_times(cas, plan, desc, wts, h, h_out, ws, steps):
+    import torch
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(cas.N_STAGE_EVENTS)] for _ in range(steps)]
+    for row in evs:
+        for ev in row:
+            ev.record()                            # creates the underlying HIP event
+    torch.cuda.synchronize()
+    for row in evs:
+        cas.cascade_layer_forward_staged(plan, desc, wts, h, h_out, ws, row)
+    torch.cuda.synchronize()
+    out = {}
+    for i, name in enumerate(cas.STAGE_NAMES):
+        out[name] = sum(row[i].elapsed_time(row[i + 1]) for row in evs) / steps
+    out["total"] = sum(row[0].elapsed_time(row[-1]) for row in evs) / steps
+    return out
+
+
+def cpu_baseline(cfg, host):
+    """The oracle as it stands, on the host cores: the whole unsharded float64 layer, one repetition."""
+    import numpy as np
+    from oracle import cascade_oracle as orc
+    w, h, h_out, a = host
+    w64 = {k: v.astype(np.float64) for k, v in w.items()}
+    t0 = time.perf_counter()
+    ref = np.stack([orc.layer_direct(h[b], w64, cfg) for b in range(cfg.batch)])
+    sec = time.perf_counter() - t0
+    err = float(np.abs(h_out - ref).max() / np.abs(ref).max())
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [os.cpu_count()])
+    except Exception:
+        cores = os.cpu_count()
+    return {"value": cfg.batch * cfg.seq_len / sec, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"whole {cfg.name} layer (all {cfg.batch * cfg.seq_len} tokens), float64 layer_direct, 1 repetition",
+            "seconds": sec}, err
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", default="C3", help="headline workload (C1..C5)")
+    ap.add_argument("--all", action="store_true", help="also time the other bf16 configurations")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs all shards on ONE GPU; --gpus N with N > 1 is not supported "
+                 "(no inter-GPU path exists)")
+    import torch
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU")
+    import paper_2507_05228_amd as cas
+    from cascade_inputs import CONFIGS
+    cas.load_library()
+
+    cfg = CONFIGS[args.config]
+    res = run_config(cas, cfg, args.steps, args.warmup, staged=True, check=not args.no_cpu_baseline)
+    fl = res["flops"]
+    st = res["stages_ms"]
+    dom = "ffn_up"
+    dom_tflops = fl[dom] / (st[dom] * 1e-3) / 1e12
+    bf16 = cfg.dtype == "bf16"
+    peak = MFMA_BF16_PEAK_TFLOPS if bf16 else FP32_VECTOR_PEAK_TFLOPS
+    es = 2 if bf16 else 4
+    T, D, H, d, S = cfg.batch * cfg.seq_len, cfg.d_model, cfg.n_heads, cfg.head_dim, cfg.n_shards
+    stm = res["stages_ms_materialised"]
+    merge_bytes = cfg.batch * S * H * cfg.seq_len * (d + 2) * 4 + T * H * d * es
+    gather_bytes = 2 * T * D * es
+    out = {
+        "metric": "sharded-layer prefill tokens/sec/GPU", "value": res["tokens_per_s"], "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": res["sec_per_step"] * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
+        "config": {"workload": cfg.name, "batch": cfg.batch, "seq_len": cfg.seq_len, "n_shards": S,
+                   "assignment": cfg.assignment, "d_model": D, "n_heads": H, "n_kv_heads": cfg.n_kv_heads,
+                   "head_dim": d, "d_ff": cfg.d_ff, "attn_mode": "fused", "io_rows": "original"},
+        "layer_tflops": res["tflops"], "layer_frac_of_mfma_peak": res["tflops"] / peak,
+        "layer_gflop_counted": fl["total"] / 1e9,
+        "roofline": {"bound": "mfma" if bf16 else "alu", "kernel": "gemm_bf16_kernel (FFN gate+up shard GEMM)"
+                     if bf16 else "gemm_f32_kernel (FFN up shard GEMM)",
+                     "achieved": dom_tflops, "peak": peak, "unit": "TFLOP/s", "frac": dom_tflops / peak,
+                     "traffic": None, "avg_launch_ms": st[dom], "flops_per_launch": fl[dom]},
+        "stages_ms": st,
+        "stage_tflops": {k: fl[k] / (st[k] * 1e-3) / 1e12 for k in ("qkv_gemm", "attention", "o_proj", "ffn_up", "ffn_down")},
+        "hbm_kernels": {
+            "lse_merge": {"ms": stm["lse_merge"], "bytes": merge_bytes, "GBs": merge_bytes / (stm["lse_merge"] * 1e-3) / 1e9,
+                          "frac_of_hbm_peak": merge_bytes / (stm["lse_merge"] * 1e-3) / 1e9 / HBM_PEAK_GBS},
+            "gather_norm1": {"ms": st["gather_norm1"], "bytes": gather_bytes,
+                             "GBs": gather_bytes / (st["gather_norm1"] * 1e-3) / 1e9,
+                             "frac_of_hbm_peak": gather_bytes / (st["gather_norm1"] * 1e-3) / 1e9 / HBM_PEAK_GBS}},
+        "materialised_mode": {"ms_per_step": res["sec_per_step_materialised"] * 1e3,
+                              "partial_attention_ms": stm["attention"], "lse_merge_ms": stm["lse_merge"]},
+    }
+    if not args.no_cpu_baseline:
+        base, err = cpu_baseline(cfg, res["_host"])
+        out["cpu_baseline"] = base
+        out["max_rel_err_vs_oracle"] = err
+    if args.all:
+        others = {}
+        for key in ("C2", "C4", "C5"):
+            if key == args.config:
+                continue
+            torch.cuda.empty_cache()
+            r = run_config(cas, CONFIGS[key], max(3, args.steps // 2), 2, staged=False)
+            others[key] = {"tokens_per_s": r["tokens_per_s"], "ms_per_step": r["sec_per_step"] * 1e3,
+                           "tflops": r["tflops"], "frac_of_mfma_peak": r["tflops"] / MFMA_BF16_PEAK_TFLOPS}
+        out["other_configs"] = others
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -220,6 +220,19 @@ CASCADE_API int32_t cascade_layer_forward(const cascade_plan *plan, const cascad
                               const void *h_in, void *h_out,
                               void *workspace, size_t workspace_bytes, void *stream);
 
+/* The same computation with stage boundaries marked for measurement: HIP event
+ * stage_events[i] (hipEvent_t, created by the caller, NULL entries skipped) is
+ * recorded on the stream at boundary i.  Boundaries (CASCADE_N_STAGE_EVENTS):
+ * 0 start, 1 gather+norm1, 2 qkv GEMM, 3 rotary, 4 attention (partial
+ * attention), 5 LSE merge (same instant as 4 in FUSED mode), 6 o projection +
+ * residual, 7 norm2, 8 FFN up/gate GEMM, 9 FFN down + residual + scatter.       */
+#define CASCADE_N_STAGE_EVENTS 10
+CASCADE_API int32_t cascade_layer_forward_staged(const cascade_plan *plan, const cascade_layer_desc *desc,
+                                     const cascade_layer_weights *weights,
+                                     const void *h_in, void *h_out,
+                                     void *workspace, size_t workspace_bytes, void *stream,
+                                     void *const *stage_events, int32_t n_stage_events);
+
 /* After a MATERIALISED cascade_layer_forward: device pointers into the workspace
  * it used, holding m, e [B,H,n_shards,N] and u~ [B,n_shards,H,N,d] (fp32).      */
 CASCADE_API int32_t cascade_layer_partials(const cascade_plan *plan, const cascade_layer_desc *desc,

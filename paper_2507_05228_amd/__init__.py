@@ -27,7 +27,9 @@ EPI_BIAS, EPI_GELU_ERF, EPI_GELU_TANH, EPI_SWIGLU, EPI_ROPE, EPI_RESIDUAL = 1, 2
 EXPORTS = ["cascade_plan_create", "cascade_plan_maps", "cascade_plan_maps_host", "cascade_plan_destroy",
            "cascade_last_hip_error", "cascade_shard_gemm", "cascade_partial_attn_workspace_bytes",
            "cascade_partial_attn", "cascade_lse_merge", "cascade_layer_workspace_bytes",
-           "cascade_layer_forward", "cascade_layer_partials"]
+           "cascade_layer_forward", "cascade_layer_forward_staged", "cascade_layer_partials"]
+N_STAGE_EVENTS = 10
+STAGE_NAMES = ["gather_norm1", "qkv_gemm", "rope", "attention", "lse_merge", "o_proj", "norm2", "ffn_up", "ffn_down"]
 
 
 class CascadeError(RuntimeError):
@@ -100,6 +102,9 @@ def load_library():
     lib.cascade_layer_workspace_bytes.restype = C.c_size_t
     lib.cascade_layer_forward.argtypes = [VP, P(LayerDesc), P(LayerWeights), VP, VP, VP, C.c_size_t, VP]
     lib.cascade_layer_forward.restype = I32
+    lib.cascade_layer_forward_staged.argtypes = [VP, P(LayerDesc), P(LayerWeights), VP, VP, VP, C.c_size_t, VP,
+                                                 P(VP), I32]
+    lib.cascade_layer_forward_staged.restype = I32
     lib.cascade_layer_partials.argtypes = [VP, P(LayerDesc), VP, P(VP), P(VP), P(VP)]
     lib.cascade_layer_partials.restype = I32
     _lib = lib
@@ -175,7 +180,7 @@ class _DeviceInt32:
     """Borrowed view of n int32 values in device memory (for torch.as_tensor)."""
 
     def __init__(self, ptr, n):
-        self.__cuda_array_interface__ = {"shape": (n,), "typestr": "<i4", "data": (ptr, True), "version": 2}
+        self.__cuda_array_interface__ = {"shape": (n,), "typestr": "<i4", "data": (ptr, False), "version": 2}
 
 
 def cascade_plan_maps_host(plan):
@@ -261,6 +266,17 @@ def cascade_layer_forward(plan, desc, weights, h_in, h_out, workspace, stream=No
     st = lib.cascade_layer_forward(plan.handle, C.byref(desc), C.byref(weights), _ptr(h_in), _ptr(h_out),
                                    _ptr(workspace), ws_bytes, _stream(stream))
     _check(st, "cascade_layer_forward")
+
+
+def cascade_layer_forward_staged(plan, desc, weights, h_in, h_out, workspace, events, stream=None):
+    """events: N_STAGE_EVENTS torch.cuda.Event(enable_timing=True), each recorded once before
+    (torch creates the HIP event lazily on its first record)."""
+    lib = load_library()
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    arr = (C.c_void_p * len(events))(*[ev.cuda_event for ev in events])
+    st = lib.cascade_layer_forward_staged(plan.handle, C.byref(desc), C.byref(weights), _ptr(h_in), _ptr(h_out),
+                                          _ptr(workspace), ws_bytes, _stream(stream), arr, len(events))
+    _check(st, "cascade_layer_forward_staged")
 
 
 def cascade_layer_partials(plan, desc, workspace, batch, n_heads, head_dim):

@@ -196,9 +196,10 @@ extern "C" int32_t cascade_layer_partials(const cascade_plan *plan, const cascad
     return CASCADE_OK;
 }
 
-extern "C" int32_t cascade_layer_forward(const cascade_plan *plan, const cascade_layer_desc *d,
-                                         const cascade_layer_weights *w, const void *h_in, void *h_out,
-                                         void *workspace, size_t workspace_bytes, void *stream) {
+static int32_t layer_forward_impl(const cascade_plan *plan, const cascade_layer_desc *d,
+                                  const cascade_layer_weights *w, const void *h_in, void *h_out,
+                                  void *workspace, size_t workspace_bytes, void *stream,
+                                  void *const *events, int32_t n_events) {
     int32_t st = check_layer_desc(plan, d);
     if (st != CASCADE_OK) return st;
     if (!w || !h_in || !h_out || h_in == h_out) return CASCADE_EINVAL;
@@ -210,6 +211,15 @@ extern "C" int32_t cascade_layer_forward(const cascade_plan *plan, const cascade
     if ((uintptr_t)workspace % 256) return CASCADE_EWORKSPACE;
 
     hipStream_t s = (hipStream_t)stream;
+    int stage = 0;
+    auto mark = [&]() -> int32_t {               // optional stage boundary for measurement
+        if (events && stage < n_events && events[stage]) {
+            hipError_t e = hipEventRecord((hipEvent_t)events[stage], s);
+            if (e != hipSuccess) { cascade_set_hip_error(e); return CASCADE_EHIP; }
+        }
+        ++stage;
+        return CASCADE_OK;
+    };
     char *base = (char *)workspace;
     const int T = plan->batch * plan->seq_len, N = plan->seq_len;
     const int D = d->d_model, H = d->n_heads, Hkv = d->n_kv_heads, hd = d->head_dim, f = d->d_ff;
@@ -219,8 +229,10 @@ extern "C" int32_t cascade_layer_forward(const cascade_plan *plan, const cascade
     const RowMap io_map = rowmap_for(plan, d->io_rows), packed = rowmap_for(plan, CASCADE_ROWS_PACKED);
 
     // 1. pre-pass: norm (with the gather into packed order), q/k/v projection, rotary embedding (Algorithm 2)
+    if ((st = mark()) != CASCADE_OK) return st;                                   // event 0: start
     NormArgs n1 = {d->dtype, T, D, d->norm_kind, d->norm_eps, h_in, w->norm1_g, w->norm1_b, x, io_map};
     if ((st = launch_norm(n1, s)) != CASCADE_OK) return st;
+    if ((st = mark()) != CASCADE_OK) return st;                                   // 1: gather + norm1
     GemmArgs g = {};
     g.dtype = d->dtype; g.M = T; g.N = QW; g.K = D; g.X = x;
     g.W[0] = w->wq; g.W[1] = w->wk; g.W[2] = w->wv;
@@ -229,10 +241,12 @@ extern "C" int32_t cascade_layer_forward(const cascade_plan *plan, const cascade
     g.epilogue = (w->bq || w->bk || w->bv) ? CASCADE_EPI_BIAS : 0;
     g.Y = qkv; g.ldx = D; g.ldy = QW; g.xmap = g.ymap = g.rmap = packed;
     if ((st = run_gemm(g, s)) != CASCADE_OK) return st;
+    if ((st = mark()) != CASCADE_OK) return st;                                   // 2: qkv GEMM
     if (d->rope) {
         RopeArgs r = {d->dtype, T, N, H + Hkv, hd, QW, d->rope_theta, plan->pos_packed_d, qkv};
         if ((st = launch_rope(r, s)) != CASCADE_OK) return st;
     }
+    if ((st = mark()) != CASCADE_OK) return st;                                   // 3: rotary embedding
 
     // 2. attention-pass on every (j, k) pair and post-pass merge (Algorithms 3 and 4)
     AttnArgs a = {};
@@ -247,14 +261,18 @@ extern "C" int32_t cascade_layer_forward(const cascade_plan *plan, const cascade
         a.fused = 1;
         st = d->dtype == CASCADE_BF16 ? launch_attn_bf16(plan, a, s) : launch_attn_f32(plan, a, s);
         if (st != CASCADE_OK) return st;
+        if ((st = mark()) != CASCADE_OK) return st;                               // 4: attention
+        if ((st = mark()) != CASCADE_OK) return st;                               // 5: (no separate merge)
     } else {
         a.fused = 0;
         a.m = (float *)(base + ws.m); a.e = (float *)(base + ws.e); a.u = (float *)(base + ws.u);
         st = d->dtype == CASCADE_BF16 ? launch_attn_bf16(plan, a, s) : launch_attn_f32(plan, a, s);
         if (st != CASCADE_OK) return st;
+        if ((st = mark()) != CASCADE_OK) return st;                               // 4: partial attention
         MergeArgs mg = {d->dtype, plan->batch, H, hd, plan->n_shards, N, CASCADE_U_UNNORMALISED,
                         a.m, a.e, a.u, ao, (int64_t)H * hd, nullptr, nullptr};
         if ((st = launch_merge(mg, s)) != CASCADE_OK) return st;
+        if ((st = mark()) != CASCADE_OK) return st;                               // 5: LSE merge
     }
 
     // 3. o projection + residual (Algorithm 4 line 9, Algorithm 1 line 17)
@@ -266,11 +284,13 @@ extern "C" int32_t cascade_layer_forward(const cascade_plan *plan, const cascade
     g.xmap = g.ymap = packed; g.rmap = io_map;
     g.epilogue = CASCADE_EPI_RESIDUAL | (w->bo ? CASCADE_EPI_BIAS : 0);
     if ((st = run_gemm(g, s)) != CASCADE_OK) return st;
+    if ((st = mark()) != CASCADE_OK) return st;                                   // 6: o projection + residual
 
     // 4. MLP: norm2, up (+ gate) projection with the activation, down projection + residual,
     //    scattered back to the caller's row order
     NormArgs n2 = {d->dtype, T, D, d->norm_kind, d->norm_eps, h1, w->norm2_g, w->norm2_b, x, packed};
     if ((st = launch_norm(n2, s)) != CASCADE_OK) return st;
+    if ((st = mark()) != CASCADE_OK) return st;                                   // 7: norm2
     g = {};
     g.dtype = d->dtype; g.M = T; g.N = f; g.K = D; g.X = x;
     g.seg_end[0] = g.seg_end[1] = g.seg_end[2] = f;
@@ -283,6 +303,7 @@ extern "C" int32_t cascade_layer_forward(const cascade_plan *plan, const cascade
                      (w->b_up ? CASCADE_EPI_BIAS : 0);
     }
     if ((st = run_gemm(g, s)) != CASCADE_OK) return st;
+    if ((st = mark()) != CASCADE_OK) return st;                                   // 8: FFN up (+ gate) GEMM
     g = {};
     g.dtype = d->dtype; g.M = T; g.N = D; g.K = f; g.X = act; g.W[0] = w->w_down;
     g.seg_end[0] = g.seg_end[1] = g.seg_end[2] = D;
@@ -290,5 +311,21 @@ extern "C" int32_t cascade_layer_forward(const cascade_plan *plan, const cascade
     g.ldx = f; g.ldy = D; g.ldres = D;
     g.xmap = g.rmap = packed; g.ymap = io_map;
     g.epilogue = CASCADE_EPI_RESIDUAL | (w->b_down ? CASCADE_EPI_BIAS : 0);
-    return run_gemm(g, s);
+    if ((st = run_gemm(g, s)) != CASCADE_OK) return st;
+    return mark();                                                                // 9: FFN down + residual + scatter
+}
+
+extern "C" int32_t cascade_layer_forward(const cascade_plan *plan, const cascade_layer_desc *d,
+                                         const cascade_layer_weights *w, const void *h_in, void *h_out,
+                                         void *workspace, size_t workspace_bytes, void *stream) {
+    return layer_forward_impl(plan, d, w, h_in, h_out, workspace, workspace_bytes, stream, nullptr, 0);
+}
+
+extern "C" int32_t cascade_layer_forward_staged(const cascade_plan *plan, const cascade_layer_desc *d,
+                                                const cascade_layer_weights *w, const void *h_in, void *h_out,
+                                                void *workspace, size_t workspace_bytes, void *stream,
+                                                void *const *stage_events, int32_t n_stage_events) {
+    if (n_stage_events < 0 || (n_stage_events > 0 && !stage_events)) return CASCADE_EINVAL;
+    return layer_forward_impl(plan, d, w, h_in, h_out, workspace, workspace_bytes, stream, stage_events,
+                              n_stage_events);
 }

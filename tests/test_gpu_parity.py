@@ -219,7 +219,7 @@ def check_partials(dtype, got, ref):
     ut_r = e_r.transpose(0, 2, 1, 3)[..., None] * u_r        # u~ = e * u, [B, beta, H, N, d]
     assert rel_err(u, ut_r) < TOL[dtype]
     assert (u[dead.transpose(0, 2, 1, 3)] == 0).all()
-    assert (e[~dead] >= 1.0 - 1e-6).all()                     # corrected bound: 1 <= e <= |S_k|
+    assert (e[~dead] >= 1.0 - 1e-4).all()                     # corrected bound: 1 <= e <= |S_k| (up to the rounding of m)
 
 
 @pytest.mark.parametrize("dtype,H,Hkv,N,d,beta,kind,layout", [
