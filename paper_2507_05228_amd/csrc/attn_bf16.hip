@@ -19,6 +19,7 @@
 // 32x32 sub-blocks whose smallest key position exceeds the largest query position are skipped;
 // sub-blocks that are fully visible skip the compare.
 #include <climits>
+#include <cstdlib>
 #include "common.h"
 #include "device_utils.h"
 
@@ -408,6 +409,8 @@ int32_t launch_attn_bf16(const cascade_plan *p, const AttnArgs &a, hipStream_t s
     if ((a.qs_n | a.qs_h | a.qs_b | a.ks_n | a.ks_h | a.ks_b) % 8 ||
         ((uintptr_t)a.q | (uintptr_t)a.k | (uintptr_t)a.v | (uintptr_t)a.workspace) % 16)
         return CASCADE_EUNSUPPORTED;
-    if (a.d == 128) return launch_attn_cfg<128, 2>(p, a, s);
-    return launch_attn_cfg<64, 2>(p, a, s);
+    const char *tq = getenv("CASCADE_ATTN_TQ");
+    const int TQ = tq ? atoi(tq) : 2;
+    if (a.d == 128) return TQ == 1 ? launch_attn_cfg<128, 1>(p, a, s) : launch_attn_cfg<128, 2>(p, a, s);
+    return TQ == 1 ? launch_attn_cfg<64, 1>(p, a, s) : launch_attn_cfg<64, 2>(p, a, s);
 }

@@ -14,6 +14,7 @@
 // tiles never straddle a segment, so the buffer resource of the W tile is workgroup-uniform.
 // SWIGLU: the B tile interleaves BN/WN/2 gate rows with the BN/WN/2 up rows of the same output
 // columns per wavefront column, so gate and up of one output element live in the same lane.
+#include <cstdlib>
 #include "common.h"
 #include "device_utils.h"
 #include "epilogue.h"
@@ -246,8 +247,14 @@ static int32_t launch_cfg(const GemmArgs &a, hipStream_t s) {
     return CASCADE_OK;
 }
 
+int32_t launch_gemm_bf16_v2(const GemmArgs &a, hipStream_t s);
+
 int32_t launch_gemm_bf16(const GemmArgs &a, hipStream_t s) {
     if (a.M == 0 || a.N == 0) return CASCADE_OK;
+    if (!getenv("CASCADE_GEMM_V1")) {
+        int32_t st = launch_gemm_bf16_v2(a, s);
+        if (st != CASCADE_EUNSUPPORTED) return st;
+    }
     if (a.K % 8 != 0 || a.ldx % 8 != 0) return CASCADE_EUNSUPPORTED;
     if (((uintptr_t)a.X | (uintptr_t)a.W[0] | (uintptr_t)a.W[1] | (uintptr_t)a.W[2] | (uintptr_t)a.W_up) % 16)
         return CASCADE_EUNSUPPORTED;

@@ -1,0 +1,278 @@
+// bf16 shard GEMM, main kernel: Y[rows] = epilogue(X[rows] W^T), fp32 accumulation, K % 64 == 0.
+// (The token-as-batch linear layers: q/k/v projection of Algorithm 2, o projection of Algorithm 4
+// line 9, the MLP of Algorithm 1 line 17.  Shards appear only as row maps.)
+//
+// Shape of the kernel (chosen from measurements on MI355X: 16x16x32 bf16 MFMA reaches ~98 % of the
+// chip's matrix peak with two wavefronts per SIMD, ~89 % with one; LDS delivers ~235 B/clk/CU on
+// conflict-free 16-byte reads):
+//  * 8 wavefronts per workgroup (2 per SIMD, <= 256 registers each), 16x16x32 MFMA blocks.
+//  * K walked in steps of 64.  Tiles go from HBM/L2 straight into LDS with buffer loads that
+//    write LDS directly (no register staging, out-of-range rows read as zero), two stages:
+//    the loads of step t+1 are in flight while step t is multiplied.
+//  * LDS rows are 128 bytes (64 bf16) without padding; the 16-byte chunk c of tile row r is stored
+//    at slot c ^ ((r >> 1) & 7), which makes both the direct-to-LDS writes (1 KiB contiguous per
+//    wavefront instruction) and the MFMA operand reads (16 rows x same chunk) bank-conflict free.
+//  * Epilogue through LDS: each wavefront transposes 16 accumulator rows at a time so that a lane
+//    ends up with 4 consecutive columns (and the 4 columns 64 further on): stores and residual
+//    reads are 128-byte runs, and the two halves of a SwiGLU pair live in one lane.
+#include <cstdlib>
+#include "common.h"
+#include "device_utils.h"
+#include "epilogue.h"
+
+#define OOB_OFF 0x80000000u
+
+struct Gemm2Params {
+    const bf16_t *X;
+    const bf16_t *W[3];
+    const bf16_t *bias[3];
+    int32_t seg_rows[3], seg_col0[3], seg_tile0[3];
+    const bf16_t *Wup;
+    const bf16_t *residual;
+    bf16_t *Y;
+    int32_t M, K;
+    int32_t tiles_m, tiles_n;
+    int64_t ldx, ldy, ldres;
+    const int32_t *xmap, *ymap, *rmap;
+    int32_t seq_len, flags;
+    uint32_t x_bytes;
+};
+
+typedef __attribute__((address_space(3))) void lds_void;
+
+// 16 bytes per lane from a buffer straight into LDS: lane i of the wavefront lands at lds + 16 i.
+__device__ __forceinline__ void load16_to_lds(__amdgpu_buffer_rsrc_t r, unsigned char *lds, uint32_t voff) {
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_void *)lds, 16, voff, 0, 0, 0);
+}
+
+template <int BM, int BN, int WM, int WN, bool SWIGLU>
+__global__ __launch_bounds__(WM *WN * 64) void gemm2_kernel(Gemm2Params p) {
+    constexpr int NW = WM * WN;
+    constexpr int WTM = BM / WM, WTN = BN / WN;
+    constexpr int TM = WTM / 16, TN = WTN / 16;
+    constexpr int A_INSTR = BM / 8 / NW, B_INSTR = BN / 8 / NW;     // direct-to-LDS instructions per wavefront
+    constexpr int A_BYTES = BM * 128, STAGE_BYTES = (BM + BN) * 128;
+    constexpr int STG_LD = WTN + 4;                                // epilogue staging row (floats)
+    static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "tile rows must split over the wavefronts");
+    static_assert(WTN == 64 || WTN == 128, "epilogue assumes 64 or 128 columns per wavefront");
+    static_assert(!SWIGLU || WTN == 128, "swiglu pairs gate and up 64 columns apart");
+    static_assert(NW * 16 * STG_LD * 4 <= 2 * STAGE_BYTES, "epilogue staging must fit in the tile buffers");
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm0 = (wave / WN) * WTM, wn0 = (wave % WN) * WTN;
+
+    // workgroup -> tile: contiguous run of tiles (m fastest) per XCD
+    const int total = p.tiles_m * p.tiles_n;
+    int tile;
+    {
+        const int pid = blockIdx.x, xcd = pid & 7, idx = pid >> 3;
+        const int base = total >> 3, rem = total & 7;
+        tile = xcd * base + min(xcd, rem) + idx;
+    }
+    const int tile_m = tile % p.tiles_m, tile_n = tile / p.tiles_m;
+    const int seg = tile_n >= p.seg_tile0[2] ? 2 : tile_n >= p.seg_tile0[1] ? 1 : 0;
+    const int m0 = tile_m * BM;
+    constexpr int BN_OUT = SWIGLU ? BN / 2 : BN;
+    const int nloc0 = (tile_n - p.seg_tile0[seg]) * BN_OUT;
+    const int seg_rows = p.seg_rows[seg];
+    const int K = p.K;
+
+    const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(p.X), 0, p.x_bytes, 0x00020000);
+    const uint32_t w_bytes = (uint32_t)((int64_t)seg_rows * K * 2);
+    const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(p.W[seg]), 0, w_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t ru =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(SWIGLU ? p.Wup : p.W[seg]), 0, w_bytes, 0x00020000);
+
+    // ---- per-lane global offsets of the direct-to-LDS loads.  Instruction i of this wavefront fills
+    // tile rows wave*(rows/NW) + 8i .. +7: lane -> row lane/8, LDS slot lane%8, which must hold the
+    // logical chunk slot ^ ((row >> 1) & 7).
+    uint32_t a_off[A_INSTR], b_off[B_INSTR];
+#pragma unroll
+    for (int i = 0; i < A_INSTR; ++i) {
+        const int row = wave * (BM / NW) + 8 * i + (lane >> 3);
+        const int c = (lane & 7) ^ ((row >> 1) & 7);
+        const int gm = m0 + row;
+        a_off[i] = gm < p.M ? (uint32_t)(map_row(p.xmap, p.seq_len, gm) * p.ldx * 2) + c * 16 : OOB_OFF;
+    }
+#pragma unroll
+    for (int i = 0; i < B_INSTR; ++i) {
+        const int row = wave * (BN / NW) + 8 * i + (lane >> 3);
+        const int c = (lane & 7) ^ ((row >> 1) & 7);
+        int col;
+        if (SWIGLU) col = nloc0 + (row / WTN) * (WTN / 2) + (row % (WTN / 2));
+        else col = nloc0 + row;
+        b_off[i] = col < seg_rows ? (uint32_t)((int64_t)col * K * 2) + c * 16 : OOB_OFF;
+    }
+
+    auto issue_loads = [&](int kt, int stage) {
+        const uint32_t kb = (uint32_t)kt * 128;
+        unsigned char *sa = smem + stage * STAGE_BYTES + wave * (BM / NW) * 128;
+        unsigned char *sb = smem + stage * STAGE_BYTES + A_BYTES + wave * (BN / NW) * 128;
+#pragma unroll
+        for (int i = 0; i < A_INSTR; ++i)
+            load16_to_lds(rx, sa + i * 1024, a_off[i] + kb);
+#pragma unroll
+        for (int i = 0; i < B_INSTR; ++i) {
+            const int row0 = wave * (BN / NW) + 8 * i;                      // wavefront-uniform
+            const bool up = SWIGLU && ((row0 % WTN) >= WTN / 2);
+            if (up) load16_to_lds(ru, sb + i * 1024, b_off[i] + kb);
+            else load16_to_lds(rw, sb + i * 1024, b_off[i] + kb);
+        }
+    };
+
+    f32x4 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    // operand fetch: lane -> tile row lane%16 of a 16-row block, chunk 4 ks + lane/16, swizzled
+    const int frow = lane & 15, fch = lane >> 4, fsw = (lane & 15) >> 1;
+    const int a_lane = (wm0 + frow) * 128, b_lane = A_BYTES + (wn0 + frow) * 128;
+    const int KT = K / 64;
+    issue_loads(0, 0);
+    for (int kt = 0; kt < KT; ++kt) {
+        __syncthreads();                                   // tile kt has landed; stage (kt+1)&1 is free
+        if (kt + 1 < KT) issue_loads(kt + 1, (kt + 1) & 1);
+        const unsigned char *st = smem + (kt & 1) * STAGE_BYTES;
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            const int coff = ((4 * ks + fch) ^ fsw) * 16;
+            bf16x8 af[TM], bfr[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) af[i] = *(const bf16x8 *)(st + a_lane + i * 16 * 128 + coff);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) bfr[j] = *(const bf16x8 *)(st + b_lane + j * 16 * 128 + coff);
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+        }
+    }
+
+    // ---- epilogue.  acc[i][j][r]: row 16i + 4(lane/16) + r, column 16j + lane%16 of the wavefront tile.
+    const int flags = p.flags;
+    __syncthreads();                                       // everyone is done with the tile buffers
+    float *stg = (float *)smem + wave * 16 * STG_LD;
+    const int m4 = (lane & 15) * 4, rsel = lane >> 4;
+    constexpr int NCH = WTN / 64;                          // 4-column chunks per lane: columns 64 cc + m4
+    constexpr int NCH_OUT = SWIGLU ? 1 : NCH;
+    const int wcol0 = SWIGLU ? nloc0 + (wn0 / WTN) * (WTN / 2) : nloc0 + wn0;   // first output column (in segment)
+    const int gcol0 = p.seg_col0[seg];
+    f32x4 bias_v[NCH_OUT];
+#pragma unroll
+    for (int cc = 0; cc < NCH_OUT; ++cc) {
+        const int c = wcol0 + 64 * cc + m4;
+        bias_v[cc] = f32x4{0.f, 0.f, 0.f, 0.f};
+        if ((flags & CASCADE_EPI_BIAS) && p.bias[seg])
+#pragma unroll
+            for (int x = 0; x < 4; ++x)
+                if (c + x < seg_rows) bias_v[cc][x] = (float)p.bias[seg][c + x];
+    }
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) stg[(4 * rsel + r) * STG_LD + 16 * j + (lane & 15)] = acc[i][j][r];
+        __syncthreads();
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const int rl = 4 * t + rsel;
+            const int gm = m0 + wm0 + 16 * i + rl;
+            if (gm < p.M) {
+                bf16_t *yrow = p.Y + map_row(p.ymap, p.seq_len, gm) * p.ldy + gcol0;
+                const bf16_t *rrow = (flags & CASCADE_EPI_RESIDUAL)
+                                         ? p.residual + map_row(p.rmap, p.seq_len, gm) * p.ldres + gcol0 : nullptr;
+#pragma unroll
+                for (int cc = 0; cc < NCH_OUT; ++cc) {
+                    const int c = wcol0 + 64 * cc + m4;
+                    if (c >= seg_rows) continue;
+                    f32x4 v = *(const f32x4 *)(stg + rl * STG_LD + 64 * cc + m4) + bias_v[cc];
+                    if (SWIGLU) {
+                        const f32x4 up = *(const f32x4 *)(stg + rl * STG_LD + 64 + m4);
+#pragma unroll
+                        for (int x = 0; x < 4; ++x) v[x] = silu_f(v[x]) * up[x];
+                    } else if (flags & (CASCADE_EPI_GELU_ERF | CASCADE_EPI_GELU_TANH)) {
+#pragma unroll
+                        for (int x = 0; x < 4; ++x) v[x] = apply_act(v[x], flags);
+                    }
+                    if (c + 4 <= seg_rows) {
+                        if (rrow) {
+                            const bf16x4 rv = *(const bf16x4 *)(rrow + c);
+#pragma unroll
+                            for (int x = 0; x < 4; ++x) v[x] += (float)rv[x];
+                        }
+                        bf16x4 o = {(bf16_t)v[0], (bf16_t)v[1], (bf16_t)v[2], (bf16_t)v[3]};
+                        *(bf16x4 *)(yrow + c) = o;
+                    } else {
+                        for (int x = 0; x < 4 && c + x < seg_rows; ++x)
+                            yrow[c + x] = (bf16_t)(v[x] + (rrow ? (float)rrow[c + x] : 0.f));
+                    }
+                }
+            }
+        }
+        __syncthreads();
+    }
+}
+
+template <int BM, int BN, int WM, int WN, bool SWIGLU>
+static int32_t launch_cfg2(const GemmArgs &a, hipStream_t s) {
+    Gemm2Params p;
+    constexpr int BN_OUT = SWIGLU ? BN / 2 : BN;
+    int col0 = 0, tile0 = 0;
+    for (int i = 0; i < 3; ++i) {
+        int end = a.seg_end[i];
+        int rows = std::max(0, end - col0);
+        p.W[i] = (const bf16_t *)a.W[i];
+        p.bias[i] = (const bf16_t *)a.bias[i];
+        p.seg_rows[i] = rows;
+        p.seg_col0[i] = col0;
+        p.seg_tile0[i] = rows ? tile0 : INT32_MAX;
+        tile0 += (rows + BN_OUT - 1) / BN_OUT;
+        col0 = std::max(col0, end);
+        if ((int64_t)rows * a.K * 2 >= (int64_t)OOB_OFF) return CASCADE_EUNSUPPORTED;
+    }
+    if (p.seg_tile0[0] == INT32_MAX) return CASCADE_ESHAPE;
+    p.X = (const bf16_t *)a.X; p.Wup = (const bf16_t *)a.W_up; p.residual = (const bf16_t *)a.residual;
+    p.Y = (bf16_t *)a.Y;
+    p.M = a.M; p.K = a.K;
+    p.tiles_m = (a.M + BM - 1) / BM; p.tiles_n = tile0;
+    p.ldx = a.ldx; p.ldy = a.ldy; p.ldres = a.ldres;
+    p.xmap = a.xmap.map; p.ymap = a.ymap.map; p.rmap = a.rmap.map;
+    p.seq_len = a.xmap.map ? a.xmap.seq_len : a.ymap.map ? a.ymap.seq_len : a.rmap.map ? a.rmap.seq_len : 1;
+    p.flags = a.epilogue;
+    int64_t xb = (int64_t)a.M * a.ldx * 2;
+    if (xb >= (int64_t)OOB_OFF) return CASCADE_EUNSUPPORTED;
+    p.x_bytes = (uint32_t)xb;
+    constexpr size_t lds = (size_t)2 * (BM + BN) * 128;
+    auto kern = gemm2_kernel<BM, BN, WM, WN, SWIGLU>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        CASCADE_HIP_TRY(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        attr_set = true;
+    }
+    int64_t total = (int64_t)p.tiles_m * p.tiles_n;
+    if (total > INT32_MAX) return CASCADE_EUNSUPPORTED;
+    hipLaunchKernelGGL(kern, dim3((unsigned)total), dim3(WM * WN * 64), lds, s, p);
+    CASCADE_HIP_TRY(hipGetLastError());
+    return CASCADE_OK;
+}
+
+// Returns CASCADE_EUNSUPPORTED when the shape is not eligible (the caller then uses the general kernel).
+int32_t launch_gemm_bf16_v2(const GemmArgs &a, hipStream_t s) {
+    if (a.K % 64 != 0 || a.ldx % 8 != 0 || a.ldy % 4 != 0 || ((a.epilogue & CASCADE_EPI_RESIDUAL) && a.ldres % 4 != 0))
+        return CASCADE_EUNSUPPORTED;
+    if (((uintptr_t)a.Y | (uintptr_t)a.residual) % 8) return CASCADE_EUNSUPPORTED;
+    for (int i = 0; i < 3; ++i)
+        if (a.seg_end[i] % 4) return CASCADE_EUNSUPPORTED;          // 4-column store chunks stay inside a segment
+    const bool swiglu = a.epilogue & CASCADE_EPI_SWIGLU;
+    if (swiglu) return launch_cfg2<256, 256, 4, 2, true>(a, s);
+    const int64_t big_tiles = (int64_t)((a.M + 255) / 256) * ((a.N + 255) / 256);
+    if (big_tiles >= 160) return launch_cfg2<256, 256, 4, 2, false>(a, s);
+    return launch_cfg2<256, 128, 4, 2, false>(a, s);
+}
