@@ -2,22 +2,26 @@
 // keeps Algorithm 4's running maximum n, weight sum w and output o in registers while it walks the
 // key/value shards (same arithmetic as the post-pass, with the maximum updated online).
 //
-// Work split: a workgroup of 4 wavefronts owns one tile of packed query rows (never straddling a
-// shard) for up to 4 query heads that share one key/value head (GQA: the K/V tile in LDS is reused
-// by all of them).  A wavefront owns 32*TQ query rows of one head.
+// Work split: a workgroup of 8 wavefronts (2 per SIMD, so one wavefront's softmax arithmetic
+// overlaps the other's MFMAs) owns one tile of packed query rows (never straddling a shard) for up
+// to 4 query heads that share one key/value head: the K / V tiles staged in LDS are reused by all
+// of them (GQA).  A wavefront owns 32 query rows (two 16-row blocks) of one head.
 //
-// MFMA arrangement (32x32x16 bf16): the score block is computed TRANSPOSED, S^T = K Q^T, so that a
-// lane holds ONE query row (column lane%32) and 16 keys of it in its accumulator registers.  Row
-// maximum and sum of exponentials are then register-local plus one exchange with lane^32; the
-// rescale of the output accumulator is a per-lane multiply.  The second product is
-// O^T = V^T P^T: the exponentials go from the accumulator layout straight into the B operand (the
-// contraction index is permuted consistently on both operands), and V^T is read from a
-// transposed copy of V (built once per call by vtranspose_kernel), so both LDS tiles are read with
-// vector loads.
+// MFMA arrangement (16x16x32 bf16): the score block is computed TRANSPOSED, S^T = K Q^T, so a lane
+// holds ONE query row (column lane%16) and 4 keys of it per 16x16 block.  Row maximum and sum of
+// exponentials are register-local plus exchanges with lanes ^16 and ^32, and rescaling the output
+// accumulator is a per-lane multiply.  The second product is O^T = V^T P^T: the exponentials go
+// from the accumulator layout straight into the B operand (the contraction index is permuted the
+// same way on both operands), and V^T comes from a transposed copy of V built once per call, so
+// both LDS tiles are read with vector loads.
+//
+// Tiles of 64 keys go from L2/HBM straight into LDS (buffer loads that write LDS, zero for rows
+// past a ragged tile), two stages; rows are stored without padding, 16-byte chunk c of row r at
+// slot c ^ swizzle(r), so operand reads are bank-conflict free.
 //
 // Masking: key visible iff position[key] <= position[query] (original token positions).  Tiles and
-// 32x32 sub-blocks whose smallest key position exceeds the largest query position are skipped;
-// sub-blocks that are fully visible skip the compare.
+// 16x16 blocks whose smallest key position exceeds the largest query position are skipped; blocks
+// that are fully visible skip the compare.
 #include <climits>
 #include <cstdlib>
 #include "common.h"
@@ -26,11 +30,26 @@
 #define KV_TILE 64
 #define LOG2E 1.4426950408889634f
 #define LN2 0.6931471805599453f
+#define OOB_OFF 0x80000000u
+
+typedef __attribute__((address_space(3))) void lds_void;
+// Plan metadata is read-only for the kernel and indexed uniformly: reading it through the constant
+// address space makes these scalar loads, which do not share a counter with the tile loads in flight.
+typedef const __attribute__((address_space(4))) CascadeTile *tile_cptr;
+typedef const __attribute__((address_space(4))) int32_t *int_cptr;
+
+__device__ __forceinline__ void load16_to_lds(__amdgpu_buffer_rsrc_t r, unsigned char *lds, uint32_t voff) {
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_void *)lds, 16, voff, 0, 0, 0);
+}
+__device__ __forceinline__ void load4_to_lds(__amdgpu_buffer_rsrc_t r, unsigned char *lds, uint32_t voff) {
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_void *)lds, 4, voff, 0, 0, 0);
+}
 
 struct AttnBf16Params {
     const bf16_t *q, *k, *vt;
     int64_t qs_b, qs_h, qs_n, ks_b, ks_h, ks_n, vts_b, vts_h;
     int32_t npad;
+    uint32_t k_bytes, vt_bytes;      // extent of one (batch, kv head) slice, for the buffer resources
     const int32_t *q_rowmap, *kv_rowmap;
     const CascadeTile *qtiles;
     const CascadeTile *kvtiles;
@@ -82,22 +101,24 @@ __global__ __launch_bounds__(256) void vtranspose_kernel(const bf16_t *__restric
 }
 
 // ---------------------------------------------------------------------------- attention
-template <int D, int TQ>
-__global__ __launch_bounds__(256) void attn_bf16_kernel(AttnBf16Params p) {
-    constexpr int K_LD = D + 8;                  // padded K row (elements)
-    constexpr int V_LD = KV_TILE + 8;            // padded V^T row
-    constexpr int K_ELEMS = KV_TILE * K_LD, V_ELEMS = D * V_LD;
-    constexpr int BUF_BYTES = (K_ELEMS + V_ELEMS) * 2 + KV_TILE * 4;
-    constexpr int KS = D / 16;                   // k-steps of the score product
-    constexpr int DB = D / 32;                   // 32-row blocks of O^T
-    constexpr int K_CPR = D / 8;                 // 16-byte chunks per K row
-    constexpr int K_PER = KV_TILE * K_CPR / 256;
-    constexpr int V_PER = D * 8 / 256;
+template <int D>
+__global__ __launch_bounds__(512) void attn_bf16_kernel(AttnBf16Params p) {
+    constexpr int TQ = 2;                              // 16-row query blocks per wavefront
+    constexpr int KS = D / 32;                         // k-steps of the score product
+    constexpr int DB = D / 16;                         // 16-row blocks of O^T
+    constexpr int K_ROW = D * 2;                       // bytes per K row in LDS (256 or 128)
+    constexpr int K_RPI = 1024 / K_ROW;                // K rows filled by one direct-to-LDS instruction
+    constexpr int K_CPR = K_ROW / 16;                  // 16-byte chunks per K row
+    constexpr int K_BYTES = KV_TILE * K_ROW, V_BYTES = D * 128;
+    constexpr int STAGE = K_BYTES + V_BYTES + KV_TILE * 4;
+    constexpr int K_INSTR = KV_TILE / K_RPI / 8;       // per wavefront (8 wavefronts): 2 (D=128) or 1 (D=64)
+    constexpr int V_INSTR = D / 8 / 8;                 // 2 or 1
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int l32 = lane & 31, g2 = lane >> 5;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l16 = lane & 15, g4 = lane >> 4;
     const int hpb = p.hpb;
     const int hsel = wave % hpb, rg = wave / hpb;
     const int rep = p.H / p.Hkv;
@@ -108,154 +129,152 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnBf16Params p) {
     const int h = g * rep + (gh % hblocks) * hpb + hsel;
     const int kk = p.fused ? 0 : blockIdx.z;
 
-    const CascadeTile *qtp = p.qtiles + blockIdx.x;
-    struct { int row_start, n_rows, pmax; } qt = {qtp->row_start, qtp->n_rows, qtp->pmax};
-    const int wrow0 = rg * 32 * TQ;              // first row of this wavefront inside the q tile
+    const tile_cptr kvtiles = (tile_cptr)p.kvtiles;
+    const tile_cptr qtp = (tile_cptr)p.qtiles + blockIdx.x;
+    const int q_row_start = qtp->row_start, q_n_rows = qtp->n_rows, q_pmax = qtp->pmax;
+    const int wrow0 = rg * 16 * TQ;                    // first row of this wavefront inside the q tile
 
-    // ---- query fragments (B operand of S^T = K Q^T): lane holds row l32 of each 32-row block
+    // ---- query fragments (B operand of S^T = K Q^T): lane holds row l16 of each 16-row block,
+    //      head-dim chunk 32 ks + 8 g4
     bf16x8 qf[TQ][KS];
-    int posq[TQ];
-    int wq_max[TQ], wq_min[TQ];
+    int posq[TQ], wq_max[TQ], wq_min[TQ];
     bool row_ok[TQ];
 #pragma unroll
     for (int qb = 0; qb < TQ; ++qb) {
-        int rloc = wrow0 + 32 * qb + l32;
-        row_ok[qb] = rloc < qt.n_rows;
-        int r = qt.row_start + (row_ok[qb] ? rloc : qt.n_rows - 1);
-        const bf16_t *qp = p.q + b * p.qs_b + h * p.qs_h + (int64_t)(p.q_rowmap ? p.q_rowmap[r] : r) * p.qs_n + g2 * 8;
+        const int rloc = wrow0 + 16 * qb + l16;
+        row_ok[qb] = rloc < q_n_rows;
+        const int r = q_row_start + (row_ok[qb] ? rloc : q_n_rows - 1);
+        const bf16_t *qp = p.q + b * p.qs_b + h * p.qs_h + (int64_t)(p.q_rowmap ? p.q_rowmap[r] : r) * p.qs_n + g4 * 8;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) qf[qb][ks] = *(const bf16x8 *)(qp + ks * 16);
+        for (int ks = 0; ks < KS; ++ks) qf[qb][ks] = *(const bf16x8 *)(qp + ks * 32);
         posq[qb] = p.pos_packed[r];
-        int sub = __builtin_amdgcn_readfirstlane(rg * TQ + qb);          // 32-row granule of the q tile
-        wq_max[qb] = sub < 8 ? qtp->sub_max[sub] : INT_MIN;
-        wq_min[qb] = sub < 8 ? qtp->sub_min[sub] : INT_MAX;
-        wq_max[qb] = __builtin_amdgcn_readfirstlane(wq_max[qb]);
-        wq_min[qb] = __builtin_amdgcn_readfirstlane(wq_min[qb]);
+        const int sub = rg * TQ + qb;                  // 16-row granule of the q tile (wavefront-uniform)
+        wq_max[qb] = __builtin_amdgcn_readfirstlane(sub < 16 ? qtp->sub_max[sub] : INT_MIN);
+        wq_min[qb] = __builtin_amdgcn_readfirstlane(sub < 16 ? qtp->sub_min[sub] : INT_MAX);
     }
 
     // ---- key/value tile range
-    const int t_begin = p.fused ? 0 : p.kv_shard_first[kk];
-    const int t_end = p.fused ? p.n_kvtiles : p.kv_shard_first[kk + 1];
-    auto next_tile = [&](int t) {                // first tile >= t that some query row of the workgroup can see
-        while (t < t_end && p.causal && p.kvtiles[t].pmin > qt.pmax) ++t;
+    const int t_begin = p.fused ? 0 : ((int_cptr)p.kv_shard_first)[kk];
+    const int t_end = p.fused ? p.n_kvtiles : ((int_cptr)p.kv_shard_first)[kk + 1];
+    auto next_tile = [&](int t) {                      // first tile >= t that some query row of the workgroup can see
+        while (t < t_end && p.causal && kvtiles[t].pmin > q_pmax) ++t;
         return t;
     };
 
-    const bf16_t *kbase = p.k + b * p.ks_b + g * p.ks_h;
-    const bf16_t *vtbase = p.vt + b * p.vts_b + g * p.vts_h;
+    const __amdgpu_buffer_rsrc_t rk = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<bf16_t *>(p.k + b * p.ks_b + g * p.ks_h), 0, p.k_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rv = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<bf16_t *>(p.vt + b * p.vts_b + g * p.vts_h), 0, p.vt_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rp = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<int32_t *>(p.pos_packed), 0, (uint32_t)p.N * 4, 0x00020000);
 
-    u32x4 rk[K_PER], rv[V_PER];
-    int rpos = 0;
-    auto issue_loads = [&](const CascadeTile &kt, int tile_col) {
+    // Direct-to-LDS loads of one tile.  K instruction i of this wavefront fills K rows
+    // (wave*K_INSTR + i)*K_RPI ..: lane -> row lane/K_CPR, slot lane%K_CPR holding chunk slot^swz(row).
+    // V^T instruction i fills V^T rows (wave*V_INSTR + i)*8 ..: lane -> row lane/8, slot lane%8.
+    auto issue_loads = [&](int t, int stage) {
+        const int row_start = kvtiles[t].row_start, n_rows = kvtiles[t].n_rows;
+        unsigned char *sk = smem + stage * STAGE;
+        unsigned char *sv = sk + K_BYTES;
 #pragma unroll
-        for (int i = 0; i < K_PER; ++i) {
-            int id = tid + 256 * i;
-            int rr = id / K_CPR, ch = id % K_CPR;
-            int r = kt.row_start + min(rr, kt.n_rows - 1);        // rows past the tile repeat the last row; masked later
-            rk[i] = *(const u32x4 *)(kbase + (int64_t)(p.kv_rowmap ? p.kv_rowmap[r] : r) * p.ks_n + ch * 8);
+        for (int i = 0; i < K_INSTR; ++i) {
+            const int row0 = (wave * K_INSTR + i) * K_RPI;
+            const int rr = row0 + lane / K_CPR;
+            const int slot = lane % K_CPR;
+            const int c = D == 128 ? (slot ^ (rr & 15)) : (slot ^ ((rr >> 1) & 7));
+            uint32_t off = OOB_OFF;
+            if (rr < n_rows) {
+                const int r = row_start + rr;
+                off = (uint32_t)((int64_t)(p.kv_rowmap ? p.kv_rowmap[r] : r) * p.ks_n * 2) + c * 16;
+            }
+            load16_to_lds(rk, sk + row0 * K_ROW, off);
         }
 #pragma unroll
-        for (int i = 0; i < V_PER; ++i) {
-            int id = tid + 256 * i;
-            int c = id / 8, ch = id % 8;
-            rv[i] = *(const u32x4 *)(vtbase + (int64_t)c * p.npad + tile_col + ch * 8);
+        for (int i = 0; i < V_INSTR; ++i) {
+            const int row0 = (wave * V_INSTR + i) * 8;
+            const int rr = row0 + (lane >> 3);
+            const int c = (lane & 7) ^ ((rr >> 1) & 7);
+            load16_to_lds(rv, sv + row0 * 128, (uint32_t)(((int64_t)rr * p.npad + (int64_t)t * KV_TILE) * 2) + c * 16);
         }
-        if (tid < KV_TILE) rpos = p.pos_packed[kt.row_start + min(tid, kt.n_rows - 1)];
-    };
-    auto store_lds = [&](int buf) {
-        bf16_t *ks = (bf16_t *)(smem + buf * BUF_BYTES);
-        bf16_t *vs = ks + K_ELEMS;
-        int *ps = (int *)(vs + V_ELEMS);
-#pragma unroll
-        for (int i = 0; i < K_PER; ++i) {
-            int id = tid + 256 * i;
-            *(u32x4 *)(ks + (id / K_CPR) * K_LD + (id % K_CPR) * 8) = rk[i];
-        }
-#pragma unroll
-        for (int i = 0; i < V_PER; ++i) {
-            int id = tid + 256 * i;
-            *(u32x4 *)(vs + (id / 8) * V_LD + (id % 8) * 8) = rv[i];
-        }
-        if (tid < KV_TILE) ps[tid] = rpos;
+        if (wave == 0) load4_to_lds(rp, sv + V_BYTES, lane < n_rows ? (uint32_t)(row_start + lane) * 4 : OOB_OFF);
     };
 
-    f32x16 oacc[TQ][DB];
+    f32x4 oacc[TQ][DB];
     float m_run[TQ], l_run[TQ];
 #pragma unroll
     for (int qb = 0; qb < TQ; ++qb) {
         m_run[qb] = -INFINITY;
         l_run[qb] = 0.f;
 #pragma unroll
-        for (int db = 0; db < DB; ++db)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) oacc[qb][db][r] = 0.f;
+        for (int db = 0; db < DB; ++db) oacc[qb][db] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
+
+    // operand read swizzles
+    const int k_swz = D == 128 ? l16 : (l16 >> 1);
+    const int v_swz = l16 >> 1;
 
     int t = next_tile(t_begin);
-    int buf = 0;
-    if (t < t_end) {
-        issue_loads(p.kvtiles[t], t * KV_TILE);
-        store_lds(0);
-    }
-    __syncthreads();
+    int stage = 0;
+    if (t < t_end) issue_loads(t, 0);
     while (t < t_end) {
-        const CascadeTile kt = p.kvtiles[t];
-        const int tn = next_tile(t + 1);
-        if (tn < t_end) issue_loads(p.kvtiles[tn], tn * KV_TILE);
-
-        const bf16_t *ks = (const bf16_t *)(smem + buf * BUF_BYTES);
-        const bf16_t *vs = ks + K_ELEMS;
-        const int *ps = (const int *)(vs + V_ELEMS);
-
-        // ---- S^T blocks: sacc[qb][kb] = K[kb] Q[qb]^T
-        f32x16 sacc[TQ][2];
-        bool skip[TQ][2];
+        __syncthreads();                               // tile t has landed; the other stage is free
+        const tile_cptr ktp = kvtiles + t;
+        const int kn = ktp->n_rows;
+        const unsigned char *sk = smem + stage * STAGE;
+        const unsigned char *sv = sk + K_BYTES;
+        // key positions of this lane's accumulator rows (keys 16 kvb + 4 g4 + 0..3), read before the
+        // next tile's loads are issued so that nothing in flight can alias them
+        int4 pk[4];
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
+        for (int kvb = 0; kvb < 4; ++kvb) pk[kvb] = *(const int4 *)(sv + V_BYTES + (kvb * 16 + 4 * g4) * 4);
+        const int tn = next_tile(t + 1);
+        if (tn < t_end) issue_loads(tn, stage ^ 1);
+
+        // ---- S^T blocks: sacc[qb][kvb] = K[kvb] Q[qb]^T  (16 keys x 16 queries)
+        f32x4 sacc[TQ][4];
+        bool skip[TQ][4];
+#pragma unroll
+        for (int kvb = 0; kvb < 4; ++kvb) {
+            const int kmin = ktp->sub_min[kvb];
             bool any = false;
 #pragma unroll
             for (int qb = 0; qb < TQ; ++qb) {
-                skip[qb][kb] = (kb * 32 >= kt.n_rows) || (p.causal && kt.sub_min[kb] > wq_max[qb]);
-                any |= !skip[qb][kb];
-#pragma unroll
-                for (int r = 0; r < 16; ++r) sacc[qb][kb][r] = 0.f;
+                skip[qb][kvb] = (kvb * 16 >= kn) || (p.causal && kmin > wq_max[qb]);
+                any |= !skip[qb][kvb];
+                sacc[qb][kvb] = f32x4{0.f, 0.f, 0.f, 0.f};
             }
             if (!any) continue;
-            const bf16_t *kp = ks + (kb * 32 + l32) * K_LD + g2 * 8;
+            const unsigned char *kp = sk + (kvb * 16 + l16) * K_ROW;
 #pragma unroll
-            for (int s = 0; s < KS; ++s) {
-                bf16x8 kf = *(const bf16x8 *)(kp + s * 16);
+            for (int ks = 0; ks < KS; ++ks) {
+                const bf16x8 kf = *(const bf16x8 *)(kp + (((4 * ks + g4) ^ k_swz) * 16));
 #pragma unroll
                 for (int qb = 0; qb < TQ; ++qb)
-                    if (!skip[qb][kb])
-                        sacc[qb][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qb][s], sacc[qb][kb], 0, 0, 0);
+                    if (!skip[qb][kvb])
+                        sacc[qb][kvb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf[qb][ks], sacc[qb][kvb], 0, 0, 0);
             }
         }
 
-        // ---- mask, row statistics, exponentials, P^T fragments
+        // ---- mask, row statistics, exponentials.  sacc[qb][kvb][r]: key 16 kvb + 4 g4 + r, query l16.
 #pragma unroll
         for (int qb = 0; qb < TQ; ++qb) {
             float mx = -INFINITY;
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb) {
-                if (skip[qb][kb]) continue;
-                const bool need_mask = (kb * 32 + 32 > kt.n_rows) || (p.causal && kt.sub_max[kb] > wq_min[qb]);
+            for (int kvb = 0; kvb < 4; ++kvb) {
+                if (skip[qb][kvb]) continue;
+                const bool need_mask = (kvb * 16 + 16 > kn) || (p.causal && ktp->sub_max[kvb] > wq_min[qb]);
                 if (need_mask) {
+                    const int kv0 = kvb * 16 + 4 * g4;
+                    const int pks[4] = {pk[kvb].x, pk[kvb].y, pk[kvb].z, pk[kvb].w};
 #pragma unroll
-                    for (int r4 = 0; r4 < 4; ++r4) {
-                        const int kv0 = kb * 32 + 8 * r4 + 4 * g2;
-                        const int4 pk = *(const int4 *)(ps + kv0);
-                        const int pks[4] = {pk.x, pk.y, pk.z, pk.w};
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) {
-                            bool vis = (kv0 + i < kt.n_rows) && (!p.causal || pks[i] <= posq[qb]);
-                            if (!vis) sacc[qb][kb][4 * r4 + i] = -INFINITY;
-                        }
+                    for (int r = 0; r < 4; ++r) {
+                        const bool vis = (kv0 + r < kn) && (!p.causal || pks[r] <= posq[qb]);
+                        if (!vis) sacc[qb][kvb][r] = -INFINITY;
                     }
                 }
 #pragma unroll
-                for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[qb][kb][r]);
+                for (int r = 0; r < 4; ++r) mx = fmaxf(mx, sacc[qb][kvb][r]);
             }
+            mx = fmaxf(mx, __shfl_xor(mx, 16, WAVE));
             mx = fmaxf(mx, __shfl_xor(mx, 32, WAVE));
             const float m_new = fmaxf(m_run[qb], mx * p.scale_log2);
             const float m_sub = (m_new == -INFINITY) ? 0.f : m_new;
@@ -263,89 +282,79 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnBf16Params p) {
             m_run[qb] = m_new;
             float psum = 0.f;
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb) {
-                if (skip[qb][kb]) continue;
+            for (int kvb = 0; kvb < 4; ++kvb) {
+                if (skip[qb][kvb]) continue;
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    float pv = __builtin_amdgcn_exp2f(fmaf(sacc[qb][kb][r], p.scale_log2, -m_sub));
-                    sacc[qb][kb][r] = pv;
+                for (int r = 0; r < 4; ++r) {
+                    const float pv = __builtin_amdgcn_exp2f(fmaf(sacc[qb][kvb][r], p.scale_log2, -m_sub));
+                    sacc[qb][kvb][r] = pv;
                     psum += pv;
                 }
             }
             l_run[qb] = l_run[qb] * alpha + psum;
+            if (__builtin_amdgcn_readfirstlane(__any(alpha != 1.0f))) {     // rescale only when some maximum moved
 #pragma unroll
-            for (int db = 0; db < DB; ++db)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) oacc[qb][db][r] *= alpha;
+                for (int db = 0; db < DB; ++db) oacc[qb][db] *= alpha;
+            }
         }
 
-        // ---- O^T += V^T P^T.  Step s covers keys 16s..16s+15 of the tile; k-slot (g2, i) of both
-        // operands is key 16s + 8(i/4) + 4 g2 + i%4, which is accumulator register 8(s%2)+i of block s/2.
+        // ---- O^T += V^T P^T.  Step s covers keys 32s..32s+31; k-slot (g4, i) of both operands is key
+        // 32s + 16(i/4) + 4 g4 + i%4, i.e. accumulator register i%4 of block 2s + i/4.
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            const int kb = s >> 1;
+        for (int s = 0; s < 2; ++s) {
             bool any = false;
             bf16x8 pf[TQ];
 #pragma unroll
             for (int qb = 0; qb < TQ; ++qb) {
-                any |= !skip[qb][kb];
+                any |= !(skip[qb][2 * s] && skip[qb][2 * s + 1]);
 #pragma unroll
-                for (int i = 0; i < 8; ++i) pf[qb][i] = (bf16_t)sacc[qb][kb][8 * (s & 1) + i];
+                for (int i = 0; i < 4; ++i) {
+                    pf[qb][i] = (bf16_t)sacc[qb][2 * s][i];
+                    pf[qb][4 + i] = (bf16_t)sacc[qb][2 * s + 1][i];
+                }
             }
             if (!any) continue;
 #pragma unroll
             for (int db = 0; db < DB; ++db) {
-                const bf16_t *vp = vs + (db * 32 + l32) * V_LD + 16 * s + 4 * g2;
-                bf16x4 lo = *(const bf16x4 *)vp, hi = *(const bf16x4 *)(vp + 8);
-                bf16x8 vf = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                const unsigned char *vp = sv + (db * 16 + l16) * 128 + 8 * (g4 & 1);
+                const bf16x4 lo = *(const bf16x4 *)(vp + (((4 * s + (g4 >> 1)) ^ v_swz) * 16));
+                const bf16x4 hi = *(const bf16x4 *)(vp + (((4 * s + 2 + (g4 >> 1)) ^ v_swz) * 16));
+                const bf16x8 vf = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
 #pragma unroll
                 for (int qb = 0; qb < TQ; ++qb)
-                    if (!skip[qb][kb])
-                        oacc[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[qb], oacc[qb][db], 0, 0, 0);
+                    if (!(skip[qb][2 * s] && skip[qb][2 * s + 1]))
+                        oacc[qb][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf[qb], oacc[qb][db], 0, 0, 0);
             }
         }
-
-        if (tn < t_end) store_lds(buf ^ 1);
-        __syncthreads();
-        buf ^= 1;
+        stage ^= 1;
         t = tn;
     }
 
-    // ---- write-out.  oacc[qb][db][r]: query row 32qb + l32, column 32db + 8(r/4) + 4 g2 + r%4.
+    // ---- write-out.  oacc[qb][db][r]: query row 16qb + l16, column 16db + 4 g4 + r.
 #pragma unroll
     for (int qb = 0; qb < TQ; ++qb) {
-        const float l_tot = l_run[qb] + __shfl_xor(l_run[qb], 32, WAVE);
+        float l_tot = l_run[qb] + __shfl_xor(l_run[qb], 16, WAVE);
+        l_tot += __shfl_xor(l_tot, 32, WAVE);
         if (!row_ok[qb]) continue;
-        const int r = qt.row_start + wrow0 + 32 * qb + l32;
+        const int r = q_row_start + wrow0 + 16 * qb + l16;
         const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
         if (p.fused) {
-            bf16_t *op = p.o + ((int64_t)b * p.N + (p.o_rowmap ? p.o_rowmap[r] : r)) * p.o_ld + (int64_t)h * D;
+            bf16_t *op = p.o + ((int64_t)b * p.N + (p.o_rowmap ? p.o_rowmap[r] : r)) * p.o_ld + (int64_t)h * D + 4 * g4;
 #pragma unroll
-            for (int db = 0; db < DB; ++db)
-#pragma unroll
-                for (int r4 = 0; r4 < 4; ++r4) {
-                    bf16x4 v;
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) v[i] = (bf16_t)(oacc[qb][db][4 * r4 + i] * inv);
-                    *(bf16x4 *)(op + 32 * db + 8 * r4 + 4 * g2) = v;
-                }
+            for (int db = 0; db < DB; ++db) {
+                const f32x4 v = oacc[qb][db] * inv;
+                *(bf16x4 *)(op + 16 * db) = bf16x4{(bf16_t)v[0], (bf16_t)v[1], (bf16_t)v[2], (bf16_t)v[3]};
+            }
         } else {
             const int64_t me = (((int64_t)b * p.H + h) * p.S + kk) * p.N + r;
-            if (g2 == 0) {
+            if (g4 == 0) {
                 p.m[me] = m_run[qb] * LN2;
                 p.e[me] = l_tot;
             }
             const float f = p.u_mode == CASCADE_U_NORMALISED ? inv : 1.0f;
-            float *up = p.u + ((((int64_t)b * p.S + kk) * p.H + h) * p.N + r) * D;
+            float *up = p.u + ((((int64_t)b * p.S + kk) * p.H + h) * p.N + r) * D + 4 * g4;
 #pragma unroll
-            for (int db = 0; db < DB; ++db)
-#pragma unroll
-                for (int r4 = 0; r4 < 4; ++r4) {
-                    f32x4 v;
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) v[i] = oacc[qb][db][4 * r4 + i] * f;
-                    *(f32x4 *)(up + 32 * db + 8 * r4 + 4 * g2) = v;
-                }
+            for (int db = 0; db < DB; ++db) *(f32x4 *)(up + 16 * db) = oacc[qb][db] * f;
         }
     }
 }
@@ -356,16 +365,17 @@ size_t attn_bf16_workspace_bytes(const cascade_plan *p, int32_t B, int32_t Hkv, 
     return align_up((size_t)B * Hkv * d * npad_of(p) * 2, 256);
 }
 
-template <int D, int TQ>
+template <int D>
 static int32_t launch_attn_cfg(const cascade_plan *p, const AttnArgs &a, hipStream_t s) {
     const int N = p->seq_len, S = p->n_shards;
     const int rep = a.H / a.Hkv;
     const int hpb = rep % 4 == 0 ? 4 : rep % 2 == 0 ? 2 : 1;
-    const int rowgroups = 4 / hpb;
-    const int granule = 32 * TQ * rowgroups;                   // 32 .. 256
+    const int rowgroups = 8 / hpb;
+    const int granule = 32 * rowgroups;                        // 64, 128 or 256 query rows per workgroup
     const CascadeTileList &ql = plan_tiles(p, granule);
     const CascadeTileList &kl = plan_tiles(p, KV_TILE);
     const int npad = npad_of(p);
+    if (ql.count == 0) return CASCADE_OK;
 
     bf16_t *vt = (bf16_t *)a.workspace;
     {
@@ -378,6 +388,9 @@ static int32_t launch_attn_cfg(const cascade_plan *p, const AttnArgs &a, hipStre
     k.q = (const bf16_t *)a.q; k.k = (const bf16_t *)a.k; k.vt = vt;
     k.qs_b = a.qs_b; k.qs_h = a.qs_h; k.qs_n = a.qs_n; k.ks_b = a.ks_b; k.ks_h = a.ks_h; k.ks_n = a.ks_n;
     k.vts_b = (int64_t)a.Hkv * D * npad; k.vts_h = (int64_t)D * npad; k.npad = npad;
+    const int64_t kb = ((int64_t)(N - 1) * a.ks_n + D) * 2, vb = (int64_t)D * npad * 2;
+    if (kb >= (int64_t)OOB_OFF || vb >= (int64_t)OOB_OFF) return CASCADE_EUNSUPPORTED;
+    k.k_bytes = (uint32_t)kb; k.vt_bytes = (uint32_t)vb;
     k.q_rowmap = a.q_rowmap; k.kv_rowmap = a.kv_rowmap;
     k.qtiles = ql.dev; k.kvtiles = kl.dev; k.kv_shard_first = kl.shard_first; k.n_kvtiles = kl.count;
     k.pos_packed = p->pos_packed_d;
@@ -387,17 +400,17 @@ static int32_t launch_attn_cfg(const cascade_plan *p, const AttnArgs &a, hipStre
     k.m = a.m; k.e = a.e; k.u = a.u; k.o = (bf16_t *)a.o; k.o_ld = a.o_ld; k.o_rowmap = a.o_rowmap;
     k.hpb = hpb;
 
-    constexpr int lds = 2 * ((KV_TILE * (D + 8) + D * (KV_TILE + 8)) * 2 + KV_TILE * 4);
-    auto kern = attn_bf16_kernel<D, TQ>;
+    constexpr int lds = 2 * (KV_TILE * D * 2 + D * 128 + KV_TILE * 4);
+    auto kern = attn_bf16_kernel<D>;
     static bool attr_set = false;
     if (!attr_set) {
         CASCADE_HIP_TRY(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds));
         attr_set = true;
     }
     const int64_t gy = (int64_t)a.B * a.Hkv * (rep / hpb);
-    if (gy > 65535 || S > 65535 || ql.count == 0) return ql.count == 0 ? CASCADE_OK : CASCADE_EUNSUPPORTED;
+    if (gy > 65535 || S > 65535) return CASCADE_EUNSUPPORTED;
     dim3 grid(ql.count, (unsigned)gy, a.fused ? 1 : S);
-    hipLaunchKernelGGL(kern, grid, dim3(256), lds, s, k);
+    hipLaunchKernelGGL(kern, grid, dim3(512), lds, s, k);
     CASCADE_HIP_TRY(hipGetLastError());
     return CASCADE_OK;
 }
@@ -409,8 +422,6 @@ int32_t launch_attn_bf16(const cascade_plan *p, const AttnArgs &a, hipStream_t s
     if ((a.qs_n | a.qs_h | a.qs_b | a.ks_n | a.ks_h | a.ks_b) % 8 ||
         ((uintptr_t)a.q | (uintptr_t)a.k | (uintptr_t)a.v | (uintptr_t)a.workspace) % 16)
         return CASCADE_EUNSUPPORTED;
-    const char *tq = getenv("CASCADE_ATTN_TQ");
-    const int TQ = tq ? atoi(tq) : 2;
-    if (a.d == 128) return TQ == 1 ? launch_attn_cfg<128, 1>(p, a, s) : launch_attn_cfg<128, 2>(p, a, s);
-    return TQ == 1 ? launch_attn_cfg<64, 1>(p, a, s) : launch_attn_cfg<64, 2>(p, a, s);
+    if (a.d == 128) return launch_attn_cfg<128>(p, a, s);
+    return launch_attn_cfg<64>(p, a, s);
 }

@@ -6,7 +6,7 @@
 #include "../../include/cascade.h"
 
 // One tile of packed rows that never straddles a shard boundary.  sub_min/sub_max hold
-// the smallest / largest token position of each 32-row granule of the tile (granules
+// the smallest / largest token position of each 16-row granule of the tile (granules
 // beyond n_rows hold min = INT_MAX, max = INT_MIN).
 struct CascadeTile {
     int32_t row_start;   // first packed row
@@ -15,8 +15,8 @@ struct CascadeTile {
     int32_t pmin;        // min position over the tile
     int32_t pmax;        // max position over the tile
     int32_t pad[3];
-    int32_t sub_min[8];
-    int32_t sub_max[8];
+    int32_t sub_min[16];
+    int32_t sub_max[16];
 };
 
 struct CascadeTileList {
@@ -107,7 +107,7 @@ struct AttnArgs {
     float scale;
     int32_t mask_kind;
     const void *q, *k, *v;
-    int64_t qs_b, qs_h, qs_n, ks_b, ks_h, ks_n, vs_b, vs_h, vs_n;
+    int64_t qs_b, qs_h, qs_n, ks_b, ks_h, ks_n;     // element strides; k and v share theirs
     const int32_t *q_rowmap, *kv_rowmap;   // packed row -> row in q / k,v (nullptr: identity)
     int32_t fused;                   // 1: running merge over all shards, write o; 0: per-shard partials
     int32_t u_mode;

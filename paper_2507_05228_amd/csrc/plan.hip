@@ -52,10 +52,10 @@ static hipError_t build_tiles(cascade_plan *p, CascadeTileList &out, int granule
             t.shard = j;
             t.pmin = INT_MAX;
             t.pmax = INT_MIN;
-            for (int g = 0; g < 8; ++g) { t.sub_min[g] = INT_MAX; t.sub_max[g] = INT_MIN; }
+            for (int g = 0; g < 16; ++g) { t.sub_min[g] = INT_MAX; t.sub_max[g] = INT_MIN; }
             for (int i = 0; i < t.n_rows; ++i) {
                 int pos = p->pos_packed_h[r + i];
-                int g = i / 32;
+                int g = i / 16;
                 t.sub_min[g] = std::min(t.sub_min[g], pos);
                 t.sub_max[g] = std::max(t.sub_max[g], pos);
                 t.pmin = std::min(t.pmin, pos);
