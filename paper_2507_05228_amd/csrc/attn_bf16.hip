@@ -45,6 +45,22 @@ __device__ __forceinline__ void load4_to_lds(__amdgpu_buffer_rsrc_t r, unsigned 
     __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_void *)lds, 4, voff, 0, 0, 0);
 }
 
+// max over the 4 lanes {l, l^16, l^32, l^48} with the gfx950 lane-swap instructions (no LDS traffic)
+__device__ __forceinline__ float xor_max_16_32(float v) {
+    typedef __attribute__((ext_vector_type(2))) unsigned u2;
+    u2 r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    v = fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+    r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float xor_sum_16_32(float v) {
+    typedef __attribute__((ext_vector_type(2))) unsigned u2;
+    u2 r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    v = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+    r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
 struct AttnBf16Params {
     const bf16_t *q, *k, *vt;
     int64_t qs_b, qs_h, qs_n, ks_b, ks_h, ks_n, vts_b, vts_h;
@@ -153,6 +169,11 @@ __global__ __launch_bounds__(512) void attn_bf16_kernel(AttnBf16Params p) {
         wq_min[qb] = __builtin_amdgcn_readfirstlane(sub < 16 ? qtp->sub_min[sub] : INT_MAX);
     }
 
+    int qlim[TQ];
+#pragma unroll
+    for (int qb = 0; qb < TQ; ++qb) qlim[qb] = p.causal ? posq[qb] : INT_MAX - 1;
+    const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
+
     // ---- key/value tile range
     const int t_begin = p.fused ? 0 : ((int_cptr)p.kv_shard_first)[kk];
     const int t_end = p.fused ? p.n_kvtiles : ((int_cptr)p.kv_shard_first)[kk + 1];
@@ -223,59 +244,74 @@ __global__ __launch_bounds__(512) void attn_bf16_kernel(AttnBf16Params p) {
         const unsigned char *sv = sk + K_BYTES;
         // key positions of this lane's accumulator rows (keys 16 kvb + 4 g4 + 0..3), read before the
         // next tile's loads are issued so that nothing in flight can alias them
-        int4 pk[4];
+        int pk[4][4];
 #pragma unroll
-        for (int kvb = 0; kvb < 4; ++kvb) pk[kvb] = *(const int4 *)(sv + V_BYTES + (kvb * 16 + 4 * g4) * 4);
+        for (int kvb = 0; kvb < 4; ++kvb) {
+            const int4 v4 = *(const int4 *)(sv + V_BYTES + (kvb * 16 + 4 * g4) * 4);
+            pk[kvb][0] = v4.x; pk[kvb][1] = v4.y; pk[kvb][2] = v4.z; pk[kvb][3] = v4.w;
+        }
+        if (kn < KV_TILE) {                            // ragged tile: keys past its end are never visible
+#pragma unroll
+            for (int kvb = 0; kvb < 4; ++kvb)
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    if (kvb * 16 + 4 * g4 + r >= kn) pk[kvb][r] = INT_MAX;
+        }
         const int tn = next_tile(t + 1);
         if (tn < t_end) issue_loads(tn, stage ^ 1);
 
-        // ---- S^T blocks: sacc[qb][kvb] = K[kvb] Q[qb]^T  (16 keys x 16 queries)
-        f32x4 sacc[TQ][4];
-        bool skip[TQ][4];
+        // Per-tile metadata (scalar): which 16-key blocks this wavefront can see at all, and which
+        // need the element-wise compare.  Decisions are per wavefront (both query blocks together) to
+        // keep the inner loops free of branches, so LDS reads can be issued ahead of the MFMAs.
+        bool skipk[4], maskk[4];
 #pragma unroll
         for (int kvb = 0; kvb < 4; ++kvb) {
-            const int kmin = ktp->sub_min[kvb];
-            bool any = false;
+            const int kmin = ktp->sub_min[kvb], kmax = ktp->sub_max[kvb];
+            const int qmax = max(wq_max[0], wq_max[1]), qmin = min(wq_min[0], wq_min[1]);
+            skipk[kvb] = (kvb * 16 >= kn) || (p.causal && kmin > qmax);
+            maskk[kvb] = (kvb * 16 + 16 > kn) || (p.causal && kmax > qmin);
+        }
+
+        // ---- S^T blocks: sacc[qb][kvb] = K[kvb] Q[qb]^T  (16 keys x 16 queries)
+        f32x4 sacc[TQ][4];
+#pragma unroll
+        for (int kvb = 0; kvb < 4; ++kvb) {
+            if (skipk[kvb]) continue;
+            const unsigned char *kp = sk + (kvb * 16 + l16) * K_ROW;
+            bf16x8 kf[KS];
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) kf[ks] = *(const bf16x8 *)(kp + (((4 * ks + g4) ^ k_swz) * 16));
 #pragma unroll
             for (int qb = 0; qb < TQ; ++qb) {
-                skip[qb][kvb] = (kvb * 16 >= kn) || (p.causal && kmin > wq_max[qb]);
-                any |= !skip[qb][kvb];
-                sacc[qb][kvb] = f32x4{0.f, 0.f, 0.f, 0.f};
-            }
-            if (!any) continue;
-            const unsigned char *kp = sk + (kvb * 16 + l16) * K_ROW;
+                sacc[qb][kvb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[0], qf[qb][0], zero4, 0, 0, 0);
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                const bf16x8 kf = *(const bf16x8 *)(kp + (((4 * ks + g4) ^ k_swz) * 16));
-#pragma unroll
-                for (int qb = 0; qb < TQ; ++qb)
-                    if (!skip[qb][kvb])
-                        sacc[qb][kvb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf[qb][ks], sacc[qb][kvb], 0, 0, 0);
+                for (int ks = 1; ks < KS; ++ks)
+                    sacc[qb][kvb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[ks], qf[qb][ks], sacc[qb][kvb], 0, 0, 0);
             }
         }
 
-        // ---- mask, row statistics, exponentials.  sacc[qb][kvb][r]: key 16 kvb + 4 g4 + r, query l16.
+        // ---- mask.  sacc[qb][kvb][r]: key 16 kvb + 4 g4 + r, query l16.  With no causal mask the
+        // limit is INT_MAX - 1, so only the keys past a ragged tile's end (position INT_MAX) are cut.
+#pragma unroll
+        for (int kvb = 0; kvb < 4; ++kvb) {
+            if (skipk[kvb] || !maskk[kvb]) continue;
+#pragma unroll
+            for (int qb = 0; qb < TQ; ++qb)
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    if (pk[kvb][r] > qlim[qb]) sacc[qb][kvb][r] = -INFINITY;
+        }
+
+        // ---- row statistics and exponentials
 #pragma unroll
         for (int qb = 0; qb < TQ; ++qb) {
             float mx = -INFINITY;
 #pragma unroll
-            for (int kvb = 0; kvb < 4; ++kvb) {
-                if (skip[qb][kvb]) continue;
-                const bool need_mask = (kvb * 16 + 16 > kn) || (p.causal && ktp->sub_max[kvb] > wq_min[qb]);
-                if (need_mask) {
-                    const int kv0 = kvb * 16 + 4 * g4;
-                    const int pks[4] = {pk[kvb].x, pk[kvb].y, pk[kvb].z, pk[kvb].w};
+            for (int kvb = 0; kvb < 4; ++kvb)
+                if (!skipk[kvb])
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        const bool vis = (kv0 + r < kn) && (!p.causal || pks[r] <= posq[qb]);
-                        if (!vis) sacc[qb][kvb][r] = -INFINITY;
-                    }
-                }
-#pragma unroll
-                for (int r = 0; r < 4; ++r) mx = fmaxf(mx, sacc[qb][kvb][r]);
-            }
-            mx = fmaxf(mx, __shfl_xor(mx, 16, WAVE));
-            mx = fmaxf(mx, __shfl_xor(mx, 32, WAVE));
+                    for (int r = 0; r < 4; ++r) mx = fmaxf(mx, sacc[qb][kvb][r]);
+            mx = xor_max_16_32(mx);
             const float m_new = fmaxf(m_run[qb], mx * p.scale_log2);
             const float m_sub = (m_new == -INFINITY) ? 0.f : m_new;
             const float alpha = __builtin_amdgcn_exp2f(m_run[qb] - m_sub);
@@ -283,7 +319,7 @@ __global__ __launch_bounds__(512) void attn_bf16_kernel(AttnBf16Params p) {
             float psum = 0.f;
 #pragma unroll
             for (int kvb = 0; kvb < 4; ++kvb) {
-                if (skip[qb][kvb]) continue;
+                if (skipk[kvb]) continue;
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     const float pv = __builtin_amdgcn_exp2f(fmaf(sacc[qb][kvb][r], p.scale_log2, -m_sub));
@@ -302,28 +338,25 @@ __global__ __launch_bounds__(512) void attn_bf16_kernel(AttnBf16Params p) {
         // 32s + 16(i/4) + 4 g4 + i%4, i.e. accumulator register i%4 of block 2s + i/4.
 #pragma unroll
         for (int s = 0; s < 2; ++s) {
-            bool any = false;
+            if (skipk[2 * s] && skipk[2 * s + 1]) continue;
             bf16x8 pf[TQ];
 #pragma unroll
-            for (int qb = 0; qb < TQ; ++qb) {
-                any |= !(skip[qb][2 * s] && skip[qb][2 * s + 1]);
+            for (int qb = 0; qb < TQ; ++qb)
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    pf[qb][i] = (bf16_t)sacc[qb][2 * s][i];
-                    pf[qb][4 + i] = (bf16_t)sacc[qb][2 * s + 1][i];
+                    pf[qb][i] = skipk[2 * s] ? (bf16_t)0.f : (bf16_t)sacc[qb][2 * s][i];
+                    pf[qb][4 + i] = skipk[2 * s + 1] ? (bf16_t)0.f : (bf16_t)sacc[qb][2 * s + 1][i];
                 }
-            }
-            if (!any) continue;
+            const unsigned char *vp = sv + l16 * 128 + 8 * (g4 & 1);
+            const int c_lo = ((4 * s + (g4 >> 1)) ^ v_swz) * 16, c_hi = ((4 * s + 2 + (g4 >> 1)) ^ v_swz) * 16;
 #pragma unroll
             for (int db = 0; db < DB; ++db) {
-                const unsigned char *vp = sv + (db * 16 + l16) * 128 + 8 * (g4 & 1);
-                const bf16x4 lo = *(const bf16x4 *)(vp + (((4 * s + (g4 >> 1)) ^ v_swz) * 16));
-                const bf16x4 hi = *(const bf16x4 *)(vp + (((4 * s + 2 + (g4 >> 1)) ^ v_swz) * 16));
+                const bf16x4 lo = *(const bf16x4 *)(vp + db * 16 * 128 + c_lo);
+                const bf16x4 hi = *(const bf16x4 *)(vp + db * 16 * 128 + c_hi);
                 const bf16x8 vf = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
 #pragma unroll
                 for (int qb = 0; qb < TQ; ++qb)
-                    if (!(skip[qb][2 * s] && skip[qb][2 * s + 1]))
-                        oacc[qb][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf[qb], oacc[qb][db], 0, 0, 0);
+                    oacc[qb][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf[qb], oacc[qb][db], 0, 0, 0);
             }
         }
         stage ^= 1;
@@ -333,8 +366,7 @@ __global__ __launch_bounds__(512) void attn_bf16_kernel(AttnBf16Params p) {
     // ---- write-out.  oacc[qb][db][r]: query row 16qb + l16, column 16db + 4 g4 + r.
 #pragma unroll
     for (int qb = 0; qb < TQ; ++qb) {
-        float l_tot = l_run[qb] + __shfl_xor(l_run[qb], 16, WAVE);
-        l_tot += __shfl_xor(l_tot, 32, WAVE);
+        const float l_tot = xor_sum_16_32(l_run[qb]);
         if (!row_ok[qb]) continue;
         const int r = q_row_start + wrow0 + 16 * qb + l16;
         const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;

@@ -6,12 +6,17 @@
 // chip's matrix peak with two wavefronts per SIMD, ~89 % with one; LDS delivers ~235 B/clk/CU on
 // conflict-free 16-byte reads):
 //  * 8 wavefronts per workgroup (2 per SIMD, <= 256 registers each), 16x16x32 MFMA blocks.
-//  * K walked in steps of 64.  Tiles go from HBM/L2 straight into LDS with buffer loads that
-//    write LDS directly (no register staging, out-of-range rows read as zero), two stages:
-//    the loads of step t+1 are in flight while step t is multiplied.
-//  * LDS rows are 128 bytes (64 bf16) without padding; the 16-byte chunk c of tile row r is stored
-//    at slot c ^ ((r >> 1) & 7), which makes both the direct-to-LDS writes (1 KiB contiguous per
-//    wavefront instruction) and the MFMA operand reads (16 rows x same chunk) bank-conflict free.
+//  * K walked in steps of BK (32 or 64).  Tiles go from HBM/L2 straight into LDS with buffer loads
+//    that write LDS directly (no register staging, out-of-range rows read as zero), NST stages deep:
+//    the loads of steps t+1 .. t+NST-1 are in flight while step t is multiplied, which is what hides
+//    the ~1.5 us load latency (with two stages the loop ran at the latency, not at the MFMA rate).
+//    The wait for "step t has landed" is s_waitcnt vmcnt(loads of the younger steps), issued
+//    together with the workgroup barrier as inline assembly: a compiler-generated barrier would
+//    wait for vmcnt(0) and drain the pipeline.
+//  * LDS rows are BK bf16 without padding; the 16-byte chunk c of tile row r is stored at slot
+//    c ^ ((r >> 1) & 7) (128-byte rows) or c ^ ((r >> 2) & 3) (64-byte rows), which makes both the
+//    direct-to-LDS writes (1 KiB contiguous per wavefront instruction) and the MFMA operand reads
+//    (16 rows x same chunk) bank-conflict free.
 //  * Epilogue through LDS: each wavefront transposes 16 accumulator rows at a time so that a lane
 //    ends up with 4 consecutive columns (and the 4 columns 64 further on): stores and residual
 //    reads are 128-byte runs, and the two halves of a SwiGLU pair live in one lane.
@@ -45,118 +50,16 @@ __device__ __forceinline__ void load16_to_lds(__amdgpu_buffer_rsrc_t r, unsigned
     __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_void *)lds, 16, voff, 0, 0, 0);
 }
 
-template <int BM, int BN, int WM, int WN, bool SWIGLU>
-__global__ __launch_bounds__(WM *WN * 64) void gemm2_kernel(Gemm2Params p) {
-    constexpr int NW = WM * WN;
-    constexpr int WTM = BM / WM, WTN = BN / WN;
-    constexpr int TM = WTM / 16, TN = WTN / 16;
-    constexpr int A_INSTR = BM / 8 / NW, B_INSTR = BN / 8 / NW;     // direct-to-LDS instructions per wavefront
-    constexpr int A_BYTES = BM * 128, STAGE_BYTES = (BM + BN) * 128;
-    constexpr int STG_LD = WTN + 4;                                // epilogue staging row (floats)
-    static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "tile rows must split over the wavefronts");
-    static_assert(WTN == 64 || WTN == 128, "epilogue assumes 64 or 128 columns per wavefront");
-    static_assert(!SWIGLU || WTN == 128, "swiglu pairs gate and up 64 columns apart");
-    static_assert(NW * 16 * STG_LD * 4 <= 2 * STAGE_BYTES, "epilogue staging must fit in the tile buffers");
-
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm0 = (wave / WN) * WTM, wn0 = (wave % WN) * WTN;
-
-    // workgroup -> tile: contiguous run of tiles (m fastest) per XCD
-    const int total = p.tiles_m * p.tiles_n;
-    int tile;
-    {
-        const int pid = blockIdx.x, xcd = pid & 7, idx = pid >> 3;
-        const int base = total >> 3, rem = total & 7;
-        tile = xcd * base + min(xcd, rem) + idx;
-    }
-    const int tile_m = tile % p.tiles_m, tile_n = tile / p.tiles_m;
-    const int seg = tile_n >= p.seg_tile0[2] ? 2 : tile_n >= p.seg_tile0[1] ? 1 : 0;
-    const int m0 = tile_m * BM;
-    constexpr int BN_OUT = SWIGLU ? BN / 2 : BN;
-    const int nloc0 = (tile_n - p.seg_tile0[seg]) * BN_OUT;
-    const int seg_rows = p.seg_rows[seg];
-    const int K = p.K;
-
-    const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(p.X), 0, p.x_bytes, 0x00020000);
-    const uint32_t w_bytes = (uint32_t)((int64_t)seg_rows * K * 2);
-    const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(p.W[seg]), 0, w_bytes, 0x00020000);
-    const __amdgpu_buffer_rsrc_t ru =
-        __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(SWIGLU ? p.Wup : p.W[seg]), 0, w_bytes, 0x00020000);
-
-    // ---- per-lane global offsets of the direct-to-LDS loads.  Instruction i of this wavefront fills
-    // tile rows wave*(rows/NW) + 8i .. +7: lane -> row lane/8, LDS slot lane%8, which must hold the
-    // logical chunk slot ^ ((row >> 1) & 7).
-    uint32_t a_off[A_INSTR], b_off[B_INSTR];
-#pragma unroll
-    for (int i = 0; i < A_INSTR; ++i) {
-        const int row = wave * (BM / NW) + 8 * i + (lane >> 3);
-        const int c = (lane & 7) ^ ((row >> 1) & 7);
-        const int gm = m0 + row;
-        a_off[i] = gm < p.M ? (uint32_t)(map_row(p.xmap, p.seq_len, gm) * p.ldx * 2) + c * 16 : OOB_OFF;
-    }
-#pragma unroll
-    for (int i = 0; i < B_INSTR; ++i) {
-        const int row = wave * (BN / NW) + 8 * i + (lane >> 3);
-        const int c = (lane & 7) ^ ((row >> 1) & 7);
-        int col;
-        if (SWIGLU) col = nloc0 + (row / WTN) * (WTN / 2) + (row % (WTN / 2));
-        else col = nloc0 + row;
-        b_off[i] = col < seg_rows ? (uint32_t)((int64_t)col * K * 2) + c * 16 : OOB_OFF;
-    }
-
-    auto issue_loads = [&](int kt, int stage) {
-        const uint32_t kb = (uint32_t)kt * 128;
-        unsigned char *sa = smem + stage * STAGE_BYTES + wave * (BM / NW) * 128;
-        unsigned char *sb = smem + stage * STAGE_BYTES + A_BYTES + wave * (BN / NW) * 128;
-#pragma unroll
-        for (int i = 0; i < A_INSTR; ++i)
-            load16_to_lds(rx, sa + i * 1024, a_off[i] + kb);
-#pragma unroll
-        for (int i = 0; i < B_INSTR; ++i) {
-            const int row0 = wave * (BN / NW) + 8 * i;                      // wavefront-uniform
-            const bool up = SWIGLU && ((row0 % WTN) >= WTN / 2);
-            if (up) load16_to_lds(ru, sb + i * 1024, b_off[i] + kb);
-            else load16_to_lds(rw, sb + i * 1024, b_off[i] + kb);
-        }
-    };
-
-    f32x4 acc[TM][TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-    // operand fetch: lane -> tile row lane%16 of a 16-row block, chunk 4 ks + lane/16, swizzled
-    const int frow = lane & 15, fch = lane >> 4, fsw = (lane & 15) >> 1;
-    const int a_lane = (wm0 + frow) * 128, b_lane = A_BYTES + (wn0 + frow) * 128;
-    const int KT = K / 64;
-    issue_loads(0, 0);
-    for (int kt = 0; kt < KT; ++kt) {
-        __syncthreads();                                   // tile kt has landed; stage (kt+1)&1 is free
-        if (kt + 1 < KT) issue_loads(kt + 1, (kt + 1) & 1);
-        const unsigned char *st = smem + (kt & 1) * STAGE_BYTES;
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-            const int coff = ((4 * ks + fch) ^ fsw) * 16;
-            bf16x8 af[TM], bfr[TN];
-#pragma unroll
-            for (int i = 0; i < TM; ++i) af[i] = *(const bf16x8 *)(st + a_lane + i * 16 * 128 + coff);
-#pragma unroll
-            for (int j = 0; j < TN; ++j) bfr[j] = *(const bf16x8 *)(st + b_lane + j * 16 * 128 + coff);
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
-        }
-    }
-
+// Epilogue shared by the shard-GEMM kernels.  acc[i][j][r] holds row 16i + 4(lane/16) + r, column
+// 16j + lane%16 of the wavefront's WTM x WTN tile.  The caller guarantees that every wavefront of the
+// workgroup is done with the tile buffers (smem is reused as staging).
+template <int TM, int TN, int WTN, bool SWIGLU>
+__device__ __forceinline__ void gemm_epilogue(const Gemm2Params &p, f32x4 (&acc)[TM][TN], unsigned char *smem,
+                                              int wave, int lane, int m0, int wm0, int wn0, int nloc0, int seg,
+                                              int seg_rows) {
+    constexpr int STG_LD = WTN + 4;
     // ---- epilogue.  acc[i][j][r]: row 16i + 4(lane/16) + r, column 16j + lane%16 of the wavefront tile.
     const int flags = p.flags;
-    __syncthreads();                                       // everyone is done with the tile buffers
     float *stg = (float *)smem + wave * 16 * STG_LD;
     const int m4 = (lane & 15) * 4, rsel = lane >> 4;
     constexpr int NCH = WTN / 64;                          // 4-column chunks per lane: columns 64 cc + m4
@@ -220,7 +123,307 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm2_kernel(Gemm2Params p) {
     }
 }
 
-template <int BM, int BN, int WM, int WN, bool SWIGLU>
+template <int N>
+__device__ __forceinline__ void wait_loads_and_barrier() {
+    // all but the N youngest vector-memory operations of this wavefront are complete, then barrier
+    asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(N) : "memory");
+}
+
+template <int BM, int BN, int WM, int WN, int BK, int NST, bool SWIGLU>
+__global__ __launch_bounds__(WM *WN * 64) void gemm2_kernel(Gemm2Params p) {
+    constexpr int NW = WM * WN;
+    constexpr int WTM = BM / WM, WTN = BN / WN;
+    constexpr int TM = WTM / 16, TN = WTN / 16;
+    constexpr int ROWB = BK * 2;                                   // bytes per tile row in LDS
+    constexpr int RPI = 1024 / ROWB;                               // tile rows per direct-to-LDS instruction
+    constexpr int CPR = ROWB / 16;                                 // 16-byte chunks per row
+    constexpr int A_INSTR = BM / RPI / NW, B_INSTR = BN / RPI / NW; // direct-to-LDS instructions per wavefront
+    constexpr int LPT = A_INSTR + B_INSTR;                         // loads per tile per wavefront
+    constexpr int A_BYTES = BM * ROWB, STAGE_BYTES = (BM + BN) * ROWB;
+    constexpr int STG_LD = WTN + 4;                                // epilogue staging row (floats)
+    static_assert(BK == 32 || BK == 64, "BK");
+    static_assert(NST >= 2 && NST <= 4 && (NST - 2) * LPT < 64, "pipeline depth");
+    static_assert(BM % (RPI * NW) == 0 && BN % (RPI * NW) == 0, "tile rows must split over the wavefronts");
+    static_assert(WTN == 64 || WTN == 128, "epilogue assumes 64 or 128 columns per wavefront");
+    static_assert(!SWIGLU || WTN == 128, "swiglu pairs gate and up 64 columns apart");
+    static_assert(!SWIGLU || (WTN / 2) % RPI == 0, "a load instruction must not straddle gate / up rows");
+    static_assert(NW * 16 * STG_LD * 4 <= NST * STAGE_BYTES, "epilogue staging must fit in the tile buffers");
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm0 = (wave / WN) * WTM, wn0 = (wave % WN) * WTN;
+
+    // workgroup -> tile: contiguous run of tiles (m fastest) per XCD
+    const int total = p.tiles_m * p.tiles_n;
+    int tile;
+    {
+        const int pid = blockIdx.x, xcd = pid & 7, idx = pid >> 3;
+        const int base = total >> 3, rem = total & 7;
+        tile = xcd * base + min(xcd, rem) + idx;
+    }
+    const int tile_m = tile % p.tiles_m, tile_n = tile / p.tiles_m;
+    const int seg = tile_n >= p.seg_tile0[2] ? 2 : tile_n >= p.seg_tile0[1] ? 1 : 0;
+    const int m0 = tile_m * BM;
+    constexpr int BN_OUT = SWIGLU ? BN / 2 : BN;
+    const int nloc0 = (tile_n - p.seg_tile0[seg]) * BN_OUT;
+    const int seg_rows = p.seg_rows[seg];
+    const int K = p.K;
+
+    const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(p.X), 0, p.x_bytes, 0x00020000);
+    const uint32_t w_bytes = (uint32_t)((int64_t)seg_rows * K * 2);
+    const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(p.W[seg]), 0, w_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t ru =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(SWIGLU ? p.Wup : p.W[seg]), 0, w_bytes, 0x00020000);
+
+    // ---- per-lane global offsets of the direct-to-LDS loads.  Instruction i of this wavefront fills
+    // tile rows wave*(rows/NW) + RPI*i .. : lane -> row lane/CPR, LDS slot lane%CPR, which must hold the
+    // logical chunk slot ^ swizzle(row).
+    auto swz = [](int row) { return BK == 64 ? ((row >> 1) & 7) : ((row >> 2) & 3); };
+    uint32_t a_off[A_INSTR], b_off[B_INSTR];
+#pragma unroll
+    for (int i = 0; i < A_INSTR; ++i) {
+        const int row = wave * (BM / NW) + RPI * i + lane / CPR;
+        const int c = (lane % CPR) ^ swz(row);
+        const int gm = m0 + row;
+        a_off[i] = gm < p.M ? (uint32_t)(map_row(p.xmap, p.seq_len, gm) * p.ldx * 2) + c * 16 : OOB_OFF;
+    }
+#pragma unroll
+    for (int i = 0; i < B_INSTR; ++i) {
+        const int row = wave * (BN / NW) + RPI * i + lane / CPR;
+        const int c = (lane % CPR) ^ swz(row);
+        int col;
+        if (SWIGLU) col = nloc0 + (row / WTN) * (WTN / 2) + (row % (WTN / 2));
+        else col = nloc0 + row;
+        b_off[i] = col < seg_rows ? (uint32_t)((int64_t)col * K * 2) + c * 16 : OOB_OFF;
+    }
+
+    auto issue_loads = [&](int kt, int stage) {
+        const uint32_t kb = (uint32_t)kt * ROWB;
+        unsigned char *sa = smem + stage * STAGE_BYTES + wave * (BM / NW) * ROWB;
+        unsigned char *sb = smem + stage * STAGE_BYTES + A_BYTES + wave * (BN / NW) * ROWB;
+#pragma unroll
+        for (int i = 0; i < A_INSTR; ++i)
+            load16_to_lds(rx, sa + i * 1024, a_off[i] + kb);
+#pragma unroll
+        for (int i = 0; i < B_INSTR; ++i) {
+            const int row0 = wave * (BN / NW) + RPI * i;                    // wavefront-uniform
+            const bool up = SWIGLU && ((row0 % WTN) >= WTN / 2);
+            if (up) load16_to_lds(ru, sb + i * 1024, b_off[i] + kb);
+            else load16_to_lds(rw, sb + i * 1024, b_off[i] + kb);
+        }
+    };
+
+    f32x4 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    // operand fetch: lane -> tile row lane%16 of a 16-row block, chunk 4 ks + lane/16, swizzled
+    const int frow = lane & 15, fch = lane >> 4, fsw = swz(lane & 15);
+    const int a_lane = (wm0 + frow) * ROWB, b_lane = A_BYTES + (wn0 + frow) * ROWB;
+    const int KT = K / BK;
+#pragma unroll
+    for (int s = 0; s < NST - 1; ++s)
+        if (s < KT) issue_loads(s, s);
+    for (int kt = 0; kt < KT; ++kt) {
+        // tile kt has landed once at most the loads of the younger tiles in flight are outstanding;
+        // after the barrier every wavefront is done with tile kt-1, whose stage is refilled next
+        const int younger = min(NST - 2, KT - 1 - kt);
+        if (younger >= 2) wait_loads_and_barrier<2 * LPT>();
+        else if (younger == 1) wait_loads_and_barrier<LPT>();
+        else wait_loads_and_barrier<0>();
+        if (kt + NST - 1 < KT) issue_loads(kt + NST - 1, (kt + NST - 1) % NST);
+        const unsigned char *st = smem + (kt % NST) * STAGE_BYTES;
+#pragma unroll
+        for (int ks = 0; ks < BK / 32; ++ks) {
+            const int coff = ((4 * ks + fch) ^ fsw) * 16;
+            bf16x8 af[TM], bfr[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) af[i] = *(const bf16x8 *)(st + a_lane + i * 16 * ROWB + coff);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) bfr[j] = *(const bf16x8 *)(st + b_lane + j * 16 * ROWB + coff);
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+        }
+    }
+
+    __syncthreads();                                       // everyone is done with the tile buffers
+    gemm_epilogue<TM, TN, WTN, SWIGLU>(p, acc, smem, wave, lane, m0, wm0, wn0, nloc0, seg, seg_rows);
+}
+
+// ---------------------------------------------------------------------------- ping-pong variant
+// Same tiles, loads, swizzle and epilogue as gemm2_kernel, different schedule.  The 8 wavefronts form
+// two groups of 4 (one wavefront of each group per SIMD).  Every K tile is handled in two phases
+// separated by workgroup barriers: a MEMORY phase (issue the direct-to-LDS loads of a tile NST-1
+// ahead, read this tile's MFMA operands from LDS into registers) and a COMPUTE phase (nothing but
+// MFMAs).  Group 1 runs one phase behind group 0, so on every SIMD one wavefront is always in its
+// compute phase: the matrix pipe never waits for LDS latency or for a barrier bubble.
+template <int VM, bool LGKM>
+__device__ __forceinline__ void phase_barrier() {
+    __builtin_amdgcn_sched_barrier(0);
+    if (VM >= 0 && LGKM) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(VM < 0 ? 0 : VM) : "memory");
+    else if (VM >= 0) asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(VM < 0 ? 0 : VM) : "memory");
+    else if (LGKM) asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    else asm volatile("s_barrier" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+}
+
+template <int BM, int BN, int WM, int WN, int BK, int NST, bool SWIGLU>
+__global__ __launch_bounds__(WM *WN * 64) void gemm3_kernel(Gemm2Params p) {
+    constexpr int NW = WM * WN;
+    static_assert(NW == 8, "two groups of four wavefronts");
+    constexpr int WTM = BM / WM, WTN = BN / WN;
+    constexpr int TM = WTM / 16, TN = WTN / 16;
+    constexpr int ROWB = BK * 2, RPI = 1024 / ROWB, CPR = ROWB / 16, KS = BK / 32;
+    constexpr int A_INSTR = BM / RPI / NW, B_INSTR = BN / RPI / NW;
+    constexpr int LPT = A_INSTR + B_INSTR;
+    constexpr int A_BYTES = BM * ROWB, STAGE_BYTES = (BM + BN) * ROWB;
+    static_assert(BK == 32 || BK == 64, "BK");
+    static_assert(NST >= 3 && NST <= 5 && (NST - 2) * LPT < 64, "pipeline depth");
+    static_assert(BM % (RPI * NW) == 0 && BN % (RPI * NW) == 0, "tile rows must split over the wavefronts");
+    static_assert(WTN == 64 || WTN == 128, "epilogue assumes 64 or 128 columns per wavefront");
+    static_assert(!SWIGLU || (WTN == 128 && (WTN / 2) % RPI == 0), "swiglu layout");
+    static_assert(NW * 16 * (WTN + 4) * 4 <= NST * STAGE_BYTES, "epilogue staging must fit in the tile buffers");
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int group = wave >> 2;                                   // wavefronts w and w+4 share a SIMD
+    const int wm0 = (wave / WN) * WTM, wn0 = (wave % WN) * WTN;
+
+    const int total = p.tiles_m * p.tiles_n;
+    int tile;
+    {
+        const int pid = blockIdx.x, xcd = pid & 7, idx = pid >> 3;
+        const int base = total >> 3, rem = total & 7;
+        tile = xcd * base + min(xcd, rem) + idx;
+    }
+    const int tile_m = tile % p.tiles_m, tile_n = tile / p.tiles_m;
+    const int seg = tile_n >= p.seg_tile0[2] ? 2 : tile_n >= p.seg_tile0[1] ? 1 : 0;
+    const int m0 = tile_m * BM;
+    constexpr int BN_OUT = SWIGLU ? BN / 2 : BN;
+    const int nloc0 = (tile_n - p.seg_tile0[seg]) * BN_OUT;
+    const int seg_rows = p.seg_rows[seg];
+    const int K = p.K;
+
+    const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(p.X), 0, p.x_bytes, 0x00020000);
+    const uint32_t w_bytes = (uint32_t)((int64_t)seg_rows * K * 2);
+    const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(p.W[seg]), 0, w_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t ru =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(SWIGLU ? p.Wup : p.W[seg]), 0, w_bytes, 0x00020000);
+
+    auto swz = [](int row) { return BK == 64 ? ((row >> 1) & 7) : ((row >> 2) & 3); };
+    uint32_t a_off[A_INSTR], b_off[B_INSTR];
+#pragma unroll
+    for (int i = 0; i < A_INSTR; ++i) {
+        const int row = wave * (BM / NW) + RPI * i + lane / CPR;
+        const int c = (lane % CPR) ^ swz(row);
+        const int gm = m0 + row;
+        a_off[i] = gm < p.M ? (uint32_t)(map_row(p.xmap, p.seq_len, gm) * p.ldx * 2) + c * 16 : OOB_OFF;
+    }
+#pragma unroll
+    for (int i = 0; i < B_INSTR; ++i) {
+        const int row = wave * (BN / NW) + RPI * i + lane / CPR;
+        const int c = (lane % CPR) ^ swz(row);
+        int col;
+        if (SWIGLU) col = nloc0 + (row / WTN) * (WTN / 2) + (row % (WTN / 2));
+        else col = nloc0 + row;
+        b_off[i] = col < seg_rows ? (uint32_t)((int64_t)col * K * 2) + c * 16 : OOB_OFF;
+    }
+    auto issue_loads = [&](int kt) {
+        const int stage = kt % NST;
+        const uint32_t kb = (uint32_t)kt * ROWB;
+        unsigned char *sa = smem + stage * STAGE_BYTES + wave * (BM / NW) * ROWB;
+        unsigned char *sb = smem + stage * STAGE_BYTES + A_BYTES + wave * (BN / NW) * ROWB;
+#pragma unroll
+        for (int i = 0; i < A_INSTR; ++i) load16_to_lds(rx, sa + i * 1024, a_off[i] + kb);
+#pragma unroll
+        for (int i = 0; i < B_INSTR; ++i) {
+            const int row0 = wave * (BN / NW) + RPI * i;
+            const bool up = SWIGLU && ((row0 % WTN) >= WTN / 2);
+            if (up) load16_to_lds(ru, sb + i * 1024, b_off[i] + kb);
+            else load16_to_lds(rw, sb + i * 1024, b_off[i] + kb);
+        }
+    };
+
+    f32x4 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    const int frow = lane & 15, fch = lane >> 4, fsw = swz(lane & 15);
+    const int a_lane = (wm0 + frow) * ROWB, b_lane = A_BYTES + (wn0 + frow) * ROWB;
+    const int KT = K / BK;
+
+    // Barrier bookkeeping.  Global barrier 2t ends group 0's memory phase of tile t and group 1's
+    // compute phase of tile t-1; barrier 2t+1 ends group 0's compute phase and group 1's memory phase of
+    // tile t, and is the one before which every wavefront makes sure its own loads of tile t+1 have
+    // landed (so the tile is complete when group 0 starts reading it).
+    // "tile t+1 landed" = at most the loads of the younger tiles t+2 .. min(KT-1, t+NST-1) outstanding.
+#define WAIT_NEXT_TILE_AND_BARRIER(t, LG)                                    \
+    do {                                                                     \
+        const int younger = max(0, min(NST - 2, KT - 2 - (t)));              \
+        if (younger >= 3) phase_barrier<3 * LPT, LG>();                      \
+        else if (younger == 2) phase_barrier<2 * LPT, LG>();                 \
+        else if (younger == 1) phase_barrier<LPT, LG>();                     \
+        else phase_barrier<0, LG>();                                         \
+    } while (0)
+
+#pragma unroll
+    for (int s = 0; s < NST - 1; ++s)
+        if (s < KT) issue_loads(s);
+    {   // tile 0 complete and visible to everyone
+        const int younger = max(0, min(NST - 2, KT - 1));
+        if (younger >= 3) phase_barrier<3 * LPT, false>();
+        else if (younger == 2) phase_barrier<2 * LPT, false>();
+        else if (younger == 1) phase_barrier<LPT, false>();
+        else phase_barrier<0, false>();
+    }
+    if (group == 1) phase_barrier<-1, false>();                    // run one phase behind group 0
+
+    for (int kt = 0; kt < KT; ++kt) {
+        // ---- memory phase: refill the stage of tile kt-1 (everyone finished reading it one barrier
+        // ago), fetch this tile's operands
+        if (kt + NST - 1 < KT) issue_loads(kt + NST - 1);
+        const unsigned char *st = smem + (kt % NST) * STAGE_BYTES;
+        bf16x8 af[KS][TM], bfr[KS][TN];
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const int coff = ((4 * ks + fch) ^ fsw) * 16;
+#pragma unroll
+            for (int i = 0; i < TM; ++i) af[ks][i] = *(const bf16x8 *)(st + a_lane + i * 16 * ROWB + coff);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) bfr[ks][j] = *(const bf16x8 *)(st + b_lane + j * 16 * ROWB + coff);
+        }
+        if (group == 1) WAIT_NEXT_TILE_AND_BARRIER(kt, true);
+        else phase_barrier<-1, true>();
+        // ---- compute phase
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[ks][i], bfr[ks][j], acc[i][j], 0, 0, 0);
+        if (group == 0) WAIT_NEXT_TILE_AND_BARRIER(kt, false);
+        else phase_barrier<-1, false>();
+    }
+#undef WAIT_NEXT_TILE_AND_BARRIER
+    if (group == 0) phase_barrier<-1, false>();                    // group 1 is one barrier ahead in count
+
+    __syncthreads();
+    gemm_epilogue<TM, TN, WTN, SWIGLU>(p, acc, smem, wave, lane, m0, wm0, wn0, nloc0, seg, seg_rows);
+}
+
+template <int BM, int BN, int WM, int WN, int BK, int NST, bool SWIGLU, bool PINGPONG = false>
 static int32_t launch_cfg2(const GemmArgs &a, hipStream_t s) {
     Gemm2Params p;
     constexpr int BN_OUT = SWIGLU ? BN / 2 : BN;
@@ -249,30 +452,46 @@ static int32_t launch_cfg2(const GemmArgs &a, hipStream_t s) {
     int64_t xb = (int64_t)a.M * a.ldx * 2;
     if (xb >= (int64_t)OOB_OFF) return CASCADE_EUNSUPPORTED;
     p.x_bytes = (uint32_t)xb;
-    constexpr size_t lds = (size_t)2 * (BM + BN) * 128;
-    auto kern = gemm2_kernel<BM, BN, WM, WN, SWIGLU>;
+    constexpr size_t lds = (size_t)NST * (BM + BN) * BK * 2;
+    static_assert(lds <= 160 * 1024, "tile buffers exceed the LDS of a CU");
+    const void *kern;
+    if constexpr (PINGPONG) kern = (const void *)gemm3_kernel<BM, BN, WM, WN, BK, NST, SWIGLU>;
+    else kern = (const void *)gemm2_kernel<BM, BN, WM, WN, BK, NST, SWIGLU>;
     static bool attr_set = false;
     if (!attr_set) {
-        CASCADE_HIP_TRY(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        CASCADE_HIP_TRY(hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         attr_set = true;
     }
     int64_t total = (int64_t)p.tiles_m * p.tiles_n;
     if (total > INT32_MAX) return CASCADE_EUNSUPPORTED;
-    hipLaunchKernelGGL(kern, dim3((unsigned)total), dim3(WM * WN * 64), lds, s, p);
+    void *args[] = {&p};
+    CASCADE_HIP_TRY(hipLaunchKernel(kern, dim3((unsigned)total), dim3(WM * WN * 64), args, lds, s));
     CASCADE_HIP_TRY(hipGetLastError());
     return CASCADE_OK;
 }
 
 // Returns CASCADE_EUNSUPPORTED when the shape is not eligible (the caller then uses the general kernel).
 int32_t launch_gemm_bf16_v2(const GemmArgs &a, hipStream_t s) {
-    if (a.K % 64 != 0 || a.ldx % 8 != 0 || a.ldy % 4 != 0 || ((a.epilogue & CASCADE_EPI_RESIDUAL) && a.ldres % 4 != 0))
+    if (a.K % 64 != 0 || a.K < 64 || a.ldx % 8 != 0 || a.ldy % 4 != 0 || ((a.epilogue & CASCADE_EPI_RESIDUAL) && a.ldres % 4 != 0))
         return CASCADE_EUNSUPPORTED;
     if (((uintptr_t)a.Y | (uintptr_t)a.residual) % 8) return CASCADE_EUNSUPPORTED;
     for (int i = 0; i < 3; ++i)
         if (a.seg_end[i] % 4) return CASCADE_EUNSUPPORTED;          // 4-column store chunks stay inside a segment
     const bool swiglu = a.epilogue & CASCADE_EPI_SWIGLU;
-    if (swiglu) return launch_cfg2<256, 256, 4, 2, true>(a, s);
+    const char *v = getenv("CASCADE_GEMM_CFG");                    // tuning aid: 0 = default
+    const int cfg = v ? atoi(v) : 0;
+    if (swiglu) {
+        if (cfg == 1) return launch_cfg2<256, 256, 4, 2, 64, 2, true>(a, s);
+        if (cfg == 2) return launch_cfg2<256, 256, 4, 2, 32, 5, true, true>(a, s);
+        return launch_cfg2<256, 256, 4, 2, 32, 4, true, true>(a, s);
+    }
     const int64_t big_tiles = (int64_t)((a.M + 255) / 256) * ((a.N + 255) / 256);
-    if (big_tiles >= 160) return launch_cfg2<256, 256, 4, 2, false>(a, s);
-    return launch_cfg2<256, 128, 4, 2, false>(a, s);
+    if (big_tiles >= 160) {
+        if (cfg == 1) return launch_cfg2<256, 256, 4, 2, 64, 2, false>(a, s);
+        if (cfg == 2) return launch_cfg2<256, 256, 4, 2, 32, 5, false, true>(a, s);
+        return launch_cfg2<256, 256, 4, 2, 32, 4, false, true>(a, s);
+    }
+    if (cfg == 1) return launch_cfg2<256, 128, 4, 2, 64, 3, false>(a, s);
+    if (cfg == 2) return launch_cfg2<256, 128, 4, 2, 32, 5, false, true>(a, s);
+    return launch_cfg2<256, 128, 4, 2, 64, 3, false, true>(a, s);
 }
