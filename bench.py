@@ -43,7 +43,10 @@ def device_inputs(cfg, seed):
     def normal(shape, std):
         return (torch.randn(shape, device="cuda", generator=g, dtype=torch.float32) * std).to(tdt)
 
-    w = {"wq": normal((H * d, D), s), "wk": normal((Hkv * d, D), s), "wv": normal((Hkv * d, D), s),
+    # q, k, v weights live in one [(H + 2 H_KV) d, D] allocation (the usual fused layout); the library is
+    # handed the three views and recognises that they are contiguous
+    wqkv = normal(((H + 2 * Hkv) * d, D), s)
+    w = {"wq": wqkv[:H * d], "wk": wqkv[H * d:(H + Hkv) * d], "wv": wqkv[(H + Hkv) * d:],
          "wo": normal((D, H * d), s), "w_up": normal((f, D), s), "w_down": normal((D, f), s),
          "norm1_g": (1.0 + normal((D,), s).float()).to(tdt), "norm2_g": (1.0 + normal((D,), s).float()).to(tdt)}
     if cfg.act == "swiglu":
@@ -51,7 +54,8 @@ def device_inputs(cfg, seed):
     if cfg.norm == "layernorm":
         w["norm1_b"], w["norm2_b"] = normal((D,), s), normal((D,), s)
     if cfg.bias:
-        w.update(bq=normal((H * d,), s), bk=normal((Hkv * d,), s), bv=normal((Hkv * d,), s), bo=normal((D,), s),
+        bqkv = normal(((H + 2 * Hkv) * d,), s)
+        w.update(bq=bqkv[:H * d], bk=bqkv[H * d:(H + Hkv) * d], bv=bqkv[(H + Hkv) * d:], bo=normal((D,), s),
                  b_up=normal((f,), s), b_down=normal((D,), s))
     h = normal((cfg.batch, cfg.seq_len, D), 1.0)
     return w, h

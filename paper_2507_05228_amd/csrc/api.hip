@@ -238,6 +238,15 @@ static int32_t layer_forward_impl(const cascade_plan *plan, const cascade_layer_
     g.W[0] = w->wq; g.W[1] = w->wk; g.W[2] = w->wv;
     g.seg_end[0] = H * hd; g.seg_end[1] = (H + Hkv) * hd; g.seg_end[2] = QW;
     g.bias[0] = w->bq; g.bias[1] = w->bk; g.bias[2] = w->bv;
+    {   // q, k, v weights stored back to back (a fused [QW, D] matrix) are one segment: tiles may then
+        // straddle the q | k | v boundaries, which lets the tile width be chosen freely
+        const char *q0 = (const char *)w->wq, *k0 = (const char *)w->wk, *v0 = (const char *)w->wv;
+        const bool w_contig = k0 == q0 + (size_t)H * hd * D * es && v0 == k0 + (size_t)Hkv * hd * D * es;
+        const char *bq = (const char *)w->bq, *bk = (const char *)w->bk, *bv = (const char *)w->bv;
+        const bool b_contig = (!bq && !bk && !bv) ||
+                              (bq && bk == bq + (size_t)H * hd * es && bv == bk + (size_t)Hkv * hd * es);
+        if (w_contig && b_contig) g.seg_end[0] = g.seg_end[1] = QW;
+    }
     g.epilogue = (w->bq || w->bk || w->bv) ? CASCADE_EPI_BIAS : 0;
     g.Y = qkv; g.ldx = D; g.ldy = QW; g.xmap = g.ymap = g.rmap = packed;
     if ((st = run_gemm(g, s)) != CASCADE_OK) return st;

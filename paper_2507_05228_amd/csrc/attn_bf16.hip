@@ -61,6 +61,19 @@ __device__ __forceinline__ float xor_sum_16_32(float v) {
     return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
+// Workgroup barrier as inline assembly, optionally preceded by "all but the VM youngest vector-memory
+// operations of this wavefront are complete" and "all LDS reads have returned".  (A compiler-generated
+// barrier waits for vmcnt(0) and would drain the tile pipeline.)
+template <int VM, bool LGKM>
+__device__ __forceinline__ void phase_barrier() {
+    __builtin_amdgcn_sched_barrier(0);
+    if (VM >= 0 && LGKM) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(VM < 0 ? 0 : VM) : "memory");
+    else if (VM >= 0) asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(VM < 0 ? 0 : VM) : "memory");
+    else if (LGKM) asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    else asm volatile("s_barrier" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+}
+
 struct AttnBf16Params {
     const bf16_t *q, *k, *vt;
     int64_t qs_b, qs_h, qs_n, ks_b, ks_h, ks_n, vts_b, vts_h;
@@ -173,6 +186,9 @@ __global__ __launch_bounds__(512) void attn_bf16_kernel(AttnBf16Params p) {
 #pragma unroll
     for (int qb = 0; qb < TQ; ++qb) qlim[qb] = p.causal ? posq[qb] : INT_MAX - 1;
     const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
+    // wavefront-level position bounds; without a causal mask nothing is skipped or compared by position
+    const int wq_hi = p.causal ? max(wq_max[0], wq_max[1]) : INT_MAX;
+    const int wq_lo = p.causal ? min(wq_min[0], wq_min[1]) : INT_MAX;
 
     // ---- key/value tile range
     const int t_begin = p.fused ? 0 : ((int_cptr)p.kv_shard_first)[kk];
@@ -216,7 +232,8 @@ __global__ __launch_bounds__(512) void attn_bf16_kernel(AttnBf16Params p) {
             const int c = (lane & 7) ^ ((rr >> 1) & 7);
             load16_to_lds(rv, sv + row0 * 128, (uint32_t)(((int64_t)rr * p.npad + (int64_t)t * KV_TILE) * 2) + c * 16);
         }
-        if (wave == 0) load4_to_lds(rp, sv + V_BYTES, lane < n_rows ? (uint32_t)(row_start + lane) * 4 : OOB_OFF);
+        // every wavefront writes the same 64 positions: keeps the loads-per-tile count uniform
+        load4_to_lds(rp, sv + V_BYTES, lane < n_rows ? (uint32_t)(row_start + lane) * 4 : OOB_OFF);
     };
 
     f32x4 oacc[TQ][DB];
@@ -233,50 +250,67 @@ __global__ __launch_bounds__(512) void attn_bf16_kernel(AttnBf16Params p) {
     const int k_swz = D == 128 ? l16 : (l16 >> 1);
     const int v_swz = l16 >> 1;
 
-    int t = next_tile(t_begin);
-    int stage = 0;
-    if (t < t_end) issue_loads(t, 0);
-    while (t < t_end) {
-        __syncthreads();                               // tile t has landed; the other stage is free
-        const tile_cptr ktp = kvtiles + t;
+    // ---- main loop, ping-pong schedule.  The 8 wavefronts form two groups of 4 (wavefronts w and
+    // w+4 share a SIMD).  Each visible tile i is handled in two phases separated by workgroup
+    // barriers:
+    //   X(i)  matrix phase : S^T(i) = K(i) Q^T  and  O^T += V^T(i-1) P^T(i-1)   (LDS reads + MFMAs)
+    //   Y(i)  vector phase : mask, row max, exponentials -> P(i); rescale O     (VALU only)
+    // Group 1 runs one phase behind group 0, so on each SIMD one wavefront is in a matrix phase while
+    // the other is in a vector phase.  The P V product trails by one tile, which is what lets a matrix
+    // phase be pure MFMA work.  Tiles are NST = 4 stages deep in LDS; the loads of tile i+2 are
+    // issued at the start of X(i) (its stage held tile i-2, whose V^T was last read in X(i-1), which
+    // both groups have left by then).  Before every odd global barrier (end of group 0's Y(i) and of
+    // group 1's X(i)) each wavefront waits for its own loads of tile i+1, so the tile is complete
+    // when group 0 enters X(i+1).
+    constexpr int NST = 4;
+    constexpr int LPT = K_INSTR + V_INSTR + 1;         // loads per tile per wavefront
+    const int group = wave >> 2;
+    int t0 = next_tile(t_begin);                       // tile i
+    int t1 = t0 < t_end ? next_tile(t0 + 1) : t_end;   // tile i+1
+    int t2 = t1 < t_end ? next_tile(t1 + 1) : t_end;   // tile i+2
+    if (t0 < t_end) issue_loads(t0, 0);
+    if (t1 < t_end) issue_loads(t1, 1);
+    if (t1 < t_end) phase_barrier<LPT, false>();       // tile 0 complete and visible
+    else phase_barrier<0, false>();
+    if (group == 1) phase_barrier<-1, false>();        // run one phase behind group 0
+
+    f32x4 sacc[TQ][4];
+    bf16x8 pf[TQ][2];                                  // P^T operands of the previous tile
+    bool pskip[2] = {true, true};                      // previous tile: both 16-key blocks of step s skipped
+    int prev_stage = 0;
+    bool have_prev = false;
+
+    for (int i = 0; t0 < t_end; ++i) {
+        const int stage = i % NST;
+        // ================= X(i): matrix phase
+        const tile_cptr ktp = kvtiles + t0;
         const int kn = ktp->n_rows;
         const unsigned char *sk = smem + stage * STAGE;
         const unsigned char *sv = sk + K_BYTES;
-        // key positions of this lane's accumulator rows (keys 16 kvb + 4 g4 + 0..3), read before the
-        // next tile's loads are issued so that nothing in flight can alias them
+        // per 16-key block: can this wavefront skip it / does it need the element-wise compare
+        int skipm = 0, maskm = 0;
+#pragma unroll
+        for (int kvb = 0; kvb < 4; ++kvb) {
+            const int kmin = ktp->sub_min[kvb], kmax = ktp->sub_max[kvb];
+            skipm |= (int)((kvb * 16 >= kn) | (kmin > wq_hi)) << kvb;
+            maskm |= (int)((kvb * 16 + 16 > kn) | (kmax > wq_lo)) << kvb;
+        }
+        // key positions of this lane's accumulator rows (keys 16 kvb + 4 g4 + 0..3)
         int pk[4][4];
 #pragma unroll
         for (int kvb = 0; kvb < 4; ++kvb) {
             const int4 v4 = *(const int4 *)(sv + V_BYTES + (kvb * 16 + 4 * g4) * 4);
             pk[kvb][0] = v4.x; pk[kvb][1] = v4.y; pk[kvb][2] = v4.z; pk[kvb][3] = v4.w;
         }
-        if (kn < KV_TILE) {                            // ragged tile: keys past its end are never visible
-#pragma unroll
-            for (int kvb = 0; kvb < 4; ++kvb)
-#pragma unroll
-                for (int r = 0; r < 4; ++r)
-                    if (kvb * 16 + 4 * g4 + r >= kn) pk[kvb][r] = INT_MAX;
-        }
-        const int tn = next_tile(t + 1);
-        if (tn < t_end) issue_loads(tn, stage ^ 1);
-
-        // Per-tile metadata (scalar): which 16-key blocks this wavefront can see at all, and which
-        // need the element-wise compare.  Decisions are per wavefront (both query blocks together) to
-        // keep the inner loops free of branches, so LDS reads can be issued ahead of the MFMAs.
-        bool skipk[4], maskk[4];
+        if (t2 < t_end) issue_loads(t2, (i + 2) % NST);        // after the position reads: nothing in flight aliases them
+        // S^T blocks: sacc[qb][kvb] = K[kvb] Q[qb]^T  (16 keys x 16 queries)
 #pragma unroll
         for (int kvb = 0; kvb < 4; ++kvb) {
-            const int kmin = ktp->sub_min[kvb], kmax = ktp->sub_max[kvb];
-            const int qmax = max(wq_max[0], wq_max[1]), qmin = min(wq_min[0], wq_min[1]);
-            skipk[kvb] = (kvb * 16 >= kn) || (p.causal && kmin > qmax);
-            maskk[kvb] = (kvb * 16 + 16 > kn) || (p.causal && kmax > qmin);
-        }
-
-        // ---- S^T blocks: sacc[qb][kvb] = K[kvb] Q[qb]^T  (16 keys x 16 queries)
-        f32x4 sacc[TQ][4];
+            if (skipm & (1 << kvb)) {                  // contributes exact zeros to P
 #pragma unroll
-        for (int kvb = 0; kvb < 4; ++kvb) {
-            if (skipk[kvb]) continue;
+                for (int qb = 0; qb < TQ; ++qb) sacc[qb][kvb] = zero4;
+                continue;
+            }
             const unsigned char *kp = sk + (kvb * 16 + l16) * K_ROW;
             bf16x8 kf[KS];
 #pragma unroll
@@ -289,26 +323,54 @@ __global__ __launch_bounds__(512) void attn_bf16_kernel(AttnBf16Params p) {
                     sacc[qb][kvb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[ks], qf[qb][ks], sacc[qb][kvb], 0, 0, 0);
             }
         }
+        // O^T += V^T(i-1) P^T(i-1).  Step s covers keys 32s..32s+31; k-slot (g4, j) of both operands is
+        // key 32s + 16(j/4) + 4 g4 + j%4, i.e. accumulator register j%4 of block 2s + j/4.
+        if (have_prev) {
+            const unsigned char *pv = smem + prev_stage * STAGE + K_BYTES + l16 * 128 + 8 * (g4 & 1);
+#pragma unroll
+            for (int s2 = 0; s2 < 2; ++s2) {
+                if (pskip[s2]) continue;
+                const int c_lo = ((4 * s2 + (g4 >> 1)) ^ v_swz) * 16, c_hi = ((4 * s2 + 2 + (g4 >> 1)) ^ v_swz) * 16;
+#pragma unroll
+                for (int db = 0; db < DB; ++db) {
+                    const bf16x4 lo = *(const bf16x4 *)(pv + db * 16 * 128 + c_lo);
+                    const bf16x4 hi = *(const bf16x4 *)(pv + db * 16 * 128 + c_hi);
+                    const bf16x8 vf = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+#pragma unroll
+                    for (int qb = 0; qb < TQ; ++qb)
+                        oacc[qb][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf[qb][s2], oacc[qb][db], 0, 0, 0);
+                }
+            }
+        }
+        if (group == 1) { if (t1 < t_end && t2 < t_end) phase_barrier<LPT, true>(); else phase_barrier<0, true>(); }
+        else phase_barrier<-1, true>();
 
-        // ---- mask.  sacc[qb][kvb][r]: key 16 kvb + 4 g4 + r, query l16.  With no causal mask the
-        // limit is INT_MAX - 1, so only the keys past a ragged tile's end (position INT_MAX) are cut.
+        // ================= Y(i): vector phase
+        if (kn < KV_TILE) {                            // ragged tile: keys past its end are never visible
+#pragma unroll
+            for (int kvb = 0; kvb < 4; ++kvb)
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    if (kvb * 16 + 4 * g4 + r >= kn) pk[kvb][r] = INT_MAX;
+        }
+        // mask.  sacc[qb][kvb][r]: key 16 kvb + 4 g4 + r, query l16.  With no causal mask the limit is
+        // INT_MAX - 1, so only the keys past a ragged tile's end (position INT_MAX) are cut.
 #pragma unroll
         for (int kvb = 0; kvb < 4; ++kvb) {
-            if (skipk[kvb] || !maskk[kvb]) continue;
+            if (!(maskm & ~skipm & (1 << kvb))) continue;
 #pragma unroll
             for (int qb = 0; qb < TQ; ++qb)
 #pragma unroll
                 for (int r = 0; r < 4; ++r)
                     if (pk[kvb][r] > qlim[qb]) sacc[qb][kvb][r] = -INFINITY;
         }
-
-        // ---- row statistics and exponentials
+        // row statistics, exponentials, rescale of the running output (Algorithm 4's n, w, o online)
 #pragma unroll
         for (int qb = 0; qb < TQ; ++qb) {
             float mx = -INFINITY;
 #pragma unroll
             for (int kvb = 0; kvb < 4; ++kvb)
-                if (!skipk[kvb])
+                if (!(skipm & (1 << kvb)))
 #pragma unroll
                     for (int r = 0; r < 4; ++r) mx = fmaxf(mx, sacc[qb][kvb][r]);
             mx = xor_max_16_32(mx);
@@ -319,7 +381,7 @@ __global__ __launch_bounds__(512) void attn_bf16_kernel(AttnBf16Params p) {
             float psum = 0.f;
 #pragma unroll
             for (int kvb = 0; kvb < 4; ++kvb) {
-                if (skipk[kvb]) continue;
+                if (skipm & (1 << kvb)) continue;
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     const float pv = __builtin_amdgcn_exp2f(fmaf(sacc[qb][kvb][r], p.scale_log2, -m_sub));
@@ -332,35 +394,41 @@ __global__ __launch_bounds__(512) void attn_bf16_kernel(AttnBf16Params p) {
 #pragma unroll
                 for (int db = 0; db < DB; ++db) oacc[qb][db] *= alpha;
             }
-        }
-
-        // ---- O^T += V^T P^T.  Step s covers keys 32s..32s+31; k-slot (g4, i) of both operands is key
-        // 32s + 16(i/4) + 4 g4 + i%4, i.e. accumulator register i%4 of block 2s + i/4.
 #pragma unroll
-        for (int s = 0; s < 2; ++s) {
-            if (skipk[2 * s] && skipk[2 * s + 1]) continue;
-            bf16x8 pf[TQ];
+            for (int s2 = 0; s2 < 2; ++s2)
 #pragma unroll
-            for (int qb = 0; qb < TQ; ++qb)
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    pf[qb][i] = skipk[2 * s] ? (bf16_t)0.f : (bf16_t)sacc[qb][2 * s][i];
-                    pf[qb][4 + i] = skipk[2 * s + 1] ? (bf16_t)0.f : (bf16_t)sacc[qb][2 * s + 1][i];
+                for (int j = 0; j < 4; ++j) {
+                    pf[qb][s2][j] = (bf16_t)sacc[qb][2 * s2][j];
+                    pf[qb][s2][4 + j] = (bf16_t)sacc[qb][2 * s2 + 1][j];
                 }
-            const unsigned char *vp = sv + l16 * 128 + 8 * (g4 & 1);
-            const int c_lo = ((4 * s + (g4 >> 1)) ^ v_swz) * 16, c_hi = ((4 * s + 2 + (g4 >> 1)) ^ v_swz) * 16;
+        }
+        pskip[0] = (skipm & 3) == 3;
+        pskip[1] = (skipm & 12) == 12;
+        prev_stage = stage;
+        have_prev = true;
+        if (group == 0) { if (t1 < t_end && t2 < t_end) phase_barrier<LPT, false>(); else phase_barrier<0, false>(); }
+        else phase_barrier<-1, false>();
+        t0 = t1; t1 = t2;
+        t2 = t1 < t_end ? next_tile(t1 + 1) : t_end;
+    }
+    if (group == 0) phase_barrier<-1, false>();        // both groups have now passed the same number of barriers
+    // the trailing P V product of the last tile
+    if (have_prev) {
+        const unsigned char *pv = smem + prev_stage * STAGE + K_BYTES + l16 * 128 + 8 * (g4 & 1);
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) {
+            if (pskip[s2]) continue;
+            const int c_lo = ((4 * s2 + (g4 >> 1)) ^ v_swz) * 16, c_hi = ((4 * s2 + 2 + (g4 >> 1)) ^ v_swz) * 16;
 #pragma unroll
             for (int db = 0; db < DB; ++db) {
-                const bf16x4 lo = *(const bf16x4 *)(vp + db * 16 * 128 + c_lo);
-                const bf16x4 hi = *(const bf16x4 *)(vp + db * 16 * 128 + c_hi);
+                const bf16x4 lo = *(const bf16x4 *)(pv + db * 16 * 128 + c_lo);
+                const bf16x4 hi = *(const bf16x4 *)(pv + db * 16 * 128 + c_hi);
                 const bf16x8 vf = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
 #pragma unroll
                 for (int qb = 0; qb < TQ; ++qb)
-                    oacc[qb][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf[qb], oacc[qb][db], 0, 0, 0);
+                    oacc[qb][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf[qb][s2], oacc[qb][db], 0, 0, 0);
             }
         }
-        stage ^= 1;
-        t = tn;
     }
 
     // ---- write-out.  oacc[qb][db][r]: query row 16qb + l16, column 16db + 4 g4 + r.
@@ -432,7 +500,7 @@ static int32_t launch_attn_cfg(const cascade_plan *p, const AttnArgs &a, hipStre
     k.m = a.m; k.e = a.e; k.u = a.u; k.o = (bf16_t *)a.o; k.o_ld = a.o_ld; k.o_rowmap = a.o_rowmap;
     k.hpb = hpb;
 
-    constexpr int lds = 2 * (KV_TILE * D * 2 + D * 128 + KV_TILE * 4);
+    constexpr int lds = 4 * (KV_TILE * D * 2 + D * 128 + KV_TILE * 4);
     auto kern = attn_bf16_kernel<D>;
     static bool attr_set = false;
     if (!attr_set) {

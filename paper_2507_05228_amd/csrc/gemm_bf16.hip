@@ -251,7 +251,7 @@ int32_t launch_gemm_bf16_v2(const GemmArgs &a, hipStream_t s);
 
 int32_t launch_gemm_bf16(const GemmArgs &a, hipStream_t s) {
     if (a.M == 0 || a.N == 0) return CASCADE_OK;
-    if (!getenv("CASCADE_GEMM_V1")) {
+    {   // the main kernels take K % 64 == 0; everything else falls through to the general kernel below
         int32_t st = launch_gemm_bf16_v2(a, s);
         if (st != CASCADE_EUNSUPPORTED) return st;
     }

@@ -62,7 +62,7 @@ __device__ __forceinline__ void gemm_epilogue(const Gemm2Params &p, f32x4 (&acc)
     const int flags = p.flags;
     float *stg = (float *)smem + wave * 16 * STG_LD;
     const int m4 = (lane & 15) * 4, rsel = lane >> 4;
-    constexpr int NCH = WTN / 64;                          // 4-column chunks per lane: columns 64 cc + m4
+    constexpr int NCH = (WTN + 63) / 64;                   // 4-column chunks per lane: columns 64 cc + m4
     constexpr int NCH_OUT = SWIGLU ? 1 : NCH;
     const int wcol0 = SWIGLU ? nloc0 + (wn0 / WTN) * (WTN / 2) : nloc0 + wn0;   // first output column (in segment)
     const int gcol0 = p.seg_col0[seg];
@@ -94,10 +94,10 @@ __device__ __forceinline__ void gemm_epilogue(const Gemm2Params &p, f32x4 (&acc)
 #pragma unroll
                 for (int cc = 0; cc < NCH_OUT; ++cc) {
                     const int c = wcol0 + 64 * cc + m4;
-                    if (c >= seg_rows) continue;
+                    if (c >= seg_rows || 64 * cc + m4 >= (SWIGLU ? WTN / 2 : WTN)) continue;
                     f32x4 v = *(const f32x4 *)(stg + rl * STG_LD + 64 * cc + m4) + bias_v[cc];
                     if (SWIGLU) {
-                        const f32x4 up = *(const f32x4 *)(stg + rl * STG_LD + 64 + m4);
+                        const f32x4 up = *(const f32x4 *)(stg + rl * STG_LD + WTN / 2 + m4);
 #pragma unroll
                         for (int x = 0; x < 4; ++x) v[x] = silu_f(v[x]) * up[x];
                     } else if (flags & (CASCADE_EPI_GELU_ERF | CASCADE_EPI_GELU_TANH)) {
@@ -137,16 +137,17 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm2_kernel(Gemm2Params p) {
     constexpr int ROWB = BK * 2;                                   // bytes per tile row in LDS
     constexpr int RPI = 1024 / ROWB;                               // tile rows per direct-to-LDS instruction
     constexpr int CPR = ROWB / 16;                                 // 16-byte chunks per row
-    constexpr int A_INSTR = BM / RPI / NW, B_INSTR = BN / RPI / NW; // direct-to-LDS instructions per wavefront
+    constexpr int BNP = (BN + RPI * NW - 1) / (RPI * NW) * (RPI * NW);   // B rows held in LDS (BN rounded up)
+    constexpr int A_INSTR = BM / RPI / NW, B_INSTR = BNP / RPI / NW;     // direct-to-LDS instructions per wavefront
     constexpr int LPT = A_INSTR + B_INSTR;                         // loads per tile per wavefront
-    constexpr int A_BYTES = BM * ROWB, STAGE_BYTES = (BM + BN) * ROWB;
+    constexpr int A_BYTES = BM * ROWB, STAGE_BYTES = (BM + BNP) * ROWB;
     constexpr int STG_LD = WTN + 4;                                // epilogue staging row (floats)
     static_assert(BK == 32 || BK == 64, "BK");
     static_assert(NST >= 2 && NST <= 4 && (NST - 2) * LPT < 64, "pipeline depth");
-    static_assert(BM % (RPI * NW) == 0 && BN % (RPI * NW) == 0, "tile rows must split over the wavefronts");
-    static_assert(WTN == 64 || WTN == 128, "epilogue assumes 64 or 128 columns per wavefront");
-    static_assert(!SWIGLU || WTN == 128, "swiglu pairs gate and up 64 columns apart");
-    static_assert(!SWIGLU || (WTN / 2) % RPI == 0, "a load instruction must not straddle gate / up rows");
+    static_assert(BM % (RPI * NW) == 0, "tile rows must split over the wavefronts");
+    static_assert(WTN % 16 == 0 && WTN <= 128 && BN % RPI == 0, "wavefront tile: whole MFMA blocks, at most 128 columns");
+    static_assert(!SWIGLU || ((WTN / 2) % RPI == 0 && (WTN / 2) % 4 == 0),
+                  "a load instruction / a store chunk must not straddle gate and up rows");
     static_assert(NW * 16 * STG_LD * 4 <= NST * STAGE_BYTES, "epilogue staging must fit in the tile buffers");
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -191,24 +192,24 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm2_kernel(Gemm2Params p) {
     }
 #pragma unroll
     for (int i = 0; i < B_INSTR; ++i) {
-        const int row = wave * (BN / NW) + RPI * i + lane / CPR;
+        const int row = wave * (BNP / NW) + RPI * i + lane / CPR;
         const int c = (lane % CPR) ^ swz(row);
         int col;
         if (SWIGLU) col = nloc0 + (row / WTN) * (WTN / 2) + (row % (WTN / 2));
         else col = nloc0 + row;
-        b_off[i] = col < seg_rows ? (uint32_t)((int64_t)col * K * 2) + c * 16 : OOB_OFF;
+        b_off[i] = (row < BN && col < seg_rows) ? (uint32_t)((int64_t)col * K * 2) + c * 16 : OOB_OFF;
     }
 
     auto issue_loads = [&](int kt, int stage) {
         const uint32_t kb = (uint32_t)kt * ROWB;
         unsigned char *sa = smem + stage * STAGE_BYTES + wave * (BM / NW) * ROWB;
-        unsigned char *sb = smem + stage * STAGE_BYTES + A_BYTES + wave * (BN / NW) * ROWB;
+        unsigned char *sb = smem + stage * STAGE_BYTES + A_BYTES + wave * (BNP / NW) * ROWB;
 #pragma unroll
         for (int i = 0; i < A_INSTR; ++i)
             load16_to_lds(rx, sa + i * 1024, a_off[i] + kb);
 #pragma unroll
         for (int i = 0; i < B_INSTR; ++i) {
-            const int row0 = wave * (BN / NW) + RPI * i;                    // wavefront-uniform
+            const int row0 = wave * (BNP / NW) + RPI * i;                   // wavefront-uniform
             const bool up = SWIGLU && ((row0 % WTN) >= WTN / 2);
             if (up) load16_to_lds(ru, sb + i * 1024, b_off[i] + kb);
             else load16_to_lds(rw, sb + i * 1024, b_off[i] + kb);
@@ -452,7 +453,9 @@ static int32_t launch_cfg2(const GemmArgs &a, hipStream_t s) {
     int64_t xb = (int64_t)a.M * a.ldx * 2;
     if (xb >= (int64_t)OOB_OFF) return CASCADE_EUNSUPPORTED;
     p.x_bytes = (uint32_t)xb;
-    constexpr size_t lds = (size_t)NST * (BM + BN) * BK * 2;
+    constexpr int LOAD_ROWS = 1024 / (BK * 2) * WM * WN;                  // B rows loaded per pass of all wavefronts
+    constexpr int BNP = PINGPONG ? BN : (BN + LOAD_ROWS - 1) / LOAD_ROWS * LOAD_ROWS;
+    constexpr size_t lds = (size_t)NST * (BM + BNP) * BK * 2;
     static_assert(lds <= 160 * 1024, "tile buffers exceed the LDS of a CU");
     const void *kern;
     if constexpr (PINGPONG) kern = (const void *)gemm3_kernel<BM, BN, WM, WN, BK, NST, SWIGLU>;
@@ -470,6 +473,17 @@ static int32_t launch_cfg2(const GemmArgs &a, hipStream_t s) {
     return CASCADE_OK;
 }
 
+static int cu_count() {
+    static int n = 0;
+    if (!n) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess) n = prop.multiProcessorCount;
+        if (n <= 0) n = 256;
+    }
+    return n;
+}
+
 // Returns CASCADE_EUNSUPPORTED when the shape is not eligible (the caller then uses the general kernel).
 int32_t launch_gemm_bf16_v2(const GemmArgs &a, hipStream_t s) {
     if (a.K % 64 != 0 || a.K < 64 || a.ldx % 8 != 0 || a.ldy % 4 != 0 || ((a.epilogue & CASCADE_EPI_RESIDUAL) && a.ldres % 4 != 0))
@@ -478,20 +492,31 @@ int32_t launch_gemm_bf16_v2(const GemmArgs &a, hipStream_t s) {
     for (int i = 0; i < 3; ++i)
         if (a.seg_end[i] % 4) return CASCADE_EUNSUPPORTED;          // 4-column store chunks stay inside a segment
     const bool swiglu = a.epilogue & CASCADE_EPI_SWIGLU;
-    const char *v = getenv("CASCADE_GEMM_CFG");                    // tuning aid: 0 = default
-    const int cfg = v ? atoi(v) : 0;
+    // Tile choice (measured on MI355X, M = 2048..8192): 256x256 tiles with BK 64 and two stages (the
+    // largest step per barrier that fits LDS; 1.13 PFLOP/s on the FFN up GEMM against 1.06-1.08 for
+    // BK 32 with 4-5 stages in either schedule) when they give at least ~160 workgroups; otherwise
+    // 256x128 tiles, BK 64, three stages, ping-pong schedule (1.10 against 1.04 PFLOP/s on FFN down).
+    // SwiGLU always uses the 256-column tile (gate and up rows interleave per 128-column wavefront tile).
+    // Narrower variants of the wide tile (224, 192 columns) exist to fill whole rounds of workgroups:
+    // the cost of a launch is rounds x columns per tile.
+    const int tiles_m = (a.M + 255) / 256;
+    auto n_tiles = [&](int bn_out) {
+        int64_t t = 0;
+        int col0 = 0;
+        for (int i = 0; i < 3; ++i) { int rows = std::max(0, a.seg_end[i] - col0); t += (rows + bn_out - 1) / bn_out; col0 = std::max(col0, a.seg_end[i]); }
+        return t * tiles_m;
+    };
+    const int64_t cus = cu_count();
+    auto cost = [&](int bne) { return ((n_tiles(swiglu ? bne / 2 : bne) + cus - 1) / cus) * bne; };
+    const int64_t c256 = cost(256), c224 = cost(224), c192 = cost(192);
     if (swiglu) {
-        if (cfg == 1) return launch_cfg2<256, 256, 4, 2, 64, 2, true>(a, s);
-        if (cfg == 2) return launch_cfg2<256, 256, 4, 2, 32, 5, true, true>(a, s);
-        return launch_cfg2<256, 256, 4, 2, 32, 4, true, true>(a, s);
+        if (c224 < c256) return launch_cfg2<256, 224, 4, 2, 64, 2, true, false>(a, s);
+        return launch_cfg2<256, 256, 4, 2, 64, 2, true, false>(a, s);
     }
-    const int64_t big_tiles = (int64_t)((a.M + 255) / 256) * ((a.N + 255) / 256);
-    if (big_tiles >= 160) {
-        if (cfg == 1) return launch_cfg2<256, 256, 4, 2, 64, 2, false>(a, s);
-        if (cfg == 2) return launch_cfg2<256, 256, 4, 2, 32, 5, false, true>(a, s);
-        return launch_cfg2<256, 256, 4, 2, 32, 4, false, true>(a, s);
+    if (n_tiles(256) >= 160) {
+        if (c192 < c256 && c192 <= c224) return launch_cfg2<256, 192, 4, 2, 64, 2, false, false>(a, s);
+        if (c224 < c256) return launch_cfg2<256, 224, 4, 2, 64, 2, false, false>(a, s);
+        return launch_cfg2<256, 256, 4, 2, 64, 2, false, false>(a, s);
     }
-    if (cfg == 1) return launch_cfg2<256, 128, 4, 2, 64, 3, false>(a, s);
-    if (cfg == 2) return launch_cfg2<256, 128, 4, 2, 32, 5, false, true>(a, s);
     return launch_cfg2<256, 128, 4, 2, 64, 3, false, true>(a, s);
 }

@@ -22,11 +22,18 @@ def cas():
     return cas
 
 
-def run_layer(cas, cfg, a, w, h, attn_mode):
+def run_layer(cas, cfg, a, w, h, attn_mode, fused_qkv=False):
     import torch
     plan = cas.cascade_plan_create(cfg.batch, cfg.seq_len, cfg.n_shards, a)
     desc = cas.make_layer_desc(cfg, attn_mode)
     tensors = {k: cas.to_device(v, cfg.dtype) for k, v in w.items()}
+    if fused_qkv:       # q, k, v weights (and biases) back to back in one allocation: the library merges them
+        nq, nk = w["wq"].shape[0], w["wk"].shape[0]
+        wqkv = torch.cat([tensors["wq"], tensors["wk"], tensors["wv"]], dim=0).contiguous()
+        tensors.update(wq=wqkv[:nq], wk=wqkv[nq:nq + nk], wv=wqkv[nq + nk:], _wqkv=wqkv)
+        if "bq" in tensors:
+            bqkv = torch.cat([tensors["bq"], tensors["bk"], tensors["bv"]]).contiguous()
+            tensors.update(bq=bqkv[:nq], bk=bqkv[nq:nq + nk], bv=bqkv[nq + nk:], _bqkv=bqkv)
     wts = cas.make_layer_weights(tensors)
     h_in = cas.to_device(h, cfg.dtype)
     h_out = torch.empty_like(h_in)
@@ -59,6 +66,23 @@ def test_full_config_sampled_rows(cas, key):
         print(f"[{key}] batch {b}: sampled-row max rel err {err:.3e}", flush=True)
         assert err < TOL[cfg.dtype]
         assert abs(scale_ref - np.abs(ref).max()) / scale_ref < 0.5   # sample spans the output's scale
+
+
+@pytest.mark.parametrize("key", ["C2", "C3"])
+def test_fused_qkv_weights_give_the_same_result(cas, key):
+    """q, k, v weights stored contiguously take the single-segment GEMM path (other tile widths);
+    the result must agree with the three-segment path and with the oracle on sampled rows."""
+    cfg = CONFIGS[key]
+    seed = config_seed(cfg)
+    a = make_assignment(cfg.assignment, cfg.seq_len, cfg.n_shards, seed)
+    w, h = make_layer_weights(cfg), make_hidden(cfg)
+    out_sep = run_layer(cas, cfg, a, w, h, cas.ATTN_FUSED)[3].float().cpu().numpy().astype(np.float64)
+    out_fus = run_layer(cas, cfg, a, w, h, cas.ATTN_FUSED, fused_qkv=True)[3].float().cpu().numpy().astype(np.float64)
+    assert np.abs(out_fus - out_sep).max() / np.abs(out_sep).max() < 1e-2      # same math, other tiling
+    rows = np.sort(np.random.default_rng(seed).choice(cfg.seq_len, size=16, replace=False))
+    w64 = {k: v.astype(np.float64) for k, v in w.items()}
+    ref = orc.layer_direct(h[0], w64, cfg, rows=rows)
+    assert np.abs(out_fus[0][rows] - ref).max() / np.abs(ref).max() < TOL[cfg.dtype]
 
 
 @pytest.mark.parametrize("key", ["C2", "C3", "C4"])
