@@ -156,6 +156,8 @@ def main():
     ap.add_argument("--config", default="C3", help="headline workload (C1..C5)")
     ap.add_argument("--all", action="store_true", help="also time the other bf16 configurations")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one plain 256 MiB device copy (reference point for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs all shards on ONE GPU; --gpus N with N > 1 is not supported "
@@ -166,6 +168,13 @@ def main():
     import paper_2507_05228_amd as cas
     from cascade_inputs import CONFIGS
     cas.load_library()
+
+    if args.calibration_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     cfg = CONFIGS[args.config]
     res = run_config(cas, cfg, args.steps, args.warmup, staged=True, check=not args.no_cpu_baseline)

@@ -1,6 +1,7 @@
 // HBM-bound per-token kernels: normalisation with row gather (Pre-Pass subsection: "applies
 // layer normalization if necessary"), rotary embedding at original token positions
 // (Algorithm 2 lines 4-5), and row gather / scatter between original and packed order.
+#include <cmath>
 #include "common.h"
 #include "device_utils.h"
 
@@ -37,20 +38,86 @@ __global__ __launch_bounds__(256) void norm_kernel(const T *__restrict__ x, cons
     }
 }
 
-int32_t launch_norm(const NormArgs &a, hipStream_t s) {
-    if (a.rows == 0) return CASCADE_OK;
-    size_t lds = (size_t)a.D * sizeof(float);
-    if (lds > 64 * 1024) return CASCADE_EUNSUPPORTED;
-    if (a.dtype == CASCADE_BF16)
-        hipLaunchKernelGGL(norm_kernel<bf16_t>, dim3(a.rows), dim3(256), lds, s, (const bf16_t *)a.x,
-                           (const bf16_t *)a.gain, (const bf16_t *)a.bias, (bf16_t *)a.y, a.D, a.kind, a.eps,
-                           a.xmap.map, a.xmap.seq_len);
-    else
-        hipLaunchKernelGGL(norm_kernel<float>, dim3(a.rows), dim3(256), lds, s, (const float *)a.x,
-                           (const float *)a.gain, (const float *)a.bias, (float *)a.y, a.D, a.kind, a.eps,
-                           a.xmap.map, a.xmap.seq_len);
+// Vector variant: the row lives in registers (CH 16-byte pieces per thread), two passes over them.
+// Requires D % VEC == 0 and D <= 256 * CH * VEC, VEC = 16 bytes / sizeof(T).
+template <typename T, int CH>
+__global__ __launch_bounds__(256) void norm_vec_kernel(const T *__restrict__ x, const T *__restrict__ gain,
+                                                       const T *__restrict__ bias, T *__restrict__ y, int D, int kind,
+                                                       float eps, const int32_t *xmap, int seq_len) {
+    constexpr int VEC = 16 / sizeof(T);
+    typedef T vecT __attribute__((ext_vector_type(VEC)));
+    __shared__ float red[4];
+    const int r = blockIdx.x;
+    const T *xr = x + map_row(xmap, seq_len, r) * (int64_t)D;
+    const int nvec = D / VEC;
+    float v[CH][VEC];
+    float s = 0.f;
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+        const int i = threadIdx.x + 256 * c;
+        if (i < nvec) {
+            const vecT t = *(const vecT *)(xr + i * VEC);
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) { v[c][j] = (float)t[j]; s += v[c][j]; }
+        } else {
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) v[c][j] = 0.f;
+        }
+    }
+    float mu = 0.f;
+    if (kind == CASCADE_NORM_LAYERNORM) mu = block_sum_256(s, red) / D;
+    float q = 0.f;
+#pragma unroll
+    for (int c = 0; c < CH; ++c)
+        if (threadIdx.x + 256 * c < nvec)
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) { const float d0 = v[c][j] - mu; q += d0 * d0; }
+    const float rstd = 1.0f / sqrtf(block_sum_256(q, red) / D + eps);
+    T *yr = y + (int64_t)r * D;
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+        const int i = threadIdx.x + 256 * c;
+        if (i < nvec) {
+            const vecT g = *(const vecT *)(gain + i * VEC);
+            vecT o;
+            if (bias) {
+                const vecT bb = *(const vecT *)(bias + i * VEC);
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) o[j] = (T)((v[c][j] - mu) * rstd * (float)g[j] + (float)bb[j]);
+            } else {
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) o[j] = (T)((v[c][j] - mu) * rstd * (float)g[j]);
+            }
+            *(vecT *)(yr + i * VEC) = o;
+        }
+    }
+}
+
+template <typename T>
+static int32_t launch_norm_t(const NormArgs &a, hipStream_t s) {
+    constexpr int VEC = 16 / sizeof(T);
+    const bool aligned = a.D % VEC == 0 && ((uintptr_t)a.x | (uintptr_t)a.y | (uintptr_t)a.gain | (uintptr_t)a.bias) % 16 == 0;
+    const int nvec = a.D / VEC;
+#define NORM_VEC(CH)                                                                                             \
+    hipLaunchKernelGGL((norm_vec_kernel<T, CH>), dim3(a.rows), dim3(256), 0, s, (const T *)a.x, (const T *)a.gain, \
+                       (const T *)a.bias, (T *)a.y, a.D, a.kind, a.eps, a.xmap.map, a.xmap.seq_len)
+    if (aligned && nvec <= 256) NORM_VEC(1);
+    else if (aligned && nvec <= 512) NORM_VEC(2);
+    else if (aligned && nvec <= 1024) NORM_VEC(4);
+    else {
+        size_t lds = (size_t)a.D * sizeof(float);
+        if (lds > 64 * 1024) return CASCADE_EUNSUPPORTED;
+        hipLaunchKernelGGL(norm_kernel<T>, dim3(a.rows), dim3(256), lds, s, (const T *)a.x, (const T *)a.gain,
+                           (const T *)a.bias, (T *)a.y, a.D, a.kind, a.eps, a.xmap.map, a.xmap.seq_len);
+    }
+#undef NORM_VEC
     CASCADE_HIP_TRY(hipGetLastError());
     return CASCADE_OK;
+}
+
+int32_t launch_norm(const NormArgs &a, hipStream_t s) {
+    if (a.rows == 0) return CASCADE_OK;
+    return a.dtype == CASCADE_BF16 ? launch_norm_t<bf16_t>(a, s) : launch_norm_t<float>(a, s);
 }
 
 // ---------------------------------------------------------------------------- rotary embedding
@@ -77,9 +144,45 @@ __global__ __launch_bounds__(256) void rope_kernel(T *__restrict__ x, int64_t to
     }
 }
 
+// Vector variant for bf16: one thread rotates 8 consecutive pairs (two 16-byte pieces half a head apart).
+__global__ __launch_bounds__(256) void rope_vec_kernel(bf16_t *__restrict__ x, int64_t total_units, int n_rope_heads,
+                                                       int head_dim, int64_t ld, float log2_theta,
+                                                       const int32_t *__restrict__ pos_packed, int seq_len) {
+    const int half = head_dim >> 1;
+    const int upr = n_rope_heads * (half / 8);                    // units per row
+    for (int64_t id = blockIdx.x * 256ll + threadIdx.x; id < total_units; id += (int64_t)gridDim.x * 256) {
+        const int64_t r = id / upr;
+        const int rem = (int)(id - r * upr);
+        const int h = rem / (half / 8), i0 = (rem % (half / 8)) * 8;
+        const float pos = (float)pos_packed[(int)(r % seq_len)];
+        bf16_t *p = x + r * ld + (int64_t)h * head_dim + i0;
+        const bf16x8 a = *(const bf16x8 *)p, b = *(const bf16x8 *)(p + half);
+        bf16x8 oa, ob;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const float inv_freq = exp2f(-2.0f * (float)(i0 + j) / (float)head_dim * log2_theta);
+            float sn, cs;
+            sincosf(pos * inv_freq, &sn, &cs);
+            const float fa = (float)a[j], fb = (float)b[j];
+            oa[j] = (bf16_t)(fa * cs - fb * sn);
+            ob[j] = (bf16_t)(fb * cs + fa * sn);
+        }
+        *(bf16x8 *)p = oa;
+        *(bf16x8 *)(p + half) = ob;
+    }
+}
+
 int32_t launch_rope(const RopeArgs &a, hipStream_t s) {
     int64_t total = (int64_t)a.rows * a.n_rope_heads * (a.head_dim / 2);
     if (total == 0) return CASCADE_OK;
+    if (a.dtype == CASCADE_BF16 && (a.head_dim / 2) % 8 == 0 && a.ld % 8 == 0 && (uintptr_t)a.x % 16 == 0) {
+        const int64_t units = total / 8;
+        const int grid = (int)std::min<int64_t>((units + 255) / 256, 1 << 20);
+        hipLaunchKernelGGL(rope_vec_kernel, dim3(grid), dim3(256), 0, s, (bf16_t *)a.x, units, a.n_rope_heads,
+                           a.head_dim, a.ld, log2f(a.theta), a.pos_packed, a.seq_len);
+        CASCADE_HIP_TRY(hipGetLastError());
+        return CASCADE_OK;
+    }
     int grid = (int)std::min<int64_t>((total + 255) / 256, 65536);
     if (a.dtype == CASCADE_BF16)
         hipLaunchKernelGGL((rope_kernel<bf16_t, float>), dim3(grid), dim3(256), 0, s, (bf16_t *)a.x, total,
