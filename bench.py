@@ -16,6 +16,9 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0      # MI355X dense bf16
+# HBM bytes per launch of the dominant kernel from rocprofv3 FETCH_SIZE / WRITE_SIZE runs, scaled by a plain
+# copy of known size (profiles/bench_C3_hbm_traffic.md); None where no counter run was made
+MEASURED_TRAFFIC_BYTES = {"C3-llama3-8b-bf16": 773.4e6 + 58.7e6}
 FP32_VECTOR_PEAK_TFLOPS = 157.3
 HBM_PEAK_GBS = 8000.0
 
@@ -202,7 +205,7 @@ def main():
         "roofline": {"bound": "mfma" if bf16 else "alu", "kernel": "gemm_bf16_kernel (FFN gate+up shard GEMM)"
                      if bf16 else "gemm_f32_kernel (FFN up shard GEMM)",
                      "achieved": dom_tflops, "peak": peak, "unit": "TFLOP/s", "frac": dom_tflops / peak,
-                     "traffic": None, "avg_launch_ms": st[dom], "flops_per_launch": fl[dom]},
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name), "avg_launch_ms": st[dom], "flops_per_launch": fl[dom]},
         "stages_ms": st,
         "stage_tflops": {k: fl[k] / (st[k] * 1e-3) / 1e12 for k in ("qkv_gemm", "attention", "o_proj", "ffn_up", "ffn_down")},
         "hbm_kernels": {

@@ -94,14 +94,6 @@ struct RopeArgs {
 };
 int32_t launch_rope(const RopeArgs &a, hipStream_t s);
 
-struct CopyRowsArgs {                // y[ymap(r)] = x[xmap(r)], rows of `width` elements
-    int32_t dtype, rows, width;
-    int64_t ldx, ldy;
-    const void *x; void *y;
-    RowMap xmap, ymap;
-};
-int32_t launch_copy_rows(const CopyRowsArgs &a, hipStream_t s);
-
 struct AttnArgs {
     int32_t dtype, B, H, Hkv, d;
     float scale;

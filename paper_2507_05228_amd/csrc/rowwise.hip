@@ -1,6 +1,7 @@
 // HBM-bound per-token kernels: normalisation with row gather (Pre-Pass subsection: "applies
 // layer normalization if necessary"), rotary embedding at original token positions
-// (Algorithm 2 lines 4-5), and row gather / scatter between original and packed order.
+// (Algorithm 2 lines 4-5).  The gather into packed order is the row map of the norm's read; the
+// scatter back is the row map of the last shard GEMM's store.
 #include <cmath>
 #include "common.h"
 #include "device_utils.h"
@@ -190,57 +191,6 @@ int32_t launch_rope(const RopeArgs &a, hipStream_t s) {
     else
         hipLaunchKernelGGL((rope_kernel<float, double>), dim3(grid), dim3(256), 0, s, (float *)a.x, total,
                            a.n_rope_heads, a.head_dim, a.ld, a.theta, a.pos_packed, a.seq_len);
-    CASCADE_HIP_TRY(hipGetLastError());
-    return CASCADE_OK;
-}
-
-// ---------------------------------------------------------------------------- gather / scatter of rows
-// y[ymap(r)] = x[xmap(r)] in 16-byte pieces (width_bytes % 16 == 0) or element by element.
-__global__ __launch_bounds__(256) void copy_rows16_kernel(const uint4 *__restrict__ x, uint4 *__restrict__ y,
-                                                          int rows, int vec_per_row, int64_t ldx_v, int64_t ldy_v,
-                                                          const int32_t *xmap, const int32_t *ymap, int seq_len) {
-    int64_t total = (int64_t)rows * vec_per_row;
-    for (int64_t id = blockIdx.x * 256ll + threadIdx.x; id < total; id += (int64_t)gridDim.x * 256) {
-        int r = (int)(id / vec_per_row);
-        int c = (int)(id - (int64_t)r * vec_per_row);
-        y[map_row(ymap, seq_len, r) * ldy_v + c] = x[map_row(xmap, seq_len, r) * ldx_v + c];
-    }
-}
-
-template <typename T>
-__global__ __launch_bounds__(256) void copy_rows_kernel(const T *__restrict__ x, T *__restrict__ y, int rows,
-                                                        int width, int64_t ldx, int64_t ldy, const int32_t *xmap,
-                                                        const int32_t *ymap, int seq_len) {
-    int64_t total = (int64_t)rows * width;
-    for (int64_t id = blockIdx.x * 256ll + threadIdx.x; id < total; id += (int64_t)gridDim.x * 256) {
-        int r = (int)(id / width);
-        int c = (int)(id - (int64_t)r * width);
-        y[map_row(ymap, seq_len, r) * ldy + c] = x[map_row(xmap, seq_len, r) * ldx + c];
-    }
-}
-
-int32_t launch_copy_rows(const CopyRowsArgs &a, hipStream_t s) {
-    if (a.rows == 0 || a.width == 0) return CASCADE_OK;
-    const int es = a.dtype == CASCADE_BF16 ? 2 : 4;
-    const int seq = a.xmap.map ? a.xmap.seq_len : a.ymap.seq_len;
-    const bool vec = ((int64_t)a.width * es) % 16 == 0 && (a.ldx * es) % 16 == 0 && (a.ldy * es) % 16 == 0 &&
-                     ((uintptr_t)a.x % 16 == 0) && ((uintptr_t)a.y % 16 == 0);
-    if (vec) {
-        int vpr = a.width * es / 16;
-        int64_t total = (int64_t)a.rows * vpr;
-        int grid = (int)std::min<int64_t>((total + 255) / 256, 1 << 20);
-        hipLaunchKernelGGL(copy_rows16_kernel, dim3(grid), dim3(256), 0, s, (const uint4 *)a.x, (uint4 *)a.y, a.rows,
-                           vpr, a.ldx * es / 16, a.ldy * es / 16, a.xmap.map, a.ymap.map, seq);
-    } else {
-        int64_t total = (int64_t)a.rows * a.width;
-        int grid = (int)std::min<int64_t>((total + 255) / 256, 1 << 20);
-        if (es == 2)
-            hipLaunchKernelGGL(copy_rows_kernel<uint16_t>, dim3(grid), dim3(256), 0, s, (const uint16_t *)a.x,
-                               (uint16_t *)a.y, a.rows, a.width, a.ldx, a.ldy, a.xmap.map, a.ymap.map, seq);
-        else
-            hipLaunchKernelGGL(copy_rows_kernel<uint32_t>, dim3(grid), dim3(256), 0, s, (const uint32_t *)a.x,
-                               (uint32_t *)a.y, a.rows, a.width, a.ldx, a.ldy, a.xmap.map, a.ymap.map, seq);
-    }
     CASCADE_HIP_TRY(hipGetLastError());
     return CASCADE_OK;
 }
