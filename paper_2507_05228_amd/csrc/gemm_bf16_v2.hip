@@ -51,38 +51,54 @@ __device__ __forceinline__ void load16_to_lds(__amdgpu_buffer_rsrc_t r, unsigned
 }
 
 // Epilogue shared by the shard-GEMM kernels.  acc[i][j][r] holds row 16i + 4(lane/16) + r, column
-// 16j + lane%16 of the wavefront's WTM x WTN tile.  The caller guarantees that every wavefront of the
-// workgroup is done with the tile buffers (smem is reused as staging).
+// 16j + lane%16 of the wavefront's WTM x WTN tile.  The caller guarantees (with a workgroup barrier)
+// that every wavefront is done with the tile buffers: smem is reused as staging, one private region
+// per wavefront, so inside the epilogue only wavefront-level ordering of LDS traffic is needed.
+// SwiGLU pairs (gate column c, up column c + WTN/2) sit in the same lane and register slot, so the
+// activation is applied in registers and only WTN/2 columns are staged.
+__device__ __forceinline__ float silu_fast(float x) {
+    // x * 1/(1 + 2^(-x log2 e)); hardware reciprocal (1 ulp), output is rounded to bf16 anyway
+    return x * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * x));
+}
+
 template <int TM, int TN, int WTN, bool SWIGLU>
 __device__ __forceinline__ void gemm_epilogue(const Gemm2Params &p, f32x4 (&acc)[TM][TN], unsigned char *smem,
                                               int wave, int lane, int m0, int wm0, int wn0, int nloc0, int seg,
                                               int seg_rows) {
-    constexpr int STG_LD = WTN + 4;
-    // ---- epilogue.  acc[i][j][r]: row 16i + 4(lane/16) + r, column 16j + lane%16 of the wavefront tile.
+    constexpr bool INREG = SWIGLU && (WTN / 2) % 16 == 0;  // gate and up of a column share lane and slot
+    constexpr int OW = SWIGLU ? WTN / 2 : WTN;             // output columns of the wavefront tile
+    constexpr int SW = INREG ? OW : WTN;                   // staged columns
+    constexpr int TNS = SW / 16;
+    constexpr int STG_LD = SW + 4;
+    constexpr int NCH = (OW + 63) / 64;                    // 4-column chunks per lane: columns 64 cc + m4
     const int flags = p.flags;
     float *stg = (float *)smem + wave * 16 * STG_LD;
-    const int m4 = (lane & 15) * 4, rsel = lane >> 4;
-    constexpr int NCH = (WTN + 63) / 64;                   // 4-column chunks per lane: columns 64 cc + m4
-    constexpr int NCH_OUT = SWIGLU ? 1 : NCH;
-    const int wcol0 = SWIGLU ? nloc0 + (wn0 / WTN) * (WTN / 2) : nloc0 + wn0;   // first output column (in segment)
+    const int l16 = lane & 15, m4 = l16 * 4, rsel = lane >> 4;
+    const int wcol0 = SWIGLU ? nloc0 + (wn0 / WTN) * OW : nloc0 + wn0;   // first output column (in segment)
     const int gcol0 = p.seg_col0[seg];
-    f32x4 bias_v[NCH_OUT];
+    const bf16_t *bias = (flags & CASCADE_EPI_BIAS) ? p.bias[seg] : nullptr;
+    f32x4 bias_v[NCH];
 #pragma unroll
-    for (int cc = 0; cc < NCH_OUT; ++cc) {
+    for (int cc = 0; cc < NCH; ++cc) {
         const int c = wcol0 + 64 * cc + m4;
         bias_v[cc] = f32x4{0.f, 0.f, 0.f, 0.f};
-        if ((flags & CASCADE_EPI_BIAS) && p.bias[seg])
+        if (bias)
 #pragma unroll
             for (int x = 0; x < 4; ++x)
-                if (c + x < seg_rows) bias_v[cc][x] = (float)p.bias[seg][c + x];
+                if (c + x < seg_rows) bias_v[cc][x] = (float)bias[c + x];
     }
+    const bool act = flags & (CASCADE_EPI_GELU_ERF | CASCADE_EPI_GELU_TANH);
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
+        for (int j = 0; j < TNS; ++j)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) stg[(4 * rsel + r) * STG_LD + 16 * j + (lane & 15)] = acc[i][j][r];
-        __syncthreads();
+            for (int r = 0; r < 4; ++r) {
+                float v = acc[i][j][r];
+                if (INREG) v = silu_fast(v) * acc[i][j + TNS][r];     // SwiGLU launches carry no bias
+                stg[(4 * rsel + r) * STG_LD + 16 * j + l16] = v;
+            }
+        __builtin_amdgcn_wave_barrier();                   // LDS serves one wavefront's accesses in order
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
             const int rl = 4 * t + rsel;
@@ -92,15 +108,16 @@ __device__ __forceinline__ void gemm_epilogue(const Gemm2Params &p, f32x4 (&acc)
                 const bf16_t *rrow = (flags & CASCADE_EPI_RESIDUAL)
                                          ? p.residual + map_row(p.rmap, p.seq_len, gm) * p.ldres + gcol0 : nullptr;
 #pragma unroll
-                for (int cc = 0; cc < NCH_OUT; ++cc) {
+                for (int cc = 0; cc < NCH; ++cc) {
                     const int c = wcol0 + 64 * cc + m4;
-                    if (c >= seg_rows || 64 * cc + m4 >= (SWIGLU ? WTN / 2 : WTN)) continue;
-                    f32x4 v = *(const f32x4 *)(stg + rl * STG_LD + 64 * cc + m4) + bias_v[cc];
-                    if (SWIGLU) {
-                        const f32x4 up = *(const f32x4 *)(stg + rl * STG_LD + WTN / 2 + m4);
+                    if (c >= seg_rows || 64 * cc + m4 >= OW) continue;
+                    f32x4 v = *(const f32x4 *)(stg + rl * STG_LD + 64 * cc + m4);
+                    if (!SWIGLU) v += bias_v[cc];
+                    if (SWIGLU && !INREG) {
+                        const f32x4 up = *(const f32x4 *)(stg + rl * STG_LD + OW + m4);
 #pragma unroll
-                        for (int x = 0; x < 4; ++x) v[x] = silu_f(v[x]) * up[x];
-                    } else if (flags & (CASCADE_EPI_GELU_ERF | CASCADE_EPI_GELU_TANH)) {
+                        for (int x = 0; x < 4; ++x) v[x] = silu_fast(v[x]) * up[x];
+                    } else if (!SWIGLU && act) {
 #pragma unroll
                         for (int x = 0; x < 4; ++x) v[x] = apply_act(v[x], flags);
                     }
@@ -119,7 +136,7 @@ __device__ __forceinline__ void gemm_epilogue(const Gemm2Params &p, f32x4 (&acc)
                 }
             }
         }
-        __syncthreads();
+        __builtin_amdgcn_wave_barrier();
     }
 }
 
@@ -141,7 +158,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm2_kernel(Gemm2Params p) {
     constexpr int A_INSTR = BM / RPI / NW, B_INSTR = BNP / RPI / NW;     // direct-to-LDS instructions per wavefront
     constexpr int LPT = A_INSTR + B_INSTR;                         // loads per tile per wavefront
     constexpr int A_BYTES = BM * ROWB, STAGE_BYTES = (BM + BNP) * ROWB;
-    constexpr int STG_LD = WTN + 4;                                // epilogue staging row (floats)
+    constexpr int STG_LD = WTN + 4;                                // widest epilogue staging row (floats)
     static_assert(BK == 32 || BK == 64, "BK");
     static_assert(NST >= 2 && NST <= 4 && (NST - 2) * LPT < 64, "pipeline depth");
     static_assert(BM % (RPI * NW) == 0, "tile rows must split over the wavefronts");
