@@ -79,9 +79,9 @@ struct AttnBf16Params {
     int64_t qs_b, qs_h, qs_n, ks_b, ks_h, ks_n, vts_b, vts_h;
     int32_t npad;
     uint32_t k_bytes, vt_bytes;      // extent of one (batch, kv head) slice, for the buffer resources
-    const int32_t *q_rowmap, *kv_rowmap;
+    const int32_t *q_rowmap;
     const CascadeTile *qtiles;
-    const CascadeTile *kvtiles;
+    const CascadeTile *kvtiles;      // fused: ordered by smallest position; else packed order (per-shard ranges)
     const int32_t *kv_shard_first;
     int32_t n_kvtiles;
     const int32_t *pos_packed;
@@ -95,9 +95,33 @@ struct AttnBf16Params {
     int32_t hpb;          // heads per workgroup (1, 2 or 4)
 };
 
+// Optional timeline instrumentation (build with -DCASCADE_TRACE): lane 0 of wavefronts 0 and 4 of one
+// workgroup stores the shader clock at a few phase boundaries of the first tiles.
+#ifdef CASCADE_TRACE
+#define ATRACE_ITERS 40
+__device__ unsigned long long g_attn_trace[2 * ATRACE_ITERS * 8];
+__device__ int g_attn_trace_wg[2] = {0, 0};
+#define ATRACE(it, slot)                                                                                        \
+    do {                                                                                                        \
+        if ((int)blockIdx.x == g_attn_trace_wg[0] && (int)blockIdx.y == g_attn_trace_wg[1] && (threadIdx.x & 255) == 0 && (it) < ATRACE_ITERS) \
+            g_attn_trace[((threadIdx.x >> 8) * ATRACE_ITERS + (it)) * 8 + (slot)] = clock64();                    \
+    } while (0)
+extern "C" __attribute__((visibility("default"))) int cascade_debug_attn_trace(unsigned long long *host, int n, int wgx, int wgy) {
+    int sel[2] = {wgx, wgy};
+    if (wgx >= 0) return (int)hipMemcpyToSymbol(HIP_SYMBOL(g_attn_trace_wg), sel, sizeof(sel), 0, hipMemcpyHostToDevice);
+    if (n > 2 * ATRACE_ITERS * 8) n = 2 * ATRACE_ITERS * 8;
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_attn_trace), (size_t)n * 8, 0, hipMemcpyDeviceToHost);
+}
+#else
+#define ATRACE(it, slot) do { } while (0)
+#endif
+
 // ---------------------------------------------------------------------------- V -> V^T (tile order)
-// vt[b][g][c][64 t + i] = v[b][g][row(tile t, i)][c] for i < n_rows(t), zero for the padding of a
-// ragged tile.  Column 64 t of V^T is therefore 16-byte aligned for every key/value tile t.
+// vt[b][g][c][64 t + col(i)] = v[b][g][row(tile t, i)][c] for i < n_rows(t), zero for the padding of a
+// ragged tile.  Column 64 t of V^T is therefore 16-byte aligned for every key/value tile t.  Inside
+// a tile the keys are permuted so that the 8 keys one lane feeds to an MFMA k-step of O^T += V^T P^T
+// are contiguous: key i = 32 s + 16 jh + 4 g + jl sits at col(i) = 32 s + 8 g + 4 jh + jl (the P^T
+// operand of lane group g is built from accumulator registers jl of score blocks 2s + jh).
 template <int D>
 __global__ __launch_bounds__(256) void vtranspose_kernel(const bf16_t *__restrict__ v, bf16_t *__restrict__ vt,
                                                          int64_t vs_b, int64_t vs_h, int64_t vs_n, int npad,
@@ -124,7 +148,7 @@ __global__ __launch_bounds__(256) void vtranspose_kernel(const bf16_t *__restric
         int c = id / 8, ch = id % 8;
         bf16x8 val;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) val[i] = tile[ch * 8 + i][c];
+        for (int i = 0; i < 8; ++i) val[i] = tile[32 * (ch >> 2) + 16 * (i >> 2) + 4 * (ch & 3) + (i & 3)][c];
         *(bf16x8 *)(ob + (int64_t)c * npad + ch * 8) = val;
     }
 }
@@ -139,7 +163,7 @@ __global__ __launch_bounds__(512) void attn_bf16_kernel(AttnBf16Params p) {
     constexpr int K_RPI = 1024 / K_ROW;                // K rows filled by one direct-to-LDS instruction
     constexpr int K_CPR = K_ROW / 16;                  // 16-byte chunks per K row
     constexpr int K_BYTES = KV_TILE * K_ROW, V_BYTES = D * 128;
-    constexpr int STAGE = K_BYTES + V_BYTES + KV_TILE * 4;
+    constexpr int STAGE = K_BYTES + V_BYTES;
     constexpr int K_INSTR = KV_TILE / K_RPI / 8;       // per wavefront (8 wavefronts): 2 (D=128) or 1 (D=64)
     constexpr int V_INSTR = D / 8 / 8;                 // 2 or 1
 
@@ -190,12 +214,33 @@ __global__ __launch_bounds__(512) void attn_bf16_kernel(AttnBf16Params p) {
     const int wq_hi = p.causal ? max(wq_max[0], wq_max[1]) : INT_MAX;
     const int wq_lo = p.causal ? min(wq_min[0], wq_min[1]) : INT_MAX;
 
-    // ---- key/value tile range
+    // ---- key/value tile range.  The tiles some query row of the workgroup can see (smallest key
+    // position <= largest query position) form a prefix of the range: the fused list is ordered by
+    // smallest position, and inside one shard positions ascend with the packed row.
     const int t_begin = p.fused ? 0 : ((int_cptr)p.kv_shard_first)[kk];
-    const int t_end = p.fused ? p.n_kvtiles : ((int_cptr)p.kv_shard_first)[kk + 1];
-    auto next_tile = [&](int t) {                      // first tile >= t that some query row of the workgroup can see
-        while (t < t_end && p.causal && kvtiles[t].pmin > q_pmax) ++t;
-        return t;
+    const int t_cap = p.fused ? p.n_kvtiles : ((int_cptr)p.kv_shard_first)[kk + 1];
+    int t_end = t_cap;
+    if (p.causal) {
+        int n = 0;
+        for (int base = t_begin; base < t_cap; base += 64) {
+            const int t = base + lane;
+            n += __popcll(__ballot(t < t_cap && p.kvtiles[t].pmin <= q_pmax));
+        }
+        t_end = t_begin + __builtin_amdgcn_readfirstlane(n);
+    }
+    // Tile metadata lives in scalar registers and is fetched three tiles ahead of its use, so the
+    // latency of the scalar loads never sits on the critical path of a phase.
+    struct TileMeta {
+        int row_start, n_rows, index;                  // index: column block of V^T
+        int smin[4], smax[4];                          // position bounds of the four 16-key blocks
+    };
+    auto load_meta = [&](int t) {
+        TileMeta m;
+        const tile_cptr tp = kvtiles + t;
+        m.row_start = tp->row_start; m.n_rows = tp->n_rows; m.index = tp->index;
+#pragma unroll
+        for (int kvb = 0; kvb < 4; ++kvb) { m.smin[kvb] = tp->sub_min[kvb]; m.smax[kvb] = tp->sub_max[kvb]; }
+        return m;
     };
 
     const __amdgpu_buffer_rsrc_t rk = __builtin_amdgcn_make_buffer_rsrc(
@@ -208,8 +253,8 @@ __global__ __launch_bounds__(512) void attn_bf16_kernel(AttnBf16Params p) {
     // Direct-to-LDS loads of one tile.  K instruction i of this wavefront fills K rows
     // (wave*K_INSTR + i)*K_RPI ..: lane -> row lane/K_CPR, slot lane%K_CPR holding chunk slot^swz(row).
     // V^T instruction i fills V^T rows (wave*V_INSTR + i)*8 ..: lane -> row lane/8, slot lane%8.
-    auto issue_loads = [&](int t, int stage) {
-        const int row_start = kvtiles[t].row_start, n_rows = kvtiles[t].n_rows;
+    auto issue_loads = [&](const TileMeta &tm, int stage) {
+        const int row_start = tm.row_start, n_rows = tm.n_rows;
         unsigned char *sk = smem + stage * STAGE;
         unsigned char *sv = sk + K_BYTES;
 #pragma unroll
@@ -218,11 +263,8 @@ __global__ __launch_bounds__(512) void attn_bf16_kernel(AttnBf16Params p) {
             const int rr = row0 + lane / K_CPR;
             const int slot = lane % K_CPR;
             const int c = D == 128 ? (slot ^ (rr & 15)) : (slot ^ ((rr >> 1) & 7));
-            uint32_t off = OOB_OFF;
-            if (rr < n_rows) {
-                const int r = row_start + rr;
-                off = (uint32_t)((int64_t)(p.kv_rowmap ? p.kv_rowmap[r] : r) * p.ks_n * 2) + c * 16;
-            }
+            // K is in packed row order here (the launcher gathers it first when the caller's is not)
+            const uint32_t off = rr < n_rows ? (uint32_t)((int64_t)(row_start + rr) * p.ks_n * 2) + c * 16 : OOB_OFF;
             load16_to_lds(rk, sk + row0 * K_ROW, off);
         }
 #pragma unroll
@@ -230,17 +272,22 @@ __global__ __launch_bounds__(512) void attn_bf16_kernel(AttnBf16Params p) {
             const int row0 = (wave * V_INSTR + i) * 8;
             const int rr = row0 + (lane >> 3);
             const int c = (lane & 7) ^ ((rr >> 1) & 7);
-            load16_to_lds(rv, sv + row0 * 128, (uint32_t)(((int64_t)rr * p.npad + (int64_t)t * KV_TILE) * 2) + c * 16);
+            load16_to_lds(rv, sv + row0 * 128, (uint32_t)(((int64_t)rr * p.npad + (int64_t)tm.index * KV_TILE) * 2) + c * 16);
         }
-        // every wavefront writes the same 64 positions: keeps the loads-per-tile count uniform
-        load4_to_lds(rp, sv + V_BYTES, lane < n_rows ? (uint32_t)(row_start + lane) * 4 : OOB_OFF);
     };
 
     f32x4 oacc[TQ][DB];
-    float m_run[TQ], l_run[TQ];
+    // m_run is the exponent offset in use (log2 units), m_top the true running maximum.  The offset
+    // follows the maximum lazily: it moves only when some row's maximum has grown by more than
+    // RESCALE_LOG2 since the offset was set, so exponentials stay below 2^RESCALE_LOG2 and the
+    // rescaling of O and of the running sum is skipped for most tiles.  The results are the same
+    // in exact arithmetic; m and e are referred to the true maximum on write-out.
+    constexpr float RESCALE_LOG2 = 8.0f;
+    float m_run[TQ], m_top[TQ], l_run[TQ];
 #pragma unroll
     for (int qb = 0; qb < TQ; ++qb) {
         m_run[qb] = -INFINITY;
+        m_top[qb] = -INFINITY;
         l_run[qb] = 0.f;
 #pragma unroll
         for (int db = 0; db < DB; ++db) oacc[qb][db] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -263,14 +310,16 @@ __global__ __launch_bounds__(512) void attn_bf16_kernel(AttnBf16Params p) {
     // group 1's X(i)) each wavefront waits for its own loads of tile i+1, so the tile is complete
     // when group 0 enters X(i+1).
     constexpr int NST = 4;
-    constexpr int LPT = K_INSTR + V_INSTR + 1;         // loads per tile per wavefront
+    constexpr int LPT = K_INSTR + V_INSTR;             // direct-to-LDS loads per tile per wavefront
     const int group = wave >> 2;
-    int t0 = next_tile(t_begin);                       // tile i
-    int t1 = t0 < t_end ? next_tile(t0 + 1) : t_end;   // tile i+1
-    int t2 = t1 < t_end ? next_tile(t1 + 1) : t_end;   // tile i+2
-    if (t0 < t_end) issue_loads(t0, 0);
-    if (t1 < t_end) issue_loads(t1, 1);
-    if (t1 < t_end) phase_barrier<LPT, false>();       // tile 0 complete and visible
+    int t = t_begin;                                   // tile i
+    TileMeta mt0 = {}, mt1 = {}, mt2 = {};             // tiles i, i+1, i+2
+    if (t < t_end) mt0 = load_meta(t);
+    if (t + 1 < t_end) mt1 = load_meta(t + 1);
+    if (t + 2 < t_end) mt2 = load_meta(t + 2);
+    if (t < t_end) issue_loads(mt0, 0);
+    if (t + 1 < t_end) issue_loads(mt1, 1);
+    if (t + 1 < t_end) phase_barrier<LPT, false>();    // tile 0 complete and visible
     else phase_barrier<0, false>();
     if (group == 1) phase_barrier<-1, false>();        // run one phase behind group 0
 
@@ -280,18 +329,20 @@ __global__ __launch_bounds__(512) void attn_bf16_kernel(AttnBf16Params p) {
     int prev_stage = 0;
     bool have_prev = false;
 
-    for (int i = 0; t0 < t_end; ++i) {
+    for (int i = 0; t < t_end; ++i, ++t) {
         const int stage = i % NST;
+        ATRACE(i, 0);
+        TileMeta mt3 = mt2;
+        if (t + 3 < t_end) mt3 = load_meta(t + 3);
         // ================= X(i): matrix phase
-        const tile_cptr ktp = kvtiles + t0;
-        const int kn = ktp->n_rows;
+        const int kn = mt0.n_rows;
         const unsigned char *sk = smem + stage * STAGE;
         const unsigned char *sv = sk + K_BYTES;
         // per 16-key block: can this wavefront skip it / does it need the element-wise compare
         int skipm = 0, maskm = 0;
 #pragma unroll
         for (int kvb = 0; kvb < 4; ++kvb) {
-            const int kmin = ktp->sub_min[kvb], kmax = ktp->sub_max[kvb];
+            const int kmin = mt0.smin[kvb], kmax = mt0.smax[kvb];
             skipm |= (int)((kvb * 16 >= kn) | (kmin > wq_hi)) << kvb;
             maskm |= (int)((kvb * 16 + 16 > kn) | (kmax > wq_lo)) << kvb;
         }
@@ -299,10 +350,14 @@ __global__ __launch_bounds__(512) void attn_bf16_kernel(AttnBf16Params p) {
         int pk[4][4];
 #pragma unroll
         for (int kvb = 0; kvb < 4; ++kvb) {
-            const int4 v4 = *(const int4 *)(sv + V_BYTES + (kvb * 16 + 4 * g4) * 4);
-            pk[kvb][0] = v4.x; pk[kvb][1] = v4.y; pk[kvb][2] = v4.z; pk[kvb][3] = v4.w;
+            // straight from the position array (L2-resident) into registers, ahead of this phase's tile
+            // loads in the wavefront's memory-operation order; rows past the array's end read as 0 and
+            // are keys past the tile's end, which the ragged-tile path below cuts
+            typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+            const u32x4 v4 = __builtin_amdgcn_raw_buffer_load_b128(rp, (mt0.row_start + kvb * 16 + 4 * g4) * 4, 0, 0);
+            pk[kvb][0] = (int)v4[0]; pk[kvb][1] = (int)v4[1]; pk[kvb][2] = (int)v4[2]; pk[kvb][3] = (int)v4[3];
         }
-        if (t2 < t_end) issue_loads(t2, (i + 2) % NST);        // after the position reads: nothing in flight aliases them
+        if (t + 2 < t_end) issue_loads(mt2, (i + 2) % NST);        // after the position reads: nothing in flight aliases them
         // S^T blocks: sacc[qb][kvb] = K[kvb] Q[qb]^T  (16 keys x 16 queries)
 #pragma unroll
         for (int kvb = 0; kvb < 4; ++kvb) {
@@ -326,24 +381,24 @@ __global__ __launch_bounds__(512) void attn_bf16_kernel(AttnBf16Params p) {
         // O^T += V^T(i-1) P^T(i-1).  Step s covers keys 32s..32s+31; k-slot (g4, j) of both operands is
         // key 32s + 16(j/4) + 4 g4 + j%4, i.e. accumulator register j%4 of block 2s + j/4.
         if (have_prev) {
-            const unsigned char *pv = smem + prev_stage * STAGE + K_BYTES + l16 * 128 + 8 * (g4 & 1);
+            const unsigned char *pv = smem + prev_stage * STAGE + K_BYTES + l16 * 128;
 #pragma unroll
             for (int s2 = 0; s2 < 2; ++s2) {
                 if (pskip[s2]) continue;
-                const int c_lo = ((4 * s2 + (g4 >> 1)) ^ v_swz) * 16, c_hi = ((4 * s2 + 2 + (g4 >> 1)) ^ v_swz) * 16;
+                const int cv = ((4 * s2 + g4) ^ v_swz) * 16;
 #pragma unroll
                 for (int db = 0; db < DB; ++db) {
-                    const bf16x4 lo = *(const bf16x4 *)(pv + db * 16 * 128 + c_lo);
-                    const bf16x4 hi = *(const bf16x4 *)(pv + db * 16 * 128 + c_hi);
-                    const bf16x8 vf = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                    const bf16x8 vf = *(const bf16x8 *)(pv + db * 16 * 128 + cv);
 #pragma unroll
                     for (int qb = 0; qb < TQ; ++qb)
                         oacc[qb][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf[qb][s2], oacc[qb][db], 0, 0, 0);
                 }
             }
         }
-        if (group == 1) { if (t1 < t_end && t2 < t_end) phase_barrier<LPT, true>(); else phase_barrier<0, true>(); }
+        ATRACE(i, 3);
+        if (group == 1) { if (t + 2 < t_end) phase_barrier<LPT, true>(); else phase_barrier<0, true>(); }
         else phase_barrier<-1, true>();
+        ATRACE(i, 4);
 
         // ================= Y(i): vector phase
         if (kn < KV_TILE) {                            // ragged tile: keys past its end are never visible
@@ -373,11 +428,17 @@ __global__ __launch_bounds__(512) void attn_bf16_kernel(AttnBf16Params p) {
                 if (!(skipm & (1 << kvb)))
 #pragma unroll
                     for (int r = 0; r < 4; ++r) mx = fmaxf(mx, sacc[qb][kvb][r]);
-            mx = xor_max_16_32(mx);
-            const float m_new = fmaxf(m_run[qb], mx * p.scale_log2);
-            const float m_sub = (m_new == -INFINITY) ? 0.f : m_new;
-            const float alpha = __builtin_amdgcn_exp2f(m_run[qb] - m_sub);
-            m_run[qb] = m_new;
+            mx = xor_max_16_32(mx) * p.scale_log2;
+            m_top[qb] = fmaxf(m_top[qb], mx);
+            if (__builtin_amdgcn_readfirstlane(__any(mx > m_run[qb] + RESCALE_LOG2))) {
+                const float m_new = fmaxf(m_run[qb], mx);
+                const float alpha = __builtin_amdgcn_exp2f(m_run[qb] - ((m_new == -INFINITY) ? 0.f : m_new));
+                m_run[qb] = m_new;
+                l_run[qb] *= alpha;
+#pragma unroll
+                for (int db = 0; db < DB; ++db) oacc[qb][db] *= alpha;
+            }
+            const float m_sub = (m_run[qb] == -INFINITY) ? 0.f : m_run[qb];
             float psum = 0.f;
 #pragma unroll
             for (int kvb = 0; kvb < 4; ++kvb) {
@@ -389,11 +450,7 @@ __global__ __launch_bounds__(512) void attn_bf16_kernel(AttnBf16Params p) {
                     psum += pv;
                 }
             }
-            l_run[qb] = l_run[qb] * alpha + psum;
-            if (__builtin_amdgcn_readfirstlane(__any(alpha != 1.0f))) {     // rescale only when some maximum moved
-#pragma unroll
-                for (int db = 0; db < DB; ++db) oacc[qb][db] *= alpha;
-            }
+            l_run[qb] += psum;
 #pragma unroll
             for (int s2 = 0; s2 < 2; ++s2)
 #pragma unroll
@@ -406,24 +463,22 @@ __global__ __launch_bounds__(512) void attn_bf16_kernel(AttnBf16Params p) {
         pskip[1] = (skipm & 12) == 12;
         prev_stage = stage;
         have_prev = true;
-        if (group == 0) { if (t1 < t_end && t2 < t_end) phase_barrier<LPT, false>(); else phase_barrier<0, false>(); }
+        ATRACE(i, 6);
+        if (group == 0) { if (t + 2 < t_end) phase_barrier<LPT, false>(); else phase_barrier<0, false>(); }
         else phase_barrier<-1, false>();
-        t0 = t1; t1 = t2;
-        t2 = t1 < t_end ? next_tile(t1 + 1) : t_end;
+        mt0 = mt1; mt1 = mt2; mt2 = mt3;
     }
     if (group == 0) phase_barrier<-1, false>();        // both groups have now passed the same number of barriers
     // the trailing P V product of the last tile
     if (have_prev) {
-        const unsigned char *pv = smem + prev_stage * STAGE + K_BYTES + l16 * 128 + 8 * (g4 & 1);
+        const unsigned char *pv = smem + prev_stage * STAGE + K_BYTES + l16 * 128;
 #pragma unroll
         for (int s2 = 0; s2 < 2; ++s2) {
             if (pskip[s2]) continue;
-            const int c_lo = ((4 * s2 + (g4 >> 1)) ^ v_swz) * 16, c_hi = ((4 * s2 + 2 + (g4 >> 1)) ^ v_swz) * 16;
+            const int cv = ((4 * s2 + g4) ^ v_swz) * 16;
 #pragma unroll
             for (int db = 0; db < DB; ++db) {
-                const bf16x4 lo = *(const bf16x4 *)(pv + db * 16 * 128 + c_lo);
-                const bf16x4 hi = *(const bf16x4 *)(pv + db * 16 * 128 + c_hi);
-                const bf16x8 vf = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                const bf16x8 vf = *(const bf16x8 *)(pv + db * 16 * 128 + cv);
 #pragma unroll
                 for (int qb = 0; qb < TQ; ++qb)
                     oacc[qb][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf[qb][s2], oacc[qb][db], 0, 0, 0);
@@ -447,11 +502,13 @@ __global__ __launch_bounds__(512) void attn_bf16_kernel(AttnBf16Params p) {
             }
         } else {
             const int64_t me = (((int64_t)b * p.H + h) * p.S + kk) * p.N + r;
+            // refer the sum and the unnormalised output to the true maximum
+            const float corr = m_top[qb] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m_run[qb] - m_top[qb]);
             if (g4 == 0) {
-                p.m[me] = m_run[qb] * LN2;
-                p.e[me] = l_tot;
+                p.m[me] = m_top[qb] * LN2;
+                p.e[me] = l_tot * corr;
             }
-            const float f = p.u_mode == CASCADE_U_NORMALISED ? inv : 1.0f;
+            const float f = p.u_mode == CASCADE_U_NORMALISED ? inv : corr;
             float *up = p.u + ((((int64_t)b * p.S + kk) * p.H + h) * p.N + r) * D + 4 * g4;
 #pragma unroll
             for (int db = 0; db < DB; ++db) *(f32x4 *)(up + 16 * db) = oacc[qb][db] * f;
@@ -459,10 +516,28 @@ __global__ __launch_bounds__(512) void attn_bf16_kernel(AttnBf16Params p) {
     }
 }
 
+// K rows into packed order (callers whose K is in original row order): 16 bytes per thread.
+template <int D>
+__global__ __launch_bounds__(256) void kgather_kernel(const bf16_t *__restrict__ k, bf16_t *__restrict__ kp,
+                                                      int64_t ks_b, int64_t ks_h, int64_t ks_n, int N, int Hkv,
+                                                      const int32_t *__restrict__ rowmap) {
+    constexpr int CPR = D / 8;
+    const int g = blockIdx.y, b = blockIdx.z;
+    const int64_t id = blockIdx.x * 256ll + threadIdx.x;
+    const int r = (int)(id / CPR), ch = (int)(id % CPR);
+    if (r >= N) return;
+    const bf16x8 val = *(const bf16x8 *)(k + b * ks_b + g * ks_h + (int64_t)rowmap[r] * ks_n + ch * 8);
+    *(bf16x8 *)(kp + (((int64_t)b * Hkv + g) * N + r) * D + ch * 8) = val;
+}
+
 static int32_t npad_of(const cascade_plan *p) { return std::max(1, plan_tiles(p, KV_TILE).count) * KV_TILE; }
 
-size_t attn_bf16_workspace_bytes(const cascade_plan *p, int32_t B, int32_t Hkv, int32_t d) {
+// V^T (tile order, padded) followed by room for K gathered into packed order
+static size_t vt_bytes_of(const cascade_plan *p, int32_t B, int32_t Hkv, int32_t d) {
     return align_up((size_t)B * Hkv * d * npad_of(p) * 2, 256);
+}
+size_t attn_bf16_workspace_bytes(const cascade_plan *p, int32_t B, int32_t Hkv, int32_t d) {
+    return vt_bytes_of(p, B, Hkv, d) + align_up((size_t)B * Hkv * p->seq_len * d * 2, 256);
 }
 
 template <int D>
@@ -487,12 +562,20 @@ static int32_t launch_attn_cfg(const cascade_plan *p, const AttnArgs &a, hipStre
     AttnBf16Params k;
     k.q = (const bf16_t *)a.q; k.k = (const bf16_t *)a.k; k.vt = vt;
     k.qs_b = a.qs_b; k.qs_h = a.qs_h; k.qs_n = a.qs_n; k.ks_b = a.ks_b; k.ks_h = a.ks_h; k.ks_n = a.ks_n;
+    if (a.kv_rowmap) {
+        bf16_t *kp = (bf16_t *)((unsigned char *)a.workspace + vt_bytes_of(p, a.B, a.Hkv, D));
+        dim3 grid((unsigned)(((int64_t)N * (D / 8) + 255) / 256), a.Hkv, a.B);
+        hipLaunchKernelGGL(kgather_kernel<D>, grid, dim3(256), 0, s, (const bf16_t *)a.k, kp, a.ks_b, a.ks_h, a.ks_n,
+                           N, a.Hkv, a.kv_rowmap);
+        CASCADE_HIP_TRY(hipGetLastError());
+        k.k = kp; k.ks_n = D; k.ks_h = (int64_t)N * D; k.ks_b = (int64_t)a.Hkv * N * D;
+    }
     k.vts_b = (int64_t)a.Hkv * D * npad; k.vts_h = (int64_t)D * npad; k.npad = npad;
-    const int64_t kb = ((int64_t)(N - 1) * a.ks_n + D) * 2, vb = (int64_t)D * npad * 2;
+    const int64_t kb = ((int64_t)(N - 1) * k.ks_n + D) * 2, vb = (int64_t)D * npad * 2;
     if (kb >= (int64_t)OOB_OFF || vb >= (int64_t)OOB_OFF) return CASCADE_EUNSUPPORTED;
     k.k_bytes = (uint32_t)kb; k.vt_bytes = (uint32_t)vb;
-    k.q_rowmap = a.q_rowmap; k.kv_rowmap = a.kv_rowmap;
-    k.qtiles = ql.dev; k.kvtiles = kl.dev; k.kv_shard_first = kl.shard_first; k.n_kvtiles = kl.count;
+    k.q_rowmap = a.q_rowmap;
+    k.qtiles = ql.dev; k.kvtiles = a.fused ? kl.dev_by_pmin : kl.dev; k.kv_shard_first = kl.shard_first; k.n_kvtiles = kl.count;
     k.pos_packed = p->pos_packed_d;
     k.B = a.B; k.H = a.H; k.Hkv = a.Hkv; k.N = N; k.S = S;
     k.scale_log2 = a.scale * LOG2E;
@@ -500,7 +583,7 @@ static int32_t launch_attn_cfg(const cascade_plan *p, const AttnArgs &a, hipStre
     k.m = a.m; k.e = a.e; k.u = a.u; k.o = (bf16_t *)a.o; k.o_ld = a.o_ld; k.o_rowmap = a.o_rowmap;
     k.hpb = hpb;
 
-    constexpr int lds = 4 * (KV_TILE * D * 2 + D * 128 + KV_TILE * 4);
+    constexpr int lds = 4 * (KV_TILE * D * 2 + D * 128);
     auto kern = attn_bf16_kernel<D>;
     static bool attr_set = false;
     if (!attr_set) {

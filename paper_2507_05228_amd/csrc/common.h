@@ -14,7 +14,8 @@ struct CascadeTile {
     int32_t shard;       // shard id
     int32_t pmin;        // min position over the tile
     int32_t pmax;        // max position over the tile
-    int32_t pad[3];
+    int32_t index;       // index of the tile in packed order (kept when the list is reordered)
+    int32_t pad[2];
     int32_t sub_min[16];
     int32_t sub_max[16];
 };
@@ -22,7 +23,8 @@ struct CascadeTile {
 struct CascadeTileList {
     int32_t granule = 0;
     int32_t count = 0;
-    CascadeTile *dev = nullptr;
+    CascadeTile *dev = nullptr;           // packed order
+    CascadeTile *dev_by_pmin = nullptr;   // the same tiles ordered by smallest position (stable)
     int32_t *shard_first = nullptr;   // device: [n_shards + 1] first tile index of each shard
     int32_t *shard_first_host = nullptr;
 };

@@ -45,6 +45,28 @@ struct Gemm2Params {
 
 typedef __attribute__((address_space(3))) void lds_void;
 
+// Optional timeline instrumentation (build with -DCASCADE_TRACE): thread 0 of each workgroup stores the
+// constant-rate wall clock at a few points of the kernel; cascade_debug_gemm_trace copies them out.
+#ifdef CASCADE_TRACE
+#define TRACE_SLOTS 8
+#define TRACE_WGS 4096
+__device__ unsigned long long g_gemm_trace[TRACE_WGS * TRACE_SLOTS];
+#define TRACE(slot)                                                                                  \
+    do {                                                                                             \
+        if (threadIdx.x == 0 && blockIdx.x < TRACE_WGS) {                                            \
+            g_gemm_trace[blockIdx.x * TRACE_SLOTS + (slot)] = wall_clock64();                        \
+            if ((slot) == 2) g_gemm_trace[blockIdx.x * TRACE_SLOTS + 6] = clock64();                 \
+            if ((slot) == 4) g_gemm_trace[blockIdx.x * TRACE_SLOTS + 7] = clock64();                 \
+        }                                                                                            \
+    } while (0)
+extern "C" __attribute__((visibility("default"))) int cascade_debug_gemm_trace(unsigned long long *host, int n) {
+    if (n > TRACE_WGS * TRACE_SLOTS) n = TRACE_WGS * TRACE_SLOTS;
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_gemm_trace), (size_t)n * 8, 0, hipMemcpyDeviceToHost);
+}
+#else
+#define TRACE(slot) do { } while (0)
+#endif
+
 // 16 bytes per lane from a buffer straight into LDS: lane i of the wavefront lands at lds + 16 i.
 __device__ __forceinline__ void load16_to_lds(__amdgpu_buffer_rsrc_t r, unsigned char *lds, uint32_t voff) {
     __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_void *)lds, 16, voff, 0, 0, 0);
@@ -172,6 +194,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm2_kernel(Gemm2Params p) {
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm0 = (wave / WN) * WTM, wn0 = (wave % WN) * WTN;
+    TRACE(0);
 
     // workgroup -> tile: contiguous run of tiles (m fastest) per XCD
     const int total = p.tiles_m * p.tiles_n;
@@ -246,6 +269,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm2_kernel(Gemm2Params p) {
 #pragma unroll
     for (int s = 0; s < NST - 1; ++s)
         if (s < KT) issue_loads(s, s);
+    TRACE(1);
     for (int kt = 0; kt < KT; ++kt) {
         // tile kt has landed once at most the loads of the younger tiles in flight are outstanding;
         // after the barrier every wavefront is done with tile kt-1, whose stage is refilled next
@@ -253,6 +277,8 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm2_kernel(Gemm2Params p) {
         if (younger >= 2) wait_loads_and_barrier<2 * LPT>();
         else if (younger == 1) wait_loads_and_barrier<LPT>();
         else wait_loads_and_barrier<0>();
+        if (kt == 0) TRACE(2);
+        if (kt == KT / 2) TRACE(3);
         if (kt + NST - 1 < KT) issue_loads(kt + NST - 1, (kt + NST - 1) % NST);
         const unsigned char *st = smem + (kt % NST) * STAGE_BYTES;
 #pragma unroll
@@ -272,7 +298,9 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm2_kernel(Gemm2Params p) {
     }
 
     __syncthreads();                                       // everyone is done with the tile buffers
+    TRACE(4);
     gemm_epilogue<TM, TN, WTN, SWIGLU>(p, acc, smem, wave, lane, m0, wm0, wn0, nloc0, seg, seg_rows);
+    TRACE(5);
 }
 
 // ---------------------------------------------------------------------------- ping-pong variant
@@ -303,7 +331,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm3_kernel(Gemm2Params p) {
     constexpr int LPT = A_INSTR + B_INSTR;
     constexpr int A_BYTES = BM * ROWB, STAGE_BYTES = (BM + BN) * ROWB;
     static_assert(BK == 32 || BK == 64, "BK");
-    static_assert(NST >= 3 && NST <= 5 && (NST - 2) * LPT < 64, "pipeline depth");
+    static_assert(NST >= 2 && NST <= 5 && (NST - 2) * LPT < 64, "pipeline depth");
     static_assert(BM % (RPI * NW) == 0 && BN % (RPI * NW) == 0, "tile rows must split over the wavefronts");
     static_assert(WTN == 64 || WTN == 128, "epilogue assumes 64 or 128 columns per wavefront");
     static_assert(!SWIGLU || (WTN == 128 && (WTN / 2) % RPI == 0), "swiglu layout");
@@ -315,6 +343,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm3_kernel(Gemm2Params p) {
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int group = wave >> 2;                                   // wavefronts w and w+4 share a SIMD
     const int wm0 = (wave / WN) * WTM, wn0 = (wave % WN) * WTN;
+    TRACE(0);
 
     const int total = p.tiles_m * p.tiles_n;
     int tile;
@@ -398,6 +427,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm3_kernel(Gemm2Params p) {
 #pragma unroll
     for (int s = 0; s < NST - 1; ++s)
         if (s < KT) issue_loads(s);
+    TRACE(1);
     {   // tile 0 complete and visible to everyone
         const int younger = max(0, min(NST - 2, KT - 1));
         if (younger >= 3) phase_barrier<3 * LPT, false>();
@@ -405,12 +435,18 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm3_kernel(Gemm2Params p) {
         else if (younger == 1) phase_barrier<LPT, false>();
         else phase_barrier<0, false>();
     }
+    TRACE(2);
+    // With two stages a tile must be requested a whole tile period before it is read, so group 1
+    // issues its share during its compute phase (the same window in which group 0 issues in its
+    // memory phase); with three or more stages both groups issue in their memory phase.
+    if (NST == 2 && group == 1 && 1 < KT) issue_loads(1);
     if (group == 1) phase_barrier<-1, false>();                    // run one phase behind group 0
 
     for (int kt = 0; kt < KT; ++kt) {
+        if (kt == KT / 2) TRACE(3);
         // ---- memory phase: refill the stage of tile kt-1 (everyone finished reading it one barrier
         // ago), fetch this tile's operands
-        if (kt + NST - 1 < KT) issue_loads(kt + NST - 1);
+        if ((NST > 2 || group == 0) && kt + NST - 1 < KT) issue_loads(kt + NST - 1);
         const unsigned char *st = smem + (kt % NST) * STAGE_BYTES;
         bf16x8 af[KS][TM], bfr[KS][TN];
 #pragma unroll
@@ -424,6 +460,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm3_kernel(Gemm2Params p) {
         if (group == 1) WAIT_NEXT_TILE_AND_BARRIER(kt, true);
         else phase_barrier<-1, true>();
         // ---- compute phase
+        if (NST == 2 && group == 1 && kt + 2 < KT) issue_loads(kt + 2);
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
@@ -438,7 +475,9 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm3_kernel(Gemm2Params p) {
     if (group == 0) phase_barrier<-1, false>();                    // group 1 is one barrier ahead in count
 
     __syncthreads();
+    TRACE(4);
     gemm_epilogue<TM, TN, WTN, SWIGLU>(p, acc, smem, wave, lane, m0, wm0, wn0, nloc0, seg, seg_rows);
+    TRACE(5);
 }
 
 template <int BM, int BN, int WM, int WN, int BK, int NST, bool SWIGLU, bool PINGPONG = false>

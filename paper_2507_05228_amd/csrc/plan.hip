@@ -1,5 +1,6 @@
 // Shard plan: the partition of [N] (Section 5.1) as index maps and tile lists.
 // Host integer work only; the results are copied to the device once.
+#include <algorithm>
 #include <climits>
 #include <cstdlib>
 #include <cstring>
@@ -22,6 +23,7 @@ static void free_plan(cascade_plan *p) {
     if (p->pos_packed_d) (void)hipFree(p->pos_packed_d);
     for (auto &t : p->tiles) {
         if (t.dev) (void)hipFree(t.dev);
+        if (t.dev_by_pmin) (void)hipFree(t.dev_by_pmin);
         if (t.shard_first) (void)hipFree(t.shard_first);
         free(t.shard_first_host);
     }
@@ -50,6 +52,7 @@ static hipError_t build_tiles(cascade_plan *p, CascadeTileList &out, int granule
             t.row_start = r;
             t.n_rows = std::min(granule, p->offsets_h[j + 1] - r);
             t.shard = j;
+            t.index = (int32_t)tiles.size();
             t.pmin = INT_MAX;
             t.pmax = INT_MIN;
             for (int g = 0; g < 16; ++g) { t.sub_min[g] = INT_MAX; t.sub_max[g] = INT_MIN; }
@@ -71,6 +74,10 @@ static hipError_t build_tiles(cascade_plan *p, CascadeTileList &out, int granule
     if (!out.shard_first_host) return hipErrorOutOfMemory;
     memcpy(out.shard_first_host, first.data(), first.size() * sizeof(int32_t));
     hipError_t e = to_device(&out.dev, tiles.data(), tiles.size());
+    if (e != hipSuccess) return e;
+    std::vector<CascadeTile> sorted(tiles);
+    std::stable_sort(sorted.begin(), sorted.end(), [](const CascadeTile &x, const CascadeTile &y) { return x.pmin < y.pmin; });
+    e = to_device(&out.dev_by_pmin, sorted.data(), sorted.size());
     if (e != hipSuccess) return e;
     return to_device(&out.shard_first, first.data(), first.size());
 }
