@@ -24,6 +24,7 @@
 // that are fully visible skip the compare.
 #include <climits>
 #include <cstdlib>
+#include <type_traits>
 #include "common.h"
 #include "device_utils.h"
 
@@ -163,7 +164,7 @@ __global__ __launch_bounds__(512) void attn_bf16_kernel(AttnBf16Params p) {
     constexpr int K_RPI = 1024 / K_ROW;                // K rows filled by one direct-to-LDS instruction
     constexpr int K_CPR = K_ROW / 16;                  // 16-byte chunks per K row
     constexpr int K_BYTES = KV_TILE * K_ROW, V_BYTES = D * 128;
-    constexpr int STAGE = K_BYTES + V_BYTES;
+    constexpr int STAGE = K_BYTES + V_BYTES + KV_TILE * 4;   // K tile, V^T tile, key positions
     constexpr int K_INSTR = KV_TILE / K_RPI / 8;       // per wavefront (8 wavefronts): 2 (D=128) or 1 (D=64)
     constexpr int V_INSTR = D / 8 / 8;                 // 2 or 1
 
@@ -228,16 +229,24 @@ __global__ __launch_bounds__(512) void attn_bf16_kernel(AttnBf16Params p) {
         }
         t_end = t_begin + __builtin_amdgcn_readfirstlane(n);
     }
-    // Tile metadata lives in scalar registers and is fetched three tiles ahead of its use, so the
-    // latency of the scalar loads never sits on the critical path of a phase.
+    // Tile metadata lives in scalar registers and is fetched ahead of its use (what the tile loads
+    // need three tiles ahead, the block bounds one tile ahead), so the latency of the scalar loads
+    // never sits on the critical path of a phase.
     struct TileMeta {
         int row_start, n_rows, index;                  // index: column block of V^T
+    };
+    struct TileBounds {
         int smin[4], smax[4];                          // position bounds of the four 16-key blocks
     };
     auto load_meta = [&](int t) {
         TileMeta m;
         const tile_cptr tp = kvtiles + t;
         m.row_start = tp->row_start; m.n_rows = tp->n_rows; m.index = tp->index;
+        return m;
+    };
+    auto load_bounds = [&](int t) {
+        TileBounds m;
+        const tile_cptr tp = kvtiles + t;
 #pragma unroll
         for (int kvb = 0; kvb < 4; ++kvb) { m.smin[kvb] = tp->sub_min[kvb]; m.smax[kvb] = tp->sub_max[kvb]; }
         return m;
@@ -253,27 +262,37 @@ __global__ __launch_bounds__(512) void attn_bf16_kernel(AttnBf16Params p) {
     // Direct-to-LDS loads of one tile.  K instruction i of this wavefront fills K rows
     // (wave*K_INSTR + i)*K_RPI ..: lane -> row lane/K_CPR, slot lane%K_CPR holding chunk slot^swz(row).
     // V^T instruction i fills V^T rows (wave*V_INSTR + i)*8 ..: lane -> row lane/8, slot lane%8.
+    // The lane-dependent part of every offset is fixed for the whole kernel (32-bit: the launcher
+    // checks that a (batch, kv head) slice stays below 2 GiB); a tile adds a scalar.
+    uint32_t k_lane[K_INSTR], v_lane[V_INSTR];
+    int k_rr[K_INSTR];
+#pragma unroll
+    for (int i = 0; i < K_INSTR; ++i) {
+        const int rr = (wave * K_INSTR + i) * K_RPI + lane / K_CPR;
+        const int slot = lane % K_CPR;
+        const int c = D == 128 ? (slot ^ (rr & 15)) : (slot ^ ((rr >> 1) & 7));
+        k_rr[i] = rr;
+        k_lane[i] = (uint32_t)rr * (uint32_t)(p.ks_n * 2) + c * 16;
+    }
+#pragma unroll
+    for (int i = 0; i < V_INSTR; ++i) {
+        const int rr = (wave * V_INSTR + i) * 8 + (lane >> 3);
+        const int c = (lane & 7) ^ ((rr >> 1) & 7);
+        v_lane[i] = (uint32_t)rr * (uint32_t)(p.npad * 2) + c * 16;
+    }
     auto issue_loads = [&](const TileMeta &tm, int stage) {
-        const int row_start = tm.row_start, n_rows = tm.n_rows;
         unsigned char *sk = smem + stage * STAGE;
         unsigned char *sv = sk + K_BYTES;
+        const uint32_t k_tile = (uint32_t)tm.row_start * (uint32_t)(p.ks_n * 2);   // K is in packed row order here
+        const uint32_t v_tile = (uint32_t)tm.index * (KV_TILE * 2);
 #pragma unroll
-        for (int i = 0; i < K_INSTR; ++i) {
-            const int row0 = (wave * K_INSTR + i) * K_RPI;
-            const int rr = row0 + lane / K_CPR;
-            const int slot = lane % K_CPR;
-            const int c = D == 128 ? (slot ^ (rr & 15)) : (slot ^ ((rr >> 1) & 7));
-            // K is in packed row order here (the launcher gathers it first when the caller's is not)
-            const uint32_t off = rr < n_rows ? (uint32_t)((int64_t)(row_start + rr) * p.ks_n * 2) + c * 16 : OOB_OFF;
-            load16_to_lds(rk, sk + row0 * K_ROW, off);
-        }
+        for (int i = 0; i < K_INSTR; ++i)
+            load16_to_lds(rk, sk + (wave * K_INSTR + i) * K_RPI * K_ROW, k_rr[i] < tm.n_rows ? k_tile + k_lane[i] : OOB_OFF);
 #pragma unroll
-        for (int i = 0; i < V_INSTR; ++i) {
-            const int row0 = (wave * V_INSTR + i) * 8;
-            const int rr = row0 + (lane >> 3);
-            const int c = (lane & 7) ^ ((rr >> 1) & 7);
-            load16_to_lds(rv, sv + row0 * 128, (uint32_t)(((int64_t)rr * p.npad + (int64_t)tm.index * KV_TILE) * 2) + c * 16);
-        }
+        for (int i = 0; i < V_INSTR; ++i)
+            load16_to_lds(rv, sv + (wave * V_INSTR + i) * 8 * 128, v_tile + v_lane[i]);
+        // every wavefront writes the same 64 positions: keeps the loads-per-tile count uniform
+        load4_to_lds(rp, sv + V_BYTES, lane < tm.n_rows ? (uint32_t)(tm.row_start + lane) * 4 : OOB_OFF);
     };
 
     f32x4 oacc[TQ][DB];
@@ -297,71 +316,60 @@ __global__ __launch_bounds__(512) void attn_bf16_kernel(AttnBf16Params p) {
     const int k_swz = D == 128 ? l16 : (l16 >> 1);
     const int v_swz = l16 >> 1;
 
-    // ---- main loop, ping-pong schedule.  The 8 wavefronts form two groups of 4 (wavefronts w and
-    // w+4 share a SIMD).  Each visible tile i is handled in two phases separated by workgroup
-    // barriers:
-    //   X(i)  matrix phase : S^T(i) = K(i) Q^T  and  O^T += V^T(i-1) P^T(i-1)   (LDS reads + MFMAs)
-    //   Y(i)  vector phase : mask, row max, exponentials -> P(i); rescale O     (VALU only)
-    // Group 1 runs one phase behind group 0, so on each SIMD one wavefront is in a matrix phase while
-    // the other is in a vector phase.  The P V product trails by one tile, which is what lets a matrix
-    // phase be pure MFMA work.  Tiles are NST = 4 stages deep in LDS; the loads of tile i+2 are
-    // issued at the start of X(i) (its stage held tile i-2, whose V^T was last read in X(i-1), which
-    // both groups have left by then).  Before every odd global barrier (end of group 0's Y(i) and of
-    // group 1's X(i)) each wavefront waits for its own loads of tile i+1, so the tile is complete
-    // when group 0 enters X(i+1).
+    // ---- main loop, skewed schedule.  The 8 wavefronts form two groups of 4 (wavefronts w and w+4
+    // share a SIMD).  Each visible tile i takes a matrix phase and a vector phase:
+    //   X(i)  S^T(i) = K(i) Q^T  and  O^T += V^T(i-1) P^T(i-1)        (LDS reads + MFMAs)
+    //   Y(i)  mask, row max, exponentials -> P(i); rescale O           (VALU only)
+    // and there is one workgroup barrier per tile.  Between barriers i and i+1 group 0 runs X(i), Y(i)
+    // and group 1 runs Y(i-1), X(i): on each SIMD one wavefront is in a matrix phase while the other is
+    // in a vector phase, without a second barrier to enforce it.  The P V product trails by one tile,
+    // so a matrix phase never waits for the exponentials of its own tile.
+    // Tiles are NST = 4 stages deep in LDS.  The loads of tile i+2 are issued in X(i), i.e. after
+    // barrier i, which every wavefront reaches only after its X(i-1): the stage they overwrite held
+    // tile i-2, whose K was last read in X(i-2) and whose V^T in X(i-1).  Before barrier i+1 each
+    // wavefront waits for its own loads of tile i+1, so the tile is complete when X(i+1) starts.
     constexpr int NST = 4;
-    constexpr int LPT = K_INSTR + V_INSTR;             // direct-to-LDS loads per tile per wavefront
+    constexpr int LPT = K_INSTR + V_INSTR + 1;         // direct-to-LDS loads per tile per wavefront
     const int group = wave >> 2;
     int t = t_begin;                                   // tile i
     TileMeta mt0 = {}, mt1 = {}, mt2 = {};             // tiles i, i+1, i+2
     if (t < t_end) mt0 = load_meta(t);
     if (t + 1 < t_end) mt1 = load_meta(t + 1);
     if (t + 2 < t_end) mt2 = load_meta(t + 2);
+    TileBounds bd0 = {}, bd1 = {};                     // tiles i, i+1
+    if (t < t_end) bd0 = load_bounds(t);
     if (t < t_end) issue_loads(mt0, 0);
     if (t + 1 < t_end) issue_loads(mt1, 1);
-    if (t + 1 < t_end) phase_barrier<LPT, false>();    // tile 0 complete and visible
+    if (t + 1 < t_end) phase_barrier<LPT, false>();    // barrier 0: tile 0 complete and visible
     else phase_barrier<0, false>();
-    if (group == 1) phase_barrier<-1, false>();        // run one phase behind group 0
 
-    f32x4 sacc[TQ][4];
-    bf16x8 pf[TQ][2];                                  // P^T operands of the previous tile
-    bool pskip[2] = {true, true};                      // previous tile: both 16-key blocks of step s skipped
-    int prev_stage = 0;
-    bool have_prev = false;
+    f32x4 sacc[TQ][4];                                 // S^T of the tile between its X and its Y
+    bf16x8 pf[TQ][2];                                  // P^T operands of the tile whose P V product is pending
+    int n_act = 0, maskm = 0, kn = KV_TILE;            // of the tile held in sacc
+    int y_stage = 0;                                   // its stage
+    int n_pv = 0;                                      // 32-key steps of the pending P V product that hold non-zero P
 
-    for (int i = 0; t < t_end; ++i, ++t) {
-        const int stage = i % NST;
-        ATRACE(i, 0);
-        TileMeta mt3 = mt2;
-        if (t + 3 < t_end) mt3 = load_meta(t + 3);
-        // ================= X(i): matrix phase
-        const int kn = mt0.n_rows;
-        const unsigned char *sk = smem + stage * STAGE;
-        const unsigned char *sv = sk + K_BYTES;
-        // per 16-key block: can this wavefront skip it / does it need the element-wise compare
-        int skipm = 0, maskm = 0;
+    auto pv_steps = [&](auto ns_tag, int stg) {
+        constexpr int NS = decltype(ns_tag)::value;
+        const unsigned char *pv = smem + stg * STAGE + K_BYTES + l16 * 128;
 #pragma unroll
-        for (int kvb = 0; kvb < 4; ++kvb) {
-            const int kmin = mt0.smin[kvb], kmax = mt0.smax[kvb];
-            skipm |= (int)((kvb * 16 >= kn) | (kmin > wq_hi)) << kvb;
-            maskm |= (int)((kvb * 16 + 16 > kn) | (kmax > wq_lo)) << kvb;
+        for (int s2 = 0; s2 < NS; ++s2) {
+            const int cv = ((4 * s2 + g4) ^ v_swz) * 16;
+#pragma unroll
+            for (int db = 0; db < DB; ++db) {
+                const bf16x8 vf = *(const bf16x8 *)(pv + db * 16 * 128 + cv);
+#pragma unroll
+                for (int qb = 0; qb < TQ; ++qb)
+                    oacc[qb][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf[qb][s2], oacc[qb][db], 0, 0, 0);
+            }
         }
-        // key positions of this lane's accumulator rows (keys 16 kvb + 4 g4 + 0..3)
-        int pk[4][4];
+    };
+    // S^T blocks: sacc[qb][kvb] = K[kvb] Q[qb]^T (16 keys x 16 queries) for the first NA blocks, zeros beyond
+    auto qk_blocks = [&](auto na_tag, const unsigned char *sk) {
+        constexpr int NA = decltype(na_tag)::value;
 #pragma unroll
         for (int kvb = 0; kvb < 4; ++kvb) {
-            // straight from the position array (L2-resident) into registers, ahead of this phase's tile
-            // loads in the wavefront's memory-operation order; rows past the array's end read as 0 and
-            // are keys past the tile's end, which the ragged-tile path below cuts
-            typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
-            const u32x4 v4 = __builtin_amdgcn_raw_buffer_load_b128(rp, (mt0.row_start + kvb * 16 + 4 * g4) * 4, 0, 0);
-            pk[kvb][0] = (int)v4[0]; pk[kvb][1] = (int)v4[1]; pk[kvb][2] = (int)v4[2]; pk[kvb][3] = (int)v4[3];
-        }
-        if (t + 2 < t_end) issue_loads(mt2, (i + 2) % NST);        // after the position reads: nothing in flight aliases them
-        // S^T blocks: sacc[qb][kvb] = K[kvb] Q[qb]^T  (16 keys x 16 queries)
-#pragma unroll
-        for (int kvb = 0; kvb < 4; ++kvb) {
-            if (skipm & (1 << kvb)) {                  // contributes exact zeros to P
+            if (kvb >= NA) {
 #pragma unroll
                 for (int qb = 0; qb < TQ; ++qb) sacc[qb][kvb] = zero4;
                 continue;
@@ -371,36 +379,70 @@ __global__ __launch_bounds__(512) void attn_bf16_kernel(AttnBf16Params p) {
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) kf[ks] = *(const bf16x8 *)(kp + (((4 * ks + g4) ^ k_swz) * 16));
 #pragma unroll
-            for (int qb = 0; qb < TQ; ++qb) {
-                sacc[qb][kvb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[0], qf[qb][0], zero4, 0, 0, 0);
+            for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
-                for (int ks = 1; ks < KS; ++ks)
-                    sacc[qb][kvb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[ks], qf[qb][ks], sacc[qb][kvb], 0, 0, 0);
-            }
+                for (int qb = 0; qb < TQ; ++qb)
+                    sacc[qb][kvb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[ks], qf[qb][ks],
+                                                                            ks == 0 ? zero4 : sacc[qb][kvb], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);         // keeps at most one block's operands in registers
         }
+    };
+
+    // ================= X(i): matrix phase
+    auto matrix_phase = [&](int i) {
+        const int stage = i % NST;
+        const unsigned char *sk = smem + stage * STAGE;
+        y_stage = stage;
+        if (t + 2 < t_end) issue_loads(mt2, (i + 2) % NST);
         // O^T += V^T(i-1) P^T(i-1).  Step s covers keys 32s..32s+31; k-slot (g4, j) of both operands is
         // key 32s + 16(j/4) + 4 g4 + j%4, i.e. accumulator register j%4 of block 2s + j/4.
-        if (have_prev) {
-            const unsigned char *pv = smem + prev_stage * STAGE + K_BYTES + l16 * 128;
+        const int prev_stage = (i + NST - 1) % NST;
+        if (n_pv == 2) pv_steps(std::integral_constant<int, 2>(), prev_stage);
+        else if (n_pv == 1) pv_steps(std::integral_constant<int, 1>(), prev_stage);
+        __builtin_amdgcn_sched_barrier(0);
+        // per 16-key block: can this wavefront skip it / does it need the element-wise compare
+        kn = mt0.n_rows;
+        int skipm = 0;
+        maskm = 0;
 #pragma unroll
-            for (int s2 = 0; s2 < 2; ++s2) {
-                if (pskip[s2]) continue;
-                const int cv = ((4 * s2 + g4) ^ v_swz) * 16;
-#pragma unroll
-                for (int db = 0; db < DB; ++db) {
-                    const bf16x8 vf = *(const bf16x8 *)(pv + db * 16 * 128 + cv);
-#pragma unroll
-                    for (int qb = 0; qb < TQ; ++qb)
-                        oacc[qb][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf[qb][s2], oacc[qb][db], 0, 0, 0);
-                }
-            }
+        for (int kvb = 0; kvb < 4; ++kvb) {
+            const int kmin = bd0.smin[kvb], kmax = bd0.smax[kvb];
+            skipm |= (int)((kvb * 16 >= kn) | (kmin > wq_hi)) << kvb;
+            maskm |= (int)((kvb * 16 + 16 > kn) | (kmax > wq_lo)) << kvb;
         }
-        ATRACE(i, 3);
-        if (group == 1) { if (t + 2 < t_end) phase_barrier<LPT, true>(); else phase_barrier<0, true>(); }
-        else phase_barrier<-1, true>();
-        ATRACE(i, 4);
+        // Positions ascend along a tile, so the blocks this wavefront cannot see are the trailing ones:
+        // blocks [0, n_act) are computed (one below n_act that could have been skipped is cut by the
+        // element-wise compare instead), blocks [n_act, 4) contribute exact zeros to P.
+        n_act = (~skipm & 15) ? 32 - __builtin_clz(~skipm & 15) : 0;
+        switch (n_act) {
+            case 4: qk_blocks(std::integral_constant<int, 4>(), sk); break;
+            case 3: qk_blocks(std::integral_constant<int, 3>(), sk); break;
+            case 2: qk_blocks(std::integral_constant<int, 2>(), sk); break;
+            case 1: qk_blocks(std::integral_constant<int, 1>(), sk); break;
+            default: qk_blocks(std::integral_constant<int, 0>(), sk);
+        }
+    };
 
-        // ================= Y(i): vector phase
+    // ================= Y(i): vector phase on the tile held in sacc
+    auto vector_phase = [&]() {
+        // Key positions of this lane's accumulator rows (keys 16 kvb + 4 g4 + 0..3), from the tile's
+        // stage.  Read in assembly, wait included: the compiler would otherwise order a typed LDS read
+        // after every tile load in flight, and the registers are needed only from here on.
+        typedef __attribute__((ext_vector_type(4))) int i32x4;
+        i32x4 pkv[4];
+        {
+            const uint32_t pa = (uint32_t)(uintptr_t)(lds_void *)(smem + y_stage * STAGE + K_BYTES + V_BYTES) + 16 * g4;
+            asm volatile("ds_read_b128 %0, %4\n\tds_read_b128 %1, %4 offset:64\n\tds_read_b128 %2, %4 offset:128\n\t"
+                         "ds_read_b128 %3, %4 offset:192\n\ts_waitcnt lgkmcnt(0)"
+                         : "=&v"(pkv[0]), "=&v"(pkv[1]), "=&v"(pkv[2]), "=&v"(pkv[3])
+                         : "v"(pa)
+                         : "memory");
+        }
+        int pk[4][4];
+#pragma unroll
+        for (int kvb = 0; kvb < 4; ++kvb)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) pk[kvb][r] = pkv[kvb][r];
         if (kn < KV_TILE) {                            // ragged tile: keys past its end are never visible
 #pragma unroll
             for (int kvb = 0; kvb < 4; ++kvb)
@@ -412,7 +454,7 @@ __global__ __launch_bounds__(512) void attn_bf16_kernel(AttnBf16Params p) {
         // INT_MAX - 1, so only the keys past a ragged tile's end (position INT_MAX) are cut.
 #pragma unroll
         for (int kvb = 0; kvb < 4; ++kvb) {
-            if (!(maskm & ~skipm & (1 << kvb))) continue;
+            if (kvb >= n_act || !(maskm & (1 << kvb))) continue;
 #pragma unroll
             for (int qb = 0; qb < TQ; ++qb)
 #pragma unroll
@@ -425,7 +467,7 @@ __global__ __launch_bounds__(512) void attn_bf16_kernel(AttnBf16Params p) {
             float mx = -INFINITY;
 #pragma unroll
             for (int kvb = 0; kvb < 4; ++kvb)
-                if (!(skipm & (1 << kvb)))
+                if (kvb < n_act)
 #pragma unroll
                     for (int r = 0; r < 4; ++r) mx = fmaxf(mx, sacc[qb][kvb][r]);
             mx = xor_max_16_32(mx) * p.scale_log2;
@@ -442,7 +484,7 @@ __global__ __launch_bounds__(512) void attn_bf16_kernel(AttnBf16Params p) {
             float psum = 0.f;
 #pragma unroll
             for (int kvb = 0; kvb < 4; ++kvb) {
-                if (skipm & (1 << kvb)) continue;
+                if (kvb >= n_act) continue;
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     const float pv = __builtin_amdgcn_exp2f(fmaf(sacc[qb][kvb][r], p.scale_log2, -m_sub));
@@ -459,31 +501,40 @@ __global__ __launch_bounds__(512) void attn_bf16_kernel(AttnBf16Params p) {
                     pf[qb][s2][4 + j] = (bf16_t)sacc[qb][2 * s2 + 1][j];
                 }
         }
-        pskip[0] = (skipm & 3) == 3;
-        pskip[1] = (skipm & 12) == 12;
-        prev_stage = stage;
-        have_prev = true;
-        ATRACE(i, 6);
-        if (group == 0) { if (t + 2 < t_end) phase_barrier<LPT, false>(); else phase_barrier<0, false>(); }
-        else phase_barrier<-1, false>();
-        mt0 = mt1; mt1 = mt2; mt2 = mt3;
+        n_pv = (n_act + 1) >> 1;
+    };
+
+    // one loop per group: the bodies differ only in the order of the two phases
+#define ATTN_TILE_BODY(FIRST, SECOND)                                                             \
+    for (; t < t_end; ++i, ++t) {                                                                 \
+        ATRACE(i, 0);                                                                             \
+        TileMeta mt3 = mt2;                                                                       \
+        if (t + 3 < t_end) mt3 = load_meta(t + 3);                                                \
+        if (t + 1 < t_end) bd1 = load_bounds(t + 1);                                              \
+        FIRST;                                                                                    \
+        ATRACE(i, 3);                                                                             \
+        SECOND;                                                                                   \
+        ATRACE(i, 6);                                                                             \
+        /* barrier i+1: own loads of tile i+1 landed (those of tile i+2, if any, stay in flight), */ \
+        /* own operand reads of this phase returned */                                            \
+        if (t + 2 < t_end) phase_barrier<LPT, true>();                                            \
+        else phase_barrier<0, true>();                                                            \
+        mt0 = mt1; mt1 = mt2; mt2 = mt3;                                                          \
+        bd0 = bd1;                                                                                \
     }
-    if (group == 0) phase_barrier<-1, false>();        // both groups have now passed the same number of barriers
+    int i = 0;
+    if (group == 0) {
+        ATTN_TILE_BODY(matrix_phase(i), vector_phase())            // X(i), Y(i)
+    } else {
+        ATTN_TILE_BODY(if (i > 0) vector_phase(), matrix_phase(i)) // Y(i-1), X(i)
+        if (i > 0) vector_phase();                                 // Y of the last tile
+    }
+#undef ATTN_TILE_BODY
     // the trailing P V product of the last tile
-    if (have_prev) {
-        const unsigned char *pv = smem + prev_stage * STAGE + K_BYTES + l16 * 128;
-#pragma unroll
-        for (int s2 = 0; s2 < 2; ++s2) {
-            if (pskip[s2]) continue;
-            const int cv = ((4 * s2 + g4) ^ v_swz) * 16;
-#pragma unroll
-            for (int db = 0; db < DB; ++db) {
-                const bf16x8 vf = *(const bf16x8 *)(pv + db * 16 * 128 + cv);
-#pragma unroll
-                for (int qb = 0; qb < TQ; ++qb)
-                    oacc[qb][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf[qb][s2], oacc[qb][db], 0, 0, 0);
-            }
-        }
+    {
+        const int prev_stage = (i + NST - 1) % NST;
+        if (n_pv == 2) pv_steps(std::integral_constant<int, 2>(), prev_stage);
+        else if (n_pv == 1) pv_steps(std::integral_constant<int, 1>(), prev_stage);
     }
 
     // ---- write-out.  oacc[qb][db][r]: query row 16qb + l16, column 16db + 4 g4 + r.
@@ -583,7 +634,7 @@ static int32_t launch_attn_cfg(const cascade_plan *p, const AttnArgs &a, hipStre
     k.m = a.m; k.e = a.e; k.u = a.u; k.o = (bf16_t *)a.o; k.o_ld = a.o_ld; k.o_rowmap = a.o_rowmap;
     k.hpb = hpb;
 
-    constexpr int lds = 4 * (KV_TILE * D * 2 + D * 128);
+    constexpr int lds = 4 * (KV_TILE * D * 2 + D * 128 + KV_TILE * 4);
     auto kern = attn_bf16_kernel<D>;
     static bool attr_set = false;
     if (!attr_set) {
