@@ -82,7 +82,7 @@ struct AttnBf16Params {
     uint32_t k_bytes, vt_bytes;      // extent of one (batch, kv head) slice, for the buffer resources
     const int32_t *q_rowmap;
     const CascadeTile *qtiles;
-    const CascadeTile *kvtiles;      // fused: ordered by smallest position; else packed order (per-shard ranges)
+    const CascadeTile *kvtiles;      // ordered by smallest position: globally (fused) or inside each shard's range
     const int32_t *kv_shard_first;
     int32_t n_kvtiles;
     const int32_t *pos_packed;
@@ -216,8 +216,8 @@ __global__ __launch_bounds__(512) void attn_bf16_kernel(AttnBf16Params p) {
     const int wq_lo = p.causal ? min(wq_min[0], wq_min[1]) : INT_MAX;
 
     // ---- key/value tile range.  The tiles some query row of the workgroup can see (smallest key
-    // position <= largest query position) form a prefix of the range: the fused list is ordered by
-    // smallest position, and inside one shard positions ascend with the packed row.
+    // position <= largest query position) form a prefix of the range: the tile list is ordered by
+    // smallest position, over the whole sequence (fused) or inside each shard's range.
     const int t_begin = p.fused ? 0 : ((int_cptr)p.kv_shard_first)[kk];
     const int t_cap = p.fused ? p.n_kvtiles : ((int_cptr)p.kv_shard_first)[kk + 1];
     int t_end = t_cap;
@@ -410,9 +410,10 @@ __global__ __launch_bounds__(512) void attn_bf16_kernel(AttnBf16Params p) {
             skipm |= (int)((kvb * 16 >= kn) | (kmin > wq_hi)) << kvb;
             maskm |= (int)((kvb * 16 + 16 > kn) | (kmax > wq_lo)) << kvb;
         }
-        // Positions ascend along a tile, so the blocks this wavefront cannot see are the trailing ones:
-        // blocks [0, n_act) are computed (one below n_act that could have been skipped is cut by the
-        // element-wise compare instead), blocks [n_act, 4) contribute exact zeros to P.
+        // With positions ascending along a tile the blocks this wavefront cannot see are the trailing
+        // ones: blocks [0, n_act) are computed (for other position orders one below n_act that could
+        // have been skipped is cut by the element-wise compare instead), blocks [n_act, 4) contribute
+        // exact zeros to P.
         n_act = (~skipm & 15) ? 32 - __builtin_clz(~skipm & 15) : 0;
         switch (n_act) {
             case 4: qk_blocks(std::integral_constant<int, 4>(), sk); break;
@@ -626,7 +627,7 @@ static int32_t launch_attn_cfg(const cascade_plan *p, const AttnArgs &a, hipStre
     if (kb >= (int64_t)OOB_OFF || vb >= (int64_t)OOB_OFF) return CASCADE_EUNSUPPORTED;
     k.k_bytes = (uint32_t)kb; k.vt_bytes = (uint32_t)vb;
     k.q_rowmap = a.q_rowmap;
-    k.qtiles = ql.dev; k.kvtiles = a.fused ? kl.dev_by_pmin : kl.dev; k.kv_shard_first = kl.shard_first; k.n_kvtiles = kl.count;
+    k.qtiles = ql.dev; k.kvtiles = a.fused ? kl.dev_by_pmin : kl.dev_by_shard_pmin; k.kv_shard_first = kl.shard_first; k.n_kvtiles = kl.count;
     k.pos_packed = p->pos_packed_d;
     k.B = a.B; k.H = a.H; k.Hkv = a.Hkv; k.N = N; k.S = S;
     k.scale_log2 = a.scale * LOG2E;

@@ -25,6 +25,7 @@ struct CascadeTileList {
     int32_t count = 0;
     CascadeTile *dev = nullptr;           // packed order
     CascadeTile *dev_by_pmin = nullptr;   // the same tiles ordered by smallest position (stable)
+    CascadeTile *dev_by_shard_pmin = nullptr;   // packed order of shards, each shard's tiles by smallest position
     int32_t *shard_first = nullptr;   // device: [n_shards + 1] first tile index of each shard
     int32_t *shard_first_host = nullptr;
 };

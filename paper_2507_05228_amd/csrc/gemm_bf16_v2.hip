@@ -21,6 +21,7 @@
 //    ends up with 4 consecutive columns (and the 4 columns 64 further on): stores and residual
 //    reads are 128-byte runs, and the two halves of a SwiGLU pair live in one lane.
 #include <cstdlib>
+#include <type_traits>
 #include "common.h"
 #include "device_utils.h"
 #include "epilogue.h"
@@ -164,8 +165,9 @@ __device__ __forceinline__ void gemm_epilogue(const Gemm2Params &p, f32x4 (&acc)
 
 template <int N>
 __device__ __forceinline__ void wait_loads_and_barrier() {
-    // all but the N youngest vector-memory operations of this wavefront are complete, then barrier
-    asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(N) : "memory");
+    // all but the N youngest vector-memory operations of this wavefront are complete and its LDS reads
+    // have returned, then barrier
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
 }
 
 template <int BM, int BN, int WM, int WN, int BK, int NST, bool SWIGLU>
@@ -266,36 +268,64 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm2_kernel(Gemm2Params p) {
     const int frow = lane & 15, fch = lane >> 4, fsw = swz(lane & 15);
     const int a_lane = (wm0 + frow) * ROWB, b_lane = A_BYTES + (wn0 + frow) * ROWB;
     const int KT = K / BK;
+    constexpr int KS = BK / 32;
+    static_assert(KS == 2, "the operand pipeline below alternates two register sets over the two k-steps of a tile");
+    bf16x8 af[2][TM], bfr[2][TN];
+    auto fetch = [&](int kt, auto ks_tag) {                // operands of k-step ks of tile kt -> register set ks
+        constexpr int ks = decltype(ks_tag)::value;
+        const unsigned char *st = smem + (kt % NST) * STAGE_BYTES;
+        const int coff = ((4 * ks + fch) ^ fsw) * 16;
 #pragma unroll
-    for (int s = 0; s < NST - 1; ++s)
-        if (s < KT) issue_loads(s, s);
-    TRACE(1);
-    for (int kt = 0; kt < KT; ++kt) {
-        // tile kt has landed once at most the loads of the younger tiles in flight are outstanding;
-        // after the barrier every wavefront is done with tile kt-1, whose stage is refilled next
+        for (int i = 0; i < TM; ++i) af[ks][i] = *(const bf16x8 *)(st + a_lane + i * 16 * ROWB + coff);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) bfr[ks][j] = *(const bf16x8 *)(st + b_lane + j * 16 * ROWB + coff);
+    };
+    auto mfmas = [&](auto ks_tag) {
+        constexpr int ks = decltype(ks_tag)::value;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[ks][i], bfr[ks][j], acc[i][j], 0, 0, 0);
+    };
+    // Tile kt has landed once at most the loads of the younger tiles in flight are outstanding; the
+    // wavefront's own LDS reads have returned (they were of the tile whose stage is refilled next);
+    // after the barrier every wavefront is done reading tile kt-1.
+    auto tile_ready = [&](int kt) {
         const int younger = min(NST - 2, KT - 1 - kt);
         if (younger >= 2) wait_loads_and_barrier<2 * LPT>();
         else if (younger == 1) wait_loads_and_barrier<LPT>();
         else wait_loads_and_barrier<0>();
-        if (kt == 0) TRACE(2);
-        if (kt == KT / 2) TRACE(3);
         if (kt + NST - 1 < KT) issue_loads(kt + NST - 1, (kt + NST - 1) % NST);
-        const unsigned char *st = smem + (kt % NST) * STAGE_BYTES;
+    };
+    const std::integral_constant<int, 0> k0;
+    const std::integral_constant<int, 1> k1;
 #pragma unroll
-        for (int ks = 0; ks < BK / 32; ++ks) {
-            const int coff = ((4 * ks + fch) ^ fsw) * 16;
-            bf16x8 af[TM], bfr[TN];
-#pragma unroll
-            for (int i = 0; i < TM; ++i) af[i] = *(const bf16x8 *)(st + a_lane + i * 16 * ROWB + coff);
-#pragma unroll
-            for (int j = 0; j < TN; ++j) bfr[j] = *(const bf16x8 *)(st + b_lane + j * 16 * ROWB + coff);
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
-        }
+    for (int s = 0; s < NST - 1; ++s)
+        if (s < KT) issue_loads(s, s);
+    TRACE(1);
+    // Software pipeline over k-steps: the LDS reads of a k-step are in flight while the MFMAs of the
+    // previous k-step run, also across the tile boundary (the second k-step of tile kt is multiplied
+    // after the barrier that opens tile kt+1, from registers).
+    tile_ready(0);
+    TRACE(2);
+    fetch(0, k0);
+    for (int kt = 0; kt + 1 < KT; ++kt) {                  // straight-line body: the last tile is peeled
+        if (kt == KT / 2) TRACE(3);
+        fetch(kt, k1);
+        __builtin_amdgcn_sched_barrier(0);                 // reads stay ahead of the MFMAs they overlap with
+        mfmas(k0);
+        __builtin_amdgcn_sched_barrier(0);
+        tile_ready(kt + 1);
+        fetch(kt + 1, k0);
+        __builtin_amdgcn_sched_barrier(0);
+        mfmas(k1);
+        __builtin_amdgcn_sched_barrier(0);
     }
+    fetch(KT - 1, k1);
+    __builtin_amdgcn_sched_barrier(0);
+    mfmas(k0);
+    mfmas(k1);
 
     __syncthreads();                                       // everyone is done with the tile buffers
     TRACE(4);

@@ -249,6 +249,18 @@ def test_partial_attn_no_mask_and_custom_positions(cas, dtype, d):
     check_partials(dtype, got, ref)
 
 
+@pytest.mark.parametrize("d", [64, 128])
+def test_partial_attn_unordered_positions_many_tiles_per_shard(cas, d):
+    """Positions that do not ascend with the token index, shards of several key/value tiles: the
+    visible tiles of a query tile are then not a prefix of the shard in packed order."""
+    N = 640
+    pos = np.random.default_rng(11).permutation(3 * N)[:N].astype(np.int32)
+    plan, got, ref, _ = attn_case(cas, "bf16", 1, 4, 2, N, d, 2, "perm", "packed", seed=5, positions=pos)
+    check_partials("bf16", got, ref)
+    plan, got, ref, _ = attn_case(cas, "bf16", 1, 2, 2, N, d, 3, "ragged", "original", seed=6, positions=pos)
+    check_partials("bf16", got, ref)
+
+
 @pytest.mark.parametrize("dtype,d", [("f32", 32), ("bf16", 128)])
 def test_partial_attn_large_logits_are_stable(cas, dtype, d):
     plan, got, ref, _ = attn_case(cas, dtype, 1, 2, 2, 128, d, 4, "perm", "original", seed=3, amp=6.0)
@@ -352,6 +364,20 @@ def test_layer_forward_matches_oracle(cas, cfg, mode):
     assert rel_err(out, ref) < TOL[cfg.dtype]
     direct = orc.layer_direct_batch(h, w, cfg)
     assert rel_err(out, direct) < TOL[cfg.dtype]
+
+
+@pytest.mark.parametrize("mode", ["fused", "materialised"])
+def test_layer_forward_with_unordered_positions(cas, mode):
+    """Token positions that do not ascend with the token index (rotary angles and the causal mask
+    both follow them): shards hold several key/value tiles whose position ranges interleave."""
+    cfg = SMALL_LLAMA
+    attn_mode = cas.ATTN_FUSED if mode == "fused" else cas.ATTN_MATERIALISED
+    a = make_assignment(cfg.assignment, cfg.seq_len, cfg.n_shards, 78)
+    pos = np.random.default_rng(12).permutation(2 * cfg.seq_len)[:cfg.seq_len].astype(np.int32)
+    w, h = make_layer_weights(cfg), make_hidden(cfg)
+    out = cas.layer_forward_numpy(cfg, w, h, a, positions=pos, attn_mode=attn_mode)
+    ref = orc.layer_direct_batch(h, w, cfg, positions=pos)
+    assert rel_err(out, ref) < TOL[cfg.dtype]
 
 
 @pytest.mark.parametrize("cfg", [CONFIGS["C1"], SMALL_LLAMA], ids=lambda c: c.name)
