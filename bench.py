@@ -74,6 +74,40 @@ def time_steps(fn, steps):
     return (time.perf_counter() - t0) / steps
 
 
+def per_step_stats(fn, steps):
+    """Each step timed on its own with events on the current stream: median, mean, 95 % interval of the mean."""
+    import statistics
+    import torch
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    for e0, e1 in evs:
+        e0.record()
+        fn()
+        e1.record()
+    torch.cuda.synchronize()
+    ms = [e0.elapsed_time(e1) for e0, e1 in evs]
+    mean = statistics.fmean(ms)
+    half = 1.96 * statistics.stdev(ms) / len(ms) ** 0.5 if len(ms) > 1 else 0.0
+    return {"median_ms": statistics.median(ms), "mean_ms": mean, "ci95_ms": [mean - half, mean + half], "n": len(ms)}
+
+
+def measured_ceilings(cas):
+    """What this device sustains: MFMA-only kernels with random bf16 operands, and a plain device copy."""
+    import torch
+    out = {"mfma_bf16_registers_tflops": cas.cascade_mfma_ceiling(0, 200000),
+           "mfma_bf16_lds_operands_tflops": cas.cascade_mfma_ceiling(1, 200000)}
+    src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(5):
+        dst.copy_(src)
+    e1.record()
+    torch.cuda.synchronize()
+    out["copy_read_plus_write_GBs"] = 5 * 2 * (1 << 30) / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    return out
+
+
 def run_config(cas, cfg, steps, warmup, staged=True, check=False):
     import numpy as np
     import torch
@@ -97,6 +131,7 @@ def run_config(cas, cfg, steps, warmup, staged=True, check=False):
     res["tflops"] = res["flops"]["total"] / sec / 1e12
 
     if staged:
+        res["per_step"] = per_step_stats(step, max(steps, 50))
         res["stages_ms"] = staged_times(cas, plan, desc, wts, h, h_out, ws, steps)
         # materialised mode: partial attention writes m, e, u~ to HBM, the merge reads them back
         desc_m = cas.make_layer_desc(cfg, cas.ATTN_MATERIALISED, cas.ROWS_ORIGINAL)
@@ -216,7 +251,12 @@ def main():
                              "frac_of_hbm_peak": gather_bytes / (st["gather_norm1"] * 1e-3) / 1e9 / HBM_PEAK_GBS}},
         "materialised_mode": {"ms_per_step": res["sec_per_step_materialised"] * 1e3,
                               "partial_attention_ms": stm["attention"], "lse_merge_ms": stm["lse_merge"]},
+        "per_step_event_timing": res["per_step"],
     }
+    if bf16:
+        ceil = measured_ceilings(cas)
+        out["measured_ceilings"] = ceil
+        out["roofline"]["frac_of_measured_lds_fed_mfma_rate"] = dom_tflops / ceil["mfma_bf16_lds_operands_tflops"]
     if not args.no_cpu_baseline:
         base, err = cpu_baseline(cfg, res["_host"])
         out["cpu_baseline"] = base

@@ -238,6 +238,17 @@ CASCADE_API int32_t cascade_layer_forward_staged(const cascade_plan *plan, const
 CASCADE_API int32_t cascade_layer_partials(const cascade_plan *plan, const cascade_layer_desc *desc,
                                void *workspace, float **m, float **e, float **u);
 
+/* ------------------------------------------------------------------ measured ceiling
+ * Not a step of the method: the rate (TFLOP/s) this device sustains on back-to-back
+ * bf16 16x16x32 MFMAs with random operands, for the roofline figures quoted next
+ * to the datasheet peak.  lds_operands = 0: operands stay in registers;
+ * 1: operands are re-read from LDS at the shard GEMM's ratio (12 16-byte reads per
+ * 32 MFMAs).  One workgroup of 8 wavefronts per compute unit, `iters` (1..2^22)
+ * iterations of 32 MFMAs each; runs twice on `stream`, synchronises, and reports
+ * the second run.  tflops_out is a HOST pointer.  Allocates 256 bytes of device
+ * memory for the duration of the call.  Errors: EINVAL, EHIP.                    */
+CASCADE_API int32_t cascade_mfma_ceiling(int32_t lds_operands, int32_t iters, float *tflops_out, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

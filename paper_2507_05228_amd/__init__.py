@@ -27,7 +27,8 @@ EPI_BIAS, EPI_GELU_ERF, EPI_GELU_TANH, EPI_SWIGLU, EPI_ROPE, EPI_RESIDUAL = 1, 2
 EXPORTS = ["cascade_plan_create", "cascade_plan_maps", "cascade_plan_maps_host", "cascade_plan_destroy",
            "cascade_last_hip_error", "cascade_shard_gemm", "cascade_partial_attn_workspace_bytes",
            "cascade_partial_attn", "cascade_lse_merge", "cascade_layer_workspace_bytes",
-           "cascade_layer_forward", "cascade_layer_forward_staged", "cascade_layer_partials"]
+           "cascade_layer_forward", "cascade_layer_forward_staged", "cascade_layer_partials",
+           "cascade_mfma_ceiling"]
 N_STAGE_EVENTS = 10
 STAGE_NAMES = ["gather_norm1", "qkv_gemm", "rope", "attention", "lse_merge", "o_proj", "norm2", "ffn_up", "ffn_down"]
 
@@ -107,6 +108,8 @@ def load_library():
     lib.cascade_layer_forward_staged.restype = I32
     lib.cascade_layer_partials.argtypes = [VP, P(LayerDesc), VP, P(VP), P(VP), P(VP)]
     lib.cascade_layer_partials.restype = I32
+    lib.cascade_mfma_ceiling.argtypes = [I32, I32, P(C.c_float), VP]
+    lib.cascade_mfma_ceiling.restype = I32
     _lib = lib
     return lib
 
@@ -309,6 +312,15 @@ def to_device(x, dtype_name):
 def new_workspace(nbytes):
     import torch
     return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device="cuda")
+
+
+def cascade_mfma_ceiling(lds_operands, iters=200000, stream=None):
+    """TFLOP/s sustained by back-to-back bf16 MFMAs with random operands (registers or LDS-fed)."""
+    lib = load_library()
+    out = C.c_float(0.0)
+    _check(lib.cascade_mfma_ceiling(int(bool(lds_operands)), int(iters), C.byref(out), _stream(stream)),
+           "cascade_mfma_ceiling")
+    return float(out.value)
 
 
 def layer_forward_numpy(cfg, weights_np, h_np, token_to_shard, positions=None, attn_mode=ATTN_FUSED,
