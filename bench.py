@@ -194,6 +194,7 @@ def main():
     ap.add_argument("--config", default="C3", help="headline workload (C1..C5)")
     ap.add_argument("--all", action="store_true", help="also time the other bf16 configurations")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-ceilings", action="store_true", help="skip the MFMA-only and copy-only ceiling measurements")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (reference point for HBM byte counters)")
     args = ap.parse_args()
@@ -253,7 +254,7 @@ def main():
                               "partial_attention_ms": stm["attention"], "lse_merge_ms": stm["lse_merge"]},
         "per_step_event_timing": res["per_step"],
     }
-    if bf16:
+    if bf16 and not args.no_ceilings:
         ceil = measured_ceilings(cas)
         out["measured_ceilings"] = ceil
         out["roofline"]["frac_of_measured_lds_fed_mfma_rate"] = dom_tflops / ceil["mfma_bf16_lds_operands_tflops"]
