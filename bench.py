@@ -166,6 +166,35 @@ def staged_times(cas, plan, desc, wts, h, h_out, ws, steps):
     return out
 
 
+def run_m_split(cas, cfg, steps):
+    """The same layer with distinct shardings: (c, delta) row shards and their m-split as key/value
+    shards (c = 8, delta = c * n_shards, m = 2): beta = 2 alpha partials per row."""
+    import torch
+    from cascade_inputs import config_seed
+    c = 8
+    a, alpha = cas.cascade_cdelta_assignment(cfg.seq_len, c, c * cfg.n_shards)
+    kv = cas.cascade_m_split(a, alpha, 2)
+    w, h = device_inputs(cfg, config_seed(cfg))
+    plan = cas.cascade_plan_create_rs(cfg.batch, cfg.seq_len, alpha, a, 2 * alpha, kv)
+    wts = cas.make_layer_weights(w)
+    h_out = torch.empty_like(h)
+    out = {"row_shards": alpha, "kv_shards": 2 * alpha, "c": c, "delta": c * cfg.n_shards, "m": 2}
+    for name, mode in (("fused", cas.ATTN_FUSED), ("materialised", cas.ATTN_MATERIALISED)):
+        desc = cas.make_layer_desc(cfg, mode, cas.ROWS_ORIGINAL)
+        ws = cas.new_workspace(cas.cascade_layer_workspace_bytes(plan, desc))
+        step = lambda: cas.cascade_layer_forward(plan, desc, wts, h, h_out, ws)
+        for _ in range(2):
+            step()
+        out[name + "_ms_per_step"] = time_steps(step, steps) * 1e3
+        st = staged_times(cas, plan, desc, wts, h, h_out, ws, steps)
+        out[name + "_attention_ms"], out[name + "_lse_merge_ms"] = st["attention"], st["lse_merge"]
+        del ws
+    T, H, d = cfg.batch * cfg.seq_len, cfg.n_heads, cfg.head_dim
+    out["partial_bytes"] = cfg.batch * 2 * alpha * H * cfg.seq_len * (d + 2) * 4
+    out["merge_GBs"] = (out["partial_bytes"] + T * H * d * 2) / (out["materialised_lse_merge_ms"] * 1e-3) / 1e9
+    return out
+
+
 def cpu_baseline(cfg, host):
     """The oracle as it stands, on the host cores: the whole unsharded float64 layer, one repetition."""
     import numpy as np
@@ -262,6 +291,9 @@ def main():
         base, err = cpu_baseline(cfg, res["_host"])
         out["cpu_baseline"] = base
         out["max_rel_err_vs_oracle"] = err
+    if bf16:
+        torch.cuda.empty_cache()
+        out["m_split"] = run_m_split(cas, cfg, max(3, args.steps // 4))
     if args.all:
         others = {}
         for key in ("C2", "C4", "C5"):

@@ -107,6 +107,44 @@ CASCADE_API int32_t cascade_plan_maps(const cascade_plan *plan, const int32_t **
 CASCADE_API int32_t cascade_plan_maps_host(const cascade_plan *plan, const int32_t **perm_host,
                                const int32_t **inv_perm_host, const int32_t **offsets_host);
 
+/* Section 5.1 keeps the sharding of hidden states {R_i} (alpha shards) apart from
+ * the sharding of queries / keys / values {S_j} (beta shards); Section 6.4 refines
+ * R into S by an m-split.  This variant takes both: token_to_row_shard_host
+ * defines the packed row order and the row shards (as token_to_shard_host does
+ * above); token_to_kv_shard_host[seq_len] (values in [0, n_kv_shards)) defines the
+ * key/value shards S_k.  Partials then have one entry per key/value shard:
+ * m, e [B,H,n_kv_shards,N], u [B,n_kv_shards,H,N,d], rows in the row partition's
+ * packed order; cascade_lse_merge merges over the n_kv_shards partials.  Keys of
+ * S_k are taken in ascending token index (the sorted concatenation rule of the
+ * Attention-Pass subsection).  The result of the merged attention does not depend
+ * on either partition.  Errors as cascade_plan_create.                          */
+CASCADE_API int32_t cascade_plan_create_rs(cascade_plan **out, int32_t batch, int32_t seq_len, int32_t n_row_shards,
+                               const int32_t *token_to_row_shard_host, int32_t n_kv_shards,
+                               const int32_t *token_to_kv_shard_host, const int32_t *positions_host,
+                               int32_t mask_kind);
+
+/* Host copies of the key/value partition's maps (owned by the plan): its shard
+ * count, kv_perm[seq_len] (kv-packed row -> token), kv_offsets[n_kv_shards + 1],
+ * kv_to_row[seq_len] (kv-packed row -> packed row of the row partition; NULL is
+ * returned when the plan has a single partition).  Any out pointer may be NULL.  */
+CASCADE_API int32_t cascade_plan_kv_maps_host(const cascade_plan *plan, int32_t *n_kv_shards,
+                                  const int32_t **kv_perm_host, const int32_t **kv_offsets_host,
+                                  const int32_t **kv_to_row_host);
+
+/* (c, delta)-sharding of Section 6: 0-based token t belongs to shard
+ * (t mod delta) div c; writes token_to_shard_host[seq_len] and the shard count
+ * ceil(delta / c) (n_shards may be NULL).  Host only.  Errors: EINVAL.           */
+CASCADE_API int32_t cascade_cdelta_assignment(int32_t seq_len, int32_t c, int32_t delta,
+                                  int32_t *token_to_shard_host, int32_t *n_shards);
+
+/* m-split of Section 6.4: the sorted tokens of row shard i are dealt round-robin
+ * into m pieces (piece x takes the elements at sorted indices x, x + m, ...), and
+ * piece x of shard i becomes key/value shard m i + x (0-based), so there are
+ * m * n_row_shards key/value shards.  Writes token_to_kv_shard_host[seq_len].
+ * Host only.  Errors: EINVAL, EASSIGN (row shard id out of range), EUNSUPPORTED. */
+CASCADE_API int32_t cascade_m_split(int32_t seq_len, int32_t n_row_shards, const int32_t *token_to_row_shard_host,
+                        int32_t m, int32_t *token_to_kv_shard_host);
+
 CASCADE_API void cascade_plan_destroy(cascade_plan *plan);
 
 /* HIP error code of the last CASCADE_EHIP on this thread (0 if none).          */

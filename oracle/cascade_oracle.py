@@ -80,6 +80,17 @@ def m_split(index_list, m):
     return [r[x::m] for x in range(m)]
 
 
+def m_split_assignment(token_to_row_shard, n_row_shards, m):
+    """The S sharding formed from an R sharding by the m-split (AttnNode Full Security
+    subsection): beta = m alpha and S_{m(i-1)+x} = R_{i,x} (1-based), i.e. 0-based kv
+    shard m*i + x holds piece x of row shard i.  Returns token_to_kv_shard."""
+    out = np.empty(len(token_to_row_shard), dtype=np.int32)
+    for i, R in enumerate(shard_index_lists(token_to_row_shard, n_row_shards)):
+        for x, piece in enumerate(m_split(R, m)):
+            out[piece] = m * i + x
+    return out
+
+
 # --------------------------------------------------------------------------- per-token pieces
 def layer_norm(x, gain, bias, eps):
     mu = x.mean(axis=-1, keepdims=True)
@@ -241,6 +252,30 @@ def partial_attention_all_pairs(q, k, v, token_to_shard, n_shards, positions=Non
     return m, e, u
 
 
+def partial_attention_rs(q, k, v, token_to_row_shard, n_row_shards, token_to_kv_shard, n_kv_shards,
+                         positions=None, scale=1.0, mask_kind="causal"):
+    """Algorithm 3 on every pair (S_j, S_k) of the query / key-value sharding S when it
+    differs from the hidden-state sharding R (Section 5.1).  The rows AttnNode_jk returns
+    are routed back to the CompNode that owns them (R_i ∩ S_j, Post-Pass subsection), so
+    the outputs are laid out in R's packed row order:
+    m, e (H, beta, N) indexed [head, kv-shard of S, R-packed query row]; u (beta, H, N, d)."""
+    q, k, v = (np.asarray(t, dtype=F64) for t in (q, k, v))
+    H, N, d = q.shape
+    pos = np.arange(N) if positions is None else np.asarray(positions)
+    s_lists = shard_index_lists(token_to_kv_shard, n_kv_shards)
+    _, _, inv_perm_r = shard_plan(token_to_row_shard, n_row_shards)
+    m = np.full((H, n_kv_shards, N), -np.inf)
+    e = np.zeros((H, n_kv_shards, N))
+    u = np.zeros((n_kv_shards, H, N, d))
+    for Sj in s_lists:
+        rows = inv_perm_r[Sj]                          # where CompNodes keep the rows of S_j
+        for kk, Sk in enumerate(s_lists):
+            s = mask_block(pos[Sj], pos[Sk], mask_kind)
+            mj, ej, uj = attn_pass(q[:, Sj], k[:, Sk], v[:, Sk], s, scale)
+            m[:, kk, rows], e[:, kk, rows], u[kk][:, rows] = mj, ej, uj
+    return m, e, u
+
+
 def lse_merge_all(m, e, u):
     """Algorithm 4 lines 1-8 over the kv-shard axis of packed partials.
     m, e (H, beta, N); u (beta, H, N, d) normalised.  Returns o (N, H*d), packed rows."""
@@ -320,6 +355,49 @@ def layer_sharded(h, w, cfg, token_to_shard, n_shards, positions=None, mask_kind
         out[R] = h1 + ffn(x2, w, cfg.act)
     if return_partials:
         return out, partial
+    return out
+
+
+def layer_sharded_rs(h, w, cfg, token_to_row_shard, n_row_shards, token_to_kv_shard, n_kv_shards,
+                     positions=None, mask_kind="causal", scale=None):
+    """Algorithm 1 with distinct shardings: CompNode_i holds the hidden rows R_i, AttnNode_jk
+    works on (S_j, S_k).  Output in original token order."""
+    w = _f64_weights(w)
+    h = np.asarray(h, dtype=F64)
+    N = h.shape[0]
+    pos = np.arange(N) if positions is None else np.asarray(positions)
+    scale = cfg.scale if scale is None else scale
+    r_lists = shard_index_lists(token_to_row_shard, n_row_shards)
+    s_lists = shard_index_lists(token_to_kv_shard, n_kv_shards)
+    H, Hkv, d = cfg.n_heads, cfg.n_kv_heads, cfg.head_dim
+
+    # pre-pass on every hidden shard, then stage-A routing: AttnNode_jk receives the rows
+    # R_i ∩ S_j of q and R_i ∩ S_k of k, v from every CompNode_i and concatenates them in
+    # sorted order (Algorithm 1 lines 1-7); held here as full-length arrays indexed by token
+    q = np.empty((H, N, d)); k = np.empty((Hkv, N, d)); v = np.empty((Hkv, N, d))
+    for R in r_lists:
+        if len(R):
+            q[:, R], k[:, R], v[:, R] = pre_pass(h[R], pos[R], w, cfg)
+
+    # attention-pass on every pair of S shards (lines 8-9); stage-B routing sends row t of
+    # AttnNode_jk's result to the CompNode that holds t (lines 10-14)
+    m = np.full((n_kv_shards, H, N), -np.inf); e = np.zeros((n_kv_shards, H, N)); u = np.zeros((n_kv_shards, H, N, d))
+    for Sj in s_lists:
+        for kk, Sk in enumerate(s_lists):
+            s = mask_block(pos[Sj], pos[Sk], mask_kind)
+            m[kk][:, Sj], e[kk][:, Sj], u[kk][:, Sj] = attn_pass(q[:, Sj], k[:, Sk], v[:, Sk], s, scale)
+
+    # post-pass, residual and MLP on every hidden shard (lines 15-17)
+    out = np.empty_like(h)
+    for R in r_lists:
+        if len(R) == 0:
+            continue
+        o = post_pass_merge([m[kk][:, R] for kk in range(n_kv_shards)], [e[kk][:, R] for kk in range(n_kv_shards)],
+                            [u[kk][:, R] for kk in range(n_kv_shards)])
+        o = o.transpose(1, 0, 2).reshape(len(R), -1)
+        h1 = h[R] + linear(o, w["wo"], w.get("bo"))
+        x2 = norm(h1, cfg.norm, w["norm2_g"], w.get("norm2_b"), cfg.eps)
+        out[R] = h1 + ffn(x2, w, cfg.act)
     return out
 
 

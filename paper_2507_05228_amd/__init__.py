@@ -24,7 +24,8 @@ ACT_GELU_ERF, ACT_GELU_TANH, ACT_SWIGLU = 0, 1, 2
 ATTN_FUSED, ATTN_MATERIALISED = 0, 1
 EPI_BIAS, EPI_GELU_ERF, EPI_GELU_TANH, EPI_SWIGLU, EPI_ROPE, EPI_RESIDUAL = 1, 2, 4, 8, 16, 32
 
-EXPORTS = ["cascade_plan_create", "cascade_plan_maps", "cascade_plan_maps_host", "cascade_plan_destroy",
+EXPORTS = ["cascade_plan_create", "cascade_plan_create_rs", "cascade_plan_maps", "cascade_plan_maps_host",
+           "cascade_plan_kv_maps_host", "cascade_cdelta_assignment", "cascade_m_split", "cascade_plan_destroy",
            "cascade_last_hip_error", "cascade_shard_gemm", "cascade_partial_attn_workspace_bytes",
            "cascade_partial_attn", "cascade_lse_merge", "cascade_layer_workspace_bytes",
            "cascade_layer_forward", "cascade_layer_forward_staged", "cascade_layer_partials",
@@ -83,6 +84,14 @@ def load_library():
     P, I32, VP = C.POINTER, C.c_int32, C.c_void_p
     lib.cascade_plan_create.argtypes = [P(VP), I32, I32, I32, P(I32), P(I32), I32]
     lib.cascade_plan_create.restype = I32
+    lib.cascade_plan_create_rs.argtypes = [P(VP), I32, I32, I32, P(I32), I32, P(I32), P(I32), I32]
+    lib.cascade_plan_create_rs.restype = I32
+    lib.cascade_plan_kv_maps_host.argtypes = [VP, P(I32), P(P(I32)), P(P(I32)), P(P(I32))]
+    lib.cascade_plan_kv_maps_host.restype = I32
+    lib.cascade_cdelta_assignment.argtypes = [I32, I32, I32, P(I32), P(I32)]
+    lib.cascade_cdelta_assignment.restype = I32
+    lib.cascade_m_split.argtypes = [I32, I32, P(I32), I32, P(I32)]
+    lib.cascade_m_split.restype = I32
     lib.cascade_plan_maps.argtypes = [VP, P(VP), P(VP), P(VP)]
     lib.cascade_plan_maps.restype = I32
     lib.cascade_plan_maps_host.argtypes = [VP, P(P(I32)), P(P(I32)), P(P(I32))]
@@ -141,8 +150,9 @@ def _dtype_code(t):
 class Plan:
     """Owner of a cascade_plan handle."""
 
-    def __init__(self, handle, batch, seq_len, n_shards, mask_kind):
+    def __init__(self, handle, batch, seq_len, n_shards, mask_kind, n_kv_shards=None):
         self.handle, self.batch, self.seq_len, self.n_shards, self.mask_kind = handle, batch, seq_len, n_shards, mask_kind
+        self.n_kv_shards = n_shards if n_kv_shards is None else n_kv_shards   # partials: one per key/value shard
 
     def __del__(self):
         if getattr(self, "handle", None) and _lib is not None:
@@ -165,6 +175,57 @@ def cascade_plan_create(batch, seq_len, n_shards, token_to_shard, positions=None
                                  None if pos is None else pos.ctypes.data_as(I32P), mask_kind)
     _check(st, "cascade_plan_create")
     return Plan(h, batch, seq_len, n_shards, mask_kind)
+
+
+def cascade_plan_create_rs(batch, seq_len, n_row_shards, token_to_row_shard, n_kv_shards, token_to_kv_shard,
+                           positions=None, mask_kind=MASK_CAUSAL):
+    lib = load_library()
+    I32P = C.POINTER(C.c_int32)
+    a = np.ascontiguousarray(token_to_row_shard, dtype=np.int32)
+    k = np.ascontiguousarray(token_to_kv_shard, dtype=np.int32)
+    if a.shape != (seq_len,) or k.shape != (seq_len,):
+        raise CascadeError(ESHAPE, "cascade_plan_create_rs: assignment length")
+    pos = None if positions is None else np.ascontiguousarray(positions, dtype=np.int32)
+    if pos is not None and pos.shape != (seq_len,):
+        raise CascadeError(ESHAPE, "cascade_plan_create_rs: positions length")
+    h = C.c_void_p()
+    st = lib.cascade_plan_create_rs(C.byref(h), batch, seq_len, n_row_shards, a.ctypes.data_as(I32P), n_kv_shards,
+                                    k.ctypes.data_as(I32P), None if pos is None else pos.ctypes.data_as(I32P), mask_kind)
+    _check(st, "cascade_plan_create_rs")
+    return Plan(h, batch, seq_len, n_row_shards, mask_kind, n_kv_shards)
+
+
+def cascade_plan_kv_maps_host(plan):
+    """(n_kv_shards, kv_perm, kv_offsets, kv_to_row or None) as numpy copies."""
+    lib = load_library()
+    I32P = C.POINTER(C.c_int32)
+    n = C.c_int32()
+    p, off, k2r = I32P(), I32P(), I32P()
+    _check(lib.cascade_plan_kv_maps_host(plan.handle, C.byref(n), C.byref(p), C.byref(off), C.byref(k2r)),
+           "cascade_plan_kv_maps_host")
+    return (n.value, np.ctypeslib.as_array(p, (plan.seq_len,)).copy(), np.ctypeslib.as_array(off, (n.value + 1,)).copy(),
+            np.ctypeslib.as_array(k2r, (plan.seq_len,)).copy() if k2r else None)
+
+
+def cascade_cdelta_assignment(seq_len, c, delta):
+    """(token_to_shard, n_shards) of the (c, delta)-sharding."""
+    lib = load_library()
+    out = np.zeros(max(seq_len, 0), dtype=np.int32)
+    n = C.c_int32()
+    _check(lib.cascade_cdelta_assignment(seq_len, c, delta, out.ctypes.data_as(C.POINTER(C.c_int32)), C.byref(n)),
+           "cascade_cdelta_assignment")
+    return out, n.value
+
+
+def cascade_m_split(token_to_row_shard, n_row_shards, m):
+    """token_to_kv_shard of the m-split of a row sharding (m * n_row_shards key/value shards)."""
+    lib = load_library()
+    I32P = C.POINTER(C.c_int32)
+    a = np.ascontiguousarray(token_to_row_shard, dtype=np.int32)
+    out = np.zeros_like(a)
+    _check(lib.cascade_m_split(a.shape[0], n_row_shards, a.ctypes.data_as(I32P), m, out.ctypes.data_as(I32P)),
+           "cascade_m_split")
+    return out
 
 
 def cascade_plan_maps(plan):
@@ -291,7 +352,7 @@ def cascade_layer_partials(plan, desc, workspace, batch, n_heads, head_dim):
            "cascade_layer_partials")
     base = workspace.data_ptr()
     f = workspace.view(torch.uint8)
-    S, N = plan.n_shards, plan.seq_len
+    S, N = plan.n_kv_shards, plan.seq_len
     n_me = batch * n_heads * S * N
 
     def view(ptr, n, shape):
@@ -324,11 +385,16 @@ def cascade_mfma_ceiling(lds_operands, iters=200000, stream=None):
 
 
 def layer_forward_numpy(cfg, weights_np, h_np, token_to_shard, positions=None, attn_mode=ATTN_FUSED,
-                        io_rows=ROWS_ORIGINAL, mask_kind=MASK_CAUSAL, return_partials=False):
-    """Upload numpy inputs, run cascade_layer_forward once, download the output as float64."""
+                        io_rows=ROWS_ORIGINAL, mask_kind=MASK_CAUSAL, return_partials=False, token_to_kv_shard=None):
+    """Upload numpy inputs, run cascade_layer_forward once, download the output as float64.
+    token_to_kv_shard: a second partition for keys / values (row shards != key/value shards)."""
     import torch
-    plan = cascade_plan_create(cfg.batch, cfg.seq_len, int(np.max(token_to_shard)) + 1 if cfg.n_shards is None
-                               else cfg.n_shards, token_to_shard, positions, mask_kind)
+    n_row = int(np.max(token_to_shard)) + 1 if cfg.n_shards is None else cfg.n_shards
+    if token_to_kv_shard is None:
+        plan = cascade_plan_create(cfg.batch, cfg.seq_len, n_row, token_to_shard, positions, mask_kind)
+    else:
+        plan = cascade_plan_create_rs(cfg.batch, cfg.seq_len, n_row, token_to_shard, int(np.max(token_to_kv_shard)) + 1,
+                                      token_to_kv_shard, positions, mask_kind)
     desc = make_layer_desc(cfg, attn_mode, io_rows)
     tensors = {k: to_device(v, cfg.dtype) for k, v in weights_np.items()}
     w = make_layer_weights(tensors)

@@ -107,7 +107,9 @@ extern "C" int32_t cascade_partial_attn(const cascade_plan *plan, const cascade_
     a.scale = d->scale; a.mask_kind = plan->mask_kind;
     a.q = q; a.k = k; a.v = v;
     fill_strides(plan, d, a);
-    a.q_rowmap = a.kv_rowmap = d->row_layout == CASCADE_ROWS_ORIGINAL ? plan->perm_d : nullptr;
+    // q rows follow the row partition, k/v rows the key/value partition (the same unless the plan has both)
+    a.q_rowmap = d->row_layout == CASCADE_ROWS_ORIGINAL ? plan->perm_d : nullptr;
+    a.kv_rowmap = d->row_layout == CASCADE_ROWS_ORIGINAL ? kv_plan(plan)->perm_d : plan->kv_to_row_d;
     a.fused = 0; a.u_mode = d->u_mode; a.m = m; a.e = e; a.u = u;
     a.workspace = workspace; a.workspace_bytes = workspace_bytes;
     hipStream_t s = (hipStream_t)stream;
@@ -120,7 +122,7 @@ extern "C" int32_t cascade_lse_merge(const cascade_plan *plan, const cascade_att
     if (st != CASCADE_OK) return st;
     if (!m || !e || !u || !o) return CASCADE_EINVAL;
     MergeArgs a = {};
-    a.dtype = d->dtype; a.B = plan->batch; a.H = d->n_heads; a.d = d->head_dim; a.n_shards = plan->n_shards;
+    a.dtype = d->dtype; a.B = plan->batch; a.H = d->n_heads; a.d = d->head_dim; a.n_shards = kv_plan(plan)->n_shards;
     a.N = plan->seq_len; a.u_mode = d->u_mode; a.m = m; a.e = e; a.u = u; a.o = o;
     a.o_ld = (int64_t)d->n_heads * d->head_dim;
     a.o_rowmap = d->row_layout == CASCADE_ROWS_ORIGINAL ? plan->perm_d : nullptr;
@@ -149,7 +151,7 @@ static LayerWs layer_ws(const cascade_plan *plan, const cascade_layer_desc *d) {
     w.attn_ws_bytes = d->dtype == CASCADE_BF16 ? attn_bf16_workspace_bytes(plan, plan->batch, d->n_kv_heads, d->head_dim) : 0;
     w.attn_ws = take(w.attn_ws_bytes);
     if (d->attn_mode == CASCADE_ATTN_MATERIALISED) {
-        const size_t me = (size_t)plan->batch * d->n_heads * plan->n_shards * plan->seq_len * 4;
+        const size_t me = (size_t)plan->batch * d->n_heads * kv_plan(plan)->n_shards * plan->seq_len * 4;
         w.m = take(me);
         w.e = take(me);
         w.u = take(me * d->head_dim);
@@ -264,6 +266,7 @@ static int32_t layer_forward_impl(const cascade_plan *plan, const cascade_layer_
     a.q = qkv; a.k = (char *)qkv + (size_t)H * hd * es; a.v = (char *)qkv + (size_t)(H + Hkv) * hd * es;
     a.qs_b = a.ks_b = (int64_t)N * QW; a.qs_h = a.ks_h = hd; a.qs_n = a.ks_n = QW;
     a.u_mode = CASCADE_U_UNNORMALISED;
+    a.kv_rowmap = plan->kv_to_row_d;                                              // null unless S differs from R
     a.workspace = base + ws.attn_ws; a.workspace_bytes = ws.attn_ws_bytes;
     a.o = ao; a.o_ld = (int64_t)H * hd;
     if (d->attn_mode == CASCADE_ATTN_FUSED) {
@@ -278,7 +281,7 @@ static int32_t layer_forward_impl(const cascade_plan *plan, const cascade_layer_
         st = d->dtype == CASCADE_BF16 ? launch_attn_bf16(plan, a, s) : launch_attn_f32(plan, a, s);
         if (st != CASCADE_OK) return st;
         if ((st = mark()) != CASCADE_OK) return st;                               // 4: partial attention
-        MergeArgs mg = {d->dtype, plan->batch, H, hd, plan->n_shards, N, CASCADE_U_UNNORMALISED,
+        MergeArgs mg = {d->dtype, plan->batch, H, hd, kv_plan(plan)->n_shards, N, CASCADE_U_UNNORMALISED,
                         a.m, a.e, a.u, ao, (int64_t)H * hd, nullptr, nullptr};
         if ((st = launch_merge(mg, s)) != CASCADE_OK) return st;
         if ((st = mark()) != CASCADE_OK) return st;                               // 5: LSE merge

@@ -85,7 +85,8 @@ struct AttnBf16Params {
     const CascadeTile *kvtiles;      // ordered by smallest position: globally (fused) or inside each shard's range
     const int32_t *kv_shard_first;
     int32_t n_kvtiles;
-    const int32_t *pos_packed;
+    const int32_t *pos_packed;       // positions of the packed query rows
+    const int32_t *pos_kv;           // positions of the key/value rows in the order of the kv tiles
     int32_t B, H, Hkv, N, S;
     float scale_log2;
     int32_t causal, fused, u_mode;
@@ -257,7 +258,7 @@ __global__ __launch_bounds__(512) void attn_bf16_kernel(AttnBf16Params p) {
     const __amdgpu_buffer_rsrc_t rv = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<bf16_t *>(p.vt + b * p.vts_b + g * p.vts_h), 0, p.vt_bytes, 0x00020000);
     const __amdgpu_buffer_rsrc_t rp = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<int32_t *>(p.pos_packed), 0, (uint32_t)p.N * 4, 0x00020000);
+        const_cast<int32_t *>(p.pos_kv), 0, (uint32_t)p.N * 4, 0x00020000);
 
     // Direct-to-LDS loads of one tile.  K instruction i of this wavefront fills K rows
     // (wave*K_INSTR + i)*K_RPI ..: lane -> row lane/K_CPR, slot lane%K_CPR holding chunk slot^swz(row).
@@ -582,7 +583,7 @@ __global__ __launch_bounds__(256) void kgather_kernel(const bf16_t *__restrict__
     *(bf16x8 *)(kp + (((int64_t)b * Hkv + g) * N + r) * D + ch * 8) = val;
 }
 
-static int32_t npad_of(const cascade_plan *p) { return std::max(1, plan_tiles(p, KV_TILE).count) * KV_TILE; }
+static int32_t npad_of(const cascade_plan *p) { return std::max(1, plan_tiles(kv_plan(p), KV_TILE).count) * KV_TILE; }
 
 // V^T (tile order, padded) followed by room for K gathered into packed order
 static size_t vt_bytes_of(const cascade_plan *p, int32_t B, int32_t Hkv, int32_t d) {
@@ -594,13 +595,14 @@ size_t attn_bf16_workspace_bytes(const cascade_plan *p, int32_t B, int32_t Hkv, 
 
 template <int D>
 static int32_t launch_attn_cfg(const cascade_plan *p, const AttnArgs &a, hipStream_t s) {
-    const int N = p->seq_len, S = p->n_shards;
+    const cascade_plan *kvp = kv_plan(p);                      // key/value shards (S); query tiles follow p (R)
+    const int N = p->seq_len, S = kvp->n_shards;
     const int rep = a.H / a.Hkv;
     const int hpb = rep % 4 == 0 ? 4 : rep % 2 == 0 ? 2 : 1;
     const int rowgroups = 8 / hpb;
     const int granule = 32 * rowgroups;                        // 64, 128 or 256 query rows per workgroup
     const CascadeTileList &ql = plan_tiles(p, granule);
-    const CascadeTileList &kl = plan_tiles(p, KV_TILE);
+    const CascadeTileList &kl = plan_tiles(kvp, KV_TILE);
     const int npad = npad_of(p);
     if (ql.count == 0) return CASCADE_OK;
 
@@ -628,7 +630,7 @@ static int32_t launch_attn_cfg(const cascade_plan *p, const AttnArgs &a, hipStre
     k.k_bytes = (uint32_t)kb; k.vt_bytes = (uint32_t)vb;
     k.q_rowmap = a.q_rowmap;
     k.qtiles = ql.dev; k.kvtiles = a.fused ? kl.dev_by_pmin : kl.dev_by_shard_pmin; k.kv_shard_first = kl.shard_first; k.n_kvtiles = kl.count;
-    k.pos_packed = p->pos_packed_d;
+    k.pos_packed = p->pos_packed_d; k.pos_kv = kvp->pos_packed_d;
     k.B = a.B; k.H = a.H; k.Hkv = a.Hkv; k.N = N; k.S = S;
     k.scale_log2 = a.scale * LOG2E;
     k.causal = a.mask_kind == CASCADE_MASK_CAUSAL; k.fused = a.fused; k.u_mode = a.u_mode;

@@ -14,7 +14,8 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(
     const float *__restrict__ q, const float *__restrict__ k, const float *__restrict__ v, int B, int H, int Hkv,
     int d, int N, int S, float scale, int causal, int64_t qs_b, int64_t qs_h, int64_t qs_n, int64_t ks_b,
     int64_t ks_h, int64_t ks_n, const int32_t *__restrict__ q_rowmap, const int32_t *__restrict__ kv_rowmap,
-    const int32_t *__restrict__ offsets, const int32_t *__restrict__ pos_packed, float *__restrict__ m_out,
+    const int32_t *__restrict__ offsets, const int32_t *__restrict__ pos_packed,
+    const int32_t *__restrict__ pos_kv, float *__restrict__ m_out,
     float *__restrict__ e_out, float *__restrict__ u_out, int u_mode, float *__restrict__ o_out, int64_t o_ld,
     const int32_t *__restrict__ o_rowmap) {
     __shared__ float qs[4][F32_MAX_D];
@@ -44,7 +45,7 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(
         const int cc = valid ? c : c_end - 1;
         const int64_t krow = kv_rowmap ? kv_rowmap[cc] : cc;
         float s = -INFINITY;
-        if (valid && (!causal || pos_packed[cc] <= pos_q)) {
+        if (valid && (!causal || pos_kv[cc] <= pos_q)) {
             const float *kr = kb + krow * ks_n;
             float dot = 0.f;
             for (int i = 0; i < d; ++i) dot = fmaf(qs[wave][i], kr[i], dot);
@@ -95,19 +96,22 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(
 
 int32_t launch_attn_f32(const cascade_plan *p, const AttnArgs &a, hipStream_t s) {
     if (a.d > F32_MAX_D) return CASCADE_EUNSUPPORTED;
-    const int N = p->seq_len, S = p->n_shards;
+    const cascade_plan *kvp = kv_plan(p);             // key rows walk the key/value partition's packed order
+    const int N = p->seq_len, S = kvp->n_shards;
     if (a.H > 65535 || (int64_t)a.B * S > 65535) return CASCADE_EUNSUPPORTED;
     dim3 grid((N + 3) / 4, a.H, a.fused ? a.B : a.B * S);
     const int causal = a.mask_kind == CASCADE_MASK_CAUSAL;
     if (a.fused)
         hipLaunchKernelGGL(attn_f32_kernel<true>, grid, dim3(256), 0, s, (const float *)a.q, (const float *)a.k,
                            (const float *)a.v, a.B, a.H, a.Hkv, a.d, N, S, a.scale, causal, a.qs_b, a.qs_h, a.qs_n,
-                           a.ks_b, a.ks_h, a.ks_n, a.q_rowmap, a.kv_rowmap, p->offsets_d, p->pos_packed_d, a.m, a.e,
+                           a.ks_b, a.ks_h, a.ks_n, a.q_rowmap, a.kv_rowmap, kvp->offsets_d, p->pos_packed_d, kvp->pos_packed_d,
+                           a.m, a.e,
                            a.u, a.u_mode, (float *)a.o, a.o_ld, a.o_rowmap);
     else
         hipLaunchKernelGGL(attn_f32_kernel<false>, grid, dim3(256), 0, s, (const float *)a.q, (const float *)a.k,
                            (const float *)a.v, a.B, a.H, a.Hkv, a.d, N, S, a.scale, causal, a.qs_b, a.qs_h, a.qs_n,
-                           a.ks_b, a.ks_h, a.ks_n, a.q_rowmap, a.kv_rowmap, p->offsets_d, p->pos_packed_d, a.m, a.e,
+                           a.ks_b, a.ks_h, a.ks_n, a.q_rowmap, a.kv_rowmap, kvp->offsets_d, p->pos_packed_d, kvp->pos_packed_d,
+                           a.m, a.e,
                            a.u, a.u_mode, (float *)a.o, a.o_ld, a.o_rowmap);
     CASCADE_HIP_TRY(hipGetLastError());
     return CASCADE_OK;

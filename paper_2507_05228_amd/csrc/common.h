@@ -38,7 +38,15 @@ struct cascade_plan {
     // device copies
     int32_t *perm_d, *inv_perm_d, *offsets_d, *pos_packed_d;
     CascadeTileList tiles[4];   // granules 32, 64, 128, 256
+    // Key/value partition S when it differs from the row partition R (Section 5.1; the m-split of
+    // Section 6.4): a plan of its own over the same tokens, plus the map from its packed rows to
+    // this plan's packed rows.  nullptr: S = R.
+    cascade_plan *kv;
+    int32_t *kv_to_row_h, *kv_to_row_d;
 };
+
+// the partition that shards keys and values (the plan itself when S = R)
+static inline const cascade_plan *kv_plan(const cascade_plan *p) { return p->kv ? p->kv : p; }
 
 static inline const CascadeTileList &plan_tiles(const cascade_plan *p, int granule) {
     return p->tiles[granule == 32 ? 0 : granule == 64 ? 1 : granule == 128 ? 2 : 3];

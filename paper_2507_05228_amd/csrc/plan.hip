@@ -16,6 +16,9 @@ extern "C" int32_t cascade_last_hip_error(void) { return g_last_hip_error; }
 
 static void free_plan(cascade_plan *p) {
     if (!p) return;
+    free_plan(p->kv);
+    free(p->kv_to_row_h);
+    if (p->kv_to_row_d) (void)hipFree(p->kv_to_row_d);
     free(p->perm_h); free(p->inv_perm_h); free(p->offsets_h); free(p->pos_packed_h);
     if (p->perm_d) (void)hipFree(p->perm_d);
     if (p->inv_perm_d) (void)hipFree(p->inv_perm_d);
@@ -89,9 +92,8 @@ static hipError_t build_tiles(cascade_plan *p, CascadeTileList &out, int granule
     return to_device(&out.shard_first, first.data(), first.size());
 }
 
-extern "C" int32_t cascade_plan_create(cascade_plan **out, int32_t batch, int32_t seq_len, int32_t n_shards,
-                                       const int32_t *token_to_shard_host, const int32_t *positions_host,
-                                       int32_t mask_kind) {
+static int32_t build_plan(cascade_plan **out, int32_t batch, int32_t seq_len, int32_t n_shards,
+                          const int32_t *token_to_shard_host, const int32_t *positions_host, int32_t mask_kind) {
     if (!out) return CASCADE_EINVAL;
     *out = nullptr;
     if (!token_to_shard_host || batch <= 0 || seq_len <= 0 || n_shards <= 0) return CASCADE_EINVAL;
@@ -134,6 +136,72 @@ extern "C" int32_t cascade_plan_create(cascade_plan **out, int32_t batch, int32_
     for (int g = 0; g < 4 && e == hipSuccess; ++g) e = build_tiles(p, p->tiles[g], granules[g]);
     if (e != hipSuccess) { cascade_set_hip_error(e); free_plan(p); return CASCADE_EHIP; }
     *out = p;
+    return CASCADE_OK;
+}
+
+extern "C" int32_t cascade_plan_create(cascade_plan **out, int32_t batch, int32_t seq_len, int32_t n_shards,
+                                       const int32_t *token_to_shard_host, const int32_t *positions_host,
+                                       int32_t mask_kind) {
+    return build_plan(out, batch, seq_len, n_shards, token_to_shard_host, positions_host, mask_kind);
+}
+
+extern "C" int32_t cascade_plan_create_rs(cascade_plan **out, int32_t batch, int32_t seq_len, int32_t n_row_shards,
+                                          const int32_t *token_to_row_shard_host, int32_t n_kv_shards,
+                                          const int32_t *token_to_kv_shard_host, const int32_t *positions_host,
+                                          int32_t mask_kind) {
+    if (!out) return CASCADE_EINVAL;
+    *out = nullptr;
+    if (!token_to_kv_shard_host || n_kv_shards <= 0) return CASCADE_EINVAL;
+    cascade_plan *p = nullptr;
+    int32_t st = build_plan(&p, batch, seq_len, n_row_shards, token_to_row_shard_host, positions_host, mask_kind);
+    if (st != CASCADE_OK) return st;
+    st = build_plan(&p->kv, batch, seq_len, n_kv_shards, token_to_kv_shard_host, positions_host, mask_kind);
+    if (st != CASCADE_OK) { free_plan(p); return st; }
+    p->kv_to_row_h = (int32_t *)malloc(sizeof(int32_t) * seq_len);
+    if (!p->kv_to_row_h) { free_plan(p); return CASCADE_EINVAL; }
+    for (int r = 0; r < seq_len; ++r) p->kv_to_row_h[r] = p->inv_perm_h[p->kv->perm_h[r]];
+    hipError_t e = to_device(&p->kv_to_row_d, p->kv_to_row_h, seq_len);
+    if (e != hipSuccess) { cascade_set_hip_error(e); free_plan(p); return CASCADE_EHIP; }
+    *out = p;
+    return CASCADE_OK;
+}
+
+extern "C" int32_t cascade_plan_kv_maps_host(const cascade_plan *plan, int32_t *n_kv_shards, const int32_t **kv_perm_host,
+                                             const int32_t **kv_offsets_host, const int32_t **kv_to_row_host) {
+    if (!plan) return CASCADE_EINVAL;
+    const cascade_plan *k = kv_plan(plan);
+    if (n_kv_shards) *n_kv_shards = k->n_shards;
+    if (kv_perm_host) *kv_perm_host = k->perm_h;
+    if (kv_offsets_host) *kv_offsets_host = k->offsets_h;
+    if (kv_to_row_host) *kv_to_row_host = plan->kv ? plan->kv_to_row_h : nullptr;
+    return CASCADE_OK;
+}
+
+// ---------------------------------------------------------------------------- (c, delta) plans
+// Section 6 ((c, delta)-sequences): shard i of a (c, delta)-sharding holds the tokens {i c .. i c + c - 1} + multiples
+// of delta (0-based), i.e. token t goes to shard (t mod delta) div c; ceil(delta / c) shards.
+extern "C" int32_t cascade_cdelta_assignment(int32_t seq_len, int32_t c, int32_t delta, int32_t *token_to_shard_host,
+                                             int32_t *n_shards) {
+    if (!token_to_shard_host || seq_len <= 0 || c <= 0 || delta <= 0) return CASCADE_EINVAL;
+    for (int t = 0; t < seq_len; ++t) token_to_shard_host[t] = (t % delta) / c;
+    if (n_shards) *n_shards = (delta + c - 1) / c;
+    return CASCADE_OK;
+}
+
+// Section 6.4 (AttnNode Full Security, m-split; its N = 18 example fixes the reading): every row
+// shard R_i, sorted, is dealt round-robin into m pieces; piece x of
+// shard i (0-based) becomes kv shard m i + x, so beta = m alpha and pairwise coverage is kept.
+extern "C" int32_t cascade_m_split(int32_t seq_len, int32_t n_row_shards, const int32_t *token_to_row_shard_host,
+                                   int32_t m, int32_t *token_to_kv_shard_host) {
+    if (!token_to_row_shard_host || !token_to_kv_shard_host || seq_len <= 0 || n_row_shards <= 0 || m <= 0)
+        return CASCADE_EINVAL;
+    if ((int64_t)n_row_shards * m > INT32_MAX) return CASCADE_EUNSUPPORTED;
+    std::vector<int32_t> seen(n_row_shards, 0);          // rank of the token inside its sorted row shard
+    for (int t = 0; t < seq_len; ++t) {
+        const int32_t i = token_to_row_shard_host[t];
+        if (i < 0 || i >= n_row_shards) return CASCADE_EASSIGN;
+        token_to_kv_shard_host[t] = m * i + seen[i]++ % m;
+    }
     return CASCADE_OK;
 }
 

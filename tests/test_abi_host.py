@@ -2,6 +2,7 @@
 declares, and the ctypes mirrors of the descriptor structs have the header's layout.
 No compute call is made here (there is no GPU in this environment)."""
 import ctypes as C
+import numpy as np
 import os
 import re
 import subprocess
@@ -83,3 +84,47 @@ def test_product_package_does_not_import_the_oracle():
                 assert "oracle" not in text.lower().replace("no cpu fallback", ""), f
     text = open(os.path.join(ROOT, "oracle", "cascade_oracle.py")).read()
     assert "paper_2507_05228_amd" not in text and "ctypes" not in text
+
+
+# ---------------------------------------------------------------------------- host-only plan generators
+def _read_rx():
+    rx = {}
+    path = os.path.join(os.path.dirname(__file__), "golden", "msplit_example.txt")
+    for line in open(path):
+        if line.startswith("RX"):
+            key, vals = line.split(":")
+            _, i, x = key.split()
+            rx[(int(i), int(x))] = [int(t) for t in vals.split()]
+    return rx
+
+
+def test_cdelta_and_m_split_generators_reproduce_the_worked_example():
+    """Section 6.4's N = 18 example (alpha = 3, c = 2, delta = 6, m = 2), through the C entry points."""
+    a, n = cas.cascade_cdelta_assignment(18, 2, 6)
+    assert n == 3
+    assert a.tolist() == [0, 0, 1, 1, 2, 2] * 3
+    kv = cas.cascade_m_split(a, 3, 2)
+    for (i, x), toks in _read_rx().items():
+        for t in toks:
+            assert kv[t - 1] == 2 * (i - 1) + (x - 1)
+
+
+@pytest.mark.parametrize("N,c,delta,m", [(18, 2, 6, 2), (256, 8, 64, 4), (50, 3, 10, 3), (32, 1, 8, 1), (100, 4, 30, 5)])
+def test_generators_agree_with_the_oracle_bit_for_bit(N, c, delta, m):
+    from oracle import cascade_oracle as orc
+    a, n = cas.cascade_cdelta_assignment(N, c, delta)
+    assert n == -(-delta // c)
+    assert np.array_equal(a, orc.cdelta_assignment(N, c, delta))
+    assert np.array_equal(cas.cascade_m_split(a, n, m), orc.m_split_assignment(a, n, m))
+
+
+def test_generator_error_paths():
+    with pytest.raises(cas.CascadeError) as ei:
+        cas.cascade_cdelta_assignment(16, 0, 4)
+    assert ei.value.status == cas.EINVAL
+    with pytest.raises(cas.CascadeError) as ei:
+        cas.cascade_m_split(np.array([0, 1, 5], dtype=np.int32), 3, 2)
+    assert ei.value.status == cas.EASSIGN
+    with pytest.raises(cas.CascadeError) as ei:
+        cas.cascade_m_split(np.array([0, 1, 2], dtype=np.int32), 3, 0)
+    assert ei.value.status == cas.EINVAL

@@ -261,6 +261,95 @@ def test_partial_attn_unordered_positions_many_tiles_per_shard(cas, d):
     check_partials("bf16", got, ref)
 
 
+# ---------------------------------------------------------------------------- distinct row / key-value shardings
+def rs_partitions(cas, N, kind, seed):
+    """(row assignment, alpha, kv assignment, beta)."""
+    if kind == "msplit":                                      # (c, delta) rows, m-split key/value shards
+        a, alpha = cas.cascade_cdelta_assignment(N, 8, 32)
+        return a, alpha, cas.cascade_m_split(a, alpha, 2), 2 * alpha
+    if kind == "msplit4":
+        a, alpha = cas.cascade_cdelta_assignment(N, 4, 8)
+        return a, alpha, cas.cascade_m_split(a, alpha, 4), 4 * alpha
+    if kind == "coarser":                                     # key/value shards = unions of row shards
+        a = make_assignment("perm", N, 6, seed)
+        return a, 6, (a // 2).astype(np.int32), 3
+    a = make_assignment("ragged", N, 4, seed)                 # unrelated partitions
+    return a, 4, make_assignment("perm", N, 5, seed + 1), 5
+
+
+@pytest.mark.parametrize("kind", ["msplit", "coarser", "unrelated"])
+def test_plan_with_two_shardings_maps_bit_exact(cas, kind):
+    N = 200
+    a, alpha, kv, beta = rs_partitions(cas, N, kind, 3)
+    plan = cas.cascade_plan_create_rs(2, N, alpha, a, beta, kv)
+    off_r, perm_r, inv_r = orc.shard_plan(a, alpha)
+    off_s, perm_s, _ = orc.shard_plan(kv, beta)
+    perm, inv, off = cas.cascade_plan_maps_host(plan)
+    assert np.array_equal(perm, perm_r) and np.array_equal(inv, inv_r) and np.array_equal(off, off_r)
+    n, kperm, koff, k2r = cas.cascade_plan_kv_maps_host(plan)
+    assert n == beta and np.array_equal(kperm, perm_s) and np.array_equal(koff, off_s)
+    assert np.array_equal(k2r, inv_r[perm_s])
+    single = cas.cascade_plan_create(2, N, alpha, a)
+    n1, kperm1, koff1, k2r1 = cas.cascade_plan_kv_maps_host(single)      # one partition: kv maps are the row maps
+    assert n1 == alpha and np.array_equal(kperm1, perm_r) and np.array_equal(koff1, off_r) and k2r1 is None
+
+
+@pytest.mark.parametrize("dtype,H,Hkv,N,d,kind,layout", [
+    ("f32", 4, 2, 96, 16, "msplit", "original"),
+    ("f32", 2, 2, 70, 8, "unrelated", "packed"),
+    ("bf16", 4, 2, 512, 128, "msplit", "packed"),             # 4 row shards of 128, 8 kv shards of 64 keys
+    ("bf16", 8, 2, 384, 128, "coarser", "original"),          # kv shards of 128 keys span two row shards
+    ("bf16", 4, 4, 300, 64, "unrelated", "packed"),
+    ("bf16", 4, 1, 256, 64, "msplit4", "original"),
+])
+def test_partial_attn_with_two_shardings_matches_oracle(cas, dtype, H, Hkv, N, d, kind, layout):
+    """Query rows follow the row sharding R, key/value shards the sharding S (Section 5.1, m-split of
+    Section 6.4): m, e, u~ per (R-packed row, kv shard), then the merge over the kv shards."""
+    import torch
+    B = 2
+    rng = np.random.default_rng(N + d)
+    q, k, v = rand(rng, (B, H, N, d), dtype), rand(rng, (B, Hkv, N, d), dtype), rand(rng, (B, Hkv, N, d), dtype)
+    a, alpha, kv, beta = rs_partitions(cas, N, kind, 7)
+    plan = cas.cascade_plan_create_rs(B, N, alpha, a, beta, kv)
+    _, perm, _ = orc.shard_plan(a, alpha)
+    scale = d ** -0.5
+    if layout == "packed":
+        qd, kd, vd = (dev(cas, t[:, :, perm], dtype) for t in (q, k, v))
+        row_layout = cas.ROWS_PACKED
+    else:
+        qd, kd, vd = (dev(cas, t, dtype) for t in (q, k, v))
+        row_layout = cas.ROWS_ORIGINAL
+    m = torch.full((B, H, beta, N), 7.0, dtype=torch.float32, device="cuda")
+    e = torch.full((B, H, beta, N), 7.0, dtype=torch.float32, device="cuda")
+    u = torch.full((B, beta, H, N, d), 7.0, dtype=torch.float32, device="cuda")
+    ws = cas.new_workspace(cas.cascade_partial_attn_workspace_bytes(plan, qd, H, Hkv, d))
+    cas.cascade_partial_attn(plan, qd, kd, vd, m, e, u, H, Hkv, d, scale, row_layout=row_layout, workspace=ws)
+    refs = [orc.partial_attention_rs(q[b], k[b], v[b], a, alpha, kv, beta, scale=scale) for b in range(B)]
+    ref = tuple(np.stack([r[i] for r in refs]) for i in range(3))
+    check_partials(dtype, (m, e, u), ref)
+    # merge over the beta key/value shards: plain attention in R-packed rows
+    o = torch.empty((B, N, H * d), dtype=qd.dtype, device="cuda")
+    cas.cascade_lse_merge(plan, m, e, u, o, H, Hkv, d, row_layout=cas.ROWS_PACKED)
+    o_ref = np.stack([orc.lse_merge_all(*r) for r in refs])
+    assert rel_err(host(o), o_ref) < TOL[dtype]
+
+
+@pytest.mark.parametrize("cfg_name,kind", [("small-llama", "msplit"), ("small-llama", "unrelated"),
+                                           ("f32-llama", "coarser"), ("small-gpt", "msplit")])
+@pytest.mark.parametrize("mode", ["fused", "materialised"])
+def test_layer_forward_with_two_shardings(cas, cfg_name, kind, mode):
+    cfg = {"small-llama": SMALL_LLAMA, "f32-llama": F32_LLAMA, "small-gpt": SMALL_GPT}[cfg_name]
+    attn_mode = cas.ATTN_FUSED if mode == "fused" else cas.ATTN_MATERIALISED
+    a, alpha, kv, beta = rs_partitions(cas, cfg.seq_len, kind, 13)
+    w, h = make_layer_weights(cfg), make_hidden(cfg)
+    out = cas.layer_forward_numpy(cfg.with_(n_shards=alpha), w, h, a, attn_mode=attn_mode, token_to_kv_shard=kv)
+    ref = orc.layer_direct_batch(h, w, cfg)
+    assert rel_err(out, ref) < TOL[cfg.dtype]
+    if mode == "materialised" and cfg_name == "small-llama" and kind == "msplit":
+        ref_rs = np.stack([orc.layer_sharded_rs(h[b], w, cfg, a, alpha, kv, beta) for b in range(cfg.batch)])
+        assert rel_err(out, ref_rs) < TOL[cfg.dtype]
+
+
 @pytest.mark.parametrize("dtype,d", [("f32", 32), ("bf16", 128)])
 def test_partial_attn_large_logits_are_stable(cas, dtype, d):
     plan, got, ref, _ = attn_case(cas, dtype, 1, 2, 2, 128, d, 4, "perm", "original", seed=3, amp=6.0)

@@ -518,3 +518,67 @@ def test_partials_from_layer_match_standalone_pairs():
         np.testing.assert_allclose(m[:, kk, sl], mj, rtol=1e-12)
         np.testing.assert_allclose(e[:, kk, sl], ej, rtol=1e-12)
         np.testing.assert_allclose(u[kk][:, sl], uj, rtol=1e-11, atol=1e-14)
+
+
+# ---------------------------------------------------------------- distinct hidden / key-value shardings (R != S)
+def test_m_split_assignment_matches_the_worked_example():
+    """Section 6.4: S_{m(i-1)+x} = R_{i,x}; with the N = 18 example, token t of R_{i,x} (1-based) must get
+    0-based kv shard m (i-1) + (x-1)."""
+    _, RX, _ = _read_example()
+    a = orc.cdelta_assignment(18, c=2, delta=6)
+    kv = orc.m_split_assignment(a, 3, 2)
+    want = np.empty(18, dtype=np.int64)
+    for (i, x), toks in RX.items():
+        for t in toks:
+            want[t - 1] = 2 * (i - 1) + (x - 1)
+    assert kv.tolist() == want.tolist()
+    # each kv shard lies inside one row shard, and the pieces of a row shard interleave
+    for s in range(6):
+        assert set(a[kv == s].tolist()) == {s // 2}
+
+
+def _rs_partitions(N, kind, seed):
+    if kind == "msplit":                                  # (c, delta) rows, m-split kv shards (the paper's scheme)
+        a = orc.cdelta_assignment(N, 2, 8)
+        return a, 4, orc.m_split_assignment(a, 4, 2), 8
+    if kind == "coarser":                                 # kv shards that are unions of row shards
+        a = make_assignment("perm", N, 6, seed)
+        return a, 6, (a // 2).astype(np.int32), 3
+    a = make_assignment("ragged", N, 4, seed)             # unrelated partitions
+    return a, 4, make_assignment("perm", N, 5, seed + 1), 5
+
+
+@pytest.mark.parametrize("kind", ["msplit", "coarser", "unrelated"])
+def test_partials_with_two_shardings_are_the_single_sharding_partials_rerouted(kind):
+    """A partial (m, e, u) of query row t against kv shard S_k does not depend on how rows are sharded:
+    partial_attention_rs must hold, at R-packed row inv_perm_R[t], what the single-partition routine
+    (pinned by brute force above) holds at S-packed row inv_perm_S[t]."""
+    H, Hkv, N, d = 4, 2, 24, 8
+    q, k, v = rand_qkv(21, H, Hkv, N, d)
+    a, alpha, kv, beta = _rs_partitions(N, kind, 5)
+    pos = np.random.default_rng(3).permutation(3 * N)[:N]
+    m, e, u = orc.partial_attention_rs(q, k, v, a, alpha, kv, beta, positions=pos, scale=0.3)
+    m1, e1, u1 = orc.partial_attention_all_pairs(q, k, v, kv, beta, positions=pos, scale=0.3)
+    _, _, inv_r = orc.shard_plan(a, alpha)
+    _, _, inv_s = orc.shard_plan(kv, beta)
+    np.testing.assert_array_equal(m[:, :, inv_r], m1[:, :, inv_s])
+    np.testing.assert_array_equal(e[:, :, inv_r], e1[:, :, inv_s])
+    np.testing.assert_array_equal(u[:, :, inv_r], u1[:, :, inv_s])
+    # and merged over the kv shards they give plain attention, rows in R-packed order
+    _, perm_r, _ = orc.shard_plan(a, alpha)
+    o = orc.lse_merge_all(m, e, u).reshape(N, H, d).transpose(1, 0, 2)
+    want = brute_attention(q, k, v, pos, 0.3)[:, perm_r]
+    np.testing.assert_allclose(o, want, rtol=1e-10, atol=1e-12)
+
+
+@pytest.mark.parametrize("cfg", [TINY_LLAMA, TINY_GPT])
+@pytest.mark.parametrize("kind", ["msplit", "coarser", "unrelated"])
+def test_layer_with_two_shardings_equals_layer_direct(cfg, kind):
+    w = make_layer_weights(cfg)
+    w = {k: v * (8.0 if v.ndim == 2 else 1.0) for k, v in w.items()}
+    h = make_hidden(cfg)[0]
+    a, alpha, kv, beta = _rs_partitions(cfg.seq_len, kind, 9)
+    direct = orc.layer_direct(h, w, cfg)
+    assert rel_err(orc.layer_sharded_rs(h, w, cfg, a, alpha, kv, beta), direct) < 1e-12
+    # with S = R it is Algorithm 1 as implemented by layer_sharded
+    assert rel_err(orc.layer_sharded_rs(h, w, cfg, a, alpha, a, alpha), orc.layer_sharded(h, w, cfg, a, alpha)) < 1e-13
