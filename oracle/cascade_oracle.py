@@ -286,6 +286,35 @@ def lse_merge_all(m, e, u):
     return o.transpose(1, 0, 2).reshape(N, H * d)
 
 
+# --------------------------------------------------------------------------- token-sharded KV-cache decode
+def decode_partials(q_new, k_shards, v_shards, scale=1.0):
+    """Single-token generation with cached keys and values (Cost Optimizations appendix,
+    'Caching'): only the newest token's query row is attended, by AttnNode_jk for every kv
+    shard k, against the rows of S_k cached so far (the new token's own key and value already
+    appended to its shard).  Every cached key is at or before the new position, so the mask
+    block is all zeros.  q_new (H, d); k_shards, v_shards: one (H_KV, L_k, d) array per shard
+    (L_k = 0 allowed).  Returns m, e (H, beta) and u (beta, H, d), u normalised."""
+    q = np.asarray(q_new, dtype=F64)[:, None, :]
+    H, _, d = q.shape
+    beta = len(k_shards)
+    m = np.full((H, beta), -np.inf)
+    e = np.zeros((H, beta))
+    u = np.zeros((beta, H, d))
+    for kk in range(beta):
+        K, V = np.asarray(k_shards[kk], dtype=F64), np.asarray(v_shards[kk], dtype=F64)
+        mk, ek, uk = attn_pass(q, K, V, np.zeros((1, K.shape[1])), scale)
+        m[:, kk], e[:, kk], u[kk] = mk[:, 0], ek[:, 0], uk[:, 0]
+    return m, e, u
+
+
+def decode_merge(m, e, u):
+    """Algorithm 4 lines 1-8 for the one new row: m, e (H, beta); u (beta, H, d).  Returns o (H*d)."""
+    beta = m.shape[1]
+    o = post_pass_merge([m[:, kk:kk + 1] for kk in range(beta)], [e[:, kk:kk + 1] for kk in range(beta)],
+                        [u[kk][:, None, :] for kk in range(beta)])
+    return o[:, 0].reshape(-1)
+
+
 # --------------------------------------------------------------------------- the two layer routes
 def layer_direct(h, w, cfg, positions=None, mask_kind="causal", scale=None, rows=None):
     """The unsharded layer, one sequence h (N, D).  With rows given, only those

@@ -582,3 +582,55 @@ def test_layer_with_two_shardings_equals_layer_direct(cfg, kind):
     assert rel_err(orc.layer_sharded_rs(h, w, cfg, a, alpha, kv, beta), direct) < 1e-12
     # with S = R it is Algorithm 1 as implemented by layer_sharded
     assert rel_err(orc.layer_sharded_rs(h, w, cfg, a, alpha, a, alpha), orc.layer_sharded(h, w, cfg, a, alpha)) < 1e-13
+
+
+# ---------------------------------------------------------------- token-sharded KV-cache decode
+def _cache_shards(k, v, assign, beta):
+    lists = orc.shard_index_lists(assign, beta)
+    return [k[:, S] for S in lists], [v[:, S] for S in lists]
+
+
+def test_decode_merge_is_plain_attention_of_the_last_row():
+    """Brute force: the newest token attends every cached token (its own included)."""
+    H, Hkv, N, d = 4, 2, 19, 6
+    q, k, v = rand_qkv(31, H, Hkv, N, d)
+    want = brute_attention(q, k, v, np.arange(N), 0.4)[:, N - 1]            # last row sees all N keys
+    for beta, kind, seed in [(1, "perm", 0), (4, "perm", 1), (5, "ragged", 2), (N, "singleton", 0), (8, "ragged", 3)]:
+        a = np.arange(N, dtype=np.int32) if kind == "singleton" else make_assignment(kind, N, beta, seed)
+        ks, vs = _cache_shards(k, v, a, beta)
+        m, e, u = orc.decode_partials(q[:, N - 1], ks, vs, 0.4)
+        np.testing.assert_allclose(orc.decode_merge(m, e, u), want.reshape(-1), rtol=1e-11, atol=1e-13)
+        assert ((e >= 1.0) | (e == 0.0)).all()
+        sizes = np.array([x.shape[1] for x in ks])
+        assert (e <= sizes[None, :] + 1e-12).all()
+        assert (np.isneginf(m) == (sizes[None, :] == 0)).all()             # empty cache shard: (-inf, 0, 0)
+        assert (u[sizes == 0] == 0).all()
+
+
+def test_decode_partials_are_the_prefill_partials_of_the_last_token():
+    """The cached-decode partials of the newest token equal row N-1 of the prefill partials of the
+    same sequence under the same sharding (the causal mask hides nothing from the last token)."""
+    H, Hkv, N, d, beta = 4, 4, 24, 8, 4
+    q, k, v = rand_qkv(32, H, Hkv, N, d)
+    a = make_assignment("perm", N, beta, 6)
+    m1, e1, u1 = orc.partial_attention_all_pairs(q, k, v, a, beta, scale=0.35)
+    _, _, inv = orc.shard_plan(a, beta)
+    ks, vs = _cache_shards(k, v, a, beta)
+    m, e, u = orc.decode_partials(q[:, N - 1], ks, vs, 0.35)
+    r = inv[N - 1]
+    np.testing.assert_allclose(m, m1[:, :, r], rtol=1e-13)
+    np.testing.assert_allclose(e, e1[:, :, r], rtol=1e-12)
+    np.testing.assert_allclose(u, u1[:, :, r], rtol=1e-11, atol=1e-14)
+
+
+def test_decode_single_key_shards():
+    """beta = N: every shard caches one key, so m = scale q.k, e = 1 and u is that key's value row."""
+    H, Hkv, N, d = 2, 1, 5, 4
+    q, k, v = rand_qkv(33, H, Hkv, N, d)
+    ks, vs = _cache_shards(k, v, np.arange(N, dtype=np.int32), N)
+    m, e, u = orc.decode_partials(q[:, N - 1], ks, vs, 0.5)
+    assert np.allclose(e, 1.0)
+    for kk in range(N):
+        for h in range(H):
+            assert abs(m[h, kk] - 0.5 * float(q[h, N - 1] @ k[0, kk])) < 1e-13
+            np.testing.assert_allclose(u[kk, h], v[0, kk], rtol=1e-13)
