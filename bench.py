@@ -195,6 +195,40 @@ def run_m_split(cas, cfg, steps):
     return out
 
 
+def run_decode(cas, cfg, steps, batch=32, cache_tokens=8192, shard_rows=128):
+    """Token-sharded KV-cache decode of one new token per sequence: partial attention of the new query
+    row against every cached kv shard, then the LSE merge.  HBM-bound: every cached K and V row is read once."""
+    import numpy as np
+    import torch
+    H, Hkv, d = cfg.n_heads, cfg.n_kv_heads, cfg.head_dim
+    S = cache_tokens // shard_rows
+    g = torch.Generator(device="cuda")
+    g.manual_seed(1234)
+    q = torch.randn((batch, H, d), device="cuda", generator=g).to(torch.bfloat16)
+    kc = torch.randn((batch, Hkv, S, shard_rows, d), device="cuda", generator=g).to(torch.bfloat16)
+    vc = torch.randn((batch, Hkv, S, shard_rows, d), device="cuda", generator=g).to(torch.bfloat16)
+    lens = torch.full((batch, S), shard_rows, dtype=torch.int32, device="cuda")
+    m = torch.empty((batch, H, S), dtype=torch.float32, device="cuda")
+    e = torch.empty_like(m)
+    u = torch.empty((batch, S, H, d), dtype=torch.float32, device="cuda")
+    o = torch.empty((batch, 1, H * d), dtype=torch.bfloat16, device="cuda")
+    plan = cas.cascade_plan_create(batch, 1, S, np.zeros(1, dtype=np.int32))
+    attn = lambda: cas.cascade_decode_partial_attn(q, kc, vc, lens, m, e, u, d ** -0.5)
+    merge = lambda: cas.cascade_lse_merge(plan, m.view(batch, H, S, 1), e.view(batch, H, S, 1),
+                                          u.view(batch, S, H, 1, d), o, H, Hkv, d)
+    for _ in range(3):
+        attn(); merge()
+    t_attn = time_steps(attn, steps)
+    t_merge = time_steps(merge, steps)
+    cache_bytes = 2 * kc.numel() * 2
+    partial_bytes = (2 * m.numel() + u.numel()) * 4
+    return {"batch": batch, "cache_tokens": cache_tokens, "kv_shards": S, "n_heads": H, "n_kv_heads": Hkv, "head_dim": d,
+            "partial_attn_us": t_attn * 1e6, "cache_bytes": cache_bytes,
+            "partial_attn_GBs": (cache_bytes + partial_bytes) / t_attn / 1e9,
+            "partial_attn_frac_of_hbm_peak": (cache_bytes + partial_bytes) / t_attn / 1e9 / HBM_PEAK_GBS,
+            "lse_merge_us": t_merge * 1e6, "partial_bytes": partial_bytes}
+
+
 def cpu_baseline(cfg, host):
     """The oracle as it stands, on the host cores: the whole unsharded float64 layer, one repetition."""
     import numpy as np
@@ -294,6 +328,8 @@ def main():
     if bf16:
         torch.cuda.empty_cache()
         out["m_split"] = run_m_split(cas, cfg, max(3, args.steps // 4))
+        torch.cuda.empty_cache()
+        out["kv_cache_decode"] = run_decode(cas, cfg, args.steps)
     if args.all:
         others = {}
         for key in ("C2", "C4", "C5"):

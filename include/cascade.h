@@ -276,6 +276,28 @@ CASCADE_API int32_t cascade_layer_forward_staged(const cascade_plan *plan, const
 CASCADE_API int32_t cascade_layer_partials(const cascade_plan *plan, const cascade_layer_desc *desc,
                                void *workspace, float **m, float **e, float **u);
 
+/* ------------------------------------------------------------------ KV-cache decode
+ * Cost Optimizations appendix ("Caching"): in single-token generation only the
+ * newest token's query row is attended, by AttnNode_jk for every kv shard k,
+ * against the keys and values of S_k cached so far (the new token's own k, v
+ * already appended to its shard by the caller).  One partial per shard:
+ *   m, e [B, H, n_shards]        (= [B, H, n_shards, 1] of cascade_partial_attn)
+ *   u    [B, n_shards, H, d]     fp32, CASCADE_U_* as in desc->u_mode
+ * which cascade_lse_merge combines when called with a plan of seq_len 1 and the
+ * same n_shards (cascade_plan_create(batch, 1, n_shards, {j}, ...)).
+ *   q [B, H, d]; k_cache, v_cache [B, H_KV, n_shards, shard_capacity, d] (dense,
+ *   desc->dtype, 16-byte aligned); shard_len_dev [B, n_shards] int32 DEVICE:
+ *   rows of each shard that are valid (clamped to shard_capacity; 0 gives
+ *   m = -inf, e = 0, u = 0).  No mask: every cached key is at or before the new
+ *   position.  From desc: dtype, n_heads, n_kv_heads, head_dim, scale, u_mode
+ *   (row_layout and strides are ignored).  head_dim must be 8 * 2^j (bf16) or
+ *   4 * 2^j (f32), at most 512 / 256.
+ * Errors: EINVAL, ESHAPE (H % H_KV), EUNSUPPORTED (head_dim, alignment), EHIP.   */
+CASCADE_API int32_t cascade_decode_partial_attn(const cascade_attn_desc *desc, int32_t batch, int32_t n_shards,
+                                    int32_t shard_capacity, const int32_t *shard_len_dev,
+                                    const void *q, const void *k_cache, const void *v_cache,
+                                    float *m, float *e, float *u, void *stream);
+
 /* ------------------------------------------------------------------ measured ceiling
  * Not a step of the method: the rate (TFLOP/s) this device sustains on back-to-back
  * bf16 16x16x32 MFMAs with random operands, for the roofline figures quoted next

@@ -29,7 +29,7 @@ EXPORTS = ["cascade_plan_create", "cascade_plan_create_rs", "cascade_plan_maps",
            "cascade_last_hip_error", "cascade_shard_gemm", "cascade_partial_attn_workspace_bytes",
            "cascade_partial_attn", "cascade_lse_merge", "cascade_layer_workspace_bytes",
            "cascade_layer_forward", "cascade_layer_forward_staged", "cascade_layer_partials",
-           "cascade_mfma_ceiling"]
+           "cascade_decode_partial_attn", "cascade_mfma_ceiling"]
 N_STAGE_EVENTS = 10
 STAGE_NAMES = ["gather_norm1", "qkv_gemm", "rope", "attention", "lse_merge", "o_proj", "norm2", "ffn_up", "ffn_down"]
 
@@ -117,6 +117,8 @@ def load_library():
     lib.cascade_layer_forward_staged.restype = I32
     lib.cascade_layer_partials.argtypes = [VP, P(LayerDesc), VP, P(VP), P(VP), P(VP)]
     lib.cascade_layer_partials.restype = I32
+    lib.cascade_decode_partial_attn.argtypes = [P(AttnDesc), I32, I32, I32, VP, VP, VP, VP, VP, VP, VP, VP]
+    lib.cascade_decode_partial_attn.restype = I32
     lib.cascade_mfma_ceiling.argtypes = [I32, I32, P(C.c_float), VP]
     lib.cascade_mfma_ceiling.restype = I32
     _lib = lib
@@ -373,6 +375,17 @@ def to_device(x, dtype_name):
 def new_workspace(nbytes):
     import torch
     return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device="cuda")
+
+
+def cascade_decode_partial_attn(q, k_cache, v_cache, shard_len, m, e, u, scale, u_mode=U_UNNORMALISED, stream=None):
+    """q [B,H,d]; k_cache, v_cache [B,Hkv,S,cap,d]; shard_len [B,S] int32 (device); m, e [B,H,S]; u [B,S,H,d]."""
+    lib = load_library()
+    B, H, d = q.shape
+    Hkv, S, cap = k_cache.shape[1], k_cache.shape[2], k_cache.shape[3]
+    desc = _attn_desc(q, H, Hkv, d, scale, ROWS_PACKED, u_mode)
+    st = lib.cascade_decode_partial_attn(C.byref(desc), B, S, cap, _ptr(shard_len), _ptr(q), _ptr(k_cache), _ptr(v_cache),
+                                         _ptr(m), _ptr(e), _ptr(u), _stream(stream))
+    _check(st, "cascade_decode_partial_attn")
 
 
 def cascade_mfma_ceiling(lds_operands, iters=200000, stream=None):

@@ -1,0 +1,158 @@
+"""Token-sharded KV-cache decode: the newest token's query row against every cached kv shard
+(Cost Optimizations appendix, "Caching"), element-wise against the oracle, then the merge through
+cascade_lse_merge with a one-row plan."""
+import numpy as np
+import pytest
+
+from cascade_inputs import bf16_bits, make_assignment, round_to_bf16
+from oracle import cascade_oracle as orc
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-5, "bf16": 2e-2}
+
+
+@pytest.fixture(scope="module")
+def cas():
+    import torch
+    assert torch.cuda.is_available()
+    import paper_2507_05228_amd as cas
+    cas.load_library()
+    return cas
+
+
+def build_cache(rng, dtype, B, H, Hkv, d, lens, cap, amp=1.0):
+    """Random q and per-shard caches; rows past a shard's length hold a large sentinel that must never be read into
+    a result."""
+    S = lens.shape[1]
+    q = amp * rng.standard_normal((B, H, d))
+    kc = np.full((B, Hkv, S, cap, d), 777.0)
+    vc = np.full((B, Hkv, S, cap, d), -777.0)
+    for b in range(B):
+        for k in range(S):
+            L = lens[b, k]
+            kc[b, :, k, :L] = amp * rng.standard_normal((Hkv, L, d))
+            vc[b, :, k, :L] = rng.standard_normal((Hkv, L, d))
+    if dtype == "bf16":
+        q, kc, vc = (round_to_bf16(t.astype(np.float32)).astype(np.float64) for t in (q, kc, vc))
+    else:
+        q, kc, vc = (t.astype(np.float32).astype(np.float64) for t in (q, kc, vc))
+    return q, kc, vc
+
+
+def run_case(cas, dtype, B, H, Hkv, d, lens, cap, u_mode="unnorm", amp=1.0, seed=0):
+    import torch
+    rng = np.random.default_rng(seed)
+    lens = np.asarray(lens, dtype=np.int32).reshape(B, -1)
+    S = lens.shape[1]
+    q, kc, vc = build_cache(rng, dtype, B, H, Hkv, d, lens, cap, amp)
+    qd, kd, vd = (cas.to_device(t, dtype) for t in (q, kc, vc))
+    ld = torch.from_numpy(lens).cuda()
+    m = torch.full((B, H, S), 7.0, dtype=torch.float32, device="cuda")
+    e = torch.full((B, H, S), 7.0, dtype=torch.float32, device="cuda")
+    u = torch.full((B, S, H, d), 7.0, dtype=torch.float32, device="cuda")
+    scale = d ** -0.5
+    mode = cas.U_UNNORMALISED if u_mode == "unnorm" else cas.U_NORMALISED
+    cas.cascade_decode_partial_attn(qd, kd, vd, ld, m, e, u, scale, u_mode=mode)
+    torch.cuda.synchronize()
+    refs = [orc.decode_partials(q[b], [kc[b, :, k, :lens[b, k]] for k in range(S)],
+                                [vc[b, :, k, :lens[b, k]] for k in range(S)], scale) for b in range(B)]
+    m_r = np.stack([r[0] for r in refs]); e_r = np.stack([r[1] for r in refs]); u_r = np.stack([r[2] for r in refs])
+    mg, eg, ug = (t.cpu().numpy().astype(np.float64) for t in (m, e, u))
+    dead = ~np.isfinite(m_r)
+    assert np.array_equal(~np.isfinite(mg), dead)
+    assert (mg[dead] == -np.inf).all() and (eg[dead] == 0).all()
+    tol_stat = 1e-5 if dtype == "f32" else 1e-4
+    assert (np.abs(mg[~dead] - m_r[~dead]) / np.maximum(1.0, np.abs(m_r[~dead]))).max() < tol_stat
+    assert (np.abs(eg - e_r) / np.maximum(1.0, e_r)).max() < tol_stat
+    want_u = u_r if u_mode == "norm" else e_r.transpose(0, 2, 1)[..., None] * u_r
+    assert np.abs(ug - want_u).max() / max(np.abs(want_u).max(), 1e-300) < TOL[dtype]
+    assert (ug[dead.transpose(0, 2, 1)] == 0).all()
+    # merge through the prefill merge with a one-row plan (bf16: the head dims the prefill path is built for)
+    if u_mode == "unnorm" and (dtype == "f32" or d in (64, 128)):
+        plan = cas.cascade_plan_create(B, 1, S, np.array([0], dtype=np.int32))
+        o = torch.empty((B, 1, H * d), dtype=qd.dtype, device="cuda")
+        cas.cascade_lse_merge(plan, m.view(B, H, S, 1), e.view(B, H, S, 1), u.view(B, S, H, 1, d), o, H, Hkv, d,
+                              row_layout=cas.ROWS_PACKED)
+        torch.cuda.synchronize()
+        o_ref = np.stack([orc.decode_merge(*r) for r in refs])
+        got = o.float().cpu().numpy().astype(np.float64).reshape(B, H * d)
+        live = np.isfinite(m_r).any(axis=2)                    # heads with at least one cached key
+        if live.any():
+            err = np.abs(got - o_ref).reshape(B, H, d)[live].max() / max(np.abs(o_ref).max(), 1e-300)
+            assert err < TOL[dtype]
+    return mg, eg, ug
+
+
+@pytest.mark.parametrize("dtype,H,Hkv,d", [
+    ("f32", 4, 4, 16), ("f32", 6, 2, 32), ("f32", 8, 1, 64), ("f32", 2, 1, 256), ("f32", 3, 3, 4),
+    ("bf16", 8, 2, 128), ("bf16", 4, 4, 64), ("bf16", 8, 1, 128), ("bf16", 4, 2, 64), ("bf16", 6, 2, 128),
+    ("bf16", 2, 2, 8), ("bf16", 2, 1, 512), ("bf16", 12, 2, 64),
+])
+def test_decode_partials_match_oracle(cas, dtype, H, Hkv, d):
+    lens = [[37, 0, 128, 1, 64, 100], [5, 128, 0, 0, 77, 3]]       # ragged, empty and full shards
+    run_case(cas, dtype, 2, H, Hkv, d, lens, 128, seed=H * d)
+
+
+@pytest.mark.parametrize("dtype,d", [("f32", 16), ("bf16", 128)])
+def test_decode_normalised_mode_and_large_logits(cas, dtype, d):
+    run_case(cas, dtype, 1, 4, 2, d, [[50, 9, 300, 17]], 300, u_mode="norm", seed=3)
+    run_case(cas, dtype, 1, 4, 2, d, [[50, 9, 300, 17]], 300, u_mode="unnorm", amp=6.0, seed=4)
+
+
+def test_decode_equals_last_row_of_prefill_partials(cas):
+    """Same sequence, same sharding: decode of the newest token == row N-1 of cascade_partial_attn."""
+    import torch
+    B, H, Hkv, N, d, beta = 1, 8, 2, 300, 128, 5
+    rng = np.random.default_rng(5)
+    q = round_to_bf16(rng.standard_normal((B, H, N, d)).astype(np.float32))
+    k = round_to_bf16(rng.standard_normal((B, Hkv, N, d)).astype(np.float32))
+    v = round_to_bf16(rng.standard_normal((B, Hkv, N, d)).astype(np.float32))
+    a = make_assignment("ragged", N, beta, 2)
+    plan = cas.cascade_plan_create(B, N, beta, a)
+    qd, kd, vd = (cas.to_device(t, "bf16") for t in (q, k, v))
+    m = torch.empty((B, H, beta, N), dtype=torch.float32, device="cuda")
+    e = torch.empty_like(m)
+    u = torch.empty((B, beta, H, N, d), dtype=torch.float32, device="cuda")
+    ws = cas.new_workspace(cas.cascade_partial_attn_workspace_bytes(plan, qd, H, Hkv, d))
+    cas.cascade_partial_attn(plan, qd, kd, vd, m, e, u, H, Hkv, d, d ** -0.5, row_layout=cas.ROWS_ORIGINAL, workspace=ws)
+    lists = orc.shard_index_lists(a, beta)
+    _, _, inv = orc.shard_plan(a, beta)
+    cap = max(len(S) for S in lists)
+    kc = np.zeros((B, Hkv, beta, cap, d), dtype=np.float32)
+    vc = np.zeros_like(kc)
+    for kk, S in enumerate(lists):
+        kc[:, :, kk, :len(S)] = k[:, :, S]
+        vc[:, :, kk, :len(S)] = v[:, :, S]
+    lens = torch.tensor([[len(S) for S in lists]], dtype=torch.int32, device="cuda")
+    md = torch.empty((B, H, beta), dtype=torch.float32, device="cuda")
+    ed = torch.empty_like(md)
+    ud = torch.empty((B, beta, H, d), dtype=torch.float32, device="cuda")
+    cas.cascade_decode_partial_attn(cas.to_device(q[:, :, N - 1], "bf16"), cas.to_device(kc, "bf16"),
+                                    cas.to_device(vc, "bf16"), lens, md, ed, ud, d ** -0.5)
+    torch.cuda.synchronize()
+    r = int(inv[N - 1])
+    assert torch.allclose(md, m[:, :, :, r], rtol=1e-5, atol=1e-5)
+    assert torch.allclose(ed, e[:, :, :, r], rtol=1e-4, atol=1e-5)
+    ref_u = u[:, :, :, r]
+    assert (ud - ref_u).abs().max() / ref_u.abs().max() < 2e-2
+
+
+def test_decode_error_paths(cas):
+    import torch
+    q = torch.zeros(1, 4, 64, dtype=torch.bfloat16, device="cuda")
+    kc = torch.zeros(1, 2, 3, 16, 64, dtype=torch.bfloat16, device="cuda")
+    lens = torch.zeros(1, 3, dtype=torch.int32, device="cuda")
+    m = torch.zeros(1, 4, 3, device="cuda"); u = torch.zeros(1, 3, 4, 64, device="cuda")
+    with pytest.raises(cas.CascadeError) as ei:
+        cas.cascade_decode_partial_attn(q, kc, kc, lens, m, m.clone(), None, 0.125)
+    assert ei.value.status == cas.EINVAL
+    kc3 = torch.zeros(1, 3, 3, 16, 64, dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(cas.CascadeError) as ei:                              # H % H_KV != 0
+        cas.cascade_decode_partial_attn(q, kc3, kc3, lens, m, m.clone(), u, 0.125)
+    assert ei.value.status == cas.ESHAPE
+    q48 = torch.zeros(1, 4, 48, dtype=torch.bfloat16, device="cuda")
+    kc48 = torch.zeros(1, 2, 3, 16, 48, dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(cas.CascadeError) as ei:                              # 48 is not 8 * 2^j
+        cas.cascade_decode_partial_attn(q48, kc48, kc48, lens, m, m.clone(), torch.zeros(1, 3, 4, 48, device="cuda"), 0.125)
+    assert ei.value.status == cas.EUNSUPPORTED
