@@ -61,7 +61,7 @@ extern "C" int32_t cascade_shard_gemm(const cascade_plan *plan, const cascade_ge
         RopeArgs r = {};
         r.dtype = d->dtype; r.rows = d->rows; r.seq_len = plan->seq_len;
         r.n_rope_heads = d->rope_cols / d->head_dim; r.head_dim = d->head_dim; r.ld = d->n_out;
-        r.theta = d->rope_theta; r.pos_packed = plan->pos_packed_d; r.x = Y;
+        r.theta = d->rope_theta; r.pos_packed = plan->pos_packed_d; r.x = Y; r.max_pos = plan->max_abs_pos;
         st = launch_rope(r, s);
     }
     return st;
@@ -254,7 +254,7 @@ static int32_t layer_forward_impl(const cascade_plan *plan, const cascade_layer_
     if ((st = run_gemm(g, s)) != CASCADE_OK) return st;
     if ((st = mark()) != CASCADE_OK) return st;                                   // 2: qkv GEMM
     if (d->rope) {
-        RopeArgs r = {d->dtype, T, N, H + Hkv, hd, QW, d->rope_theta, plan->pos_packed_d, qkv};
+        RopeArgs r = {d->dtype, T, N, H + Hkv, hd, QW, d->rope_theta, plan->pos_packed_d, qkv, plan->max_abs_pos};
         if ((st = launch_rope(r, s)) != CASCADE_OK) return st;
     }
     if ((st = mark()) != CASCADE_OK) return st;                                   // 3: rotary embedding

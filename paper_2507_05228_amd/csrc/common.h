@@ -37,6 +37,7 @@ struct cascade_plan {
     int32_t *perm_h, *inv_perm_h, *offsets_h, *pos_packed_h;
     // device copies
     int32_t *perm_d, *inv_perm_d, *offsets_d, *pos_packed_d;
+    int32_t max_abs_pos;        // largest |position|
     CascadeTileList tiles[4];   // granules 32, 64, 128, 256
     // Key/value partition S when it differs from the row partition R (Section 5.1; the m-split of
     // Section 6.4): a plan of its own over the same tokens, plus the map from its packed rows to
@@ -102,6 +103,7 @@ struct RopeArgs {
     float theta;
     const int32_t *pos_packed;       // [seq_len]
     void *x;                         // in place
+    int32_t max_pos;                 // largest |position| of the plan (the fast bf16 path needs < 2^24)
 };
 int32_t launch_rope(const RopeArgs &a, hipStream_t s);
 

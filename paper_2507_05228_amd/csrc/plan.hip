@@ -124,8 +124,11 @@ static int32_t build_plan(cascade_plan **out, int32_t batch, int32_t seq_len, in
             p->inv_perm_h[t] = r;
         }
     }
-    for (int r = 0; r < seq_len; ++r)
+    for (int r = 0; r < seq_len; ++r) {
         p->pos_packed_h[r] = positions_host ? positions_host[p->perm_h[r]] : p->perm_h[r];
+        const int64_t ap = std::llabs((int64_t)p->pos_packed_h[r]);
+        p->max_abs_pos = (int32_t)std::min<int64_t>(std::max<int64_t>(p->max_abs_pos, ap), INT32_MAX);
+    }
 
     hipError_t e = hipGetDevice(&p->device);
     if (e == hipSuccess) e = to_device(&p->perm_d, p->perm_h, seq_len);

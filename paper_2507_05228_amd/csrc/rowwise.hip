@@ -146,8 +146,17 @@ __global__ __launch_bounds__(256) void rope_kernel(T *__restrict__ x, int64_t to
 }
 
 // Vector variant for bf16: one thread rotates 8 consecutive pairs (two 16-byte pieces half a head apart).
+// The angle is carried in revolutions: rev[i] = theta^(-2i/d) / (2 pi) comes from the host in double
+// precision, split into two floats, and position * rev is formed with a compensated product, so the
+// fractional part (all that sine and cosine need) stays accurate to ~1e-7 revolutions however large the
+// position; sine and cosine are then single hardware instructions.
+#define ROPE_MAX_HALF 128
+struct RopeFreq {
+    float hi[ROPE_MAX_HALF], lo[ROPE_MAX_HALF];
+};
+
 __global__ __launch_bounds__(256) void rope_vec_kernel(bf16_t *__restrict__ x, int64_t total_units, int n_rope_heads,
-                                                       int head_dim, int64_t ld, float log2_theta,
+                                                       int head_dim, int64_t ld, RopeFreq freq,
                                                        const int32_t *__restrict__ pos_packed, int seq_len) {
     const int half = head_dim >> 1;
     const int upr = n_rope_heads * (half / 8);                    // units per row
@@ -155,15 +164,17 @@ __global__ __launch_bounds__(256) void rope_vec_kernel(bf16_t *__restrict__ x, i
         const int64_t r = id / upr;
         const int rem = (int)(id - r * upr);
         const int h = rem / (half / 8), i0 = (rem % (half / 8)) * 8;
-        const float pos = (float)pos_packed[(int)(r % seq_len)];
+        const float pos = (float)pos_packed[(int)(r % seq_len)];  // exact: positions are below 2^24
         bf16_t *p = x + r * ld + (int64_t)h * head_dim + i0;
         const bf16x8 a = *(const bf16x8 *)p, b = *(const bf16x8 *)(p + half);
         bf16x8 oa, ob;
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            const float inv_freq = exp2f(-2.0f * (float)(i0 + j) / (float)head_dim * log2_theta);
-            float sn, cs;
-            sincosf(pos * inv_freq, &sn, &cs);
+            const float c_hi = freq.hi[i0 + j], c_lo = freq.lo[i0 + j];
+            const float r_hi = pos * c_hi;
+            const float r_err = fmaf(pos, c_hi, -r_hi) + pos * c_lo;          // pos * (hi + lo) = r_hi + r_err
+            const float rev = (r_hi - floorf(r_hi)) + r_err;
+            const float sn = __builtin_amdgcn_sinf(rev), cs = __builtin_amdgcn_cosf(rev);
             const float fa = (float)a[j], fb = (float)b[j];
             oa[j] = (bf16_t)(fa * cs - fb * sn);
             ob[j] = (bf16_t)(fb * cs + fa * sn);
@@ -176,11 +187,18 @@ __global__ __launch_bounds__(256) void rope_vec_kernel(bf16_t *__restrict__ x, i
 int32_t launch_rope(const RopeArgs &a, hipStream_t s) {
     int64_t total = (int64_t)a.rows * a.n_rope_heads * (a.head_dim / 2);
     if (total == 0) return CASCADE_OK;
-    if (a.dtype == CASCADE_BF16 && (a.head_dim / 2) % 8 == 0 && a.ld % 8 == 0 && (uintptr_t)a.x % 16 == 0) {
+    if (a.dtype == CASCADE_BF16 && (a.head_dim / 2) % 8 == 0 && a.head_dim / 2 <= ROPE_MAX_HALF && a.ld % 8 == 0 &&
+        (uintptr_t)a.x % 16 == 0 && a.max_pos < (1 << 24)) {
         const int64_t units = total / 8;
         const int grid = (int)std::min<int64_t>((units + 255) / 256, 1 << 20);
+        RopeFreq freq;
+        for (int i = 0; i < a.head_dim / 2; ++i) {
+            const double rev = pow((double)a.theta, -2.0 * i / a.head_dim) / 6.283185307179586476925;
+            freq.hi[i] = (float)rev;
+            freq.lo[i] = (float)(rev - (double)freq.hi[i]);
+        }
         hipLaunchKernelGGL(rope_vec_kernel, dim3(grid), dim3(256), 0, s, (bf16_t *)a.x, units, a.n_rope_heads,
-                           a.head_dim, a.ld, log2f(a.theta), a.pos_packed, a.seq_len);
+                           a.head_dim, a.ld, freq, a.pos_packed, a.seq_len);
         CASCADE_HIP_TRY(hipGetLastError());
         return CASCADE_OK;
     }
