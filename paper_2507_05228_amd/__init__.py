@@ -77,6 +77,10 @@ def load_library():
     global _lib
     if _lib is not None:
         return _lib
+    try:
+        import torch  # noqa: F401  (its HIP runtime must be the one this process initialises first)
+    except ImportError:
+        pass
     if not os.path.exists(LIB_PATH):
         raise RuntimeError(f"{LIB_PATH} is missing: run `python __graft_entry__.py` (build()) first; "
                            "there is no fallback path")

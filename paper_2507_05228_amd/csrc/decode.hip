@@ -3,12 +3,15 @@
 // which cascade_lse_merge then combines exactly as in the prefill path (Algorithm 4 lines 1-8).
 // Every cached key is at or before the new position, so there is no mask; only the shard lengths.
 //
-// HBM-bound: each cached K and V row is read once.  One workgroup (4 wavefronts) per (shard, kv head,
-// sequence); the REP query heads that share the kv head are processed together so the cache is read
-// once for all of them.  A row is spread over LPR = d / VEC lanes (16 bytes per lane), so one
-// wavefront instruction reads 64 / LPR consecutive rows, fully coalesced.  Scores are reduced over the
-// LPR lanes with xor shuffles; each lane group keeps a running (m, e, u~) per head (the same online
-// recurrence as the fused prefill kernel), merged across lane groups and wavefronts at the end.
+// HBM-bound: each cached K and V row is read once.  WPS wavefronts share one (shard, kv head,
+// sequence): 1 for small shards (four shards per workgroup, no LDS, no barrier), 4 for large ones
+// (more loads in flight per shard; the four running states are merged through LDS).  The REP query
+// heads that share the kv head are processed together so the cache is read once for all of them.
+// A row is spread over LPR = d / VEC lanes (16 bytes per lane), so one wavefront instruction reads
+// 64 / LPR consecutive rows, fully coalesced, and the rows of the next two steps are requested before
+// the arithmetic of the current one.  Scores are reduced over the LPR lanes with xor shuffles; each
+// lane group keeps a running (m, e, u~) per head (the same online recurrence as the fused prefill
+// kernel); the lane groups of a wavefront are merged with shuffles at the end.
 #include <cmath>
 #include "common.h"
 #include "device_utils.h"
@@ -27,18 +30,21 @@ struct DecodeParams {
     int32_t rep;
 };
 
-template <typename T, int REP, int LPR>
+template <typename T, int REP, int LPR, int WPS>
 __global__ __launch_bounds__(256) void decode_attn_kernel(DecodeParams p) {
     constexpr int VEC = 16 / sizeof(T);
     constexpr int RPW = 64 / LPR;                          // rows per wavefront instruction
+    constexpr int AHEAD = WPS == 1 ? 2 : 1;                // row steps requested ahead of their use
     typedef T vecT __attribute__((ext_vector_type(VEC)));
-    __shared__ float red_me[4][REP][2];
-    extern __shared__ float red_u[];                       // [4][REP][d]
+    __shared__ float red_me[WPS == 1 ? 1 : 4][REP][2];
+    extern __shared__ float red_u[];                       // [4][REP][d] when WPS == 4
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int sub = lane % LPR, rgrp = lane / LPR;
-    const int k = blockIdx.x, b = blockIdx.z;
-    const int head0 = p.per_head ? blockIdx.y : blockIdx.y * REP;      // first query head of this workgroup
+    const int wsub = wave % WPS;                           // this wavefront's share of the shard's rows
+    const int k = blockIdx.x * (4 / WPS) + wave / WPS, b = blockIdx.z;
+    if (k >= p.S) return;                                  // uniform over the wavefronts that share a shard
+    const int head0 = p.per_head ? blockIdx.y : blockIdx.y * REP;      // first query head handled here
     const int g = p.per_head ? blockIdx.y / p.rep : blockIdx.y;        // kv head
     const int d = p.d;
     const int len = min(p.shard_len[b * p.S + k], p.cap);
@@ -62,32 +68,46 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(DecodeParams p) {
     const int64_t base = (((int64_t)b * p.Hkv + g) * p.S + k) * p.cap;
     const T *kc = (const T *)p.kc + base * d + sub * VEC;
     const T *vc = (const T *)p.vc + base * d + sub * VEC;
-    const int iters = (len + 4 * RPW - 1) / (4 * RPW);     // uniform trip count: shuffles stay convergent
-    for (int it = 0; it < iters; ++it) {
-        const int r = it * 4 * RPW + wave * RPW + rgrp;
-        const bool valid = r < len;
-        const int rr = valid ? r : 0;                      // row 0 exists whenever the loop runs
-        const vecT kv = *(const vecT *)(kc + (int64_t)rr * d);
-        const vecT vv = *(const vecT *)(vc + (int64_t)rr * d);
+    const int iters = (len + WPS * RPW - 1) / (WPS * RPW);  // uniform trip count: shuffles stay convergent
+    vecT kbuf[AHEAD + 1], vbuf[AHEAD + 1];
+    auto row_of = [&](int it) { return (it * WPS + wsub) * RPW + rgrp; };
+    auto load_row = [&](int it, vecT &kv, vecT &vv) {
+        const int r = row_of(it);
+        const int rr = r < len ? r : 0;                    // row 0 exists whenever the loop runs
+        kv = *(const vecT *)(kc + (int64_t)rr * d);
+        vv = *(const vecT *)(vc + (int64_t)rr * d);
+    };
 #pragma unroll
-        for (int h = 0; h < REP; ++h) {
-            float s = 0.f;
+    for (int a = 0; a < AHEAD; ++a)
+        if (a < iters) load_row(a, kbuf[a], vbuf[a]);
+    for (int it0 = 0; it0 < iters; it0 += AHEAD + 1) {
 #pragma unroll
-            for (int i = 0; i < VEC; ++i) s = fmaf(qf[h][i], (float)kv[i], s);
+        for (int a = 0; a <= AHEAD; ++a) {                 // unrolled so the row buffers stay in registers
+            const int it = it0 + a;
+            if (it >= iters) break;
+            if (it + AHEAD < iters) load_row(it + AHEAD, kbuf[(a + AHEAD) % (AHEAD + 1)], vbuf[(a + AHEAD) % (AHEAD + 1)]);
+            const vecT kv = kbuf[a], vv = vbuf[a];
+            const bool valid = row_of(it) < len;
 #pragma unroll
-            for (int o = LPR / 2; o > 0; o >>= 1) s += __shfl_xor(s, o, WAVE);
-            if (!valid) s = -INFINITY;
-            const float m_new = fmaxf(mrun[h], s);
-            const float m_sub = m_new == -INFINITY ? 0.f : m_new;
-            const float alpha = __builtin_amdgcn_exp2f(mrun[h] - m_sub);
-            const float pr = __builtin_amdgcn_exp2f(s - m_sub);
-            mrun[h] = m_new;
-            erun[h] = erun[h] * alpha + pr;
+            for (int h = 0; h < REP; ++h) {
+                float s = 0.f;
 #pragma unroll
-            for (int i = 0; i < VEC; ++i) acc[h][i] = acc[h][i] * alpha + pr * (float)vv[i];
+                for (int i = 0; i < VEC; ++i) s = fmaf(qf[h][i], (float)kv[i], s);
+#pragma unroll
+                for (int o = LPR / 2; o > 0; o >>= 1) s += __shfl_xor(s, o, WAVE);
+                if (!valid) s = -INFINITY;
+                const float m_new = fmaxf(mrun[h], s);
+                const float m_sub = m_new == -INFINITY ? 0.f : m_new;
+                const float alpha = __builtin_amdgcn_exp2f(mrun[h] - m_sub);
+                const float pr = __builtin_amdgcn_exp2f(s - m_sub);
+                mrun[h] = m_new;
+                erun[h] = erun[h] * alpha + pr;
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) acc[h][i] = acc[h][i] * alpha + pr * (float)vv[i];
+            }
         }
     }
-    // merge the RPW lane groups of the wavefront (lanes with equal `sub`), then the 4 wavefronts
+    // merge the RPW lane groups of the wavefront (lanes with equal `sub`)
 #pragma unroll
     for (int h = 0; h < REP; ++h) {
 #pragma unroll
@@ -101,7 +121,28 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(DecodeParams p) {
             for (int i = 0; i < VEC; ++i) acc[h][i] = acc[h][i] * a0 + __shfl_xor(acc[h][i], o, WAVE) * a1;
             mrun[h] = m_new;
         }
+    }
+    if (WPS == 1) {                                        // the wavefront owns the shard: write the partial
         if (lane < LPR) {
+#pragma unroll
+            for (int h = 0; h < REP; ++h) {
+                const int head = head0 + h;
+                if (lane == 0) {
+                    p.m[((int64_t)b * p.H + head) * p.S + k] = mrun[h] * LN2;     // back to the units of a
+                    p.e[((int64_t)b * p.H + head) * p.S + k] = erun[h];
+                }
+                const float f = p.u_mode == CASCADE_U_NORMALISED ? (erun[h] > 0.f ? 1.0f / erun[h] : 0.f) : 1.0f;
+                float *up = p.u + (((int64_t)b * p.S + k) * p.H + head) * d + sub * VEC;
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) up[i] = acc[h][i] * f;
+            }
+        }
+        return;
+    }
+    // four wavefronts per shard: merge their states through LDS
+    if (lane < LPR) {
+#pragma unroll
+        for (int h = 0; h < REP; ++h) {
             if (lane == 0) { red_me[wave][h][0] = mrun[h]; red_me[wave][h][1] = erun[h]; }
 #pragma unroll
             for (int i = 0; i < VEC; ++i) red_u[(wave * REP + h) * d + sub * VEC + i] = acc[h][i];
@@ -123,7 +164,7 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(DecodeParams p) {
         }
         const int head = head0 + h;
         if (i == 0) {
-            p.m[((int64_t)b * p.H + head) * p.S + k] = n * LN2;           // back to the units of a
+            p.m[((int64_t)b * p.H + head) * p.S + k] = n * LN2;
             p.e[((int64_t)b * p.H + head) * p.S + k] = wsum;
         }
         const float f = p.u_mode == CASCADE_U_NORMALISED ? (wsum > 0.f ? 1.0f / wsum : 0.f) : 1.0f;
@@ -132,11 +173,19 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(DecodeParams p) {
 }
 
 template <typename T, int REP>
-static int32_t launch_lpr(const DecodeParams &p, dim3 grid, hipStream_t s) {
+static int32_t launch_lpr(const DecodeParams &p, int y_dim, hipStream_t s) {
     constexpr int VEC = 16 / sizeof(T);
     const int lpr = p.d / VEC;
-    const size_t lds = (size_t)4 * REP * p.d * sizeof(float);
-#define DECODE_LAUNCH(L) hipLaunchKernelGGL((decode_attn_kernel<T, REP, L>), grid, dim3(256), lds, s, p)
+    // shards of at least 256 rows get four wavefronts each (measured on MI355X: 5.1 against 3.8 TB/s at
+    // 512 rows; at 64-128 rows one wavefront per shard wins, 4.4 against 3.6-4.2 TB/s)
+    const bool wide = p.cap >= 256;
+    const dim3 grid(wide ? p.S : (p.S + 3) / 4, y_dim, p.B);
+    const size_t lds = wide ? (size_t)4 * REP * p.d * sizeof(float) : 0;
+#define DECODE_LAUNCH(L)                                                                              \
+    do {                                                                                              \
+        if (wide) hipLaunchKernelGGL((decode_attn_kernel<T, REP, L, 4>), grid, dim3(256), lds, s, p); \
+        else hipLaunchKernelGGL((decode_attn_kernel<T, REP, L, 1>), grid, dim3(256), 0, s, p);        \
+    } while (0)
     switch (lpr) {
         case 1: DECODE_LAUNCH(1); break;
         case 2: DECODE_LAUNCH(2); break;
@@ -156,20 +205,18 @@ template <typename T>
 static int32_t launch_rep(DecodeParams p, hipStream_t s) {
     const int rep = p.H / p.Hkv;
     p.rep = rep;
-    if ((int64_t)p.S > 2147483647 || p.H > 65535 || p.B > 65535) return CASCADE_EUNSUPPORTED;
+    if (p.H > 65535 || p.B > 65535) return CASCADE_EUNSUPPORTED;
     if (rep == 1 || rep == 2 || rep == 4 || rep == 8) {
         p.per_head = 0;
-        dim3 grid(p.S, p.Hkv, p.B);
         switch (rep) {
-            case 1: return launch_lpr<T, 1>(p, grid, s);
-            case 2: return launch_lpr<T, 2>(p, grid, s);
-            case 4: return launch_lpr<T, 4>(p, grid, s);
-            default: return launch_lpr<T, 8>(p, grid, s);
+            case 1: return launch_lpr<T, 1>(p, p.Hkv, s);
+            case 2: return launch_lpr<T, 2>(p, p.Hkv, s);
+            case 4: return launch_lpr<T, 4>(p, p.Hkv, s);
+            default: return launch_lpr<T, 8>(p, p.Hkv, s);
         }
     }
-    p.per_head = 1;                                        // other group sizes: one query head per workgroup
-    dim3 grid(p.S, p.H, p.B);
-    return launch_lpr<T, 1>(p, grid, s);
+    p.per_head = 1;                                        // other group sizes: one query head per wavefront group
+    return launch_lpr<T, 1>(p, p.H, s);
 }
 
 extern "C" int32_t cascade_decode_partial_attn(const cascade_attn_desc *d, int32_t batch, int32_t n_shards,
