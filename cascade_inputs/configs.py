@@ -23,6 +23,7 @@ class LayerConfig:
     assignment: str     # "perm" | "contiguous" | "roundrobin"
     sigma: float        # std of weight entries
     index: int          # position in the benchmark's config list
+    norm_placement: str = "pre"   # "pre": x + f(norm(x)) blocks; "post": norm(x + f(x)) blocks (BERT-shaped)
 
     @property
     def scale(self) -> float:

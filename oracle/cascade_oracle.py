@@ -169,8 +169,10 @@ def _split_heads(x, n_heads, d):
 
 # --------------------------------------------------------------------------- Algorithm 2
 def pre_pass(h_rows, pos_rows, w, cfg):
-    """Algorithm 2 on one hidden shard: norm, q/k/v projection, rotary embedding."""
-    x = norm(h_rows, cfg.norm, w["norm1_g"], w.get("norm1_b"), cfg.eps)
+    """Algorithm 2 on one hidden shard: norm ("if necessary": not in a post-norm block), q/k/v
+    projection, rotary embedding."""
+    post = getattr(cfg, "norm_placement", "pre") == "post"
+    x = h_rows if post else norm(h_rows, cfg.norm, w["norm1_g"], w.get("norm1_b"), cfg.eps)
     q = _split_heads(linear(x, w["wq"], w.get("bq")), cfg.n_heads, cfg.head_dim)
     k = _split_heads(linear(x, w["wk"], w.get("bk")), cfg.n_kv_heads, cfg.head_dim)
     v = _split_heads(linear(x, w["wv"], w.get("bv")), cfg.n_kv_heads, cfg.head_dim)
@@ -327,7 +329,8 @@ def layer_direct(h, w, cfg, positions=None, mask_kind="causal", scale=None, rows
     rows = np.arange(N) if rows is None else np.asarray(rows)
     H, Hkv, d = cfg.n_heads, cfg.n_kv_heads, cfg.head_dim
 
-    x = norm(h, cfg.norm, w["norm1_g"], w.get("norm1_b"), cfg.eps)
+    post = getattr(cfg, "norm_placement", "pre") == "post"
+    x = h if post else norm(h, cfg.norm, w["norm1_g"], w.get("norm1_b"), cfg.eps)
     k = _split_heads(linear(x, w["wk"], w.get("bk")), Hkv, d)
     v = _split_heads(linear(x, w["wv"], w.get("bv")), Hkv, d)
     q = _split_heads(linear(x[rows], w["wq"], w.get("bq")), H, d)
@@ -343,7 +346,17 @@ def layer_direct(h, w, cfg, positions=None, mask_kind="causal", scale=None, rows
         p = np.exp(a)
         p = p / p.sum(axis=-1, keepdims=True)
         o[:, hh * d:(hh + 1) * d] = p @ v[hh // rep]
-    h1 = h[rows] + linear(o, w["wo"], w.get("bo"))
+    return _block_tail(h[rows], o, w, cfg)
+
+
+def _block_tail(h_rows, o, w, cfg):
+    """What follows the attention values on a set of rows (Algorithm 4 line 9 and Algorithm 1 line 17):
+    output projection, residual and MLP, with the norms before the sub-blocks ("pre", the default
+    reading) or after the residual sums ("post", the BERT-shaped block of the paper's timing runs)."""
+    if getattr(cfg, "norm_placement", "pre") == "post":
+        h1 = norm(h_rows + linear(o, w["wo"], w.get("bo")), cfg.norm, w["norm1_g"], w.get("norm1_b"), cfg.eps)
+        return norm(h1 + ffn(h1, w, cfg.act), cfg.norm, w["norm2_g"], w.get("norm2_b"), cfg.eps)
+    h1 = h_rows + linear(o, w["wo"], w.get("bo"))
     x2 = norm(h1, cfg.norm, w["norm2_g"], w.get("norm2_b"), cfg.eps)
     return h1 + ffn(x2, w, cfg.act)
 
@@ -379,9 +392,7 @@ def layer_sharded(h, w, cfg, token_to_shard, n_shards, positions=None, mask_kind
         us = [partial[(i, kk)][2] for kk in range(n_shards)]
         o = post_pass_merge(ms, es, us)                               # Algorithm 4 lines 1-8
         o = o.transpose(1, 0, 2).reshape(len(R), -1)
-        h1 = h[R] + linear(o, w["wo"], w.get("bo"))                   # line 9 + residual
-        x2 = norm(h1, cfg.norm, w["norm2_g"], w.get("norm2_b"), cfg.eps)
-        out[R] = h1 + ffn(x2, w, cfg.act)
+        out[R] = _block_tail(h[R], o, w, cfg)                         # line 9, residual, MLP
     if return_partials:
         return out, partial
     return out
@@ -424,10 +435,22 @@ def layer_sharded_rs(h, w, cfg, token_to_row_shard, n_row_shards, token_to_kv_sh
         o = post_pass_merge([m[kk][:, R] for kk in range(n_kv_shards)], [e[kk][:, R] for kk in range(n_kv_shards)],
                             [u[kk][:, R] for kk in range(n_kv_shards)])
         o = o.transpose(1, 0, 2).reshape(len(R), -1)
-        h1 = h[R] + linear(o, w["wo"], w.get("bo"))
-        x2 = norm(h1, cfg.norm, w["norm2_g"], w.get("norm2_b"), cfg.eps)
-        out[R] = h1 + ffn(x2, w, cfg.act)
+        out[R] = _block_tail(h[R], o, w, cfg)
     return out
+
+
+def layer_stack_direct(h, layer_weights, cfg, **kw):
+    """Consecutive layers (Single Layer Pipeline subsection: the output of layer l is the input of
+    layer l+1 on the same CompNode); one weight dict per layer."""
+    for w in layer_weights:
+        h = layer_direct(h, w, cfg, **kw)
+    return h
+
+
+def layer_stack_sharded(h, layer_weights, cfg, token_to_shard, n_shards, **kw):
+    for w in layer_weights:
+        h = layer_sharded(h, w, cfg, token_to_shard, n_shards, **kw)
+    return h
 
 
 def layer_direct_batch(h, w, cfg, **kw):

@@ -639,11 +639,8 @@ static int32_t launch_attn_cfg(const cascade_plan *p, const AttnArgs &a, hipStre
 
     constexpr int lds = 4 * (KV_TILE * D * 2 + D * 128 + KV_TILE * 4);
     auto kern = attn_bf16_kernel<D>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        CASCADE_HIP_TRY(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds));
-        attr_set = true;
-    }
+    static std::atomic<uint64_t> lds_ready{0};
+    CASCADE_HIP_TRY(ensure_dynamic_lds((const void *)kern, lds, lds_ready));
     const int64_t gy = (int64_t)a.B * a.Hkv * (rep / hpb);
     if (gy > 65535 || S > 65535) return CASCADE_EUNSUPPORTED;
     dim3 grid(ql.count, (unsigned)gy, a.fused ? 1 : S);

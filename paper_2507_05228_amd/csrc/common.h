@@ -1,6 +1,7 @@
 // Internal declarations shared by the library's translation units (host side).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <atomic>
 #include <stdint.h>
 #include <stddef.h>
 #include "../../include/cascade.h"
@@ -62,6 +63,19 @@ void cascade_set_hip_error(hipError_t e);
     } while (0)
 
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Raises a kernel's dynamic LDS limit once per device (the attribute is per device; setting it again
+// is harmless, so concurrent first calls need no lock).  `done` is a bit mask of devices, one per kernel.
+static inline hipError_t ensure_dynamic_lds(const void *kernel, int bytes, std::atomic<uint64_t> &done) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const uint64_t bit = dev < 64 ? (1ull << dev) : 0;
+    if (bit && (done.load(std::memory_order_acquire) & bit)) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess && bit) done.fetch_or(bit, std::memory_order_release);
+    return e;
+}
 
 // ---------------------------------------------------------------------------- internal launchers
 // Row map convention: map == nullptr -> identity; else global row = b * seq_len + map[r % seq_len].

@@ -235,11 +235,8 @@ static int32_t launch_cfg(const GemmArgs &a, hipStream_t s) {
     p.x_bytes = (uint32_t)xb;
     constexpr size_t lds = (size_t)2 * (BM + BN) * LDS_LD * sizeof(bf16_t);
     auto kern = gemm_bf16_kernel<BM, BN, WM, WN, SWIGLU>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        CASCADE_HIP_TRY(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        attr_set = true;
-    }
+    static std::atomic<uint64_t> lds_ready{0};
+    CASCADE_HIP_TRY(ensure_dynamic_lds((const void *)kern, (int)lds, lds_ready));
     int64_t total = (int64_t)p.tiles_m * p.tiles_n;
     if (total > INT32_MAX) return CASCADE_EUNSUPPORTED;
     hipLaunchKernelGGL(kern, dim3((unsigned)total), dim3(WM * WN * 64), lds, s, p);

@@ -546,11 +546,8 @@ static int32_t launch_cfg2(const GemmArgs &a, hipStream_t s) {
     const void *kern;
     if constexpr (PINGPONG) kern = (const void *)gemm3_kernel<BM, BN, WM, WN, BK, NST, SWIGLU>;
     else kern = (const void *)gemm2_kernel<BM, BN, WM, WN, BK, NST, SWIGLU>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        CASCADE_HIP_TRY(hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        attr_set = true;
-    }
+    static std::atomic<uint64_t> lds_ready{0};                 // one per instantiation of this launcher
+    CASCADE_HIP_TRY(ensure_dynamic_lds(kern, (int)lds, lds_ready));
     int64_t total = (int64_t)p.tiles_m * p.tiles_n;
     if (total > INT32_MAX) return CASCADE_EUNSUPPORTED;
     void *args[] = {&p};
@@ -559,14 +556,10 @@ static int32_t launch_cfg2(const GemmArgs &a, hipStream_t s) {
     return CASCADE_OK;
 }
 
-static int cu_count() {
-    static int n = 0;
-    if (!n) {
-        int dev = 0;
-        hipDeviceProp_t prop;
-        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess) n = prop.multiProcessorCount;
-        if (n <= 0) n = 256;
-    }
+static int cu_count() {                                   // of the current device
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+        n = 256;
     return n;
 }
 

@@ -430,7 +430,8 @@ def brute_layer(h, w, cfg):
             y[i + half] = x[i + half] * math.cos(ang) + x[i] * math.sin(ang)
         return y
 
-    x = nrm(h, w["norm1_g"], w.get("norm1_b"))
+    post = getattr(cfg, "norm_placement", "pre") == "post"
+    x = h if post else nrm(h, w["norm1_g"], w.get("norm1_b"))
     q = lin(x, w["wq"], w.get("bq")).reshape(N, H, d).transpose(1, 0, 2).copy()
     k = lin(x, w["wk"], w.get("bk")).reshape(N, Hkv, d).transpose(1, 0, 2).copy()
     v = lin(x, w["wv"], w.get("bv")).reshape(N, Hkv, d).transpose(1, 0, 2).copy()
@@ -442,19 +443,27 @@ def brute_layer(h, w, cfg):
                 k[hh, t] = rot(k[hh, t], t)
     o = brute_attention(q, k, v, np.arange(N), cfg.scale).transpose(1, 0, 2).reshape(N, H * d)
     h1 = h + lin(o, w["wo"], w.get("bo"))
-    x2 = nrm(h1, w["norm2_g"], w.get("norm2_b"))
+    if post:
+        h1 = nrm(h1, w["norm1_g"], w.get("norm1_b"))
+    x2 = h1 if post else nrm(h1, w["norm2_g"], w.get("norm2_b"))
     if cfg.act == "swiglu":
         g = lin(x2, w["w_gate"], None)
         up = lin(x2, w["w_up"], None)
         act = np.array([[gg / (1 + math.exp(-gg)) * uu for gg, uu in zip(gr, ur)] for gr, ur in zip(g, up)])
-        return h1 + lin(act, w["w_down"], None)
-    up = lin(x2, w["w_up"], w.get("b_up"))
-    act = np.array([[0.5 * t * (1 + math.erf(t / math.sqrt(2))) for t in row] for row in up])
-    return h1 + lin(act, w["w_down"], w.get("b_down"))
+        out = h1 + lin(act, w["w_down"], None)
+    else:
+        up = lin(x2, w["w_up"], w.get("b_up"))
+        act = np.array([[0.5 * t * (1 + math.erf(t / math.sqrt(2))) for t in row] for row in up])
+        out = h1 + lin(act, w["w_down"], w.get("b_down"))
+    return nrm(out, w["norm2_g"], w.get("norm2_b")) if post else out
 
 
 @pytest.mark.parametrize("cfg", [TINY_LLAMA.with_(seq_len=7, d_model=12, n_heads=2, n_kv_heads=1, head_dim=4, d_ff=10),
-                                 TINY_GPT.with_(seq_len=6, d_model=10, n_heads=2, n_kv_heads=2, head_dim=4, d_ff=9)])
+                                 TINY_GPT.with_(seq_len=6, d_model=10, n_heads=2, n_kv_heads=2, head_dim=4, d_ff=9),
+                                 TINY_GPT.with_(seq_len=6, d_model=10, n_heads=2, n_kv_heads=2, head_dim=4, d_ff=9,
+                                                norm_placement="post"),
+                                 TINY_LLAMA.with_(seq_len=5, d_model=8, n_heads=2, n_kv_heads=2, head_dim=4, d_ff=6,
+                                                  norm_placement="post")])
 def test_layer_direct_equals_brute_force_layer(cfg):
     w = {k: v.astype(np.float64) * 10 for k, v in make_layer_weights(cfg).items()}   # x10: make every term matter
     for key in ("norm1_g", "norm2_g"):
@@ -634,3 +643,35 @@ def test_decode_single_key_shards():
         for h in range(H):
             assert abs(m[h, kk] - 0.5 * float(q[h, N - 1] @ k[0, kk])) < 1e-13
             np.testing.assert_allclose(u[kk, h], v[0, kk], rtol=1e-13)
+
+
+# ---------------------------------------------------------------- post-norm block, layer stack
+@pytest.mark.parametrize("cfg", [TINY_GPT.with_(norm_placement="post"), TINY_LLAMA.with_(norm_placement="post")])
+@pytest.mark.parametrize("mask_kind", ["causal", "none"])
+def test_post_norm_layer_sharded_equals_direct(cfg, mask_kind):
+    """The BERT-shaped block (norm after each residual sum), bidirectional or causal."""
+    w = make_layer_weights(cfg)
+    w = {k: v * (8.0 if v.ndim == 2 else 1.0) for k, v in w.items()}
+    h = make_hidden(cfg)[0]
+    a = make_assignment("perm", cfg.seq_len, cfg.n_shards, 4)
+    direct = orc.layer_direct(h, w, cfg, mask_kind=mask_kind)
+    assert rel_err(orc.layer_sharded(h, w, cfg, a, cfg.n_shards, mask_kind=mask_kind), direct) < 1e-12
+    assert rel_err(orc.layer_direct(h, w, cfg.with_(norm_placement="pre"), mask_kind=mask_kind), direct) > 1e-3
+    # every output row of a post-norm layer is normalised: zero mean / unit variance before gain and bias
+    if cfg.norm == "layernorm":
+        z = (direct - w["norm2_b"]) / w["norm2_g"]
+        assert np.abs(z.mean(axis=1)).max() < 1e-9 and np.abs(z.var(axis=1) - 1).max() < 1e-3
+
+
+def test_layer_stack_is_the_composition_of_layers_under_any_sharding():
+    cfg = TINY_LLAMA
+    ws = [make_layer_weights(cfg.with_(index=40 + l)) for l in range(3)]
+    ws = [{k: v * (6.0 if v.ndim == 2 else 1.0) for k, v in w.items()} for w in ws]
+    h = make_hidden(cfg)[0]
+    want = h.astype(np.float64)
+    for w in ws:
+        want = orc.layer_direct(want, w, cfg)
+    assert rel_err(orc.layer_stack_direct(h, ws, cfg), want) == 0
+    for seed, beta in [(1, 4), (2, 6)]:
+        a = make_assignment("perm", cfg.seq_len, beta, seed)
+        assert rel_err(orc.layer_stack_sharded(h, ws, cfg, a, beta), want) < 1e-11
