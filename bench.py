@@ -229,6 +229,44 @@ def run_decode(cas, cfg, steps, batch=32, cache_tokens=8192, shard_rows=128):
             "lse_merge_us": t_merge * 1e6, "partial_bytes": partial_bytes}
 
 
+def run_variants(cas, cfg, steps):
+    """Post-norm bidirectional block (the BERT-shaped layer of the paper's timing runs) on the C2 shape,
+    and a four-layer stack of the headline layer (packed order kept between layers)."""
+    import torch
+    from cascade_inputs import CONFIGS, config_seed, make_assignment
+    out = {}
+    c2 = CONFIGS["C2"].with_(norm_placement="post")
+    a = make_assignment(c2.assignment, c2.seq_len, c2.n_shards, config_seed(c2))
+    w, h = device_inputs(c2, config_seed(c2))
+    plan = cas.cascade_plan_create(c2.batch, c2.seq_len, c2.n_shards, a, mask_kind=cas.MASK_NONE)
+    desc = cas.make_layer_desc(c2, cas.ATTN_FUSED, cas.ROWS_ORIGINAL)
+    wts = cas.make_layer_weights(w)
+    h_out = torch.empty_like(h)
+    ws = cas.new_workspace(cas.cascade_layer_workspace_bytes(plan, desc))
+    step = lambda: cas.cascade_layer_forward(plan, desc, wts, h, h_out, ws)
+    for _ in range(3):
+        step()
+    sec = time_steps(step, steps)
+    out["post_norm_bidirectional_C2"] = {"ms_per_layer": sec * 1e3, "tokens_per_s": c2.batch * c2.seq_len / sec}
+    del ws, w, h, h_out
+
+    L = 4
+    a = make_assignment(cfg.assignment, cfg.seq_len, cfg.n_shards, config_seed(cfg))
+    plan = cas.cascade_plan_create(cfg.batch, cfg.seq_len, cfg.n_shards, a)
+    desc = cas.make_layer_desc(cfg, cas.ATTN_FUSED, cas.ROWS_ORIGINAL)
+    tensors = [device_inputs(cfg, config_seed(cfg) + l)[0] for l in range(L)]
+    wl = [cas.make_layer_weights(t) for t in tensors]
+    _, h = device_inputs(cfg, config_seed(cfg))
+    h_out = torch.empty_like(h)
+    ws = cas.new_workspace(cas.cascade_layer_stack_workspace_bytes(plan, desc, L))
+    step = lambda: cas.cascade_layer_stack_forward(plan, desc, wl, h, h_out, ws)
+    for _ in range(2):
+        step()
+    sec = time_steps(step, max(3, steps // 2))
+    out["stack_of_4_layers"] = {"workload": cfg.name, "ms_per_layer": sec * 1e3 / L, "tokens_per_s": cfg.batch * cfg.seq_len / sec}
+    return out
+
+
 def cpu_baseline(cfg, host):
     """The oracle as it stands, on the host cores: the whole unsharded float64 layer, one repetition."""
     import numpy as np
@@ -330,6 +368,8 @@ def main():
         out["m_split"] = run_m_split(cas, cfg, max(3, args.steps // 4))
         torch.cuda.empty_cache()
         out["kv_cache_decode"] = run_decode(cas, cfg, args.steps)
+        torch.cuda.empty_cache()
+        out["variants"] = run_variants(cas, cfg, max(5, args.steps // 2))
     if args.all:
         others = {}
         for key in ("C2", "C4", "C5"):

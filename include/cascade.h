@@ -227,6 +227,15 @@ CASCADE_API int32_t cascade_lse_merge(const cascade_plan *plan, const cascade_at
 /* ------------------------------------------------------------------ whole layer
  * Algorithm 1 on one GPU: h1 = h + o_proj(attention(norm1(h))),
  * h_out = h1 + FFN(norm2(h1)); pre-norm block.                                  */
+/* Where the two norms of the block sit (the paper leaves the block's internals to
+ * the model: "layer normalization if necessary", "Residual and MLP"):
+ *   PRE :  h1 = h + Attn(norm1(h));      out = h1 + MLP(norm2(h1))      (GPT / Llama)
+ *   POST:  h1 = norm1(h + Attn(h));      out = norm2(h1 + MLP(h1))      (BERT, the
+ *          model of the paper's timing runs; use a plan with CASCADE_MASK_NONE for
+ *          its bidirectional attention)                                           */
+#define CASCADE_NORM_PRE  0
+#define CASCADE_NORM_POST 1
+
 typedef struct cascade_layer_desc {
     int32_t dtype;
     int32_t d_model, n_heads, n_kv_heads, head_dim, d_ff;
@@ -238,6 +247,7 @@ typedef struct cascade_layer_desc {
     float   scale;
     int32_t attn_mode;    /* CASCADE_ATTN_*                                           */
     int32_t io_rows;      /* row order of h_in and h_out: CASCADE_ROWS_*              */
+    int32_t norm_placement;   /* CASCADE_NORM_PRE (0) | CASCADE_NORM_POST             */
 } cascade_layer_desc;
 
 /* Device pointers, borrowed.  Matrices [out, in].  NULL = absent (biases, norm
@@ -257,6 +267,20 @@ CASCADE_API int32_t cascade_layer_forward(const cascade_plan *plan, const cascad
                               const cascade_layer_weights *weights,
                               const void *h_in, void *h_out,
                               void *workspace, size_t workspace_bytes, void *stream);
+
+/* n_layers consecutive layers with the same descriptor and one weight set each
+ * (weights[0 .. n_layers-1]): the output of layer l is the input of layer l+1 on
+ * the same rows (Single Layer Pipeline subsection).  Only the first layer gathers
+ * h_in into packed order and only the last one scatters into h_out (both in
+ * desc->io_rows order); between layers the activations stay packed, in two
+ * buffers taken from the workspace (cascade_layer_stack_workspace_bytes).
+ * h_in, h_out [B, N, D]; must not alias.  Errors as cascade_layer_forward.       */
+CASCADE_API size_t cascade_layer_stack_workspace_bytes(const cascade_plan *plan, const cascade_layer_desc *desc,
+                                           int32_t n_layers);
+CASCADE_API int32_t cascade_layer_stack_forward(const cascade_plan *plan, const cascade_layer_desc *desc,
+                                    const cascade_layer_weights *weights, int32_t n_layers,
+                                    const void *h_in, void *h_out,
+                                    void *workspace, size_t workspace_bytes, void *stream);
 
 /* The same computation with stage boundaries marked for measurement: HIP event
  * stage_events[i] (hipEvent_t, created by the caller, NULL entries skipped) is

@@ -22,6 +22,7 @@ U_UNNORMALISED, U_NORMALISED = 0, 1
 NORM_NONE, NORM_LAYERNORM, NORM_RMSNORM = 0, 1, 2
 ACT_GELU_ERF, ACT_GELU_TANH, ACT_SWIGLU = 0, 1, 2
 ATTN_FUSED, ATTN_MATERIALISED = 0, 1
+NORM_PRE, NORM_POST = 0, 1
 EPI_BIAS, EPI_GELU_ERF, EPI_GELU_TANH, EPI_SWIGLU, EPI_ROPE, EPI_RESIDUAL = 1, 2, 4, 8, 16, 32
 
 EXPORTS = ["cascade_plan_create", "cascade_plan_create_rs", "cascade_plan_maps", "cascade_plan_maps_host",
@@ -29,6 +30,7 @@ EXPORTS = ["cascade_plan_create", "cascade_plan_create_rs", "cascade_plan_maps",
            "cascade_last_hip_error", "cascade_shard_gemm", "cascade_partial_attn_workspace_bytes",
            "cascade_partial_attn", "cascade_lse_merge", "cascade_layer_workspace_bytes",
            "cascade_layer_forward", "cascade_layer_forward_staged", "cascade_layer_partials",
+           "cascade_layer_stack_workspace_bytes", "cascade_layer_stack_forward",
            "cascade_decode_partial_attn", "cascade_mfma_ceiling"]
 N_STAGE_EVENTS = 10
 STAGE_NAMES = ["gather_norm1", "qkv_gemm", "rope", "attention", "lse_merge", "o_proj", "norm2", "ffn_up", "ffn_down"]
@@ -58,7 +60,7 @@ class LayerDesc(C.Structure):
     _fields_ = [("dtype", C.c_int32), ("d_model", C.c_int32), ("n_heads", C.c_int32), ("n_kv_heads", C.c_int32),
                 ("head_dim", C.c_int32), ("d_ff", C.c_int32), ("norm_kind", C.c_int32), ("norm_eps", C.c_float),
                 ("act", C.c_int32), ("rope", C.c_int32), ("rope_theta", C.c_float), ("scale", C.c_float),
-                ("attn_mode", C.c_int32), ("io_rows", C.c_int32)]
+                ("attn_mode", C.c_int32), ("io_rows", C.c_int32), ("norm_placement", C.c_int32)]
 
 
 _WEIGHT_FIELDS = ["wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down", "bq", "bk", "bv", "bo", "b_up", "b_down",
@@ -121,6 +123,10 @@ def load_library():
     lib.cascade_layer_forward_staged.restype = I32
     lib.cascade_layer_partials.argtypes = [VP, P(LayerDesc), VP, P(VP), P(VP), P(VP)]
     lib.cascade_layer_partials.restype = I32
+    lib.cascade_layer_stack_workspace_bytes.argtypes = [VP, P(LayerDesc), I32]
+    lib.cascade_layer_stack_workspace_bytes.restype = C.c_size_t
+    lib.cascade_layer_stack_forward.argtypes = [VP, P(LayerDesc), P(LayerWeights), I32, VP, VP, VP, C.c_size_t, VP]
+    lib.cascade_layer_stack_forward.restype = I32
     lib.cascade_decode_partial_attn.argtypes = [P(AttnDesc), I32, I32, I32, VP, VP, VP, VP, VP, VP, VP, VP]
     lib.cascade_decode_partial_attn.restype = I32
     lib.cascade_mfma_ceiling.argtypes = [I32, I32, P(C.c_float), VP]
@@ -314,7 +320,8 @@ def make_layer_desc(cfg, attn_mode=ATTN_FUSED, io_rows=ROWS_ORIGINAL, scale=None
     nk = {"layernorm": NORM_LAYERNORM, "rmsnorm": NORM_RMSNORM}[cfg.norm]
     return LayerDesc(BF16 if cfg.dtype == "bf16" else F32, cfg.d_model, cfg.n_heads, cfg.n_kv_heads, cfg.head_dim,
                      cfg.d_ff, nk, cfg.eps, act, 1 if cfg.rope else 0, cfg.rope_theta,
-                     cfg.scale if scale is None else scale, attn_mode, io_rows)
+                     cfg.scale if scale is None else scale, attn_mode, io_rows,
+                     NORM_POST if getattr(cfg, "norm_placement", "pre") == "post" else NORM_PRE)
 
 
 def make_layer_weights(tensors):
@@ -347,6 +354,19 @@ def cascade_layer_forward_staged(plan, desc, weights, h_in, h_out, workspace, ev
     st = lib.cascade_layer_forward_staged(plan.handle, C.byref(desc), C.byref(weights), _ptr(h_in), _ptr(h_out),
                                           _ptr(workspace), ws_bytes, _stream(stream), arr, len(events))
     _check(st, "cascade_layer_forward_staged")
+
+
+def cascade_layer_stack_workspace_bytes(plan, desc, n_layers):
+    return load_library().cascade_layer_stack_workspace_bytes(plan.handle, C.byref(desc), n_layers)
+
+
+def cascade_layer_stack_forward(plan, desc, weights_list, h_in, h_out, workspace, stream=None):
+    """weights_list: one LayerWeights per layer (the tensors behind them must stay alive)."""
+    lib = load_library()
+    arr = (LayerWeights * len(weights_list))(*weights_list)
+    st = lib.cascade_layer_stack_forward(plan.handle, C.byref(desc), arr, len(weights_list), _ptr(h_in), _ptr(h_out),
+                                         _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream))
+    _check(st, "cascade_layer_stack_forward")
 
 
 def cascade_layer_partials(plan, desc, workspace, batch, n_heads, head_dim):

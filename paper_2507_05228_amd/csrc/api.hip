@@ -171,6 +171,7 @@ static int32_t check_layer_desc(const cascade_plan *plan, const cascade_layer_de
         return CASCADE_EINVAL;
     if (d->attn_mode != CASCADE_ATTN_FUSED && d->attn_mode != CASCADE_ATTN_MATERIALISED) return CASCADE_EINVAL;
     if (!rows_ok(d->io_rows)) return CASCADE_EINVAL;
+    if (d->norm_placement != CASCADE_NORM_PRE && d->norm_placement != CASCADE_NORM_POST) return CASCADE_EINVAL;
     if (d->rope != 0 && d->rope != 1) return CASCADE_EUNSUPPORTED;
     if (d->rope && (d->head_dim % 2 || d->rope_theta <= 0.f)) return CASCADE_EUNSUPPORTED;
     if (d->dtype == CASCADE_BF16) {
@@ -198,10 +199,11 @@ extern "C" int32_t cascade_layer_partials(const cascade_plan *plan, const cascad
     return CASCADE_OK;
 }
 
+// in_rows / out_rows: row order of h_in / h_out (a layer stack keeps packed order between layers)
 static int32_t layer_forward_impl(const cascade_plan *plan, const cascade_layer_desc *d,
                                   const cascade_layer_weights *w, const void *h_in, void *h_out,
                                   void *workspace, size_t workspace_bytes, void *stream,
-                                  void *const *events, int32_t n_events) {
+                                  void *const *events, int32_t n_events, int32_t in_rows, int32_t out_rows) {
     int32_t st = check_layer_desc(plan, d);
     if (st != CASCADE_OK) return st;
     if (!w || !h_in || !h_out || h_in == h_out) return CASCADE_EINVAL;
@@ -228,15 +230,20 @@ static int32_t layer_forward_impl(const cascade_plan *plan, const cascade_layer_
     const int QW = (H + 2 * Hkv) * hd;
     const int es = esize(d->dtype);
     void *x = base + ws.x, *qkv = base + ws.qkv, *ao = base + ws.ao, *h1 = base + ws.h1, *act = base + ws.act;
-    const RowMap io_map = rowmap_for(plan, d->io_rows), packed = rowmap_for(plan, CASCADE_ROWS_PACKED);
+    const RowMap in_map = rowmap_for(plan, in_rows), out_map = rowmap_for(plan, out_rows);
+    const RowMap packed = rowmap_for(plan, CASCADE_ROWS_PACKED);
+    const bool post = d->norm_placement == CASCADE_NORM_POST;
 
-    // 1. pre-pass: norm (with the gather into packed order), q/k/v projection, rotary embedding (Algorithm 2)
+    // 1. pre-pass: norm (with the gather into packed order), q/k/v projection, rotary embedding (Algorithm 2).
+    //    A post-norm block has no norm here: the projection gathers h_in itself.
     if ((st = mark()) != CASCADE_OK) return st;                                   // event 0: start
-    NormArgs n1 = {d->dtype, T, D, d->norm_kind, d->norm_eps, h_in, w->norm1_g, w->norm1_b, x, io_map};
-    if ((st = launch_norm(n1, s)) != CASCADE_OK) return st;
+    if (!post) {
+        NormArgs n1 = {d->dtype, T, D, d->norm_kind, d->norm_eps, h_in, w->norm1_g, w->norm1_b, x, in_map, packed};
+        if ((st = launch_norm(n1, s)) != CASCADE_OK) return st;
+    }
     if ((st = mark()) != CASCADE_OK) return st;                                   // 1: gather + norm1
     GemmArgs g = {};
-    g.dtype = d->dtype; g.M = T; g.N = QW; g.K = D; g.X = x;
+    g.dtype = d->dtype; g.M = T; g.N = QW; g.K = D; g.X = post ? h_in : x;
     g.W[0] = w->wq; g.W[1] = w->wk; g.W[2] = w->wv;
     g.seg_end[0] = H * hd; g.seg_end[1] = (H + Hkv) * hd; g.seg_end[2] = QW;
     g.bias[0] = w->bq; g.bias[1] = w->bk; g.bias[2] = w->bv;
@@ -250,7 +257,7 @@ static int32_t layer_forward_impl(const cascade_plan *plan, const cascade_layer_
         if (w_contig && b_contig) g.seg_end[0] = g.seg_end[1] = QW;
     }
     g.epilogue = (w->bq || w->bk || w->bv) ? CASCADE_EPI_BIAS : 0;
-    g.Y = qkv; g.ldx = D; g.ldy = QW; g.xmap = g.ymap = g.rmap = packed;
+    g.Y = qkv; g.ldx = D; g.ldy = QW; g.xmap = post ? in_map : packed; g.ymap = g.rmap = packed;
     if ((st = run_gemm(g, s)) != CASCADE_OK) return st;
     if ((st = mark()) != CASCADE_OK) return st;                                   // 2: qkv GEMM
     if (d->rope) {
@@ -291,20 +298,23 @@ static int32_t layer_forward_impl(const cascade_plan *plan, const cascade_layer_
     g = {};
     g.dtype = d->dtype; g.M = T; g.N = D; g.K = H * hd; g.X = ao; g.W[0] = w->wo;
     g.seg_end[0] = g.seg_end[1] = g.seg_end[2] = D;
-    g.bias[0] = w->bo; g.residual = h_in; g.Y = h1;
+    // pre-norm: h1 = h + o Wo^T, then x = norm2(h1) feeds the MLP.
+    // post-norm: x = h + o Wo^T, then h1 = norm1(x) is both the MLP input and its residual.
+    g.bias[0] = w->bo; g.residual = h_in; g.Y = post ? x : h1;
     g.ldx = H * hd; g.ldy = D; g.ldres = D;
-    g.xmap = g.ymap = packed; g.rmap = io_map;
+    g.xmap = g.ymap = packed; g.rmap = in_map;
     g.epilogue = CASCADE_EPI_RESIDUAL | (w->bo ? CASCADE_EPI_BIAS : 0);
     if ((st = run_gemm(g, s)) != CASCADE_OK) return st;
     if ((st = mark()) != CASCADE_OK) return st;                                   // 6: o projection + residual
 
-    // 4. MLP: norm2, up (+ gate) projection with the activation, down projection + residual,
+    // 4. MLP: norm, up (+ gate) projection with the activation, down projection + residual,
     //    scattered back to the caller's row order
-    NormArgs n2 = {d->dtype, T, D, d->norm_kind, d->norm_eps, h1, w->norm2_g, w->norm2_b, x, packed};
+    NormArgs n2 = {d->dtype, T, D, d->norm_kind, d->norm_eps, post ? x : h1, post ? w->norm1_g : w->norm2_g,
+                   post ? w->norm1_b : w->norm2_b, post ? h1 : x, packed, packed};
     if ((st = launch_norm(n2, s)) != CASCADE_OK) return st;
-    if ((st = mark()) != CASCADE_OK) return st;                                   // 7: norm2
+    if ((st = mark()) != CASCADE_OK) return st;                                   // 7: norm before the MLP
     g = {};
-    g.dtype = d->dtype; g.M = T; g.N = f; g.K = D; g.X = x;
+    g.dtype = d->dtype; g.M = T; g.N = f; g.K = D; g.X = post ? h1 : x;
     g.seg_end[0] = g.seg_end[1] = g.seg_end[2] = f;
     g.Y = act; g.ldx = D; g.ldy = f; g.xmap = g.ymap = g.rmap = packed;
     if (d->act == CASCADE_ACT_SWIGLU) {
@@ -319,25 +329,68 @@ static int32_t layer_forward_impl(const cascade_plan *plan, const cascade_layer_
     g = {};
     g.dtype = d->dtype; g.M = T; g.N = D; g.K = f; g.X = act; g.W[0] = w->w_down;
     g.seg_end[0] = g.seg_end[1] = g.seg_end[2] = D;
-    g.bias[0] = w->b_down; g.residual = h1; g.Y = h_out;
+    g.bias[0] = w->b_down; g.residual = h1; g.Y = post ? x : h_out;
     g.ldx = f; g.ldy = D; g.ldres = D;
-    g.xmap = g.rmap = packed; g.ymap = io_map;
+    g.xmap = g.rmap = packed; g.ymap = post ? packed : out_map;
     g.epilogue = CASCADE_EPI_RESIDUAL | (w->b_down ? CASCADE_EPI_BIAS : 0);
     if ((st = run_gemm(g, s)) != CASCADE_OK) return st;
-    return mark();                                                                // 9: FFN down + residual + scatter
+    if (post) {                                                                   // closing norm, with the scatter
+        NormArgs n3 = {d->dtype, T, D, d->norm_kind, d->norm_eps, x, w->norm2_g, w->norm2_b, h_out, packed, out_map};
+        if ((st = launch_norm(n3, s)) != CASCADE_OK) return st;
+    }
+    return mark();                                                                // 9: FFN down + residual (+ norm) + scatter
+}
+
+// ---------------------------------------------------------------------------- layer stack
+// Single Layer Pipeline subsection: the output of layer l on a CompNode is its input of layer l+1, so
+// the packed row order persists: only the first layer gathers and only the last one scatters.
+static size_t stack_hidden_bytes(const cascade_plan *plan, const cascade_layer_desc *d) {
+    return align_up((size_t)plan->batch * plan->seq_len * d->d_model * esize(d->dtype), 256);
+}
+
+extern "C" size_t cascade_layer_stack_workspace_bytes(const cascade_plan *plan, const cascade_layer_desc *d,
+                                                      int32_t n_layers) {
+    if (check_layer_desc(plan, d) != CASCADE_OK || n_layers <= 0) return 0;
+    return layer_ws(plan, d).total + (n_layers > 1 ? 2 * stack_hidden_bytes(plan, d) : 0);
+}
+
+extern "C" int32_t cascade_layer_stack_forward(const cascade_plan *plan, const cascade_layer_desc *d,
+                                               const cascade_layer_weights *weights, int32_t n_layers,
+                                               const void *h_in, void *h_out, void *workspace,
+                                               size_t workspace_bytes, void *stream) {
+    int32_t st = check_layer_desc(plan, d);
+    if (st != CASCADE_OK) return st;
+    if (!weights || n_layers <= 0 || !h_in || !h_out || h_in == h_out) return CASCADE_EINVAL;
+    const size_t need = cascade_layer_stack_workspace_bytes(plan, d, n_layers);
+    if (!workspace || workspace_bytes < need || (uintptr_t)workspace % 256) return CASCADE_EWORKSPACE;
+    const size_t lw = layer_ws(plan, d).total, hb = stack_hidden_bytes(plan, d);
+    char *base = (char *)workspace;
+    void *pp[2] = {base + lw, base + lw + hb};                                    // packed activations between layers
+    const void *src = h_in;
+    for (int l = 0; l < n_layers; ++l) {
+        const bool first = l == 0, last = l == n_layers - 1;
+        void *dst = last ? h_out : pp[l & 1];
+        st = layer_forward_impl(plan, d, weights + l, src, dst, workspace, lw, stream, nullptr, 0,
+                                first ? d->io_rows : CASCADE_ROWS_PACKED, last ? d->io_rows : CASCADE_ROWS_PACKED);
+        if (st != CASCADE_OK) return st;
+        src = dst;
+    }
+    return CASCADE_OK;
 }
 
 extern "C" int32_t cascade_layer_forward(const cascade_plan *plan, const cascade_layer_desc *d,
                                          const cascade_layer_weights *w, const void *h_in, void *h_out,
                                          void *workspace, size_t workspace_bytes, void *stream) {
-    return layer_forward_impl(plan, d, w, h_in, h_out, workspace, workspace_bytes, stream, nullptr, 0);
+    if (!d) return CASCADE_EINVAL;
+    return layer_forward_impl(plan, d, w, h_in, h_out, workspace, workspace_bytes, stream, nullptr, 0, d->io_rows,
+                              d->io_rows);
 }
 
 extern "C" int32_t cascade_layer_forward_staged(const cascade_plan *plan, const cascade_layer_desc *d,
                                                 const cascade_layer_weights *w, const void *h_in, void *h_out,
                                                 void *workspace, size_t workspace_bytes, void *stream,
                                                 void *const *stage_events, int32_t n_stage_events) {
-    if (n_stage_events < 0 || (n_stage_events > 0 && !stage_events)) return CASCADE_EINVAL;
+    if (!d || n_stage_events < 0 || (n_stage_events > 0 && !stage_events)) return CASCADE_EINVAL;
     return layer_forward_impl(plan, d, w, h_in, h_out, workspace, workspace_bytes, stream, stage_events,
-                              n_stage_events);
+                              n_stage_events, d->io_rows, d->io_rows);
 }

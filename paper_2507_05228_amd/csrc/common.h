@@ -107,6 +107,7 @@ struct NormArgs {
     float eps;
     const void *x; const void *gain; const void *bias; void *y;
     RowMap xmap;                     // gather on the read
+    RowMap ymap;                     // scatter on the write
 };
 int32_t launch_norm(const NormArgs &a, hipStream_t s);
 

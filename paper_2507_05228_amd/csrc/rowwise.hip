@@ -11,7 +11,7 @@
 template <typename T>
 __global__ __launch_bounds__(256) void norm_kernel(const T *__restrict__ x, const T *__restrict__ gain,
                                                    const T *__restrict__ bias, T *__restrict__ y, int D, int kind,
-                                                   float eps, const int32_t *xmap, int seq_len) {
+                                                   float eps, const int32_t *xmap, const int32_t *ymap, int seq_len) {
     extern __shared__ float row[];
     __shared__ float red[4];
     const int r = blockIdx.x;
@@ -31,7 +31,7 @@ __global__ __launch_bounds__(256) void norm_kernel(const T *__restrict__ x, cons
     }
     float var = block_sum_256(q, red) / D;
     float rstd = 1.0f / sqrtf(var + eps);
-    T *yr = y + (int64_t)r * D;
+    T *yr = y + map_row(ymap, seq_len, r) * (int64_t)D;
     for (int i = threadIdx.x; i < D; i += 256) {
         float v = (row[i] - mu) * rstd * Elem<T>::load(gain + i);
         if (bias) v += Elem<T>::load(bias + i);
@@ -44,7 +44,7 @@ __global__ __launch_bounds__(256) void norm_kernel(const T *__restrict__ x, cons
 template <typename T, int CH>
 __global__ __launch_bounds__(256) void norm_vec_kernel(const T *__restrict__ x, const T *__restrict__ gain,
                                                        const T *__restrict__ bias, T *__restrict__ y, int D, int kind,
-                                                       float eps, const int32_t *xmap, int seq_len) {
+                                                       float eps, const int32_t *xmap, const int32_t *ymap, int seq_len) {
     constexpr int VEC = 16 / sizeof(T);
     typedef T vecT __attribute__((ext_vector_type(VEC)));
     __shared__ float red[4];
@@ -74,7 +74,7 @@ __global__ __launch_bounds__(256) void norm_vec_kernel(const T *__restrict__ x, 
 #pragma unroll
             for (int j = 0; j < VEC; ++j) { const float d0 = v[c][j] - mu; q += d0 * d0; }
     const float rstd = 1.0f / sqrtf(block_sum_256(q, red) / D + eps);
-    T *yr = y + (int64_t)r * D;
+    T *yr = y + map_row(ymap, seq_len, r) * (int64_t)D;
 #pragma unroll
     for (int c = 0; c < CH; ++c) {
         const int i = threadIdx.x + 256 * c;
@@ -101,7 +101,8 @@ static int32_t launch_norm_t(const NormArgs &a, hipStream_t s) {
     const int nvec = a.D / VEC;
 #define NORM_VEC(CH)                                                                                             \
     hipLaunchKernelGGL((norm_vec_kernel<T, CH>), dim3(a.rows), dim3(256), 0, s, (const T *)a.x, (const T *)a.gain, \
-                       (const T *)a.bias, (T *)a.y, a.D, a.kind, a.eps, a.xmap.map, a.xmap.seq_len)
+                       (const T *)a.bias, (T *)a.y, a.D, a.kind, a.eps, a.xmap.map, a.ymap.map,                 \
+                       a.xmap.map ? a.xmap.seq_len : a.ymap.seq_len)
     if (aligned && nvec <= 256) NORM_VEC(1);
     else if (aligned && nvec <= 512) NORM_VEC(2);
     else if (aligned && nvec <= 1024) NORM_VEC(4);
@@ -109,7 +110,8 @@ static int32_t launch_norm_t(const NormArgs &a, hipStream_t s) {
         size_t lds = (size_t)a.D * sizeof(float);
         if (lds > 64 * 1024) return CASCADE_EUNSUPPORTED;
         hipLaunchKernelGGL(norm_kernel<T>, dim3(a.rows), dim3(256), lds, s, (const T *)a.x, (const T *)a.gain,
-                           (const T *)a.bias, (T *)a.y, a.D, a.kind, a.eps, a.xmap.map, a.xmap.seq_len);
+                           (const T *)a.bias, (T *)a.y, a.D, a.kind, a.eps, a.xmap.map, a.ymap.map,                 \
+                       a.xmap.map ? a.xmap.seq_len : a.ymap.seq_len);
     }
 #undef NORM_VEC
     CASCADE_HIP_TRY(hipGetLastError());

@@ -539,3 +539,58 @@ def test_layer_error_paths(cas):
     with pytest.raises(cas.CascadeError) as ei:
         cas.cascade_layer_forward(plan, desc, cas.make_layer_weights(tensors2), h, out, cas.new_workspace(need))
     assert ei.value.status == cas.EINVAL
+
+
+# ---------------------------------------------------------------------------- post-norm block, layer stack
+@pytest.mark.parametrize("cfg_name", ["small-gpt", "small-llama", "f32-llama", "C1"])
+@pytest.mark.parametrize("mode", ["fused", "materialised"])
+@pytest.mark.parametrize("mask_kind", ["none", "causal"])
+def test_post_norm_layer_matches_oracle(cas, cfg_name, mode, mask_kind):
+    """The BERT-shaped block: norms after the residual sums, bidirectional (mask none) or causal."""
+    base = {"small-gpt": SMALL_GPT, "small-llama": SMALL_LLAMA, "f32-llama": F32_LLAMA, "C1": CONFIGS["C1"]}[cfg_name]
+    cfg = base.with_(norm_placement="post")
+    attn_mode = cas.ATTN_FUSED if mode == "fused" else cas.ATTN_MATERIALISED
+    a = make_assignment(cfg.assignment, cfg.seq_len, cfg.n_shards, 21)
+    w, h = make_layer_weights(cfg), make_hidden(cfg)
+    mk = cas.MASK_NONE if mask_kind == "none" else cas.MASK_CAUSAL
+    out = cas.layer_forward_numpy(cfg, w, h, a, attn_mode=attn_mode, mask_kind=mk)
+    ref = orc.layer_direct_batch(h, w, cfg, mask_kind=mask_kind)
+    assert rel_err(out, ref) < TOL[cfg.dtype]
+    pre = orc.layer_direct_batch(h, w, base, mask_kind=mask_kind)
+    assert rel_err(pre, ref) > 2 * TOL[cfg.dtype]             # the placement matters at this tolerance
+
+
+@pytest.mark.parametrize("cfg_name,n_layers,io", [("small-llama", 3, "original"), ("small-gpt", 2, "original"),
+                                                  ("f32-llama", 4, "packed"), ("small-llama", 1, "original")])
+def test_layer_stack_matches_oracle_and_single_layer_calls(cas, cfg_name, n_layers, io):
+    import torch
+    cfg = {"small-gpt": SMALL_GPT.with_(norm_placement="post"), "small-llama": SMALL_LLAMA, "f32-llama": F32_LLAMA}[cfg_name]
+    a = make_assignment(cfg.assignment, cfg.seq_len, cfg.n_shards, 23)
+    ws_np = [make_layer_weights(cfg.with_(index=50 + l)) for l in range(n_layers)]
+    h = make_hidden(cfg)
+    io_rows = cas.ROWS_ORIGINAL if io == "original" else cas.ROWS_PACKED
+    plan = cas.cascade_plan_create(cfg.batch, cfg.seq_len, cfg.n_shards, a)
+    desc = cas.make_layer_desc(cfg, cas.ATTN_FUSED, io_rows)
+    tensors = [{k: cas.to_device(v, cfg.dtype) for k, v in w.items()} for w in ws_np]
+    wts = [cas.make_layer_weights(t) for t in tensors]
+    _, perm, _ = orc.shard_plan(a, cfg.n_shards)
+    h_host = h if io == "original" else h[:, perm]
+    h_in = cas.to_device(h_host, cfg.dtype)
+    h_out = torch.empty_like(h_in)
+    ws = cas.new_workspace(cas.cascade_layer_stack_workspace_bytes(plan, desc, n_layers))
+    cas.cascade_layer_stack_forward(plan, desc, wts, h_in, h_out, ws)
+    torch.cuda.synchronize()
+    got = h_out.float().cpu().numpy().astype(np.float64)
+    # the same layers one call at a time (every intermediate in the caller's row order): bit-identical
+    ws1 = cas.new_workspace(cas.cascade_layer_workspace_bytes(plan, desc))
+    cur = h_in
+    for wl in wts:
+        nxt = torch.empty_like(cur)
+        cas.cascade_layer_forward(plan, desc, wl, cur, nxt, ws1)
+        cur = nxt
+    torch.cuda.synchronize()
+    assert torch.equal(cur, h_out)
+    ref = np.stack([orc.layer_stack_direct(h[b], ws_np, cfg) for b in range(cfg.batch)])
+    ref = ref if io == "original" else ref[:, perm]
+    tol = TOL[cfg.dtype] * (1 if cfg.dtype == "f32" else n_layers)      # bf16 roundings accumulate over the layers
+    assert rel_err(got, ref) < tol
