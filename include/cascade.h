@@ -145,6 +145,19 @@ CASCADE_API int32_t cascade_cdelta_assignment(int32_t seq_len, int32_t c, int32_
 CASCADE_API int32_t cascade_m_split(int32_t seq_len, int32_t n_row_shards, const int32_t *token_to_row_shard_host,
                         int32_t m, int32_t *token_to_kv_shard_host);
 
+/* Cost model of the multi-party setting the method was designed for (Equation 1
+ * and the rounds count of the Communication Analysis appendix); on one GPU these
+ * are the bytes MATERIALISED mode moves through HBM.  Per layer:
+ *   stage_a_bytes = beta F d (H + 2 H_KV) N     q, k, v rows to the AttnNodes
+ *   stage_b_bytes = beta F (d + 2) H N          m, e, u rows back
+ *   rounds        = 2 alpha beta^2, or 2 beta^2 when m_split_scheme != 0
+ *                   ((c, delta)-sharding with an m-split: beta = m alpha)
+ * with alpha = n_row_shards, beta = n_kv_shards, F = bytes_per_value.  Any out
+ * pointer may be NULL.  Host only.  Errors: EINVAL.                              */
+CASCADE_API int32_t cascade_comm_cost(int32_t n_row_shards, int32_t n_kv_shards, int32_t m_split_scheme,
+                          int32_t bytes_per_value, int32_t head_dim, int32_t n_heads, int32_t n_kv_heads,
+                          int64_t seq_len, int64_t *stage_a_bytes, int64_t *stage_b_bytes, int64_t *rounds);
+
 CASCADE_API void cascade_plan_destroy(cascade_plan *plan);
 
 /* HIP error code of the last CASCADE_EHIP on this thread (0 if none).          */

@@ -26,7 +26,7 @@ NORM_PRE, NORM_POST = 0, 1
 EPI_BIAS, EPI_GELU_ERF, EPI_GELU_TANH, EPI_SWIGLU, EPI_ROPE, EPI_RESIDUAL = 1, 2, 4, 8, 16, 32
 
 EXPORTS = ["cascade_plan_create", "cascade_plan_create_rs", "cascade_plan_maps", "cascade_plan_maps_host",
-           "cascade_plan_kv_maps_host", "cascade_cdelta_assignment", "cascade_m_split", "cascade_plan_destroy",
+           "cascade_plan_kv_maps_host", "cascade_cdelta_assignment", "cascade_m_split", "cascade_comm_cost", "cascade_plan_destroy",
            "cascade_last_hip_error", "cascade_shard_gemm", "cascade_partial_attn_workspace_bytes",
            "cascade_partial_attn", "cascade_lse_merge", "cascade_layer_workspace_bytes",
            "cascade_layer_forward", "cascade_layer_forward_staged", "cascade_layer_partials",
@@ -98,6 +98,8 @@ def load_library():
     lib.cascade_cdelta_assignment.restype = I32
     lib.cascade_m_split.argtypes = [I32, I32, P(I32), I32, P(I32)]
     lib.cascade_m_split.restype = I32
+    lib.cascade_comm_cost.argtypes = [I32, I32, I32, I32, I32, I32, I32, C.c_int64, P(C.c_int64), P(C.c_int64), P(C.c_int64)]
+    lib.cascade_comm_cost.restype = I32
     lib.cascade_plan_maps.argtypes = [VP, P(VP), P(VP), P(VP)]
     lib.cascade_plan_maps.restype = I32
     lib.cascade_plan_maps_host.argtypes = [VP, P(P(I32)), P(P(I32)), P(P(I32))]
@@ -238,6 +240,16 @@ def cascade_m_split(token_to_row_shard, n_row_shards, m):
     _check(lib.cascade_m_split(a.shape[0], n_row_shards, a.ctypes.data_as(I32P), m, out.ctypes.data_as(I32P)),
            "cascade_m_split")
     return out
+
+
+def cascade_comm_cost(n_row_shards, n_kv_shards, bytes_per_value, head_dim, n_heads, n_kv_heads, seq_len,
+                      m_split_scheme=False):
+    """(stage_a_bytes, stage_b_bytes, rounds) per layer (Equation 1 and the rounds bound)."""
+    lib = load_library()
+    a, b, r = C.c_int64(), C.c_int64(), C.c_int64()
+    _check(lib.cascade_comm_cost(n_row_shards, n_kv_shards, int(bool(m_split_scheme)), bytes_per_value, head_dim, n_heads,
+                                 n_kv_heads, seq_len, C.byref(a), C.byref(b), C.byref(r)), "cascade_comm_cost")
+    return a.value, b.value, r.value
 
 
 def cascade_plan_maps(plan):

@@ -208,6 +208,25 @@ extern "C" int32_t cascade_m_split(int32_t seq_len, int32_t n_row_shards, const 
     return CASCADE_OK;
 }
 
+// ---------------------------------------------------------------------------- cost model
+// Equation 1 (Communication Analysis appendix): bytes per layer moved between CompNodes and
+// AttnNodes.  Stage A ships every q row to beta AttnNodes and every k, v row to beta AttnNodes;
+// stage B ships m, e (1 + 1 values) and u (d values) per head and row back from beta AttnNodes.
+// Rounds per layer: at most 2 alpha beta^2 in general, 2 beta^2 for (c, delta)-sharding with an m-split.
+extern "C" int32_t cascade_comm_cost(int32_t n_row_shards, int32_t n_kv_shards, int32_t m_split_scheme,
+                                     int32_t bytes_per_value, int32_t head_dim, int32_t n_heads, int32_t n_kv_heads,
+                                     int64_t seq_len, int64_t *stage_a_bytes, int64_t *stage_b_bytes,
+                                     int64_t *rounds) {
+    if (n_row_shards <= 0 || n_kv_shards <= 0 || bytes_per_value <= 0 || head_dim <= 0 || n_heads <= 0 ||
+        n_kv_heads <= 0 || seq_len <= 0)
+        return CASCADE_EINVAL;
+    const int64_t beta = n_kv_shards, F = bytes_per_value, d = head_dim;
+    if (stage_a_bytes) *stage_a_bytes = beta * F * d * (n_heads + 2 * (int64_t)n_kv_heads) * seq_len;
+    if (stage_b_bytes) *stage_b_bytes = beta * F * (d + 2) * n_heads * seq_len;
+    if (rounds) *rounds = m_split_scheme ? 2 * beta * beta : 2 * (int64_t)n_row_shards * beta * beta;
+    return CASCADE_OK;
+}
+
 extern "C" int32_t cascade_plan_maps(const cascade_plan *plan, const int32_t **perm_dev,
                                      const int32_t **inv_perm_dev, const int32_t **offsets_dev) {
     if (!plan) return CASCADE_EINVAL;

@@ -128,3 +128,27 @@ def test_generator_error_paths():
     with pytest.raises(cas.CascadeError) as ei:
         cas.cascade_m_split(np.array([0, 1, 2], dtype=np.int32), 3, 0)
     assert ei.value.status == cas.EINVAL
+
+
+def test_comm_cost_matches_equation_1_and_the_papers_table():
+    from oracle import cascade_oracle as orc
+    for alpha, beta, F, d, H, Hkv, N in [(16, 16, 2, 128, 32, 8, 2048), (3, 6, 4, 64, 12, 12, 128), (1, 1, 2, 16, 4, 4, 18)]:
+        a, b, r = cas.cascade_comm_cost(alpha, beta, F, d, H, Hkv, N)
+        total, oa, ob = orc.comm_bytes(beta, F, d, H, Hkv, N)
+        assert (a, b) == (oa, ob) and a + b == total == beta * F * (2 * d * H + 2 * d * Hkv + 2 * H) * N
+        assert r == 2 * alpha * beta * beta
+        assert cas.cascade_comm_cost(alpha, beta, F, d, H, Hkv, N, m_split_scheme=True)[2] == 2 * beta * beta
+    # the printed byte table (bf16, N = 128, beta = alpha, summed over layers; 3 decimals)
+    models = {"base": dict(H=12, d=64, layers=12), "large": dict(H=16, d=64, layers=24)}
+    path = os.path.join(os.path.dirname(__file__), "golden", "comm_table.txt")
+    for line in open(path):
+        if line.startswith("#") or not line.strip():
+            continue
+        alpha, base_gb, large_gb = line.split()
+        for name, want in (("base", float(base_gb)), ("large", float(large_gb))):
+            mdl = models[name]
+            a, b, _ = cas.cascade_comm_cost(int(alpha), int(alpha), 2, mdl["d"], mdl["H"], mdl["H"], 128)
+            assert abs((a + b) * mdl["layers"] / 1e9 - want) <= 0.0006
+    with pytest.raises(cas.CascadeError) as ei:
+        cas.cascade_comm_cost(0, 4, 2, 64, 8, 8, 128)
+    assert ei.value.status == cas.EINVAL
