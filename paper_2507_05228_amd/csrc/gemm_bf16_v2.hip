@@ -270,15 +270,16 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm2_kernel(Gemm2Params p) {
     const int KT = K / BK;
     constexpr int KS = BK / 32;
     static_assert(KS == 2, "the operand pipeline below alternates two register sets over the two k-steps of a tile");
-    bf16x8 af[2][TM], bfr[2][TN];
-    auto fetch = [&](int kt, auto ks_tag) {                // operands of k-step ks of tile kt -> register set ks
-        constexpr int ks = decltype(ks_tag)::value;
+    constexpr int NSETS = 4 * TM * TN + 8 * (TM + TN) <= 216 ? 2 : 1;
+    bf16x8 af[NSETS][TM], bfr[NSETS][TN];
+    auto fetch_into = [&](int kt, auto set_tag, auto ks_tag) {   // operands of k-step ks of tile kt -> register set
+        constexpr int set = decltype(set_tag)::value, ks = decltype(ks_tag)::value;
         const unsigned char *st = smem + (kt % NST) * STAGE_BYTES;
         const int coff = ((4 * ks + fch) ^ fsw) * 16;
 #pragma unroll
-        for (int i = 0; i < TM; ++i) af[ks][i] = *(const bf16x8 *)(st + a_lane + i * 16 * ROWB + coff);
+        for (int i = 0; i < TM; ++i) af[set][i] = *(const bf16x8 *)(st + a_lane + i * 16 * ROWB + coff);
 #pragma unroll
-        for (int j = 0; j < TN; ++j) bfr[ks][j] = *(const bf16x8 *)(st + b_lane + j * 16 * ROWB + coff);
+        for (int j = 0; j < TN; ++j) bfr[set][j] = *(const bf16x8 *)(st + b_lane + j * 16 * ROWB + coff);
     };
     auto mfmas = [&](auto ks_tag) {
         constexpr int ks = decltype(ks_tag)::value;
@@ -306,26 +307,41 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm2_kernel(Gemm2Params p) {
     TRACE(1);
     // Software pipeline over k-steps: the LDS reads of a k-step are in flight while the MFMAs of the
     // previous k-step run, also across the tile boundary (the second k-step of tile kt is multiplied
-    // after the barrier that opens tile kt+1, from registers).
+    // after the barrier that opens tile kt+1, from registers).  It needs two operand register sets;
+    // the widest tile (256 columns: 128 accumulator + 96 operand registers) would spill with them and
+    // keeps one k-step's reads directly ahead of its own MFMAs instead.
+    constexpr bool PIPE = 4 * TM * TN + 8 * (TM + TN) <= 216;
     tile_ready(0);
     TRACE(2);
-    fetch(0, k0);
-    for (int kt = 0; kt + 1 < KT; ++kt) {                  // straight-line body: the last tile is peeled
-        if (kt == KT / 2) TRACE(3);
-        fetch(kt, k1);
-        __builtin_amdgcn_sched_barrier(0);                 // reads stay ahead of the MFMAs they overlap with
+    if constexpr (PIPE) {
+        auto fetch = [&](int kt, auto ks_tag) { fetch_into(kt, ks_tag, ks_tag); };   // k-step ks -> register set ks
+        fetch(0, k0);
+        for (int kt = 0; kt + 1 < KT; ++kt) {              // straight-line body: the last tile is peeled
+            if (kt == KT / 2) TRACE(3);
+            fetch(kt, k1);
+            __builtin_amdgcn_sched_barrier(0);             // reads stay ahead of the MFMAs they overlap with
+            mfmas(k0);
+            __builtin_amdgcn_sched_barrier(0);
+            tile_ready(kt + 1);
+            fetch(kt + 1, k0);
+            __builtin_amdgcn_sched_barrier(0);
+            mfmas(k1);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        fetch(KT - 1, k1);
+        __builtin_amdgcn_sched_barrier(0);
         mfmas(k0);
-        __builtin_amdgcn_sched_barrier(0);
-        tile_ready(kt + 1);
-        fetch(kt + 1, k0);
-        __builtin_amdgcn_sched_barrier(0);
         mfmas(k1);
-        __builtin_amdgcn_sched_barrier(0);
+    } else {
+        for (int kt = 0; kt < KT; ++kt) {
+            if (kt == KT / 2) TRACE(3);
+            if (kt > 0) tile_ready(kt);
+            fetch_into(kt, k0, k0);
+            mfmas(k0);
+            fetch_into(kt, k0, k1);
+            mfmas(k0);
+        }
     }
-    fetch(KT - 1, k1);
-    __builtin_amdgcn_sched_barrier(0);
-    mfmas(k0);
-    mfmas(k1);
 
     __syncthreads();                                       // everyone is done with the tile buffers
     TRACE(4);
