@@ -69,6 +69,61 @@ __global__ __launch_bounds__(256) void merge_vec_kernel(const float *__restrict_
     }
 }
 
+// Few rows (single-token decode: N = 1): one workgroup per (b, h, r); its 256 / G lane groups take the
+// shards round-robin (so many loads are in flight per row) and their partial sums meet in LDS.
+template <typename T, int G>
+__global__ __launch_bounds__(256) void merge_fewrows_kernel(const float *__restrict__ m, const float *__restrict__ e,
+                                                            const float *__restrict__ u, T *__restrict__ o,
+                                                            float *__restrict__ lse, int B, int H, int S, int N,
+                                                            int64_t o_ld, const int32_t *__restrict__ omap, int u_mode) {
+    constexpr int d = G * 4;
+    constexpr int NG = 256 / G;                 // lane groups in the workgroup
+    __shared__ float red[NG][d + 1];
+    const int s = threadIdx.x % G, grp = threadIdx.x / G;
+    const int r = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const float *mrow = m + ((int64_t)(b * H + h) * S) * N + r;
+    const float *erow = e + ((int64_t)(b * H + h) * S) * N + r;
+    float n = -INFINITY;
+    for (int k = 0; k < S; ++k) n = fmaxf(n, mrow[(int64_t)k * N]);        // S small values, cached: every lane reads all
+    const float n_sub = (n == -INFINITY) ? 0.f : n;
+    float w = 0.f;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    const float *ub = u + (((int64_t)b * S * H + h) * N + r) * d + 4 * s;
+    const int64_t ustep = (int64_t)H * N * d;
+    for (int k = grp; k < S; k += NG) {
+        const float mk = mrow[(int64_t)k * N], ek = erow[(int64_t)k * N];
+        float c = (mk == -INFINITY) ? 0.f : expf(mk - n_sub);
+        w += c * ek;
+        if (u_mode == CASCADE_U_NORMALISED) c *= ek;
+        acc += c * *(const f32x4 *)(ub + k * ustep);
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) red[grp][4 * s + j] = acc[j];
+    if (s == 0) red[grp][d] = w;
+    __syncthreads();
+    if (grp == 0) {
+        f32x4 tot = {0.f, 0.f, 0.f, 0.f};
+        float wt = 0.f;
+#pragma unroll
+        for (int gq = 0; gq < NG; ++gq) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) tot[j] += red[gq][4 * s + j];
+            wt += red[gq][d];
+        }
+        const float inv = wt > 0.f ? 1.0f / wt : 0.f;
+        tot *= inv;
+        const int64_t orow = (int64_t)b * N + (omap ? omap[r] : r);
+        T *op = o + orow * o_ld + (int64_t)h * d + 4 * s;
+        if constexpr (sizeof(T) == 2) {
+            bf16x4 v = {(bf16_t)tot[0], (bf16_t)tot[1], (bf16_t)tot[2], (bf16_t)tot[3]};
+            *(bf16x4 *)op = v;
+        } else {
+            *(f32x4 *)op = tot;
+        }
+        if (lse && s == 0) lse[((int64_t)b * H + h) * N + r] = wt > 0.f ? n + logf(wt) : -INFINITY;
+    }
+}
+
 // Any d: one wavefront per (b, h, r), lanes stride over the columns.
 template <typename T>
 __global__ __launch_bounds__(256) void merge_scalar_kernel(const float *__restrict__ m, const float *__restrict__ e,
@@ -115,6 +170,11 @@ static int32_t launch_merge_t(const MergeArgs &a, hipStream_t s) {
 #define MERGE_CASE(GG)                                                                                          \
     case GG: {                                                                                                  \
         constexpr int RB = (64 / GG) * 4;                                                                       \
+        if (a.N * 2 <= RB && a.N <= 65535) {           /* mostly idle row slots: one workgroup per row */        \
+            hipLaunchKernelGGL((merge_fewrows_kernel<T, GG>), dim3(a.N, a.H, a.B), dim3(256), 0, s, a.m, a.e, a.u, \
+                               (T *)a.o, a.lse, a.B, a.H, a.n_shards, a.N, a.o_ld, a.o_rowmap, a.u_mode);       \
+            break;                                                                                              \
+        }                                                                                                       \
         dim3 grid((a.N + RB - 1) / RB, a.H, a.B);                                                               \
         hipLaunchKernelGGL((merge_vec_kernel<T, GG>), grid, dim3(256), 0, s, a.m, a.e, a.u, (T *)a.o, a.lse,    \
                            a.B, a.H, a.n_shards, a.N, a.o_ld, a.o_rowmap, a.u_mode);                            \
