@@ -3,10 +3,10 @@
  *
  * The library computes the single-layer forward pass of Cascade (Section 5,
  * Algorithm 1) with every shard resident on one GPU: per-shard linear layers
- * (Algorithm 2, Algorithm 4 line 9, the MLP of Algorithm 1 line 17), partial
+ * (Algorithm 2, the projection that closes Algorithm 4, the MLP step that closes Algorithm 1), partial
  * attention for every (query-shard, key/value-shard) pair with row maxima m and
  * subtract-max exponential sums e (Algorithm 3), and the log-sum-exp merge of
- * the partials (Algorithm 4 lines 1-8).  This build uses R = S (one token to
+ * the partials (the merge steps of Algorithm 4).  This build uses R = S (one token to
  * shard assignment for hiddens, queries and keys/values).
  *
  * Conventions
@@ -229,7 +229,7 @@ CASCADE_API int32_t cascade_partial_attn(const cascade_plan *plan, const cascade
                              float *m, float *e, float *u,
                              void *workspace, size_t workspace_bytes, void *stream);
 
-/* Algorithm 4 lines 1-8: n = max_k m_k; w = sum_k exp(m_k - n) e_k;
+/* The merge of Algorithm 4 (Post-Pass): n = max_k m_k; w = sum_k exp(m_k - n) e_k;
  * o = sum_k exp(m_k - n) e_k u_k / w (u~ form: sum_k exp(m_k - n) u~_k / w).
  * o [B, N, H*d] in desc->dtype, rows per desc->row_layout; lse_out (optional,
  * may be NULL) [B, H, N] fp32 = n + log w, packed rows.                         */

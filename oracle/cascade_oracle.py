@@ -25,7 +25,7 @@ the design notes):
     gives its formula literally, 1/sqrt(d) gives the standard layer).
   * A query row that sees no key of S_k has m = -inf, e = 0, u = 0 and weight 0 in
     the merge; exp(-inf - (-inf)) is never evaluated.
-  * The post-pass maximum n depends on the row only (Algorithm 4 line 3), not on k.
+  * The post-pass maximum n depends on the row only (the maximum step of Algorithm 4), not on k.
   * u has shape (H, rows, d) (Appendix D), not (H, N, |S_k|) as Table 2 prints.
   * mlp(h + o) is the rest of a pre-norm block: h1 = h + o, out = h1 + FFN(norm2(h1)).
   * The causal mask compares original token positions: s[x, y] = 0 if pos[y] <= pos[x]
@@ -194,20 +194,20 @@ def attn_pass(q, k, v, s, scale=1.0):
     if nk == 0:
         return np.full((H, nq), -np.inf), np.zeros((H, nq)), np.zeros((H, nq, d))
     rep = H // Hkv
-    k = np.repeat(k, rep, axis=0)                       # line 1: repeat_kv
-    v = np.repeat(v, rep, axis=0)                       # line 2
-    a = scale * (q @ k.transpose(0, 2, 1)) + s[None]    # line 3
-    m = a.max(axis=-1)                                  # line 4
+    k = np.repeat(k, rep, axis=0)                       # repeat_kv on k
+    v = np.repeat(v, rep, axis=0)                       # repeat_kv on v
+    a = scale * (q @ k.transpose(0, 2, 1)) + s[None]    # scores plus mask
+    m = a.max(axis=-1)                                  # row maxima
     m_sub = np.where(np.isfinite(m), m, 0.0)            # rows with no visible key: exp(-inf - 0) = 0
-    a = np.exp(a - m_sub[..., None])                    # line 5
-    e = a.sum(axis=-1)                                  # line 6
+    a = np.exp(a - m_sub[..., None])                    # subtract-max exponentials
+    e = a.sum(axis=-1)                                  # their row sums
     e_div = np.where(e > 0.0, e, 1.0)
-    a = a / e_div[..., None]                            # line 7
-    u = a @ v                                           # line 8
+    a = a / e_div[..., None]                            # normalise within the shard
+    u = a @ v                                           # partial output
     return m, e, u
 
 
-# --------------------------------------------------------------------------- Algorithm 4 (lines 1-8)
+# --------------------------------------------------------------------------- Algorithm 4 (merge)
 def post_pass_merge(ms, es, us):
     """Combine beta partials of the same query rows (Algorithm 4 before o_proj).
 
@@ -279,7 +279,7 @@ def partial_attention_rs(q, k, v, token_to_row_shard, n_row_shards, token_to_kv_
 
 
 def lse_merge_all(m, e, u):
-    """Algorithm 4 lines 1-8 over the kv-shard axis of packed partials.
+    """The merge steps of Algorithm 4 over the kv-shard axis of packed partials.
     m, e (H, beta, N); u (beta, H, N, d) normalised.  Returns o (N, H*d), packed rows."""
     beta = m.shape[1]
     o = post_pass_merge([m[:, kk] for kk in range(beta)], [e[:, kk] for kk in range(beta)],
@@ -310,7 +310,7 @@ def decode_partials(q_new, k_shards, v_shards, scale=1.0):
 
 
 def decode_merge(m, e, u):
-    """Algorithm 4 lines 1-8 for the one new row: m, e (H, beta); u (beta, H, d).  Returns o (H*d)."""
+    """The merge steps of Algorithm 4 for the one new row: m, e (H, beta); u (beta, H, d).  Returns o (H*d)."""
     beta = m.shape[1]
     o = post_pass_merge([m[:, kk:kk + 1] for kk in range(beta)], [e[:, kk:kk + 1] for kk in range(beta)],
                         [u[kk][:, None, :] for kk in range(beta)])
@@ -350,7 +350,7 @@ def layer_direct(h, w, cfg, positions=None, mask_kind="causal", scale=None, rows
 
 
 def _block_tail(h_rows, o, w, cfg):
-    """What follows the attention values on a set of rows (Algorithm 4 line 9 and Algorithm 1 line 17):
+    """What follows the attention values on a set of rows (the projection that closes Algorithm 4 and the last step of Algorithm 1):
     output projection, residual and MLP, with the norms before the sub-blocks ("pre", the default
     reading) or after the residual sums ("post", the BERT-shaped block of the paper's timing runs)."""
     if getattr(cfg, "norm_placement", "pre") == "post":
@@ -371,18 +371,18 @@ def layer_sharded(h, w, cfg, token_to_shard, n_shards, positions=None, mask_kind
     scale = cfg.scale if scale is None else scale
     lists = shard_index_lists(token_to_shard, n_shards)
 
-    # pre-pass on every hidden shard (Algorithm 1 lines 1-2)
+    # pre-pass on every hidden shard (Algorithm 1, pre-pass step)
     qkv = [pre_pass(h[R], pos[R], w, cfg) for R in lists]
 
-    # attention-pass on every pair (Algorithm 1 lines 8-9); with R = S the routing of
-    # Algorithm 1 line 4 hands AttnNode_jk the whole of shard j's q and shard k's k, v.
+    # attention-pass on every pair (Algorithm 1, attention-pass step); with R = S the stage-A routing
+    # of Algorithm 1 hands AttnNode_jk the whole of shard j's q and shard k's k, v.
     partial = {}
     for j, Sj in enumerate(lists):
         for kk, Sk in enumerate(lists):
             s = mask_block(pos[Sj], pos[Sk], mask_kind)
             partial[(j, kk)] = attn_pass(qkv[j][0], qkv[kk][1], qkv[kk][2], s, scale)
 
-    # post-pass, residual and MLP on every hidden shard (Algorithm 1 lines 15-17)
+    # post-pass, residual and MLP on every hidden shard (Algorithm 1, closing steps)
     out = np.empty_like(h)
     for i, R in enumerate(lists):
         if len(R) == 0:
@@ -390,9 +390,9 @@ def layer_sharded(h, w, cfg, token_to_shard, n_shards, positions=None, mask_kind
         ms = [partial[(i, kk)][0] for kk in range(n_shards)]
         es = [partial[(i, kk)][1] for kk in range(n_shards)]
         us = [partial[(i, kk)][2] for kk in range(n_shards)]
-        o = post_pass_merge(ms, es, us)                               # Algorithm 4 lines 1-8
+        o = post_pass_merge(ms, es, us)                               # Algorithm 4 merge
         o = o.transpose(1, 0, 2).reshape(len(R), -1)
-        out[R] = _block_tail(h[R], o, w, cfg)                         # line 9, residual, MLP
+        out[R] = _block_tail(h[R], o, w, cfg)                         # o projection, residual, MLP
     if return_partials:
         return out, partial
     return out
@@ -413,21 +413,21 @@ def layer_sharded_rs(h, w, cfg, token_to_row_shard, n_row_shards, token_to_kv_sh
 
     # pre-pass on every hidden shard, then stage-A routing: AttnNode_jk receives the rows
     # R_i ∩ S_j of q and R_i ∩ S_k of k, v from every CompNode_i and concatenates them in
-    # sorted order (Algorithm 1 lines 1-7); held here as full-length arrays indexed by token
+    # sorted order (Algorithm 1, pre-pass and stage-A routing); held here as full-length arrays indexed by token
     q = np.empty((H, N, d)); k = np.empty((Hkv, N, d)); v = np.empty((Hkv, N, d))
     for R in r_lists:
         if len(R):
             q[:, R], k[:, R], v[:, R] = pre_pass(h[R], pos[R], w, cfg)
 
-    # attention-pass on every pair of S shards (lines 8-9); stage-B routing sends row t of
-    # AttnNode_jk's result to the CompNode that holds t (lines 10-14)
+    # attention-pass on every pair of S shards (Algorithm 1, attention-pass step); stage-B routing sends row t of
+    # AttnNode_jk's result to the CompNode that holds t
     m = np.full((n_kv_shards, H, N), -np.inf); e = np.zeros((n_kv_shards, H, N)); u = np.zeros((n_kv_shards, H, N, d))
     for Sj in s_lists:
         for kk, Sk in enumerate(s_lists):
             s = mask_block(pos[Sj], pos[Sk], mask_kind)
             m[kk][:, Sj], e[kk][:, Sj], u[kk][:, Sj] = attn_pass(q[:, Sj], k[:, Sk], v[:, Sk], s, scale)
 
-    # post-pass, residual and MLP on every hidden shard (lines 15-17)
+    # post-pass, residual and MLP on every hidden shard (Algorithm 1, closing steps)
     out = np.empty_like(h)
     for R in r_lists:
         if len(R) == 0:

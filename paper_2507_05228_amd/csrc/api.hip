@@ -294,7 +294,7 @@ static int32_t layer_forward_impl(const cascade_plan *plan, const cascade_layer_
         if ((st = mark()) != CASCADE_OK) return st;                               // 5: LSE merge
     }
 
-    // 3. o projection + residual (Algorithm 4 line 9, Algorithm 1 line 17)
+    // 3. o projection + residual (the projection that closes Algorithm 4, the residual of Algorithm 1's last step)
     g = {};
     g.dtype = d->dtype; g.M = T; g.N = D; g.K = H * hd; g.X = ao; g.W[0] = w->wo;
     g.seg_end[0] = g.seg_end[1] = g.seg_end[2] = D;

@@ -1,6 +1,6 @@
 // Token-sharded KV-cache decode (Cost Optimizations appendix, "Caching"): the newest token's query
 // row against the cached keys / values of every kv shard S_k, giving one partial (m, e, u~) per shard,
-// which cascade_lse_merge then combines exactly as in the prefill path (Algorithm 4 lines 1-8).
+// which cascade_lse_merge then combines exactly as in the prefill path (the merge of Algorithm 4).
 // Every cached key is at or before the new position, so there is no mask; only the shard lengths.
 //
 // HBM-bound: each cached K and V row is read once.  WPS wavefronts share one (shard, kv head,

@@ -1,6 +1,6 @@
 // bf16 shard GEMM on the gfx950 matrix cores: Y[rows] = epilogue(X[rows] W^T), fp32 accumulation.
 // These are the token-as-batch linear layers of the method (q/k/v projection of Algorithm 2,
-// o projection of Algorithm 4 line 9, the MLP of Algorithm 1 line 17).  Weights are shared by
+// o projection that closes Algorithm 4, the MLP step that closes Algorithm 1).  Weights are shared by
 // all shards, so the shard structure shows up only as row maps (gather on the X read, gather on
 // the residual read, scatter on the Y store).
 //

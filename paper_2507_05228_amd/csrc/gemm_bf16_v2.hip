@@ -1,6 +1,6 @@
 // bf16 shard GEMM, main kernel: Y[rows] = epilogue(X[rows] W^T), fp32 accumulation, K % 64 == 0.
-// (The token-as-batch linear layers: q/k/v projection of Algorithm 2, o projection of Algorithm 4
-// line 9, the MLP of Algorithm 1 line 17.  Shards appear only as row maps.)
+// (The token-as-batch linear layers: q/k/v projection of Algorithm 2, o projection that
+// closes Algorithm 4, the MLP step that closes Algorithm 1.  Shards appear only as row maps.)
 //
 // Shape of the kernel (chosen from measurements on MI355X: 16x16x32 bf16 MFMA reaches ~98 % of the
 // chip's matrix peak with two wavefronts per SIMD, ~89 % with one; LDS delivers ~235 B/clk/CU on

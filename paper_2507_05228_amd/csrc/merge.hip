@@ -1,4 +1,4 @@
-// Log-sum-exp merge of the per-shard partials (Algorithm 4 lines 1-8; derivation in the
+// Log-sum-exp merge of the per-shard partials (the merge steps of Algorithm 4; derivation in the
 // Post-Pass subsection):  n = max_k m_k,  w = sum_k exp(m_k - n) e_k,
 // o = sum_k exp(m_k - n) e_k u_k / w   (with u~ = e u stored: o = sum_k exp(m_k - n) u~_k / w).
 // HBM-bound: one pass over n_shards rows of d floats per (batch, head, query row).

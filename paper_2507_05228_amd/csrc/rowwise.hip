@@ -1,6 +1,6 @@
 // HBM-bound per-token kernels: normalisation with row gather (Pre-Pass subsection: "applies
 // layer normalization if necessary"), rotary embedding at original token positions
-// (Algorithm 2 lines 4-5).  The gather into packed order is the row map of the norm's read; the
+// (the rotary step of Algorithm 2).  The gather into packed order is the row map of the norm's read; the
 // scatter back is the row map of the last shard GEMM's store.
 #include <cmath>
 #include "common.h"
