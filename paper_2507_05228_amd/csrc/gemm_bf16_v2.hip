@@ -163,6 +163,96 @@ __device__ __forceinline__ void gemm_epilogue(const Gemm2Params &p, f32x4 (&acc)
     }
 }
 
+// Epilogue for accumulators computed transposed (W block as the first MFMA operand): acc[i][j][r]
+// holds row 16i + lane%16, columns 16j + 4(lane/16) + r of the wavefront's tile, so a lane owns four
+// consecutive output columns.  Bias, activation, SwiGLU (block j = gate, block j + TN/2 = up: same
+// lane, same slot) and the residual are applied in registers, before the one rounding to bf16; the
+// result of the whole workgroup tile is laid out row-major in LDS (the tile buffers are free by then)
+// and written out in 16-byte pieces that follow each other along the output rows, so every store
+// instruction fills whole cache lines.  Row pitch: an odd multiple of 32 bytes, which spreads the 16
+// rows of a block write over all banks.
+template <int BN_OUT>
+struct EpiTile {
+    static constexpr int PITCH = ((BN_OUT * 2 + 31) / 32 | 1) * 32;   // bytes
+    static constexpr int bytes(int bm) { return bm * PITCH; }
+};
+template <int BM, int NTHREADS, int TM, int TN, int WTN, bool SWIGLU, int BN_OUT>
+__device__ __forceinline__ void gemm_epilogue_tile(const Gemm2Params &p, f32x4 (&acc)[TM][TN], unsigned char *smem,
+                                                   int tid, int m0, int wm0, int wn0, int nloc0, int seg,
+                                                   int seg_rows) {
+    static_assert(!SWIGLU || TN % 2 == 0, "gate and up blocks pair up inside the wavefront tile");
+    constexpr int TNO = SWIGLU ? TN / 2 : TN;              // output blocks of the wavefront tile
+    constexpr int OW = SWIGLU ? WTN / 2 : WTN;
+    constexpr int PITCH = EpiTile<BN_OUT>::PITCH;
+    const int flags = p.flags;
+    const int lane = tid & 63, l16 = lane & 15, c4 = (lane >> 4) * 4;
+    const int wc0 = (wn0 / WTN) * OW;                      // wavefront's first output column inside the tile
+    const bf16_t *bias = (!SWIGLU && (flags & CASCADE_EPI_BIAS)) ? p.bias[seg] : nullptr;
+    const bool act = flags & (CASCADE_EPI_GELU_ERF | CASCADE_EPI_GELU_TANH);
+    const int gcol0 = p.seg_col0[seg];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        const int row = wm0 + 16 * i + l16, gm = m0 + row;
+        const bf16_t *rrow = ((flags & CASCADE_EPI_RESIDUAL) && gm < p.M)
+                                 ? p.residual + map_row(p.rmap, p.seq_len, gm) * p.ldres + gcol0 + nloc0 : nullptr;
+#pragma unroll
+        for (int j = 0; j < TNO; ++j) {
+            const int tc = wc0 + 16 * j + c4;              // column inside the tile
+            const int nleft = seg_rows - (nloc0 + tc);     // columns of the segment from here on
+            f32x4 v = acc[i][j];
+            if (SWIGLU) {
+#pragma unroll
+                for (int x = 0; x < 4; ++x) v[x] = silu_fast(v[x]) * acc[i][j + TNO][x];
+            } else {
+                if (bias)
+#pragma unroll
+                    for (int x = 0; x < 4; ++x)
+                        if (x < nleft) v[x] += (float)bias[nloc0 + tc + x];
+                if (act)
+#pragma unroll
+                    for (int x = 0; x < 4; ++x) v[x] = apply_act(v[x], flags);
+            }
+            if (rrow) {                                    // added before the one rounding to bf16
+                if (nleft >= 4) {
+                    const bf16x4 rv = *(const bf16x4 *)(rrow + tc);
+#pragma unroll
+                    for (int x = 0; x < 4; ++x) v[x] += (float)rv[x];
+                } else {
+#pragma unroll
+                    for (int x = 0; x < 4; ++x)
+                        if (x < nleft) v[x] += (float)rrow[tc + x];
+                }
+            }
+            const bf16x4 o = {(bf16_t)v[0], (bf16_t)v[1], (bf16_t)v[2], (bf16_t)v[3]};
+            *(bf16x4 *)(smem + row * PITCH + tc * 2) = o;
+        }
+    }
+    __syncthreads();
+    constexpr int CPRO = BN_OUT / 8;                       // 16-byte pieces per tile row
+    static_assert(BN_OUT % 8 == 0, "whole pieces");
+    // 16-byte stores need the rows to start on 16-byte boundaries; otherwise two 8-byte halves
+    const bool wide = ((p.ldy | gcol0) % 8 == 0) && ((uintptr_t)p.Y % 16 == 0);
+    for (int q = tid; q < BM * CPRO; q += NTHREADS) {
+        const int row = q / CPRO, c = nloc0 + (q % CPRO) * 8;
+        const int gm = m0 + row;
+        if (gm >= p.M || c >= seg_rows) continue;
+        const bf16x8 v = *(const bf16x8 *)(smem + row * PITCH + (q % CPRO) * 16);
+        bf16_t *y = p.Y + map_row(p.ymap, p.seq_len, gm) * p.ldy + gcol0 + c;
+        if (c + 8 <= seg_rows) {
+            if (wide) {
+                *(bf16x8 *)y = v;
+            } else {
+                *(bf16x4 *)y = bf16x4{v[0], v[1], v[2], v[3]};
+                *(bf16x4 *)(y + 4) = bf16x4{v[4], v[5], v[6], v[7]};
+            }
+        } else {
+#pragma unroll
+            for (int x = 0; x < 8; ++x)
+                if (c + x < seg_rows) y[x] = v[x];
+        }
+    }
+}
+
 template <int N>
 __device__ __forceinline__ void wait_loads_and_barrier() {
     // all but the N youngest vector-memory operations of this wavefront are complete and its LDS reads
@@ -170,11 +260,24 @@ __device__ __forceinline__ void wait_loads_and_barrier() {
     asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
 }
 
+// MFMA with the accumulator tied to the destination and held in the accumulation registers.  Used by
+// the one-wavefront-per-SIMD schedule, where the 224-256 accumulator registers of a 128-row wavefront
+// tile only fit there; written as assembly so that source and destination stay the same registers and
+// so that the hand-placed operand reads and tile loads keep their place between the MFMAs (the
+// compiler does not move memory operations across these statements).
+__device__ __forceinline__ void mfma_tied(f32x4 &c, const bf16x8 &a, const bf16x8 &b) {
+    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
+}
+// The compiler does not see those MFMAs: before anything else reads the accumulators, let the last
+// ones leave the matrix pipeline.
+__device__ __forceinline__ void mfma_drain() { asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" ::: "memory"); }
+
 template <int BM, int BN, int WM, int WN, int BK, int NST, bool SWIGLU>
 __global__ __launch_bounds__(WM *WN * 64) void gemm2_kernel(Gemm2Params p) {
     constexpr int NW = WM * WN;
     constexpr int WTM = BM / WM, WTN = BN / WN;
     constexpr int TM = WTM / 16, TN = WTN / 16;
+    constexpr bool SOLO = NW == 4;                                 // one wavefront per SIMD, up to 512 registers
     constexpr int ROWB = BK * 2;                                   // bytes per tile row in LDS
     constexpr int RPI = 1024 / ROWB;                               // tile rows per direct-to-LDS instruction
     constexpr int CPR = ROWB / 16;                                 // 16-byte chunks per row
@@ -186,10 +289,10 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm2_kernel(Gemm2Params p) {
     static_assert(BK == 32 || BK == 64, "BK");
     static_assert(NST >= 2 && NST <= 4 && (NST - 2) * LPT < 64, "pipeline depth");
     static_assert(BM % (RPI * NW) == 0, "tile rows must split over the wavefronts");
-    static_assert(WTN % 16 == 0 && WTN <= 128 && BN % RPI == 0, "wavefront tile: whole MFMA blocks, at most 128 columns");
+    static_assert(WTN % 16 == 0 && (SOLO || WTN <= 128) && BN % RPI == 0, "wavefront tile: whole MFMA blocks, at most 128 columns");
     static_assert(!SWIGLU || ((WTN / 2) % RPI == 0 && (WTN / 2) % 4 == 0),
                   "a load instruction / a store chunk must not straddle gate and up rows");
-    static_assert(NW * 16 * STG_LD * 4 <= NST * STAGE_BYTES, "epilogue staging must fit in the tile buffers");
+    static_assert(SOLO || NW * 16 * STG_LD * 4 <= NST * STAGE_BYTES, "epilogue staging must fit in the tile buffers");
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
@@ -242,20 +345,23 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm2_kernel(Gemm2Params p) {
         b_off[i] = (row < BN && col < seg_rows) ? (uint32_t)((int64_t)col * K * 2) + c * 16 : OOB_OFF;
     }
 
-    auto issue_loads = [&](int kt, int stage) {
+    auto issue_load = [&](int kt, int stage, int x) {              // instruction x of LPT (x known after unrolling)
         const uint32_t kb = (uint32_t)kt * ROWB;
-        unsigned char *sa = smem + stage * STAGE_BYTES + wave * (BM / NW) * ROWB;
-        unsigned char *sb = smem + stage * STAGE_BYTES + A_BYTES + wave * (BNP / NW) * ROWB;
-#pragma unroll
-        for (int i = 0; i < A_INSTR; ++i)
-            load16_to_lds(rx, sa + i * 1024, a_off[i] + kb);
-#pragma unroll
-        for (int i = 0; i < B_INSTR; ++i) {
+        if (x < A_INSTR) {
+            unsigned char *sa = smem + stage * STAGE_BYTES + wave * (BM / NW) * ROWB;
+            load16_to_lds(rx, sa + x * 1024, a_off[x] + kb);
+        } else {
+            const int i = x - A_INSTR;
+            unsigned char *sb = smem + stage * STAGE_BYTES + A_BYTES + wave * (BNP / NW) * ROWB;
             const int row0 = wave * (BNP / NW) + RPI * i;                   // wavefront-uniform
             const bool up = SWIGLU && ((row0 % WTN) >= WTN / 2);
             if (up) load16_to_lds(ru, sb + i * 1024, b_off[i] + kb);
             else load16_to_lds(rw, sb + i * 1024, b_off[i] + kb);
         }
+    };
+    auto issue_loads = [&](int kt, int stage) {
+#pragma unroll
+        for (int x = 0; x < LPT; ++x) issue_load(kt, stage, x);
     };
 
     f32x4 acc[TM][TN];
@@ -270,7 +376,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm2_kernel(Gemm2Params p) {
     const int KT = K / BK;
     constexpr int KS = BK / 32;
     static_assert(KS == 2, "the operand pipeline below alternates two register sets over the two k-steps of a tile");
-    constexpr int NSETS = 4 * TM * TN + 8 * (TM + TN) <= 216 ? 2 : 1;
+    constexpr int NSETS = SOLO || 4 * TM * TN + 8 * (TM + TN) <= 216 ? 2 : 1;
     bf16x8 af[NSETS][TM], bfr[NSETS][TN];
     auto fetch_into = [&](int kt, auto set_tag, auto ks_tag) {   // operands of k-step ks of tile kt -> register set
         constexpr int set = decltype(set_tag)::value, ks = decltype(ks_tag)::value;
@@ -313,7 +419,54 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm2_kernel(Gemm2Params p) {
     constexpr bool PIPE = 4 * TM * TN + 8 * (TM + TN) <= 216;
     tile_ready(0);
     TRACE(2);
-    if constexpr (PIPE) {
+    if constexpr (SOLO) {
+        // One wavefront per SIMD: nothing else covers this wavefront's waits, so every memory operation
+        // is placed between two MFMAs of the k-step that runs meanwhile.  Tile kt, first k-step: its
+        // MFMAs with the operand reads of the second k-step between them, all issued in the first half
+        // so that they have returned at the barrier.  Barrier (tile kt+1 landed, everyone is done reading
+        // tile kt).  Second k-step: its MFMAs with the direct-to-LDS loads of tile kt+NST (into the stage
+        // tile kt just left) and the operand reads of tile kt+1's first k-step between them.
+        constexpr int NR = TM + TN;
+        static_assert(2 * NR <= TM * TN && 2 * LPT <= TM * TN, "one memory operation per two MFMAs");
+        auto fetch_one = [&](int kt, auto ks_tag, int r) {     // read r of a k-step: A block 0, the B blocks, the other A blocks
+            constexpr int ks = decltype(ks_tag)::value;
+            const unsigned char *st = smem + (kt % NST) * STAGE_BYTES;
+            const int coff = ((4 * ks + fch) ^ fsw) * 16;
+            if (r == 0) af[ks][0] = *(const bf16x8 *)(st + a_lane + coff);
+            else if (r <= TN) bfr[ks][r - 1] = *(const bf16x8 *)(st + b_lane + (r - 1) * 16 * ROWB + coff);
+            else af[ks][r - TN] = *(const bf16x8 *)(st + a_lane + (r - TN) * 16 * ROWB + coff);
+        };
+        auto phase = [&](auto ks_tag, auto &&between) {        // the MFMAs of one k-step; between(x) follows MFMA x
+            constexpr int ks = decltype(ks_tag)::value;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    mfma_tied(acc[i][j], bfr[ks][j], af[ks][i]);     // transposed: lane = row, 4 columns
+                    between(i * TN + j);
+                }
+        };
+#pragma unroll
+        for (int r = 0; r < NR; ++r) fetch_one(0, k0, r);
+        int kt = 0;
+        for (; kt + NST < KT; ++kt) {                          // tiles kt+1 .. kt+NST-1 are in flight or landed
+            if (kt == KT / 2) TRACE(3);
+            phase(k0, [&](int x) { if (x % 2 == 0 && x / 2 < NR) fetch_one(kt, k1, x / 2); });
+            wait_loads_and_barrier<(NST - 2) * LPT>();
+            phase(k1, [&](int x) {
+                if (x % 2 == 0 && x / 2 < LPT) issue_load(kt + NST, kt % NST, x / 2);
+                if (x % 2 == 1 && x / 2 < NR) fetch_one(kt + 1, k0, x / 2);
+            });
+        }
+        for (; kt + 1 < KT; ++kt) {                            // the last tiles but one: nothing left to load
+            phase(k0, [&](int x) { if (x % 2 == 0 && x / 2 < NR) fetch_one(kt, k1, x / 2); });
+            wait_loads_and_barrier<0>();
+            phase(k1, [&](int x) { if (x % 2 == 1 && x / 2 < NR) fetch_one(kt + 1, k0, x / 2); });
+        }
+        phase(k0, [&](int x) { if (x % 2 == 0 && x / 2 < NR) fetch_one(KT - 1, k1, x / 2); });
+        phase(k1, [&](int) {});
+        mfma_drain();
+    } else if constexpr (PIPE) {
         auto fetch = [&](int kt, auto ks_tag) { fetch_into(kt, ks_tag, ks_tag); };   // k-step ks -> register set ks
         fetch(0, k0);
         for (int kt = 0; kt + 1 < KT; ++kt) {              // straight-line body: the last tile is peeled
@@ -343,9 +496,15 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm2_kernel(Gemm2Params p) {
         }
     }
 
-    __syncthreads();                                       // everyone is done with the tile buffers
-    TRACE(4);
-    gemm_epilogue<TM, TN, WTN, SWIGLU>(p, acc, smem, wave, lane, m0, wm0, wn0, nloc0, seg, seg_rows);
+    if constexpr (SOLO) {
+        __syncthreads();                                   // everyone is done with the tile buffers
+        TRACE(4);
+        gemm_epilogue_tile<BM, NW * 64, TM, TN, WTN, SWIGLU, BN_OUT>(p, acc, smem, tid, m0, wm0, wn0, nloc0, seg, seg_rows);
+    } else {
+        __syncthreads();                                   // everyone is done with the tile buffers
+        TRACE(4);
+        gemm_epilogue<TM, TN, WTN, SWIGLU>(p, acc, smem, wave, lane, m0, wm0, wn0, nloc0, seg, seg_rows);
+    }
     TRACE(5);
 }
 
@@ -557,7 +716,8 @@ static int32_t launch_cfg2(const GemmArgs &a, hipStream_t s) {
     p.x_bytes = (uint32_t)xb;
     constexpr int LOAD_ROWS = 1024 / (BK * 2) * WM * WN;                  // B rows loaded per pass of all wavefronts
     constexpr int BNP = PINGPONG ? BN : (BN + LOAD_ROWS - 1) / LOAD_ROWS * LOAD_ROWS;
-    constexpr size_t lds = (size_t)NST * (BM + BNP) * BK * 2;
+    constexpr size_t lds_loop = (size_t)NST * (BM + BNP) * BK * 2;
+    constexpr size_t lds = (!PINGPONG && WM * WN == 4) ? std::max(lds_loop, (size_t)EpiTile<BN_OUT>::bytes(BM)) : lds_loop;
     static_assert(lds <= 160 * 1024, "tile buffers exceed the LDS of a CU");
     const void *kern;
     if constexpr (PINGPONG) kern = (const void *)gemm3_kernel<BM, BN, WM, WN, BK, NST, SWIGLU>;
@@ -605,13 +765,13 @@ int32_t launch_gemm_bf16_v2(const GemmArgs &a, hipStream_t s) {
     auto cost = [&](int bne) { return ((n_tiles(swiglu ? bne / 2 : bne) + cus - 1) / cus) * bne; };
     const int64_t c256 = cost(256), c224 = cost(224), c192 = cost(192);
     if (swiglu) {
-        if (c224 < c256) return launch_cfg2<256, 224, 4, 2, 64, 2, true, false>(a, s);
-        return launch_cfg2<256, 256, 4, 2, 64, 2, true, false>(a, s);
+        if (c224 < c256) return launch_cfg2<256, 224, 4, 1, 64, 2, true, false>(a, s);
+        return launch_cfg2<256, 256, 2, 2, 64, 2, true, false>(a, s);
     }
     if (n_tiles(256) >= 160) {
         if (c192 < c256 && c192 <= c224) return launch_cfg2<256, 192, 4, 2, 64, 2, false, false>(a, s);
         if (c224 < c256) return launch_cfg2<256, 224, 4, 2, 64, 2, false, false>(a, s);
-        return launch_cfg2<256, 256, 4, 2, 64, 2, false, false>(a, s);
+        return launch_cfg2<256, 256, 4, 2, 64, 2, false, false>(a, s);   // 256 accumulators leave the one-wavefront schedule no room
     }
     return launch_cfg2<256, 128, 4, 2, 64, 3, false, true>(a, s);
 }
