@@ -7,9 +7,9 @@ bit-identical inputs.  Neither the oracle nor the HIP library imports the other;
 both may import this.
 """
 from .configs import CONFIGS, LayerConfig, get_config
-from .generate import (make_assignment, make_hidden, make_layer_weights,
+from .generate import (make_assignment, make_hidden, make_layer_weights, make_head_weights,
                        round_to_bf16, bf16_bits, bf16_bits_to_f32, config_seed)
 
 __all__ = ["CONFIGS", "LayerConfig", "get_config", "make_assignment", "make_hidden",
-           "make_layer_weights", "round_to_bf16", "bf16_bits", "bf16_bits_to_f32",
+           "make_layer_weights", "make_head_weights", "round_to_bf16", "bf16_bits", "bf16_bits_to_f32",
            "config_seed"]

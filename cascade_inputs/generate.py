@@ -101,3 +101,17 @@ def make_layer_weights(cfg: LayerConfig, seed: int = None) -> dict:
         w["b_up"] = _normal(rng, (f,), s, bf)
         w["b_down"] = _normal(rng, (D,), s, bf)
     return w
+
+
+def make_head_weights(cfg: LayerConfig, vocab: int, seed: int = None) -> dict:
+    """Closing norm and vocabulary projection [vocab, d_model], drawn like the layer parameters."""
+    seed = config_seed(cfg) if seed is None else seed
+    rng = np.random.Generator(np.random.PCG64(seed ^ 0x4444))
+    bf = cfg.dtype == "bf16"
+    head = {"w_vocab": _normal(rng, (vocab, cfg.d_model), cfg.sigma, bf),
+            "norm_g": (1.0 + _normal(rng, (cfg.d_model,), cfg.sigma, False)).astype(np.float32)}
+    if bf:
+        head["norm_g"] = round_to_bf16(head["norm_g"])
+    if cfg.norm == "layernorm":
+        head["norm_b"] = _normal(rng, (cfg.d_model,), cfg.sigma, bf)
+    return head

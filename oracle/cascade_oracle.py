@@ -453,6 +453,40 @@ def layer_stack_sharded(h, layer_weights, cfg, token_to_shard, n_shards, **kw):
     return h
 
 
+# --------------------------------------------------------------------------- LM head on sharded rows
+def lm_head_direct(h, head, cfg):
+    """Definition of the result: logits[t] = W_vocab . norm_f(h[t]) for every token t (the closing
+    normalisation of the model, then the vocabulary projection).  h (N, D) -> (N, V)."""
+    h = np.asarray(h, dtype=F64)
+    x = norm(h, cfg.norm, np.asarray(head["norm_g"], F64),
+             None if head.get("norm_b") is None else np.asarray(head["norm_b"], F64), cfg.eps)
+    return linear(x, np.asarray(head["w_vocab"], F64), None)
+
+
+def lm_head_sharded(h, head, cfg, token_to_shard, n_shards):
+    """Single Layer Pipeline subsection, after the last layer: every CompNode_i applies the LM head to
+    its own rows R_i and obtains R_i-sharded logits; they are laid back at the token positions."""
+    h = np.asarray(h, dtype=F64)
+    lists = shard_index_lists(token_to_shard, n_shards)
+    V = np.asarray(head["w_vocab"]).shape[0]
+    logits = np.empty((h.shape[0], V), dtype=F64)
+    for R in lists:
+        if len(R):
+            logits[R] = lm_head_direct(h[R], head, cfg)
+    return logits
+
+
+def next_token(h, head, cfg, token_to_shard, n_shards, positions=None):
+    """The CompNode that holds the last token (largest position) turns its logits row into the next
+    token: greedy choice, lowest index on ties.  Returns (token id, shard that produced it, logits row)."""
+    N = np.asarray(h).shape[0]
+    pos = np.arange(N) if positions is None else np.asarray(positions)
+    t_last = int(np.argmax(pos))
+    shard = int(np.asarray(token_to_shard)[t_last])
+    row = lm_head_direct(np.asarray(h, F64)[t_last:t_last + 1], head, cfg)[0]
+    return int(np.argmax(row)), shard, row
+
+
 def layer_direct_batch(h, w, cfg, **kw):
     return np.stack([layer_direct(h[b], w, cfg, **kw) for b in range(h.shape[0])])
 

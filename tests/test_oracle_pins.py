@@ -675,3 +675,66 @@ def test_layer_stack_is_the_composition_of_layers_under_any_sharding():
     for seed, beta in [(1, 4), (2, 6)]:
         a = make_assignment("perm", cfg.seq_len, beta, seed)
         assert rel_err(orc.layer_stack_sharded(h, ws, cfg, a, beta), want) < 1e-11
+
+
+# ---------------------------------------------------------------- LM head on sharded rows
+@pytest.mark.parametrize("cfg", [TINY_LLAMA, TINY_GPT], ids=lambda c: c.name)
+def test_lm_head_direct_equals_brute_force(cfg):
+    """Closing norm and vocabulary projection from their definitions, Python loops."""
+    from cascade_inputs import make_head_weights
+    V = 37
+    head = make_head_weights(cfg, V)
+    head = {k: v * (8.0 if v.ndim == 2 else 1.0) for k, v in head.items()}
+    h = make_hidden(cfg)[0].astype(np.float64)
+    N, D = h.shape
+    want = np.zeros((N, V))
+    for t in range(N):
+        row = [float(x) for x in h[t]]
+        if cfg.norm == "layernorm":
+            mu = sum(row) / D
+            var = sum((x - mu) ** 2 for x in row) / D
+            xn = [(x - mu) / math.sqrt(var + cfg.eps) * float(head["norm_g"][i]) + float(head["norm_b"][i])
+                  for i, x in enumerate(row)]
+        else:
+            ms = sum(x * x for x in row) / D
+            xn = [x / math.sqrt(ms + cfg.eps) * float(head["norm_g"][i]) for i, x in enumerate(row)]
+        for c in range(V):
+            want[t, c] = sum(xn[i] * float(head["w_vocab"][c, i]) for i in range(D))
+    assert rel_err(orc.lm_head_direct(h, head, cfg), want) < 1e-13
+
+
+def test_lm_head_sharded_equals_direct_and_names_the_owner_of_the_last_token():
+    from cascade_inputs import make_head_weights
+    cfg = TINY_LLAMA
+    V = 53
+    head = make_head_weights(cfg, V)
+    head["w_vocab"] = head["w_vocab"] * 8.0
+    h = make_hidden(cfg)[0]
+    direct = orc.lm_head_direct(h, head, cfg)
+    for kind, beta, seed in [("perm", 4, 1), ("round_robin", 6, 2), ("ragged", 5, 3), ("contiguous", 3, 4)]:
+        a = make_assignment(kind, cfg.seq_len, beta, seed)
+        assert rel_err(orc.lm_head_sharded(h, head, cfg, a, beta), direct) < 1e-13  # same rows, row-wise arithmetic
+        tok, shard, row = orc.next_token(h, head, cfg, a, beta)
+        assert shard == a[cfg.seq_len - 1] and tok == int(np.argmax(direct[-1])) and rel_err(row, direct[-1]) < 1e-13
+    # custom positions: the last token is the one with the largest position, wherever it is stored
+    pos = np.random.default_rng(5).permutation(cfg.seq_len) * 3 + 2
+    a = make_assignment("perm", cfg.seq_len, 4, 6)
+    tok, shard, row = orc.next_token(h, head, cfg, a, 4, positions=pos)
+    t_last = int(np.argmax(pos))
+    assert shard == a[t_last] and tok == int(np.argmax(direct[t_last]))
+    # ties go to the lowest index
+    head2 = dict(head)
+    head2["w_vocab"] = np.concatenate([head["w_vocab"][:5], head["w_vocab"][:5]])
+    tok2, _, row2 = orc.next_token(h, head2, cfg, a, 4)
+    assert tok2 < 5 and row2[tok2] == row2[tok2 + 5]
+
+
+def test_lm_head_identity_projection_returns_the_normalised_row():
+    """W_vocab = I: the logits are the closing norm's output, whose rows have unit mean square before the gain."""
+    from cascade_inputs import make_head_weights
+    cfg = TINY_LLAMA
+    head = make_head_weights(cfg, cfg.d_model)
+    head["w_vocab"] = np.eye(cfg.d_model)
+    h = make_hidden(cfg)[0]
+    z = orc.lm_head_direct(h, head, cfg) / head["norm_g"].astype(np.float64)
+    assert np.abs((z ** 2).mean(axis=1) - 1).max() < 1e-4
