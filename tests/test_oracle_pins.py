@@ -711,7 +711,7 @@ def test_lm_head_sharded_equals_direct_and_names_the_owner_of_the_last_token():
     head["w_vocab"] = head["w_vocab"] * 8.0
     h = make_hidden(cfg)[0]
     direct = orc.lm_head_direct(h, head, cfg)
-    for kind, beta, seed in [("perm", 4, 1), ("round_robin", 6, 2), ("ragged", 5, 3), ("contiguous", 3, 4)]:
+    for kind, beta, seed in [("perm", 4, 1), ("roundrobin", 6, 2), ("ragged", 5, 3), ("contiguous", 3, 4)]:
         a = make_assignment(kind, cfg.seq_len, beta, seed)
         assert rel_err(orc.lm_head_sharded(h, head, cfg, a, beta), direct) < 1e-13  # same rows, row-wise arithmetic
         tok, shard, row = orc.next_token(h, head, cfg, a, beta)
