@@ -722,11 +722,14 @@ def test_lm_head_sharded_equals_direct_and_names_the_owner_of_the_last_token():
     tok, shard, row = orc.next_token(h, head, cfg, a, 4, positions=pos)
     t_last = int(np.argmax(pos))
     assert shard == a[t_last] and tok == int(np.argmax(direct[t_last]))
-    # ties go to the lowest index
+    # ties go to the lowest index (rows 2 and 7 equal and largest, exactly: one-hot rows pick a coordinate)
     head2 = dict(head)
-    head2["w_vocab"] = np.concatenate([head["w_vocab"][:5], head["w_vocab"][:5]])
-    tok2, _, row2 = orc.next_token(h, head2, cfg, a, 4)
-    assert tok2 < 5 and row2[tok2] == row2[tok2 + 5]
+    w2 = np.zeros((9, cfg.d_model))
+    w2[2, 0] = w2[7, 0] = 1.0
+    head2["w_vocab"] = w2
+    h2 = np.abs(h) + 0.5                                  # coordinate 0 of the normalised row is positive
+    tok2, _, row2 = orc.next_token(h2, head2, cfg, a, 4)
+    assert tok2 == 2 and row2[2] == row2[7] > 0
 
 
 def test_lm_head_identity_projection_returns_the_normalised_row():
