@@ -264,6 +264,35 @@ def run_variants(cas, cfg, steps):
         step()
     sec = time_steps(step, max(3, steps // 2))
     out["stack_of_4_layers"] = {"workload": cfg.name, "ms_per_layer": sec * 1e3 / L, "tokens_per_s": cfg.batch * cfg.seq_len / sec}
+    del ws, tensors, wl, h_out
+
+    # LM head on the sharded rows of the headline workload (Llama-3 vocabulary size): logits of every token
+    # (one shard GEMM over the packed rows, MFMA-bound) and of the last token only (reads W_vocab once: HBM-bound)
+    V = 128256
+    D = cfg.d_model
+    g = torch.Generator(device="cuda").manual_seed(config_seed(cfg))
+    w_vocab = (torch.randn(V, D, device="cuda", generator=g) * cfg.sigma).to(h.dtype)
+    gain = torch.ones(D, device="cuda", dtype=h.dtype)
+    nk = {"layernorm": cas.NORM_LAYERNORM, "rmsnorm": cas.NORM_RMSNORM}[cfg.norm]
+    dt = cas.BF16 if cfg.dtype == "bf16" else cas.F32
+    for rows, name in ((cas.LM_ALL_ROWS, "lm_head_all_rows"), (cas.LM_LAST_ROW, "lm_head_last_row")):
+        d = cas.LmHeadDesc(dt, D, V, nk, cfg.eps, rows, cas.ROWS_ORIGINAL, cas.ROWS_ORIGINAL)
+        n_rows = cfg.batch * cfg.seq_len if rows == cas.LM_ALL_ROWS else cfg.batch
+        logits = torch.empty(n_rows, V, device="cuda", dtype=h.dtype)
+        tok = torch.empty(n_rows, device="cuda", dtype=torch.int32)
+        ws = cas.new_workspace(cas.cascade_lm_head_workspace_bytes(plan, d))
+
+        def step():
+            cas.cascade_lm_head(plan, d, h, gain, None, w_vocab, logits, ws)
+            cas.cascade_greedy_token(logits, tok)
+        for _ in range(2):
+            step()
+        sec = time_steps(step, max(3, steps // 5))
+        flops = 2.0 * n_rows * D * V
+        bytes_w = V * D * w_vocab.element_size()
+        out[name] = {"vocab": V, "rows": n_rows, "ms": sec * 1e3, "tflops": flops / sec / 1e12,
+                     "weight_GB_per_s": bytes_w / sec / 1e9}
+        del logits, ws
     return out
 
 

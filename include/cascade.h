@@ -295,6 +295,48 @@ CASCADE_API int32_t cascade_layer_stack_forward(const cascade_plan *plan, const 
                                     const void *h_in, void *h_out,
                                     void *workspace, size_t workspace_bytes, void *stream);
 
+/* ---- LM head on sharded rows -------------------------------------------------
+ * After the last layer every CompNode applies the LM head to its own hidden rows
+ * and holds R_i-sharded logits; the CompNode that holds the last token turns its
+ * logits row into the next token (Single Layer Pipeline subsection, the
+ * paragraph after Algorithm 1).  logits = W_vocab . norm_f(h): the model's
+ * closing normalisation, then the vocabulary projection as one shard GEMM over
+ * the packed rows (weights shared by all shards).
+ *
+ * rows = CASCADE_LM_ALL_ROWS: logits [B, N, vocab] for every token, h_in rows in
+ *   in_rows order, logits rows in out_rows order (CASCADE_ROWS_*).
+ * rows = CASCADE_LM_LAST_ROW: logits [B, vocab] of the token with the largest
+ *   position in each sequence (lowest index among equal positions); out_rows is
+ *   ignored.
+ * h_in [B, N, D], norm_gain [D], norm_bias [D] or NULL, w_vocab [vocab, D],
+ * logits in desc->dtype: device pointers, borrowed.  workspace: device,
+ * 256-byte aligned, cascade_lm_head_workspace_bytes (the normalised rows).
+ * vocab % 4 == 0.  Errors: EINVAL, ESHAPE, EUNSUPPORTED, EWORKSPACE, EHIP.       */
+#define CASCADE_LM_ALL_ROWS 0
+#define CASCADE_LM_LAST_ROW 1
+
+typedef struct cascade_lm_head_desc {
+    int32_t dtype;
+    int32_t d_model, vocab;
+    int32_t norm_kind;    /* CASCADE_NORM_LAYERNORM | CASCADE_NORM_RMSNORM            */
+    float   norm_eps;
+    int32_t rows;         /* CASCADE_LM_ALL_ROWS | CASCADE_LM_LAST_ROW                */
+    int32_t in_rows;      /* row order of h_in: CASCADE_ROWS_*                        */
+    int32_t out_rows;     /* row order of the logits (ALL_ROWS): CASCADE_ROWS_*       */
+} cascade_lm_head_desc;
+
+CASCADE_API size_t cascade_lm_head_workspace_bytes(const cascade_plan *plan, const cascade_lm_head_desc *desc);
+CASCADE_API int32_t cascade_lm_head(const cascade_plan *plan, const cascade_lm_head_desc *desc,
+                        const void *h_in, const void *norm_gain, const void *norm_bias,
+                        const void *w_vocab, void *logits,
+                        void *workspace, size_t workspace_bytes, void *stream);
+
+/* Greedy choice: token_out[r] (device int32 [rows]) = lowest index of the
+ * largest of logits[r, 0 .. vocab) (device, [rows, vocab] in dtype).  NaNs never
+ * win; a row of NaNs gives 0.  Errors: EINVAL, EUNSUPPORTED, EHIP.               */
+CASCADE_API int32_t cascade_greedy_token(const void *logits, int32_t dtype, int32_t rows, int32_t vocab,
+                             int32_t *token_out, void *stream);
+
 /* The same computation with stage boundaries marked for measurement: HIP event
  * stage_events[i] (hipEvent_t, created by the caller, NULL entries skipped) is
  * recorded on the stream at boundary i.  Boundaries (CASCADE_N_STAGE_EVENTS):

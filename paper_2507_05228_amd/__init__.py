@@ -31,6 +31,7 @@ EXPORTS = ["cascade_plan_create", "cascade_plan_create_rs", "cascade_plan_maps",
            "cascade_partial_attn", "cascade_lse_merge", "cascade_layer_workspace_bytes",
            "cascade_layer_forward", "cascade_layer_forward_staged", "cascade_layer_partials",
            "cascade_layer_stack_workspace_bytes", "cascade_layer_stack_forward",
+           "cascade_lm_head_workspace_bytes", "cascade_lm_head", "cascade_greedy_token",
            "cascade_decode_partial_attn", "cascade_mfma_ceiling"]
 N_STAGE_EVENTS = 10
 STAGE_NAMES = ["gather_norm1", "qkv_gemm", "rope", "attention", "lse_merge", "o_proj", "norm2", "ffn_up", "ffn_down"]
@@ -62,6 +63,13 @@ class LayerDesc(C.Structure):
                 ("act", C.c_int32), ("rope", C.c_int32), ("rope_theta", C.c_float), ("scale", C.c_float),
                 ("attn_mode", C.c_int32), ("io_rows", C.c_int32), ("norm_placement", C.c_int32)]
 
+
+class LmHeadDesc(C.Structure):
+    _fields_ = [("dtype", C.c_int32), ("d_model", C.c_int32), ("vocab", C.c_int32), ("norm_kind", C.c_int32),
+                ("norm_eps", C.c_float), ("rows", C.c_int32), ("in_rows", C.c_int32), ("out_rows", C.c_int32)]
+
+
+LM_ALL_ROWS, LM_LAST_ROW = 0, 1
 
 _WEIGHT_FIELDS = ["wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down", "bq", "bk", "bv", "bo", "b_up", "b_down",
                   "norm1_g", "norm1_b", "norm2_g", "norm2_b"]
@@ -129,6 +137,12 @@ def load_library():
     lib.cascade_layer_stack_workspace_bytes.restype = C.c_size_t
     lib.cascade_layer_stack_forward.argtypes = [VP, P(LayerDesc), P(LayerWeights), I32, VP, VP, VP, C.c_size_t, VP]
     lib.cascade_layer_stack_forward.restype = I32
+    lib.cascade_lm_head_workspace_bytes.argtypes = [VP, P(LmHeadDesc)]
+    lib.cascade_lm_head_workspace_bytes.restype = C.c_size_t
+    lib.cascade_lm_head.argtypes = [VP, P(LmHeadDesc), VP, VP, VP, VP, VP, VP, C.c_size_t, VP]
+    lib.cascade_lm_head.restype = I32
+    lib.cascade_greedy_token.argtypes = [VP, I32, I32, I32, VP, VP]
+    lib.cascade_greedy_token.restype = I32
     lib.cascade_decode_partial_attn.argtypes = [P(AttnDesc), I32, I32, I32, VP, VP, VP, VP, VP, VP, VP, VP]
     lib.cascade_decode_partial_attn.restype = I32
     lib.cascade_mfma_ceiling.argtypes = [I32, I32, P(C.c_float), VP]
@@ -379,6 +393,25 @@ def cascade_layer_stack_forward(plan, desc, weights_list, h_in, h_out, workspace
     st = lib.cascade_layer_stack_forward(plan.handle, C.byref(desc), arr, len(weights_list), _ptr(h_in), _ptr(h_out),
                                          _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream))
     _check(st, "cascade_layer_stack_forward")
+
+
+def cascade_lm_head_workspace_bytes(plan, desc):
+    return load_library().cascade_lm_head_workspace_bytes(plan.handle, C.byref(desc))
+
+
+def cascade_lm_head(plan, desc, h_in, norm_gain, norm_bias, w_vocab, logits, workspace, stream=None):
+    lib = load_library()
+    st = lib.cascade_lm_head(plan.handle, C.byref(desc), _ptr(h_in), _ptr(norm_gain), _ptr(norm_bias), _ptr(w_vocab),
+                             _ptr(logits), _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream))
+    _check(st, "cascade_lm_head")
+
+
+def cascade_greedy_token(logits, token_out, stream=None):
+    """logits [rows, vocab] (bf16 or fp32, contiguous), token_out int32 [rows]."""
+    lib = load_library()
+    st = lib.cascade_greedy_token(_ptr(logits), _dtype_code(logits), logits.shape[0], logits.shape[1], _ptr(token_out),
+                                  _stream(stream))
+    _check(st, "cascade_greedy_token")
 
 
 def cascade_layer_partials(plan, desc, workspace, batch, n_heads, head_dim):

@@ -378,6 +378,80 @@ extern "C" int32_t cascade_layer_stack_forward(const cascade_plan *plan, const c
     return CASCADE_OK;
 }
 
+// ---------------------------------------------------------------------------- LM head on sharded rows
+static int32_t check_lm_desc(const cascade_plan *plan, const cascade_lm_head_desc *d) {
+    if (!plan || !d) return CASCADE_EINVAL;
+    if (!dtype_ok(d->dtype)) return CASCADE_EUNSUPPORTED;
+    if (d->d_model <= 0 || d->vocab <= 0) return CASCADE_EINVAL;
+    if (d->vocab % 4) return CASCADE_EUNSUPPORTED;
+    if (d->norm_kind != CASCADE_NORM_LAYERNORM && d->norm_kind != CASCADE_NORM_RMSNORM) return CASCADE_EINVAL;
+    if (d->rows != CASCADE_LM_ALL_ROWS && d->rows != CASCADE_LM_LAST_ROW) return CASCADE_EINVAL;
+    if (!rows_ok(d->in_rows) || (d->rows == CASCADE_LM_ALL_ROWS && !rows_ok(d->out_rows))) return CASCADE_EINVAL;
+    return CASCADE_OK;
+}
+
+static int64_t lm_rows(const cascade_plan *plan, const cascade_lm_head_desc *d) {
+    return d->rows == CASCADE_LM_ALL_ROWS ? (int64_t)plan->batch * plan->seq_len : plan->batch;
+}
+
+extern "C" size_t cascade_lm_head_workspace_bytes(const cascade_plan *plan, const cascade_lm_head_desc *d) {
+    if (check_lm_desc(plan, d) != CASCADE_OK) return 0;
+    return align_up((size_t)lm_rows(plan, d) * d->d_model * esize(d->dtype), 256);
+}
+
+extern "C" int32_t cascade_lm_head(const cascade_plan *plan, const cascade_lm_head_desc *d, const void *h_in,
+                                   const void *norm_gain, const void *norm_bias, const void *w_vocab, void *logits,
+                                   void *workspace, size_t workspace_bytes, void *stream) {
+    int32_t st = check_lm_desc(plan, d);
+    if (st != CASCADE_OK) return st;
+    if (!h_in || !norm_gain || !w_vocab || !logits) return CASCADE_EINVAL;
+    const size_t need = cascade_lm_head_workspace_bytes(plan, d);
+    if (!workspace || workspace_bytes < need || (uintptr_t)workspace % 256) return CASCADE_EWORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    const int32_t M = (int32_t)lm_rows(plan, d), D = d->d_model, V = d->vocab;
+    const bool all = d->rows == CASCADE_LM_ALL_ROWS;
+
+    // closing norm: rows gathered into packed order (ALL) or the last token's row of every sequence
+    NormArgs n = {};
+    n.dtype = d->dtype; n.rows = M; n.D = D; n.kind = d->norm_kind; n.eps = d->norm_eps;
+    n.x = h_in; n.gain = norm_gain; n.bias = norm_bias; n.y = workspace;
+    if (all) {
+        n.xmap = rowmap_for(plan, d->in_rows);
+    } else {
+        n.xmap.map = plan->last_rows_d + (d->in_rows == CASCADE_ROWS_ORIGINAL ? plan->batch : 0);
+        n.xmap.seq_len = plan->batch;
+    }
+    n.ymap.map = nullptr; n.ymap.seq_len = n.xmap.seq_len;
+    st = launch_norm(n, s);
+    if (st != CASCADE_OK) return st;
+
+    // vocabulary projection; the weight is cut into at most three row ranges so that each stays below the
+    // 2 GiB a buffer descriptor can address
+    GemmArgs g = {};
+    g.dtype = d->dtype; g.M = M; g.N = V; g.K = D;
+    g.X = workspace; g.Y = logits;
+    g.ldx = D; g.ldy = V; g.ldres = V;
+    g.xmap.map = nullptr; g.xmap.seq_len = 1;
+    g.ymap = all ? rowmap_for(plan, d->out_rows) : g.xmap;
+    g.rmap = g.xmap;
+    const int64_t max_rows = ((int64_t)0x7FFF0000 / ((int64_t)D * esize(d->dtype))) & ~(int64_t)255;
+    if (max_rows <= 0 || (int64_t)V > 3 * max_rows) return CASCADE_EUNSUPPORTED;
+    int32_t col = 0;
+    for (int i = 0; i < 3; ++i) {
+        g.W[i] = (const char *)w_vocab + (size_t)col * D * esize(d->dtype);
+        col = (int32_t)std::min<int64_t>(V, col + max_rows);
+        g.seg_end[i] = col;
+    }
+    return run_gemm(g, s);
+}
+
+extern "C" int32_t cascade_greedy_token(const void *logits, int32_t dtype, int32_t rows, int32_t vocab,
+                                        int32_t *token_out, void *stream) {
+    if (!logits || !token_out || rows < 0 || vocab <= 0) return CASCADE_EINVAL;
+    if (!dtype_ok(dtype)) return CASCADE_EUNSUPPORTED;
+    return launch_argmax_rows(dtype, logits, vocab, rows, vocab, token_out, (hipStream_t)stream);
+}
+
 extern "C" int32_t cascade_layer_forward(const cascade_plan *plan, const cascade_layer_desc *d,
                                          const cascade_layer_weights *w, const void *h_in, void *h_out,
                                          void *workspace, size_t workspace_bytes, void *stream) {

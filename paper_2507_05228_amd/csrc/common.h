@@ -39,6 +39,8 @@ struct cascade_plan {
     // device copies
     int32_t *perm_d, *inv_perm_d, *offsets_d, *pos_packed_d;
     int32_t max_abs_pos;        // largest |position|
+    int32_t last_token;         // token with the largest position (lowest index among equals)
+    int32_t *last_rows_d;       // [2][batch]: row of that token in every sequence, packed order then original order
     CascadeTileList tiles[4];   // granules 32, 64, 128, 256
     // Key/value partition S when it differs from the row partition R (Section 5.1; the m-split of
     // Section 6.4): a plan of its own over the same tokens, plus the map from its packed rows to
@@ -110,6 +112,9 @@ struct NormArgs {
     RowMap ymap;                     // scatter on the write
 };
 int32_t launch_norm(const NormArgs &a, hipStream_t s);
+// token_out[r] = lowest index of the largest element of row r of x [rows, ld] (first `vocab` columns)
+int32_t launch_argmax_rows(int32_t dtype, const void *x, int64_t ld, int32_t rows, int32_t vocab, int32_t *token_out,
+                           hipStream_t s);
 
 struct RopeArgs {
     int32_t dtype, rows, seq_len;    // rows = B * N packed rows

@@ -24,6 +24,7 @@ static void free_plan(cascade_plan *p) {
     if (p->inv_perm_d) (void)hipFree(p->inv_perm_d);
     if (p->offsets_d) (void)hipFree(p->offsets_d);
     if (p->pos_packed_d) (void)hipFree(p->pos_packed_d);
+    if (p->last_rows_d) (void)hipFree(p->last_rows_d);
     for (auto &t : p->tiles) {
         if (t.dev) (void)hipFree(t.dev);
         if (t.dev_by_pmin) (void)hipFree(t.dev_by_pmin);
@@ -130,7 +131,19 @@ static int32_t build_plan(cascade_plan **out, int32_t batch, int32_t seq_len, in
         p->max_abs_pos = (int32_t)std::min<int64_t>(std::max<int64_t>(p->max_abs_pos, ap), INT32_MAX);
     }
 
+    for (int t = 1; t < seq_len; ++t) {
+        const int32_t pt = positions_host ? positions_host[t] : t;
+        const int32_t pl = positions_host ? positions_host[p->last_token] : p->last_token;
+        if (pt > pl) p->last_token = t;
+    }
+    std::vector<int32_t> last_rows(2 * (size_t)batch);
+    for (int b = 0; b < batch; ++b) {
+        last_rows[b] = b * seq_len + p->inv_perm_h[p->last_token];
+        last_rows[batch + b] = b * seq_len + p->last_token;
+    }
+
     hipError_t e = hipGetDevice(&p->device);
+    if (e == hipSuccess) e = to_device(&p->last_rows_d, last_rows.data(), 2 * batch);
     if (e == hipSuccess) e = to_device(&p->perm_d, p->perm_h, seq_len);
     if (e == hipSuccess) e = to_device(&p->inv_perm_d, p->inv_perm_h, seq_len);
     if (e == hipSuccess) e = to_device(&p->offsets_d, p->offsets_h, n_shards + 1);

@@ -2,6 +2,7 @@
 // layer normalization if necessary"), rotary embedding at original token positions
 // (the rotary step of Algorithm 2).  The gather into packed order is the row map of the norm's read; the
 // scatter back is the row map of the last shard GEMM's store.
+#include <climits>
 #include <cmath>
 #include "common.h"
 #include "device_utils.h"
@@ -121,6 +122,47 @@ static int32_t launch_norm_t(const NormArgs &a, hipStream_t s) {
 int32_t launch_norm(const NormArgs &a, hipStream_t s) {
     if (a.rows == 0) return CASCADE_OK;
     return a.dtype == CASCADE_BF16 ? launch_norm_t<bf16_t>(a, s) : launch_norm_t<float>(a, s);
+}
+
+// ---------------------------------------------------------------------------- greedy token
+// Lowest index of the largest logit of a row (the CompNode holding the last token turns its logits
+// into the next token).  One 1024-thread block per row; a thread walks ascending indices and keeps
+// the first maximum it meets, the reductions prefer the lower index among equal values.  NaNs never
+// win a comparison; a row of NaNs gives 0.
+template <typename T>
+__global__ __launch_bounds__(1024) void argmax_rows_kernel(const T *__restrict__ x, int64_t ld, int vocab,
+                                                           int32_t *__restrict__ out) {
+    __shared__ float sv[16];
+    __shared__ int si[16];
+    const T *row = x + (int64_t)blockIdx.x * ld;
+    float best = -INFINITY;
+    int idx = INT32_MAX;
+    for (int i = threadIdx.x; i < vocab; i += 1024) {
+        const float v = Elem<T>::load(row + i);
+        if (v > best || (v == best && i < idx)) { best = v; idx = i; }
+    }
+    auto take = [&](float ov, int oi) {
+        if (ov > best || (ov == best && oi < idx)) { best = ov; idx = oi; }
+    };
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) take(__shfl_xor(best, o, WAVE), __shfl_xor(idx, o, WAVE));
+    if ((threadIdx.x & 63) == 0) { sv[threadIdx.x >> 6] = best; si[threadIdx.x >> 6] = idx; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < 16; ++w) take(sv[w], si[w]);
+        out[blockIdx.x] = idx == INT32_MAX ? 0 : idx;
+    }
+}
+
+int32_t launch_argmax_rows(int32_t dtype, const void *x, int64_t ld, int32_t rows, int32_t vocab, int32_t *token_out,
+                           hipStream_t s) {
+    if (rows == 0) return CASCADE_OK;
+    if (dtype == CASCADE_BF16)
+        hipLaunchKernelGGL(argmax_rows_kernel<bf16_t>, dim3(rows), dim3(1024), 0, s, (const bf16_t *)x, ld, vocab, token_out);
+    else
+        hipLaunchKernelGGL(argmax_rows_kernel<float>, dim3(rows), dim3(1024), 0, s, (const float *)x, ld, vocab, token_out);
+    CASCADE_HIP_TRY(hipGetLastError());
+    return CASCADE_OK;
 }
 
 // ---------------------------------------------------------------------------- rotary embedding

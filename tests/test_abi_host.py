@@ -58,6 +58,7 @@ def test_struct_layouts_match_the_header(tmp_path):
         'printf("%zu %zu %zu\\n", offsetof(cascade_attn_desc, q_stride_b), offsetof(cascade_layer_desc, io_rows),'
         " offsetof(cascade_layer_weights, norm2_b));\n"
         'printf("%zu\\n", offsetof(cascade_gemm_desc, rope_theta));\n'
+        'printf("%zu %zu\\n", sizeof(cascade_lm_head_desc), offsetof(cascade_lm_head_desc, out_rows));\n'
         "return 0;}\n")
     exe = tmp_path / "layout"
     subprocess.run(["gcc", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)], check=True)
@@ -65,7 +66,7 @@ def test_struct_layouts_match_the_header(tmp_path):
     got = [int(t) for t in out]
     want = [C.sizeof(cas.GemmDesc), C.sizeof(cas.AttnDesc), C.sizeof(cas.LayerDesc), C.sizeof(cas.LayerWeights),
             cas.AttnDesc.q_stride_b.offset, cas.LayerDesc.io_rows.offset, cas.LayerWeights.norm2_b.offset,
-            cas.GemmDesc.rope_theta.offset]
+            cas.GemmDesc.rope_theta.offset, C.sizeof(cas.LmHeadDesc), cas.LmHeadDesc.out_rows.offset]
     assert got == want
 
 

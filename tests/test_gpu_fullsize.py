@@ -124,3 +124,42 @@ def test_full_config_materialised_partials_sampled(cas, key):
             ut = e_r[0][:, None] * u_r[0]
             assert np.abs(u_g - ut).max() / max(np.abs(ut).max(), 1e-300) < tol
         print(f"[{key}] triple (h={hh}, j={j}, k={kk}) ok", flush=True)
+
+
+def test_lm_head_at_the_headline_shape_sampled_rows(cas):
+    """Llama-3-sized vocabulary on the C3 rows, in the launch configuration bench.py times: sampled logits rows
+    against the oracle, the greedy tokens against numpy on the same logits, and the last-row mode."""
+    import torch
+    from cascade_inputs import make_head_weights
+    cfg = CONFIGS["C3"]
+    V = 128256
+    seed = config_seed(cfg)
+    a = make_assignment(cfg.assignment, cfg.seq_len, cfg.n_shards, seed)
+    h = make_hidden(cfg)
+    head = make_head_weights(cfg, V)
+    print("[lm head] inputs ready", flush=True)
+    plan = cas.cascade_plan_create(cfg.batch, cfg.seq_len, cfg.n_shards, a)
+    hd = cas.to_device(h, cfg.dtype)
+    g = cas.to_device(head["norm_g"], cfg.dtype)
+    w = cas.to_device(head["w_vocab"], cfg.dtype)
+    T = cfg.batch * cfg.seq_len
+    desc = cas.LmHeadDesc(cas.BF16, cfg.d_model, V, cas.NORM_RMSNORM, cfg.eps, cas.LM_ALL_ROWS, cas.ROWS_ORIGINAL,
+                          cas.ROWS_ORIGINAL)
+    ws = cas.new_workspace(cas.cascade_lm_head_workspace_bytes(plan, desc))
+    logits = torch.empty(T, V, dtype=hd.dtype, device="cuda")
+    tok = torch.empty(T, dtype=torch.int32, device="cuda")
+    cas.cascade_lm_head(plan, desc, hd, g, None, w, logits, ws)
+    cas.cascade_greedy_token(logits, tok)
+    desc_last = cas.LmHeadDesc(cas.BF16, cfg.d_model, V, cas.NORM_RMSNORM, cfg.eps, cas.LM_LAST_ROW, cas.ROWS_ORIGINAL,
+                               cas.ROWS_ORIGINAL)
+    last = torch.empty(cfg.batch, V, dtype=hd.dtype, device="cuda")
+    cas.cascade_lm_head(plan, desc_last, hd, g, None, w, last, ws)
+    torch.cuda.synchronize()
+    print("[lm head] gpu done", flush=True)
+    rows = np.sort(np.random.default_rng(seed).choice(cfg.seq_len, size=12, replace=False))
+    rows[-1] = cfg.seq_len - 1
+    want = orc.lm_head_direct(h[0][rows], head, cfg)
+    got = logits[torch.from_numpy(rows).cuda()].float().cpu().numpy().astype(np.float64)
+    assert np.abs(got - want).max() / np.abs(want).max() < TOL["bf16"]
+    assert np.array_equal(tok.cpu().numpy(), logits.float().argmax(dim=1).cpu().numpy())
+    assert torch.equal(last[0], logits[cfg.seq_len - 1])          # same rows, same kernels: bit-identical
