@@ -111,6 +111,30 @@ __device__ __forceinline__ void gemm_epilogue(const Gemm2Params &p, f32x4 (&acc)
                 if (c + x < seg_rows) bias_v[cc][x] = (float)bias[c + x];
     }
     const bool act = flags & (CASCADE_EPI_GELU_ERF | CASCADE_EPI_GELU_TANH);
+    // Residual of every row block requested up front (when the registers allow): one memory latency for the
+    // whole epilogue instead of one per row block.
+    constexpr bool RES_AHEAD = TM * 4 * NCH <= 32;
+    bf16x4 rres[RES_AHEAD ? TM : 1][4][NCH];
+    const bool res_ahead = RES_AHEAD && (flags & CASCADE_EPI_RESIDUAL);
+    if (res_ahead) {
+#pragma unroll
+        for (int i = 0; i < (RES_AHEAD ? TM : 1); ++i)
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const int gm = m0 + wm0 + 16 * i + 4 * t + rsel;
+                const bf16_t *rrow = p.residual + map_row(p.rmap, p.seq_len, gm < p.M ? gm : 0) * p.ldres + gcol0;
+#pragma unroll
+                for (int cc = 0; cc < NCH; ++cc) {
+                    const int c = wcol0 + 64 * cc + m4;
+                    rres[i][t][cc] = bf16x4{0, 0, 0, 0};
+                    if (gm < p.M && c + 4 <= seg_rows && 64 * cc + m4 < OW) rres[i][t][cc] = *(const bf16x4 *)(rrow + c);
+                }
+            }
+    }
+    // Two copies of the unrolled loops, chosen once: without the (long) GELU code the plain one stays small
+    // and contiguous in the instruction cache.
+    auto blocks = [&](auto act_tag) {
+    constexpr bool ACT = decltype(act_tag)::value;
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
 #pragma unroll
@@ -140,12 +164,16 @@ __device__ __forceinline__ void gemm_epilogue(const Gemm2Params &p, f32x4 (&acc)
                         const f32x4 up = *(const f32x4 *)(stg + rl * STG_LD + OW + m4);
 #pragma unroll
                         for (int x = 0; x < 4; ++x) v[x] = silu_fast(v[x]) * up[x];
-                    } else if (!SWIGLU && act) {
+                    } else if constexpr (!SWIGLU && ACT) {
 #pragma unroll
                         for (int x = 0; x < 4; ++x) v[x] = apply_act(v[x], flags);
                     }
                     if (c + 4 <= seg_rows) {
-                        if (rrow) {
+                        if (RES_AHEAD && res_ahead) {
+                            const bf16x4 rv = rres[RES_AHEAD ? i : 0][t][cc];
+#pragma unroll
+                            for (int x = 0; x < 4; ++x) v[x] += (float)rv[x];
+                        } else if (rrow) {
                             const bf16x4 rv = *(const bf16x4 *)(rrow + c);
 #pragma unroll
                             for (int x = 0; x < 4; ++x) v[x] += (float)rv[x];
@@ -161,6 +189,9 @@ __device__ __forceinline__ void gemm_epilogue(const Gemm2Params &p, f32x4 (&acc)
         }
         __builtin_amdgcn_wave_barrier();
     }
+    };
+    if (!SWIGLU && act) blocks(std::true_type{});
+    else blocks(std::false_type{});
 }
 
 // Epilogue for accumulators computed transposed (W block as the first MFMA operand): acc[i][j][r]
@@ -190,6 +221,11 @@ __device__ __forceinline__ void gemm_epilogue_tile(const Gemm2Params &p, f32x4 (
     const bf16_t *bias = (!SWIGLU && (flags & CASCADE_EPI_BIAS)) ? p.bias[seg] : nullptr;
     const bool act = flags & (CASCADE_EPI_GELU_ERF | CASCADE_EPI_GELU_TANH);
     const int gcol0 = p.seg_col0[seg];
+    // Two copies of the unrolled loops, chosen once: the plain one (no bias, no activation) stays small and
+    // contiguous in the instruction cache; the GELU code is long and would otherwise sit between every pair
+    // of its stores.
+    auto to_lds = [&](auto general_tag) {
+    constexpr bool GENERAL = decltype(general_tag)::value;
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
         const int row = wm0 + 16 * i + l16, gm = m0 + row;
@@ -203,7 +239,7 @@ __device__ __forceinline__ void gemm_epilogue_tile(const Gemm2Params &p, f32x4 (
             if (SWIGLU) {
 #pragma unroll
                 for (int x = 0; x < 4; ++x) v[x] = silu_fast(v[x]) * acc[i][j + TNO][x];
-            } else {
+            } else if constexpr (GENERAL) {
                 if (bias)
 #pragma unroll
                     for (int x = 0; x < 4; ++x)
@@ -227,6 +263,9 @@ __device__ __forceinline__ void gemm_epilogue_tile(const Gemm2Params &p, f32x4 (
             *(bf16x4 *)(smem + row * PITCH + tc * 2) = o;
         }
     }
+    };
+    if (!SWIGLU && (bias || act)) to_lds(std::true_type{});
+    else to_lds(std::false_type{});
     __syncthreads();
     constexpr int CPRO = BN_OUT / 8;                       // 16-byte pieces per tile row
     static_assert(BN_OUT % 8 == 0, "whole pieces");
