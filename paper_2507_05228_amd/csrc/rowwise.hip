@@ -137,9 +137,24 @@ __global__ __launch_bounds__(1024) void argmax_rows_kernel(const T *__restrict__
     const T *row = x + (int64_t)blockIdx.x * ld;
     float best = -INFINITY;
     int idx = INT32_MAX;
-    for (int i = threadIdx.x; i < vocab; i += 1024) {
-        const float v = Elem<T>::load(row + i);
-        if (v > best || (v == best && i < idx)) { best = v; idx = i; }
+    constexpr int VEC = 16 / sizeof(T);
+    if (vocab % VEC == 0 && (((uintptr_t)x | (uintptr_t)(ld * sizeof(T))) % 16) == 0) {
+        typedef T vec_t __attribute__((ext_vector_type(VEC)));     // 16-byte pieces, several in flight per thread
+        const int nvec = vocab / VEC;
+#pragma unroll 4
+        for (int c = threadIdx.x; c < nvec; c += 1024) {
+            const vec_t pv = *(const vec_t *)(row + (int64_t)c * VEC);
+#pragma unroll
+            for (int k = 0; k < VEC; ++k) {
+                const float v = (float)pv[k];
+                if (v > best) { best = v; idx = c * VEC + k; }      // ascending indices: the first maximum stays
+            }
+        }
+    } else {
+        for (int i = threadIdx.x; i < vocab; i += 1024) {
+            const float v = Elem<T>::load(row + i);
+            if (v > best) { best = v; idx = i; }
+        }
     }
     auto take = [&](float ov, int oi) {
         if (ov > best || (ov == best && oi < idx)) { best = ov; idx = oi; }
