@@ -5,21 +5,27 @@
 // Shape of the kernel (chosen from measurements on MI355X: 16x16x32 bf16 MFMA reaches ~98 % of the
 // chip's matrix peak with two wavefronts per SIMD, ~89 % with one; LDS delivers ~235 B/clk/CU on
 // conflict-free 16-byte reads):
-//  * 8 wavefronts per workgroup (2 per SIMD, <= 256 registers each), 16x16x32 MFMA blocks.
+//  * 8 wavefronts per workgroup (2 per SIMD, <= 256 registers each) or 4 (one per SIMD, up to 512
+//    registers: 128-row wavefront tiles whose accumulators live in the accumulation registers; every
+//    memory operation hand-placed between two MFMAs), 16x16x32 MFMA blocks.
 //  * K walked in steps of BK (32 or 64).  Tiles go from HBM/L2 straight into LDS with buffer loads
 //    that write LDS directly (no register staging, out-of-range rows read as zero), NST stages deep:
-//    the loads of steps t+1 .. t+NST-1 are in flight while step t is multiplied, which is what hides
-//    the ~1.5 us load latency (with two stages the loop ran at the latency, not at the MFMA rate).
-//    The wait for "step t has landed" is s_waitcnt vmcnt(loads of the younger steps), issued
-//    together with the workgroup barrier as inline assembly: a compiler-generated barrier would
-//    wait for vmcnt(0) and drain the pipeline.
+//    the loads of steps t+1 .. t+NST-1 are in flight while step t is multiplied.  The wait for "step
+//    t has landed" is s_waitcnt vmcnt(loads of the younger steps), issued together with the
+//    workgroup barrier as inline assembly: a compiler-generated barrier would wait for vmcnt(0) and
+//    drain the pipeline.
 //  * LDS rows are BK bf16 without padding; the 16-byte chunk c of tile row r is stored at slot
 //    c ^ ((r >> 1) & 7) (128-byte rows) or c ^ ((r >> 2) & 3) (64-byte rows), which makes both the
 //    direct-to-LDS writes (1 KiB contiguous per wavefront instruction) and the MFMA operand reads
 //    (16 rows x same chunk) bank-conflict free.
-//  * Epilogue through LDS: each wavefront transposes 16 accumulator rows at a time so that a lane
-//    ends up with 4 consecutive columns (and the 4 columns 64 further on): stores and residual
-//    reads are 128-byte runs, and the two halves of a SwiGLU pair live in one lane.
+//  * Epilogue through LDS.  8 wavefronts: each wavefront transposes 16 accumulator rows at a time so
+//    that a lane ends up with 4 consecutive columns (and the 4 columns 64 further on): stores and
+//    residual reads are 128-byte runs, and the two halves of a SwiGLU pair live in one lane.
+//    4 wavefronts: accumulators are computed transposed (a lane owns 4 consecutive columns already),
+//    the bf16 tile of the whole workgroup is laid out in LDS once and stored in 16-byte pieces.
+//  * The machine is power-limited under this load (the clock falls from 2.4 to 1.7-2.0 GHz as the
+//    matrix pipes fill up), so what counts is energy per flop as much as issue slots: fewer LDS bytes
+//    and fewer instructions per MFMA, which is what the 4-wavefront schedule buys.
 #include <cstdlib>
 #include <type_traits>
 #include "common.h"
