@@ -814,9 +814,21 @@ int32_t launch_gemm_bf16_v2(const GemmArgs &a, hipStream_t s) {
         return launch_cfg2<256, 256, 2, 2, 64, 2, true, false>(a, s);
     }
     if (n_tiles(256) >= 160) {
-        if (c192 < c256 && c192 <= c224) return launch_cfg2<256, 192, 4, 2, 64, 2, false, false>(a, s);
-        if (c224 < c256) return launch_cfg2<256, 224, 4, 2, 64, 2, false, false>(a, s);
-        return launch_cfg2<256, 256, 4, 2, 64, 2, false, false>(a, s);   // 256 accumulators leave the one-wavefront schedule no room
+        // The one-wavefront-per-SIMD schedule exists for the 192- and 224-column tiles (256 accumulator
+        // registers per lane leave it no room at 256 columns).  It wins when a CU works through several
+        // tiles; in a single round its faster loop is paid back in the epilogue, where all workgroups store
+        // at the same time.  So: the narrowest cost, ties to the narrower tile when that brings it in.
+        const bool solo192 = n_tiles(192) > cus, solo224 = n_tiles(224) > cus;
+        const int64_t best = std::min(c192, std::min(c224, c256));
+        if (c192 == best && (solo192 || c192 < c224))
+            return solo192 ? launch_cfg2<256, 192, 2, 2, 64, 2, false, false>(a, s)
+                           : launch_cfg2<256, 192, 4, 2, 64, 2, false, false>(a, s);
+        if (c224 == best && (solo224 || c224 < c256))
+            return solo224 ? launch_cfg2<256, 224, 2, 2, 64, 2, false, false>(a, s)
+                           : launch_cfg2<256, 224, 4, 2, 64, 2, false, false>(a, s);
+        if (c192 == best) return launch_cfg2<256, 192, 4, 2, 64, 2, false, false>(a, s);
+        if (c224 == best) return launch_cfg2<256, 224, 4, 2, 64, 2, false, false>(a, s);
+        return launch_cfg2<256, 256, 4, 2, 64, 2, false, false>(a, s);   // 8 wavefronts
     }
     return launch_cfg2<256, 128, 4, 2, 64, 3, false, true>(a, s);
 }

@@ -135,6 +135,44 @@ def test_shard_gemm_swiglu_and_tanh(cas, dtype):
     assert rel_err(host(Y), orc.gelu_tanh(orc.linear(x64, wg.astype(np.float64)))) < TOL[dtype]
 
 
+# One shape per tile variant of the bf16 MFMA kernels (8 wavefronts at 192 / 224 / 256 columns, one wavefront per
+# SIMD at 192 / 224 and for SwiGLU at 224 / 256, the 256x128 ping-pong kernel), chosen with the launcher's own cost
+# rule on 256 CUs; ragged M and N, bias + GELU or residual, every output element against the oracle.
+@pytest.mark.parametrize("M,N,swiglu", [(700, 1000, False), (700, 1000, True), (700, 9600, True), (700, 13728, False),
+                                        (1000, 12352, False), (1000, 14416, False), (1300, 10804, False),
+                                        (2000, 12352, False)])
+@pytest.mark.parametrize("epi", ["plain", "bias_gelu", "residual"])
+def test_shard_gemm_every_mfma_tile_variant(cas, M, N, swiglu, epi):
+    import torch
+    if swiglu and epi == "bias_gelu":
+        pytest.skip("SwiGLU launches carry no bias or GELU")
+    K = 192
+    rng = np.random.default_rng(M + N)
+    x, w = rand(rng, (M, K), "bf16"), rand(rng, (N, K), "bf16", 0.2)
+    x64, w64 = x.astype(np.float64), w.astype(np.float64)
+    X, W = dev(cas, x, "bf16"), dev(cas, w, "bf16")
+    Y = torch.full((M, N), 7.0, dtype=X.dtype, device="cuda")
+    kw, ep = {}, 0
+    ref = orc.linear(x64, w64)
+    if swiglu:
+        wu = rand(rng, (N, K), "bf16", 0.2)
+        kw["W_up"] = dev(cas, wu, "bf16")
+        ep |= cas.EPI_SWIGLU
+        ref = orc.silu(ref) * orc.linear(x64, wu.astype(np.float64))
+    if epi == "bias_gelu":
+        b = rand(rng, (N,), "bf16", 0.3)
+        kw["bias"] = dev(cas, b, "bf16")
+        ep |= cas.EPI_BIAS | cas.EPI_GELU_ERF
+        ref = orc.gelu_erf(ref + b.astype(np.float64))
+    if epi == "residual":
+        r = rand(rng, (M, N), "bf16")
+        kw["residual"] = dev(cas, r, "bf16")
+        ep |= cas.EPI_RESIDUAL
+        ref = ref + r.astype(np.float64)
+    cas.cascade_shard_gemm(None, X, W, Y, epilogue=ep, **kw)
+    assert rel_err(host(Y), ref) < TOL["bf16"]
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_shard_gemm_rope_uses_original_positions(cas, dtype):
     import torch
