@@ -390,14 +390,24 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm2_kernel(Gemm2Params p) {
         b_off[i] = (row < BN && col < seg_rows) ? (uint32_t)((int64_t)col * K * 2) + c * 16 : OOB_OFF;
     }
 
+    // LDS layout.  8 wavefronts: NST stages of [A tile | B tile].  One wavefront per SIMD: three A stages
+    // followed by two B stages (the A part of a refill is issued half a tile earlier than the B part, so the
+    // vector-memory instructions are spread over both k-steps; that needs the third A stage).
+    constexpr int B_BYTES = BNP * ROWB;
+    constexpr int NSTA = 3, NSTB = 2;
+    auto a_stage = [&](int kt) { return SOLO ? smem + (kt % NSTA) * A_BYTES : smem + (kt % NST) * STAGE_BYTES; };
+    auto b_stage = [&](int kt) {
+        return SOLO ? smem + NSTA * A_BYTES + (kt % NSTB) * B_BYTES : smem + (kt % NST) * STAGE_BYTES + A_BYTES;
+    };
     auto issue_load = [&](int kt, int stage, int x) {              // instruction x of LPT (x known after unrolling)
         const uint32_t kb = (uint32_t)kt * ROWB;
+        (void)stage;                                               // = kt % NST for the 8-wavefront layout
         if (x < A_INSTR) {
-            unsigned char *sa = smem + stage * STAGE_BYTES + wave * (BM / NW) * ROWB;
+            unsigned char *sa = a_stage(kt) + wave * (BM / NW) * ROWB;
             load16_to_lds(rx, sa + x * 1024, a_off[x] + kb);
         } else {
             const int i = x - A_INSTR;
-            unsigned char *sb = smem + stage * STAGE_BYTES + A_BYTES + wave * (BNP / NW) * ROWB;
+            unsigned char *sb = b_stage(kt) + wave * (BNP / NW) * ROWB;
             const int row0 = wave * (BNP / NW) + RPI * i;                   // wavefront-uniform
             const bool up = SWIGLU && ((row0 % WTN) >= WTN / 2);
             if (up) load16_to_lds(ru, sb + i * 1024, b_off[i] + kb);
@@ -467,19 +477,22 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm2_kernel(Gemm2Params p) {
     if constexpr (SOLO) {
         // One wavefront per SIMD: nothing else covers this wavefront's waits, so every memory operation
         // is placed between two MFMAs of the k-step that runs meanwhile.  Tile kt, first k-step: its
-        // MFMAs with the operand reads of the second k-step between them, all issued in the first half
-        // so that they have returned at the barrier.  Barrier (tile kt+1 landed, everyone is done reading
-        // tile kt).  Second k-step: its MFMAs with the direct-to-LDS loads of tile kt+NST (into the stage
-        // tile kt just left) and the operand reads of tile kt+1's first k-step between them.
+        // MFMAs with the operand reads of the second k-step (all issued in the first half, so that they
+        // have returned at the barrier) and the A loads of tile kt+2 (into the A stage tile kt-1 left)
+        // between them.  Barrier (tile kt+1 landed: everything but those A loads; everyone is done reading
+        // tile kt).  Second k-step: its MFMAs with the B loads of tile kt+2 (into the B stage tile kt just
+        // left) and the operand reads of tile kt+1's first k-step between them.
+        static_assert(NST == 2, "the prologue requests tiles 0 and 1");
         constexpr int NR = TM + TN;
-        static_assert(2 * NR <= TM * TN && 2 * LPT <= TM * TN, "one memory operation per two MFMAs");
+        static_assert(2 * NR <= TM * TN && 2 * A_INSTR <= TM * TN && 2 * B_INSTR <= TM * TN,
+                      "one read and one load per two MFMAs");
         auto fetch_one = [&](int kt, auto ks_tag, int r) {     // read r of a k-step: A block 0, the B blocks, the other A blocks
             constexpr int ks = decltype(ks_tag)::value;
-            const unsigned char *st = smem + (kt % NST) * STAGE_BYTES;
+            const unsigned char *sa = a_stage(kt) + a_lane, *sb = b_stage(kt) + (b_lane - A_BYTES);
             const int coff = ((4 * ks + fch) ^ fsw) * 16;
-            if (r == 0) af[ks][0] = *(const bf16x8 *)(st + a_lane + coff);
-            else if (r <= TN) bfr[ks][r - 1] = *(const bf16x8 *)(st + b_lane + (r - 1) * 16 * ROWB + coff);
-            else af[ks][r - TN] = *(const bf16x8 *)(st + a_lane + (r - TN) * 16 * ROWB + coff);
+            if (r == 0) af[ks][0] = *(const bf16x8 *)(sa + coff);
+            else if (r <= TN) bfr[ks][r - 1] = *(const bf16x8 *)(sb + (r - 1) * 16 * ROWB + coff);
+            else af[ks][r - TN] = *(const bf16x8 *)(sa + (r - TN) * 16 * ROWB + coff);
         };
         auto phase = [&](auto ks_tag, auto &&between) {        // the MFMAs of one k-step; between(x) follows MFMA x
             constexpr int ks = decltype(ks_tag)::value;
@@ -494,12 +507,15 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm2_kernel(Gemm2Params p) {
 #pragma unroll
         for (int r = 0; r < NR; ++r) fetch_one(0, k0, r);
         int kt = 0;
-        for (; kt + NST < KT; ++kt) {                          // tiles kt+1 .. kt+NST-1 are in flight or landed
+        for (; kt + 2 < KT; ++kt) {                            // tile kt+1 is in flight or landed
             if (kt == KT / 2) TRACE(3);
-            phase(k0, [&](int x) { if (x % 2 == 0 && x / 2 < NR) fetch_one(kt, k1, x / 2); });
-            wait_loads_and_barrier<(NST - 2) * LPT>();
+            phase(k0, [&](int x) {
+                if (x % 2 == 0 && x / 2 < NR) fetch_one(kt, k1, x / 2);
+                if (x % 2 == 1 && x / 2 < A_INSTR) issue_load(kt + 2, 0, x / 2);
+            });
+            wait_loads_and_barrier<A_INSTR>();
             phase(k1, [&](int x) {
-                if (x % 2 == 0 && x / 2 < LPT) issue_load(kt + NST, kt % NST, x / 2);
+                if (x % 2 == 0 && x / 2 < B_INSTR) issue_load(kt + 2, 0, A_INSTR + x / 2);
                 if (x % 2 == 1 && x / 2 < NR) fetch_one(kt + 1, k0, x / 2);
             });
         }
@@ -762,7 +778,8 @@ static int32_t launch_cfg2(const GemmArgs &a, hipStream_t s) {
     constexpr int LOAD_ROWS = 1024 / (BK * 2) * WM * WN;                  // B rows loaded per pass of all wavefronts
     constexpr int BNP = PINGPONG ? BN : (BN + LOAD_ROWS - 1) / LOAD_ROWS * LOAD_ROWS;
     constexpr size_t lds_loop = (size_t)NST * (BM + BNP) * BK * 2;
-    constexpr size_t lds = (!PINGPONG && WM * WN == 4) ? std::max(lds_loop, (size_t)EpiTile<BN_OUT>::bytes(BM)) : lds_loop;
+    constexpr size_t lds_solo = (size_t)(3 * BM + 2 * BNP) * BK * 2;            // three A stages, two B stages
+    constexpr size_t lds = (!PINGPONG && WM * WN == 4) ? std::max(lds_solo, (size_t)EpiTile<BN_OUT>::bytes(BM)) : lds_loop;
     static_assert(lds <= 160 * 1024, "tile buffers exceed the LDS of a CU");
     const void *kern;
     if constexpr (PINGPONG) kern = (const void *)gemm3_kernel<BM, BN, WM, WN, BK, NST, SWIGLU>;
