@@ -18,7 +18,7 @@ sys.path.insert(0, ROOT)
 MFMA_BF16_PEAK_TFLOPS = 2500.0      # MI355X dense bf16
 # HBM bytes per launch of the dominant kernel from rocprofv3 FETCH_SIZE / WRITE_SIZE runs, scaled by a plain
 # copy of known size (profiles/bench_C3_hbm_traffic.md); None where no counter run was made
-MEASURED_TRAFFIC_BYTES = {"C3-llama3-8b-bf16": 773.4e6 + 58.7e6}
+MEASURED_TRAFFIC_BYTES = {"C3-llama3-8b-bf16": 772.3e6 + 58.7e6}
 FP32_VECTOR_PEAK_TFLOPS = 157.3
 HBM_PEAK_GBS = 8000.0
 
@@ -319,8 +319,8 @@ def cpu_baseline(cfg, host):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", default="C3", help="headline workload (C1..C5)")
     ap.add_argument("--all", action="store_true", help="also time the other bf16 configurations")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -368,7 +368,7 @@ def main():
                    "head_dim": d, "d_ff": cfg.d_ff, "attn_mode": "fused", "io_rows": "original"},
         "layer_tflops": res["tflops"], "layer_frac_of_mfma_peak": res["tflops"] / peak,
         "layer_gflop_counted": fl["total"] / 1e9,
-        "roofline": {"bound": "mfma" if bf16 else "alu", "kernel": "gemm_bf16_kernel (FFN gate+up shard GEMM)"
+        "roofline": {"bound": "mfma" if bf16 else "alu", "kernel": "gemm2_kernel<256,224,4,1,64,2,true> (FFN gate+up shard GEMM)"
                      if bf16 else "gemm_f32_kernel (FFN up shard GEMM)",
                      "achieved": dom_tflops, "peak": peak, "unit": "TFLOP/s", "frac": dom_tflops / peak,
                      "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name), "avg_launch_ms": st[dom], "flops_per_launch": fl[dom]},
