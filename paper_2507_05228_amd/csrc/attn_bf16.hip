@@ -395,6 +395,9 @@ __global__ __launch_bounds__(512) void attn_bf16_kernel(AttnBf16Params p) {
         const unsigned char *sk = smem + stage * STAGE;
         y_stage = stage;
         if (t + 2 < t_end) issue_loads(mt2, (i + 2) % NST);
+        // The SIMD's other wavefront is in its vector phase: let this one's MFMAs and operand reads win the
+        // issue arbitration, so the matrix pipe is fed first and the softmax arithmetic fills the gaps.
+        __builtin_amdgcn_s_setprio(3);
         // O^T += V^T(i-1) P^T(i-1).  Step s covers keys 32s..32s+31; k-slot (g4, j) of both operands is
         // key 32s + 16(j/4) + 4 g4 + j%4, i.e. accumulator register j%4 of block 2s + j/4.
         const int prev_stage = (i + NST - 1) % NST;
@@ -423,6 +426,7 @@ __global__ __launch_bounds__(512) void attn_bf16_kernel(AttnBf16Params p) {
             case 1: qk_blocks(std::integral_constant<int, 1>(), sk); break;
             default: qk_blocks(std::integral_constant<int, 0>(), sk);
         }
+        __builtin_amdgcn_s_setprio(0);
     };
 
     // ================= Y(i): vector phase on the tile held in sacc

@@ -140,7 +140,7 @@ def test_shard_gemm_swiglu_and_tanh(cas, dtype):
 # rule on 256 CUs; ragged M and N, bias + GELU or residual, every output element against the oracle.
 @pytest.mark.parametrize("M,N,swiglu", [(700, 1000, False), (700, 1000, True), (700, 9600, True), (700, 13728, False),
                                         (1000, 12352, False), (1000, 14416, False), (1300, 10804, False),
-                                        (2000, 12352, False)])
+                                        (2000, 12352, False), (40, 448, True), (1, 1000, True), (3, 5000, False)])
 @pytest.mark.parametrize("epi", ["plain", "bias_gelu", "residual"])
 def test_shard_gemm_every_mfma_tile_variant(cas, M, N, swiglu, epi):
     import torch
