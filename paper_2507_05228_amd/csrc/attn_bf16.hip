@@ -389,6 +389,46 @@ __global__ __launch_bounds__(512) void attn_bf16_kernel(AttnBf16Params p) {
         }
     };
 
+    // Both products of a full tile (all four key blocks visible, a full P pending), interleaved so that
+    // the LDS latency of one product's operand reads is covered by the other's MFMAs: per key block b,
+    // V^T reads of quarter b of O^T += V^T P^T, the 8 MFMAs of S^T block b (its K operands were read a
+    // step earlier), K reads of block b+1, the 8 MFMAs of that quarter.
+    auto x_full_tile = [&](int stg, const unsigned char *sk) {
+        const unsigned char *pv = smem + stg * STAGE + K_BYTES + l16 * 128;
+        bf16x8 kf[KS];
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) kf[ks] = *(const bf16x8 *)(sk + l16 * K_ROW + (((4 * ks + g4) ^ k_swz) * 16));
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            constexpr int QD = DB / 4;                     // d-blocks per quarter of the P V product
+            const int s2 = b >> 1, db0 = (b & 1) * 2 * QD;
+            const int cv = ((4 * s2 + g4) ^ v_swz) * 16;
+            bf16x8 vf[2 * QD];
+#pragma unroll
+            for (int q = 0; q < 2 * QD; ++q) vf[q] = *(const bf16x8 *)(pv + (db0 + q) * 16 * 128 + cv);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+                for (int qb = 0; qb < TQ; ++qb)
+                    sacc[qb][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[ks], qf[qb][ks],
+                                                                          ks == 0 ? zero4 : sacc[qb][b], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            if (b + 1 < 4) {
+                const unsigned char *kp = sk + ((b + 1) * 16 + l16) * K_ROW;
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) kf[ks] = *(const bf16x8 *)(kp + (((4 * ks + g4) ^ k_swz) * 16));
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int q = 0; q < 2 * QD; ++q)
+#pragma unroll
+                for (int qb = 0; qb < TQ; ++qb)
+                    oacc[qb][db0 + q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[q], pf[qb][s2], oacc[qb][db0 + q], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
     // ================= X(i): matrix phase
     auto matrix_phase = [&](int i) {
         const int stage = i % NST;
@@ -401,9 +441,6 @@ __global__ __launch_bounds__(512) void attn_bf16_kernel(AttnBf16Params p) {
         // O^T += V^T(i-1) P^T(i-1).  Step s covers keys 32s..32s+31; k-slot (g4, j) of both operands is
         // key 32s + 16(j/4) + 4 g4 + j%4, i.e. accumulator register j%4 of block 2s + j/4.
         const int prev_stage = (i + NST - 1) % NST;
-        if (n_pv == 2) pv_steps(std::integral_constant<int, 2>(), prev_stage);
-        else if (n_pv == 1) pv_steps(std::integral_constant<int, 1>(), prev_stage);
-        __builtin_amdgcn_sched_barrier(0);
         // per 16-key block: can this wavefront skip it / does it need the element-wise compare
         kn = mt0.n_rows;
         int skipm = 0;
@@ -418,14 +455,22 @@ __global__ __launch_bounds__(512) void attn_bf16_kernel(AttnBf16Params p) {
         // ones: blocks [0, n_act) are computed (for other position orders one below n_act that could
         // have been skipped is cut by the element-wise compare instead), blocks [n_act, 4) contribute
         // exact zeros to P.
-        n_act = (~skipm & 15) ? 32 - __builtin_clz(~skipm & 15) : 0;
-        switch (n_act) {
-            case 4: qk_blocks(std::integral_constant<int, 4>(), sk); break;
-            case 3: qk_blocks(std::integral_constant<int, 3>(), sk); break;
-            case 2: qk_blocks(std::integral_constant<int, 2>(), sk); break;
-            case 1: qk_blocks(std::integral_constant<int, 1>(), sk); break;
-            default: qk_blocks(std::integral_constant<int, 0>(), sk);
+        const int n_act_new = (~skipm & 15) ? 32 - __builtin_clz(~skipm & 15) : 0;
+        if (n_pv == 2 && n_act_new == 4) {
+            x_full_tile(prev_stage, sk);
+        } else {
+            if (n_pv == 2) pv_steps(std::integral_constant<int, 2>(), prev_stage);
+            else if (n_pv == 1) pv_steps(std::integral_constant<int, 1>(), prev_stage);
+            __builtin_amdgcn_sched_barrier(0);
+            switch (n_act_new) {
+                case 4: qk_blocks(std::integral_constant<int, 4>(), sk); break;
+                case 3: qk_blocks(std::integral_constant<int, 3>(), sk); break;
+                case 2: qk_blocks(std::integral_constant<int, 2>(), sk); break;
+                case 1: qk_blocks(std::integral_constant<int, 1>(), sk); break;
+                default: qk_blocks(std::integral_constant<int, 0>(), sk);
+            }
         }
+        n_act = n_act_new;
         __builtin_amdgcn_s_setprio(0);
     };
 
