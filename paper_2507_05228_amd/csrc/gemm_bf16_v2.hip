@@ -809,13 +809,12 @@ int32_t launch_gemm_bf16_v2(const GemmArgs &a, hipStream_t s) {
     for (int i = 0; i < 3; ++i)
         if (a.seg_end[i] % 4) return CASCADE_EUNSUPPORTED;          // 4-column store chunks stay inside a segment
     const bool swiglu = a.epilogue & CASCADE_EPI_SWIGLU;
-    // Tile choice (measured on MI355X, M = 2048..8192): 256x256 tiles with BK 64 and two stages (the
-    // largest step per barrier that fits LDS; 1.13 PFLOP/s on the FFN up GEMM against 1.06-1.08 for
-    // BK 32 with 4-5 stages in either schedule) when they give at least ~160 workgroups; otherwise
-    // 256x128 tiles, BK 64, three stages, ping-pong schedule (1.10 against 1.04 PFLOP/s on FFN down).
-    // SwiGLU always uses the 256-column tile (gate and up rows interleave per 128-column wavefront tile).
-    // Narrower variants of the wide tile (224, 192 columns) exist to fill whole rounds of workgroups:
-    // the cost of a launch is rounds x columns per tile.
+    // Tile choice.  The cost of a launch is rounds of workgroups x columns per tile; candidates are
+    // 256 rows x {256, 224, 192} columns (BK 64, two stages; the widths exist to fill whole rounds) and
+    // 256 x 128 (three stages, ping-pong schedule).  The cheapest wins, the narrow one only by a margin.
+    // SwiGLU always uses a wide tile (gate and up rows are interleaved inside it).  Measured on MI355X:
+    // wide tiles 1.13 PFLOP/s on the FFN up GEMM with 8 wavefronts (1.06-1.08 for BK 32 with 4-5 stages),
+    // 1.25-1.3 with one wavefront per SIMD; 256x128 ping-pong 1.10 against 1.04 PFLOP/s on FFN down.
     const int tiles_m = (a.M + 255) / 256;
     auto n_tiles = [&](int bn_out) {
         int64_t t = 0;
@@ -825,12 +824,13 @@ int32_t launch_gemm_bf16_v2(const GemmArgs &a, hipStream_t s) {
     };
     const int64_t cus = cu_count();
     auto cost = [&](int bne) { return ((n_tiles(swiglu ? bne / 2 : bne) + cus - 1) / cus) * bne; };
-    const int64_t c256 = cost(256), c224 = cost(224), c192 = cost(192);
+    const int64_t c256 = cost(256), c224 = cost(224), c192 = cost(192), c128 = cost(128);
     if (swiglu) {
         if (c224 < c256) return launch_cfg2<256, 224, 4, 1, 64, 2, true, false>(a, s);
         return launch_cfg2<256, 256, 2, 2, 64, 2, true, false>(a, s);
     }
-    if (n_tiles(256) >= 160) {
+    // the 256x128 kernel does ~15 % fewer flops per cycle than the wide ones: it has to be that much cheaper
+    if (std::min(c192, std::min(c224, c256)) * 20 <= c128 * 23) {
         // The one-wavefront-per-SIMD schedule exists for the 192- and 224-column tiles (256 accumulator
         // registers per lane leave it no room at 256 columns).  It wins when a CU works through several
         // tiles; in a single round its faster loop is paid back in the epilogue, where all workgroups store
@@ -847,5 +847,8 @@ int32_t launch_gemm_bf16_v2(const GemmArgs &a, hipStream_t s) {
         if (c224 == best) return launch_cfg2<256, 224, 4, 2, 64, 2, false, false>(a, s);
         return launch_cfg2<256, 256, 4, 2, 64, 2, false, false>(a, s);   // 8 wavefronts
     }
+    // narrow GEMMs (N of a few hundred to a few thousand columns): 256x128 tiles, or 128x128 when even those
+    // would leave half of the CUs without a workgroup (small-model o projection / FFN down)
+    if (n_tiles(128) * 2 <= cus) return launch_cfg2<128, 128, 4, 2, 64, 3, false, true>(a, s);
     return launch_cfg2<256, 128, 4, 2, 64, 3, false, true>(a, s);
 }
