@@ -156,8 +156,11 @@ __global__ __launch_bounds__(256) void vtranspose_kernel(const bf16_t *__restric
 }
 
 // ---------------------------------------------------------------------------- attention
-template <int D>
-__global__ __launch_bounds__(512) void attn_bf16_kernel(AttnBf16Params p) {
+// NWV = 8: the workgroup described above.  NWV = 4: half of it (one wavefront per SIMD, up to 128 query rows
+// of one head), for plans whose shards are too short to give 8 wavefronts rows; two such workgroups share a
+// CU when their LDS fits (head dimension 64) and overlap each other's phases instead.
+template <int D, int NWV>
+__global__ __launch_bounds__(NWV * 64) void attn_bf16_kernel(AttnBf16Params p) {
     constexpr int TQ = 2;                              // 16-row query blocks per wavefront
     constexpr int KS = D / 32;                         // k-steps of the score product
     constexpr int DB = D / 16;                         // 16-row blocks of O^T
@@ -166,8 +169,9 @@ __global__ __launch_bounds__(512) void attn_bf16_kernel(AttnBf16Params p) {
     constexpr int K_CPR = K_ROW / 16;                  // 16-byte chunks per K row
     constexpr int K_BYTES = KV_TILE * K_ROW, V_BYTES = D * 128;
     constexpr int STAGE = K_BYTES + V_BYTES + KV_TILE * 4;   // K tile, V^T tile, key positions
-    constexpr int K_INSTR = KV_TILE / K_RPI / 8;       // per wavefront (8 wavefronts): 2 (D=128) or 1 (D=64)
-    constexpr int V_INSTR = D / 8 / 8;                 // 2 or 1
+    constexpr int K_INSTR = KV_TILE / K_RPI / NWV;     // per wavefront; 8 wavefronts: 2 (D=128) or 1 (D=64)
+    constexpr int V_INSTR = D / 8 / NWV;               // 2 or 1
+    static_assert(NWV == 4 || NWV == 8, "one or two wavefronts per SIMD");
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
@@ -331,7 +335,7 @@ __global__ __launch_bounds__(512) void attn_bf16_kernel(AttnBf16Params p) {
     // wavefront waits for its own loads of tile i+1, so the tile is complete when X(i+1) starts.
     constexpr int NST = 4;
     constexpr int LPT = K_INSTR + V_INSTR + 1;         // direct-to-LDS loads per tile per wavefront
-    const int group = wave >> 2;
+    const int group = NWV == 8 ? wave >> 2 : 0;
     int t = t_begin;                                   // tile i
     TileMeta mt0 = {}, mt1 = {}, mt2 = {};             // tiles i, i+1, i+2
     if (t < t_end) mt0 = load_meta(t);
@@ -642,14 +646,14 @@ size_t attn_bf16_workspace_bytes(const cascade_plan *p, int32_t B, int32_t Hkv, 
     return vt_bytes_of(p, B, Hkv, d) + align_up((size_t)B * Hkv * p->seq_len * d * 2, 256);
 }
 
-template <int D>
+template <int D, int NWV>
 static int32_t launch_attn_cfg(const cascade_plan *p, const AttnArgs &a, hipStream_t s) {
     const cascade_plan *kvp = kv_plan(p);                      // key/value shards (S); query tiles follow p (R)
     const int N = p->seq_len, S = kvp->n_shards;
     const int rep = a.H / a.Hkv;
     const int hpb = rep % 4 == 0 ? 4 : rep % 2 == 0 ? 2 : 1;
-    const int rowgroups = 8 / hpb;
-    const int granule = 32 * rowgroups;                        // 64, 128 or 256 query rows per workgroup
+    const int rowgroups = NWV / hpb;
+    const int granule = 32 * rowgroups;                        // 32 .. 256 query rows per workgroup
     const CascadeTileList &ql = plan_tiles(p, granule);
     const CascadeTileList &kl = plan_tiles(kvp, KV_TILE);
     const int npad = npad_of(p);
@@ -687,13 +691,13 @@ static int32_t launch_attn_cfg(const cascade_plan *p, const AttnArgs &a, hipStre
     k.hpb = hpb;
 
     constexpr int lds = 4 * (KV_TILE * D * 2 + D * 128 + KV_TILE * 4);
-    auto kern = attn_bf16_kernel<D>;
+    auto kern = attn_bf16_kernel<D, NWV>;
     static std::atomic<uint64_t> lds_ready{0};
     CASCADE_HIP_TRY(ensure_dynamic_lds((const void *)kern, lds, lds_ready));
     const int64_t gy = (int64_t)a.B * a.Hkv * (rep / hpb);
     if (gy > 65535 || S > 65535) return CASCADE_EUNSUPPORTED;
     dim3 grid(ql.count, (unsigned)gy, a.fused ? 1 : S);
-    hipLaunchKernelGGL(kern, grid, dim3(512), lds, s, k);
+    hipLaunchKernelGGL(kern, grid, dim3(NWV * 64), lds, s, k);
     CASCADE_HIP_TRY(hipGetLastError());
     return CASCADE_OK;
 }
@@ -705,6 +709,13 @@ int32_t launch_attn_bf16(const cascade_plan *p, const AttnArgs &a, hipStream_t s
     if ((a.qs_n | a.qs_h | a.qs_b | a.ks_n | a.ks_h | a.ks_b) % 8 ||
         ((uintptr_t)a.q | (uintptr_t)a.k | (uintptr_t)a.v | (uintptr_t)a.workspace) % 16)
         return CASCADE_EUNSUPPORTED;
-    if (a.d == 128) return launch_attn_cfg<128>(p, a, s);
-    return launch_attn_cfg<64>(p, a, s);
+    // 8 wavefronts cover 256 / hpb query rows of a shard; when no shard of the plan has more than half of that,
+    // four of them would never have rows: use the 4-wavefront workgroup
+    const int rep = a.H / a.Hkv;
+    const int hpb = rep % 4 == 0 ? 4 : rep % 2 == 0 ? 2 : 1;
+    int max_shard = 0;
+    for (int j = 0; j < p->n_shards; ++j) max_shard = std::max(max_shard, p->offsets_h[j + 1] - p->offsets_h[j]);
+    const bool half = max_shard <= 32 * (4 / hpb);
+    if (a.d == 128) return half ? launch_attn_cfg<128, 4>(p, a, s) : launch_attn_cfg<128, 8>(p, a, s);
+    return half ? launch_attn_cfg<64, 4>(p, a, s) : launch_attn_cfg<64, 8>(p, a, s);
 }
