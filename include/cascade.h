@@ -377,6 +377,30 @@ CASCADE_API int32_t cascade_decode_partial_attn(const cascade_attn_desc *desc, i
                                     const void *q, const void *k_cache, const void *v_cache,
                                     float *m, float *e, float *u, void *stream);
 
+/* Normalisation of `rows` rows of D values (the "layer normalization if
+ * necessary" of the Pre-Pass subsection, exposed for callers that compose a
+ * single-token step themselves): y = norm(x) * gain (+ bias), statistics in
+ * fp32.  x, y [rows, D], gain [D], bias [D] or NULL: device, dtype; x == y allowed.
+ * Errors: EINVAL, EUNSUPPORTED, EHIP.                                            */
+CASCADE_API int32_t cascade_norm(int32_t dtype, int32_t rows, int32_t d_model, int32_t norm_kind, float eps,
+                     const void *x, const void *gain, const void *bias, void *y, void *stream);
+
+/* Token-sharded KV cache from a prefill ("Caching": every AttnNode_jk keeps the
+ * k, v of its shard S_k between tokens).  Copies the keys (rotary embedding
+ * already applied) and values that the last cascade_layer_forward /
+ * cascade_layer_stack_forward call with this plan and descriptor left in
+ * `workspace` into the slabs cascade_decode_partial_attn reads:
+ *   k_cache, v_cache [B, H_KV, n_kv_shards, shard_capacity, d] in desc->dtype;
+ *   row r of kv shard k (ascending token index inside the shard) goes to slab
+ *   row r; slab rows past the shard's size are left untouched.
+ *   shard_len_dev [B, n_kv_shards] int32 DEVICE receives the shard sizes.
+ * shard_capacity must hold the largest shard (ESHAPE otherwise).  The workspace
+ * must not have been reused since that forward call.
+ * Errors: EINVAL, ESHAPE, EUNSUPPORTED, EHIP.                                    */
+CASCADE_API int32_t cascade_layer_kv_to_cache(const cascade_plan *plan, const cascade_layer_desc *desc,
+                                  const void *workspace, void *k_cache, void *v_cache,
+                                  int32_t shard_capacity, int32_t *shard_len_dev, void *stream);
+
 /* ------------------------------------------------------------------ measured ceiling
  * Not a step of the method: the rate (TFLOP/s) this device sustains on back-to-back
  * bf16 16x16x32 MFMAs with random operands, for the roofline figures quoted next

@@ -31,7 +31,7 @@ EXPORTS = ["cascade_plan_create", "cascade_plan_create_rs", "cascade_plan_maps",
            "cascade_partial_attn", "cascade_lse_merge", "cascade_layer_workspace_bytes",
            "cascade_layer_forward", "cascade_layer_forward_staged", "cascade_layer_partials",
            "cascade_layer_stack_workspace_bytes", "cascade_layer_stack_forward",
-           "cascade_lm_head_workspace_bytes", "cascade_lm_head", "cascade_greedy_token",
+           "cascade_lm_head_workspace_bytes", "cascade_lm_head", "cascade_greedy_token", "cascade_layer_kv_to_cache", "cascade_norm",
            "cascade_decode_partial_attn", "cascade_mfma_ceiling"]
 N_STAGE_EVENTS = 10
 STAGE_NAMES = ["gather_norm1", "qkv_gemm", "rope", "attention", "lse_merge", "o_proj", "norm2", "ffn_up", "ffn_down"]
@@ -143,6 +143,10 @@ def load_library():
     lib.cascade_lm_head.restype = I32
     lib.cascade_greedy_token.argtypes = [VP, I32, I32, I32, VP, VP]
     lib.cascade_greedy_token.restype = I32
+    lib.cascade_layer_kv_to_cache.argtypes = [VP, P(LayerDesc), VP, VP, VP, I32, VP, VP]
+    lib.cascade_layer_kv_to_cache.restype = I32
+    lib.cascade_norm.argtypes = [I32, I32, I32, I32, C.c_float, VP, VP, VP, VP, VP]
+    lib.cascade_norm.restype = I32
     lib.cascade_decode_partial_attn.argtypes = [P(AttnDesc), I32, I32, I32, VP, VP, VP, VP, VP, VP, VP, VP]
     lib.cascade_decode_partial_attn.restype = I32
     lib.cascade_mfma_ceiling.argtypes = [I32, I32, P(C.c_float), VP]
@@ -393,6 +397,22 @@ def cascade_layer_stack_forward(plan, desc, weights_list, h_in, h_out, workspace
     st = lib.cascade_layer_stack_forward(plan.handle, C.byref(desc), arr, len(weights_list), _ptr(h_in), _ptr(h_out),
                                          _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream))
     _check(st, "cascade_layer_stack_forward")
+
+
+def cascade_norm(x, gain, bias, y, norm_kind, eps, stream=None):
+    """x, y [rows, D]."""
+    lib = load_library()
+    st = lib.cascade_norm(_dtype_code(x), x.shape[0], x.shape[1], norm_kind, eps, _ptr(x), _ptr(gain), _ptr(bias), _ptr(y),
+                          _stream(stream))
+    _check(st, "cascade_norm")
+
+
+def cascade_layer_kv_to_cache(plan, desc, workspace, k_cache, v_cache, shard_len, stream=None):
+    """k_cache, v_cache [B, Hkv, n_kv_shards, capacity, d]; shard_len int32 [B, n_kv_shards] (device)."""
+    lib = load_library()
+    st = lib.cascade_layer_kv_to_cache(plan.handle, C.byref(desc), _ptr(workspace), _ptr(k_cache), _ptr(v_cache),
+                                       k_cache.shape[3], _ptr(shard_len), _stream(stream))
+    _check(st, "cascade_layer_kv_to_cache")
 
 
 def cascade_lm_head_workspace_bytes(plan, desc):

@@ -199,6 +199,41 @@ extern "C" int32_t cascade_layer_partials(const cascade_plan *plan, const cascad
     return CASCADE_OK;
 }
 
+extern "C" int32_t cascade_norm(int32_t dtype, int32_t rows, int32_t d_model, int32_t norm_kind, float eps,
+                                const void *x, const void *gain, const void *bias, void *y, void *stream) {
+    if (!x || !gain || !y || rows < 0 || d_model <= 0) return CASCADE_EINVAL;
+    if (!dtype_ok(dtype)) return CASCADE_EUNSUPPORTED;
+    if (norm_kind != CASCADE_NORM_LAYERNORM && norm_kind != CASCADE_NORM_RMSNORM) return CASCADE_EINVAL;
+    NormArgs n = {};
+    n.dtype = dtype; n.rows = rows; n.D = d_model; n.kind = norm_kind; n.eps = eps;
+    n.x = x; n.gain = gain; n.bias = bias; n.y = y;
+    n.xmap.map = n.ymap.map = nullptr; n.xmap.seq_len = n.ymap.seq_len = 1;
+    return launch_norm(n, (hipStream_t)stream);
+}
+
+extern "C" int32_t cascade_layer_kv_to_cache(const cascade_plan *plan, const cascade_layer_desc *d,
+                                             const void *workspace, void *k_cache, void *v_cache,
+                                             int32_t shard_capacity, int32_t *shard_len_dev, void *stream) {
+    int32_t st = check_layer_desc(plan, d);
+    if (st != CASCADE_OK) return st;
+    if (!workspace || !k_cache || !v_cache || !shard_len_dev || shard_capacity <= 0) return CASCADE_EINVAL;
+    const cascade_plan *kvp = kv_plan(plan);
+    for (int k = 0; k < kvp->n_shards; ++k)
+        if (kvp->offsets_h[k + 1] - kvp->offsets_h[k] > shard_capacity) return CASCADE_ESHAPE;
+    const LayerWs w = layer_ws(plan, d);
+    KvCacheArgs a = {};
+    a.dtype = d->dtype; a.B = plan->batch; a.N = plan->seq_len; a.Hkv = d->n_kv_heads; a.d = d->head_dim;
+    a.n_shards = kvp->n_shards; a.cap = shard_capacity;
+    a.act = (const char *)workspace + w.qkv;
+    a.ld = (int64_t)(d->n_heads + 2 * d->n_kv_heads) * d->head_dim;
+    a.k_col0 = d->n_heads * d->head_dim;
+    a.v_col0 = (d->n_heads + d->n_kv_heads) * d->head_dim;
+    a.offsets = kvp->offsets_d;
+    a.row_of = plan->kv ? plan->kv_to_row_d : nullptr;
+    a.k_cache = k_cache; a.v_cache = v_cache; a.shard_len = shard_len_dev;
+    return launch_kv_to_cache(a, (hipStream_t)stream);
+}
+
 // in_rows / out_rows: row order of h_in / h_out (a layer stack keeps packed order between layers)
 static int32_t layer_forward_impl(const cascade_plan *plan, const cascade_layer_desc *d,
                                   const cascade_layer_weights *w, const void *h_in, void *h_out,

@@ -112,6 +112,16 @@ struct NormArgs {
     RowMap ymap;                     // scatter on the write
 };
 int32_t launch_norm(const NormArgs &a, hipStream_t s);
+// k, v rows of a packed [T, ld] activation (columns k_col0 .. and v_col0 .., H_kv heads of d) -> cache slabs
+// [B, H_kv, n_shards, cap, d]; shard k holds rows offsets[k] .. offsets[k+1] of the (kv) packed order, row_of
+// maps those to rows of the activation (nullptr: identity); shard_len [B, n_shards] receives the sizes
+struct KvCacheArgs {
+    int32_t dtype, B, N, Hkv, d, n_shards, cap;
+    const void *act; int64_t ld; int32_t k_col0, v_col0;
+    const int32_t *offsets, *row_of;
+    void *k_cache, *v_cache; int32_t *shard_len;
+};
+int32_t launch_kv_to_cache(const KvCacheArgs &a, hipStream_t s);
 // token_out[r] = lowest index of the largest element of row r of x [rows, ld] (first `vocab` columns)
 int32_t launch_argmax_rows(int32_t dtype, const void *x, int64_t ld, int32_t rows, int32_t vocab, int32_t *token_out,
                            hipStream_t s);

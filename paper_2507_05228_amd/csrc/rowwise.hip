@@ -124,6 +124,41 @@ int32_t launch_norm(const NormArgs &a, hipStream_t s) {
     return a.dtype == CASCADE_BF16 ? launch_norm_t<bf16_t>(a, s) : launch_norm_t<float>(a, s);
 }
 
+// ---------------------------------------------------------------------------- prefill k, v -> cache slabs
+// One workgroup per (kv shard, kv head, sequence); 16-byte pieces, a row of d elements per d*sizeof(T)/16 lanes.
+template <typename T>
+__global__ __launch_bounds__(256) void kv_to_cache_kernel(KvCacheArgs a) {
+    constexpr int VEC = 16 / sizeof(T);
+    const int k = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
+    const int r0 = a.offsets[k], n = a.offsets[k + 1] - r0;
+    if (g == 0 && threadIdx.x == 0) a.shard_len[b * a.n_shards + k] = n;
+    const int cpr = a.d / VEC;                              // pieces per row
+    const T *act = (const T *)a.act + (int64_t)b * a.N * a.ld;
+    T *kc = (T *)a.k_cache + (((int64_t)b * a.Hkv + g) * a.n_shards + k) * (int64_t)a.cap * a.d;
+    T *vc = (T *)a.v_cache + (((int64_t)b * a.Hkv + g) * a.n_shards + k) * (int64_t)a.cap * a.d;
+    typedef T vec_t __attribute__((ext_vector_type(VEC)));
+    for (int id = threadIdx.x; id < n * cpr; id += 256) {
+        const int i = id / cpr, c = id - i * cpr;
+        const int row = a.row_of ? a.row_of[r0 + i] : r0 + i;
+        const T *src = act + (int64_t)row * a.ld + g * a.d + c * VEC;
+        *(vec_t *)(kc + (int64_t)i * a.d + c * VEC) = *(const vec_t *)(src + a.k_col0);
+        *(vec_t *)(vc + (int64_t)i * a.d + c * VEC) = *(const vec_t *)(src + a.v_col0);
+    }
+}
+
+int32_t launch_kv_to_cache(const KvCacheArgs &a, hipStream_t s) {
+    const int vec = a.dtype == CASCADE_BF16 ? 8 : 4;
+    if (a.d % vec || a.ld % vec || a.k_col0 % vec || a.v_col0 % vec ||
+        ((uintptr_t)a.act | (uintptr_t)a.k_cache | (uintptr_t)a.v_cache) % 16)
+        return CASCADE_EUNSUPPORTED;
+    if (a.n_shards > 65535 * 32 || a.Hkv > 65535 || a.B > 65535) return CASCADE_EUNSUPPORTED;
+    dim3 grid(a.n_shards, a.Hkv, a.B);
+    if (a.dtype == CASCADE_BF16) hipLaunchKernelGGL(kv_to_cache_kernel<bf16_t>, grid, dim3(256), 0, s, a);
+    else hipLaunchKernelGGL(kv_to_cache_kernel<float>, grid, dim3(256), 0, s, a);
+    CASCADE_HIP_TRY(hipGetLastError());
+    return CASCADE_OK;
+}
+
 // ---------------------------------------------------------------------------- greedy token
 // Lowest index of the largest logit of a row (the CompNode holding the last token turns its logits
 // into the next token).  One 1024-thread block per row; a thread walks ascending indices and keeps

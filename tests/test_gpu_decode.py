@@ -156,3 +156,92 @@ def test_decode_error_paths(cas):
     with pytest.raises(cas.CascadeError) as ei:                              # 48 is not 8 * 2^j
         cas.cascade_decode_partial_attn(q48, kc48, kc48, lens, m, m.clone(), torch.zeros(1, 3, 4, 48, device="cuda"), 0.125)
     assert ei.value.status == cas.EUNSUPPORTED
+
+
+# ---------------------------------------------------------------- prefill -> cache -> one decode step
+def _small_llama(dtype, d):
+    from cascade_inputs import CONFIGS
+    return CONFIGS["C3"].with_(name=f"decode-llama-{dtype}-{d}", dtype=dtype, d_model=256, n_heads=4, n_kv_heads=2,
+                               head_dim=d, d_ff=512, batch=2, seq_len=199, n_shards=5, index=51)
+
+
+@pytest.mark.parametrize("dtype,d,kind", [("bf16", 64, "perm"), ("bf16", 128, "ragged"), ("f32", 32, "roundrobin")])
+def test_prefill_cache_then_decode_step_is_the_last_row_of_the_longer_sequence(cas, dtype, d, kind):
+    """Layer forward on the first N tokens, its k, v moved into the per-shard cache, then the token N composed from
+    the entry points (norm, q/k/v shard GEMM with rotary at position N, append, per-shard partials, merge, o
+    projection + residual, norm, FFN): equals row N of the unsharded layer on N + 1 tokens."""
+    import torch
+    from cascade_inputs import make_hidden, make_layer_weights
+    cfg = _small_llama(dtype, d)
+    N, B, beta = cfg.seq_len, cfg.batch, cfg.n_shards
+    H, Hkv, D = cfg.n_heads, cfg.n_kv_heads, cfg.d_model
+    w = make_layer_weights(cfg)
+    h_full = make_hidden(cfg.with_(seq_len=N + 1))                        # [B, N + 1, D]
+    a_full = make_assignment(kind, N + 1, beta, 5)
+    a, j_new = a_full[:N], int(a_full[N])
+    tol = TOL[dtype]
+
+    # prefill of the first N tokens
+    plan = cas.cascade_plan_create(B, N, beta, a)
+    desc = cas.make_layer_desc(cfg, cas.ATTN_FUSED)
+    t = {k: cas.to_device(v, dtype) for k, v in w.items()}
+    wts = cas.make_layer_weights(t)
+    h_in = cas.to_device(h_full[:, :N], dtype)
+    h_out = torch.empty_like(h_in)
+    ws = cas.new_workspace(cas.cascade_layer_workspace_bytes(plan, desc))
+    cas.cascade_layer_forward(plan, desc, wts, h_in, h_out, ws)
+    sizes = np.bincount(a, minlength=beta)
+    cap = int(sizes.max()) + 3
+    kc = torch.full((B, Hkv, beta, cap, d), 768.0, dtype=h_in.dtype, device="cuda")
+    vc = torch.full((B, Hkv, beta, cap, d), -768.0, dtype=h_in.dtype, device="cuda")
+    lens = torch.full((B, beta), -1, dtype=torch.int32, device="cuda")
+    cas.cascade_layer_kv_to_cache(plan, desc, ws, kc, vc, lens)
+    torch.cuda.synchronize()
+    assert np.array_equal(lens.cpu().numpy(), np.tile(sizes, (B, 1)))
+    # cache content = the oracle's pre-pass k, v of every shard (rotary at the tokens' own positions)
+    lists = orc.shard_index_lists(a, beta)
+    w64 = {k: v.astype(np.float64) for k, v in w.items()}
+    for b in range(B):
+        for k, R in enumerate(lists):
+            _, k_ref, v_ref = orc.pre_pass(h_full[b, R].astype(np.float64), R, w64, cfg)
+            got_k = kc[b, :, k, :len(R)].float().cpu().numpy()
+            got_v = vc[b, :, k, :len(R)].float().cpu().numpy()
+            assert np.abs(got_k - k_ref).max() < tol * max(np.abs(k_ref).max(), 1) * 1.5
+            assert np.abs(got_v - v_ref).max() < tol * max(np.abs(v_ref).max(), 1) * 1.5
+    assert float(kc[:, :, 0, sizes[0]:].float().min()) == 768.0            # rows past a shard's size untouched
+
+    # token N
+    nk = cas.NORM_RMSNORM
+    hn = cas.to_device(h_full[:, N], dtype)                               # [B, D]
+    x = torch.empty_like(hn)
+    cas.cascade_norm(hn, t["norm1_g"], None, x, nk, cfg.eps)
+    wqkv = torch.cat([t["wq"], t["wk"], t["wv"]], dim=0).contiguous()
+    QW = (H + 2 * Hkv) * d
+    qkv = torch.empty(B, QW, dtype=hn.dtype, device="cuda")
+    plan_pos = cas.cascade_plan_create(B, 1, 1, np.zeros(1, np.int32), positions=np.array([N], np.int32))
+    cas.cascade_shard_gemm(plan_pos, x, wqkv, qkv, epilogue=cas.EPI_ROPE, rope_cols=(H + Hkv) * d, head_dim=d,
+                           rope_theta=cfg.rope_theta)
+    q = qkv[:, :H * d].reshape(B, H, d).contiguous()
+    kc[:, :, j_new, sizes[j_new]] = qkv[:, H * d:(H + Hkv) * d].reshape(B, Hkv, d)
+    vc[:, :, j_new, sizes[j_new]] = qkv[:, (H + Hkv) * d:].reshape(B, Hkv, d)
+    lens[:, j_new] += 1
+    m = torch.empty(B, H, beta, dtype=torch.float32, device="cuda")
+    e = torch.empty_like(m)
+    u = torch.empty(B, beta, H, d, dtype=torch.float32, device="cuda")
+    cas.cascade_decode_partial_attn(q, kc, vc, lens, m, e, u, cfg.scale)
+    plan1 = cas.cascade_plan_create(B, 1, beta, np.array([j_new], np.int32))
+    o = torch.empty(B, 1, H * d, dtype=hn.dtype, device="cuda")
+    cas.cascade_lse_merge(plan1, m.view(B, H, beta, 1), e.view(B, H, beta, 1), u.view(B, beta, H, 1, d), o, H, Hkv, d)
+    h1 = torch.empty_like(hn)
+    cas.cascade_shard_gemm(None, o.view(B, H * d), t["wo"], h1, residual=hn, epilogue=cas.EPI_RESIDUAL)
+    x2 = torch.empty_like(hn)
+    cas.cascade_norm(h1, t["norm2_g"], None, x2, nk, cfg.eps)
+    act = torch.empty(B, cfg.d_ff, dtype=hn.dtype, device="cuda")
+    cas.cascade_shard_gemm(None, x2, t["w_gate"], act, W_up=t["w_up"], epilogue=cas.EPI_SWIGLU)
+    out = torch.empty_like(hn)
+    cas.cascade_shard_gemm(None, act, t["w_down"], out, residual=h1, epilogue=cas.EPI_RESIDUAL)
+    torch.cuda.synchronize()
+    got = out.float().cpu().numpy().astype(np.float64)
+    for b in range(B):
+        want = orc.layer_direct(h_full[b], w, cfg, rows=np.array([N]))[0]
+        assert np.abs(got[b] - want).max() / np.abs(want).max() < tol
