@@ -13,6 +13,7 @@
 // lane group keeps a running (m, e, u~) per head (the same online recurrence as the fused prefill
 // kernel); the lane groups of a wavefront are merged with shuffles at the end.
 #include <cmath>
+#include <type_traits>
 #include "common.h"
 #include "device_utils.h"
 
@@ -29,6 +30,25 @@ struct DecodeParams {
     int32_t per_head;        // 1: one query head per workgroup (kv head = head / rep)
     int32_t rep;
 };
+
+// Sum over the LPR lanes that hold one row (LPR a power of two, lane groups aligned).  Inside a 16-lane row
+// the exchange is a data-parallel-primitive modifier on the add (no LDS traffic): lanes ^1 and ^2 by quad
+// permutes, then the two mirrors (a sum does not care that they reverse instead of swapping halves); wider
+// groups finish with cross-row shuffles.  Every lane of the group ends with the total.
+template <int LPR>
+__device__ __forceinline__ float group_sum(float s) {
+    auto dpp_add = [](float v, auto ctrl_tag) {
+        constexpr int ctrl = decltype(ctrl_tag)::value;
+        return v + __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), ctrl, 0xf, 0xf, true));
+    };
+    if (LPR >= 2) s = dpp_add(s, std::integral_constant<int, 0xB1>());     // quad_perm [1,0,3,2]
+    if (LPR >= 4) s = dpp_add(s, std::integral_constant<int, 0x4E>());     // quad_perm [2,3,0,1]
+    if (LPR >= 8) s = dpp_add(s, std::integral_constant<int, 0x141>());    // row_half_mirror
+    if (LPR >= 16) s = dpp_add(s, std::integral_constant<int, 0x140>());   // row_mirror
+#pragma unroll
+    for (int o = 16; o < LPR; o <<= 1) s += __shfl_xor(s, o, WAVE);
+    return s;
+}
 
 template <typename T, int REP, int LPR, int WPS>
 __global__ __launch_bounds__(256) void decode_attn_kernel(DecodeParams p) {
@@ -93,8 +113,7 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(DecodeParams p) {
                 float s = 0.f;
 #pragma unroll
                 for (int i = 0; i < VEC; ++i) s = fmaf(qf[h][i], (float)kv[i], s);
-#pragma unroll
-                for (int o = LPR / 2; o > 0; o >>= 1) s += __shfl_xor(s, o, WAVE);
+                s = group_sum<LPR>(s);
                 if (!valid) s = -INFINITY;
                 const float m_new = fmaxf(mrun[h], s);
                 const float m_sub = m_new == -INFINITY ? 0.f : m_new;
