@@ -27,15 +27,29 @@ template <> struct Elem<bf16_t> {
     static __device__ __forceinline__ void store(bf16_t *p, float v) { *p = (bf16_t)v; }
 };
 
+// Wavefront reductions; every lane gets the result.  Inside a 16-lane row the partner's value comes
+// through a data-parallel-primitive move (lanes ^1, ^2 by quad permutes, then the half-row and row
+// mirrors: for a symmetric reduction a reversal is as good as a swap) and costs no LDS traffic; the
+// four rows are combined with two cross-row shuffles.
+template <int CTRL>
+__device__ __forceinline__ float dpp_row_move(float v) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
+}
 __device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, WAVE));
-    return v;
+    v = fmaxf(v, dpp_row_move<0xB1>(v));      // quad_perm [1,0,3,2]
+    v = fmaxf(v, dpp_row_move<0x4E>(v));      // quad_perm [2,3,0,1]
+    v = fmaxf(v, dpp_row_move<0x141>(v));     // row_half_mirror
+    v = fmaxf(v, dpp_row_move<0x140>(v));     // row_mirror
+    v = fmaxf(v, __shfl_xor(v, 16, WAVE));
+    return fmaxf(v, __shfl_xor(v, 32, WAVE));
 }
 __device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, WAVE);
-    return v;
+    v += dpp_row_move<0xB1>(v);
+    v += dpp_row_move<0x4E>(v);
+    v += dpp_row_move<0x141>(v);
+    v += dpp_row_move<0x140>(v);
+    v += __shfl_xor(v, 16, WAVE);
+    return v + __shfl_xor(v, 32, WAVE);
 }
 
 // Sum over a 256-thread block; scratch holds >= 4 floats.  Every thread gets the result.
