@@ -245,3 +245,41 @@ def test_prefill_cache_then_decode_step_is_the_last_row_of_the_longer_sequence(c
     for b in range(B):
         want = orc.layer_direct(h_full[b], w, cfg, rows=np.array([N]))[0]
         assert np.abs(got[b] - want).max() / np.abs(want).max() < tol
+
+
+def test_cache_from_a_prefill_with_distinct_row_and_kv_shardings(cas):
+    """Row shards R (5) and key/value shards S = their 2-split (10): the cache slabs follow S."""
+    import torch
+    from cascade_inputs import make_hidden, make_layer_weights
+    cfg = _small_llama("bf16", 64)
+    N, B, alpha = cfg.seq_len, cfg.batch, cfg.n_shards
+    a = make_assignment("perm", N, alpha, 8)
+    a_kv = orc.m_split_assignment(a, alpha, 2)
+    beta = 2 * alpha
+    w, h = make_layer_weights(cfg), make_hidden(cfg)
+    plan = cas.cascade_plan_create_rs(B, N, alpha, a, beta, a_kv)
+    desc = cas.make_layer_desc(cfg, cas.ATTN_FUSED)
+    t = {k: cas.to_device(v, "bf16") for k, v in w.items()}
+    h_in = cas.to_device(h, "bf16")
+    h_out = torch.empty_like(h_in)
+    ws = cas.new_workspace(cas.cascade_layer_workspace_bytes(plan, desc))
+    cas.cascade_layer_forward(plan, desc, cas.make_layer_weights(t), h_in, h_out, ws)
+    sizes = np.bincount(a_kv, minlength=beta)
+    cap = int(sizes.max())
+    kc = torch.zeros((B, cfg.n_kv_heads, beta, cap, 64), dtype=h_in.dtype, device="cuda")
+    vc = torch.zeros_like(kc)
+    lens = torch.zeros((B, beta), dtype=torch.int32, device="cuda")
+    cas.cascade_layer_kv_to_cache(plan, desc, ws, kc, vc, lens)
+    torch.cuda.synchronize()
+    assert np.array_equal(lens.cpu().numpy(), np.tile(sizes, (B, 1)))
+    w64 = {k: v.astype(np.float64) for k, v in w.items()}
+    for b in range(B):
+        for k, S in enumerate(orc.shard_index_lists(a_kv, beta)):
+            _, k_ref, v_ref = orc.pre_pass(h[b, S].astype(np.float64), S, w64, cfg)
+            assert np.abs(kc[b, :, k, :len(S)].float().cpu().numpy() - k_ref).max() < 3e-2 * max(np.abs(k_ref).max(), 1)
+            assert np.abs(vc[b, :, k, :len(S)].float().cpu().numpy() - v_ref).max() < 3e-2 * max(np.abs(v_ref).max(), 1)
+    # a capacity below the largest shard is refused
+    small = torch.zeros((B, cfg.n_kv_heads, beta, cap - 1, 64), dtype=h_in.dtype, device="cuda")
+    with pytest.raises(cas.CascadeError) as ei:
+        cas.cascade_layer_kv_to_cache(plan, desc, ws, small, small.clone(), lens)
+    assert ei.value.status == cas.ESHAPE
