@@ -271,6 +271,10 @@ def check_partials(dtype, got, ref):
     ("bf16", 3, 3, 330, 64, 2, "contiguous", "packed"),        # MHA, shards larger than a tile
     ("bf16", 4, 1, 96, 128, 24, "ragged", "original"),         # tiny shards, some empty
     ("bf16", 4, 2, 512, 128, 8, "roundrobin", "original"),
+    ("bf16", 4, 2, 48, 64, 48, "roundrobin", "original"),      # singleton shards: e = 1, u~ = the one visible v
+    ("bf16", 4, 2, 130, 128, 1, "contiguous", "packed"),       # one shard: plain causal attention, ragged tail
+    ("bf16", 2, 2, 1, 64, 1, "contiguous", "original"),        # a single token
+    ("f32", 2, 1, 33, 16, 33, "roundrobin", "packed"),
 ])
 def test_partial_attn_matches_oracle(cas, dtype, H, Hkv, N, d, beta, kind, layout):
     B = 2
