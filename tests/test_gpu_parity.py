@@ -636,3 +636,48 @@ def test_layer_stack_matches_oracle_and_single_layer_calls(cas, cfg_name, n_laye
     ref = ref if io == "original" else ref[:, perm]
     tol = TOL[cfg.dtype] * (1 if cfg.dtype == "f32" else n_layers)      # bf16 roundings accumulate over the layers
     assert rel_err(got, ref) < tol
+
+
+def test_layer_forward_can_be_captured_in_a_hip_graph_and_replayed(cas):
+    """The layer forward allocates nothing and records no memset: a caller can capture it once and replay it.
+    Every replay (with eager work and synchronisations in between, and the output cleared first) reproduces the
+    eager result bit for bit, also after the input changed in place."""
+    import torch
+    cfg = SMALL_LLAMA
+    a = make_assignment("perm", cfg.seq_len, cfg.n_shards, 3)
+    w, h = make_layer_weights(cfg), make_hidden(cfg)
+    plan = cas.cascade_plan_create(cfg.batch, cfg.seq_len, cfg.n_shards, a)
+    desc = cas.make_layer_desc(cfg, cas.ATTN_FUSED)
+    t = {k: cas.to_device(v, cfg.dtype) for k, v in w.items()}
+    wts = cas.make_layer_weights(t)
+    h_in = cas.to_device(h, cfg.dtype)
+    h_out = torch.empty_like(h_in)
+    ws = cas.new_workspace(cas.cascade_layer_workspace_bytes(plan, desc))
+    step = lambda: cas.cascade_layer_forward(plan, desc, wts, h_in, h_out, ws)
+    step()
+    torch.cuda.synchronize()
+    ref = h_out.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()                                                     # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        step()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        h_out.fill_(7.0)
+        junk = torch.randn(256, 256, device="cuda") @ torch.randn(256, 256, device="cuda")   # eager work in between
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(h_out, ref), rep
+    h_in.mul_(0.5)                                                 # same buffers, new contents
+    step()
+    torch.cuda.synchronize()
+    ref2 = h_out.clone()
+    h_out.fill_(7.0)
+    g.replay()
+    torch.cuda.synchronize()
+    assert torch.equal(h_out, ref2) and not torch.equal(ref2, ref)
