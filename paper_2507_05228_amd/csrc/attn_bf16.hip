@@ -95,6 +95,7 @@ struct AttnBf16Params {
     int64_t o_ld;
     const int32_t *o_rowmap;
     int32_t hpb;          // heads per workgroup (1, 2 or 4)
+    int32_t gy;           // (batch, kv head, head block) combinations: blockIdx.x = query tile * gy + combination
 };
 
 // Optional timeline instrumentation (build with -DCASCADE_TRACE): lane 0 of wavefronts 0 and 4 of one
@@ -105,7 +106,7 @@ __device__ unsigned long long g_attn_trace[2 * ATRACE_ITERS * 8];
 __device__ int g_attn_trace_wg[2] = {0, 0};
 #define ATRACE(it, slot)                                                                                        \
     do {                                                                                                        \
-        if ((int)blockIdx.x == g_attn_trace_wg[0] && (int)blockIdx.y == g_attn_trace_wg[1] && (threadIdx.x & 255) == 0 && (it) < ATRACE_ITERS) \
+        if ((int)(blockIdx.x / p.gy) == g_attn_trace_wg[0] && (int)(blockIdx.x % p.gy) == g_attn_trace_wg[1] && (threadIdx.x & 255) == 0 && (it) < ATRACE_ITERS) \
             g_attn_trace[((threadIdx.x >> 8) * ATRACE_ITERS + (it)) * 8 + (slot)] = clock64();                    \
     } while (0)
 extern "C" __attribute__((visibility("default"))) int cascade_debug_attn_trace(unsigned long long *host, int n, int wgx, int wgy) {
@@ -182,14 +183,17 @@ __global__ __launch_bounds__(NWV * 64) void attn_bf16_kernel(AttnBf16Params p) {
     const int hsel = wave % hpb, rg = wave / hpb;
     const int rep = p.H / p.Hkv;
     const int hblocks = rep / hpb;
-    const int b = blockIdx.y / (p.Hkv * hblocks);
-    const int gh = blockIdx.y % (p.Hkv * hblocks);
+    // Workgroups of one query tile are neighbours in launch order (the kv heads fastest: with 8 of them each
+    // XCD serves one head's K and V), and the tiles come heaviest first.
+    const int q_tile = blockIdx.x / p.gy, by = blockIdx.x % p.gy;
+    const int b = by / (p.Hkv * hblocks);
+    const int gh = by % (p.Hkv * hblocks);
     const int g = gh / hblocks;
     const int h = g * rep + (gh % hblocks) * hpb + hsel;
     const int kk = p.fused ? 0 : blockIdx.z;
 
     const tile_cptr kvtiles = (tile_cptr)p.kvtiles;
-    const tile_cptr qtp = (tile_cptr)p.qtiles + blockIdx.x;
+    const tile_cptr qtp = (tile_cptr)p.qtiles + q_tile;
     const int q_row_start = qtp->row_start, q_n_rows = qtp->n_rows, q_pmax = qtp->pmax;
     const int wrow0 = rg * 16 * TQ;                    // first row of this wavefront inside the q tile
 
@@ -682,7 +686,9 @@ static int32_t launch_attn_cfg(const cascade_plan *p, const AttnArgs &a, hipStre
     if (kb >= (int64_t)OOB_OFF || vb >= (int64_t)OOB_OFF) return CASCADE_EUNSUPPORTED;
     k.k_bytes = (uint32_t)kb; k.vt_bytes = (uint32_t)vb;
     k.q_rowmap = a.q_rowmap;
-    k.qtiles = ql.dev; k.kvtiles = a.fused ? kl.dev_by_pmin : kl.dev_by_shard_pmin; k.kv_shard_first = kl.shard_first; k.n_kvtiles = kl.count;
+    // Under a causal mask a tile's work grows with its largest position: longest tiles first, so that a
+    // launch of several rounds does not end on a long workgroup.
+    k.qtiles = a.mask_kind == CASCADE_MASK_CAUSAL ? ql.dev_by_pmax_desc : ql.dev; k.kvtiles = a.fused ? kl.dev_by_pmin : kl.dev_by_shard_pmin; k.kv_shard_first = kl.shard_first; k.n_kvtiles = kl.count;
     k.pos_packed = p->pos_packed_d; k.pos_kv = kvp->pos_packed_d;
     k.B = a.B; k.H = a.H; k.Hkv = a.Hkv; k.N = N; k.S = S;
     k.scale_log2 = a.scale * LOG2E;
@@ -695,8 +701,9 @@ static int32_t launch_attn_cfg(const cascade_plan *p, const AttnArgs &a, hipStre
     static std::atomic<uint64_t> lds_ready{0};
     CASCADE_HIP_TRY(ensure_dynamic_lds((const void *)kern, lds, lds_ready));
     const int64_t gy = (int64_t)a.B * a.Hkv * (rep / hpb);
-    if (gy > 65535 || S > 65535) return CASCADE_EUNSUPPORTED;
-    dim3 grid(ql.count, (unsigned)gy, a.fused ? 1 : S);
+    if (gy * ql.count > INT32_MAX || S > 65535) return CASCADE_EUNSUPPORTED;
+    k.gy = (int32_t)gy;
+    dim3 grid((unsigned)(gy * ql.count), 1, a.fused ? 1 : S);
     hipLaunchKernelGGL(kern, grid, dim3(NWV * 64), lds, s, k);
     CASCADE_HIP_TRY(hipGetLastError());
     return CASCADE_OK;

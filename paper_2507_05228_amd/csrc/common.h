@@ -27,6 +27,7 @@ struct CascadeTileList {
     CascadeTile *dev = nullptr;           // packed order
     CascadeTile *dev_by_pmin = nullptr;   // the same tiles ordered by smallest position (stable)
     CascadeTile *dev_by_shard_pmin = nullptr;   // packed order of shards, each shard's tiles by smallest position
+    CascadeTile *dev_by_pmax_desc = nullptr;    // the same tiles ordered by largest position, descending (stable)
     int32_t *shard_first = nullptr;   // device: [n_shards + 1] first tile index of each shard
     int32_t *shard_first_host = nullptr;
 };

@@ -29,6 +29,7 @@ static void free_plan(cascade_plan *p) {
         if (t.dev) (void)hipFree(t.dev);
         if (t.dev_by_pmin) (void)hipFree(t.dev_by_pmin);
         if (t.dev_by_shard_pmin) (void)hipFree(t.dev_by_shard_pmin);
+        if (t.dev_by_pmax_desc) (void)hipFree(t.dev_by_pmax_desc);
         if (t.shard_first) (void)hipFree(t.shard_first);
         free(t.shard_first_host);
     }
@@ -89,6 +90,10 @@ static hipError_t build_tiles(cascade_plan *p, CascadeTileList &out, int granule
         std::stable_sort(sorted.begin() + first[j], sorted.begin() + first[j + 1],
                          [](const CascadeTile &x, const CascadeTile &y) { return x.pmin < y.pmin; });
     e = to_device(&out.dev_by_shard_pmin, sorted.data(), sorted.size());
+    if (e != hipSuccess) return e;
+    sorted = tiles;
+    std::stable_sort(sorted.begin(), sorted.end(), [](const CascadeTile &x, const CascadeTile &y) { return x.pmax > y.pmax; });
+    e = to_device(&out.dev_by_pmax_desc, sorted.data(), sorted.size());
     if (e != hipSuccess) return e;
     return to_device(&out.shard_first, first.data(), first.size());
 }
