@@ -464,6 +464,7 @@ __global__ __launch_bounds__(NWV * 64) void attn_bf16_kernel(AttnBf16Params p) {
         // have been skipped is cut by the element-wise compare instead), blocks [n_act, 4) contribute
         // exact zeros to P.
         const int n_act_new = (~skipm & 15) ? 32 - __builtin_clz(~skipm & 15) : 0;
+        maskm &= (1 << n_act_new) - 1;                 // blocks that are not computed need no compare
         if (n_pv == 2 && n_act_new == 4) {
             x_full_tile(prev_stage, sk);
         } else {
@@ -484,41 +485,43 @@ __global__ __launch_bounds__(NWV * 64) void attn_bf16_kernel(AttnBf16Params p) {
 
     // ================= Y(i): vector phase on the tile held in sacc
     auto vector_phase = [&]() {
-        // Key positions of this lane's accumulator rows (keys 16 kvb + 4 g4 + 0..3), from the tile's
-        // stage.  Read in assembly, wait included: the compiler would otherwise order a typed LDS read
-        // after every tile load in flight, and the registers are needed only from here on.
-        typedef __attribute__((ext_vector_type(4))) int i32x4;
-        i32x4 pkv[4];
-        {
-            const uint32_t pa = (uint32_t)(uintptr_t)(lds_void *)(smem + y_stage * STAGE + K_BYTES + V_BYTES) + 16 * g4;
-            asm volatile("ds_read_b128 %0, %4\n\tds_read_b128 %1, %4 offset:64\n\tds_read_b128 %2, %4 offset:128\n\t"
-                         "ds_read_b128 %3, %4 offset:192\n\ts_waitcnt lgkmcnt(0)"
-                         : "=&v"(pkv[0]), "=&v"(pkv[1]), "=&v"(pkv[2]), "=&v"(pkv[3])
-                         : "v"(pa)
-                         : "memory");
-        }
-        int pk[4][4];
-#pragma unroll
-        for (int kvb = 0; kvb < 4; ++kvb)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) pk[kvb][r] = pkv[kvb][r];
-        if (kn < KV_TILE) {                            // ragged tile: keys past its end are never visible
+        if (maskm) {                                   // some visible block needs the element-wise compare
+            // Key positions of this lane's accumulator rows (keys 16 kvb + 4 g4 + 0..3), from the tile's
+            // stage.  Read in assembly, wait included: the compiler would otherwise order a typed LDS read
+            // after every tile load in flight, and the registers are needed only from here on.
+            typedef __attribute__((ext_vector_type(4))) int i32x4;
+            i32x4 pkv[4];
+            {
+                const uint32_t pa = (uint32_t)(uintptr_t)(lds_void *)(smem + y_stage * STAGE + K_BYTES + V_BYTES) + 16 * g4;
+                asm volatile("ds_read_b128 %0, %4\n\tds_read_b128 %1, %4 offset:64\n\tds_read_b128 %2, %4 offset:128\n\t"
+                             "ds_read_b128 %3, %4 offset:192\n\ts_waitcnt lgkmcnt(0)"
+                             : "=&v"(pkv[0]), "=&v"(pkv[1]), "=&v"(pkv[2]), "=&v"(pkv[3])
+                             : "v"(pa)
+                             : "memory");
+            }
+            int pk[4][4];
 #pragma unroll
             for (int kvb = 0; kvb < 4; ++kvb)
 #pragma unroll
-                for (int r = 0; r < 4; ++r)
-                    if (kvb * 16 + 4 * g4 + r >= kn) pk[kvb][r] = INT_MAX;
-        }
-        // mask.  sacc[qb][kvb][r]: key 16 kvb + 4 g4 + r, query l16.  With no causal mask the limit is
-        // INT_MAX - 1, so only the keys past a ragged tile's end (position INT_MAX) are cut.
+                for (int r = 0; r < 4; ++r) pk[kvb][r] = pkv[kvb][r];
+            if (kn < KV_TILE) {                            // ragged tile: keys past its end are never visible
 #pragma unroll
-        for (int kvb = 0; kvb < 4; ++kvb) {
-            if (kvb >= n_act || !(maskm & (1 << kvb))) continue;
+                for (int kvb = 0; kvb < 4; ++kvb)
 #pragma unroll
-            for (int qb = 0; qb < TQ; ++qb)
+                    for (int r = 0; r < 4; ++r)
+                        if (kvb * 16 + 4 * g4 + r >= kn) pk[kvb][r] = INT_MAX;
+            }
+            // mask.  sacc[qb][kvb][r]: key 16 kvb + 4 g4 + r, query l16.  With no causal mask the limit is
+            // INT_MAX - 1, so only the keys past a ragged tile's end (position INT_MAX) are cut.
 #pragma unroll
-                for (int r = 0; r < 4; ++r)
-                    if (pk[kvb][r] > qlim[qb]) sacc[qb][kvb][r] = -INFINITY;
+            for (int kvb = 0; kvb < 4; ++kvb) {
+                if (kvb >= n_act || !(maskm & (1 << kvb))) continue;
+#pragma unroll
+                for (int qb = 0; qb < TQ; ++qb)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        if (pk[kvb][r] > qlim[qb]) sacc[qb][kvb][r] = -INFINITY;
+            }
         }
         // row statistics, exponentials, rescale of the running output (Algorithm 4's n, w, o online)
 #pragma unroll
