@@ -163,3 +163,59 @@ def test_lm_head_at_the_headline_shape_sampled_rows(cas):
     assert np.abs(got - want).max() / np.abs(want).max() < TOL["bf16"]
     assert np.array_equal(tok.cpu().numpy(), logits.float().argmax(dim=1).cpu().numpy())
     assert torch.equal(last[0], logits[cfg.seq_len - 1])          # same rows, same kernels: bit-identical
+
+
+def test_shard_gemm_at_the_largest_operand_the_32_bit_tile_offsets_allow(cas):
+    """The bf16 shard GEMM addresses its input through 32-bit byte offsets: an activation of one row below
+    2 GiB must work up to its last row (sampled rows against the oracle), one of exactly 2 GiB must be refused
+    with CASCADE_EUNSUPPORTED rather than wrap around."""
+    import torch
+    K, N = 8192, 192
+    M = (1 << 31) // (2 * K) - 1                       # 131071 rows: 2 GiB minus one row
+    g = torch.Generator(device="cuda").manual_seed(5)
+    X = torch.randn(M + 1, K, generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    W = (torch.randn(N, K, generator=g, device="cuda", dtype=torch.float32) * 0.05).to(torch.bfloat16)
+    Y = torch.full((M, N), 7.0, dtype=torch.bfloat16, device="cuda")
+    cas.cascade_shard_gemm(None, X[:M], W, Y)
+    rows = np.unique(np.concatenate([np.random.default_rng(6).integers(0, M, 48), [0, 1, M // 2, M - 2, M - 1]]))
+    x64 = X[torch.from_numpy(rows).cuda()].float().cpu().numpy().astype(np.float64)
+    ref = orc.linear(x64, W.float().cpu().numpy().astype(np.float64))
+    got = Y[torch.from_numpy(rows).cuda()].float().cpu().numpy().astype(np.float64)
+    assert np.abs(got - ref).max() / np.abs(ref).max() < TOL["bf16"]
+    assert float(Y.float().abs().max()) < 100.0 and not bool((Y == 7.0).all(dim=1).any())   # every row written
+    Y2 = torch.empty((M + 1, N), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(cas.CascadeError) as ei:
+        cas.cascade_shard_gemm(None, X, W, Y2)
+    assert ei.value.status == cas.EUNSUPPORTED
+
+
+def test_lm_head_with_a_vocabulary_matrix_above_2_gib_is_cut_into_ranges(cas):
+    """A vocabulary projection of more than 2 GiB (300000 x 4096 bf16 = 2.46 GB): the library walks it as
+    row ranges of less than 2 GiB each.  Last-row mode; logits on a sample of vocabulary entries from every
+    range, and across the cut, against the oracle; every logit written."""
+    import torch
+    cfg = CONFIGS["C3"].with_(name="bigvocab", seq_len=96, n_shards=3, index=55)
+    V, D = 300000, cfg.d_model
+    cut = ((0x7FFF0000 // (D * 2)) // 256) * 256      # rows per range the library uses (262016 at D = 4096)
+    assert cut < V < 2 * cut
+    a = make_assignment("perm", cfg.seq_len, cfg.n_shards, 3)
+    h = make_hidden(cfg)
+    gen = torch.Generator(device="cuda").manual_seed(17)
+    w = (torch.randn(V, D, generator=gen, device="cuda", dtype=torch.float32) * 0.02).to(torch.bfloat16)
+    gain = (1.0 + 0.1 * torch.randn(D, generator=gen, device="cuda", dtype=torch.float32)).to(torch.bfloat16)
+    plan = cas.cascade_plan_create(cfg.batch, cfg.seq_len, cfg.n_shards, a)
+    hd = cas.to_device(h, cfg.dtype)
+    desc = cas.LmHeadDesc(cas.BF16, D, V, cas.NORM_RMSNORM, cfg.eps, cas.LM_LAST_ROW, cas.ROWS_ORIGINAL, cas.ROWS_ORIGINAL)
+    ws = cas.new_workspace(cas.cascade_lm_head_workspace_bytes(plan, desc))
+    logits = torch.full((cfg.batch, V), 7.0, dtype=torch.bfloat16, device="cuda")
+    cas.cascade_lm_head(plan, desc, hd, gain, None, w, logits, ws)
+    torch.cuda.synchronize()
+    cols = np.unique(np.concatenate([np.random.default_rng(8).integers(0, V, 200),
+                                     [0, cut - 2, cut - 1, cut, cut + 1, V - 2, V - 1]]))
+    idx = torch.from_numpy(cols).cuda()
+    head = {"norm_g": gain.float().cpu().numpy().astype(np.float64),
+            "w_vocab": w[idx].float().cpu().numpy().astype(np.float64)}
+    want = orc.lm_head_direct(h[0][cfg.seq_len - 1:cfg.seq_len], head, cfg)[0]
+    got = logits[0, idx].float().cpu().numpy().astype(np.float64)
+    assert np.abs(got - want).max() / np.abs(want).max() < TOL["bf16"]
+    assert int((logits == 7.0).sum()) < V // 100       # the fill value survives only where a logit rounds to it
