@@ -219,3 +219,24 @@ def test_lm_head_with_a_vocabulary_matrix_above_2_gib_is_cut_into_ranges(cas):
     got = logits[0, idx].float().cpu().numpy().astype(np.float64)
     assert np.abs(got - want).max() / np.abs(want).max() < TOL["bf16"]
     assert int((logits == 7.0).sum()) < V // 100       # the fill value survives only where a logit rounds to it
+
+
+def test_long_sequence_many_shards_sampled_rows(cas):
+    """65536 tokens in 512 round-robin shards through the fused layer (1024 key/value tiles per query tile walk,
+    a 512-way running merge): sampled rows, the first and the last token included, against the oracle."""
+    cfg = CONFIGS["C4"].with_(name="long-64k", d_model=1024, n_heads=8, n_kv_heads=2, head_dim=128, d_ff=2048,
+                              seq_len=65536, n_shards=512, index=56)
+    a = make_assignment(cfg.assignment, cfg.seq_len, cfg.n_shards, 56)
+    w, h = make_layer_weights(cfg), make_hidden(cfg)
+    print("[64k] inputs ready", flush=True)
+    _, _, _, h_out = run_layer(cas, cfg, a, w, h, cas.ATTN_FUSED)
+    out = h_out.float().cpu().numpy().astype(np.float64)
+    assert np.isfinite(out).all()
+    print("[64k] gpu done", flush=True)
+    rows = np.sort(np.random.default_rng(57).choice(cfg.seq_len, size=12, replace=False))
+    rows[0], rows[-1] = 0, cfg.seq_len - 1
+    w64 = {k: v.astype(np.float64) for k, v in w.items()}
+    ref = orc.layer_direct(h[0], w64, cfg, rows=rows)
+    err = np.abs(out[0][rows] - ref).max() / np.abs(ref).max()
+    print(f"[64k] sampled-row max rel err {err:.3e}", flush=True)
+    assert err < TOL["bf16"]
