@@ -173,6 +173,30 @@ def test_shard_gemm_every_mfma_tile_variant(cas, M, N, swiglu, epi):
     assert rel_err(host(Y), ref) < TOL["bf16"]
 
 
+@pytest.mark.parametrize("epi", ["plain", "bias", "bias_residual"])
+def test_shard_gemm_256_wide_tiles_one_wavefront_per_simd(cas, epi):
+    """Several rounds of 256 x 256 tiles over a long reduction (the o projection / FFN down of a long prefill):
+    the launcher then takes the one-wavefront schedule with 256 accumulator registers.  Ragged M and N."""
+    import torch
+    M, N, K = 8000, 4000, 2048
+    rng = np.random.default_rng(77)
+    x, w = rand(rng, (M, K), "bf16"), rand(rng, (N, K), "bf16", 0.05)
+    X, W = dev(cas, x, "bf16"), dev(cas, w, "bf16")
+    ref = orc.linear(x.astype(np.float64), w.astype(np.float64))
+    kw, ep = {}, 0
+    if "bias" in epi:
+        b = rand(rng, (N,), "bf16", 0.3)
+        kw["bias"] = dev(cas, b, "bf16"); ep |= cas.EPI_BIAS
+        ref = ref + b.astype(np.float64)
+    if "residual" in epi:
+        r = rand(rng, (M, N), "bf16")
+        kw["residual"] = dev(cas, r, "bf16"); ep |= cas.EPI_RESIDUAL
+        ref = ref + r.astype(np.float64)
+    Y = torch.full((M, N), 7.0, dtype=X.dtype, device="cuda")
+    cas.cascade_shard_gemm(None, X, W, Y, epilogue=ep, **kw)
+    assert rel_err(host(Y), ref) < TOL["bf16"]
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_shard_gemm_rope_uses_original_positions(cas, dtype):
     import torch
