@@ -838,11 +838,12 @@ int32_t launch_gemm_bf16_v2(const GemmArgs &a, hipStream_t s) {
         const int64_t best = std::min(c192, std::min(c224, c256));
         // 256 columns: the one-wavefront schedule when a CU works through several tiles of a long reduction and
         // the epilogue is light (its 256 accumulators leave the GELU code no registers); measured on
-        // 8192 x 4096 x 4096 with residual 1.10 against 0.98 PFLOP/s, x 14336 1.27 against 1.14.  At equal cost it
-        // goes before the narrower tiles: fewer tile-load instructions per MFMA.
+        // 8192 x 4096 x 4096 with residual 1.10 against 0.98 PFLOP/s, x 14336 1.27 against 1.14.  It goes before
+        // the narrower tiles up to a 4 % higher cost: fewer tile-load instructions and operand reads per MFMA
+        // (8192 x 32000 x 4096: 1.24 against 1.11 PFLOP/s for 192 columns at 1.6 % more rounds x width).
         const bool solo256 = n_tiles(256) > cus && a.K >= 2048 &&
                              !(a.epilogue & (CASCADE_EPI_GELU_ERF | CASCADE_EPI_GELU_TANH));
-        if (c256 == best && solo256) return launch_cfg2<256, 256, 2, 2, 64, 2, false, false>(a, s);
+        if (c256 * 100 <= best * 104 && solo256) return launch_cfg2<256, 256, 2, 2, 64, 2, false, false>(a, s);
         if (c192 == best && (solo192 || c192 < c224))
             return solo192 ? launch_cfg2<256, 192, 2, 2, 64, 2, false, false>(a, s)
                            : launch_cfg2<256, 192, 4, 2, 64, 2, false, false>(a, s);
