@@ -240,30 +240,25 @@ __device__ __forceinline__ void gemm_epilogue_tile(const Gemm2Params &p, f32x4 (
 #pragma unroll
         for (int j = 0; j < TNO; ++j) {
             const int tc = wc0 + 16 * j + c4;              // column inside the tile
-            const int nleft = seg_rows - (nloc0 + tc);     // columns of the segment from here on
+            // the segment's width and tc are multiples of 4: these 4 columns are all inside the segment or all
+            // outside (then their values are never stored and need neither bias nor residual)
+            const bool inside = nloc0 + tc < seg_rows;
             f32x4 v = acc[i][j];
             if (SWIGLU) {
 #pragma unroll
                 for (int x = 0; x < 4; ++x) v[x] = silu_fast(v[x]) * acc[i][j + TNO][x];
             } else if constexpr (GENERAL) {
-                if (bias)
+                if (bias && inside)
 #pragma unroll
-                    for (int x = 0; x < 4; ++x)
-                        if (x < nleft) v[x] += (float)bias[nloc0 + tc + x];
+                    for (int x = 0; x < 4; ++x) v[x] += (float)bias[nloc0 + tc + x];
                 if (act)
 #pragma unroll
                     for (int x = 0; x < 4; ++x) v[x] = apply_act(v[x], flags);
             }
-            if (rrow) {                                    // added before the one rounding to bf16
-                if (nleft >= 4) {
-                    const bf16x4 rv = *(const bf16x4 *)(rrow + tc);
+            if (rrow && inside) {                          // added before the one rounding to bf16
+                const bf16x4 rv = *(const bf16x4 *)(rrow + tc);
 #pragma unroll
-                    for (int x = 0; x < 4; ++x) v[x] += (float)rv[x];
-                } else {
-#pragma unroll
-                    for (int x = 0; x < 4; ++x)
-                        if (x < nleft) v[x] += (float)rrow[tc + x];
-                }
+                for (int x = 0; x < 4; ++x) v[x] += (float)rv[x];
             }
             const bf16x4 o = {(bf16_t)v[0], (bf16_t)v[1], (bf16_t)v[2], (bf16_t)v[3]};
             *(bf16x4 *)(smem + row * PITCH + tc * 2) = o;
