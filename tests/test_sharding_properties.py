@@ -31,7 +31,7 @@ def _sequence_from_definition(N, start, width, delta):
 params = st.tuples(st.integers(1, 400), st.integers(1, 12), st.integers(1, 96)).filter(lambda p: p[1] <= p[2])
 
 
-@settings(max_examples=150, deadline=None)
+@settings(max_examples=150, deadline=None, derandomize=True)
 @given(params)
 def test_every_shard_is_a_c_delta_sequence_and_the_shards_partition_the_tokens(p):
     N, c, delta = p
@@ -50,7 +50,7 @@ def test_every_shard_is_a_c_delta_sequence_and_the_shards_partition_the_tokens(p
         assert (seen == 1).all(), name
 
 
-@settings(max_examples=100, deadline=None)
+@settings(max_examples=100, deadline=None, derandomize=True)
 @given(params)
 def test_gap_between_the_clusters_of_a_shard(p):
     """From the last index of a cluster to the first of the next one: delta - c + 1 (full clusters)."""
@@ -67,7 +67,7 @@ msplit_params = st.tuples(st.integers(1, 300), st.integers(1, 8), st.integers(1,
     lambda p: p[1] <= p[2])
 
 
-@settings(max_examples=150, deadline=None)
+@settings(max_examples=150, deadline=None, derandomize=True)
 @given(msplit_params)
 def test_m_split_partitions_every_row_shard_into_interleaved_pieces(p):
     N, c, delta, m = p
@@ -86,7 +86,7 @@ def test_m_split_partitions_every_row_shard_into_interleaved_pieces(p):
             assert max(sizes) - min(sizes) <= 1
 
 
-@settings(max_examples=100, deadline=None)
+@settings(max_examples=100, deadline=None, derandomize=True)
 @given(st.tuples(st.integers(2, 8), st.integers(2, 8), st.integers(1, 6)))
 def test_with_m_equal_c_the_pieces_are_delta_apart_and_no_attn_node_sees_three_neighbours(p):
     """Section 6.4: with m = c (and c dividing delta) the elements of R_{i,x} are delta positions
