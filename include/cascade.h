@@ -229,6 +229,26 @@ CASCADE_API int32_t cascade_partial_attn(const cascade_plan *plan, const cascade
                              float *m, float *e, float *u,
                              void *workspace, size_t workspace_bytes, void *stream);
 
+/* cascade_partial_attn for callers that cannot allocate device memory or hand over
+ * a workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, results and errors as cascade_partial_attn
+ * (bit-identical outputs: the same kernels run); the scratch memory of the bf16
+ * kernels is a static device array of CASCADE_STATIC_SCRATCH_BYTES that every GPU
+ * the library runs on holds until the process ends.  The call allocates nothing and
+ * frees nothing.  A problem whose cascade_partial_attn_workspace_bytes exceeds
+ * CASCADE_STATIC_SCRATCH_BYTES (36 MiB) is refused with CASCADE_EWORKSPACE.  The
+ * bf16 kernels need 2 B H_KV d (N + N') bytes, N' = 64 x the number of 64-key
+ * tiles of the key/value shards (N rounded up shard by shard); the limit covers
+ * 8 kv heads of 128 at N = 8192 in 64-row-aligned shards.  fp32 needs none.
+ * All calls on one GPU share that GPU's array: calls that overlap in time on the
+ * same GPU (different streams or threads) race and must be serialised by the
+ * caller.  Nothing in the array needs to start at zero; every call rewrites what
+ * it reads.                                                                      */
+#define CASCADE_STATIC_SCRATCH_BYTES (36u << 20)
+CASCADE_API int32_t cascade_partial_attn_static(const cascade_plan *plan, const cascade_attn_desc *desc,
+                                    const void *q, const void *k, const void *v,
+                                    float *m, float *e, float *u, void *stream);
+
 /* The merge of Algorithm 4 (Post-Pass): n = max_k m_k; w = sum_k exp(m_k - n) e_k;
  * o = sum_k exp(m_k - n) e_k u_k / w (u~ form: sum_k exp(m_k - n) u~_k / w).
  * o [B, N, H*d] in desc->dtype, rows per desc->row_layout; lse_out (optional,

@@ -28,7 +28,7 @@ EPI_BIAS, EPI_GELU_ERF, EPI_GELU_TANH, EPI_SWIGLU, EPI_ROPE, EPI_RESIDUAL = 1, 2
 EXPORTS = ["cascade_plan_create", "cascade_plan_create_rs", "cascade_plan_maps", "cascade_plan_maps_host",
            "cascade_plan_kv_maps_host", "cascade_cdelta_assignment", "cascade_m_split", "cascade_comm_cost", "cascade_plan_destroy",
            "cascade_last_hip_error", "cascade_shard_gemm", "cascade_partial_attn_workspace_bytes",
-           "cascade_partial_attn", "cascade_lse_merge", "cascade_layer_workspace_bytes",
+           "cascade_partial_attn", "cascade_partial_attn_static", "cascade_lse_merge", "cascade_layer_workspace_bytes",
            "cascade_layer_forward", "cascade_layer_forward_staged", "cascade_layer_partials",
            "cascade_layer_stack_workspace_bytes", "cascade_layer_stack_forward",
            "cascade_lm_head_workspace_bytes", "cascade_lm_head", "cascade_greedy_token", "cascade_layer_kv_to_cache", "cascade_norm",
@@ -122,6 +122,8 @@ def load_library():
     lib.cascade_partial_attn_workspace_bytes.restype = C.c_size_t
     lib.cascade_partial_attn.argtypes = [VP, P(AttnDesc), VP, VP, VP, VP, VP, VP, VP, C.c_size_t, VP]
     lib.cascade_partial_attn.restype = I32
+    lib.cascade_partial_attn_static.argtypes = [VP, P(AttnDesc), VP, VP, VP, VP, VP, VP, VP]
+    lib.cascade_partial_attn_static.restype = I32
     lib.cascade_lse_merge.argtypes = [VP, P(AttnDesc), VP, VP, VP, VP, VP, VP]
     lib.cascade_lse_merge.restype = I32
     lib.cascade_layer_workspace_bytes.argtypes = [VP, P(LayerDesc)]
@@ -333,6 +335,20 @@ def cascade_partial_attn(plan, q, k, v, m, e, u, n_heads, n_kv_heads, head_dim, 
     st = lib.cascade_partial_attn(plan.handle, C.byref(d), _ptr(q), _ptr(k), _ptr(v), _ptr(m), _ptr(e), _ptr(u),
                                   _ptr(workspace), ws_bytes, _stream(stream))
     _check(st, "cascade_partial_attn")
+
+
+STATIC_SCRATCH_BYTES = 36 << 20
+
+
+def cascade_partial_attn_static(plan, q, k, v, m, e, u, n_heads, n_kv_heads, head_dim, scale,
+                                row_layout=ROWS_ORIGINAL, u_mode=U_UNNORMALISED, q_strides=None, kv_strides=None,
+                                stream=None):
+    """cascade_partial_attn with the library's static device scratch instead of a workspace."""
+    lib = load_library()
+    d = _attn_desc(q, n_heads, n_kv_heads, head_dim, scale, row_layout, u_mode, q_strides, kv_strides)
+    st = lib.cascade_partial_attn_static(plan.handle, C.byref(d), _ptr(q), _ptr(k), _ptr(v), _ptr(m), _ptr(e), _ptr(u),
+                                         _stream(stream))
+    _check(st, "cascade_partial_attn_static")
 
 
 def cascade_lse_merge(plan, m, e, u, o, n_heads, n_kv_heads, head_dim, row_layout=ROWS_PACKED,

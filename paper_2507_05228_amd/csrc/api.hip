@@ -116,6 +116,44 @@ extern "C" int32_t cascade_partial_attn(const cascade_plan *plan, const cascade_
     return d->dtype == CASCADE_BF16 ? launch_attn_bf16(plan, a, s) : launch_attn_f32(plan, a, s);
 }
 
+// ---------------------------------------------------------------------------- partial attention without a workspace
+// For callers that cannot allocate (HIP graph capture, tight serving loops): the scratch memory the bf16
+// kernels need (V^T in tile order, K gathered into packed order) lives in a static device array of this
+// code object instead of a caller's workspace.  Every GPU the library runs on holds its own copy of the
+// array at its own address, looked up once per device.
+static __device__ __align__(256) unsigned char scratch[CASCADE_STATIC_SCRATCH_BYTES];
+
+static int32_t static_scratch_for_current_device(void **out) {
+    constexpr int MAX_DEV = 64;
+    static std::atomic<void *> ptrs[MAX_DEV];
+    int dev = 0;
+    CASCADE_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= MAX_DEV) return CASCADE_EUNSUPPORTED;
+    void *p = ptrs[dev].load(std::memory_order_acquire);
+    if (!p) {                                      // the address is per device and fixed: a racing first call stores the same value
+        CASCADE_HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return CASCADE_EHIP;
+        ptrs[dev].store(p, std::memory_order_release);
+    }
+    *out = p;
+    return CASCADE_OK;
+}
+
+extern "C" int32_t cascade_partial_attn_static(const cascade_plan *plan, const cascade_attn_desc *d, const void *q,
+                                               const void *k, const void *v, float *m, float *e, float *u,
+                                               void *stream) {
+    int32_t st = check_attn_desc(plan, d);
+    if (st != CASCADE_OK) return st;
+    const size_t need = cascade_partial_attn_workspace_bytes(plan, d);
+    if (need > (size_t)CASCADE_STATIC_SCRATCH_BYTES) return CASCADE_EWORKSPACE;
+    void *ws = nullptr;
+    if (need) {
+        st = static_scratch_for_current_device(&ws);
+        if (st != CASCADE_OK) return st;
+    }
+    return cascade_partial_attn(plan, d, q, k, v, m, e, u, ws, need ? (size_t)CASCADE_STATIC_SCRATCH_BYTES : 0, stream);
+}
+
 extern "C" int32_t cascade_lse_merge(const cascade_plan *plan, const cascade_attn_desc *d, const float *m,
                                      const float *e, const float *u, void *o, float *lse_out, void *stream) {
     int32_t st = check_attn_desc(plan, d);
