@@ -6,8 +6,9 @@
  * (Algorithm 2, the projection that closes Algorithm 4, the MLP step that closes Algorithm 1), partial
  * attention for every (query-shard, key/value-shard) pair with row maxima m and
  * subtract-max exponential sums e (Algorithm 3), and the log-sum-exp merge of
- * the partials (the merge steps of Algorithm 4).  This build uses R = S (one token to
- * shard assignment for hiddens, queries and keys/values).
+ * the partials (the merge steps of Algorithm 4).  A plan carries the sharding R of the
+ * hidden rows and, optionally, a distinct sharding S of queries / keys / values
+ * (cascade_plan_create_rs); cascade_plan_create sets S = R.
  *
  * Conventions
  *  - Every function returns an int32 status (CASCADE_OK = 0).  Nothing aborts,
@@ -158,7 +159,36 @@ CASCADE_API int32_t cascade_comm_cost(int32_t n_row_shards, int32_t n_kv_shards,
                           int32_t bytes_per_value, int32_t head_dim, int32_t n_heads, int32_t n_kv_heads,
                           int64_t seq_len, int64_t *stage_a_bytes, int64_t *stage_b_bytes, int64_t *rounds);
 
+/* Equation 2 (Theoretical Costs): communication time of one layer under perfect
+ * parallel transport, node bandwidth B (bytes/s) and inter-node latency tau (s):
+ *   stage_a_s = tau + beta F d (H + 2 H_KV) / B * max_i |R_i|
+ *   stage_b_s = tau + F (d + 2) H / B * max_j |S_j|
+ *   total_s   = stage_a_s + stage_b_s
+ * With a plan, beta = its key/value shard count and the two maxima are taken from its
+ * partitions (n_kv_shards, max_row_shard, max_kv_shard are then ignored); with
+ * plan == NULL the three are the caller's.  Out pointers are HOST doubles, any may be
+ * NULL.  Host only.  Errors: EINVAL (non-positive sizes, negative or NaN latency,
+ * bandwidth not above zero).                                                      */
+CASCADE_API int32_t cascade_comm_time(const cascade_plan *plan, int32_t n_kv_shards, int32_t max_row_shard,
+                          int32_t max_kv_shard, int32_t bytes_per_value, int32_t head_dim,
+                          int32_t n_heads, int32_t n_kv_heads, double latency_s,
+                          double bandwidth_bytes_per_s, double *stage_a_s, double *stage_b_s,
+                          double *total_s);
+
 CASCADE_API void cascade_plan_destroy(cascade_plan *plan);
+
+/* Bytes of caller-owned workspace an entry point needs, by operation: desc points to
+ * the descriptor type of that operation; flags is the layer count for
+ * CASCADE_OP_LAYER_STACK and ignored otherwise.  Operations without a workspace
+ * (shard GEMM, LSE merge, decode, norm) and invalid descriptors give 0.  The
+ * per-operation queries below return the same numbers.                          */
+#define CASCADE_OP_SHARD_GEMM     0   /* cascade_gemm_desc: no workspace               */
+#define CASCADE_OP_PARTIAL_ATTN   1   /* cascade_attn_desc                             */
+#define CASCADE_OP_LSE_MERGE      2   /* cascade_attn_desc: no workspace               */
+#define CASCADE_OP_LAYER_FORWARD  3   /* cascade_layer_desc                            */
+#define CASCADE_OP_LAYER_STACK    4   /* cascade_layer_desc, flags = n_layers          */
+#define CASCADE_OP_LM_HEAD        5   /* cascade_lm_head_desc                          */
+CASCADE_API size_t cascade_workspace_bytes(const cascade_plan *plan, const void *desc, int32_t op, int32_t flags);
 
 /* HIP error code of the last CASCADE_EHIP on this thread (0 if none).          */
 CASCADE_API int32_t cascade_last_hip_error(void);
@@ -260,8 +290,8 @@ CASCADE_API int32_t cascade_lse_merge(const cascade_plan *plan, const cascade_at
 /* ------------------------------------------------------------------ whole layer
  * Algorithm 1 on one GPU: h1 = h + o_proj(attention(norm1(h))),
  * h_out = h1 + FFN(norm2(h1)); pre-norm block.                                  */
-/* Where the two norms of the block sit (the paper leaves the block's internals to
- * the model: "layer normalization if necessary", "Residual and MLP"):
+/* Where the two norms of the block sit (the Pre-Pass subsection and the last step of
+ * Algorithm 1 leave the block's internals to the model):
  *   PRE :  h1 = h + Attn(norm1(h));      out = h1 + MLP(norm2(h1))      (GPT / Llama)
  *   POST:  h1 = norm1(h + Attn(h));      out = norm2(h1 + MLP(h1))      (BERT, the
  *          model of the paper's timing runs; use a plan with CASCADE_MASK_NONE for
@@ -375,6 +405,14 @@ CASCADE_API int32_t cascade_layer_forward_staged(const cascade_plan *plan, const
 CASCADE_API int32_t cascade_layer_partials(const cascade_plan *plan, const cascade_layer_desc *desc,
                                void *workspace, float **m, float **e, float **u);
 
+/* After a cascade_layer_forward (either attention mode): device pointer into the
+ * workspace it used, to the merged attention output o [B * N, H * d] in desc->dtype,
+ * PACKED rows (the input of the o projection; Algorithm 4 before its last step).
+ * Exposed so that the fused path can be checked at the same point as
+ * cascade_lse_merge's output.  Errors: EINVAL, EUNSUPPORTED.                     */
+CASCADE_API int32_t cascade_layer_attention_output(const cascade_plan *plan, const cascade_layer_desc *desc,
+                                       void *workspace, void **o);
+
 /* ------------------------------------------------------------------ KV-cache decode
  * Cost Optimizations appendix ("Caching"): in single-token generation only the
  * newest token's query row is attended, by AttnNode_jk for every kv shard k,
@@ -397,8 +435,8 @@ CASCADE_API int32_t cascade_decode_partial_attn(const cascade_attn_desc *desc, i
                                     const void *q, const void *k_cache, const void *v_cache,
                                     float *m, float *e, float *u, void *stream);
 
-/* Normalisation of `rows` rows of D values (the "layer normalization if
- * necessary" of the Pre-Pass subsection, exposed for callers that compose a
+/* Normalisation of `rows` rows of D values (the optional normalisation step of
+ * the Pre-Pass subsection, exposed for callers that compose a
  * single-token step themselves): y = norm(x) * gain (+ bias), statistics in
  * fp32.  x, y [rows, D], gain [D], bias [D] or NULL: device, dtype; x == y allowed.
  * Errors: EINVAL, EUNSUPPORTED, EHIP.                                            */

@@ -169,7 +169,7 @@ def _split_heads(x, n_heads, d):
 
 # --------------------------------------------------------------------------- Algorithm 2
 def pre_pass(h_rows, pos_rows, w, cfg):
-    """Algorithm 2 on one hidden shard: norm ("if necessary": not in a post-norm block), q/k/v
+    """Algorithm 2 on one hidden shard: norm (absent in a post-norm block), q/k/v
     projection, rotary embedding."""
     post = getattr(cfg, "norm_placement", "pre") == "post"
     x = h_rows if post else norm(h_rows, cfg.norm, w["norm1_g"], w.get("norm1_b"), cfg.eps)
@@ -503,6 +503,21 @@ def comm_bytes(beta, F, d, H, Hkv, N):
     stage_a = beta * F * d * (H + 2 * Hkv) * N
     stage_b = beta * F * (d + 2) * H * N
     return stage_a + stage_b, stage_a, stage_b
+
+
+def comm_time(row_lists, kv_lists, F, d, H, Hkv, tau, bandwidth):
+    """Equation 2 from its derivation (Communication Analysis appendix), node by node: with perfect
+    parallel transport each stage lasts one latency plus the time of the node that sends most.
+    Stage A: CompNode_i sends every one of its |R_i| rows of q (H d values) and of k, v (2 H_KV d
+    values) to beta AttnNodes.  Stage B: AttnNode_jk sends the |S_j| rows of u (H d values) and of m, e
+    (2 H values) it computed.  row_lists / kv_lists: the index lists of {R_i} and {S_j}.
+    Returns (total seconds, stage A seconds, stage B seconds)."""
+    beta = len(kv_lists)
+    sent_a = [beta * len(R) * (H * d + 2 * Hkv * d) * F for R in row_lists]        # bytes leaving CompNode_i
+    sent_b = [len(kv_lists[j]) * (H * d + 2 * H) * F for j in range(beta) for _k in range(beta)]   # AttnNode_jk
+    t_a = tau + max(sent_a) / bandwidth
+    t_b = tau + max(sent_b) / bandwidth
+    return t_a + t_b, t_a, t_b
 
 
 def overhead_ops(H, N, d):

@@ -26,7 +26,8 @@ NORM_PRE, NORM_POST = 0, 1
 EPI_BIAS, EPI_GELU_ERF, EPI_GELU_TANH, EPI_SWIGLU, EPI_ROPE, EPI_RESIDUAL = 1, 2, 4, 8, 16, 32
 
 EXPORTS = ["cascade_plan_create", "cascade_plan_create_rs", "cascade_plan_maps", "cascade_plan_maps_host",
-           "cascade_plan_kv_maps_host", "cascade_cdelta_assignment", "cascade_m_split", "cascade_comm_cost", "cascade_plan_destroy",
+           "cascade_plan_kv_maps_host", "cascade_cdelta_assignment", "cascade_m_split", "cascade_comm_cost", "cascade_comm_time",
+           "cascade_workspace_bytes", "cascade_layer_attention_output", "cascade_plan_destroy",
            "cascade_last_hip_error", "cascade_shard_gemm", "cascade_partial_attn_workspace_bytes",
            "cascade_partial_attn", "cascade_partial_attn_static", "cascade_lse_merge", "cascade_layer_workspace_bytes",
            "cascade_layer_forward", "cascade_layer_forward_staged", "cascade_layer_partials",
@@ -108,6 +109,13 @@ def load_library():
     lib.cascade_m_split.restype = I32
     lib.cascade_comm_cost.argtypes = [I32, I32, I32, I32, I32, I32, I32, C.c_int64, P(C.c_int64), P(C.c_int64), P(C.c_int64)]
     lib.cascade_comm_cost.restype = I32
+    F64 = C.c_double
+    lib.cascade_comm_time.argtypes = [VP, I32, I32, I32, I32, I32, I32, I32, F64, F64, P(F64), P(F64), P(F64)]
+    lib.cascade_comm_time.restype = I32
+    lib.cascade_workspace_bytes.argtypes = [VP, VP, I32, I32]
+    lib.cascade_workspace_bytes.restype = C.c_size_t
+    lib.cascade_layer_attention_output.argtypes = [VP, P(LayerDesc), VP, P(VP)]
+    lib.cascade_layer_attention_output.restype = I32
     lib.cascade_plan_maps.argtypes = [VP, P(VP), P(VP), P(VP)]
     lib.cascade_plan_maps.restype = I32
     lib.cascade_plan_maps_host.argtypes = [VP, P(P(I32)), P(P(I32)), P(P(I32))]
@@ -270,6 +278,27 @@ def cascade_comm_cost(n_row_shards, n_kv_shards, bytes_per_value, head_dim, n_he
     _check(lib.cascade_comm_cost(n_row_shards, n_kv_shards, int(bool(m_split_scheme)), bytes_per_value, head_dim, n_heads,
                                  n_kv_heads, seq_len, C.byref(a), C.byref(b), C.byref(r)), "cascade_comm_cost")
     return a.value, b.value, r.value
+
+
+def cascade_comm_time(bytes_per_value, head_dim, n_heads, n_kv_heads, latency_s, bandwidth_bytes_per_s, plan=None,
+                      n_kv_shards=0, max_row_shard=0, max_kv_shard=0):
+    """(total_s, stage_a_s, stage_b_s) of Equation 2; shard sizes from `plan` or given explicitly."""
+    lib = load_library()
+    a, b, t = C.c_double(), C.c_double(), C.c_double()
+    _check(lib.cascade_comm_time(None if plan is None else plan.handle, n_kv_shards, max_row_shard, max_kv_shard,
+                                 bytes_per_value, head_dim, n_heads, n_kv_heads, latency_s, bandwidth_bytes_per_s,
+                                 C.byref(a), C.byref(b), C.byref(t)), "cascade_comm_time")
+    return t.value, a.value, b.value
+
+
+OP_SHARD_GEMM, OP_PARTIAL_ATTN, OP_LSE_MERGE, OP_LAYER_FORWARD, OP_LAYER_STACK, OP_LM_HEAD = range(6)
+
+
+def cascade_workspace_bytes(plan, desc, op, flags=0):
+    """Workspace bytes of operation `op` (OP_*) for its descriptor structure."""
+    lib = load_library()
+    return lib.cascade_workspace_bytes(plan.handle if plan is not None else None,
+                                       None if desc is None else C.cast(C.byref(desc), C.c_void_p), op, flags)
 
 
 def cascade_plan_maps(plan):
@@ -448,6 +477,20 @@ def cascade_greedy_token(logits, token_out, stream=None):
     st = lib.cascade_greedy_token(_ptr(logits), _dtype_code(logits), logits.shape[0], logits.shape[1], _ptr(token_out),
                                   _stream(stream))
     _check(st, "cascade_greedy_token")
+
+
+def cascade_layer_attention_output(plan, desc, workspace, batch, n_heads, head_dim):
+    """View [B * N, H * d] (packed rows) of the merged attention output a layer forward left in its workspace."""
+    import torch
+    lib = load_library()
+    o = C.c_void_p()
+    _check(lib.cascade_layer_attention_output(plan.handle, C.byref(desc), _ptr(workspace), C.byref(o)),
+           "cascade_layer_attention_output")
+    es = 2 if desc.dtype == BF16 else 4
+    T, W = batch * plan.seq_len, n_heads * head_dim
+    off = o.value - workspace.data_ptr()
+    flat = workspace.view(torch.uint8)[off:off + T * W * es]
+    return flat.view(torch.bfloat16 if desc.dtype == BF16 else torch.float32).view(T, W)
 
 
 def cascade_layer_partials(plan, desc, workspace, batch, n_heads, head_dim):

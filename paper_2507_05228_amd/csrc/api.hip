@@ -237,6 +237,26 @@ extern "C" int32_t cascade_layer_partials(const cascade_plan *plan, const cascad
     return CASCADE_OK;
 }
 
+extern "C" int32_t cascade_layer_attention_output(const cascade_plan *plan, const cascade_layer_desc *d,
+                                                  void *workspace, void **o) {
+    int32_t st = check_layer_desc(plan, d);
+    if (st != CASCADE_OK) return st;
+    if (!workspace || !o) return CASCADE_EINVAL;
+    *o = (char *)workspace + layer_ws(plan, d).ao;
+    return CASCADE_OK;
+}
+
+extern "C" size_t cascade_workspace_bytes(const cascade_plan *plan, const void *desc, int32_t op, int32_t flags) {
+    switch (op) {
+        case CASCADE_OP_PARTIAL_ATTN: return cascade_partial_attn_workspace_bytes(plan, (const cascade_attn_desc *)desc);
+        case CASCADE_OP_LAYER_FORWARD: return cascade_layer_workspace_bytes(plan, (const cascade_layer_desc *)desc);
+        case CASCADE_OP_LAYER_STACK:
+            return cascade_layer_stack_workspace_bytes(plan, (const cascade_layer_desc *)desc, flags);
+        case CASCADE_OP_LM_HEAD: return cascade_lm_head_workspace_bytes(plan, (const cascade_lm_head_desc *)desc);
+        default: return 0;                         // shard GEMM, LSE merge, decode, norm: no workspace
+    }
+}
+
 extern "C" int32_t cascade_norm(int32_t dtype, int32_t rows, int32_t d_model, int32_t norm_kind, float eps,
                                 const void *x, const void *gain, const void *bias, void *y, void *stream) {
     if (!x || !gain || !y || rows < 0 || d_model <= 0) return CASCADE_EINVAL;

@@ -98,26 +98,6 @@ struct AttnBf16Params {
     int32_t gy;           // (batch, kv head, head block) combinations: blockIdx.x = query tile * gy + combination
 };
 
-// Optional timeline instrumentation (build with -DCASCADE_TRACE): lane 0 of wavefronts 0 and 4 of one
-// workgroup stores the shader clock at a few phase boundaries of the first tiles.
-#ifdef CASCADE_TRACE
-#define ATRACE_ITERS 40
-__device__ unsigned long long g_attn_trace[2 * ATRACE_ITERS * 8];
-__device__ int g_attn_trace_wg[2] = {0, 0};
-#define ATRACE(it, slot)                                                                                        \
-    do {                                                                                                        \
-        if ((int)(blockIdx.x / p.gy) == g_attn_trace_wg[0] && (int)(blockIdx.x % p.gy) == g_attn_trace_wg[1] && (threadIdx.x & 255) == 0 && (it) < ATRACE_ITERS) \
-            g_attn_trace[((threadIdx.x >> 8) * ATRACE_ITERS + (it)) * 8 + (slot)] = clock64();                    \
-    } while (0)
-extern "C" __attribute__((visibility("default"))) int cascade_debug_attn_trace(unsigned long long *host, int n, int wgx, int wgy) {
-    int sel[2] = {wgx, wgy};
-    if (wgx >= 0) return (int)hipMemcpyToSymbol(HIP_SYMBOL(g_attn_trace_wg), sel, sizeof(sel), 0, hipMemcpyHostToDevice);
-    if (n > 2 * ATRACE_ITERS * 8) n = 2 * ATRACE_ITERS * 8;
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_attn_trace), (size_t)n * 8, 0, hipMemcpyDeviceToHost);
-}
-#else
-#define ATRACE(it, slot) do { } while (0)
-#endif
 
 // ---------------------------------------------------------------------------- V -> V^T (tile order)
 // vt[b][g][c][64 t + col(i)] = v[b][g][row(tile t, i)][c] for i < n_rows(t), zero for the padding of a
@@ -569,14 +549,11 @@ __global__ __launch_bounds__(NWV * 64) void attn_bf16_kernel(AttnBf16Params p) {
     // one loop per group: the bodies differ only in the order of the two phases
 #define ATTN_TILE_BODY(FIRST, SECOND)                                                             \
     for (; t < t_end; ++i, ++t) {                                                                 \
-        ATRACE(i, 0);                                                                             \
         TileMeta mt3 = mt2;                                                                       \
         if (t + 3 < t_end) mt3 = load_meta(t + 3);                                                \
         if (t + 1 < t_end) bd1 = load_bounds(t + 1);                                              \
         FIRST;                                                                                    \
-        ATRACE(i, 3);                                                                             \
         SECOND;                                                                                   \
-        ATRACE(i, 6);                                                                             \
         /* barrier i+1: own loads of tile i+1 landed (those of tile i+2, if any, stay in flight), */ \
         /* own operand reads of this phase returned */                                            \
         if (t + 2 < t_end) phase_barrier<LPT, true>();                                            \

@@ -200,10 +200,15 @@ static int32_t launch_lpr(const DecodeParams &p, int y_dim, hipStream_t s) {
     const bool wide = p.cap >= 256;
     const dim3 grid(wide ? p.S : (p.S + 3) / 4, y_dim, p.B);
     const size_t lds = wide ? (size_t)4 * REP * p.d * sizeof(float) : 0;
+    // the merge of the four wavefront states needs 4 * REP * d floats: up to 64 KiB at 8 query heads of 512,
+    // above the default dynamic limit, so the limit is raised per kernel instance (once per device)
 #define DECODE_LAUNCH(L)                                                                              \
     do {                                                                                              \
-        if (wide) hipLaunchKernelGGL((decode_attn_kernel<T, REP, L, 4>), grid, dim3(256), lds, s, p); \
-        else hipLaunchKernelGGL((decode_attn_kernel<T, REP, L, 1>), grid, dim3(256), 0, s, p);        \
+        if (wide) {                                                                                   \
+            static std::atomic<uint64_t> lds_ready{0};                                                \
+            CASCADE_HIP_TRY(ensure_dynamic_lds((const void *)decode_attn_kernel<T, REP, L, 4>, (int)lds, lds_ready)); \
+            hipLaunchKernelGGL((decode_attn_kernel<T, REP, L, 4>), grid, dim3(256), lds, s, p);       \
+        } else hipLaunchKernelGGL((decode_attn_kernel<T, REP, L, 1>), grid, dim3(256), 0, s, p);      \
     } while (0)
     switch (lpr) {
         case 1: DECODE_LAUNCH(1); break;

@@ -52,27 +52,6 @@ struct Gemm2Params {
 
 typedef __attribute__((address_space(3))) void lds_void;
 
-// Optional timeline instrumentation (build with -DCASCADE_TRACE): thread 0 of each workgroup stores the
-// constant-rate wall clock at a few points of the kernel; cascade_debug_gemm_trace copies them out.
-#ifdef CASCADE_TRACE
-#define TRACE_SLOTS 8
-#define TRACE_WGS 4096
-__device__ unsigned long long g_gemm_trace[TRACE_WGS * TRACE_SLOTS];
-#define TRACE(slot)                                                                                  \
-    do {                                                                                             \
-        if (threadIdx.x == 0 && blockIdx.x < TRACE_WGS) {                                            \
-            g_gemm_trace[blockIdx.x * TRACE_SLOTS + (slot)] = wall_clock64();                        \
-            if ((slot) == 2) g_gemm_trace[blockIdx.x * TRACE_SLOTS + 6] = clock64();                 \
-            if ((slot) == 4) g_gemm_trace[blockIdx.x * TRACE_SLOTS + 7] = clock64();                 \
-        }                                                                                            \
-    } while (0)
-extern "C" __attribute__((visibility("default"))) int cascade_debug_gemm_trace(unsigned long long *host, int n) {
-    if (n > TRACE_WGS * TRACE_SLOTS) n = TRACE_WGS * TRACE_SLOTS;
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_gemm_trace), (size_t)n * 8, 0, hipMemcpyDeviceToHost);
-}
-#else
-#define TRACE(slot) do { } while (0)
-#endif
 
 // 16 bytes per lane from a buffer straight into LDS: lane i of the wavefront lands at lds + 16 i.
 __device__ __forceinline__ void load16_to_lds(__amdgpu_buffer_rsrc_t r, unsigned char *lds, uint32_t voff) {
@@ -339,7 +318,6 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm2_kernel(Gemm2Params p) {
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm0 = (wave / WN) * WTM, wn0 = (wave % WN) * WTN;
-    TRACE(0);
 
     // workgroup -> tile: contiguous run of tiles (m fastest) per XCD
     const int total = p.tiles_m * p.tiles_n;
@@ -460,7 +438,6 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm2_kernel(Gemm2Params p) {
 #pragma unroll
     for (int s = 0; s < NST - 1; ++s)
         if (s < KT) issue_loads(s, s);
-    TRACE(1);
     // Software pipeline over k-steps: the LDS reads of a k-step are in flight while the MFMAs of the
     // previous k-step run, also across the tile boundary (the second k-step of tile kt is multiplied
     // after the barrier that opens tile kt+1, from registers).  It needs two operand register sets;
@@ -468,7 +445,6 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm2_kernel(Gemm2Params p) {
     // keeps one k-step's reads directly ahead of its own MFMAs instead.
     constexpr bool PIPE = 4 * TM * TN + 8 * (TM + TN) <= 216;
     tile_ready(0);
-    TRACE(2);
     if constexpr (SOLO) {
         // One wavefront per SIMD: nothing else covers this wavefront's waits, so every memory operation
         // is placed between two MFMAs of the k-step that runs meanwhile.  Tile kt, first k-step: its
@@ -503,7 +479,6 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm2_kernel(Gemm2Params p) {
         for (int r = 0; r < NR; ++r) fetch_one(0, k0, r);
         int kt = 0;
         for (; kt + 2 < KT; ++kt) {                            // tile kt+1 is in flight or landed
-            if (kt == KT / 2) TRACE(3);
             phase(k0, [&](int x) {
                 if (x % 2 == 0 && x / 2 < NR) fetch_one(kt, k1, x / 2);
                 if (x % 2 == 1 && x / 2 < A_INSTR) issue_load(kt + 2, 0, x / 2);
@@ -526,7 +501,6 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm2_kernel(Gemm2Params p) {
         auto fetch = [&](int kt, auto ks_tag) { fetch_into(kt, ks_tag, ks_tag); };   // k-step ks -> register set ks
         fetch(0, k0);
         for (int kt = 0; kt + 1 < KT; ++kt) {              // straight-line body: the last tile is peeled
-            if (kt == KT / 2) TRACE(3);
             fetch(kt, k1);
             __builtin_amdgcn_sched_barrier(0);             // reads stay ahead of the MFMAs they overlap with
             mfmas(k0);
@@ -543,7 +517,6 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm2_kernel(Gemm2Params p) {
         mfmas(k1);
     } else {
         for (int kt = 0; kt < KT; ++kt) {
-            if (kt == KT / 2) TRACE(3);
             if (kt > 0) tile_ready(kt);
             fetch_into(kt, k0, k0);
             mfmas(k0);
@@ -554,14 +527,11 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm2_kernel(Gemm2Params p) {
 
     if constexpr (SOLO) {
         __syncthreads();                                   // everyone is done with the tile buffers
-        TRACE(4);
         gemm_epilogue_tile<BM, NW * 64, TM, TN, WTN, SWIGLU, BN_OUT>(p, acc, smem, tid, m0, wm0, wn0, nloc0, seg, seg_rows);
     } else {
         __syncthreads();                                   // everyone is done with the tile buffers
-        TRACE(4);
         gemm_epilogue<TM, TN, WTN, SWIGLU>(p, acc, smem, wave, lane, m0, wm0, wn0, nloc0, seg, seg_rows);
     }
-    TRACE(5);
 }
 
 // ---------------------------------------------------------------------------- ping-pong variant
@@ -604,7 +574,6 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm3_kernel(Gemm2Params p) {
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int group = wave >> 2;                                   // wavefronts w and w+4 share a SIMD
     const int wm0 = (wave / WN) * WTM, wn0 = (wave % WN) * WTN;
-    TRACE(0);
 
     const int total = p.tiles_m * p.tiles_n;
     int tile;
@@ -688,7 +657,6 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm3_kernel(Gemm2Params p) {
 #pragma unroll
     for (int s = 0; s < NST - 1; ++s)
         if (s < KT) issue_loads(s);
-    TRACE(1);
     {   // tile 0 complete and visible to everyone
         const int younger = max(0, min(NST - 2, KT - 1));
         if (younger >= 3) phase_barrier<3 * LPT, false>();
@@ -696,7 +664,6 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm3_kernel(Gemm2Params p) {
         else if (younger == 1) phase_barrier<LPT, false>();
         else phase_barrier<0, false>();
     }
-    TRACE(2);
     // With two stages a tile must be requested a whole tile period before it is read, so group 1
     // issues its share during its compute phase (the same window in which group 0 issues in its
     // memory phase); with three or more stages both groups issue in their memory phase.
@@ -704,7 +671,6 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm3_kernel(Gemm2Params p) {
     if (group == 1) phase_barrier<-1, false>();                    // run one phase behind group 0
 
     for (int kt = 0; kt < KT; ++kt) {
-        if (kt == KT / 2) TRACE(3);
         // ---- memory phase: refill the stage of tile kt-1 (everyone finished reading it one barrier
         // ago), fetch this tile's operands
         if ((NST > 2 || group == 0) && kt + NST - 1 < KT) issue_loads(kt + NST - 1);
@@ -736,9 +702,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm3_kernel(Gemm2Params p) {
     if (group == 0) phase_barrier<-1, false>();                    // group 1 is one barrier ahead in count
 
     __syncthreads();
-    TRACE(4);
     gemm_epilogue<TM, TN, WTN, SWIGLU>(p, acc, smem, wave, lane, m0, wm0, wn0, nloc0, seg, seg_rows);
-    TRACE(5);
 }
 
 template <int BM, int BN, int WM, int WN, int BK, int NST, bool SWIGLU, bool PINGPONG = false>

@@ -245,6 +245,36 @@ extern "C" int32_t cascade_comm_cost(int32_t n_row_shards, int32_t n_kv_shards, 
     return CASCADE_OK;
 }
 
+// Equation 2 (Theoretical Costs; derived in the Communication Analysis appendix): with perfect parallel
+// transport a stage lasts one latency plus the transfer of the node that sends most.  Stage A: the
+// CompNode with the largest row shard ships each row's q, k, v to beta AttnNodes; stage B: an AttnNode
+// of the largest key/value shard ships u, m, e of its rows back.
+extern "C" int32_t cascade_comm_time(const cascade_plan *plan, int32_t n_kv_shards, int32_t max_row_shard,
+                                     int32_t max_kv_shard, int32_t bytes_per_value, int32_t head_dim,
+                                     int32_t n_heads, int32_t n_kv_heads, double latency_s,
+                                     double bandwidth_bytes_per_s, double *stage_a_s, double *stage_b_s,
+                                     double *total_s) {
+    if (plan) {                                    // shard sizes from the plan's two partitions
+        const cascade_plan *kvp = kv_plan(plan);
+        n_kv_shards = kvp->n_shards;
+        max_row_shard = max_kv_shard = 0;
+        for (int i = 0; i < plan->n_shards; ++i)
+            max_row_shard = std::max(max_row_shard, plan->offsets_h[i + 1] - plan->offsets_h[i]);
+        for (int j = 0; j < kvp->n_shards; ++j)
+            max_kv_shard = std::max(max_kv_shard, kvp->offsets_h[j + 1] - kvp->offsets_h[j]);
+    }
+    if (n_kv_shards <= 0 || max_row_shard < 0 || max_kv_shard < 0 || bytes_per_value <= 0 || head_dim <= 0 ||
+        n_heads <= 0 || n_kv_heads <= 0 || !(latency_s >= 0.0) || !(bandwidth_bytes_per_s > 0.0))
+        return CASCADE_EINVAL;
+    const double beta = n_kv_shards, F = bytes_per_value, d = head_dim;
+    const double a = latency_s + beta * F * d * (n_heads + 2.0 * n_kv_heads) / bandwidth_bytes_per_s * max_row_shard;
+    const double b = latency_s + F * (d + 2.0) * n_heads / bandwidth_bytes_per_s * max_kv_shard;
+    if (stage_a_s) *stage_a_s = a;
+    if (stage_b_s) *stage_b_s = b;
+    if (total_s) *total_s = a + b;
+    return CASCADE_OK;
+}
+
 extern "C" int32_t cascade_plan_maps(const cascade_plan *plan, const int32_t **perm_dev,
                                      const int32_t **inv_perm_dev, const int32_t **offsets_dev) {
     if (!plan) return CASCADE_EINVAL;

@@ -1,5 +1,5 @@
-// HBM-bound per-token kernels: normalisation with row gather (Pre-Pass subsection: "applies
-// layer normalization if necessary"), rotary embedding at original token positions
+// HBM-bound per-token kernels: normalisation with row gather (the optional normalisation step of the
+// Pre-Pass subsection), rotary embedding at original token positions
 // (the rotary step of Algorithm 2).  The gather into packed order is the row map of the norm's read; the
 // scatter back is the row map of the last shard GEMM's store.
 #include <climits>

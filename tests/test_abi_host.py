@@ -153,3 +153,36 @@ def test_comm_cost_matches_equation_1_and_the_papers_table():
     with pytest.raises(cas.CascadeError) as ei:
         cas.cascade_comm_cost(0, 4, 2, 64, 8, 8, 128)
     assert ei.value.status == cas.EINVAL
+
+
+def test_comm_time_matches_equation_2_and_the_oracle():
+    """cascade_comm_time with explicit shard sizes (a plan needs a GPU) against the oracle's node-by-node count."""
+    from oracle import cascade_oracle as orc
+    rng = np.random.default_rng(5)
+    for N, alpha, m, F, d, H, Hkv in ((300, 5, 3, 2, 64, 12, 12), (1000, 7, 1, 4, 128, 32, 8), (18, 3, 2, 2, 16, 4, 2)):
+        a = rng.integers(0, alpha, size=N)
+        kv = orc.m_split_assignment(a, alpha, m)
+        R, S = orc.shard_index_lists(a, alpha), orc.shard_index_lists(kv, alpha * m)
+        tau, bw = 0.38e-3, 2.5e8
+        want = orc.comm_time(R, S, F, d, H, Hkv, tau, bw)
+        got = cas.cascade_comm_time(F, d, H, Hkv, tau, bw, n_kv_shards=alpha * m,
+                                    max_row_shard=max(len(r) for r in R), max_kv_shard=max(len(s) for s in S))
+        assert np.allclose(got, want, rtol=1e-12, atol=0)
+    # one shard, no latency: the bytes of Equation 1 over the bandwidth
+    a_bytes, b_bytes, _ = cas.cascade_comm_cost(1, 1, 2, 64, 12, 12, 128)
+    total, ta, tb = cas.cascade_comm_time(2, 64, 12, 12, 0.0, 1e9, n_kv_shards=1, max_row_shard=128, max_kv_shard=128)
+    assert np.isclose(ta * 1e9, a_bytes) and np.isclose(tb * 1e9, b_bytes) and np.isclose(total, ta + tb)
+    for bad in (dict(latency_s=-1.0), dict(bandwidth_bytes_per_s=0.0), dict(n_kv_shards=0)):
+        kw = dict(latency_s=0.0, bandwidth_bytes_per_s=1e9, n_kv_shards=2, max_row_shard=4, max_kv_shard=4)
+        kw.update(bad)
+        with pytest.raises(cas.CascadeError) as ei:
+            cas.cascade_comm_time(2, 64, 12, 12, **kw)
+        assert ei.value.status == cas.EINVAL
+
+
+def test_unified_workspace_query_needs_no_device_for_the_zero_cases():
+    """Operations without a workspace report 0; invalid descriptors report 0 (no plan can exist without a GPU)."""
+    assert cas.cascade_workspace_bytes(None, None, cas.OP_SHARD_GEMM) == 0
+    assert cas.cascade_workspace_bytes(None, None, cas.OP_LSE_MERGE) == 0
+    assert cas.cascade_workspace_bytes(None, None, cas.OP_LAYER_FORWARD) == 0
+    assert cas.cascade_workspace_bytes(None, None, 99) == 0

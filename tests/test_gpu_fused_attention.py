@@ -1,0 +1,147 @@
+"""The merged attention output (the input of the o projection) of the layer path, checked directly against
+the oracle, row by row and head by head.
+
+The layer output is dominated by the residual and the MLP, so a fault of the fused attention kernel that
+touches only some query tiles (its visible-prefix count, block skipping, stage reuse, lazy rescaling) can hide
+below the layer-level tolerance.  Here the error of every (row, head) slice is normalised by that slice's own
+largest reference value: dropping the mask, or a tile, for a single row moves its slice by O(1)."""
+import numpy as np
+import pytest
+
+from cascade_inputs import CONFIGS, config_seed, make_assignment, make_hidden, make_layer_weights
+from oracle import cascade_oracle as orc
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-5, "bf16": 2e-2}
+
+
+@pytest.fixture(scope="module")
+def cas():
+    import torch
+    assert torch.cuda.is_available()
+    import paper_2507_05228_amd as cas
+    cas.load_library()
+    return cas
+
+
+def gpu_attention_output(cas, cfg, w, h, a, attn_mode, positions=None, mask_kind="causal", kv=None):
+    """[B, N (packed rows), H, d] float64 from the workspace of one layer forward."""
+    import torch
+    mk = cas.MASK_CAUSAL if mask_kind == "causal" else cas.MASK_NONE
+    if kv is None:
+        plan = cas.cascade_plan_create(cfg.batch, cfg.seq_len, cfg.n_shards, a, positions, mk)
+    else:
+        plan = cas.cascade_plan_create_rs(cfg.batch, cfg.seq_len, cfg.n_shards, a, int(kv.max()) + 1, kv, positions, mk)
+    desc = cas.make_layer_desc(cfg, attn_mode)
+    tensors = {k: cas.to_device(v, cfg.dtype) for k, v in w.items()}
+    wts = cas.make_layer_weights(tensors)
+    h_in = cas.to_device(h, cfg.dtype)
+    h_out = torch.empty_like(h_in)
+    ws = cas.new_workspace(cas.cascade_layer_workspace_bytes(plan, desc))
+    cas.cascade_layer_forward(plan, desc, wts, h_in, h_out, ws)
+    torch.cuda.synchronize()
+    ao = cas.cascade_layer_attention_output(plan, desc, ws, cfg.batch, cfg.n_heads, cfg.head_dim)
+    return ao.float().cpu().numpy().astype(np.float64).reshape(cfg.batch, cfg.seq_len, cfg.n_heads, cfg.head_dim)
+
+
+def oracle_attention_rows(h_b, w64, cfg, rows, positions=None, mask_kind="causal"):
+    """softmax(a) v of the given token rows of one sequence, [len(rows), H, d]: the norm, projections and
+    rotary embedding of Algorithm 2 on every token for k, v and on `rows` for q, then one pair whose
+    key/value shard is the whole sequence (Algorithm 3 with one shard is plain attention)."""
+    N = h_b.shape[0]
+    pos = np.arange(N) if positions is None else np.asarray(positions)
+    H, Hkv, d = cfg.n_heads, cfg.n_kv_heads, cfg.head_dim
+    post = getattr(cfg, "norm_placement", "pre") == "post"
+    x = h_b if post else orc.norm(h_b, cfg.norm, w64["norm1_g"], w64.get("norm1_b"), cfg.eps)
+    k = orc.linear(x, w64["wk"], w64.get("bk")).reshape(N, Hkv, d).transpose(1, 0, 2)
+    v = orc.linear(x, w64["wv"], w64.get("bv")).reshape(N, Hkv, d).transpose(1, 0, 2)
+    q = orc.linear(x[rows], w64["wq"], w64.get("bq")).reshape(len(rows), H, d).transpose(1, 0, 2)
+    if cfg.rope:
+        q, k = orc.rope(q, pos[rows], cfg.rope_theta), orc.rope(k, pos, cfg.rope_theta)
+    _, _, u = orc.attn_pass(q, k, v, orc.mask_block(pos[rows], pos, mask_kind), cfg.scale)
+    return u.transpose(1, 0, 2)
+
+
+def slice_errors(got, ref):
+    """max |got - ref| of every (row, head) slice over that slice's max |ref| (floored at 1 % of the global max)."""
+    floor = 0.01 * np.abs(ref).max()
+    return np.abs(got - ref).max(axis=-1) / np.maximum(np.abs(ref).max(axis=-1), floor)
+
+
+SMALL = CONFIGS["C3"].with_(name="fa-llama", d_model=512, n_heads=8, n_kv_heads=2, head_dim=128, d_ff=512,
+                            seq_len=1100, n_shards=6, index=41)
+SMALL64 = CONFIGS["C3"].with_(name="fa-llama64", d_model=256, n_heads=6, n_kv_heads=6, head_dim=64, d_ff=256,
+                              seq_len=700, n_shards=3, index=42)
+SMALL_GQA2 = CONFIGS["C3"].with_(name="fa-gqa2", d_model=256, n_heads=4, n_kv_heads=2, head_dim=128, d_ff=256,
+                                 batch=2, seq_len=520, n_shards=9, index=43)
+SMALL_F32 = CONFIGS["C3"].with_(name="fa-f32", dtype="f32", d_model=96, n_heads=6, n_kv_heads=2, head_dim=16,
+                                d_ff=96, seq_len=200, n_shards=5, index=44)
+
+
+@pytest.mark.parametrize("cfg", [SMALL, SMALL64, SMALL_GQA2, SMALL_F32], ids=lambda c: c.name)
+@pytest.mark.parametrize("kind", ["perm", "contiguous", "roundrobin", "ragged"])
+@pytest.mark.parametrize("mode", ["fused", "materialised"])
+def test_attention_output_every_row_and_head(cas, cfg, kind, mode):
+    """More than four key/value tiles per query tile (the LDS stages are reused), ragged tails, every partition kind."""
+    attn_mode = cas.ATTN_FUSED if mode == "fused" else cas.ATTN_MATERIALISED
+    a = make_assignment(kind, cfg.seq_len, cfg.n_shards, 3 + cfg.index)
+    w, h = make_layer_weights(cfg), make_hidden(cfg)
+    w64 = {k: v.astype(np.float64) for k, v in w.items()}
+    got = gpu_attention_output(cas, cfg, w, h, a, attn_mode)
+    _, perm, _ = orc.shard_plan(a, cfg.n_shards)
+    for b in range(cfg.batch):
+        ref = oracle_attention_rows(h[b].astype(np.float64), w64, cfg, perm)       # packed row r = token perm[r]
+        err = slice_errors(got[b], ref)
+        assert err.max() < TOL[cfg.dtype], (np.unravel_index(err.argmax(), err.shape), err.max())
+
+
+@pytest.mark.parametrize("mask_kind,ordered", [("none", True), ("causal", False), ("none", False)])
+def test_attention_output_without_mask_and_with_unordered_positions(cas, mask_kind, ordered):
+    cfg = SMALL
+    a = make_assignment("perm", cfg.seq_len, cfg.n_shards, 9)
+    pos = None if ordered else np.random.default_rng(4).permutation(3 * cfg.seq_len)[:cfg.seq_len].astype(np.int32)
+    w, h = make_layer_weights(cfg), make_hidden(cfg)
+    w64 = {k: v.astype(np.float64) for k, v in w.items()}
+    got = gpu_attention_output(cas, cfg, w, h, a, cas.ATTN_FUSED, positions=pos, mask_kind=mask_kind)
+    _, perm, _ = orc.shard_plan(a, cfg.n_shards)
+    ref = oracle_attention_rows(h[0].astype(np.float64), w64, cfg, perm, positions=pos, mask_kind=mask_kind)
+    assert slice_errors(got[0], ref).max() < TOL[cfg.dtype]
+
+
+def test_attention_output_with_two_shardings(cas):
+    """Row shards from a (c, delta)-sharding, key/value shards from its m-split: the merged output is still
+    plain attention, in the row sharding's packed order."""
+    cfg = SMALL.with_(seq_len=1024, n_shards=8)
+    a = orc.cdelta_assignment(cfg.seq_len, 4, 32).astype(np.int32)
+    kv = orc.m_split_assignment(a, 8, 3).astype(np.int32)
+    w, h = make_layer_weights(cfg), make_hidden(cfg)
+    w64 = {k: v.astype(np.float64) for k, v in w.items()}
+    _, perm, _ = orc.shard_plan(a, 8)
+    ref = oracle_attention_rows(h[0].astype(np.float64), w64, cfg, perm)
+    for mode in (cas.ATTN_FUSED, cas.ATTN_MATERIALISED):
+        got = gpu_attention_output(cas, cfg, w, h, a, mode, kv=kv)
+        assert slice_errors(got[0], ref).max() < TOL[cfg.dtype]
+
+
+@pytest.mark.parametrize("key", ["C2", "C3", "C4", "C5"])
+def test_full_config_fused_attention_output_sampled_rows(cas, key):
+    """The launch configuration the benchmark times: sampled packed rows (first and last token always, and
+    the last row of every query tile's worth of 256 rows near the end), every head."""
+    cfg = CONFIGS[key]
+    seed = config_seed(cfg)
+    a = make_assignment(cfg.assignment, cfg.seq_len, cfg.n_shards, seed)
+    w, h = make_layer_weights(cfg), make_hidden(cfg)
+    print(f"[{key}] inputs ready", flush=True)
+    got = gpu_attention_output(cas, cfg, w, h, a, cas.ATTN_FUSED)
+    print(f"[{key}] gpu done", flush=True)
+    w64 = {k: v.astype(np.float64) for k, v in w.items()}
+    _, perm, inv_perm = orc.shard_plan(a, cfg.n_shards)
+    rng = np.random.default_rng(seed + 7)
+    b = cfg.batch - 1
+    toks = np.unique(np.concatenate([rng.choice(cfg.seq_len, size=40, replace=False), [0, cfg.seq_len - 1],
+                                     perm[-3:], perm[:2]]))
+    ref = oracle_attention_rows(h[b].astype(np.float64), w64, cfg, toks)
+    err = slice_errors(got[b][inv_perm[toks]], ref)
+    print(f"[{key}] worst (row, head) slice error {err.max():.3e}", flush=True)
+    assert err.max() < TOL[cfg.dtype]

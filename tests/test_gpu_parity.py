@@ -281,7 +281,10 @@ def check_partials(dtype, got, ref):
     ut_r = e_r.transpose(0, 2, 1, 3)[..., None] * u_r        # u~ = e * u, [B, beta, H, N, d]
     assert rel_err(u, ut_r) < TOL[dtype]
     assert (u[dead.transpose(0, 2, 1, 3)] == 0).all()
-    assert (e[~dead] >= 1.0 - 1e-4).all()                     # corrected bound: 1 <= e <= |S_k| (up to the rounding of m)
+    # 1 <= e <= |S_k| (the stability remark's "e <= 1" is a slip).  The kernel's e is the sum relative to its
+    # fp32 row maximum, which may sit half an fp32 ulp of the logit (~1e-5 relative at logits in the hundreds,
+    # scaled by log2 e) above the exact one, so e may undershoot 1 by that much; m + log e is unaffected.
+    assert (e[~dead] >= 1.0 - 2e-5).all()
 
 
 @pytest.mark.parametrize("dtype,H,Hkv,N,d,beta,kind,layout", [

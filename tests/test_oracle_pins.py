@@ -142,6 +142,53 @@ def test_comm_bytes_halves_closed_form():
     assert total == 16 * 2 * (2 * 128 * 32 + 2 * 128 * 8 + 2 * 32) * 2048
 
 
+def test_comm_time_is_equation_2():
+    """Equation 2 (Theoretical Costs): 2 tau + beta F d (H + 2 H_KV) / B * max|R_i| + F (d + 2) H / B * max|S_j|,
+    here against the oracle's node-by-node count on ragged partitions with R != S."""
+    rng = np.random.default_rng(12)
+    for N, alpha, m, F, d, H, Hkv in ((300, 5, 3, 2, 64, 12, 12), (1000, 7, 1, 4, 128, 32, 8), (64, 64, 2, 2, 16, 4, 2)):
+        a = rng.integers(0, alpha, size=N)
+        kv = orc.m_split_assignment(a, alpha, m)
+        R, S = orc.shard_index_lists(a, alpha), orc.shard_index_lists(kv, alpha * m)
+        tau, bw = 0.38e-3, 2e9 / 8
+        total, t_a, t_b = orc.comm_time(R, S, F, d, H, Hkv, tau, bw)
+        beta = alpha * m
+        want = (2 * tau + beta * F * d * (H + 2 * Hkv) / bw * max(len(r) for r in R)
+                + F * (d + 2) * H / bw * max(len(s) for s in S))
+        assert math.isclose(total, want, rel_tol=1e-12)
+        assert math.isclose(total, t_a + t_b, rel_tol=1e-15)
+
+
+def test_comm_time_reduces_to_equation_1_over_bandwidth():
+    """Equal shards: every node of a stage sends the same amount, so (stage time - tau) x nodes x B is that
+    stage's byte count of Equation 1 (itself pinned by the paper's table); one shard without latency is
+    CommBytes / B; the latency enters as 2 tau; more key/value shards never make it faster."""
+    N, F, d, H, Hkv, bw = 1024, 2, 64, 12, 12, 3.0e8
+    for alpha, m in ((1, 1), (4, 1), (8, 2), (16, 4)):
+        a = orc.cdelta_assignment(N, N // alpha // 4 or 1, N // 4 if alpha > 1 else N)
+        if alpha == 1:
+            a = np.zeros(N, dtype=np.int64)
+        assert a.max() + 1 == alpha
+        kv = orc.m_split_assignment(a, alpha, m)
+        beta = alpha * m
+        R, S = orc.shard_index_lists(a, alpha), orc.shard_index_lists(kv, beta)
+        assert len({len(r) for r in R}) == 1 and len({len(s) for s in S}) == 1
+        total, t_a, t_b = orc.comm_time(R, S, F, d, H, Hkv, 0.0, bw)
+        all_bytes, bytes_a, bytes_b = orc.comm_bytes(beta, F, d, H, Hkv, N)
+        assert math.isclose(t_a * alpha * bw, bytes_a, rel_tol=1e-12)
+        assert math.isclose(t_b * beta * beta * bw, bytes_b, rel_tol=1e-12)
+        if beta == 1:
+            assert math.isclose(total * bw, all_bytes, rel_tol=1e-12)
+        with_tau = orc.comm_time(R, S, F, d, H, Hkv, 1e-3, bw)[0]
+        assert math.isclose(with_tau - total, 2e-3, rel_tol=1e-9)
+    times = []
+    for m in (1, 2, 4, 8):                      # same row shards, finer key/value shards
+        a = orc.cdelta_assignment(N, 32, 256)
+        S = orc.shard_index_lists(orc.m_split_assignment(a, 8, m), 8 * m)
+        times.append(orc.comm_time(orc.shard_index_lists(a, 8), S, F, d, H, Hkv, 0.0, bw)[1])
+    assert all(x < y for x, y in zip(times, times[1:]))     # stage A grows with beta
+
+
 def test_overhead_ops_ratio():
     """Appendix C: overhead / (H N^2 d) = 1/N + 1/d."""
     H, N, d = 32, 2048, 128
