@@ -124,6 +124,71 @@ def test_attention_output_with_two_shardings(cas):
         assert slice_errors(got[0], ref).max() < TOL[cfg.dtype]
 
 
+def counting_inputs(cfg, perm):
+    """Inputs that turn the attention output into exact visible-key counts (the q = 0 pin of the mask and the
+    gather, through the whole layer path): w_q = 0 makes every logit 0, so softmax is uniform over the visible
+    keys; token s carries a one-hot hidden state whose index is the 16-row block of s in packed order, and w_v
+    routes block c to column c mod d of kv head 0, column (c div d) mod d of kv head 1, c mod 97 of head 2,
+    c mod 89 of head 3 (then repeating), so v rows are one-hot per kv head.  Then
+    o[r, head, j] = #{visible keys of row r whose block maps to j} / #{visible keys of row r}, up to the common
+    factor v0 = the normalised hidden value times the weight entry.  Leaving out, or counting twice, a single
+    key anywhere changes some element by at least 1/16 of its value."""
+    N, D, H, Hkv, d = cfg.seq_len, cfg.d_model, cfg.n_heads, cfg.n_kv_heads, cfg.head_dim
+    assert N // 16 + 1 <= D
+    inv_perm = np.empty(N, dtype=np.int64)
+    inv_perm[perm] = np.arange(N)
+    block = inv_perm // 16                                       # class of token s
+    h = np.zeros((cfg.batch, N, D), dtype=np.float32)
+    h[:, np.arange(N), block] = 1.0
+    w = make_layer_weights(cfg)
+    w = {k: v.copy() for k, v in w.items()}
+    w["wq"][:] = 0.0
+    if "bq" in w:
+        w["bq"][:] = 0.0
+    w["norm1_g"][:] = 1.0
+    if "norm1_b" in w:
+        w["norm1_b"][:] = 0.0
+    w["wv"][:] = 0.0
+    if "bv" in w:
+        w["bv"][:] = 0.0
+    maps = [lambda c: c % d, lambda c: (c // d) % d, lambda c: c % 97, lambda c: c % 89]
+    cls = np.arange(N // 16 + 1)
+    for g in range(Hkv):
+        w["wv"][g * d + maps[g % 4](cls), cls] = 1.0 / 64.0
+    return w, h
+
+
+@pytest.mark.parametrize("name,kind,N,beta", [("fa-llama", "perm", 1100, 6), ("fa-llama", "ragged", 900, 7),
+                                              ("fa-llama", "roundrobin", 1024, 16), ("fa-llama", "contiguous", 1000, 4),
+                                              ("fa-llama64", "perm", 700, 3), ("C3", "perm", 2048, 16),
+                                              ("C4", "roundrobin", 8192, 64), ("C5", "perm", 4096, 32)])
+@pytest.mark.parametrize("mode", ["fused", "materialised"])
+def test_attention_output_counts_visible_keys_exactly(cas, name, kind, N, beta, mode):
+    """Every row, every head: the output must be the visible-key histogram the causal mask and the shard
+    gather define (see counting_inputs).  Rank-deficient layer norm is avoided: RMSNorm models only, or
+    LayerNorm would centre the one-hot rows; the full-size shapes run the benchmark's launch configuration."""
+    base = {"fa-llama": SMALL, "fa-llama64": SMALL64}.get(name) or CONFIGS[name]
+    cfg = base.with_(seq_len=N, n_shards=beta, assignment=kind)
+    if mode == "materialised" and N > 4096:
+        pytest.skip("the materialised partials of this shape are checked in test_gpu_fullsize.py")
+    a = make_assignment(kind, N, beta, 11)
+    _, perm, _ = orc.shard_plan(a, beta)
+    w, h = counting_inputs(cfg, perm)
+    attn_mode = cas.ATTN_FUSED if mode == "fused" else cas.ATTN_MATERIALISED
+    got = gpu_attention_output(cas, cfg, w, h, a, attn_mode)
+    w64 = {k: v.astype(np.float64) for k, v in w.items()}
+    rows = perm if N <= 2048 else np.sort(np.random.default_rng(N).choice(N, size=512, replace=False))
+    ref = oracle_attention_rows(h[0].astype(np.float64), w64, cfg, rows)
+    inv_perm = np.empty(N, dtype=np.int64)
+    inv_perm[perm] = np.arange(N)
+    g = got[0][inv_perm[rows]]
+    assert (g[ref == 0.0] == 0.0).all()                                  # no key leaks into a class it is not in
+    live = ref > 0.0
+    rel = np.abs(g[live] - ref[live]) / ref[live]
+    # three bf16 roundings on the GPU side (normalised hidden value, v, the output): 3 * 2^-9 < 1e-2 < 1/16
+    assert rel.max() < 1e-2, rel.max()
+
+
 @pytest.mark.parametrize("key", ["C2", "C3", "C4", "C5"])
 def test_full_config_fused_attention_output_sampled_rows(cas, key):
     """The launch configuration the benchmark times: sampled packed rows (first and last token always, and
@@ -142,6 +207,11 @@ def test_full_config_fused_attention_output_sampled_rows(cas, key):
     toks = np.unique(np.concatenate([rng.choice(cfg.seq_len, size=40, replace=False), [0, cfg.seq_len - 1],
                                      perm[-3:], perm[:2]]))
     ref = oracle_attention_rows(h[b].astype(np.float64), w64, cfg, toks)
-    err = slice_errors(got[b][inv_perm[toks]], ref)
-    print(f"[{key}] worst (row, head) slice error {err.max():.3e}", flush=True)
-    assert err.max() < TOL[cfg.dtype]
+    g = got[b][inv_perm[toks]]
+    err = np.abs(g - ref).max() / np.abs(ref).max()
+    print(f"[{key}] attention output, sampled rows: max rel err {err:.3e}; worst (row, head) slice by its own "
+          f"scale {slice_errors(g, ref).max():.3e}", flush=True)
+    # Per tensor, as the tolerance is stated.  Slice by slice the random-input error is dominated by the bf16
+    # rounding of q, k, v ahead of the kernel (late rows average many values, their slices are several times
+    # smaller than the tensor's maximum); the structure of the walk is pinned exactly by the counting test above.
+    assert err < TOL[cfg.dtype]
