@@ -25,79 +25,7 @@
 #include <climits>
 #include <cstdlib>
 #include <type_traits>
-#include "common.h"
-#include "device_utils.h"
-
-#define KV_TILE 64
-#define LOG2E 1.4426950408889634f
-#define LN2 0.6931471805599453f
-#define OOB_OFF 0x80000000u
-
-typedef __attribute__((address_space(3))) void lds_void;
-// Plan metadata is read-only for the kernel and indexed uniformly: reading it through the constant
-// address space makes these scalar loads, which do not share a counter with the tile loads in flight.
-typedef const __attribute__((address_space(4))) CascadeTile *tile_cptr;
-typedef const __attribute__((address_space(4))) int32_t *int_cptr;
-
-__device__ __forceinline__ void load16_to_lds(__amdgpu_buffer_rsrc_t r, unsigned char *lds, uint32_t voff) {
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_void *)lds, 16, voff, 0, 0, 0);
-}
-__device__ __forceinline__ void load4_to_lds(__amdgpu_buffer_rsrc_t r, unsigned char *lds, uint32_t voff) {
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_void *)lds, 4, voff, 0, 0, 0);
-}
-
-// max over the 4 lanes {l, l^16, l^32, l^48} with the gfx950 lane-swap instructions (no LDS traffic)
-__device__ __forceinline__ float xor_max_16_32(float v) {
-    typedef __attribute__((ext_vector_type(2))) unsigned u2;
-    u2 r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
-    v = fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
-    r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
-    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
-}
-__device__ __forceinline__ float xor_sum_16_32(float v) {
-    typedef __attribute__((ext_vector_type(2))) unsigned u2;
-    u2 r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
-    v = __uint_as_float(r[0]) + __uint_as_float(r[1]);
-    r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
-    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
-}
-
-// Workgroup barrier as inline assembly, optionally preceded by "all but the VM youngest vector-memory
-// operations of this wavefront are complete" and "all LDS reads have returned".  (A compiler-generated
-// barrier waits for vmcnt(0) and would drain the tile pipeline.)
-template <int VM, bool LGKM>
-__device__ __forceinline__ void phase_barrier() {
-    __builtin_amdgcn_sched_barrier(0);
-    if (VM >= 0 && LGKM) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(VM < 0 ? 0 : VM) : "memory");
-    else if (VM >= 0) asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(VM < 0 ? 0 : VM) : "memory");
-    else if (LGKM) asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-    else asm volatile("s_barrier" ::: "memory");
-    __builtin_amdgcn_sched_barrier(0);
-}
-
-struct AttnBf16Params {
-    const bf16_t *q, *k, *vt;
-    int64_t qs_b, qs_h, qs_n, ks_b, ks_h, ks_n, vts_b, vts_h;
-    int32_t npad;
-    uint32_t k_bytes, vt_bytes;      // extent of one (batch, kv head) slice, for the buffer resources
-    const int32_t *q_rowmap;
-    const CascadeTile *qtiles;
-    const CascadeTile *kvtiles;      // ordered by smallest position: globally (fused) or inside each shard's range
-    const int32_t *kv_shard_first;
-    int32_t n_kvtiles;
-    const int32_t *pos_packed;       // positions of the packed query rows
-    const int32_t *pos_kv;           // positions of the key/value rows in the order of the kv tiles
-    int32_t B, H, Hkv, N, S;
-    float scale_log2;
-    int32_t causal, fused, u_mode;
-    float *m, *e, *u;
-    bf16_t *o;
-    int64_t o_ld;
-    const int32_t *o_rowmap;
-    int32_t hpb;          // heads per workgroup (1, 2 or 4)
-    int32_t gy;           // (batch, kv head, head block) combinations: blockIdx.x = query tile * gy + combination
-};
-
+#include "attn_bf16.h"
 
 // ---------------------------------------------------------------------------- V -> V^T (tile order)
 // vt[b][g][c][64 t + col(i)] = v[b][g][row(tile t, i)][c] for i < n_rows(t), zero for the padding of a
@@ -669,7 +597,7 @@ static int32_t launch_attn_cfg(const cascade_plan *p, const AttnArgs &a, hipStre
     // Under a causal mask a tile's work grows with its largest position: longest tiles first, so that a
     // launch of several rounds does not end on a long workgroup.
     k.qtiles = a.mask_kind == CASCADE_MASK_CAUSAL ? ql.dev_by_pmax_desc : ql.dev; k.kvtiles = a.fused ? kl.dev_by_pmin : kl.dev_by_shard_pmin; k.kv_shard_first = kl.shard_first; k.n_kvtiles = kl.count;
-    k.pos_packed = p->pos_packed_d; k.pos_kv = kvp->pos_packed_d;
+    k.pos_packed = p->pos_packed_d; k.pos_kv = kvp->pos_packed_d; k.pos_kv_padded = kl.pos_padded;
     k.B = a.B; k.H = a.H; k.Hkv = a.Hkv; k.N = N; k.S = S;
     k.scale_log2 = a.scale * LOG2E;
     k.causal = a.mask_kind == CASCADE_MASK_CAUSAL; k.fused = a.fused; k.u_mode = a.u_mode;
@@ -683,6 +611,14 @@ static int32_t launch_attn_cfg(const cascade_plan *p, const AttnArgs &a, hipStre
     const int64_t gy = (int64_t)a.B * a.Hkv * (rep / hpb);
     if (gy * ql.count > INT32_MAX || S > 65535) return CASCADE_EUNSUPPORTED;
     k.gy = (int32_t)gy;
+    // fused mode with full-size query tiles: the software-pipelined kernel (same tiles, same parameters; its mask
+    // forms "query position - key position" in 32 bits: positions below 2^30 in magnitude)
+    if (a.fused && NWV == 8 && p->max_abs_pos < (1 << 30) && kvp->max_abs_pos < (1 << 30)) {
+        bool all_visible = a.mask_kind != CASCADE_MASK_CAUSAL;
+        for (int j = 0; j < kvp->n_shards && all_visible; ++j)
+            all_visible = (kvp->offsets_h[j + 1] - kvp->offsets_h[j]) % KV_TILE == 0;
+        return launch_attn_fused(k, D, ql.count, all_visible, s);
+    }
     dim3 grid((unsigned)(gy * ql.count), 1, a.fused ? 1 : S);
     hipLaunchKernelGGL(kern, grid, dim3(NWV * 64), lds, s, k);
     CASCADE_HIP_TRY(hipGetLastError());

@@ -1,0 +1,490 @@
+// Fused bf16 attention for the layer path: the attention-pass of every (query shard, key/value shard) pair
+// (Algorithm 3) with the post-pass merge (the running n, w, o of Algorithm 4) kept in registers while the
+// key/value tiles of all shards are walked.  Software-pipelined inside each wavefront.
+//
+// Work split and data layout are those of the partial-attention kernel (attn_bf16.hip): a workgroup of 8
+// wavefronts, two per SIMD, owns one tile of packed query rows for up to 4 query heads sharing a key/value
+// head; a wavefront owns 32 query rows of one head; S^T = K Q^T so a lane holds one query row; O^T = V^T P^T
+// with the exponentials going from the accumulator layout straight into the B operand; 64-key tiles of K,
+// V^T (key-permuted) and key positions go from L2/HBM straight into LDS, four stages, swizzled rows.
+//
+// What is different.  The three independent streams of work of a step are interleaved by hand inside the
+// wavefront, instruction by instruction:
+//
+//   step k (half tile = 32 keys):   MFMA   S^T(k)   = K(k) Q^T            (scores of half tile k)
+//                                   MFMA   O^T     += V^T(k-2) P^T(k-2)   (trailing by two half tiles)
+//                                   MFMA   l       += 1 P^T(k-2)          (row sums: the same product against ones)
+//                                   VALU   P(k-1)   = exp2(S(k-1) scale - m)
+//                                   VALU   mask and lane maximum of S(k) (second half of the step)
+//
+// Measured on MI355X (one wavefront, loops of MFMAs with vector instructions behind each): a 16x16x32 MFMA
+// holds the matrix pipe for 16 cycles but the wavefront's issue for 8, a vector instruction takes 4 (an
+// exponential ~9), so two vector instructions per MFMA are free and every further one costs its full time;
+// a taken branch costs ~50 cycles (the kernel is issue-bound: one instruction stream per wavefront, and the
+// scalar, LDS and vector instructions of a wavefront only overlap with those of the SIMD's other wavefront).
+// Hence: the MFMAs are inline assembly in a fixed order with the vector arithmetic cut into chunks of a few
+// instructions between them (a scheduling barrier after every group keeps the compiler from regrouping them);
+// a step is straight-line code; the row sums and the rescaling bookkeeping cost no vector instructions; the
+// mask is a few branch-free instructions per score; operand fragments are read from LDS RD fragments ahead
+// through a register ring, across step boundaries; tile loads are requested two tile periods ahead and the
+// barrier waits with a counted vmcnt, not for the youngest requests.
+// (Tried and measured slower: one wavefront per SIMD with 64 query rows, i.e. half the LDS reads per MFMA
+// and 512 registers - without a second wavefront nothing overlaps its scalar instructions and waits.)
+//
+// Rules this file has to keep, because the compiler does not see the MFMAs:
+//  * nothing but the MFMA statements may touch the accumulators (O^T, row sums) inside the tile loop; a
+//    compiler-visible use there makes it copy them between register files right behind an MFMA that is still
+//    in flight.  That is why a late move of an exponent offset restarts the pass instead of rescaling.
+//  * a register an MFMA reads must not be written by a vector instruction directly in front of it (the
+//    hardware needs wait states the compiler only inserts for MFMAs it knows): constants fed to MFMAs are
+//    made opaque so that they are not rebuilt in place; the build scans the ISA for both conditions.
+//  * every MFMA statement appears once in the loop (two copies make the register allocator shuffle the
+//    accumulators between them), so "masked or not" is a kernel parameter, not a choice per tile.
+//
+// The exponent offset m of a row is an integer (the ceiling of the running maximum in log2 units) that is
+// set by the row's first visible score and moves only when a later maximum exceeds it by more than 2^40.
+#include <climits>
+#include <cstdlib>
+#include <type_traits>
+#include <utility>
+#include "attn_bf16.h"
+
+namespace {
+
+template <int... I, typename F>
+__device__ __forceinline__ void static_for_impl(std::integer_sequence<int, I...>, F &&f) {
+    (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F &&f) {
+    static_for_impl(std::make_integer_sequence<int, N>{}, static_cast<F &&>(f));
+}
+
+// S^T accumulators live in vector registers (the softmax reads them), query fragments in accumulation
+// registers; O^T accumulators in accumulation registers.
+__device__ __forceinline__ void mfma_s_first(f32x4 &c, const bf16x8 &k, const bf16x8 &q) {
+    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, 0" : "=&v"(c) : "v"(k), "a"(q));
+}
+__device__ __forceinline__ void mfma_s(f32x4 &c, const bf16x8 &k, const bf16x8 &q) {
+    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+v"(c) : "v"(k), "a"(q));
+}
+__device__ __forceinline__ void mfma_o(f32x4 &c, const bf16x8 &vt, const bf16x8 &pt) {
+    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(vt), "v"(pt));
+}
+// The compiler does not see those MFMAs: before anything else touches their results, let the last
+// ones leave the matrix pipeline.
+__device__ __forceinline__ void mfma_drain() { asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" ::: "memory"); }
+__device__ __forceinline__ void fence() { __builtin_amdgcn_sched_barrier(0); }
+
+}   // namespace
+
+// TQ: 16-row query blocks per wavefront (2: 32 rows, 8 wavefronts; 4: 64 rows, 4 wavefronts).  MASKED: every score is compared with its
+// key's position (causal plans, plans with ragged key/value tiles); false only when every key of every tile
+// is visible to every query.  A kernel parameter rather than a choice per tile: a second copy of the MFMA
+// statements inside the loop makes the register allocator shuffle the accumulators between the copies.
+template <int D, int TQ, bool MASKED>
+__global__ __launch_bounds__(1024 / TQ) void attn_fused_kernel(AttnBf16Params p) {
+    constexpr int KS = D / 32;                         // k-steps of the score product
+    constexpr int DB = D / 16;                         // 16-row blocks of O^T
+    constexpr int K_ROW = D * 2;                       // bytes per K row in LDS
+    constexpr int K_RPI = 1024 / K_ROW;                // K rows filled by one direct-to-LDS instruction
+    constexpr int K_CPR = K_ROW / 16;
+    constexpr int K_BYTES = KV_TILE * K_ROW, V_BYTES = D * 128;
+    constexpr int STAGE = K_BYTES + V_BYTES + KV_TILE * 4;
+    constexpr int NWV = 16 / TQ, NST = 4;              // 4 wavefronts (one per SIMD) or 8 (two per SIMD)
+    constexpr int K_INSTR = KV_TILE / K_RPI / NWV, V_INSTR = D / 8 / NWV;
+    constexpr int NQF = 2 * KS, NVF = DB;              // operand fragments per step: K (2 key blocks), V^T
+    constexpr float RESCALE_LOG2 = 40.0f;              // exponentials stay below 2^40
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l16 = lane & 15, g4 = lane >> 4;
+    const int hpb = p.hpb;
+    const int hsel = wave % hpb, rg = wave / hpb;
+    const int rep = p.H / p.Hkv;
+    const int hblocks = rep / hpb;
+    const int q_tile = blockIdx.x / p.gy, by = blockIdx.x % p.gy;
+    const int b = by / (p.Hkv * hblocks);
+    const int gh = by % (p.Hkv * hblocks);
+    const int g = gh / hblocks;
+    const int h = g * rep + (gh % hblocks) * hpb + hsel;
+
+    const tile_cptr kvtiles = (tile_cptr)p.kvtiles;
+    const tile_cptr qtp = (tile_cptr)p.qtiles + q_tile;
+    const int q_row_start = qtp->row_start, q_n_rows = qtp->n_rows, q_pmax = qtp->pmax;
+    const int wrow0 = rg * 16 * TQ;
+
+    // ---- query fragments (B operand of S^T = K Q^T): lane holds row l16 of each 16-row block, head-dim
+    //      chunk 32 ks + 8 g4
+    bf16x8 Q[TQ][KS];
+    int qlim[TQ];
+    bool row_ok[TQ];
+#pragma unroll
+    for (int qb = 0; qb < TQ; ++qb) {
+        const int rloc = wrow0 + 16 * qb + l16;
+        row_ok[qb] = rloc < q_n_rows;
+        const int r = q_row_start + (row_ok[qb] ? rloc : q_n_rows - 1);
+        const bf16_t *qp = p.q + b * p.qs_b + h * p.qs_h + (int64_t)(p.q_rowmap ? p.q_rowmap[r] : r) * p.qs_n + g4 * 8;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) Q[qb][ks] = *(const bf16x8 *)(qp + ks * 32);
+        qlim[qb] = p.causal ? p.pos_packed[r] : INT_MAX - 1;
+    }
+
+    // ---- visible key/value tiles: a prefix of the list ordered by smallest position
+    int t_end = p.n_kvtiles;
+    if (p.causal) {
+        int n = 0;
+        for (int base = 0; base < p.n_kvtiles; base += 64) {
+            const int t = base + lane;
+            n += __popcll(__ballot(t < p.n_kvtiles && p.kvtiles[t].pmin <= q_pmax));
+        }
+        t_end = __builtin_amdgcn_readfirstlane(n);
+    }
+    const int n_tiles = t_end;
+
+    struct TileMeta {
+        int row_start, n_rows, index, pmax;
+    };
+    auto load_meta = [&](int t) {
+        TileMeta m;
+        const tile_cptr tp = kvtiles + t;
+        m.row_start = tp->row_start; m.n_rows = tp->n_rows; m.index = tp->index; m.pmax = tp->pmax;
+        return m;
+    };
+
+    const __amdgpu_buffer_rsrc_t rk = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<bf16_t *>(p.k + b * p.ks_b + g * p.ks_h), 0, p.k_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rv = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<bf16_t *>(p.vt + b * p.vts_b + g * p.vts_h), 0, p.vt_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rp = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<int32_t *>(p.pos_kv_padded), 0, (uint32_t)p.n_kvtiles * KV_TILE * 4, 0x00020000);
+
+    uint32_t k_lane[K_INSTR], v_lane[V_INSTR];
+    int k_rr[K_INSTR];
+#pragma unroll
+    for (int i = 0; i < K_INSTR; ++i) {
+        const int rr = (wave * K_INSTR + i) * K_RPI + lane / K_CPR;
+        const int slot = lane % K_CPR;
+        const int c = D == 128 ? (slot ^ (rr & 15)) : (slot ^ ((rr >> 1) & 7));
+        k_rr[i] = rr;
+        k_lane[i] = (uint32_t)rr * (uint32_t)(p.ks_n * 2) + c * 16;
+    }
+#pragma unroll
+    for (int i = 0; i < V_INSTR; ++i) {
+        const int rr = (wave * V_INSTR + i) * 8 + (lane >> 3);
+        const int c = (lane & 7) ^ ((rr >> 1) & 7);
+        v_lane[i] = (uint32_t)rr * (uint32_t)(p.npad * 2) + c * 16;
+    }
+    // K rows and key positions of a tile (K_INSTR + 1 loads per wavefront), V^T columns of a tile (V_INSTR loads)
+    auto issue_k = [&](const TileMeta &tm, int stage) {
+        unsigned char *sk = smem + stage * STAGE;
+        const uint32_t k_tile = (uint32_t)tm.row_start * (uint32_t)(p.ks_n * 2);
+#pragma unroll
+        for (int i = 0; i < K_INSTR; ++i)
+            load16_to_lds(rk, sk + (wave * K_INSTR + i) * K_RPI * K_ROW, k_rr[i] < tm.n_rows ? k_tile + k_lane[i] : OOB_OFF);
+        // every wavefront writes the same 64 positions (INT_MAX past a ragged tile's end): keeps the
+        // loads-per-batch count uniform
+        load4_to_lds(rp, sk + K_BYTES + V_BYTES, (uint32_t)(tm.index * KV_TILE + lane) * 4);
+    };
+    auto issue_v = [&](const TileMeta &tm, int stage) {
+        unsigned char *sv = smem + stage * STAGE + K_BYTES;
+        const uint32_t v_tile = (uint32_t)tm.index * (KV_TILE * 2);
+#pragma unroll
+        for (int i = 0; i < V_INSTR; ++i)
+            load16_to_lds(rv, sv + (wave * V_INSTR + i) * 8 * 128, v_tile + v_lane[i]);
+    };
+
+    // ---- state
+    f32x4 O[TQ][DB];                                   // accumulation registers
+    f32x4 L[TQ];                                       // row sums of the exponentials, accumulated by the matrix pipe
+    f32x4 S[2][TQ][2];                                 // scores of a half tile: [buffer][query block][key block]
+    u32x4 P[2][TQ];                                    // exponentials of a half tile (8 bf16), B operand layout
+    constexpr int RD = (D == 128 ? 7 : 3);             // operand fragments read ahead of their use
+    constexpr int RING = RD + 1;
+    static_assert((NQF + NVF) % RING == 0, "the ring position of a step's first fragment must not move");
+    bf16x8 ring[RING];                                 // operand fragments in flight
+    float m_run[TQ], m_thr[TQ], nm_sub[TQ], lmax[TQ];
+#pragma unroll
+    for (int qb = 0; qb < TQ; ++qb) {
+        // the threshold starts at the most negative finite value: any finite score passes it, -inf does not,
+        // and "score - threshold" is never inf - inf
+        m_run[qb] = -INFINITY; m_thr[qb] = -3.0e38f; nm_sub[qb] = 0.f; lmax[qb] = -INFINITY;
+    }
+    // A block of ones as A operand turns the output product into the row sums.  The value is made opaque so
+    // that it stays in four registers: rebuilt by moves right in front of an MFMA the compiler does not see,
+    // it would be read before the moves have landed.
+    bf16x8 ones = {(bf16_t)1.f, (bf16_t)1.f, (bf16_t)1.f, (bf16_t)1.f, (bf16_t)1.f, (bf16_t)1.f, (bf16_t)1.f, (bf16_t)1.f};
+    asm volatile("" : "+v"(ones));
+    const float sl2 = p.scale_log2;
+    const int k_swz = D == 128 ? l16 : (l16 >> 1);
+    const int v_swz = l16 >> 1;
+    const int kf_lane = l16 * K_ROW, vf_lane = K_BYTES + l16 * 128;
+
+    // Fragment f of a step whose score product reads half X of the K tile in stage qs and whose output
+    // product reads half X of the V^T tile in stage vs: the K fragments (key block, k-step) come first.
+    auto frag_ptr = [&](int qs, int vs, auto x_tag, int f) -> const unsigned char * {
+        constexpr int X = decltype(x_tag)::value;
+        if (f < NQF) {
+            const int kvb = 2 * X + f / KS, ks = f % KS;
+            return smem + qs * STAGE + kvb * 16 * K_ROW + kf_lane + (((4 * ks + g4) ^ k_swz) * 16);
+        }
+        const int db = f - NQF;
+        return smem + vs * STAGE + db * 16 * 128 + vf_lane + (((4 * X + g4) ^ v_swz) * 16);
+    };
+
+    // ---- pieces of a step.  X = which half of their tiles the two products of the step read; the scores go
+    // to S[X], the exponentials consumed by the output product are P[X]; the softmax turns S[1-X] into P[1-X].
+    // Every chunk of vector arithmetic is bracketed by empty volatile assembly statements on its inputs and
+    // results, which keeps the optimiser from hoisting or sinking it past the MFMAs it is placed between.
+    typedef __attribute__((ext_vector_type(4))) int i32x4;
+
+    // exponentials of the four scores of one (query block, key block) pair: chunk e = 2 qb + kb
+    auto exp_chunk = [&](auto x_tag, auto e_tag) {
+        constexpr int X = decltype(x_tag)::value, e = decltype(e_tag)::value;
+        constexpr int qb = e / 2, kb = e % 2;
+        const f32x4 sv = S[1 - X][qb][kb];
+        const float p0 = __builtin_amdgcn_exp2f(fmaf(sv[0], sl2, nm_sub[qb]));
+        const float p1 = __builtin_amdgcn_exp2f(fmaf(sv[1], sl2, nm_sub[qb]));
+        const float p2 = __builtin_amdgcn_exp2f(fmaf(sv[2], sl2, nm_sub[qb]));
+        const float p3 = __builtin_amdgcn_exp2f(fmaf(sv[3], sl2, nm_sub[qb]));
+        uint32_t w0 = __builtin_bit_cast(uint32_t, bf16x2{(bf16_t)p0, (bf16_t)p1});
+        uint32_t w1 = __builtin_bit_cast(uint32_t, bf16x2{(bf16_t)p2, (bf16_t)p3});
+        asm volatile("" : "+v"(w0), "+v"(w1));
+        P[1 - X][qb][2 * kb] = w0;
+        P[1 - X][qb][2 * kb + 1] = w1;
+    };
+    // mask of the four scores of one (query block, key block) pair of S[X]: a score whose key position is above
+    // the query's becomes -inf.  d = limit - position is negative exactly then; its sign bit over the bits of
+    // +inf is -inf or +inf, and min(score, that) needs no condition register and no branch.
+    uint32_t sign_bit = 0x80000000u, inf_bits = 0x7F800000u;
+    asm volatile("" : "+v"(sign_bit), "+v"(inf_bits));   // in registers: one bit-field insert per score
+    auto mask_chunk = [&](auto x_tag, auto qb_tag, auto kb_tag, const i32x4 (&pk)[2]) {
+        constexpr int X = decltype(x_tag)::value, qb = decltype(qb_tag)::value, kb = decltype(kb_tag)::value;
+        f32x4 sv = S[X][qb][kb];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const uint32_t d = (uint32_t)(qlim[qb] - pk[kb][r]);
+            const float bias = __builtin_bit_cast(float, (d & sign_bit) | (inf_bits & ~sign_bit));
+            sv[r] = fminf(sv[r], bias);
+        }
+        asm volatile("" : "+v"(sv));
+        S[X][qb][kb] = sv;
+    };
+    // this lane's maximum over its 8 scores of query block qb of S[X] (log2 units); flagv collects by how much
+    // a maximum is above its row's threshold
+    auto max_chunk = [&](auto x_tag, auto qb_tag, float &flagv) {
+        constexpr int X = decltype(x_tag)::value, qb = decltype(qb_tag)::value;
+        const f32x4 a = S[X][qb][0], c = S[X][qb][1];
+        float mx = fmaxf(fmaxf(fmaxf(a[0], a[1]), fmaxf(a[2], a[3])), fmaxf(fmaxf(c[0], c[1]), fmaxf(c[2], c[3]))) * sl2;
+        float fl = fmaxf(flagv, mx - m_thr[qb]);
+        asm volatile("" : "+v"(mx), "+v"(fl));
+        lmax[qb] = mx;
+        flagv = fl;
+    };
+    // key positions of this lane's accumulator rows (keys 16 kb + 4 g4 + 0..3 of half X) from the tile's stage
+    // (INT_MAX for the keys past a ragged tile's end: never visible)
+    auto read_positions = [&](auto x_tag, int qs, i32x4 (&pk)[2]) {
+        constexpr int X = decltype(x_tag)::value;
+        const unsigned char *pp = smem + qs * STAGE + K_BYTES + V_BYTES + (32 * X + 4 * g4) * 4;
+        pk[0] = *(const i32x4 *)pp;
+        pk[1] = *(const i32x4 *)(pp + 64);
+    };
+
+    // ---- one step: scores of (qs, X) into S[X], output product of (vs, X) with P[X] (and the row sums: the
+    // same product against a block of ones), exponentials of S[1-X] into P[1-X], then (MASKED) the mask and
+    // the lane maxima of the new scores.  Straight-line code: a taken branch costs this kernel some fifty
+    // cycles, so the only choice, masked or not, is made once per tile outside.  On entry the ring holds the
+    // first RD fragments; on exit those of the next step (half 1-X, stages nqs / nvs).  Returns whether some
+    // maximum passed its row's threshold.
+    auto step = [&](auto x_tag, int qs, int vs, int nqs, int nvs) -> bool {
+        constexpr int X = decltype(x_tag)::value;
+        constexpr int NF = NQF + NVF, QS = TQ * NQF, NS = TQ * NF + TQ;   // slots: scores, output, row sums
+        constexpr int NE = 2 * TQ;                           // chunks of exponentials: one per (query block, key block) pair
+        constexpr int NT = 3 * TQ;                           // chunks of the tail: per query block 2 of mask, 1 of maxima
+        const std::integral_constant<int, 1 - X> nx;
+        i32x4 pk[2];
+        if constexpr (MASKED) read_positions(x_tag, qs, pk);
+        float flagv = 0.f;
+        fence();
+        auto after_slot = [&](auto s_tag) {
+            constexpr int s = decltype(s_tag)::value;
+            // exponentials: chunk e behind slot e * NS / NE + 1
+            static_for<NE>([&](auto e_tag) {
+                constexpr int e = decltype(e_tag)::value;
+                if constexpr (e * NS / NE + 1 == s) exp_chunk(x_tag, e_tag);
+            });
+            // tail: chunk t behind slot QS + 2 + t * (NS - QS - 3) / NT (the scores are complete after slot QS - 1)
+            static_for<NT>([&](auto t_tag) {
+                constexpr int t = decltype(t_tag)::value;
+                if constexpr (QS + 2 + t * (NS - QS - 3) / NT == s) {
+                    constexpr int tq = t / 3, c = t % 3;
+                    if constexpr (c < 2) {
+                        if constexpr (MASKED)
+                            mask_chunk(x_tag, std::integral_constant<int, tq>{}, std::integral_constant<int, c>{}, pk);
+                    } else {
+                        max_chunk(x_tag, std::integral_constant<int, tq>{}, flagv);
+                    }
+                }
+            });
+            fence();
+        };
+        static_for<NF>([&](auto f_tag) {
+            constexpr int f = decltype(f_tag)::value;
+            // fragment f + RD of this step, or one of the first RD of the next
+            if constexpr (f + RD < NF) ring[(f + RD) % RING] = *(const bf16x8 *)frag_ptr(qs, vs, x_tag, f + RD);
+            else ring[(f + RD) % RING] = *(const bf16x8 *)frag_ptr(nqs, nvs, nx, f + RD - NF);
+            fence();
+            static_for<TQ>([&](auto qb_tag) {
+                constexpr int qb = decltype(qb_tag)::value;
+                if constexpr (f < NQF) {
+                    constexpr int kb = f / KS, ks = f % KS;
+                    if constexpr (ks == 0) mfma_s_first(S[X][qb][kb], ring[f % RING], Q[qb][ks]);
+                    else mfma_s(S[X][qb][kb], ring[f % RING], Q[qb][ks]);
+                } else {
+                    mfma_o(O[qb][f - NQF], ring[f % RING], __builtin_bit_cast(bf16x8, P[X][qb]));
+                }
+                after_slot(std::integral_constant<int, TQ * f + qb>{});
+            });
+        });
+        static_for<TQ>([&](auto qb_tag) {
+            constexpr int qb = decltype(qb_tag)::value;
+            mfma_o(L[qb], ones, __builtin_bit_cast(bf16x8, P[X][qb]));
+            after_slot(std::integral_constant<int, TQ * NF + qb>{});
+        });
+        return __builtin_amdgcn_readfirstlane(__any(flagv > 0.f));
+    };
+
+    // ---- between steps.  A maximum that passed its row's threshold moves the row's exponent offset to the
+    // ceiling of that maximum.  For a row without a maximum so far this is free (its exponentials were all
+    // zero).  For a row that already has contributions the accumulators would have to be rescaled; nothing
+    // but the MFMAs may touch them inside the loop (the compiler does not see those MFMAs and would move
+    // accumulators around them), so that case, which needs a score 2^RESCALE_LOG2 times above everything
+    // the row has seen before, abandons the pass instead: the offset moves, the pass runs to its end on
+    // values nobody uses, and the whole workgroup starts over with the larger offsets.
+    bool redo = false;
+    auto between_steps = [&](bool need) {
+        if (__builtin_expect(need, 0)) {
+#pragma unroll
+            for (int qb = 0; qb < TQ; ++qb) {
+                const float rowmax = xor_max_16_32(lmax[qb]);
+                const bool grow = rowmax > m_thr[qb];
+                const float m_new = grow ? ceilf(rowmax) : m_run[qb];
+                if (__builtin_amdgcn_readfirstlane(__any(grow && m_run[qb] != -INFINITY))) redo = true;
+                m_run[qb] = m_new;
+                m_thr[qb] = m_new == -INFINITY ? -3.0e38f : m_new + RESCALE_LOG2;
+                nm_sub[qb] = m_new == -INFINITY ? 0.f : -m_new;
+            }
+        }
+        fence();
+    };
+
+    // ---- main loop.  Step k: scores of half tile k, exponentials of half tile k-1, output product of half
+    // tile k-2.  Tile i = half tiles 2i, 2i+1; its K rows and key positions sit in stage i % NST from two tile
+    // periods before their first use, its V^T columns from one period later (they are needed a step later and
+    // the V^T region of a stage is released a step later).  The first two and the last two steps run the same
+    // code on stand-ins: scores of -inf give exponentials of zero, exponentials of zero add nothing, and the
+    // scores computed past the last tile are never used.
+    const std::integral_constant<int, 0> x0;
+    const std::integral_constant<int, 1> x1;
+    constexpr int LPT_K = K_INSTR + 1, LPT_V = V_INSTR;
+    static_assert(NST == 4, "stage arithmetic");
+    volatile int *redo_flags = (volatile int *)(smem + NST * STAGE);   // one word per wavefront
+    for (;;) {                                         // one pass, unless an exponent offset had to move late
+        redo = false;
+#pragma unroll
+        for (int qb = 0; qb < TQ; ++qb) {
+            P[0][qb] = P[1][qb] = u32x4{0u, 0u, 0u, 0u};
+            L[qb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb) S[0][qb][kb] = S[1][qb][kb] = f32x4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+#pragma unroll
+            for (int db = 0; db < DB; ++db) O[qb][db] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+        TileMeta mt0 = {0, 0, 0, INT_MAX}, mt1 = mt0, mt2 = mt0, mt3 = mt0;     // tiles i .. i+3
+        if (0 < n_tiles) mt0 = load_meta(0);
+        if (1 < n_tiles) mt1 = load_meta(1);
+        if (2 < n_tiles) mt2 = load_meta(2);
+        if (3 < n_tiles) mt3 = load_meta(3);
+        if (0 < n_tiles) { issue_k(mt0, 0); issue_v(mt0, 0); }
+        if (1 < n_tiles) { issue_k(mt1, 1); issue_v(mt1, 1); }
+        if (2 < n_tiles) issue_k(mt2, 2);
+        phase_barrier<0, false>();                     // everything requested so far is complete and visible
+        if (n_tiles > 0) {
+#pragma unroll
+            for (int f = 0; f < RD; ++f) ring[f] = *(const bf16x8 *)frag_ptr(0, 0, x0, f);
+            int in_flight = 0;                         // loads of this wavefront requested at the previous barrier
+            for (int i = 0; i <= n_tiles; ++i) {
+                const bool real = i < n_tiles, next_real = i + 1 < n_tiles;
+                const int qs = (real ? i : i - 1) & (NST - 1);      // past the end: the last tile again (finite scores)
+                const int vs = (i > 0 ? i - 1 : 0) & (NST - 1);     // tile i-1; in front of the first tile: P is zero
+                const int nqs = (next_real ? i + 1 : i) & (NST - 1), nvs = i & (NST - 1);
+                const bool need0 = step(x0, qs, vs, qs, vs);
+                between_steps(need0 && real);
+                // The barrier between the two steps of a tile: what was requested two barriers ago has landed (the
+                // requests of the previous barrier may still be in flight), everyone is past step 2i.  Free from
+                // here on: the K region of stage i-1 (last read in step 2i-1), the V^T region of stage i-2 (2i-1).
+                __builtin_amdgcn_sched_barrier(0);
+                if (in_flight == LPT_K + LPT_V) asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(LPT_K + LPT_V) : "memory");
+                else if (in_flight == LPT_V) asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(LPT_V) : "memory");
+                else asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+                __builtin_amdgcn_sched_barrier(0);
+                in_flight = 0;
+                if (i + 3 < n_tiles) { issue_k(mt3, (i + 3) & (NST - 1)); in_flight += LPT_K; }
+                if (i + 2 < n_tiles) { issue_v(mt2, (i + 2) & (NST - 1)); in_flight += LPT_V; }
+                const bool need1 = step(x1, qs, vs, nqs, nvs);
+                between_steps(need1 && real);
+                if (real) {
+                    if (next_real) mt0 = mt1;
+                    mt1 = mt2; mt2 = mt3;
+                    if (i + 4 < n_tiles) mt3 = load_meta(i + 4);
+                }
+            }
+        }
+        mfma_drain();
+        // start over together if any wavefront had to move an offset late (the barriers are the workgroup's)
+        if (lane == 0) redo_flags[wave] = redo ? 1 : 0;
+        phase_barrier<0, true>();
+        int any_redo = 0;
+#pragma unroll
+        for (int w = 0; w < NWV; ++w) any_redo |= redo_flags[w];
+        phase_barrier<-1, true>();
+        if (!__builtin_amdgcn_readfirstlane(any_redo)) break;
+    }
+
+    // ---- write-out.  O[qb][db][r]: query row 16 qb + l16, column 16 db + 4 g4 + r; every row of L[qb] holds the
+    // row sum of query 16 qb + l16.
+#pragma unroll
+    for (int qb = 0; qb < TQ; ++qb) {
+        if (!row_ok[qb]) continue;
+        const float l_tot = L[qb][0];
+        const int r = q_row_start + wrow0 + 16 * qb + l16;
+        const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
+        bf16_t *op = p.o + ((int64_t)b * p.N + (p.o_rowmap ? p.o_rowmap[r] : r)) * p.o_ld + (int64_t)h * D + 4 * g4;
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+            const f32x4 v = O[qb][db] * inv;
+            *(bf16x4 *)(op + 16 * db) = bf16x4{(bf16_t)v[0], (bf16_t)v[1], (bf16_t)v[2], (bf16_t)v[3]};
+        }
+    }
+}
+
+template <int D, int TQ, bool MASKED>
+static int32_t launch_fused_cfg(const AttnBf16Params &k, int n_qtiles, hipStream_t s) {
+    constexpr int lds = 4 * (KV_TILE * D * 2 + D * 128 + KV_TILE * 4) + 32;   // four stages + the start-over flags
+    auto kern = attn_fused_kernel<D, TQ, MASKED>;
+    static std::atomic<uint64_t> lds_ready{0};
+    CASCADE_HIP_TRY(ensure_dynamic_lds((const void *)kern, lds, lds_ready));
+    dim3 grid((unsigned)((int64_t)k.gy * n_qtiles), 1, 1);
+    hipLaunchKernelGGL(kern, grid, dim3(1024 / TQ), lds, s, k);
+    CASCADE_HIP_TRY(hipGetLastError());
+    return CASCADE_OK;
+}
+
+int32_t launch_attn_fused(const AttnBf16Params &k, int head_dim, int n_qtiles, bool all_visible, hipStream_t s) {
+    if (!k.fused) return CASCADE_EINVAL;
+    if (all_visible)
+        return head_dim == 128 ? launch_fused_cfg<128, 2, false>(k, n_qtiles, s) : launch_fused_cfg<64, 2, false>(k, n_qtiles, s);
+    return head_dim == 128 ? launch_fused_cfg<128, 2, true>(k, n_qtiles, s) : launch_fused_cfg<64, 2, true>(k, n_qtiles, s);
+}

@@ -31,6 +31,7 @@ static void free_plan(cascade_plan *p) {
         if (t.dev_by_shard_pmin) (void)hipFree(t.dev_by_shard_pmin);
         if (t.dev_by_pmax_desc) (void)hipFree(t.dev_by_pmax_desc);
         if (t.shard_first) (void)hipFree(t.shard_first);
+        if (t.pos_padded) (void)hipFree(t.pos_padded);
         free(t.shard_first_host);
     }
     delete p;
@@ -95,6 +96,13 @@ static hipError_t build_tiles(cascade_plan *p, CascadeTileList &out, int granule
     std::stable_sort(sorted.begin(), sorted.end(), [](const CascadeTile &x, const CascadeTile &y) { return x.pmax > y.pmax; });
     e = to_device(&out.dev_by_pmax_desc, sorted.data(), sorted.size());
     if (e != hipSuccess) return e;
+    if (granule == 64) {
+        std::vector<int32_t> padded(tiles.size() * 64, INT_MAX);
+        for (size_t t = 0; t < tiles.size(); ++t)
+            for (int i = 0; i < tiles[t].n_rows; ++i) padded[t * 64 + i] = p->pos_packed_h[tiles[t].row_start + i];
+        e = to_device(&out.pos_padded, padded.data(), padded.size());
+        if (e != hipSuccess) return e;
+    }
     return to_device(&out.shard_first, first.data(), first.size());
 }
 
