@@ -546,9 +546,12 @@ def cascade_mfma_ceiling(lds_operands, iters=200000, stream=None):
 
 
 def layer_forward_numpy(cfg, weights_np, h_np, token_to_shard, positions=None, attn_mode=ATTN_FUSED,
-                        io_rows=ROWS_ORIGINAL, mask_kind=MASK_CAUSAL, return_partials=False, token_to_kv_shard=None):
+                        io_rows=ROWS_ORIGINAL, mask_kind=MASK_CAUSAL, return_partials=False, token_to_kv_shard=None,
+                        fused_qkv=False):
     """Upload numpy inputs, run cascade_layer_forward once, download the output as float64.
-    token_to_kv_shard: a second partition for keys / values (row shards != key/value shards)."""
+    token_to_kv_shard: a second partition for keys / values (row shards != key/value shards).
+    fused_qkv: the q, k, v weights (and biases) are uploaded as one [(H + 2 H_KV) d, D] matrix and handed over
+    as three views of it (the library then runs the projection as one segment)."""
     import torch
     n_row = int(np.max(token_to_shard)) + 1 if cfg.n_shards is None else cfg.n_shards
     if token_to_kv_shard is None:
@@ -558,6 +561,15 @@ def layer_forward_numpy(cfg, weights_np, h_np, token_to_shard, positions=None, a
                                       token_to_kv_shard, positions, mask_kind)
     desc = make_layer_desc(cfg, attn_mode, io_rows)
     tensors = {k: to_device(v, cfg.dtype) for k, v in weights_np.items()}
+    if fused_qkv:
+        for names in (("wq", "wk", "wv"), ("bq", "bk", "bv")):
+            if all(n in tensors for n in names):
+                whole = torch.cat([tensors[n] for n in names], dim=0).contiguous()
+                row = 0
+                for n in names:
+                    rows = tensors[n].shape[0]
+                    tensors[n] = whole[row:row + rows]
+                    row += rows
     w = make_layer_weights(tensors)
     h_in = to_device(h_np, cfg.dtype)
     h_out = torch.empty_like(h_in)

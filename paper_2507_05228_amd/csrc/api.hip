@@ -170,7 +170,7 @@ extern "C" int32_t cascade_lse_merge(const cascade_plan *plan, const cascade_att
 
 // ---------------------------------------------------------------------------- whole layer
 struct LayerWs {
-    size_t x, qkv, ao, h1, act, attn_ws, m, e, u, total;
+    size_t x, qkv, ao, h1, act, attn_ws, m, e, u, rope, total;
     size_t attn_ws_bytes;
 };
 
@@ -188,6 +188,7 @@ static LayerWs layer_ws(const cascade_plan *plan, const cascade_layer_desc *d) {
     w.act = take(T * (size_t)d->d_ff * es);
     w.attn_ws_bytes = d->dtype == CASCADE_BF16 ? attn_bf16_workspace_bytes(plan, plan->batch, d->n_kv_heads, d->head_dim) : 0;
     w.attn_ws = take(w.attn_ws_bytes);
+    w.rope = take(d->rope && d->dtype == CASCADE_BF16 ? T * (size_t)d->head_dim * 4 : 0);   // cos | sin per row
     if (d->attn_mode == CASCADE_ATTN_MATERIALISED) {
         const size_t me = (size_t)plan->batch * d->n_heads * kv_plan(plan)->n_shards * plan->seq_len * 4;
         w.m = take(me);
@@ -330,11 +331,6 @@ static int32_t layer_forward_impl(const cascade_plan *plan, const cascade_layer_
     // 1. pre-pass: norm (with the gather into packed order), q/k/v projection, rotary embedding (Algorithm 2).
     //    A post-norm block has no norm here: the projection gathers h_in itself.
     if ((st = mark()) != CASCADE_OK) return st;                                   // event 0: start
-    if (!post) {
-        NormArgs n1 = {d->dtype, T, D, d->norm_kind, d->norm_eps, h_in, w->norm1_g, w->norm1_b, x, in_map, packed};
-        if ((st = launch_norm(n1, s)) != CASCADE_OK) return st;
-    }
-    if ((st = mark()) != CASCADE_OK) return st;                                   // 1: gather + norm1
     GemmArgs g = {};
     g.dtype = d->dtype; g.M = T; g.N = QW; g.K = D; g.X = post ? h_in : x;
     g.W[0] = w->wq; g.W[1] = w->wk; g.W[2] = w->wv;
@@ -351,9 +347,24 @@ static int32_t layer_forward_impl(const cascade_plan *plan, const cascade_layer_
     }
     g.epilogue = (w->bq || w->bk || w->bv) ? CASCADE_EPI_BIAS : 0;
     g.Y = qkv; g.ldx = D; g.ldy = QW; g.xmap = post ? in_map : packed; g.ymap = g.rmap = packed;
+    // Rotary embedding: in the projection's epilogue when that kernel can do it (bf16, pre-norm: the norm kernel
+    // then writes every row's cos | sin table on the side), else as a pass of its own over q and k.
+    g.rope_cols = (H + Hkv) * hd; g.rope_head_dim = hd;
+    const bool rope_fused = d->rope && !post && d->dtype == CASCADE_BF16 && plan->max_abs_pos < (1 << 24) &&
+                            gemm_bf16_rope_fusable(g);
+    if (!post) {
+        NormArgs n1 = {d->dtype, T, D, d->norm_kind, d->norm_eps, h_in, w->norm1_g, w->norm1_b, x, in_map, packed};
+        if (rope_fused) {
+            n1.rope_table = (float *)(base + ws.rope); n1.rope_pos = plan->pos_packed_d; n1.rope_seq_len = N;
+            n1.rope_head_dim = hd; n1.rope_theta = d->rope_theta;
+        }
+        if ((st = launch_norm(n1, s)) != CASCADE_OK) return st;
+    }
+    if ((st = mark()) != CASCADE_OK) return st;                                   // 1: gather + norm1
+    if (rope_fused) g.rope_table = (const float *)(base + ws.rope);
     if ((st = run_gemm(g, s)) != CASCADE_OK) return st;
     if ((st = mark()) != CASCADE_OK) return st;                                   // 2: qkv GEMM
-    if (d->rope) {
+    if (d->rope && !rope_fused) {
         RopeArgs r = {d->dtype, T, N, H + Hkv, hd, QW, d->rope_theta, plan->pos_packed_d, qkv, plan->max_abs_pos};
         if ((st = launch_rope(r, s)) != CASCADE_OK) return st;
     }

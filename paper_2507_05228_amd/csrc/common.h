@@ -103,9 +103,15 @@ struct GemmArgs {
     int64_t ldx, ldy, ldres;         // row strides in elements
     RowMap xmap, ymap, rmap;
     int32_t epilogue;
+    // Rotary embedding applied to the output in the epilogue (bf16, see gemm_bf16_rope_fusable): cos | sin of the
+    // angles of every row, [M][rope_head_dim] fp32, rows in the order of the GEMM's rows; columns below rope_cols
+    // are rotated (half-split pairs inside heads of rope_head_dim columns).  nullptr: no rotation.
+    const float *rope_table;
+    int32_t rope_cols, rope_head_dim;
 };
 
 int32_t launch_gemm_bf16(const GemmArgs &a, hipStream_t s);
+bool gemm_bf16_rope_fusable(const GemmArgs &a);
 int32_t launch_gemm_f32(const GemmArgs &a, hipStream_t s);
 
 struct NormArgs {
@@ -114,6 +120,12 @@ struct NormArgs {
     const void *x; const void *gain; const void *bias; void *y;
     RowMap xmap;                     // gather on the read
     RowMap ymap;                     // scatter on the write
+    // Optional by-product: cos | sin of the rotary angles of row r (position rope_pos[r % rope_seq_len]),
+    // [rows][rope_head_dim] fp32, written by the workgroup that normalises row r.  nullptr: none.
+    float *rope_table;
+    const int32_t *rope_pos;
+    int32_t rope_seq_len, rope_head_dim;
+    float rope_theta;
 };
 int32_t launch_norm(const NormArgs &a, hipStream_t s);
 // k, v rows of a packed [T, ld] activation (columns k_col0 .. and v_col0 .., H_kv heads of d) -> cache slabs

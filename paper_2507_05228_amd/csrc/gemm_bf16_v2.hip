@@ -48,6 +48,10 @@ struct Gemm2Params {
     const int32_t *xmap, *ymap, *rmap;
     int32_t seq_len, flags;
     uint32_t x_bytes;
+    // rotary embedding in the epilogue (ROPE kernels): cos | sin of every packed row's angles, [M][head_dim] fp32;
+    // output columns below rope_cols are rotated; rope_lh = log2(head_dim / 2)
+    const float *rope_table;
+    int32_t rope_cols, rope_lh;
 };
 
 typedef __attribute__((address_space(3))) void lds_void;
@@ -187,12 +191,86 @@ __device__ __forceinline__ void gemm_epilogue(const Gemm2Params &p, f32x4 (&acc)
 // and written out in 16-byte pieces that follow each other along the output rows, so every store
 // instruction fills whole cache lines.  Row pitch: an odd multiple of 32 bytes, which spreads the 16
 // rows of a block write over all banks.
+// Accumulator block of the one-wavefront kernels (held in accumulation registers by the tied MFMAs) -> vector
+// registers, at the point of use.  Read through plain C++ the compiler copies all blocks across right behind
+// the main loop, which a 256-accumulator tile has no registers for.
+__device__ __forceinline__ f32x4 acc_load(const f32x4 &c) {
+    float x0, x1, x2, x3;
+    asm volatile("v_accvgpr_read_b32 %0, %4\n\tv_accvgpr_read_b32 %1, %5\n\tv_accvgpr_read_b32 %2, %6\n\t"
+                 "v_accvgpr_read_b32 %3, %7"
+                 : "=v"(x0), "=v"(x1), "=v"(x2), "=v"(x3)
+                 : "a"(c[0]), "a"(c[1]), "a"(c[2]), "a"(c[3]));
+    return f32x4{x0, x1, x2, x3};
+}
+
 template <int BN_OUT>
 struct EpiTile {
     static constexpr int PITCH = ((BN_OUT * 2 + 31) / 32 | 1) * 32;   // bytes
     static constexpr int bytes(int bm) { return bm * PITCH; }
 };
-template <int BM, int NTHREADS, int TM, int TN, int WTN, bool SWIGLU, int BN_OUT>
+// ROPE: the wavefront tile holds WTN/2 rotation pairs (i, i + head_dim/2 of one head): block j the first
+// halves, block j + TN/2 the second halves, same lane and slot, like gate and up of SwiGLU.  The tile's BN
+// staged columns are BN/2 first halves followed by their BN/2 partners; pair p of a segment is column
+// (p / half) head_dim + p % half and the column `half` further on, so 4 (8) consecutive pairs are 4 (8) consecutive
+// columns as long as half is a multiple of 4 (8).  The rotation runs on the fp32 accumulators (one rounding to
+// bf16), with cos and sin read from the table the pre-pass norm kernel wrote for every row.
+template <int BM, int NTHREADS, int TM, int TN, int WTN, int BN>
+__device__ __forceinline__ void gemm_epilogue_tile_rope(const Gemm2Params &p, f32x4 (&acc)[TM][TN], unsigned char *smem,
+                                                        int tid, int m0, int wm0, int wn0, int pair0, int seg,
+                                                        int seg_rows) {
+    static_assert(TN % 2 == 0 && (BN / 2) % 8 == 0, "pairs split the wavefront tile; 16-byte pieces hold 8 pairs");
+    constexpr int TNO = TN / 2;
+    constexpr int PITCH = EpiTile<BN>::PITCH;
+    const int lane = tid & 63, l16 = lane & 15, c4 = (lane >> 4) * 4;
+    const int wp0 = (wn0 / WTN) * (WTN / 2);               // wavefront's first pair inside the tile
+    const int lh = p.rope_lh, half = 1 << lh, n_pairs = seg_rows >> 1;
+    const int gcol0 = p.seg_col0[seg];
+    const bf16_t *bias = (p.flags & CASCADE_EPI_BIAS) ? p.bias[seg] : nullptr;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        const int row = wm0 + 16 * i + l16, gm = m0 + row;
+        const float *trow = p.rope_table + (int64_t)(gm < p.M ? gm : 0) * (2 * half);
+#pragma unroll
+        for (int j = 0; j < TNO; ++j) {
+            const int tp = wp0 + 16 * j + c4;              // pair inside the tile; 4 consecutive pairs, one head
+            const int pp = pair0 + tp, ph = pp & (half - 1);
+            const int col1 = ((pp >> lh) << (lh + 1)) + ph;
+            const bool inside = pp < n_pairs;
+            f32x4 a = acc_load(acc[i][j]), b = acc_load(acc[i][j + TNO]);
+            if (bias && inside)
+#pragma unroll
+                for (int x = 0; x < 4; ++x) { a[x] += (float)bias[col1 + x]; b[x] += (float)bias[col1 + half + x]; }
+            if (inside && gcol0 + col1 < p.rope_cols) {
+                const f32x4 cs = *(const f32x4 *)(trow + ph), sn = *(const f32x4 *)(trow + half + ph);
+                const f32x4 ra = a * cs - b * sn, rb = b * cs + a * sn;
+                a = ra; b = rb;
+            }
+            *(bf16x4 *)(smem + row * PITCH + tp * 2) = bf16x4{(bf16_t)a[0], (bf16_t)a[1], (bf16_t)a[2], (bf16_t)a[3]};
+            *(bf16x4 *)(smem + row * PITCH + (BN / 2 + tp) * 2) = bf16x4{(bf16_t)b[0], (bf16_t)b[1], (bf16_t)b[2], (bf16_t)b[3]};
+        }
+    }
+    __syncthreads();
+    constexpr int CPRO = BN / 8;                           // 16-byte pieces per tile row
+    const bool wide = ((p.ldy | gcol0) % 8 == 0) && ((uintptr_t)p.Y % 16 == 0);
+    for (int q = tid; q < BM * CPRO; q += NTHREADS) {
+        const int row = q / CPRO, piece = q % CPRO;
+        const int hs = piece >= CPRO / 2;                  // second halves
+        const int pp = pair0 + (piece - hs * (CPRO / 2)) * 8;
+        const int gm = m0 + row;
+        if (gm >= p.M || pp >= n_pairs) continue;          // n_pairs is a multiple of half, half of 8
+        const int c = ((pp >> lh) << (lh + 1)) + (pp & (half - 1)) + (hs << lh);
+        const bf16x8 v = *(const bf16x8 *)(smem + row * PITCH + piece * 16);
+        bf16_t *y = p.Y + map_row(p.ymap, p.seq_len, gm) * p.ldy + gcol0 + c;
+        if (wide) {
+            *(bf16x8 *)y = v;
+        } else {
+            *(bf16x4 *)y = bf16x4{v[0], v[1], v[2], v[3]};
+            *(bf16x4 *)(y + 4) = bf16x4{v[4], v[5], v[6], v[7]};
+        }
+    }
+}
+
+template <int BM, int NTHREADS, int TM, int TN, int WTN, bool SWIGLU, int BN_OUT, bool ACT_OK>
 __device__ __forceinline__ void gemm_epilogue_tile(const Gemm2Params &p, f32x4 (&acc)[TM][TN], unsigned char *smem,
                                                    int tid, int m0, int wm0, int wn0, int nloc0, int seg,
                                                    int seg_rows) {
@@ -204,44 +282,63 @@ __device__ __forceinline__ void gemm_epilogue_tile(const Gemm2Params &p, f32x4 (
     const int lane = tid & 63, l16 = lane & 15, c4 = (lane >> 4) * 4;
     const int wc0 = (wn0 / WTN) * OW;                      // wavefront's first output column inside the tile
     const bf16_t *bias = (!SWIGLU && (flags & CASCADE_EPI_BIAS)) ? p.bias[seg] : nullptr;
-    const bool act = flags & (CASCADE_EPI_GELU_ERF | CASCADE_EPI_GELU_TANH);
+    const bool act = ACT_OK && (flags & (CASCADE_EPI_GELU_ERF | CASCADE_EPI_GELU_TANH));
     const int gcol0 = p.seg_col0[seg];
     // Two copies of the unrolled loops, chosen once: the plain one (no bias, no activation) stays small and
     // contiguous in the instruction cache; the GELU code is long and would otherwise sit between every pair
     // of its stores.
+    // The residual of row block i + 1 is requested before row block i is worked on (two register sets), and the
+    // compiler may not move anything across the row-block boundaries: left alone it hoists the loads and the
+    // accumulator reads of all blocks to the top, which the 256-accumulator tile has no registers for.
+    const bool has_res = flags & CASCADE_EPI_RESIDUAL;
+    bf16x4 rv[2][TNO];
+    auto load_res = [&](int i, int buf) {
+        const int gm = m0 + wm0 + 16 * i + l16;
+        const bf16_t *rrow = p.residual + map_row(p.rmap, p.seq_len, gm < p.M ? gm : 0) * p.ldres + gcol0 + nloc0;
+#pragma unroll
+        for (int j = 0; j < TNO; ++j) {
+            const int tc = wc0 + 16 * j + c4;
+            rv[buf][j] = bf16x4{0, 0, 0, 0};
+            if (gm < p.M && nloc0 + tc < seg_rows) rv[buf][j] = *(const bf16x4 *)(rrow + tc);
+        }
+    };
     auto to_lds = [&](auto general_tag) {
     constexpr bool GENERAL = decltype(general_tag)::value;
+    if (has_res) load_res(0, 0);
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
-        const int row = wm0 + 16 * i + l16, gm = m0 + row;
-        const bf16_t *rrow = ((flags & CASCADE_EPI_RESIDUAL) && gm < p.M)
-                                 ? p.residual + map_row(p.rmap, p.seq_len, gm) * p.ldres + gcol0 + nloc0 : nullptr;
+        const int row = wm0 + 16 * i + l16;
+        if (has_res && i + 1 < TM) load_res(i + 1, (i + 1) & 1);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int j = 0; j < TNO; ++j) {
             const int tc = wc0 + 16 * j + c4;              // column inside the tile
             // the segment's width and tc are multiples of 4: these 4 columns are all inside the segment or all
             // outside (then their values are never stored and need neither bias nor residual)
             const bool inside = nloc0 + tc < seg_rows;
-            f32x4 v = acc[i][j];
-            if (SWIGLU) {
+            f32x4 v = acc_load(acc[i][j]);
+            if constexpr (SWIGLU) {
+                const f32x4 up = acc_load(acc[i][j + TNO]);
 #pragma unroll
-                for (int x = 0; x < 4; ++x) v[x] = silu_fast(v[x]) * acc[i][j + TNO][x];
+                for (int x = 0; x < 4; ++x) v[x] = silu_fast(v[x]) * up[x];
             } else if constexpr (GENERAL) {
                 if (bias && inside)
 #pragma unroll
                     for (int x = 0; x < 4; ++x) v[x] += (float)bias[nloc0 + tc + x];
-                if (act)
+                if constexpr (ACT_OK)
+                    if (act)
 #pragma unroll
-                    for (int x = 0; x < 4; ++x) v[x] = apply_act(v[x], flags);
+                        for (int x = 0; x < 4; ++x) v[x] = apply_act(v[x], flags);
             }
-            if (rrow && inside) {                          // added before the one rounding to bf16
-                const bf16x4 rv = *(const bf16x4 *)(rrow + tc);
+            if (has_res) {                                 // added before the one rounding to bf16
+                const bf16x4 r4 = rv[i & 1][j];
 #pragma unroll
-                for (int x = 0; x < 4; ++x) v[x] += (float)rv[x];
+                for (int x = 0; x < 4; ++x) v[x] += (float)r4[x];
             }
             const bf16x4 o = {(bf16_t)v[0], (bf16_t)v[1], (bf16_t)v[2], (bf16_t)v[3]};
             *(bf16x4 *)(smem + row * PITCH + tc * 2) = o;
         }
+        __builtin_amdgcn_sched_barrier(0);
     }
     };
     if (!SWIGLU && (bias || act)) to_lds(std::true_type{});
@@ -291,8 +388,9 @@ __device__ __forceinline__ void mfma_tied(f32x4 &c, const bf16x8 &a, const bf16x
 // ones leave the matrix pipeline.
 __device__ __forceinline__ void mfma_drain() { asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" ::: "memory"); }
 
-template <int BM, int BN, int WM, int WN, int BK, int NST, bool SWIGLU>
+template <int BM, int BN, int WM, int WN, int BK, int NST, bool SWIGLU, bool ROPE = false>
 __global__ __launch_bounds__(WM *WN * 64) void gemm2_kernel(Gemm2Params p) {
+    static_assert(!ROPE || (!SWIGLU && WM * WN == 4), "rotary epilogue: plain GEMM, one wavefront per SIMD");
     constexpr int NW = WM * WN;
     constexpr int WTM = BM / WM, WTN = BN / WN;
     constexpr int TM = WTM / 16, TN = WTN / 16;
@@ -359,7 +457,12 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm2_kernel(Gemm2Params p) {
         const int c = (lane % CPR) ^ swz(row);
         int col;
         if (SWIGLU) col = nloc0 + (row / WTN) * (WTN / 2) + (row % (WTN / 2));
-        else col = nloc0 + row;
+        else if (ROPE) {                                           // tile row -> rotation pair and half of it
+            const int rr = row % WTN, hs = rr / (WTN / 2);
+            const int pp = (nloc0 >> 1) + (row / WTN) * (WTN / 2) + rr % (WTN / 2);
+            const int lh = p.rope_lh;
+            col = pp < (seg_rows >> 1) ? ((pp >> lh) << (lh + 1)) + (pp & ((1 << lh) - 1)) + (hs << lh) : seg_rows;
+        } else col = nloc0 + row;
         b_off[i] = (row < BN && col < seg_rows) ? (uint32_t)((int64_t)col * K * 2) + c * 16 : OOB_OFF;
     }
 
@@ -527,7 +630,12 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm2_kernel(Gemm2Params p) {
 
     if constexpr (SOLO) {
         __syncthreads();                                   // everyone is done with the tile buffers
-        gemm_epilogue_tile<BM, NW * 64, TM, TN, WTN, SWIGLU, BN_OUT>(p, acc, smem, tid, m0, wm0, wn0, nloc0, seg, seg_rows);
+        if constexpr (ROPE)
+            gemm_epilogue_tile_rope<BM, NW * 64, TM, TN, WTN, BN>(p, acc, smem, tid, m0, wm0, wn0, nloc0 >> 1, seg, seg_rows);
+        else
+            // only the 192-column tile takes GELU launches: with more accumulator blocks the compiler no longer
+            // unrolls the (long) activation code and would index the accumulators through memory
+            gemm_epilogue_tile<BM, NW * 64, TM, TN, WTN, SWIGLU, BN_OUT, TM * TN <= 48>(p, acc, smem, tid, m0, wm0, wn0, nloc0, seg, seg_rows);
     } else {
         __syncthreads();                                   // everyone is done with the tile buffers
         gemm_epilogue<TM, TN, WTN, SWIGLU>(p, acc, smem, wave, lane, m0, wm0, wn0, nloc0, seg, seg_rows);
@@ -705,9 +813,14 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm3_kernel(Gemm2Params p) {
     gemm_epilogue<TM, TN, WTN, SWIGLU>(p, acc, smem, wave, lane, m0, wm0, wn0, nloc0, seg, seg_rows);
 }
 
-template <int BM, int BN, int WM, int WN, int BK, int NST, bool SWIGLU, bool PINGPONG = false>
+template <int BM, int BN, int WM, int WN, int BK, int NST, bool SWIGLU, bool PINGPONG = false, bool ROPE = false>
 static int32_t launch_cfg2(const GemmArgs &a, hipStream_t s) {
     Gemm2Params p;
+    p.rope_table = a.rope_table; p.rope_cols = a.rope_cols; p.rope_lh = 0;
+    if (ROPE) {
+        while ((2 << p.rope_lh) < a.rope_head_dim) ++p.rope_lh;
+        if ((uintptr_t)a.rope_table % 16) return CASCADE_EINVAL;
+    }
     constexpr int BN_OUT = SWIGLU ? BN / 2 : BN;
     int col0 = 0, tile0 = 0;
     for (int i = 0; i < 3; ++i) {
@@ -742,7 +855,7 @@ static int32_t launch_cfg2(const GemmArgs &a, hipStream_t s) {
     static_assert(lds <= 160 * 1024, "tile buffers exceed the LDS of a CU");
     const void *kern;
     if constexpr (PINGPONG) kern = (const void *)gemm3_kernel<BM, BN, WM, WN, BK, NST, SWIGLU>;
-    else kern = (const void *)gemm2_kernel<BM, BN, WM, WN, BK, NST, SWIGLU>;
+    else kern = (const void *)gemm2_kernel<BM, BN, WM, WN, BK, NST, SWIGLU, ROPE>;
     static std::atomic<uint64_t> lds_ready{0};                 // one per instantiation of this launcher
     CASCADE_HIP_TRY(ensure_dynamic_lds(kern, (int)lds, lds_ready));
     int64_t total = (int64_t)p.tiles_m * p.tiles_n;
@@ -760,13 +873,34 @@ static int cu_count() {                                   // of the current devi
     return n;
 }
 
+static bool v2_eligible(const GemmArgs &a) {
+    if (a.K % 64 != 0 || a.K < 64 || a.ldx % 8 != 0 || a.ldy % 4 != 0 || ((a.epilogue & CASCADE_EPI_RESIDUAL) && a.ldres % 4 != 0))
+        return false;
+    if (((uintptr_t)a.Y | (uintptr_t)a.residual) % 8) return false;
+    for (int i = 0; i < 3; ++i)
+        if (a.seg_end[i] % 4) return false;                         // 4-column store chunks stay inside a segment
+    return true;
+}
+
+// Whether this launch (a.rope_head_dim and a.rope_cols set, a.rope_table not needed yet) can rotate its output
+// in the epilogue: a plain projection (bias at most) whose segments hold whole heads of a power-of-two width.
+bool gemm_bf16_rope_fusable(const GemmArgs &a) {
+    if (a.dtype != CASCADE_BF16 || !v2_eligible(a)) return false;
+    if (a.epilogue & ~CASCADE_EPI_BIAS) return false;
+    const int hd = a.rope_head_dim;
+    if (hd < 16 || hd > 256 || (hd & (hd - 1)) || a.rope_cols % hd) return false;
+    int col0 = 0;
+    for (int i = 0; i < 3; ++i) {
+        const int rows = std::max(0, a.seg_end[i] - col0);
+        if (rows % hd) return false;
+        col0 = std::max(col0, a.seg_end[i]);
+    }
+    return true;
+}
+
 // Returns CASCADE_EUNSUPPORTED when the shape is not eligible (the caller then uses the general kernel).
 int32_t launch_gemm_bf16_v2(const GemmArgs &a, hipStream_t s) {
-    if (a.K % 64 != 0 || a.K < 64 || a.ldx % 8 != 0 || a.ldy % 4 != 0 || ((a.epilogue & CASCADE_EPI_RESIDUAL) && a.ldres % 4 != 0))
-        return CASCADE_EUNSUPPORTED;
-    if (((uintptr_t)a.Y | (uintptr_t)a.residual) % 8) return CASCADE_EUNSUPPORTED;
-    for (int i = 0; i < 3; ++i)
-        if (a.seg_end[i] % 4) return CASCADE_EUNSUPPORTED;          // 4-column store chunks stay inside a segment
+    if (!v2_eligible(a)) return a.rope_table ? CASCADE_EINVAL : CASCADE_EUNSUPPORTED;
     const bool swiglu = a.epilogue & CASCADE_EPI_SWIGLU;
     // Tile choice.  The cost of a launch is rounds of workgroups x columns per tile; candidates are
     // 256 rows x {256, 224, 192} columns (BK 64, two stages; the widths exist to fill whole rounds) and
@@ -784,6 +918,14 @@ int32_t launch_gemm_bf16_v2(const GemmArgs &a, hipStream_t s) {
     const int64_t cus = cu_count();
     auto cost = [&](int bne) { return ((n_tiles(swiglu ? bne / 2 : bne) + cus - 1) / cus) * bne; };
     const int64_t c256 = cost(256), c224 = cost(224), c192 = cost(192), c128 = cost(128);
+    if (a.rope_table) {                  // rotary embedding in the epilogue: the one-wavefront kernels only
+        if (!gemm_bf16_rope_fusable(a)) return CASCADE_EINVAL;
+        const int64_t best = std::min(c192, std::min(c224, c256));
+        if (c256 * 100 <= best * 104 && n_tiles(256) > cus) return launch_cfg2<256, 256, 2, 2, 64, 2, false, false, true>(a, s);
+        if (c192 == best) return launch_cfg2<256, 192, 2, 2, 64, 2, false, false, true>(a, s);
+        if (c224 == best) return launch_cfg2<256, 224, 4, 1, 64, 2, false, false, true>(a, s);
+        return launch_cfg2<256, 256, 2, 2, 64, 2, false, false, true>(a, s);
+    }
     if (swiglu) {
         if (c224 < c256) return launch_cfg2<256, 224, 4, 1, 64, 2, true, false>(a, s);
         return launch_cfg2<256, 256, 2, 2, 64, 2, true, false>(a, s);
@@ -796,13 +938,15 @@ int32_t launch_gemm_bf16_v2(const GemmArgs &a, hipStream_t s) {
         // 8192 x 4096 x 4096 with residual 1.10 against 0.98 PFLOP/s, x 14336 1.27 against 1.14.  It goes before
         // the narrower tiles up to a 4 % higher cost: fewer tile-load instructions and operand reads per MFMA
         // (8192 x 32000 x 4096: 1.24 against 1.11 PFLOP/s for 192 columns at 1.6 % more rounds x width).
-        const bool solo256 = n_tiles(256) > cus && a.K >= 2048 &&
-                             !(a.epilogue & (CASCADE_EPI_GELU_ERF | CASCADE_EPI_GELU_TANH));
+        const bool gelu = a.epilogue & (CASCADE_EPI_GELU_ERF | CASCADE_EPI_GELU_TANH);
+        const bool solo256 = n_tiles(256) > cus && a.K >= 2048 && !gelu;
         if (c256 * 100 <= best * 104 && solo256) return launch_cfg2<256, 256, 2, 2, 64, 2, false, false>(a, s);
         // 192 and 224 columns: always the one-wavefront schedule, the narrowest cost first (2048 x 6144 x 4096 in
         // one round of 256 tiles: 86 us inside the layer against 100 us with 8 wavefronts)
         if (c192 == best) return launch_cfg2<256, 192, 2, 2, 64, 2, false, false>(a, s);
-        if (c224 == best) return launch_cfg2<256, 224, 2, 2, 64, 2, false, false>(a, s);
+        if (c224 == best)
+            return gelu ? launch_cfg2<256, 224, 4, 2, 64, 2, false, false>(a, s)     // 8 wavefronts
+                        : launch_cfg2<256, 224, 2, 2, 64, 2, false, false>(a, s);
         return launch_cfg2<256, 256, 4, 2, 64, 2, false, false>(a, s);   // 8 wavefronts
     }
     // narrow GEMMs (N of a few hundred to a few thousand columns): 256x128 tiles, or 128x128 when even those

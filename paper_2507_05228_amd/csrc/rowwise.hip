@@ -7,15 +7,57 @@
 #include "common.h"
 #include "device_utils.h"
 
+// ---------------------------------------------------------------------------- rotary angles
+// cos and sin of position * theta^(-2i/d), i < d/2.  The angle is carried in revolutions: rev = theta^(-2i/d) /
+// (2 pi) in double precision, split into two floats, and position * rev is formed with a compensated product, so
+// the fractional part (all that sine and cosine need) stays accurate to ~1e-7 revolutions however large the
+// position (below 2^24); sine and cosine are then single hardware instructions.
+struct RopeRev { float hi, lo; };
+__device__ __forceinline__ RopeRev rope_rev(float theta, int i, int head_dim) {
+    const double rev = exp2(-2.0 * i / head_dim * log2((double)theta)) / 6.283185307179586476925;
+    RopeRev r;
+    r.hi = (float)rev;
+    r.lo = (float)(rev - (double)r.hi);
+    return r;
+}
+__device__ __forceinline__ void rope_cos_sin(float pos, float c_hi, float c_lo, float &cs, float &sn) {
+    const float r_hi = pos * c_hi;
+    const float r_err = fmaf(pos, c_hi, -r_hi) + pos * c_lo;      // pos * (hi + lo) = r_hi + r_err
+    const float rev = (r_hi - floorf(r_hi)) + r_err;
+    sn = __builtin_amdgcn_sinf(rev);
+    cs = __builtin_amdgcn_cosf(rev);
+}
+// By-product of the pre-pass norm: the workgroup of row r writes that row's cos | sin table (the shard GEMM
+// that follows rotates q and k with it in its epilogue).
+struct RopeTableOut {
+    float *table;
+    const int32_t *pos;
+    int32_t seq_len, head_dim;
+    float theta;
+};
+__device__ __forceinline__ void write_rope_row(const RopeTableOut &t, int r) {
+    const int half = t.head_dim >> 1;
+    const float pos = (float)t.pos[r % t.seq_len];
+    for (int i = threadIdx.x; i < half; i += blockDim.x) {
+        const RopeRev c = rope_rev(t.theta, i, t.head_dim);
+        float cs, sn;
+        rope_cos_sin(pos, c.hi, c.lo, cs, sn);
+        t.table[(int64_t)r * t.head_dim + i] = cs;
+        t.table[(int64_t)r * t.head_dim + half + i] = sn;
+    }
+}
+
 // ---------------------------------------------------------------------------- norm
 // One 256-thread block per row; the row is staged in LDS as fp32 (D * 4 bytes).
 template <typename T>
 __global__ __launch_bounds__(256) void norm_kernel(const T *__restrict__ x, const T *__restrict__ gain,
                                                    const T *__restrict__ bias, T *__restrict__ y, int D, int kind,
-                                                   float eps, const int32_t *xmap, const int32_t *ymap, int seq_len) {
+                                                   float eps, const int32_t *xmap, const int32_t *ymap, int seq_len,
+                                                   RopeTableOut rope) {
     extern __shared__ float row[];
     __shared__ float red[4];
     const int r = blockIdx.x;
+    if (rope.table) write_rope_row(rope, r);
     const T *xr = x + map_row(xmap, seq_len, r) * (int64_t)D;
     float s = 0.f;
     for (int i = threadIdx.x; i < D; i += 256) {
@@ -45,11 +87,13 @@ __global__ __launch_bounds__(256) void norm_kernel(const T *__restrict__ x, cons
 template <typename T, int CH>
 __global__ __launch_bounds__(256) void norm_vec_kernel(const T *__restrict__ x, const T *__restrict__ gain,
                                                        const T *__restrict__ bias, T *__restrict__ y, int D, int kind,
-                                                       float eps, const int32_t *xmap, const int32_t *ymap, int seq_len) {
+                                                       float eps, const int32_t *xmap, const int32_t *ymap, int seq_len,
+                                                       RopeTableOut rope) {
     constexpr int VEC = 16 / sizeof(T);
     typedef T vecT __attribute__((ext_vector_type(VEC)));
     __shared__ float red[4];
     const int r = blockIdx.x;
+    if (rope.table) write_rope_row(rope, r);
     const T *xr = x + map_row(xmap, seq_len, r) * (int64_t)D;
     const int nvec = D / VEC;
     float v[CH][VEC];
@@ -100,10 +144,11 @@ static int32_t launch_norm_t(const NormArgs &a, hipStream_t s) {
     constexpr int VEC = 16 / sizeof(T);
     const bool aligned = a.D % VEC == 0 && ((uintptr_t)a.x | (uintptr_t)a.y | (uintptr_t)a.gain | (uintptr_t)a.bias) % 16 == 0;
     const int nvec = a.D / VEC;
+    const RopeTableOut rope = {a.rope_table, a.rope_pos, a.rope_seq_len, a.rope_head_dim, a.rope_theta};
 #define NORM_VEC(CH)                                                                                             \
     hipLaunchKernelGGL((norm_vec_kernel<T, CH>), dim3(a.rows), dim3(256), 0, s, (const T *)a.x, (const T *)a.gain, \
                        (const T *)a.bias, (T *)a.y, a.D, a.kind, a.eps, a.xmap.map, a.ymap.map,                 \
-                       a.xmap.map ? a.xmap.seq_len : a.ymap.seq_len)
+                       a.xmap.map ? a.xmap.seq_len : a.ymap.seq_len, rope)
     if (aligned && nvec <= 256) NORM_VEC(1);
     else if (aligned && nvec <= 512) NORM_VEC(2);
     else if (aligned && nvec <= 1024) NORM_VEC(4);
@@ -111,8 +156,8 @@ static int32_t launch_norm_t(const NormArgs &a, hipStream_t s) {
         size_t lds = (size_t)a.D * sizeof(float);
         if (lds > 64 * 1024) return CASCADE_EUNSUPPORTED;
         hipLaunchKernelGGL(norm_kernel<T>, dim3(a.rows), dim3(256), lds, s, (const T *)a.x, (const T *)a.gain,
-                           (const T *)a.bias, (T *)a.y, a.D, a.kind, a.eps, a.xmap.map, a.ymap.map,                 \
-                       a.xmap.map ? a.xmap.seq_len : a.ymap.seq_len);
+                           (const T *)a.bias, (T *)a.y, a.D, a.kind, a.eps, a.xmap.map, a.ymap.map,
+                           a.xmap.map ? a.xmap.seq_len : a.ymap.seq_len, rope);
     }
 #undef NORM_VEC
     CASCADE_HIP_TRY(hipGetLastError());
@@ -240,10 +285,7 @@ __global__ __launch_bounds__(256) void rope_kernel(T *__restrict__ x, int64_t to
 }
 
 // Vector variant for bf16: one thread rotates 8 consecutive pairs (two 16-byte pieces half a head apart).
-// The angle is carried in revolutions: rev[i] = theta^(-2i/d) / (2 pi) comes from the host in double
-// precision, split into two floats, and position * rev is formed with a compensated product, so the
-// fractional part (all that sine and cosine need) stays accurate to ~1e-7 revolutions however large the
-// position; sine and cosine are then single hardware instructions.
+// rev[i] = theta^(-2i/d) / (2 pi) comes from the host in double precision, split into two floats.
 #define ROPE_MAX_HALF 128
 struct RopeFreq {
     float hi[ROPE_MAX_HALF], lo[ROPE_MAX_HALF];
@@ -264,11 +306,8 @@ __global__ __launch_bounds__(256) void rope_vec_kernel(bf16_t *__restrict__ x, i
         bf16x8 oa, ob;
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            const float c_hi = freq.hi[i0 + j], c_lo = freq.lo[i0 + j];
-            const float r_hi = pos * c_hi;
-            const float r_err = fmaf(pos, c_hi, -r_hi) + pos * c_lo;          // pos * (hi + lo) = r_hi + r_err
-            const float rev = (r_hi - floorf(r_hi)) + r_err;
-            const float sn = __builtin_amdgcn_sinf(rev), cs = __builtin_amdgcn_cosf(rev);
+            float cs, sn;
+            rope_cos_sin(pos, freq.hi[i0 + j], freq.lo[i0 + j], cs, sn);
             const float fa = (float)a[j], fb = (float)b[j];
             oa[j] = (bf16_t)(fa * cs - fb * sn);
             ob[j] = (bf16_t)(fb * cs + fa * sn);

@@ -524,6 +524,26 @@ def test_layer_forward_matches_oracle(cas, cfg, mode):
     assert rel_err(out, direct) < TOL[cfg.dtype]
 
 
+ROPE_BIAS = SMALL_LLAMA.with_(name="small-llama-bias", bias=True, norm="layernorm", act="gelu", index=35)
+ROPE_POST = SMALL_LLAMA64.with_(name="small-llama64-post", norm_placement="post", index=36)
+ROPE_WIDE = SMALL_LLAMA.with_(name="llama-2-tiles", d_model=1024, n_heads=16, n_kv_heads=4, seq_len=520, n_shards=3,
+                              index=37)
+
+
+@pytest.mark.parametrize("cfg", [SMALL_LLAMA, SMALL_LLAMA64, ROPE_BIAS, ROPE_POST, ROPE_WIDE], ids=lambda c: c.name)
+@pytest.mark.parametrize("fused_qkv", [False, True], ids=["three-weights", "one-qkv-weight"])
+def test_layer_rotary_embedding_paths(cas, cfg, fused_qkv):
+    """The rotary embedding runs in the q/k/v projection's epilogue (bf16, pre-norm: one segment when the three
+    weights are one matrix, three segments otherwise; with and without a bias) or as a pass of its own
+    (post-norm); positions do not ascend with the token index, so a rotation by the row number would show."""
+    a = make_assignment(cfg.assignment, cfg.seq_len, cfg.n_shards, 79)
+    pos = np.random.default_rng(13).permutation(3 * cfg.seq_len)[:cfg.seq_len].astype(np.int32)
+    w, h = make_layer_weights(cfg), make_hidden(cfg)
+    out = cas.layer_forward_numpy(cfg, w, h, a, positions=pos, fused_qkv=fused_qkv)
+    ref = orc.layer_direct_batch(h, w, cfg, positions=pos)
+    assert rel_err(out, ref) < TOL[cfg.dtype]
+
+
 @pytest.mark.parametrize("mode", ["fused", "materialised"])
 def test_layer_forward_with_unordered_positions(cas, mode):
     """Token positions that do not ascend with the token index (rotary angles and the causal mask
