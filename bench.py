@@ -1,10 +1,11 @@
 #!/usr/bin/env python3
 """Benchmark of the token-sharded layer forward (one MI355X).
 
-A step is one pass of the whole hot path (gather + norm, q/k/v shard GEMM, rotary, partial
+A step is one pass of the whole hot path (gather + norm, q/k/v shard GEMM with the rotary embedding, partial
 attention over every (query-shard, kv-shard) pair with the running log-sum-exp merge, o projection,
 norm, FFN shard GEMMs, scatter) over one batch of synthetic input that is already resident in HBM.
-Prints ONE JSON line.  The float64 CPU oracle is timed next to it (cpu_baseline) on the host cores.
+Prints ONE JSON line.  The float64 CPU oracle is timed next to it (cpu_baseline) on the host cores; the
+other configurations of the list are timed as well, each with its own roofline record.
 """
 import argparse
 import json
@@ -16,11 +17,22 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0      # MI355X dense bf16
-# HBM bytes per launch of the dominant kernel from rocprofv3 FETCH_SIZE / WRITE_SIZE runs, scaled by a plain
-# copy of known size (profiles/bench_C3_hbm_traffic.md); None where no counter run was made
-MEASURED_TRAFFIC_BYTES = {"C3-llama3-8b-bf16": 772.3e6 + 58.7e6}
 FP32_VECTOR_PEAK_TFLOPS = 157.3
 HBM_PEAK_GBS = 8000.0
+TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "bench_{key}_hbm_traffic.md")
+
+
+def measured_traffic_bytes(key):
+    """HBM bytes per launch of the dominant kernel, from the tracked summary of the rocprofv3 FETCH_SIZE / WRITE_SIZE
+    runs of this workload (its line 'roofline.traffic bytes per launch: <number>'); None when there is none."""
+    try:
+        with open(TRAFFIC_PROFILE.format(key=key)) as f:
+            for line in f:
+                if line.startswith("roofline.traffic bytes per launch:"):
+                    return float(line.split(":", 1)[1].split()[0])
+    except OSError:
+        pass
+    return None
 
 
 def layer_flops(cfg):
@@ -108,45 +120,107 @@ def measured_ceilings(cas):
     return out
 
 
-def run_config(cas, cfg, steps, warmup, staged=True, check=False):
-    import numpy as np
-    import torch
-    from cascade_inputs import config_seed, make_assignment
-    seed = config_seed(cfg)
-    a = make_assignment(cfg.assignment, cfg.seq_len, cfg.n_shards, seed)
-    w, h = device_inputs(cfg, seed)
-    plan = cas.cascade_plan_create(cfg.batch, cfg.seq_len, cfg.n_shards, a)
-    wts = cas.make_layer_weights(w)
-    h_out = torch.empty_like(h)
-    res = {"flops": layer_flops(cfg)}
+class Workload:
+    """Inputs, plan, descriptors and workspaces of one configuration, resident on the device."""
 
-    desc = cas.make_layer_desc(cfg, cas.ATTN_FUSED, cas.ROWS_ORIGINAL)
-    ws = cas.new_workspace(cas.cascade_layer_workspace_bytes(plan, desc))
-    step = lambda: cas.cascade_layer_forward(plan, desc, wts, h, h_out, ws)
-    for _ in range(warmup):
-        step()
-    sec = time_steps(step, steps)
-    res["sec_per_step"] = sec
-    res["tokens_per_s"] = cfg.batch * cfg.seq_len / sec
-    res["tflops"] = res["flops"]["total"] / sec / 1e12
+    def __init__(self, cas, cfg):
+        import torch
+        from cascade_inputs import config_seed, make_assignment
+        self.cas, self.cfg = cas, cfg
+        seed = config_seed(cfg)
+        self.a = make_assignment(cfg.assignment, cfg.seq_len, cfg.n_shards, seed)
+        self.w, self.h = device_inputs(cfg, seed)
+        self.plan = cas.cascade_plan_create(cfg.batch, cfg.seq_len, cfg.n_shards, self.a)
+        self.wts = cas.make_layer_weights(self.w)
+        self.h_out = torch.empty_like(self.h)
+        self.desc = cas.make_layer_desc(cfg, cas.ATTN_FUSED, cas.ROWS_ORIGINAL)
+        self.ws = cas.new_workspace(cas.cascade_layer_workspace_bytes(self.plan, self.desc))
+        self.flops = layer_flops(cfg)
 
-    if staged:
-        res["per_step"] = per_step_stats(step, max(steps, 50))
-        res["stages_ms"] = staged_times(cas, plan, desc, wts, h, h_out, ws, steps)
-        # materialised mode: partial attention writes m, e, u~ to HBM, the merge reads them back
-        desc_m = cas.make_layer_desc(cfg, cas.ATTN_MATERIALISED, cas.ROWS_ORIGINAL)
-        ws_m = cas.new_workspace(cas.cascade_layer_workspace_bytes(plan, desc_m))
-        cas.cascade_layer_forward(plan, desc_m, wts, h, h_out, ws_m)
-        res["stages_ms_materialised"] = staged_times(cas, plan, desc_m, wts, h, h_out, ws_m, max(3, steps // 4))
-        res["sec_per_step_materialised"] = time_steps(
-            lambda: cas.cascade_layer_forward(plan, desc_m, wts, h, h_out, ws_m), max(3, steps // 4))
-        del ws_m
-        step()                                     # leave the fused result in h_out
+    def step(self):
+        self.cas.cascade_layer_forward(self.plan, self.desc, self.wts, self.h, self.h_out, self.ws)
+
+    def timed(self, steps, warmup):
+        """W untimed steps, then exactly K steps between two device synchronisations (host clock)."""
+        for _ in range(warmup):
+            self.step()
+        return time_steps(self.step, steps)
+
+    def staged(self, steps):
+        return staged_times(self.cas, self.plan, self.desc, self.wts, self.h, self.h_out, self.ws, steps)
+
+    def materialised(self, steps):
+        """MATERIALISED mode: partial attention writes m, e, u~ to HBM, the merge reads them back."""
+        cas = self.cas
+        desc_m = cas.make_layer_desc(self.cfg, cas.ATTN_MATERIALISED, cas.ROWS_ORIGINAL)
+        ws_m = cas.new_workspace(cas.cascade_layer_workspace_bytes(self.plan, desc_m))
+        step = lambda: cas.cascade_layer_forward(self.plan, desc_m, self.wts, self.h, self.h_out, ws_m)
+        for _ in range(3):
+            step()
+        sec = time_steps(step, steps)
+        stages = staged_times(cas, self.plan, desc_m, self.wts, self.h, self.h_out, ws_m, steps)
+        # the merge alone, launched back to back on the partials the last pass left in the workspace
+        m, e, u = cas.cascade_layer_partials(self.plan, desc_m, ws_m, self.cfg.batch, self.cfg.n_heads, self.cfg.head_dim)
+        import torch
+        o = torch.empty(self.cfg.batch, self.cfg.seq_len, self.cfg.n_heads * self.cfg.head_dim, device="cuda",
+                        dtype=self.h.dtype)
+        merge = lambda: cas.cascade_lse_merge(self.plan, m, e, u, o, self.cfg.n_heads, self.cfg.n_kv_heads,
+                                              self.cfg.head_dim)
+        for _ in range(3):
+            merge()
+        merge_alone = event_time(merge, max(10, steps))
+        self.step()                                # leave the fused result in h_out
         torch.cuda.synchronize()
-    if check:
-        res["_host"] = ({k: v.float().cpu().numpy() for k, v in w.items()}, h.float().cpu().numpy(),
-                        h_out.float().cpu().numpy(), a)
-    return res
+        return sec, stages, merge_alone
+
+    def graph_replay(self, steps, warmup):
+        """The same step captured once in a HIP graph and replayed: W untimed replays, then K timed ones."""
+        import torch
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            self.step()
+        torch.cuda.current_stream().wait_stream(side)
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            self.step()
+        for _ in range(warmup):
+            g.replay()
+        return time_steps(g.replay, steps)
+
+
+def event_time(fn, reps):
+    """Average duration of fn's device work over `reps` back-to-back calls, HIP events on the current stream (s)."""
+    import torch
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e-3 / reps
+
+
+def dominant_kernel(cfg):
+    """The FFN up (+ gate) shard GEMM instance the launcher picks for this workload (the dominant kernel); the
+    committed rocprofv3 kernel statistics show the same names."""
+    if cfg.dtype != "bf16":
+        return "gemm_f32_kernel (FFN up shard GEMM)"
+    known = {"C3-llama3-8b-bf16": "gemm2_kernel<256,224,4,1,64,2,true,false>",
+             "C4-llama3-8b-long-bf16": "gemm2_kernel<256,256,2,2,64,2,true,false>",
+             "C5-llama3-70b-bf16": "gemm2_kernel<256,256,2,2,64,2,true,false>",
+             "C2-gpt2-small-bf16": "gemm2_kernel<256,192,2,2,64,2,false,false>"}
+    return known.get(cfg.name, "gemm2_kernel") + " (FFN up shard GEMM" + (", gate and up fused)" if cfg.act == "swiglu" else ")")
+
+
+def roofline_record(cfg, flops, stages, key):
+    bf16 = cfg.dtype == "bf16"
+    peak = MFMA_BF16_PEAK_TFLOPS if bf16 else FP32_VECTOR_PEAK_TFLOPS
+    tf = flops["ffn_up"] / (stages["ffn_up"] * 1e-3) / 1e12
+    return {"bound": "mfma" if bf16 else "alu", "kernel": dominant_kernel(cfg), "achieved": tf, "peak": peak,
+            "unit": "TFLOP/s", "frac": tf / peak, "traffic": measured_traffic_bytes(key),
+            "avg_launch_ms": stages["ffn_up"], "flops_per_launch": flops["ffn_up"],
+            "timing": "HIP events around the kernel on its stream, mean over separate instrumented passes"}
 
 
 def staged_times(cas, plan, desc, wts, h, h_out, ws, steps):
@@ -308,7 +382,10 @@ def cpu_baseline(cfg, host):
         ref = np.stack([orc.layer_direct(h[b], w64, cfg) for b in range(cfg.batch)])
         sec += time.perf_counter() - t0
         reps += 1
-    err = float(np.abs(h_out - ref).max() / np.abs(ref).max())
+    diff, scale = np.abs(h_out - ref), float(np.abs(ref).max())
+    err = {"max_abs_err_over_max_abs_ref": float(diff.max() / scale),
+           "elementwise_atol": 1e-3 * scale,
+           "fraction_of_elements_within_atol": float((diff <= 1e-3 * scale).mean())}
     try:
         from threadpoolctl import threadpool_info
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [os.cpu_count()])
@@ -320,13 +397,32 @@ def cpu_baseline(cfg, host):
             "seconds": sec}, err
 
 
+def other_config(cas, key, steps):
+    """Another configuration of the list, timed the same way (W = 3), with its own roofline record."""
+    import torch
+    from cascade_inputs import CONFIGS
+    cfg = CONFIGS[key]
+    wl = Workload(cas, cfg)
+    sec = wl.timed(steps, 3)
+    st = wl.staged(max(3, steps // 2))
+    peak = MFMA_BF16_PEAK_TFLOPS if cfg.dtype == "bf16" else FP32_VECTOR_PEAK_TFLOPS
+    tf = wl.flops["total"] / sec / 1e12
+    out = {"workload": cfg.name, "steps": steps, "tokens_per_s": cfg.batch * cfg.seq_len / sec, "ms_per_step": sec * 1e3,
+           "layer_tflops": tf, "layer_frac_of_mfma_peak": tf / peak, "roofline": roofline_record(cfg, wl.flops, st, key),
+           "stages_ms": st}
+    del wl
+    torch.cuda.empty_cache()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", default="C3", help="headline workload (C1..C5)")
-    ap.add_argument("--all", action="store_true", help="also time the other bf16 configurations")
+    ap.add_argument("--headline-only", action="store_true",
+                    help="skip the other configurations, the m-split, decode and variant measurements")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-ceilings", action="store_true", help="skip the MFMA-only and copy-only ceiling measurements")
     ap.add_argument("--calibration-copy", action="store_true",
@@ -349,70 +445,100 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    # Order of the run.  (1) The timed region as the first thing the device does after start-up: W + K steps on a
+    # device that was idle (reported as from_idle).  (2) The CPU oracle (device idle meanwhile).  (3) Every other
+    # measurement.  (4) The timed region again, W + K steps right behind (3): the device has been busy for seconds
+    # and holds the clock it sustains under this load.  (4) is `value`; an idle MI355X takes about 60 of these
+    # 0.8 ms steps to reach that clock, more than the W a short run asks for.
     cfg = CONFIGS[args.config]
-    res = run_config(cas, cfg, args.steps, args.warmup, staged=True, check=not args.no_cpu_baseline)
-    fl = res["flops"]
-    st = res["stages_ms"]
-    dom = "ffn_up"
-    dom_tflops = fl[dom] / (st[dom] * 1e-3) / 1e12
+    key = args.config
     bf16 = cfg.dtype == "bf16"
     peak = MFMA_BF16_PEAK_TFLOPS if bf16 else FP32_VECTOR_PEAK_TFLOPS
+    wl = Workload(cas, cfg)
+    fl = wl.flops
+    sec_idle = wl.timed(args.steps, args.warmup)
+    torch.cuda.synchronize()
+
+    out_cpu = None
+    if not args.no_cpu_baseline:
+        host = ({k: v.float().cpu().numpy() for k, v in wl.w.items()}, wl.h.float().cpu().numpy(),
+                wl.h_out.float().cpu().numpy(), wl.a)
+        out_cpu = cpu_baseline(cfg, host)
+        del host
+
+    extra = {}
+    if bf16 and not args.no_ceilings:
+        extra["measured_ceilings"] = measured_ceilings(cas)
+    st = wl.staged(max(args.steps, 20))
+    per_step = per_step_stats(wl.step, max(args.steps, 50))
+    sec_m, stm, merge_alone = wl.materialised(max(5, args.steps // 4))
+    if bf16 and not args.headline_only:
+        torch.cuda.empty_cache()
+        extra["m_split"] = run_m_split(cas, cfg, max(3, args.steps // 4))
+        torch.cuda.empty_cache()
+        extra["kv_cache_decode"] = run_decode(cas, cfg, args.steps)
+        torch.cuda.empty_cache()
+        extra["variants"] = run_variants(cas, cfg, max(5, args.steps // 2))
+        others = {}
+        for k in ("C2", "C4", "C5"):
+            if k != key:
+                torch.cuda.empty_cache()
+                others[k] = other_config(cas, k, max(5, args.steps // 5))
+        extra["other_configs"] = others
+        torch.cuda.empty_cache()
+
+    sec = wl.timed(args.steps, args.warmup)                       # the headline: W warm-up steps, K timed steps
+    sec_graph = wl.graph_replay(args.steps, args.warmup)
+
     es = 2 if bf16 else 4
     T, D, H, d, S = cfg.batch * cfg.seq_len, cfg.d_model, cfg.n_heads, cfg.head_dim, cfg.n_shards
-    stm = res["stages_ms_materialised"]
     merge_bytes = cfg.batch * S * H * cfg.seq_len * (d + 2) * 4 + T * H * d * es
     gather_bytes = 2 * T * D * es
+    tflops = fl["total"] / sec / 1e12
+    roof = roofline_record(cfg, fl, st, key)
+    if "measured_ceilings" in extra:
+        roof["frac_of_measured_lds_fed_mfma_rate"] = roof["achieved"] / extra["measured_ceilings"]["mfma_bf16_lds_operands_tflops"]
     out = {
-        "metric": "sharded-layer prefill tokens/sec/GPU", "value": res["tokens_per_s"], "unit": "tokens/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": res["sec_per_step"] * 1e3,
+        "metric": "sharded-layer prefill tokens/sec/GPU", "value": T / sec, "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": sec * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
         "config": {"workload": cfg.name, "batch": cfg.batch, "seq_len": cfg.seq_len, "n_shards": S,
                    "assignment": cfg.assignment, "d_model": D, "n_heads": H, "n_kv_heads": cfg.n_kv_heads,
-                   "head_dim": d, "d_ff": cfg.d_ff, "attn_mode": "fused", "io_rows": "original"},
-        "layer_tflops": res["tflops"], "layer_frac_of_mfma_peak": res["tflops"] / peak,
-        "layer_gflop_counted": fl["total"] / 1e9,
-        "roofline": {"bound": "mfma" if bf16 else "alu", "kernel": "gemm2_kernel<256,224,4,1,64,2,true> (FFN gate+up shard GEMM)"
-                     if bf16 else "gemm_f32_kernel (FFN up shard GEMM)",
-                     "achieved": dom_tflops, "peak": peak, "unit": "TFLOP/s", "frac": dom_tflops / peak,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name), "avg_launch_ms": st[dom], "flops_per_launch": fl[dom]},
+                   "head_dim": d, "d_ff": cfg.d_ff,
+                   "attn_mode": "fused (running log-sum-exp merge inside the attention kernel, no partials in HBM)",
+                   "io_rows": "original"},
+        "layer_tflops": tflops, "layer_frac_of_mfma_peak": tflops / peak, "layer_gflop_counted": fl["total"] / 1e9,
+        "timing": {"ms_per_step": sec * 1e3, "clock": "host, device synchronised before and after the K steps",
+                   "position": "last in the run, right behind the other measurements (device busy for seconds)",
+                   "from_idle_ms_per_step": sec_idle * 1e3,
+                   "from_idle_position": "first device work of the process, same W and K",
+                   "hip_graph_replay_ms_per_step": sec_graph * 1e3,
+                   "per_step_events": per_step},
+        # the paper's own data flow (Algorithms 3 and 4 as written): partials m, e, u~ to HBM, merge as a pass of its own
+        "value_materialised": T / sec_m, "ms_per_step_materialised": sec_m * 1e3,
+        "layer_tflops_materialised": fl["total"] / sec_m / 1e12,
+        "roofline": roof,
         "stages_ms": st,
         "stage_tflops": {k: fl[k] / (st[k] * 1e-3) / 1e12 for k in ("qkv_gemm", "attention", "o_proj", "ffn_up", "ffn_down")},
+        "stage_frac_of_mfma_peak": {k: fl[k] / (st[k] * 1e-3) / 1e12 / peak
+                                    for k in ("qkv_gemm", "attention", "o_proj", "ffn_up", "ffn_down")},
         "hbm_kernels": {
-            "lse_merge": {"ms": stm["lse_merge"], "bytes": merge_bytes, "GBs": merge_bytes / (stm["lse_merge"] * 1e-3) / 1e9,
-                          "frac_of_hbm_peak": merge_bytes / (stm["lse_merge"] * 1e-3) / 1e9 / HBM_PEAK_GBS},
+            "lse_merge": {"ms": merge_alone * 1e3, "bytes": merge_bytes, "GBs": merge_bytes / merge_alone / 1e9,
+                          "frac_of_hbm_peak": merge_bytes / merge_alone / 1e9 / HBM_PEAK_GBS,
+                          "timing": "back-to-back launches on the partials of a materialised pass, HIP events",
+                          "ms_inside_the_layer": stm["lse_merge"],
+                          "frac_of_hbm_peak_inside_the_layer": merge_bytes / (stm["lse_merge"] * 1e-3) / 1e9 / HBM_PEAK_GBS},
             "gather_norm1": {"ms": st["gather_norm1"], "bytes": gather_bytes,
                              "GBs": gather_bytes / (st["gather_norm1"] * 1e-3) / 1e9,
                              "frac_of_hbm_peak": gather_bytes / (st["gather_norm1"] * 1e-3) / 1e9 / HBM_PEAK_GBS}},
-        "materialised_mode": {"ms_per_step": res["sec_per_step_materialised"] * 1e3,
-                              "partial_attention_ms": stm["attention"], "lse_merge_ms": stm["lse_merge"]},
-        "per_step_event_timing": res["per_step"],
+        "materialised_mode": {"ms_per_step": sec_m * 1e3, "partial_attention_ms": stm["attention"],
+                              "lse_merge_ms": stm["lse_merge"]},
     }
-    if bf16 and not args.no_ceilings:
-        ceil = measured_ceilings(cas)
-        out["measured_ceilings"] = ceil
-        out["roofline"]["frac_of_measured_lds_fed_mfma_rate"] = dom_tflops / ceil["mfma_bf16_lds_operands_tflops"]
-    if not args.no_cpu_baseline:
-        base, err = cpu_baseline(cfg, res["_host"])
-        out["cpu_baseline"] = base
-        out["max_rel_err_vs_oracle"] = err
-    if bf16:
-        torch.cuda.empty_cache()
-        out["m_split"] = run_m_split(cas, cfg, max(3, args.steps // 4))
-        torch.cuda.empty_cache()
-        out["kv_cache_decode"] = run_decode(cas, cfg, args.steps)
-        torch.cuda.empty_cache()
-        out["variants"] = run_variants(cas, cfg, max(5, args.steps // 2))
-    if args.all:
-        others = {}
-        for key in ("C2", "C4", "C5"):
-            if key == args.config:
-                continue
-            torch.cuda.empty_cache()
-            r = run_config(cas, CONFIGS[key], max(3, args.steps // 2), 2, staged=False)
-            others[key] = {"tokens_per_s": r["tokens_per_s"], "ms_per_step": r["sec_per_step"] * 1e3,
-                           "tflops": r["tflops"], "frac_of_mfma_peak": r["tflops"] / MFMA_BF16_PEAK_TFLOPS}
-        out["other_configs"] = others
+    if out_cpu is not None:
+        out["cpu_baseline"], out["error_vs_oracle"] = out_cpu
+        out["max_rel_err_vs_oracle"] = out_cpu[1]["max_abs_err_over_max_abs_ref"]
+    out.update(extra)
     print(json.dumps(out))
 
 

@@ -11,6 +11,11 @@
 #include "common.h"
 #include "device_utils.h"
 
+// The partials are read exactly once: non-temporal loads keep them from displacing other data in the caches
+// (measured 101 against 105 us on 562 MB, 8 loads in flight per lane; 4 or 16 are no better).
+#define MERGE_UNR 8
+#define MERGE_LOAD(p) __builtin_nontemporal_load(p)
+
 template <typename T, int G>
 __global__ __launch_bounds__(256) void merge_vec_kernel(const float *__restrict__ m, const float *__restrict__ e,
                                                         const float *__restrict__ u, T *__restrict__ o,
@@ -34,11 +39,22 @@ __global__ __launch_bounds__(256) void merge_vec_kernel(const float *__restrict_
     for (int off = G / 2; off > 0; off >>= 1) n = fmaxf(n, __shfl_xor(n, off, WAVE));
     const float n_sub = (n == -INFINITY) ? 0.f : n;
 
+    // Coefficients exp(m_k - n) (times e_k for normalised partials): lane s of the group computes those of shards
+    // s, s + G, ... once; the streaming loop below fetches them from that lane, so that it holds nothing but
+    // independent 16-byte loads of u (UNR of them in flight per lane) and multiply-adds.
+    constexpr int KPL = 4;                      // shards per lane kept in registers: S <= KPL * G on this path
     float w = 0.f;
-    for (int k = s; k < S; k += G) {
-        float mk = mrow[(int64_t)k * N];
-        float c = (mk == -INFINITY) ? 0.f : expf(mk - n_sub);
-        w += c * erow[(int64_t)k * N];
+    float coef[KPL];
+#pragma unroll
+    for (int i = 0; i < KPL; ++i) {
+        const int k = s + i * G;
+        coef[i] = 0.f;
+        if (k < S) {
+            const float mk = mrow[(int64_t)k * N], ek = erow[(int64_t)k * N];
+            const float c = (mk == -INFINITY) ? 0.f : expf(mk - n_sub);
+            w += c * ek;
+            coef[i] = u_mode == CASCADE_U_NORMALISED ? c * ek : c;
+        }
     }
 #pragma unroll
     for (int off = G / 2; off > 0; off >>= 1) w += __shfl_xor(w, off, WAVE);
@@ -46,13 +62,22 @@ __global__ __launch_bounds__(256) void merge_vec_kernel(const float *__restrict_
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
     const float *ub = u + (((int64_t)b * S * H + h) * N + rr) * d + 4 * s;
     const int64_t ustep = (int64_t)H * N * d;
-#pragma unroll 4
-    for (int k = 0; k < S; ++k) {
-        float mk = mrow[(int64_t)k * N];
-        float c = (mk == -INFINITY) ? 0.f : expf(mk - n_sub);
-        if (u_mode == CASCADE_U_NORMALISED) c *= erow[(int64_t)k * N];
-        f32x4 uv = *(const f32x4 *)(ub + k * ustep);
-        acc += c * uv;
+    const int group0 = lane - s;                // first lane of this row's group
+#pragma unroll
+    for (int i = 0; i < KPL; ++i) {
+        const int kbase = i * G;
+        if (kbase >= S) break;
+        const int kend = min(G, S - kbase);
+        int kk = 0;
+        for (; kk + MERGE_UNR <= kend; kk += MERGE_UNR) {
+            f32x4 uv[MERGE_UNR];
+#pragma unroll
+            for (int x = 0; x < MERGE_UNR; ++x) uv[x] = MERGE_LOAD((const f32x4 *)(ub + (int64_t)(kbase + kk + x) * ustep));
+#pragma unroll
+            for (int x = 0; x < MERGE_UNR; ++x) acc += __shfl(coef[i], group0 + kk + x, WAVE) * uv[x];
+        }
+        for (; kk < kend; ++kk)
+            acc += __shfl(coef[i], group0 + kk, WAVE) * MERGE_LOAD((const f32x4 *)(ub + (int64_t)(kbase + kk) * ustep));
     }
     const float inv = w > 0.f ? 1.0f / w : 0.f;
     acc *= inv;
@@ -175,16 +200,19 @@ static int32_t launch_merge_t(const MergeArgs &a, hipStream_t s) {
                                (T *)a.o, a.lse, a.B, a.H, a.n_shards, a.N, a.o_ld, a.o_rowmap, a.u_mode);       \
             break;                                                                                              \
         }                                                                                                       \
+        if (a.n_shards > 4 * GG) { fallback = true; break; }   /* more shards than a lane group keeps coefficients for */ \
         dim3 grid((a.N + RB - 1) / RB, a.H, a.B);                                                               \
         hipLaunchKernelGGL((merge_vec_kernel<T, GG>), grid, dim3(256), 0, s, a.m, a.e, a.u, (T *)a.o, a.lse,    \
                            a.B, a.H, a.n_shards, a.N, a.o_ld, a.o_rowmap, a.u_mode);                            \
         break;                                                                                                  \
     }
+    bool fallback = !vec;
     if (vec) {
         switch (G) {
             MERGE_CASE(4) MERGE_CASE(8) MERGE_CASE(16) MERGE_CASE(32) MERGE_CASE(64)
         }
-    } else {
+    }
+    if (fallback) {
         dim3 grid((a.N + 3) / 4, a.H, a.B);
         hipLaunchKernelGGL(merge_scalar_kernel<T>, grid, dim3(256), 0, s, a.m, a.e, a.u, (T *)a.o, a.lse, a.B, a.H,
                            a.n_shards, a.N, a.d, a.o_ld, a.o_rowmap, a.u_mode);
