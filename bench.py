@@ -174,7 +174,7 @@ class Workload:
         return sec, stages, merge_alone
 
     def graph_replay(self, steps, warmup):
-        """The same step captured once in a HIP graph and replayed: W untimed replays, then K timed ones."""
+        """The same step captured once in a HIP graph and replayed: max(W, 60) untimed replays, then K timed ones."""
         import torch
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
@@ -184,7 +184,7 @@ class Workload:
         g = torch.cuda.CUDAGraph()
         with torch.cuda.graph(g):
             self.step()
-        for _ in range(warmup):
+        for _ in range(max(warmup, 60)):           # capture left the device idle: at least 60 replays to be busy again
             g.replay()
         return time_steps(g.replay, steps)
 
