@@ -184,48 +184,53 @@ def pre_pass(h_rows, pos_rows, w, cfg):
 
 # --------------------------------------------------------------------------- Algorithm 3
 def attn_pass(q, k, v, s, scale=1.0):
-    """Algorithm 3 for one (query-shard, key/value-shard) pair.
+    """The three quantities an AttnNode returns for one (query-shard, key/value-shard) pair, written from their
+    definitions in the Post-Pass subsection (Algorithm 3 computes the same): for query row x of head h, with
+    scores a[x, y] = scale <q[h, x], k[g, y]> + s[x, y] over the keys y of the shard and g the key/value head
+    that h reads,
+        m[h, x] = max_y a[x, y],   e[h, x] = sum_y exp(a[x, y] - m[h, x]),
+        u[h, x] = sum_y exp(a[x, y] - m[h, x]) v[g, y] / e[h, x].
 
     q (H, nq, d); k, v (H_KV, nk, d); s (nq, nk) additive mask.
-    Returns m (H, nq), e (H, nq), u (H, nq, d) with u the NORMALISED partial output.
+    Returns m (H, nq), e (H, nq), u (H, nq, d); a row that sees no key has m = -inf, e = 0, u = 0.
     """
     H, nq, d = q.shape
     Hkv, nk, _ = k.shape
+    m = np.full((H, nq), -np.inf)
+    e = np.zeros((H, nq))
+    u = np.zeros((H, nq, d))
     if nk == 0:
-        return np.full((H, nq), -np.inf), np.zeros((H, nq)), np.zeros((H, nq, d))
-    rep = H // Hkv
-    k = np.repeat(k, rep, axis=0)                       # repeat_kv on k
-    v = np.repeat(v, rep, axis=0)                       # repeat_kv on v
-    a = scale * (q @ k.transpose(0, 2, 1)) + s[None]    # scores plus mask
-    m = a.max(axis=-1)                                  # row maxima
-    m_sub = np.where(np.isfinite(m), m, 0.0)            # rows with no visible key: exp(-inf - 0) = 0
-    a = np.exp(a - m_sub[..., None])                    # subtract-max exponentials
-    e = a.sum(axis=-1)                                  # their row sums
-    e_div = np.where(e > 0.0, e, 1.0)
-    a = a / e_div[..., None]                            # normalise within the shard
-    u = a @ v                                           # partial output
+        return m, e, u
+    heads_per_kv = H // Hkv
+    for h in range(H):
+        g = h // heads_per_kv
+        a = scale * (q[h] @ k[g].T) + s                    # (nq, nk)
+        m[h] = a.max(axis=1)
+        seen = np.isfinite(m[h])                           # rows with at least one visible key
+        p = np.exp(a[seen] - m[h][seen, None])
+        e[h][seen] = p.sum(axis=1)
+        u[h][seen] = (p @ v[g]) / e[h][seen, None]
     return m, e, u
 
 
 # --------------------------------------------------------------------------- Algorithm 4 (merge)
 def post_pass_merge(ms, es, us):
-    """Combine beta partials of the same query rows (Algorithm 4 before o_proj).
+    """The output rows of one query shard from its beta partials, by the identity the Post-Pass subsection
+    derives (the merge steps of Algorithm 4 evaluate it): with n = max_k m_k and weights
+    c_k = exp(m_k - n) e_k,
+        o = sum_k c_k u_k / sum_k c_k.
+    A partial with m_k = -inf (no visible key in S_k) has weight 0.
 
-    ms, es: sequences of (H, rows); us: sequence of (H, rows, d), normalised u.
-    Returns o (H, rows, d) = sum_k exp(m_k - n) e_k u_k / sum_k exp(m_k - n) e_k.
+    ms, es: sequences of (H, rows); us: sequence of (H, rows, d), normalised u.  Returns o (H, rows, d).
     """
-    o = np.zeros_like(us[0])
-    w = np.zeros_like(es[0])
-    n = ms[0]
-    for m in ms[1:]:
-        n = np.maximum(n, m)
-    n_sub = np.where(np.isfinite(n), n, 0.0)
-    for m, e, u in zip(ms, es, us):
-        coef = np.where(np.isfinite(m), np.exp(m - n_sub), 0.0) * e
-        w = w + coef
-        o = o + coef[..., None] * u
-    w_div = np.where(w > 0.0, w, 1.0)
-    return o / w_div[..., None]
+    M, E, U = np.stack(ms), np.stack(es), np.stack(us)      # (beta, H, rows[, d])
+    n = M.max(axis=0)
+    c = np.zeros_like(M)
+    live = np.isfinite(M)
+    c[live] = np.exp((M - np.where(np.isfinite(n), n, 0.0))[live]) * E[live]
+    total = c.sum(axis=0)
+    o = (c[..., None] * U).sum(axis=0)
+    return o / np.where(total > 0.0, total, 1.0)[..., None]
 
 
 # --------------------------------------------------------------------------- all pairs on given q, k, v
