@@ -447,8 +447,9 @@ def main():
 
     # Order of the run.  (1) The timed region as the first thing the device does after start-up: W + K steps on a
     # device that was idle (reported as from_idle).  (2) The CPU oracle (device idle meanwhile).  (3) Every other
-    # measurement.  (4) The timed region again, W + K steps right behind (3): the device has been busy for seconds
-    # and holds the clock it sustains under this load.  (4) is `value`; an idle MI355X takes about 60 of these
+    # measurement, ending with at least 100 individually timed steps of the headline workload.  (4) The timed
+    # region again, W + K steps right behind (3): the device has been busy and holds the clock it sustains
+    # under this load.  (4) is `value`; an idle MI355X takes about 60 of these
     # 0.8 ms steps to reach that clock, more than the W a short run asks for.
     cfg = CONFIGS[args.config]
     key = args.config
@@ -470,7 +471,6 @@ def main():
     if bf16 and not args.no_ceilings:
         extra["measured_ceilings"] = measured_ceilings(cas)
     st = wl.staged(max(args.steps, 20))
-    per_step = per_step_stats(wl.step, max(args.steps, 50))
     sec_m, stm, merge_alone = wl.materialised(max(5, args.steps // 4))
     if bf16 and not args.headline_only:
         torch.cuda.empty_cache()
@@ -487,6 +487,8 @@ def main():
         extra["other_configs"] = others
         torch.cuda.empty_cache()
 
+    # per-step statistics of the headline step (events around every step), then the headline itself
+    per_step = per_step_stats(wl.step, max(args.steps, 100))
     sec = wl.timed(args.steps, args.warmup)                       # the headline: W warm-up steps, K timed steps
     sec_graph = wl.graph_replay(args.steps, args.warmup)
 
@@ -510,7 +512,8 @@ def main():
                    "io_rows": "original"},
         "layer_tflops": tflops, "layer_frac_of_mfma_peak": tflops / peak, "layer_gflop_counted": fl["total"] / 1e9,
         "timing": {"ms_per_step": sec * 1e3, "clock": "host, device synchronised before and after the K steps",
-                   "position": "last in the run, right behind the other measurements (device busy for seconds)",
+                   "position": "last in the run, right behind the other measurements, the last of which are the per-step "
+                               "event timings of this same step (per_step_events)",
                    "from_idle_ms_per_step": sec_idle * 1e3,
                    "from_idle_position": "first device work of the process, same W and K",
                    "hip_graph_replay_ms_per_step": sec_graph * 1e3,
