@@ -390,7 +390,8 @@ CASCADE_API int32_t cascade_greedy_token(const void *logits, int32_t dtype, int3
 /* The same computation with stage boundaries marked for measurement: HIP event
  * stage_events[i] (hipEvent_t, created by the caller, NULL entries skipped) is
  * recorded on the stream at boundary i.  Boundaries (CASCADE_N_STAGE_EVENTS):
- * 0 start, 1 gather+norm1, 2 qkv GEMM, 3 rotary, 4 attention (partial
+ * 0 start, 1 gather+norm1, 2 qkv GEMM, 3 rotary (same instant as 2 when the
+ * rotation ran in the GEMM's epilogue: bf16 pre-norm layers), 4 attention (partial
  * attention), 5 LSE merge (same instant as 4 in FUSED mode), 6 o projection +
  * residual, 7 norm2, 8 FFN up/gate GEMM, 9 FFN down + residual + scatter.       */
 #define CASCADE_N_STAGE_EVENTS 10
