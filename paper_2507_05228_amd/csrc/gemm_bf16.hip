@@ -194,7 +194,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_kernel(GemmBf16Params p
                 if (c >= seg_rows) continue;
                 float v = acc[i][j][r] + bias_v[j];
                 if (SWIGLU) v = silu_f(v) * acc[i][j + TN_OUT][r];
-                else v = apply_act(v, flags);
+                else v = apply_act_bf16(v, flags);
                 if (rrow) v += (float)rrow[c];
                 yrow[c] = (bf16_t)v;
             }

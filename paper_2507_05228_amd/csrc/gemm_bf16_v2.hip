@@ -155,7 +155,7 @@ __device__ __forceinline__ void gemm_epilogue(const Gemm2Params &p, f32x4 (&acc)
                         for (int x = 0; x < 4; ++x) v[x] = silu_fast(v[x]) * up[x];
                     } else if constexpr (!SWIGLU && ACT) {
 #pragma unroll
-                        for (int x = 0; x < 4; ++x) v[x] = apply_act(v[x], flags);
+                        for (int x = 0; x < 4; ++x) v[x] = apply_act_bf16(v[x], flags);
                     }
                     if (c + 4 <= seg_rows) {
                         if (RES_AHEAD && res_ahead) {
@@ -226,6 +226,18 @@ __device__ __forceinline__ void gemm_epilogue_tile_rope(const Gemm2Params &p, f3
     const int lh = p.rope_lh, half = 1 << lh, n_pairs = seg_rows >> 1;
     const int gcol0 = p.seg_col0[seg];
     const bf16_t *bias = (p.flags & CASCADE_EPI_BIAS) ? p.bias[seg] : nullptr;
+    f32x4 bias_a[TNO], bias_b[TNO];                        // of this lane's pairs, once
+#pragma unroll
+    for (int j = 0; j < TNO; ++j) {
+        const int pp = pair0 + wp0 + 16 * j + c4;
+        const int col1 = ((pp >> lh) << (lh + 1)) + (pp & (half - 1));
+        bias_a[j] = bias_b[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (bias && pp < n_pairs) {
+            const bf16x4 a4 = *(const bf16x4 *)(bias + col1), b4 = *(const bf16x4 *)(bias + col1 + half);
+            bias_a[j] = f32x4{(float)a4[0], (float)a4[1], (float)a4[2], (float)a4[3]};
+            bias_b[j] = f32x4{(float)b4[0], (float)b4[1], (float)b4[2], (float)b4[3]};
+        }
+    }
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
         const int row = wm0 + 16 * i + l16, gm = m0 + row;
@@ -236,10 +248,7 @@ __device__ __forceinline__ void gemm_epilogue_tile_rope(const Gemm2Params &p, f3
             const int pp = pair0 + tp, ph = pp & (half - 1);
             const int col1 = ((pp >> lh) << (lh + 1)) + ph;
             const bool inside = pp < n_pairs;
-            f32x4 a = acc_load(acc[i][j]), b = acc_load(acc[i][j + TNO]);
-            if (bias && inside)
-#pragma unroll
-                for (int x = 0; x < 4; ++x) { a[x] += (float)bias[col1 + x]; b[x] += (float)bias[col1 + half + x]; }
+            f32x4 a = acc_load(acc[i][j]) + bias_a[j], b = acc_load(acc[i][j + TNO]) + bias_b[j];
             if (inside && gcol0 + col1 < p.rope_cols) {
                 const f32x4 cs = *(const f32x4 *)(trow + ph), sn = *(const f32x4 *)(trow + half + ph);
                 const f32x4 ra = a * cs - b * sn, rb = b * cs + a * sn;
@@ -304,6 +313,19 @@ __device__ __forceinline__ void gemm_epilogue_tile(const Gemm2Params &p, f32x4 (
     };
     auto to_lds = [&](auto general_tag) {
     constexpr bool GENERAL = decltype(general_tag)::value;
+    // the bias of this lane's columns, once (it does not depend on the row block)
+    f32x4 bias_v[GENERAL ? TNO : 1];
+    if constexpr (GENERAL) {
+#pragma unroll
+        for (int j = 0; j < TNO; ++j) {
+            const int tc = wc0 + 16 * j + c4;
+            bias_v[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+            if (bias && nloc0 + tc < seg_rows) {
+                const bf16x4 b4 = *(const bf16x4 *)(bias + nloc0 + tc);
+                bias_v[j] = f32x4{(float)b4[0], (float)b4[1], (float)b4[2], (float)b4[3]};
+            }
+        }
+    }
     if (has_res) load_res(0, 0);
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
@@ -322,13 +344,11 @@ __device__ __forceinline__ void gemm_epilogue_tile(const Gemm2Params &p, f32x4 (
 #pragma unroll
                 for (int x = 0; x < 4; ++x) v[x] = silu_fast(v[x]) * up[x];
             } else if constexpr (GENERAL) {
-                if (bias && inside)
-#pragma unroll
-                    for (int x = 0; x < 4; ++x) v[x] += (float)bias[nloc0 + tc + x];
+                v += bias_v[j];
                 if constexpr (ACT_OK)
                     if (act)
 #pragma unroll
-                        for (int x = 0; x < 4; ++x) v[x] = apply_act(v[x], flags);
+                        for (int x = 0; x < 4; ++x) v[x] = apply_act_bf16(v[x], flags);
             }
             if (has_res) {                                 // added before the one rounding to bf16
                 const bf16x4 r4 = rv[i & 1][j];
@@ -876,7 +896,8 @@ static int cu_count() {                                   // of the current devi
 static bool v2_eligible(const GemmArgs &a) {
     if (a.K % 64 != 0 || a.K < 64 || a.ldx % 8 != 0 || a.ldy % 4 != 0 || ((a.epilogue & CASCADE_EPI_RESIDUAL) && a.ldres % 4 != 0))
         return false;
-    if (((uintptr_t)a.Y | (uintptr_t)a.residual) % 8) return false;
+    if (((uintptr_t)a.Y | (uintptr_t)a.residual | (uintptr_t)a.bias[0] | (uintptr_t)a.bias[1] | (uintptr_t)a.bias[2]) % 8)
+        return false;                                                // 8-byte pieces of output, residual and bias
     for (int i = 0; i < 3; ++i)
         if (a.seg_end[i] % 4) return false;                         // 4-column store chunks stay inside a segment
     return true;
