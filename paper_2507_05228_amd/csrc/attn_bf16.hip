@@ -632,6 +632,30 @@ int32_t launch_attn_bf16(const cascade_plan *p, const AttnArgs &a, hipStream_t s
     if ((a.qs_n | a.qs_h | a.qs_b | a.ks_n | a.ks_h | a.ks_b) % 8 ||
         ((uintptr_t)a.q | (uintptr_t)a.k | (uintptr_t)a.v | (uintptr_t)a.workspace) % 16)
         return CASCADE_EUNSUPPORTED;
+    // FUSED mode under a causal mask, launches of more than one round of workgroups: walk queries and keys in
+    // ascending position (the plan's one-shard view; q, k, v and o rows are reached through its row map, K and
+    // V^T are gathered in that order).  Tiles of a shard of scattered tokens span a large part of the sequence,
+    // so that most (query tile, key tile) pairs are partly masked and a third to a half of the products of the
+    // shard-ordered walk are thrown away; in position order only the diagonal tiles are.  The result is the same:
+    // the merge over key/value shards does not depend on how the keys are grouped.  A launch of a single round
+    // gains nothing (its duration is that of the workgroup with the last query rows, which sees every tile either
+    // way) and keeps the shard order, which needs no gather of K.
+    if (a.fused && a.mask_kind == CASCADE_MASK_CAUSAL && p->sorted && !a.q_rowmap && !a.o_rowmap &&
+        p->max_abs_pos < (1 << 30)) {
+        const int rep = a.H / a.Hkv;
+        const int hpb = rep % 4 == 0 ? 4 : rep % 2 == 0 ? 2 : 1;
+        const int granule = 32 * (8 / hpb);
+        const int64_t wgs = (int64_t)a.B * a.Hkv * (rep / hpb) * ((p->seq_len + granule - 1) / granule);
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) cus = 256;
+        if (wgs > cus && p->seq_len > 32 * (4 / hpb)) {
+            AttnArgs b = a;
+            b.q_rowmap = b.o_rowmap = b.kv_rowmap = p->sorted_to_row_d;
+            if (a.d == 128) return launch_attn_cfg<128, 8>(p->sorted, b, s);
+            return launch_attn_cfg<64, 8>(p->sorted, b, s);
+        }
+    }
     // 8 wavefronts cover 256 / hpb query rows of a shard; when no shard of the plan has more than half of that,
     // four of them would never have rows: use the 4-wavefront workgroup
     const int rep = a.H / a.Hkv;

@@ -51,6 +51,12 @@ struct cascade_plan {
     // this plan's packed rows.  nullptr: S = R.
     cascade_plan *kv;
     int32_t *kv_to_row_h, *kv_to_row_d;
+    // Causal plans: the same tokens as one shard in ascending position (ties by token index), with its tile
+    // lists, and the map from its rows to this plan's packed rows.  The fused attention kernel may walk queries
+    // and keys in that order (the merge over key/value shards does not depend on how the keys are grouped):
+    // a tile then covers neighbouring positions and only the tiles on the diagonal hold masked scores.
+    cascade_plan *sorted;
+    int32_t *sorted_to_row_d;
 };
 
 // the partition that shards keys and values (the plan itself when S = R)

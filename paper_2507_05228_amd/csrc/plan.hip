@@ -17,6 +17,8 @@ extern "C" int32_t cascade_last_hip_error(void) { return g_last_hip_error; }
 static void free_plan(cascade_plan *p) {
     if (!p) return;
     free_plan(p->kv);
+    free_plan(p->sorted);
+    if (p->sorted_to_row_d) (void)hipFree(p->sorted_to_row_d);
     free(p->kv_to_row_h);
     if (p->kv_to_row_d) (void)hipFree(p->kv_to_row_d);
     free(p->perm_h); free(p->inv_perm_h); free(p->offsets_h); free(p->pos_packed_h);
@@ -106,8 +108,12 @@ static hipError_t build_tiles(cascade_plan *p, CascadeTileList &out, int granule
     return to_device(&out.shard_first, first.data(), first.size());
 }
 
+static int32_t complete_plan(cascade_plan *p, const int32_t *positions_host);
+static int32_t build_sorted_view(cascade_plan *p, const int32_t *positions_host);
+
 static int32_t build_plan(cascade_plan **out, int32_t batch, int32_t seq_len, int32_t n_shards,
-                          const int32_t *token_to_shard_host, const int32_t *positions_host, int32_t mask_kind) {
+                          const int32_t *token_to_shard_host, const int32_t *positions_host, int32_t mask_kind,
+                          bool with_sorted_view) {
     if (!out) return CASCADE_EINVAL;
     *out = nullptr;
     if (!token_to_shard_host || batch <= 0 || seq_len <= 0 || n_shards <= 0) return CASCADE_EINVAL;
@@ -138,6 +144,20 @@ static int32_t build_plan(cascade_plan **out, int32_t batch, int32_t seq_len, in
             p->inv_perm_h[t] = r;
         }
     }
+    const int32_t st = complete_plan(p, positions_host);
+    if (st != CASCADE_OK) { free_plan(p); return st; }
+    if (with_sorted_view && mask_kind == CASCADE_MASK_CAUSAL) {
+        const int32_t st2 = build_sorted_view(p, positions_host);
+        if (st2 != CASCADE_OK) { free_plan(p); return st2; }
+    }
+    *out = p;
+    return CASCADE_OK;
+}
+
+// Positions of the packed rows, the last token, device copies and tile lists of a plan whose perm_h, inv_perm_h and
+// offsets_h are filled in.
+static int32_t complete_plan(cascade_plan *p, const int32_t *positions_host) {
+    const int32_t batch = p->batch, seq_len = p->seq_len, n_shards = p->n_shards;
     for (int r = 0; r < seq_len; ++r) {
         p->pos_packed_h[r] = positions_host ? positions_host[p->perm_h[r]] : p->perm_h[r];
         const int64_t ap = std::llabs((int64_t)p->pos_packed_h[r]);
@@ -163,15 +183,41 @@ static int32_t build_plan(cascade_plan **out, int32_t batch, int32_t seq_len, in
     if (e == hipSuccess) e = to_device(&p->pos_packed_d, p->pos_packed_h, seq_len);
     static const int granules[4] = {32, 64, 128, 256};
     for (int g = 0; g < 4 && e == hipSuccess; ++g) e = build_tiles(p, p->tiles[g], granules[g]);
-    if (e != hipSuccess) { cascade_set_hip_error(e); free_plan(p); return CASCADE_EHIP; }
-    *out = p;
+    if (e != hipSuccess) { cascade_set_hip_error(e); return CASCADE_EHIP; }
+    return CASCADE_OK;
+}
+
+// The position-sorted one-shard view of a causal plan (see cascade_plan::sorted).
+static int32_t build_sorted_view(cascade_plan *p, const int32_t *positions_host) {
+    const int32_t N = p->seq_len;
+    cascade_plan *v = new (std::nothrow) cascade_plan();
+    if (!v) return CASCADE_EINVAL;
+    memset(v, 0, sizeof(*v));
+    p->sorted = v;                                           // freed with p from here on
+    v->batch = p->batch; v->seq_len = N; v->n_shards = 1; v->mask_kind = p->mask_kind;
+    v->perm_h = (int32_t *)malloc(sizeof(int32_t) * N);
+    v->inv_perm_h = (int32_t *)malloc(sizeof(int32_t) * N);
+    v->offsets_h = (int32_t *)malloc(sizeof(int32_t) * 2);
+    v->pos_packed_h = (int32_t *)malloc(sizeof(int32_t) * N);
+    if (!v->perm_h || !v->inv_perm_h || !v->offsets_h || !v->pos_packed_h) return CASCADE_EINVAL;
+    for (int t = 0; t < N; ++t) v->perm_h[t] = t;
+    if (positions_host)
+        std::stable_sort(v->perm_h, v->perm_h + N, [&](int32_t x, int32_t y) { return positions_host[x] < positions_host[y]; });
+    for (int r = 0; r < N; ++r) v->inv_perm_h[v->perm_h[r]] = r;
+    v->offsets_h[0] = 0; v->offsets_h[1] = N;
+    const int32_t st = complete_plan(v, positions_host);
+    if (st != CASCADE_OK) return st;
+    std::vector<int32_t> to_row(N);
+    for (int r = 0; r < N; ++r) to_row[r] = p->inv_perm_h[v->perm_h[r]];
+    const hipError_t e = to_device(&p->sorted_to_row_d, to_row.data(), N);
+    if (e != hipSuccess) { cascade_set_hip_error(e); return CASCADE_EHIP; }
     return CASCADE_OK;
 }
 
 extern "C" int32_t cascade_plan_create(cascade_plan **out, int32_t batch, int32_t seq_len, int32_t n_shards,
                                        const int32_t *token_to_shard_host, const int32_t *positions_host,
                                        int32_t mask_kind) {
-    return build_plan(out, batch, seq_len, n_shards, token_to_shard_host, positions_host, mask_kind);
+    return build_plan(out, batch, seq_len, n_shards, token_to_shard_host, positions_host, mask_kind, true);
 }
 
 extern "C" int32_t cascade_plan_create_rs(cascade_plan **out, int32_t batch, int32_t seq_len, int32_t n_row_shards,
@@ -182,9 +228,9 @@ extern "C" int32_t cascade_plan_create_rs(cascade_plan **out, int32_t batch, int
     *out = nullptr;
     if (!token_to_kv_shard_host || n_kv_shards <= 0) return CASCADE_EINVAL;
     cascade_plan *p = nullptr;
-    int32_t st = build_plan(&p, batch, seq_len, n_row_shards, token_to_row_shard_host, positions_host, mask_kind);
+    int32_t st = build_plan(&p, batch, seq_len, n_row_shards, token_to_row_shard_host, positions_host, mask_kind, true);
     if (st != CASCADE_OK) return st;
-    st = build_plan(&p->kv, batch, seq_len, n_kv_shards, token_to_kv_shard_host, positions_host, mask_kind);
+    st = build_plan(&p->kv, batch, seq_len, n_kv_shards, token_to_kv_shard_host, positions_host, mask_kind, false);
     if (st != CASCADE_OK) { free_plan(p); return st; }
     p->kv_to_row_h = (int32_t *)malloc(sizeof(int32_t) * seq_len);
     if (!p->kv_to_row_h) { free_plan(p); return CASCADE_EINVAL; }

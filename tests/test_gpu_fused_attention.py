@@ -109,6 +109,36 @@ def test_attention_output_without_mask_and_with_unordered_positions(cas, mask_ki
     assert slice_errors(got[0], ref).max() < TOL[cfg.dtype]
 
 
+MANY_WG = CONFIGS["C3"].with_(name="fa-many-workgroups", d_model=256, n_heads=4, n_kv_heads=4, head_dim=64, d_ff=256,
+                              batch=9, seq_len=2000, n_shards=7, index=45)
+
+
+@pytest.mark.parametrize("case", ["token-order", "unordered-positions", "repeated-positions", "two-shardings"])
+def test_attention_output_of_a_launch_of_several_rounds(cas, case):
+    """More workgroups than CUs (9 sequences x 4 heads x 8 query tiles): the fused kernel then walks queries and keys
+    in ascending position through the plan's one-shard view, whatever the shards are.  Checked for every row and
+    head of two of the sequences, with positions that do not follow the token index, with positions that repeat
+    (every key at the same position as the query is visible), and with distinct row and key/value shardings."""
+    cfg = MANY_WG
+    rng = np.random.default_rng(17)
+    a = make_assignment("ragged", cfg.seq_len, cfg.n_shards, 21)
+    pos = kv = None
+    if case == "unordered-positions":
+        pos = rng.permutation(5 * cfg.seq_len)[:cfg.seq_len].astype(np.int32)
+    elif case == "repeated-positions":
+        pos = rng.integers(0, cfg.seq_len // 3, cfg.seq_len).astype(np.int32)
+    elif case == "two-shardings":
+        kv = make_assignment("perm", cfg.seq_len, 5, 22)
+    w, h = make_layer_weights(cfg), make_hidden(cfg)
+    w64 = {k: v.astype(np.float64) for k, v in w.items()}
+    got = gpu_attention_output(cas, cfg, w, h, a, cas.ATTN_FUSED, positions=pos, kv=kv)
+    _, perm, _ = orc.shard_plan(a, cfg.n_shards)
+    for b in (0, cfg.batch - 1):
+        ref = oracle_attention_rows(h[b].astype(np.float64), w64, cfg, perm, positions=pos)
+        err = slice_errors(got[b], ref)
+        assert err.max() < TOL[cfg.dtype], (case, b, np.unravel_index(err.argmax(), err.shape), err.max())
+
+
 def test_attention_output_with_two_shardings(cas):
     """Row shards from a (c, delta)-sharding, key/value shards from its m-split: the merged output is still
     plain attention, in the row sharding's packed order."""
