@@ -80,4 +80,6 @@ struct AttnBf16Params {
 // Fused attention, software-pipelined (attn_bf16_fused.hip).  The parameters are the ones the kernel of
 // attn_bf16.hip takes; the query tiles are those of granule 256 / hpb rows.
 // all_visible: no causal mask and no ragged key/value tile, i.e. no score needs a compare.
-int32_t launch_attn_fused(const AttnBf16Params &k, int head_dim, int n_qtiles, bool all_visible, hipStream_t s);
+// split: the query tiles are 32-row tiles and each workgroup's two wavefront groups share one, every other
+// key/value tile each (four heads per workgroup, masked kernel only).
+int32_t launch_attn_fused(const AttnBf16Params &k, int head_dim, int n_qtiles, bool all_visible, bool split, hipStream_t s);

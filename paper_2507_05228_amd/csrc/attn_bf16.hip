@@ -558,14 +558,15 @@ size_t attn_bf16_workspace_bytes(const cascade_plan *p, int32_t B, int32_t Hkv, 
     return vt_bytes_of(p, B, Hkv, d) + align_up((size_t)B * Hkv * p->seq_len * d * 2, 256);
 }
 
+// split: fused mode only; 32-row query tiles for the fused kernel's split walk (see attn_bf16_fused.hip)
 template <int D, int NWV>
-static int32_t launch_attn_cfg(const cascade_plan *p, const AttnArgs &a, hipStream_t s) {
+static int32_t launch_attn_cfg(const cascade_plan *p, const AttnArgs &a, hipStream_t s, bool split = false) {
     const cascade_plan *kvp = kv_plan(p);                      // key/value shards (S); query tiles follow p (R)
     const int N = p->seq_len, S = kvp->n_shards;
     const int rep = a.H / a.Hkv;
     const int hpb = rep % 4 == 0 ? 4 : rep % 2 == 0 ? 2 : 1;
     const int rowgroups = NWV / hpb;
-    const int granule = 32 * rowgroups;                        // 32 .. 256 query rows per workgroup
+    const int granule = split ? 32 : 32 * rowgroups;           // 32 .. 256 query rows per workgroup
     const CascadeTileList &ql = plan_tiles(p, granule);
     const CascadeTileList &kl = plan_tiles(kvp, KV_TILE);
     const int npad = npad_of(p);
@@ -617,8 +618,9 @@ static int32_t launch_attn_cfg(const cascade_plan *p, const AttnArgs &a, hipStre
         bool all_visible = a.mask_kind != CASCADE_MASK_CAUSAL;
         for (int j = 0; j < kvp->n_shards && all_visible; ++j)
             all_visible = (kvp->offsets_h[j + 1] - kvp->offsets_h[j]) % KV_TILE == 0;
-        return launch_attn_fused(k, D, ql.count, all_visible, s);
+        return launch_attn_fused(k, D, ql.count, all_visible, split, s);
     }
+    if (split) return CASCADE_EINVAL;
     dim3 grid((unsigned)(gy * ql.count), 1, a.fused ? 1 : S);
     hipLaunchKernelGGL(kern, grid, dim3(NWV * 64), lds, s, k);
     CASCADE_HIP_TRY(hipGetLastError());
@@ -649,11 +651,15 @@ int32_t launch_attn_bf16(const cascade_plan *p, const AttnArgs &a, hipStream_t s
         int dev = 0, cus = 0;
         if (hipGetDevice(&dev) != hipSuccess ||
             hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) cus = 256;
-        if (wgs > cus && p->seq_len > 32 * (4 / hpb)) {
+        // A launch of a single round: with four heads per workgroup the split walk (32-row query tiles, the two
+        // wavefront groups of a workgroup take every other key/value tile) doubles the workgroups and halves the
+        // longest walk; it needs the position order for its tile counts to be even.
+        const bool split = wgs <= cus && hpb == 4 && p->seq_len >= 4 * KV_TILE;
+        if ((wgs > cus && p->seq_len > 32 * (4 / hpb)) || split) {
             AttnArgs b = a;
             b.q_rowmap = b.o_rowmap = b.kv_rowmap = p->sorted_to_row_d;
-            if (a.d == 128) return launch_attn_cfg<128, 8>(p->sorted, b, s);
-            return launch_attn_cfg<64, 8>(p->sorted, b, s);
+            if (a.d == 128) return launch_attn_cfg<128, 8>(p->sorted, b, s, split);
+            return launch_attn_cfg<64, 8>(p->sorted, b, s, split);
         }
     }
     // 8 wavefronts cover 256 / hpb query rows of a shard; when no shard of the plan has more than half of that,

@@ -82,8 +82,13 @@ __device__ __forceinline__ void fence() { __builtin_amdgcn_sched_barrier(0); }
 // key's position (causal plans, plans with ragged key/value tiles); false only when every key of every tile
 // is visible to every query.  A kernel parameter rather than a choice per tile: a second copy of the MFMA
 // statements inside the loop makes the register allocator shuffle the accumulators between the copies.
-template <int D, int TQ, bool MASKED>
+// SPLIT (TQ = 2, MASKED, four heads per workgroup): the two wavefront groups take the same 32 query rows and every
+// other key/value tile each, and their running (offset, row sum, output) are merged through LDS at the end.  For
+// launches of a single round of workgroups: a query tile's walk is then half as long and there are twice as many
+// workgroups, so that the CUs with early (short) query tiles take a second one instead of idling.
+template <int D, int TQ, bool MASKED, bool SPLIT = false>
 __global__ __launch_bounds__(1024 / TQ) void attn_fused_kernel(AttnBf16Params p) {
+    static_assert(!SPLIT || (TQ == 2 && MASKED), "the split walk exists for the masked 8-wavefront kernel");
     constexpr int KS = D / 32;                         // k-steps of the score product
     constexpr int DB = D / 16;                         // 16-row blocks of O^T
     constexpr int K_ROW = D * 2;                       // bytes per K row in LDS
@@ -114,7 +119,7 @@ __global__ __launch_bounds__(1024 / TQ) void attn_fused_kernel(AttnBf16Params p)
     const tile_cptr kvtiles = (tile_cptr)p.kvtiles;
     const tile_cptr qtp = (tile_cptr)p.qtiles + q_tile;
     const int q_row_start = qtp->row_start, q_n_rows = qtp->n_rows, q_pmax = qtp->pmax;
-    const int wrow0 = rg * 16 * TQ;
+    const int wrow0 = SPLIT ? 0 : rg * 16 * TQ;       // SPLIT: both wavefront groups hold the query tile's 32 rows
 
     // ---- query fragments (B operand of S^T = K Q^T): lane holds row l16 of each 16-row block, head-dim
     //      chunk 32 ks + 8 g4
@@ -129,7 +134,9 @@ __global__ __launch_bounds__(1024 / TQ) void attn_fused_kernel(AttnBf16Params p)
         const bf16_t *qp = p.q + b * p.qs_b + h * p.qs_h + (int64_t)(p.q_rowmap ? p.q_rowmap[r] : r) * p.qs_n + g4 * 8;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) Q[qb][ks] = *(const bf16x8 *)(qp + ks * 32);
-        qlim[qb] = p.causal ? p.pos_packed[r] : INT_MAX - 1;
+        // without a mask: the largest position the launcher accepts, so that only the padding of ragged tiles
+        // (position 2^30) is cut; all positions are below 2^30 in magnitude, so "limit - position" cannot overflow
+        qlim[qb] = p.causal ? p.pos_packed[r] : (1 << 30) - 1;
     }
 
     // ---- visible key/value tiles: a prefix of the list ordered by smallest position
@@ -178,13 +185,13 @@ __global__ __launch_bounds__(1024 / TQ) void attn_fused_kernel(AttnBf16Params p)
         v_lane[i] = (uint32_t)rr * (uint32_t)(p.npad * 2) + c * 16;
     }
     // K rows and key positions of a tile (K_INSTR + 1 loads per wavefront), V^T columns of a tile (V_INSTR loads)
-    auto issue_k = [&](const TileMeta &tm, int stage) {
+    auto issue_k = [&](const TileMeta &tm, int stage) {          // stage: counted in STAGE bytes from smem
         unsigned char *sk = smem + stage * STAGE;
         const uint32_t k_tile = (uint32_t)tm.row_start * (uint32_t)(p.ks_n * 2);
 #pragma unroll
         for (int i = 0; i < K_INSTR; ++i)
             load16_to_lds(rk, sk + (wave * K_INSTR + i) * K_RPI * K_ROW, k_rr[i] < tm.n_rows ? k_tile + k_lane[i] : OOB_OFF);
-        // every wavefront writes the same 64 positions (INT_MAX past a ragged tile's end): keeps the
+        // every wavefront writes the same 64 positions (2^30 past a ragged tile's end): keeps the
         // loads-per-batch count uniform
         load4_to_lds(rp, sk + K_BYTES + V_BYTES, (uint32_t)(tm.index * KV_TILE + lane) * 4);
     };
@@ -201,7 +208,7 @@ __global__ __launch_bounds__(1024 / TQ) void attn_fused_kernel(AttnBf16Params p)
     f32x4 L[TQ];                                       // row sums of the exponentials, accumulated by the matrix pipe
     f32x4 S[2][TQ][2];                                 // scores of a half tile: [buffer][query block][key block]
     u32x4 P[2][TQ];                                    // exponentials of a half tile (8 bf16), B operand layout
-    constexpr int RD = (D == 128 ? 7 : 3);             // operand fragments read ahead of their use
+    constexpr int RD = (D == 128 && !SPLIT ? 7 : 3);   // operand fragments read ahead of their use
     constexpr int RING = RD + 1;
     static_assert((NQF + NVF) % RING == 0, "the ring position of a step's first fragment must not move");
     bf16x8 ring[RING];                                 // operand fragments in flight
@@ -220,21 +227,22 @@ __global__ __launch_bounds__(1024 / TQ) void attn_fused_kernel(AttnBf16Params p)
     const float sl2 = p.scale_log2;
     const int k_swz = D == 128 ? l16 : (l16 >> 1);
     const int v_swz = l16 >> 1;
-    const int kf_lane = l16 * K_ROW, vf_lane = K_BYTES + l16 * 128;
+    const int kf_lane = l16 * K_ROW, vf_lane = l16 * 128;
 
     // Fragment f of a step whose score product reads half X of the K tile in stage qs and whose output
     // product reads half X of the V^T tile in stage vs: the K fragments come first, k-step by k-step with the
     // two key blocks alternating (an accumulator then recurs every 2 TQ MFMAs instead of every TQ: 1-2 % faster).
     // (Cutting the vector arithmetic into pieces of 3-5 instructions, one behind every MFMA, instead of chunks of
     // 10-12 behind every third or fourth, was measured 1-2 % slower: the SIMD's other wavefront fills the gaps.)
+    // (qs: byte offset of the K tile's stage in LDS; vs: byte offset of the V^T tile itself)
     auto frag_ptr = [&](int qs, int vs, auto x_tag, int f) -> const unsigned char * {
         constexpr int X = decltype(x_tag)::value;
         if (f < NQF) {
             const int kvb = 2 * X + f % 2, ks = f / 2;
-            return smem + qs * STAGE + kvb * 16 * K_ROW + kf_lane + (((4 * ks + g4) ^ k_swz) * 16);
+            return smem + qs + kvb * 16 * K_ROW + kf_lane + (((4 * ks + g4) ^ k_swz) * 16);
         }
         const int db = f - NQF;
-        return smem + vs * STAGE + db * 16 * 128 + vf_lane + (((4 * X + g4) ^ v_swz) * 16);
+        return smem + vs + db * 16 * 128 + vf_lane + (((4 * X + g4) ^ v_swz) * 16);
     };
 
     // ---- pieces of a step.  X = which half of their tiles the two products of the step read; the scores go
@@ -287,10 +295,10 @@ __global__ __launch_bounds__(1024 / TQ) void attn_fused_kernel(AttnBf16Params p)
         flagv = fl;
     };
     // key positions of this lane's accumulator rows (keys 16 kb + 4 g4 + 0..3 of half X) from the tile's stage
-    // (INT_MAX for the keys past a ragged tile's end: never visible)
+    // (2^30 for the keys past a ragged tile's end: never visible)
     auto read_positions = [&](auto x_tag, int qs, i32x4 (&pk)[2]) {
         constexpr int X = decltype(x_tag)::value;
-        const unsigned char *pp = smem + qs * STAGE + K_BYTES + V_BYTES + (32 * X + 4 * g4) * 4;
+        const unsigned char *pp = smem + qs + K_BYTES + V_BYTES + (32 * X + 4 * g4) * 4;
         pk[0] = *(const i32x4 *)pp;
         pk[1] = *(const i32x4 *)(pp + 64);
     };
@@ -301,7 +309,10 @@ __global__ __launch_bounds__(1024 / TQ) void attn_fused_kernel(AttnBf16Params p)
     // cycles, so the only choice, masked or not, is made once per tile outside.  On entry the ring holds the
     // first RD fragments; on exit those of the next step (half 1-X, stages nqs / nvs).  Returns whether some
     // maximum passed its row's threshold.
-    auto step = [&](auto x_tag, int qs, int vs, int nqs, int nvs) -> bool {
+    // NEXT: whether the ring is refilled for the next step at all (false in front of a barrier that has yet to
+    // confirm the next step's tiles: the caller then fills it behind the barrier).
+    auto step = [&](auto x_tag, auto next_tag, int qs, int vs, int nqs, int nvs) -> bool {
+        constexpr bool NEXT = decltype(next_tag)::value;
         constexpr int X = decltype(x_tag)::value;
         constexpr int NF = NQF + NVF, QS = TQ * NQF, NS = TQ * NF + TQ;   // slots: scores, output, row sums
         constexpr int NE = 2 * TQ;                           // chunks of exponentials: one per (query block, key block) pair
@@ -337,7 +348,7 @@ __global__ __launch_bounds__(1024 / TQ) void attn_fused_kernel(AttnBf16Params p)
             constexpr int f = decltype(f_tag)::value;
             // fragment f + RD of this step, or one of the first RD of the next
             if constexpr (f + RD < NF) ring[(f + RD) % RING] = *(const bf16x8 *)frag_ptr(qs, vs, x_tag, f + RD);
-            else ring[(f + RD) % RING] = *(const bf16x8 *)frag_ptr(nqs, nvs, nx, f + RD - NF);
+            else if constexpr (NEXT) ring[(f + RD) % RING] = *(const bf16x8 *)frag_ptr(nqs, nvs, nx, f + RD - NF);
             fence();
             static_for<TQ>([&](auto qb_tag) {
                 constexpr int qb = decltype(qb_tag)::value;
@@ -399,12 +410,22 @@ __global__ __launch_bounds__(1024 / TQ) void attn_fused_kernel(AttnBf16Params p)
 #pragma unroll
         for (int qb = 0; qb < TQ; ++qb) {
             P[0][qb] = P[1][qb] = u32x4{0u, 0u, 0u, 0u};
+            // (opaque: zeros rebuilt by moves right in front of the first MFMA that reads them would be read too early)
+            if constexpr (SPLIT) asm volatile("" : "+v"(P[0][qb]), "+v"(P[1][qb]));
             L[qb] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb) S[0][qb][kb] = S[1][qb][kb] = f32x4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
 #pragma unroll
-            for (int db = 0; db < DB; ++db) O[qb][db] = f32x4{0.f, 0.f, 0.f, 0.f};
+            for (int db = 0; db < DB; ++db) {
+                O[qb][db] = f32x4{0.f, 0.f, 0.f, 0.f};
+                // (split walk: zeroed here, in the accumulation registers, not inside its conditional loop body)
+                if constexpr (SPLIT) asm volatile("" : "+a"(O[qb][db]));
+            }
+            if constexpr (SPLIT) asm volatile("" : "+a"(L[qb]));
         }
+        const std::true_type refill;
+        const std::false_type no_refill;
+        if constexpr (!SPLIT) {
         TileMeta mt0 = {0, 0, 0, INT_MAX}, mt1 = mt0, mt2 = mt0, mt3 = mt0;     // tiles i .. i+3
         if (0 < n_tiles) mt0 = load_meta(0);
         if (1 < n_tiles) mt1 = load_meta(1);
@@ -416,14 +437,15 @@ __global__ __launch_bounds__(1024 / TQ) void attn_fused_kernel(AttnBf16Params p)
         phase_barrier<0, false>();                     // everything requested so far is complete and visible
         if (n_tiles > 0) {
 #pragma unroll
-            for (int f = 0; f < RD; ++f) ring[f] = *(const bf16x8 *)frag_ptr(0, 0, x0, f);
+            for (int f = 0; f < RD; ++f) ring[f] = *(const bf16x8 *)frag_ptr(0, K_BYTES, x0, f);
             int in_flight = 0;                         // loads of this wavefront requested at the previous barrier
             for (int i = 0; i <= n_tiles; ++i) {
                 const bool real = i < n_tiles, next_real = i + 1 < n_tiles;
-                const int qs = (real ? i : i - 1) & (NST - 1);      // past the end: the last tile again (finite scores)
-                const int vs = (i > 0 ? i - 1 : 0) & (NST - 1);     // tile i-1; in front of the first tile: P is zero
-                const int nqs = (next_real ? i + 1 : i) & (NST - 1), nvs = i & (NST - 1);
-                const bool need0 = step(x0, qs, vs, qs, vs);
+                // past the end: the last tile again (finite scores); in front of the first tile: P is zero
+                const int qs = ((real ? i : i - 1) & (NST - 1)) * STAGE;
+                const int vs = ((i > 0 ? i - 1 : 0) & (NST - 1)) * STAGE + K_BYTES;
+                const int nqs = ((next_real ? i + 1 : i) & (NST - 1)) * STAGE, nvs = (i & (NST - 1)) * STAGE + K_BYTES;
+                const bool need0 = step(x0, refill, qs, vs, qs, vs);
                 between_steps(need0 && real);
                 // The barrier between the two steps of a tile: what was requested two barriers ago has landed (the
                 // requests of the previous barrier may still be in flight), everyone is past step 2i.  Free from
@@ -436,7 +458,7 @@ __global__ __launch_bounds__(1024 / TQ) void attn_fused_kernel(AttnBf16Params p)
                 in_flight = 0;
                 if (i + 3 < n_tiles) { issue_k(mt3, (i + 3) & (NST - 1)); in_flight += LPT_K; }
                 if (i + 2 < n_tiles) { issue_v(mt2, (i + 2) & (NST - 1)); in_flight += LPT_V; }
-                const bool need1 = step(x1, qs, vs, nqs, nvs);
+                const bool need1 = step(x1, refill, qs, vs, nqs, nvs);
                 between_steps(need1 && real);
                 if (real) {
                     if (next_real) mt0 = mt1;
@@ -444,6 +466,57 @@ __global__ __launch_bounds__(1024 / TQ) void attn_fused_kernel(AttnBf16Params p)
                     if (i + 4 < n_tiles) mt3 = load_meta(i + 4);
                 }
             }
+        }
+        } else {
+        // Split walk.  Wavefront group g (0, 1) takes the tiles 2 j + g, j = 0 .. n_g - 1, through two stages of its
+        // own (stages 2 g and 2 g + 1); all eight wavefronts load the tiles of both groups.  One barrier in front of
+        // every iteration: there K of the tiles j + 1 and V^T of the tiles j are requested (V^T is used an iteration
+        // later: the output product trails by a tile), and everything requested at the previous barrier has landed.
+        // The operand ring is filled behind the barrier (the second step of an iteration does not read ahead into a
+        // tile the barrier has yet to confirm).  Iteration n_g flushes the group's pipeline on a stand-in (its last K
+        // tile with every score masked: the query limits are dropped below every position, and fetched again if the
+        // pass is repeated); a group with fewer tiles than the other only meets the remaining barriers.
+#pragma unroll
+        for (int qb = 0; qb < TQ; ++qb) {
+            const int rloc = 16 * qb + l16;
+            qlim[qb] = p.pos_packed[q_row_start + (rloc < q_n_rows ? rloc : max(q_n_rows - 1, 0))];
+        }
+        const int n_g0 = (n_tiles + 1) / 2, n_g1 = n_tiles / 2;     // tiles of the two groups; n_g0 >= n_g1
+        const int n_mine = rg == 0 ? n_g0 : n_g1, gst = 2 * rg;
+        TileMeta mv0 = {0, 0, 0, INT_MAX}, mk0 = mv0, mv1 = mv0, mk1 = mv0;   // tiles j and j + 1 of group 0, of group 1
+        if (0 < n_g0) mv0 = load_meta(0);
+        if (0 < n_g1) mv1 = load_meta(1);
+        if (1 < n_g0) mk0 = load_meta(2);
+        if (1 < n_g1) mk1 = load_meta(3);
+        if (0 < n_g0) issue_k(mv0, 0);
+        if (0 < n_g1) issue_k(mv1, 2);
+        for (int j = 0; j <= n_g0; ++j) {
+            __builtin_amdgcn_sched_barrier(0);
+            asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+            __builtin_amdgcn_sched_barrier(0);
+            if (j + 1 < n_g0) issue_k(mk0, (j + 1) & 1);
+            if (j + 1 < n_g1) issue_k(mk1, 2 + ((j + 1) & 1));
+            if (j < n_g0) issue_v(mv0, j & 1);
+            if (j < n_g1) issue_v(mv1, 2 + (j & 1));
+            if (n_mine > 0 && j <= n_mine) {
+                const bool real = j < n_mine;
+                const int qs = (gst + ((real ? j : j - 1) & 1)) * STAGE;
+                // in front of the group's first tile the output product (P is zero) reads the K rows: finite numbers
+                const int vs = j > 0 ? (gst + ((j - 1) & 1)) * STAGE + K_BYTES : qs;
+                if (!real)
+#pragma unroll
+                    for (int qb = 0; qb < TQ; ++qb) qlim[qb] = -(1 << 30);                 // nothing is visible
+#pragma unroll
+                for (int f = 0; f < RD; ++f) ring[f] = *(const bf16x8 *)frag_ptr(qs, vs, x0, f);
+                const bool need0 = step(x0, refill, qs, vs, qs, vs);
+                between_steps(need0 && real);
+                const bool need1 = step(x1, no_refill, qs, vs, qs, vs);
+                between_steps(need1 && real);
+            }
+            mv0 = mk0; mv1 = mk1;
+            if (j + 2 < n_g0) mk0 = load_meta(2 * (j + 2));
+            if (j + 2 < n_g1) mk1 = load_meta(2 * (j + 2) + 1);
+        }
         }
         mfma_drain();
         // start over together if any wavefront had to move an offset late (the barriers are the workgroup's)
@@ -454,6 +527,38 @@ __global__ __launch_bounds__(1024 / TQ) void attn_fused_kernel(AttnBf16Params p)
         for (int w = 0; w < NWV; ++w) any_redo |= redo_flags[w];
         phase_barrier<-1, true>();
         if (!__builtin_amdgcn_readfirstlane(any_redo)) break;
+    }
+
+    // ---- split walk: the second group hands its offsets, row sums and outputs to the first through LDS (the tile
+    // stages are free: everyone is past the last barrier of the pass); the offsets are integers, so bringing both
+    // to the larger one is exact.
+    if constexpr (SPLIT) {
+        float *xch = (float *)smem + (wave % (NWV / 2)) * ((TQ * DB * 4 + 2 * TQ) * 64) + lane;
+        if (rg == 1) {
+#pragma unroll
+            for (int qb = 0; qb < TQ; ++qb) {
+#pragma unroll
+                for (int db = 0; db < DB; ++db)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) xch[((qb * DB + db) * 4 + r) * 64] = O[qb][db][r];
+                xch[(TQ * DB * 4 + qb) * 64] = L[qb][0];
+                xch[(TQ * DB * 4 + TQ + qb) * 64] = m_run[qb];
+            }
+        }
+        phase_barrier<-1, true>();
+        if (rg == 1) return;
+#pragma unroll
+        for (int qb = 0; qb < TQ; ++qb) {
+            const float m1 = xch[(TQ * DB * 4 + TQ + qb) * 64], l1 = xch[(TQ * DB * 4 + qb) * 64];
+            const float m = fmaxf(m_run[qb], m1);
+            const float f0 = m_run[qb] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m_run[qb] - m);
+            const float f1 = m1 == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m1 - m);
+            L[qb][0] = L[qb][0] * f0 + l1 * f1;
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) O[qb][db][r] = O[qb][db][r] * f0 + xch[((qb * DB + db) * 4 + r) * 64] * f1;
+        }
     }
 
     // ---- write-out.  O[qb][db][r]: query row 16 qb + l16, column 16 db + 4 g4 + r; every row of L[qb] holds the
@@ -473,10 +578,10 @@ __global__ __launch_bounds__(1024 / TQ) void attn_fused_kernel(AttnBf16Params p)
     }
 }
 
-template <int D, int TQ, bool MASKED>
+template <int D, int TQ, bool MASKED, bool SPLIT = false>
 static int32_t launch_fused_cfg(const AttnBf16Params &k, int n_qtiles, hipStream_t s) {
     constexpr int lds = 4 * (KV_TILE * D * 2 + D * 128 + KV_TILE * 4) + 32;   // four stages + the start-over flags
-    auto kern = attn_fused_kernel<D, TQ, MASKED>;
+    auto kern = attn_fused_kernel<D, TQ, MASKED, SPLIT>;
     static std::atomic<uint64_t> lds_ready{0};
     CASCADE_HIP_TRY(ensure_dynamic_lds((const void *)kern, lds, lds_ready));
     dim3 grid((unsigned)((int64_t)k.gy * n_qtiles), 1, 1);
@@ -485,8 +590,12 @@ static int32_t launch_fused_cfg(const AttnBf16Params &k, int n_qtiles, hipStream
     return CASCADE_OK;
 }
 
-int32_t launch_attn_fused(const AttnBf16Params &k, int head_dim, int n_qtiles, bool all_visible, hipStream_t s) {
+int32_t launch_attn_fused(const AttnBf16Params &k, int head_dim, int n_qtiles, bool all_visible, bool split, hipStream_t s) {
     if (!k.fused) return CASCADE_EINVAL;
+    if (split) {                                       // 32-row query tiles, four heads per workgroup, causal
+        if (all_visible || k.hpb != 4) return CASCADE_EINVAL;
+        return head_dim == 128 ? launch_fused_cfg<128, 2, true, true>(k, n_qtiles, s) : launch_fused_cfg<64, 2, true, true>(k, n_qtiles, s);
+    }
     if (all_visible)
         return head_dim == 128 ? launch_fused_cfg<128, 2, false>(k, n_qtiles, s) : launch_fused_cfg<64, 2, false>(k, n_qtiles, s);
     return head_dim == 128 ? launch_fused_cfg<128, 2, true>(k, n_qtiles, s) : launch_fused_cfg<64, 2, true>(k, n_qtiles, s);

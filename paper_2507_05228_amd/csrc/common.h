@@ -31,7 +31,7 @@ struct CascadeTileList {
     int32_t *shard_first = nullptr;   // device: [n_shards + 1] first tile index of each shard
     int32_t *shard_first_host = nullptr;
     // positions of the tile's rows, granule values per tile (tile `index` at index * granule), rows past the
-    // tile's end hold INT_MAX; built for the 64-row list only (the key/value tiles of the attention kernels)
+    // tile's end hold 2^30; built for the 64-row list only (the key/value tiles of the attention kernels)
     int32_t *pos_padded = nullptr;
 };
 

@@ -99,7 +99,8 @@ static hipError_t build_tiles(cascade_plan *p, CascadeTileList &out, int granule
     e = to_device(&out.dev_by_pmax_desc, sorted.data(), sorted.size());
     if (e != hipSuccess) return e;
     if (granule == 64) {
-        std::vector<int32_t> padded(tiles.size() * 64, INT_MAX);
+        // (2^30: above every position the fused kernel accepts, and "limit - 2^30" cannot overflow for any limit it uses)
+        std::vector<int32_t> padded(tiles.size() * 64, 1 << 30);
         for (size_t t = 0; t < tiles.size(); ++t)
             for (int i = 0; i < tiles[t].n_rows; ++i) padded[t * 64 + i] = p->pos_packed_h[tiles[t].row_start + i];
         e = to_device(&out.pos_padded, padded.data(), padded.size());
