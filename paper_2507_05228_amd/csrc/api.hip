@@ -170,8 +170,8 @@ extern "C" int32_t cascade_lse_merge(const cascade_plan *plan, const cascade_att
 
 // ---------------------------------------------------------------------------- whole layer
 struct LayerWs {
-    size_t x, qkv, ao, h1, act, attn_ws, m, e, u, rope, total;
-    size_t attn_ws_bytes;
+    size_t x, qkv, ao, h1, act, attn_ws, m, e, u, rope, sk_partial, sk_sync, total;
+    size_t attn_ws_bytes, sk_partial_bytes;
 };
 
 static LayerWs layer_ws(const cascade_plan *plan, const cascade_layer_desc *d) {
@@ -189,6 +189,13 @@ static LayerWs layer_ws(const cascade_plan *plan, const cascade_layer_desc *d) {
     w.attn_ws_bytes = d->dtype == CASCADE_BF16 ? attn_bf16_workspace_bytes(plan, plan->batch, d->n_kv_heads, d->head_dim) : 0;
     w.attn_ws = take(w.attn_ws_bytes);
     w.rope = take(d->rope && d->dtype == CASCADE_BF16 ? T * (size_t)d->head_dim * 4 : 0);   // cos | sin per row
+    // o projection and FFN down as split reductions, where their shape asks for it (same output shape, two K)
+    w.sk_partial_bytes = 0;
+    if (d->dtype == CASCADE_BF16 && T <= (size_t)INT32_MAX)
+        w.sk_partial_bytes = std::max(gemm_bf16_splitk_bytes((int32_t)T, d->d_model, d->n_heads * d->head_dim),
+                                      gemm_bf16_splitk_bytes((int32_t)T, d->d_model, d->d_ff));
+    w.sk_partial = take(w.sk_partial_bytes);
+    w.sk_sync = take(w.sk_partial_bytes ? GEMM_SPLITK_SYNC_WORDS * 4 : 0);
     if (d->attn_mode == CASCADE_ATTN_MATERIALISED) {
         const size_t me = (size_t)plan->batch * d->n_heads * kv_plan(plan)->n_shards * plan->seq_len * 4;
         w.m = take(me);
@@ -352,8 +359,21 @@ static int32_t layer_forward_impl(const cascade_plan *plan, const cascade_layer_
     g.rope_cols = (H + Hkv) * hd; g.rope_head_dim = hd;
     const bool rope_fused = d->rope && !post && d->dtype == CASCADE_BF16 && plan->max_abs_pos < (1 << 24) &&
                             gemm_bf16_rope_fusable(g);
+    // The split-reduction GEMMs count on flag words that a norm launch of this call has cleared before them.
+    bool sk_ready = false;
+    auto clear_sk_sync = [&](NormArgs &n) {
+        if (!ws.sk_partial_bytes) return;
+        n.zero_words = (uint32_t *)(base + ws.sk_sync); n.n_zero_words = GEMM_SPLITK_SYNC_WORDS;
+        sk_ready = true;
+    };
+    auto offer_splitk = [&](GemmArgs &ga) {
+        if (!sk_ready) return;
+        ga.sk_partial = (float *)(base + ws.sk_partial); ga.sk_partial_bytes = ws.sk_partial_bytes;
+        ga.sk_sync = (uint32_t *)(base + ws.sk_sync);
+    };
     if (!post) {
         NormArgs n1 = {d->dtype, T, D, d->norm_kind, d->norm_eps, h_in, w->norm1_g, w->norm1_b, x, in_map, packed};
+        clear_sk_sync(n1);
         if (rope_fused) {
             n1.rope_table = (float *)(base + ws.rope); n1.rope_pos = plan->pos_packed_d; n1.rope_seq_len = N;
             n1.rope_head_dim = hd; n1.rope_theta = d->rope_theta;
@@ -408,6 +428,7 @@ static int32_t layer_forward_impl(const cascade_plan *plan, const cascade_layer_
     g.ldx = H * hd; g.ldy = D; g.ldres = D;
     g.xmap = g.ymap = packed; g.rmap = in_map;
     g.epilogue = CASCADE_EPI_RESIDUAL | (w->bo ? CASCADE_EPI_BIAS : 0);
+    offer_splitk(g);
     if ((st = run_gemm(g, s)) != CASCADE_OK) return st;
     if ((st = mark()) != CASCADE_OK) return st;                                   // 6: o projection + residual
 
@@ -415,6 +436,7 @@ static int32_t layer_forward_impl(const cascade_plan *plan, const cascade_layer_
     //    scattered back to the caller's row order
     NormArgs n2 = {d->dtype, T, D, d->norm_kind, d->norm_eps, post ? x : h1, post ? w->norm1_g : w->norm2_g,
                    post ? w->norm1_b : w->norm2_b, post ? h1 : x, packed, packed};
+    clear_sk_sync(n2);
     if ((st = launch_norm(n2, s)) != CASCADE_OK) return st;
     if ((st = mark()) != CASCADE_OK) return st;                                   // 7: norm before the MLP
     g = {};
@@ -437,6 +459,7 @@ static int32_t layer_forward_impl(const cascade_plan *plan, const cascade_layer_
     g.ldx = f; g.ldy = D; g.ldres = D;
     g.xmap = g.rmap = packed; g.ymap = post ? packed : out_map;
     g.epilogue = CASCADE_EPI_RESIDUAL | (w->b_down ? CASCADE_EPI_BIAS : 0);
+    offer_splitk(g);
     if ((st = run_gemm(g, s)) != CASCADE_OK) return st;
     if (post) {                                                                   // closing norm, with the scatter
         NormArgs n3 = {d->dtype, T, D, d->norm_kind, d->norm_eps, x, w->norm2_g, w->norm2_b, h_out, packed, out_map};

@@ -114,10 +114,22 @@ struct GemmArgs {
     // are rotated (half-split pairs inside heads of rope_head_dim columns).  nullptr: no rotation.
     const float *rope_table;
     int32_t rope_cols, rope_head_dim;
+    // Scratch for a reduction split over two workgroups per tile (bf16, see gemm_bf16_splitk_bytes): fp32 partial
+    // tiles, and the per-tile ticket and flag words, GEMM_SPLITK_SYNC_WORDS of them, which must have been zero when
+    // the first launch that uses them started (launches that share them run one after the other).  nullptr: the
+    // launch does not split.
+    float *sk_partial;
+    size_t sk_partial_bytes;
+    uint32_t *sk_sync;
 };
+constexpr int GEMM_SPLITK_MAX_TILES = 256;
+constexpr int GEMM_SPLITK_SYNC_WORDS = 2 * GEMM_SPLITK_MAX_TILES;
 
 int32_t launch_gemm_bf16(const GemmArgs &a, hipStream_t s);
 bool gemm_bf16_rope_fusable(const GemmArgs &a);
+// Bytes of GemmArgs::sk_partial that a launch of this shape would use for a split reduction; 0 when it would not
+// split (the shape fills the CUs without, or the split kernel does not take it).
+size_t gemm_bf16_splitk_bytes(int32_t M, int32_t N, int32_t K);
 int32_t launch_gemm_f32(const GemmArgs &a, hipStream_t s);
 
 struct NormArgs {
@@ -132,6 +144,9 @@ struct NormArgs {
     const int32_t *rope_pos;
     int32_t rope_seq_len, rope_head_dim;
     float rope_theta;
+    // Optional: n_zero_words words cleared by the launch (flags of the split-reduction GEMMs later in the stream)
+    uint32_t *zero_words;
+    int32_t n_zero_words;
 };
 int32_t launch_norm(const NormArgs &a, hipStream_t s);
 // k, v rows of a packed [T, ld] activation (columns k_col0 .. and v_col0 .., H_kv heads of d) -> cache slabs

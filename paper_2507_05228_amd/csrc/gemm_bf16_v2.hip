@@ -52,6 +52,10 @@ struct Gemm2Params {
     // output columns below rope_cols are rotated; rope_lh = log2(head_dim / 2)
     const float *rope_table;
     int32_t rope_cols, rope_lh;
+    // split reduction (SPLITK kernels): fp32 partial tiles [tile][accumulator block][thread] and per tile a ticket
+    // word and a flag word
+    float *sk_partial;
+    uint32_t *sk_sync;
 };
 
 typedef __attribute__((address_space(3))) void lds_void;
@@ -72,6 +76,34 @@ __device__ __forceinline__ float silu_fast(float x) {
     // x * 1/(1 + 2^(-x log2 e)); hardware reciprocal (1 ulp), output is rounded to bf16 anyway
     return x * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * x));
 }
+
+// The residual values a lane adds in gemm_epilogue, all row blocks of its wavefront tile: [row block][row group
+// of 4][4-column chunk].
+template <int TM, int WTN, bool SWIGLU>
+struct ResidualAhead {
+    static constexpr int OW = SWIGLU ? WTN / 2 : WTN;
+    static constexpr int NCH = (OW + 63) / 64;
+    bf16x4 r[TM][4][NCH];
+    __device__ __forceinline__ void load(const Gemm2Params &p, int lane, int m0, int wm0, int wn0, int nloc0, int seg,
+                                         int seg_rows) {
+        const int m4 = (lane & 15) * 4, rsel = lane >> 4;
+        const int wcol0 = SWIGLU ? nloc0 + (wn0 / WTN) * OW : nloc0 + wn0;
+        const int gcol0 = p.seg_col0[seg];
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const int gm = m0 + wm0 + 16 * i + 4 * t + rsel;
+                const bf16_t *rrow = p.residual + map_row(p.rmap, p.seq_len, gm < p.M ? gm : 0) * p.ldres + gcol0;
+#pragma unroll
+                for (int cc = 0; cc < NCH; ++cc) {
+                    const int c = wcol0 + 64 * cc + m4;
+                    r[i][t][cc] = bf16x4{0, 0, 0, 0};
+                    if (gm < p.M && c + 4 <= seg_rows && 64 * cc + m4 < OW) r[i][t][cc] = *(const bf16x4 *)(rrow + c);
+                }
+            }
+    }
+};
 
 template <int TM, int TN, int WTN, bool SWIGLU>
 __device__ __forceinline__ void gemm_epilogue(const Gemm2Params &p, f32x4 (&acc)[TM][TN], unsigned char *smem,
@@ -100,26 +132,12 @@ __device__ __forceinline__ void gemm_epilogue(const Gemm2Params &p, f32x4 (&acc)
                 if (c + x < seg_rows) bias_v[cc][x] = (float)bias[c + x];
     }
     const bool act = flags & (CASCADE_EPI_GELU_ERF | CASCADE_EPI_GELU_TANH);
-    // Residual of every row block requested up front (when the registers allow): one memory latency for the
-    // whole epilogue instead of one per row block.
+    // Residual of every row block requested up front (when the registers allow, if the kernel has not done so
+    // ahead of its main loop): one memory latency for the whole epilogue instead of one per row block.
     constexpr bool RES_AHEAD = TM * 4 * NCH <= 32;
-    bf16x4 rres[RES_AHEAD ? TM : 1][4][NCH];
+    ResidualAhead<RES_AHEAD ? TM : 1, WTN, SWIGLU> res;
     const bool res_ahead = RES_AHEAD && (flags & CASCADE_EPI_RESIDUAL);
-    if (res_ahead) {
-#pragma unroll
-        for (int i = 0; i < (RES_AHEAD ? TM : 1); ++i)
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                const int gm = m0 + wm0 + 16 * i + 4 * t + rsel;
-                const bf16_t *rrow = p.residual + map_row(p.rmap, p.seq_len, gm < p.M ? gm : 0) * p.ldres + gcol0;
-#pragma unroll
-                for (int cc = 0; cc < NCH; ++cc) {
-                    const int c = wcol0 + 64 * cc + m4;
-                    rres[i][t][cc] = bf16x4{0, 0, 0, 0};
-                    if (gm < p.M && c + 4 <= seg_rows && 64 * cc + m4 < OW) rres[i][t][cc] = *(const bf16x4 *)(rrow + c);
-                }
-            }
-    }
+    if (res_ahead) res.load(p, lane, m0, wm0, wn0, nloc0, seg, seg_rows);
     // Two copies of the unrolled loops, chosen once: without the (long) GELU code the plain one stays small
     // and contiguous in the instruction cache.
     auto blocks = [&](auto act_tag) {
@@ -158,8 +176,8 @@ __device__ __forceinline__ void gemm_epilogue(const Gemm2Params &p, f32x4 (&acc)
                         for (int x = 0; x < 4; ++x) v[x] = apply_act_bf16(v[x], flags);
                     }
                     if (c + 4 <= seg_rows) {
-                        if (RES_AHEAD && res_ahead) {
-                            const bf16x4 rv = rres[RES_AHEAD ? i : 0][t][cc];
+                        if (res_ahead) {
+                            const bf16x4 rv = res.r[RES_AHEAD ? i : 0][t][cc];
 #pragma unroll
                             for (int x = 0; x < 4; ++x) v[x] += (float)rv[x];
                         } else if (rrow) {
@@ -261,20 +279,37 @@ __device__ __forceinline__ void gemm_epilogue_tile_rope(const Gemm2Params &p, f3
     __syncthreads();
     constexpr int CPRO = BN / 8;                           // 16-byte pieces per tile row
     const bool wide = ((p.ldy | gcol0) % 8 == 0) && ((uintptr_t)p.Y % 16 == 0);
-    for (int q = tid; q < BM * CPRO; q += NTHREADS) {
-        const int row = q / CPRO, piece = q % CPRO;
-        const int hs = piece >= CPRO / 2;                  // second halves
-        const int pp = pair0 + (piece - hs * (CPRO / 2)) * 8;
-        const int gm = m0 + row;
-        if (gm >= p.M || pp >= n_pairs) continue;          // n_pairs is a multiple of half, half of 8
-        const int c = ((pp >> lh) << (lh + 1)) + (pp & (half - 1)) + (hs << lh);
-        const bf16x8 v = *(const bf16x8 *)(smem + row * PITCH + piece * 16);
-        bf16_t *y = p.Y + map_row(p.ymap, p.seq_len, gm) * p.ldy + gcol0 + c;
-        if (wide) {
-            *(bf16x8 *)y = v;
-        } else {
-            *(bf16x4 *)y = bf16x4{v[0], v[1], v[2], v[3]};
-            *(bf16x4 *)(y + 4) = bf16x4{v[4], v[5], v[6], v[7]};
+    // Pieces in groups: all LDS reads (and row-map lookups) of a group are in flight before its first store, instead
+    // of one LDS latency per piece (one wavefront per SIMD: nothing else would cover it).
+    static_assert((BM * CPRO) % NTHREADS == 0, "every thread stores the same number of pieces");
+    constexpr int NIT = BM * CPRO / NTHREADS, GRP = NIT % 8 == 0 ? 8 : NIT % 7 == 0 ? 7 : NIT % 6 == 0 ? 6 : NIT % 5 == 0 ? 5 : 4;
+    static_assert(NIT % GRP == 0, "pieces held in registers per group");
+#pragma unroll
+    for (int g0 = 0; g0 < NIT; g0 += GRP) {
+        bf16x8 v[GRP];
+        bf16_t *y[GRP];
+#pragma unroll
+        for (int g = 0; g < GRP; ++g) {
+            const int q = tid + (g0 + g) * NTHREADS;
+            const int row = q / CPRO, piece = q % CPRO;
+            const int hs = piece >= CPRO / 2;              // second halves
+            const int pp = pair0 + (piece - hs * (CPRO / 2)) * 8;
+            const int gm = m0 + row;
+            y[g] = nullptr;
+            if (gm >= p.M || pp >= n_pairs) continue;      // n_pairs is a multiple of half, half of 8
+            const int c = ((pp >> lh) << (lh + 1)) + (pp & (half - 1)) + (hs << lh);
+            v[g] = *(const bf16x8 *)(smem + row * PITCH + piece * 16);
+            y[g] = p.Y + map_row(p.ymap, p.seq_len, gm) * p.ldy + gcol0 + c;
+        }
+#pragma unroll
+        for (int g = 0; g < GRP; ++g) {
+            if (!y[g]) continue;
+            if (wide) {
+                *(bf16x8 *)y[g] = v[g];
+            } else {
+                *(bf16x4 *)y[g] = bf16x4{v[g][0], v[g][1], v[g][2], v[g][3]};
+                *(bf16x4 *)(y[g] + 4) = bf16x4{v[g][4], v[g][5], v[g][6], v[g][7]};
+            }
         }
     }
 }
@@ -368,23 +403,41 @@ __device__ __forceinline__ void gemm_epilogue_tile(const Gemm2Params &p, f32x4 (
     static_assert(BN_OUT % 8 == 0, "whole pieces");
     // 16-byte stores need the rows to start on 16-byte boundaries; otherwise two 8-byte halves
     const bool wide = ((p.ldy | gcol0) % 8 == 0) && ((uintptr_t)p.Y % 16 == 0);
-    for (int q = tid; q < BM * CPRO; q += NTHREADS) {
-        const int row = q / CPRO, c = nloc0 + (q % CPRO) * 8;
-        const int gm = m0 + row;
-        if (gm >= p.M || c >= seg_rows) continue;
-        const bf16x8 v = *(const bf16x8 *)(smem + row * PITCH + (q % CPRO) * 16);
-        bf16_t *y = p.Y + map_row(p.ymap, p.seq_len, gm) * p.ldy + gcol0 + c;
-        if (c + 8 <= seg_rows) {
-            if (wide) {
-                *(bf16x8 *)y = v;
-            } else {
-                *(bf16x4 *)y = bf16x4{v[0], v[1], v[2], v[3]};
-                *(bf16x4 *)(y + 4) = bf16x4{v[4], v[5], v[6], v[7]};
-            }
-        } else {
+    // Pieces in groups: all LDS reads (and row-map lookups) of a group are in flight before its first store, instead
+    // of one LDS latency per piece (one wavefront per SIMD: nothing else would cover it).
+    static_assert((BM * CPRO) % NTHREADS == 0, "every thread stores the same number of pieces");
+    constexpr int NIT = BM * CPRO / NTHREADS, GRP = NIT % 8 == 0 ? 8 : NIT % 7 == 0 ? 7 : NIT % 6 == 0 ? 6 : NIT % 5 == 0 ? 5 : 4;
+    static_assert(NIT % GRP == 0, "pieces held in registers per group");
 #pragma unroll
-            for (int x = 0; x < 8; ++x)
-                if (c + x < seg_rows) y[x] = v[x];
+    for (int g0 = 0; g0 < NIT; g0 += GRP) {
+        bf16x8 v[GRP];
+        bf16_t *y[GRP];
+#pragma unroll
+        for (int g = 0; g < GRP; ++g) {
+            const int q = tid + (g0 + g) * NTHREADS;
+            const int row = q / CPRO, c = nloc0 + (q % CPRO) * 8;
+            const int gm = m0 + row;
+            y[g] = nullptr;
+            if (gm >= p.M || c >= seg_rows) continue;
+            v[g] = *(const bf16x8 *)(smem + row * PITCH + (q % CPRO) * 16);
+            y[g] = p.Y + map_row(p.ymap, p.seq_len, gm) * p.ldy + gcol0 + c;
+        }
+#pragma unroll
+        for (int g = 0; g < GRP; ++g) {
+            if (!y[g]) continue;
+            const int c = nloc0 + ((tid + (g0 + g) * NTHREADS) % CPRO) * 8;
+            if (c + 8 <= seg_rows) {
+                if (wide) {
+                    *(bf16x8 *)y[g] = v[g];
+                } else {
+                    *(bf16x4 *)y[g] = bf16x4{v[g][0], v[g][1], v[g][2], v[g][3]};
+                    *(bf16x4 *)(y[g] + 4) = bf16x4{v[g][4], v[g][5], v[g][6], v[g][7]};
+                }
+            } else {
+#pragma unroll
+                for (int x = 0; x < 8; ++x)
+                    if (c + x < seg_rows) y[g][x] = v[g][x];
+            }
         }
     }
 }
@@ -408,9 +461,69 @@ __device__ __forceinline__ void mfma_tied(f32x4 &c, const bf16x8 &a, const bf16x
 // ones leave the matrix pipeline.
 __device__ __forceinline__ void mfma_drain() { asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" ::: "memory"); }
 
-template <int BM, int BN, int WM, int WN, int BK, int NST, bool SWIGLU, bool ROPE = false>
+// The lane number from the execution mask, as assembly: the compiler can neither tell that it is threadIdx.x % 64
+// nor merge two of these, so nothing is kept in a register between them.
+__device__ __forceinline__ int lane_id_again() {
+    int l;
+    asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(l));
+    return l;
+}
+
+// Reduction split over two workgroups per tile (a launch whose tiles would fill half of the CUs).  Each computes
+// one half of K into its accumulators.  Then it takes a ticket from the tile's counter: the holder of the even
+// ticket (the first to finish) writes its accumulators to the tile's slot of the scratch as they lie in its
+// registers, publishes them by setting the tile's flag to the use count of the slot, and is done; the holder of
+// the odd ticket waits for that flag, adds the stored accumulators to its own and returns true: it runs the
+// epilogue.  The workgroup that is waited for took its ticket earlier, so it is running, has its main loop
+// behind it and waits for nothing itself: the wait ends whatever the order in which workgroups are placed on the
+// CUs (the spin count only guards against a partner that died).  Ticket and flag count up over the launches that
+// share the words (which run one after the other), so nothing has to be reset between them.
+template <int TM, int TN, int NTHREADS>
+__device__ __forceinline__ bool splitk_combine(const Gemm2Params &p, f32x4 (&acc)[TM][TN], int tile, int tid,
+                                               unsigned char *smem) {
+    uint32_t *sync = p.sk_sync + 2 * tile;
+    f32x4 *part = (f32x4 *)p.sk_partial + (size_t)tile * (TM * TN * NTHREADS) + tid;
+    volatile uint32_t *sh = (volatile uint32_t *)smem;
+    if (tid == 0) sh[0] = __hip_atomic_fetch_add(&sync[0], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    const uint32_t ticket = sh[0];
+    const uint32_t use = (ticket >> 1) + 1;
+    // Cache maintenance across the XCDs' L2s is expensive (a release writes back, an acquire invalidates a whole
+    // L2), so exactly one wavefront of each workgroup does it: the workgroup barrier orders the other wavefronts'
+    // stores before thread 0's release and their loads after thread 0's acquire.
+    if ((ticket & 1u) == 0u) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) part[(i * TN + j) * NTHREADS] = acc_load(acc[i][j]);
+        __syncthreads();
+        if (tid == 0) __hip_atomic_store(&sync[1], use, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        return false;
+    }
+    if (tid == 0) {
+        int spins = 0;
+        while (__hip_atomic_load(&sync[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != use && ++spins < (1 << 22))
+            __builtin_amdgcn_s_sleep(8);
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        f32x4 pv[TN];
+#pragma unroll
+        for (int j = 0; j < TN; ++j) pv[j] = __builtin_nontemporal_load(part + (i * TN + j) * NTHREADS);
+        __builtin_amdgcn_sched_barrier(0);                 // one row block's loads at a time: 8 x 4 registers
+#pragma unroll
+        for (int j = 0; j < TN; ++j) acc[i][j] = acc_load(acc[i][j]) + pv[j];
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    return true;
+}
+
+template <int BM, int BN, int WM, int WN, int BK, int NST, bool SWIGLU, bool ROPE = false, bool SPLITK = false>
 __global__ __launch_bounds__(WM *WN * 64) void gemm2_kernel(Gemm2Params p) {
     static_assert(!ROPE || (!SWIGLU && WM * WN == 4), "rotary epilogue: plain GEMM, one wavefront per SIMD");
+    static_assert(!SPLITK || (!SWIGLU && !ROPE && WM * WN == 4), "split reduction: plain GEMM, one wavefront per SIMD");
     constexpr int NW = WM * WN;
     constexpr int WTM = BM / WM, WTN = BN / WN;
     constexpr int TM = WTM / 16, TN = WTN / 16;
@@ -438,10 +551,21 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm2_kernel(Gemm2Params p) {
     const int wm0 = (wave / WN) * WTM, wn0 = (wave % WN) * WTN;
 
     // workgroup -> tile: contiguous run of tiles (m fastest) per XCD
+    // One wavefront per SIMD: the workgroup is persistent.  The launch has one workgroup per CU (a multiple of 8)
+    // and workgroup w takes the tiles that workgroups w, w + gridDim.x, ... of a launch with one workgroup per
+    // tile would take: nothing waits for a workgroup's last stores to be acknowledged, for its registers and LDS
+    // to be handed on, or for a new workgroup to set itself up; the stores of a tile drain while the first
+    // tile loads of the next are in flight.
+    constexpr bool PERSISTENT = SOLO && !SPLITK;
     const int total = p.tiles_m * p.tiles_n;
-    int tile;
-    {
-        const int pid = blockIdx.x, xcd = pid & 7, idx = pid >> 3;
+    for (int pid = blockIdx.x;; pid += gridDim.x) {
+    int tile, khalf = 0;
+    if constexpr (SPLITK) {                                        // total % 8 == 0; the two halves of a tile are
+        const int xcd = pid & 7, idx = pid >> 3;                   // neighbours in the dispatch order of one XCD
+        tile = xcd * (total >> 3) + (idx >> 1);
+        khalf = idx & 1;
+    } else {
+        const int xcd = pid & 7, idx = pid >> 3;
         const int base = total >> 3, rem = total & 7;
         tile = xcd * base + min(xcd, rem) + idx;
     }
@@ -495,6 +619,14 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm2_kernel(Gemm2Params p) {
     auto b_stage = [&](int kt) {
         return SOLO ? smem + NSTA * A_BYTES + (kt % NSTB) * B_BYTES : smem + (kt % NST) * STAGE_BYTES + A_BYTES;
     };
+    const int KT = SPLITK ? K / BK / 2 : K / BK;                   // k-tiles of this workgroup
+    if constexpr (SPLITK) {                                        // the second half starts KT k-tiles in (offsets of
+        const uint32_t koff = (uint32_t)(khalf * KT) * ROWB;       // rows outside stay outside: K bytes < 2^31)
+#pragma unroll
+        for (int i = 0; i < A_INSTR; ++i) a_off[i] += koff;
+#pragma unroll
+        for (int i = 0; i < B_INSTR; ++i) b_off[i] += koff;
+    }
     auto issue_load = [&](int kt, int stage, int x) {              // instruction x of LPT (x known after unrolling)
         const uint32_t kb = (uint32_t)kt * ROWB;
         (void)stage;                                               // = kt % NST for the 8-wavefront layout
@@ -524,7 +656,6 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm2_kernel(Gemm2Params p) {
     // operand fetch: lane -> tile row lane%16 of a 16-row block, chunk 4 ks + lane/16, swizzled
     const int frow = lane & 15, fch = lane >> 4, fsw = swz(lane & 15);
     const int a_lane = (wm0 + frow) * ROWB, b_lane = A_BYTES + (wn0 + frow) * ROWB;
-    const int KT = K / BK;
     constexpr int KS = BK / 32;
     static_assert(KS == 2, "the operand pipeline below alternates two register sets over the two k-steps of a tile");
     constexpr int NSETS = SOLO || 4 * TM * TN + 8 * (TM + TN) <= 216 ? 2 : 1;
@@ -650,15 +781,28 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm2_kernel(Gemm2Params p) {
 
     if constexpr (SOLO) {
         __syncthreads();                                   // everyone is done with the tile buffers
+        // The thread index computed again (the lane number from the execution mask, so that the compiler cannot
+        // tell it is tid): otherwise everything the epilogue derives from it is computed once, ahead of the tile
+        // loop, and kept in registers across the main loop, which has none to spare.
+        int tid_e = wave * 64 + lane_id_again();
+        if constexpr (SPLITK) {
+            const int tile_sk = ((int)blockIdx.x & 7) * (total >> 3) + ((int)blockIdx.x >> 4);
+            if (!splitk_combine<TM, TN, NW * 64>(p, acc, tile_sk, tid_e, smem)) return;
+            __syncthreads();                               // the ticket has been read: the epilogue may stage
+            tid_e = wave * 64 + lane_id_again();
+        }
         if constexpr (ROPE)
-            gemm_epilogue_tile_rope<BM, NW * 64, TM, TN, WTN, BN>(p, acc, smem, tid, m0, wm0, wn0, nloc0 >> 1, seg, seg_rows);
+            gemm_epilogue_tile_rope<BM, NW * 64, TM, TN, WTN, BN>(p, acc, smem, tid_e, m0, wm0, wn0, nloc0 >> 1, seg, seg_rows);
         else
             // only the 192-column tile takes GELU launches: with more accumulator blocks the compiler no longer
             // unrolls the (long) activation code and would index the accumulators through memory
-            gemm_epilogue_tile<BM, NW * 64, TM, TN, WTN, SWIGLU, BN_OUT, TM * TN <= 48>(p, acc, smem, tid, m0, wm0, wn0, nloc0, seg, seg_rows);
+            gemm_epilogue_tile<BM, NW * 64, TM, TN, WTN, SWIGLU, BN_OUT, TM * TN <= 48>(p, acc, smem, tid_e, m0, wm0, wn0, nloc0, seg, seg_rows);
     } else {
         __syncthreads();                                   // everyone is done with the tile buffers
         gemm_epilogue<TM, TN, WTN, SWIGLU>(p, acc, smem, wave, lane, m0, wm0, wn0, nloc0, seg, seg_rows);
+    }
+    if (!PERSISTENT || pid + (int)gridDim.x >= total) break;
+    __syncthreads();                                       // the staged tile has been read: the next tile may load
     }
 }
 
@@ -833,9 +977,18 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm3_kernel(Gemm2Params p) {
     gemm_epilogue<TM, TN, WTN, SWIGLU>(p, acc, smem, wave, lane, m0, wm0, wn0, nloc0, seg, seg_rows);
 }
 
-template <int BM, int BN, int WM, int WN, int BK, int NST, bool SWIGLU, bool PINGPONG = false, bool ROPE = false>
+static int cu_count() {                                   // of the current device
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+        n = 256;
+    return n;
+}
+
+template <int BM, int BN, int WM, int WN, int BK, int NST, bool SWIGLU, bool PINGPONG = false, bool ROPE = false,
+          bool SPLITK = false>
 static int32_t launch_cfg2(const GemmArgs &a, hipStream_t s) {
     Gemm2Params p;
+    p.sk_partial = a.sk_partial; p.sk_sync = a.sk_sync;
     p.rope_table = a.rope_table; p.rope_cols = a.rope_cols; p.rope_lh = 0;
     if (ROPE) {
         while ((2 << p.rope_lh) < a.rope_head_dim) ++p.rope_lh;
@@ -875,22 +1028,25 @@ static int32_t launch_cfg2(const GemmArgs &a, hipStream_t s) {
     static_assert(lds <= 160 * 1024, "tile buffers exceed the LDS of a CU");
     const void *kern;
     if constexpr (PINGPONG) kern = (const void *)gemm3_kernel<BM, BN, WM, WN, BK, NST, SWIGLU>;
-    else kern = (const void *)gemm2_kernel<BM, BN, WM, WN, BK, NST, SWIGLU, ROPE>;
+    else kern = (const void *)gemm2_kernel<BM, BN, WM, WN, BK, NST, SWIGLU, ROPE, SPLITK>;
     static std::atomic<uint64_t> lds_ready{0};                 // one per instantiation of this launcher
     CASCADE_HIP_TRY(ensure_dynamic_lds(kern, (int)lds, lds_ready));
     int64_t total = (int64_t)p.tiles_m * p.tiles_n;
     if (total > INT32_MAX) return CASCADE_EUNSUPPORTED;
+    if (SPLITK) {                                              // what the kernel's tile mapping and scratch indexing assume
+        if (total % 8 || total > GEMM_SPLITK_MAX_TILES || a.K % (2 * BK) || a.K / BK / 2 < 2) return CASCADE_EINVAL;
+        if (!a.sk_partial || !a.sk_sync || a.sk_partial_bytes < (size_t)total * BM * BN * 4) return CASCADE_EWORKSPACE;
+        if (((uintptr_t)a.sk_partial % 16) || ((uintptr_t)a.sk_sync % 4)) return CASCADE_EINVAL;
+    }
     void *args[] = {&p};
-    CASCADE_HIP_TRY(hipLaunchKernel(kern, dim3((unsigned)total), dim3(WM * WN * 64), args, lds, s));
+    unsigned grid = (unsigned)(SPLITK ? 2 * total : total);
+    if (!PINGPONG && !SPLITK && WM * WN == 4) {                 // persistent workgroups, one per CU, 8 | grid
+        const int64_t per_round = cu_count() / 8 * 8;
+        if (per_round >= 8 && total > per_round) grid = (unsigned)per_round;
+    }
+    CASCADE_HIP_TRY(hipLaunchKernel(kern, dim3(grid), dim3(WM * WN * 64), args, lds, s));
     CASCADE_HIP_TRY(hipGetLastError());
     return CASCADE_OK;
-}
-
-static int cu_count() {                                   // of the current device
-    int dev = 0, n = 0;
-    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
-        n = 256;
-    return n;
 }
 
 static bool v2_eligible(const GemmArgs &a) {
@@ -917,6 +1073,20 @@ bool gemm_bf16_rope_fusable(const GemmArgs &a) {
         col0 = std::max(col0, a.seg_end[i]);
     }
     return true;
+}
+
+// Split reduction: 256 x 256 tiles would fill between a quarter and a half of the CUs (so two workgroups per
+// tile fill them in one round), their number is a multiple of the 8 XCDs, and K is long enough to pay for the
+// exchange (one segment of plain columns assumed: N is the output width).  Measured on MI355X at 2048 x 4096
+// outputs against the 256 x 128 kernel on the same 256 CUs: the main loop gains 6 us at K = 4096 and 35-40 us at
+// K = 14336, the exchange (256 KB written and read per tile, one L2 write-back and one invalidation per
+// workgroup, the epilogue on half of the CUs) costs 15-20 us: 88 against 77 us and 199 against 205 us.
+constexpr int GEMM_SPLITK_MIN_K = 8192;
+size_t gemm_bf16_splitk_bytes(int32_t M, int32_t N, int32_t K) {
+    if (M <= 0 || N <= 0 || K % 128 != 0 || K < GEMM_SPLITK_MIN_K) return 0;
+    const int64_t tiles = (int64_t)((M + 255) / 256) * ((N + 255) / 256), cus = cu_count();
+    if (tiles % 8 || tiles > GEMM_SPLITK_MAX_TILES || 2 * tiles > cus || 4 * tiles <= cus) return 0;
+    return (size_t)tiles * 256 * 256 * 4;
 }
 
 // Returns CASCADE_EUNSUPPORTED when the shape is not eligible (the caller then uses the general kernel).
@@ -950,6 +1120,13 @@ int32_t launch_gemm_bf16_v2(const GemmArgs &a, hipStream_t s) {
     if (swiglu) {
         if (c224 < c256) return launch_cfg2<256, 224, 4, 1, 64, 2, true, false>(a, s);
         return launch_cfg2<256, 256, 2, 2, 64, 2, true, false>(a, s);
+    }
+    {   // single-round launch of 256 x 128 tiles -> the same number of workgroups on 256 x 256 tiles, half of K each
+        const bool gelu = a.epilogue & (CASCADE_EPI_GELU_ERF | CASCADE_EPI_GELU_TANH);
+        const bool one_seg = a.seg_end[0] == a.N && a.seg_end[1] == a.N && a.seg_end[2] == a.N;
+        const size_t need = (a.sk_partial && a.sk_sync && one_seg && !gelu) ? gemm_bf16_splitk_bytes(a.M, a.N, a.K) : 0;
+        if (need && a.sk_partial_bytes >= need && (uintptr_t)a.sk_partial % 16 == 0)
+            return launch_cfg2<256, 256, 2, 2, 64, 2, false, false, false, true>(a, s);
     }
     // the 256x128 kernel does ~15 % fewer flops per cycle than the wide ones: it has to be that much cheaper
     if (std::min(c192, std::min(c224, c256)) * 20 <= c128 * 23) {

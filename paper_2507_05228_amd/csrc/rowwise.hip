@@ -35,6 +35,16 @@ struct RopeTableOut {
     int32_t seq_len, head_dim;
     float theta;
 };
+// Second by-product: a few words cleared by the first workgroup (the flags of the split-reduction shard GEMMs that
+// follow in the stream; a fill of its own would cost a launch, and a memset cannot be captured in a graph).
+struct ZeroWords {
+    uint32_t *words;
+    int32_t n;
+};
+__device__ __forceinline__ void clear_words(const ZeroWords &z) {
+    if (z.words && blockIdx.x == 0)
+        for (int i = threadIdx.x; i < z.n; i += blockDim.x) z.words[i] = 0u;
+}
 __device__ __forceinline__ void write_rope_row(const RopeTableOut &t, int r) {
     const int half = t.head_dim >> 1;
     const float pos = (float)t.pos[r % t.seq_len];
@@ -53,10 +63,11 @@ template <typename T>
 __global__ __launch_bounds__(256) void norm_kernel(const T *__restrict__ x, const T *__restrict__ gain,
                                                    const T *__restrict__ bias, T *__restrict__ y, int D, int kind,
                                                    float eps, const int32_t *xmap, const int32_t *ymap, int seq_len,
-                                                   RopeTableOut rope) {
+                                                   RopeTableOut rope, ZeroWords zero) {
     extern __shared__ float row[];
     __shared__ float red[4];
     const int r = blockIdx.x;
+    clear_words(zero);
     if (rope.table) write_rope_row(rope, r);
     const T *xr = x + map_row(xmap, seq_len, r) * (int64_t)D;
     float s = 0.f;
@@ -88,11 +99,12 @@ template <typename T, int CH>
 __global__ __launch_bounds__(256) void norm_vec_kernel(const T *__restrict__ x, const T *__restrict__ gain,
                                                        const T *__restrict__ bias, T *__restrict__ y, int D, int kind,
                                                        float eps, const int32_t *xmap, const int32_t *ymap, int seq_len,
-                                                       RopeTableOut rope) {
+                                                       RopeTableOut rope, ZeroWords zero) {
     constexpr int VEC = 16 / sizeof(T);
     typedef T vecT __attribute__((ext_vector_type(VEC)));
     __shared__ float red[4];
     const int r = blockIdx.x;
+    clear_words(zero);
     if (rope.table) write_rope_row(rope, r);
     const T *xr = x + map_row(xmap, seq_len, r) * (int64_t)D;
     const int nvec = D / VEC;
@@ -145,10 +157,11 @@ static int32_t launch_norm_t(const NormArgs &a, hipStream_t s) {
     const bool aligned = a.D % VEC == 0 && ((uintptr_t)a.x | (uintptr_t)a.y | (uintptr_t)a.gain | (uintptr_t)a.bias) % 16 == 0;
     const int nvec = a.D / VEC;
     const RopeTableOut rope = {a.rope_table, a.rope_pos, a.rope_seq_len, a.rope_head_dim, a.rope_theta};
+    const ZeroWords zero = {a.zero_words, a.n_zero_words};
 #define NORM_VEC(CH)                                                                                             \
     hipLaunchKernelGGL((norm_vec_kernel<T, CH>), dim3(a.rows), dim3(256), 0, s, (const T *)a.x, (const T *)a.gain, \
                        (const T *)a.bias, (T *)a.y, a.D, a.kind, a.eps, a.xmap.map, a.ymap.map,                 \
-                       a.xmap.map ? a.xmap.seq_len : a.ymap.seq_len, rope)
+                       a.xmap.map ? a.xmap.seq_len : a.ymap.seq_len, rope, zero)
     if (aligned && nvec <= 256) NORM_VEC(1);
     else if (aligned && nvec <= 512) NORM_VEC(2);
     else if (aligned && nvec <= 1024) NORM_VEC(4);
@@ -157,7 +170,7 @@ static int32_t launch_norm_t(const NormArgs &a, hipStream_t s) {
         if (lds > 64 * 1024) return CASCADE_EUNSUPPORTED;
         hipLaunchKernelGGL(norm_kernel<T>, dim3(a.rows), dim3(256), lds, s, (const T *)a.x, (const T *)a.gain,
                            (const T *)a.bias, (T *)a.y, a.D, a.kind, a.eps, a.xmap.map, a.ymap.map,
-                           a.xmap.map ? a.xmap.seq_len : a.ymap.seq_len, rope);
+                           a.xmap.map ? a.xmap.seq_len : a.ymap.seq_len, rope, zero);
     }
 #undef NORM_VEC
     CASCADE_HIP_TRY(hipGetLastError());
