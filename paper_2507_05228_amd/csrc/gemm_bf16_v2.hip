@@ -279,31 +279,33 @@ __device__ __forceinline__ void gemm_epilogue_tile_rope(const Gemm2Params &p, f3
     __syncthreads();
     constexpr int CPRO = BN / 8;                           // 16-byte pieces per tile row
     const bool wide = ((p.ldy | gcol0) % 8 == 0) && ((uintptr_t)p.Y % 16 == 0);
-    // Pieces in groups: all LDS reads (and row-map lookups) of a group are in flight before its first store, instead
-    // of one LDS latency per piece (one wavefront per SIMD: nothing else would cover it).
-    static_assert((BM * CPRO) % NTHREADS == 0, "every thread stores the same number of pieces");
-    constexpr int NIT = BM * CPRO / NTHREADS, GRP = NIT % 8 == 0 ? 8 : NIT % 7 == 0 ? 7 : NIT % 6 == 0 ? 6 : NIT % 5 == 0 ? 5 : 4;
-    static_assert(NIT % GRP == 0, "pieces held in registers per group");
+    // A thread keeps its piece of the row (CPRO pieces per row: its column offset is computed once) and walks down
+    // the rows RPP at a time; the LDS reads (and row-map lookups) of a group of pieces are in flight before the
+    // group's first store.
+    constexpr int RPP = NTHREADS / CPRO, NPASS = (BM + RPP - 1) / RPP, GRP = 8;
+    static_assert(CPRO <= NTHREADS, "a row of pieces per pass at least");
+    const int trow = tid / CPRO, piece = tid - trow * CPRO;
+    const int hs = piece >= CPRO / 2;                      // second halves
+    const int pp = pair0 + (piece - hs * (CPRO / 2)) * 8;
+    const int c = ((pp >> lh) << (lh + 1)) + (pp & (half - 1)) + (hs << lh);
+    const bool t_ok = trow < RPP && pp < n_pairs;          // n_pairs is a multiple of half, half of 8
+    const bool rows_inside = m0 + BM <= p.M;
+    const unsigned char *src = smem + trow * PITCH + piece * 16;
 #pragma unroll
-    for (int g0 = 0; g0 < NIT; g0 += GRP) {
+    for (int g0 = 0; g0 < NPASS; g0 += GRP) {
         bf16x8 v[GRP];
         bf16_t *y[GRP];
 #pragma unroll
         for (int g = 0; g < GRP; ++g) {
-            const int q = tid + (g0 + g) * NTHREADS;
-            const int row = q / CPRO, piece = q % CPRO;
-            const int hs = piece >= CPRO / 2;              // second halves
-            const int pp = pair0 + (piece - hs * (CPRO / 2)) * 8;
-            const int gm = m0 + row;
+            const int row = (g0 + g) * RPP + trow, gm = m0 + row;
             y[g] = nullptr;
-            if (gm >= p.M || pp >= n_pairs) continue;      // n_pairs is a multiple of half, half of 8
-            const int c = ((pp >> lh) << (lh + 1)) + (pp & (half - 1)) + (hs << lh);
-            v[g] = *(const bf16x8 *)(smem + row * PITCH + piece * 16);
+            if (g0 + g >= NPASS || !t_ok || row >= BM || (!rows_inside && gm >= p.M)) continue;
+            v[g] = *(const bf16x8 *)(src + (g0 + g) * RPP * PITCH);
             y[g] = p.Y + map_row(p.ymap, p.seq_len, gm) * p.ldy + gcol0 + c;
         }
 #pragma unroll
         for (int g = 0; g < GRP; ++g) {
-            if (!y[g]) continue;
+            if (g0 + g >= NPASS || !y[g]) continue;
             if (wide) {
                 *(bf16x8 *)y[g] = v[g];
             } else {
@@ -328,26 +330,36 @@ __device__ __forceinline__ void gemm_epilogue_tile(const Gemm2Params &p, f32x4 (
     const bf16_t *bias = (!SWIGLU && (flags & CASCADE_EPI_BIAS)) ? p.bias[seg] : nullptr;
     const bool act = ACT_OK && (flags & (CASCADE_EPI_GELU_ERF | CASCADE_EPI_GELU_TANH));
     const int gcol0 = p.seg_col0[seg];
-    // Two copies of the unrolled loops, chosen once: the plain one (no bias, no activation) stays small and
-    // contiguous in the instruction cache; the GELU code is long and would otherwise sit between every pair
-    // of its stores.
+    const bool has_res = flags & CASCADE_EPI_RESIDUAL;
+    // 16-byte stores need the rows to start on 16-byte boundaries; otherwise two 8-byte halves
+    const bool wide = ((p.ldy | gcol0) % 8 == 0) && ((uintptr_t)p.Y % 16 == 0);
+    // One wavefront per SIMD: the epilogue is as long as its instruction count, nothing overlaps it.  A tile that
+    // lies inside the matrix (all but the last row and column of tiles) takes copies of the two loops without any
+    // of the per-element range checks, chosen once per tile; so does the choice between residual and none.
+    const bool interior = m0 + BM <= p.M && nloc0 + BN_OUT <= seg_rows && wide;
+    // Stage 1, accumulators -> bf16 tile in LDS.  GENERAL: bias and activation code present.  INTERIOR: no range
+    // checks.  RES: 0 no residual, 1 residual, 2 decided at run time.
     // The residual of row block i + 1 is requested before row block i is worked on (two register sets), and the
     // compiler may not move anything across the row-block boundaries: left alone it hoists the loads and the
     // accumulator reads of all blocks to the top, which the 256-accumulator tile has no registers for.
-    const bool has_res = flags & CASCADE_EPI_RESIDUAL;
+    auto to_lds = [&](auto general_tag, auto interior_tag, auto res_tag) {
+    constexpr bool GENERAL = decltype(general_tag)::value, INTERIOR = decltype(interior_tag)::value;
+    constexpr int RES = decltype(res_tag)::value;
+    const bool res = RES == 2 ? has_res : RES == 1;
     bf16x4 rv[2][TNO];
     auto load_res = [&](int i, int buf) {
         const int gm = m0 + wm0 + 16 * i + l16;
-        const bf16_t *rrow = p.residual + map_row(p.rmap, p.seq_len, gm < p.M ? gm : 0) * p.ldres + gcol0 + nloc0;
+        const bf16_t *rrow = p.residual + map_row(p.rmap, p.seq_len, INTERIOR || gm < p.M ? gm : 0) * p.ldres + gcol0 + nloc0;
 #pragma unroll
         for (int j = 0; j < TNO; ++j) {
             const int tc = wc0 + 16 * j + c4;
-            rv[buf][j] = bf16x4{0, 0, 0, 0};
-            if (gm < p.M && nloc0 + tc < seg_rows) rv[buf][j] = *(const bf16x4 *)(rrow + tc);
+            if (INTERIOR) rv[buf][j] = *(const bf16x4 *)(rrow + tc);
+            else {
+                rv[buf][j] = bf16x4{0, 0, 0, 0};
+                if (gm < p.M && nloc0 + tc < seg_rows) rv[buf][j] = *(const bf16x4 *)(rrow + tc);
+            }
         }
     };
-    auto to_lds = [&](auto general_tag) {
-    constexpr bool GENERAL = decltype(general_tag)::value;
     // the bias of this lane's columns, once (it does not depend on the row block)
     f32x4 bias_v[GENERAL ? TNO : 1];
     if constexpr (GENERAL) {
@@ -361,18 +373,15 @@ __device__ __forceinline__ void gemm_epilogue_tile(const Gemm2Params &p, f32x4 (
             }
         }
     }
-    if (has_res) load_res(0, 0);
+    if (res) load_res(0, 0);
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
         const int row = wm0 + 16 * i + l16;
-        if (has_res && i + 1 < TM) load_res(i + 1, (i + 1) & 1);
+        if (res && i + 1 < TM) load_res(i + 1, (i + 1) & 1);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int j = 0; j < TNO; ++j) {
             const int tc = wc0 + 16 * j + c4;              // column inside the tile
-            // the segment's width and tc are multiples of 4: these 4 columns are all inside the segment or all
-            // outside (then their values are never stored and need neither bias nor residual)
-            const bool inside = nloc0 + tc < seg_rows;
             f32x4 v = acc_load(acc[i][j]);
             if constexpr (SWIGLU) {
                 const f32x4 up = acc_load(acc[i][j + TNO]);
@@ -385,7 +394,7 @@ __device__ __forceinline__ void gemm_epilogue_tile(const Gemm2Params &p, f32x4 (
 #pragma unroll
                         for (int x = 0; x < 4; ++x) v[x] = apply_act_bf16(v[x], flags);
             }
-            if (has_res) {                                 // added before the one rounding to bf16
+            if (res) {                                     // added before the one rounding to bf16
                 const bf16x4 r4 = rv[i & 1][j];
 #pragma unroll
                 for (int x = 0; x < 4; ++x) v[x] += (float)r4[x];
@@ -396,50 +405,58 @@ __device__ __forceinline__ void gemm_epilogue_tile(const Gemm2Params &p, f32x4 (
         __builtin_amdgcn_sched_barrier(0);
     }
     };
-    if (!SWIGLU && (bias || act)) to_lds(std::true_type{});
-    else to_lds(std::false_type{});
+    const std::integral_constant<int, 0> res_no;
+    const std::integral_constant<int, 1> res_yes;
+    const std::integral_constant<int, 2> res_rt;
+    if (!SWIGLU && (bias || act)) to_lds(std::true_type{}, std::false_type{}, res_rt);
+    else if (!interior) to_lds(std::false_type{}, std::false_type{}, res_rt);
+    else if (has_res) to_lds(std::false_type{}, std::true_type{}, res_yes);
+    else to_lds(std::false_type{}, std::true_type{}, res_no);
     __syncthreads();
+    // Stage 2, LDS tile -> global in 16-byte pieces.  A thread keeps its piece of the row (CPRO pieces per row) and
+    // walks down the rows RPP at a time, so the only per-piece work is an LDS read, a row-map lookup where the
+    // output is scattered, one address addition and the store; the reads (and lookups) of a group of pieces are
+    // in flight before the group's first store.
     constexpr int CPRO = BN_OUT / 8;                       // 16-byte pieces per tile row
-    static_assert(BN_OUT % 8 == 0, "whole pieces");
-    // 16-byte stores need the rows to start on 16-byte boundaries; otherwise two 8-byte halves
-    const bool wide = ((p.ldy | gcol0) % 8 == 0) && ((uintptr_t)p.Y % 16 == 0);
-    // Pieces in groups: all LDS reads (and row-map lookups) of a group are in flight before its first store, instead
-    // of one LDS latency per piece (one wavefront per SIMD: nothing else would cover it).
-    static_assert((BM * CPRO) % NTHREADS == 0, "every thread stores the same number of pieces");
-    constexpr int NIT = BM * CPRO / NTHREADS, GRP = NIT % 8 == 0 ? 8 : NIT % 7 == 0 ? 7 : NIT % 6 == 0 ? 6 : NIT % 5 == 0 ? 5 : 4;
-    static_assert(NIT % GRP == 0, "pieces held in registers per group");
+    static_assert(BN_OUT % 8 == 0 && CPRO <= NTHREADS, "whole pieces");
+    constexpr int RPP = NTHREADS / CPRO, NPASS = (BM + RPP - 1) / RPP, GRP = 8;
+    const int trow = tid / CPRO, piece = tid - trow * CPRO;
+    const int c = nloc0 + piece * 8;
+    const unsigned char *src = smem + trow * PITCH + piece * 16;
+    auto store_tile = [&](auto interior_tag) {
+        constexpr bool INTERIOR = decltype(interior_tag)::value;
+        const bool t_ok = trow < RPP && (INTERIOR || c < seg_rows);
+        const bool whole = INTERIOR || c + 8 <= seg_rows;  // else the segment ends inside this piece
 #pragma unroll
-    for (int g0 = 0; g0 < NIT; g0 += GRP) {
-        bf16x8 v[GRP];
-        bf16_t *y[GRP];
+        for (int g0 = 0; g0 < NPASS; g0 += GRP) {
+            bf16x8 v[GRP];
+            bf16_t *y[GRP];
 #pragma unroll
-        for (int g = 0; g < GRP; ++g) {
-            const int q = tid + (g0 + g) * NTHREADS;
-            const int row = q / CPRO, c = nloc0 + (q % CPRO) * 8;
-            const int gm = m0 + row;
-            y[g] = nullptr;
-            if (gm >= p.M || c >= seg_rows) continue;
-            v[g] = *(const bf16x8 *)(smem + row * PITCH + (q % CPRO) * 16);
-            y[g] = p.Y + map_row(p.ymap, p.seq_len, gm) * p.ldy + gcol0 + c;
-        }
+            for (int g = 0; g < GRP; ++g) {
+                const int row = (g0 + g) * RPP + trow, gm = m0 + row;
+                y[g] = nullptr;
+                if (g0 + g >= NPASS || !t_ok || row >= BM || (!INTERIOR && gm >= p.M)) continue;
+                v[g] = *(const bf16x8 *)(src + (g0 + g) * RPP * PITCH);
+                y[g] = p.Y + map_row(p.ymap, p.seq_len, gm) * p.ldy + gcol0 + c;
+            }
 #pragma unroll
-        for (int g = 0; g < GRP; ++g) {
-            if (!y[g]) continue;
-            const int c = nloc0 + ((tid + (g0 + g) * NTHREADS) % CPRO) * 8;
-            if (c + 8 <= seg_rows) {
-                if (wide) {
+            for (int g = 0; g < GRP; ++g) {
+                if (g0 + g >= NPASS || !y[g]) continue;
+                if (INTERIOR || (whole && wide)) {
                     *(bf16x8 *)y[g] = v[g];
-                } else {
+                } else if (whole) {
                     *(bf16x4 *)y[g] = bf16x4{v[g][0], v[g][1], v[g][2], v[g][3]};
                     *(bf16x4 *)(y[g] + 4) = bf16x4{v[g][4], v[g][5], v[g][6], v[g][7]};
-                }
-            } else {
+                } else {
 #pragma unroll
-                for (int x = 0; x < 8; ++x)
-                    if (c + x < seg_rows) y[g][x] = v[g][x];
+                    for (int x = 0; x < 8; ++x)
+                        if (c + x < seg_rows) y[g][x] = v[g][x];
+                }
             }
         }
-    }
+    };
+    if (interior) store_tile(std::true_type{});
+    else store_tile(std::false_type{});
 }
 
 template <int N>
