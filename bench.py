@@ -206,10 +206,10 @@ def dominant_kernel(cfg):
     committed rocprofv3 kernel statistics show the same names."""
     if cfg.dtype != "bf16":
         return "gemm_f32_kernel (FFN up shard GEMM)"
-    known = {"C3-llama3-8b-bf16": "gemm2_kernel<256,224,4,1,64,2,true,false>",
-             "C4-llama3-8b-long-bf16": "gemm2_kernel<256,256,2,2,64,2,true,false>",
-             "C5-llama3-70b-bf16": "gemm2_kernel<256,256,2,2,64,2,true,false>",
-             "C2-gpt2-small-bf16": "gemm2_kernel<256,192,2,2,64,2,false,false>"}
+    known = {"C3-llama3-8b-bf16": "gemm2_kernel<256,224,4,1,64,2,true,false,false>",
+             "C4-llama3-8b-long-bf16": "gemm2_kernel<256,256,2,2,64,2,true,false,false>",
+             "C5-llama3-70b-bf16": "gemm2_kernel<256,256,2,2,64,2,true,false,false>",
+             "C2-gpt2-small-bf16": "gemm2_kernel<256,192,2,2,64,2,false,false,false>"}
     return known.get(cfg.name, "gemm2_kernel") + " (FFN up shard GEMM" + (", gate and up fused)" if cfg.act == "swiglu" else ")")
 
 

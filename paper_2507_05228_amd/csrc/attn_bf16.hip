@@ -37,12 +37,23 @@ template <int D>
 __global__ __launch_bounds__(256) void vtranspose_kernel(const bf16_t *__restrict__ v, bf16_t *__restrict__ vt,
                                                          int64_t vs_b, int64_t vs_h, int64_t vs_n, int npad,
                                                          int Hkv, const CascadeTile *__restrict__ kvtiles,
-                                                         const int32_t *__restrict__ rowmap) {
+                                                         const int32_t *__restrict__ rowmap,
+                                                         const bf16_t *__restrict__ k, bf16_t *__restrict__ kp, int N) {
     __shared__ bf16_t tile[64][D + 2];
     const int t = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
     const int r0 = kvtiles[t].row_start, nr = kvtiles[t].n_rows;
     const bf16_t *vb = v + b * vs_b + g * vs_h;
     constexpr int CPR = D / 8;
+    // On the side (kp given; k has v's strides): the tile's K rows into packed order, kp[b][g][r][D], for callers
+    // whose K is in another row order, so that the attention kernel's tile loads never chase a row map.
+    if (kp) {
+        const bf16_t *kb = k + b * vs_b + g * vs_h;
+        for (int id = threadIdx.x; id < nr * CPR; id += 256) {
+            const int rr = id / CPR, ch = id % CPR, r = r0 + rr;
+            *(bf16x8 *)(kp + (((int64_t)b * Hkv + g) * N + r) * D + ch * 8) =
+                *(const bf16x8 *)(kb + (int64_t)rowmap[r] * vs_n + ch * 8);
+        }
+    }
     for (int id = threadIdx.x; id < 64 * CPR; id += 256) {
         int rr = id / CPR, ch = id % CPR;
         bf16x8 val = {0, 0, 0, 0, 0, 0, 0, 0};
@@ -534,20 +545,6 @@ __global__ __launch_bounds__(NWV * 64) void attn_bf16_kernel(AttnBf16Params p) {
     }
 }
 
-// K rows into packed order (callers whose K is in original row order): 16 bytes per thread.
-template <int D>
-__global__ __launch_bounds__(256) void kgather_kernel(const bf16_t *__restrict__ k, bf16_t *__restrict__ kp,
-                                                      int64_t ks_b, int64_t ks_h, int64_t ks_n, int N, int Hkv,
-                                                      const int32_t *__restrict__ rowmap) {
-    constexpr int CPR = D / 8;
-    const int g = blockIdx.y, b = blockIdx.z;
-    const int64_t id = blockIdx.x * 256ll + threadIdx.x;
-    const int r = (int)(id / CPR), ch = (int)(id % CPR);
-    if (r >= N) return;
-    const bf16x8 val = *(const bf16x8 *)(k + b * ks_b + g * ks_h + (int64_t)rowmap[r] * ks_n + ch * 8);
-    *(bf16x8 *)(kp + (((int64_t)b * Hkv + g) * N + r) * D + ch * 8) = val;
-}
-
 static int32_t npad_of(const cascade_plan *p) { return std::max(1, plan_tiles(kv_plan(p), KV_TILE).count) * KV_TILE; }
 
 // V^T (tile order, padded) followed by room for K gathered into packed order
@@ -573,23 +570,17 @@ static int32_t launch_attn_cfg(const cascade_plan *p, const AttnArgs &a, hipStre
     if (ql.count == 0) return CASCADE_OK;
 
     bf16_t *vt = (bf16_t *)a.workspace;
-    {
+    bf16_t *kp = a.kv_rowmap ? (bf16_t *)((unsigned char *)a.workspace + vt_bytes_of(p, a.B, a.Hkv, D)) : nullptr;
+    {   // V^T in tile order and, where K is not in packed order, K gathered into it: one launch
         dim3 grid(kl.count, a.Hkv, a.B);
         hipLaunchKernelGGL(vtranspose_kernel<D>, grid, dim3(256), 0, s, (const bf16_t *)a.v, vt, a.ks_b, a.ks_h,
-                           a.ks_n, npad, a.Hkv, kl.dev, a.kv_rowmap);
+                           a.ks_n, npad, a.Hkv, kl.dev, a.kv_rowmap, (const bf16_t *)a.k, kp, N);
         CASCADE_HIP_TRY(hipGetLastError());
     }
     AttnBf16Params k;
     k.q = (const bf16_t *)a.q; k.k = (const bf16_t *)a.k; k.vt = vt;
     k.qs_b = a.qs_b; k.qs_h = a.qs_h; k.qs_n = a.qs_n; k.ks_b = a.ks_b; k.ks_h = a.ks_h; k.ks_n = a.ks_n;
-    if (a.kv_rowmap) {
-        bf16_t *kp = (bf16_t *)((unsigned char *)a.workspace + vt_bytes_of(p, a.B, a.Hkv, D));
-        dim3 grid((unsigned)(((int64_t)N * (D / 8) + 255) / 256), a.Hkv, a.B);
-        hipLaunchKernelGGL(kgather_kernel<D>, grid, dim3(256), 0, s, (const bf16_t *)a.k, kp, a.ks_b, a.ks_h, a.ks_n,
-                           N, a.Hkv, a.kv_rowmap);
-        CASCADE_HIP_TRY(hipGetLastError());
-        k.k = kp; k.ks_n = D; k.ks_h = (int64_t)N * D; k.ks_b = (int64_t)a.Hkv * N * D;
-    }
+    if (kp) { k.k = kp; k.ks_n = D; k.ks_h = (int64_t)N * D; k.ks_b = (int64_t)a.Hkv * N * D; }
     k.vts_b = (int64_t)a.Hkv * D * npad; k.vts_h = (int64_t)D * npad; k.npad = npad;
     const int64_t kb = ((int64_t)(N - 1) * k.ks_n + D) * 2, vb = (int64_t)D * npad * 2;
     if (kb >= (int64_t)OOB_OFF || vb >= (int64_t)OOB_OFF) return CASCADE_EUNSUPPORTED;
