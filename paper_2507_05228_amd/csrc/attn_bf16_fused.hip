@@ -135,7 +135,7 @@ __global__ __launch_bounds__(1024 / TQ) void attn_fused_kernel(AttnBf16Params p)
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) Q[qb][ks] = *(const bf16x8 *)(qp + ks * 32);
         // without a mask: the largest position the launcher accepts, so that only the padding of ragged tiles
-        // (position 2^30) is cut; all positions are below 2^30 in magnitude, so "limit - position" cannot overflow
+        // (position 2^30) is cut; every position is below 2^30 in magnitude
         qlim[qb] = p.causal ? p.pos_packed[r] : (1 << 30) - 1;
     }
 
@@ -267,18 +267,15 @@ __global__ __launch_bounds__(1024 / TQ) void attn_fused_kernel(AttnBf16Params p)
         P[1 - X][qb][2 * kb + 1] = w1;
     };
     // mask of the four scores of one (query block, key block) pair of S[X]: a score whose key position is above
-    // the query's becomes -inf.  d = limit - position is negative exactly then; its sign bit over the bits of
-    // +inf is -inf or +inf, and min(score, that) needs no condition register and no branch.
-    uint32_t sign_bit = 0x80000000u, inf_bits = 0x7F800000u;
-    asm volatile("" : "+v"(sign_bit), "+v"(inf_bits));   // in registers: one bit-field insert per score
+    // the query's becomes -inf: a compare and a select per score (measured 1-1.5 % faster over the kernel than
+    // the branch-free form without a condition register: sign of limit - position inserted over the bits of
+    // +inf, then a minimum, three instructions).
     auto mask_chunk = [&](auto x_tag, auto qb_tag, auto kb_tag, const i32x4 (&pk)[2]) {
         constexpr int X = decltype(x_tag)::value, qb = decltype(qb_tag)::value, kb = decltype(kb_tag)::value;
         f32x4 sv = S[X][qb][kb];
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            const uint32_t d = (uint32_t)(qlim[qb] - pk[kb][r]);
-            const float bias = __builtin_bit_cast(float, (d & sign_bit) | (inf_bits & ~sign_bit));
-            sv[r] = fminf(sv[r], bias);
+            sv[r] = qlim[qb] >= pk[kb][r] ? sv[r] : -INFINITY;
         }
         asm volatile("" : "+v"(sv));
         S[X][qb][kb] = sv;
