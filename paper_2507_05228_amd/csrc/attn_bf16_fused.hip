@@ -285,7 +285,11 @@ __global__ __launch_bounds__(1024 / TQ) void attn_fused_kernel(AttnBf16Params p)
     auto max_chunk = [&](auto x_tag, auto qb_tag, float &flagv) {
         constexpr int X = decltype(x_tag)::value, qb = decltype(qb_tag)::value;
         const f32x4 a = S[X][qb][0], c = S[X][qb][1];
-        float mx = fmaxf(fmaxf(fmaxf(a[0], a[1]), fmaxf(a[2], a[3])), fmaxf(fmaxf(c[0], c[1]), fmaxf(c[2], c[3]))) * sl2;
+        // a chain of three-operand maxima: 4 instructions for the 8 scores (a balanced tree of pairs takes 6-7)
+        float mx = fmaxf(fmaxf(a[0], a[1]), a[2]);
+        mx = fmaxf(fmaxf(mx, a[3]), c[0]);
+        mx = fmaxf(fmaxf(mx, c[1]), c[2]);
+        mx = fmaxf(mx, c[3]) * sl2;
         float fl = fmaxf(flagv, mx - m_thr[qb]);
         asm volatile("" : "+v"(mx), "+v"(fl));
         lmax[qb] = mx;
