@@ -78,10 +78,14 @@ __device__ __forceinline__ void fence() { __builtin_amdgcn_sched_barrier(0); }
 
 }   // namespace
 
-// TQ: 16-row query blocks per wavefront (2: 32 rows, 8 wavefronts; 4: 64 rows, 4 wavefronts).  MASKED: every score is compared with its
-// key's position (causal plans, plans with ragged key/value tiles); false only when every key of every tile
-// is visible to every query.  A kernel parameter rather than a choice per tile: a second copy of the MFMA
-// statements inside the loop makes the register allocator shuffle the accumulators between the copies.
+// TQ: 16-row query blocks per wavefront (2: 32 rows, 8 wavefronts; 4: 64 rows, 4 wavefronts).  MASKED: the kernel
+// holds the code that compares a score with its key's position (causal plans, plans with ragged key/value tiles);
+// false only when every key of every tile is visible to every query.  A kernel parameter: a second copy of the
+// MFMA statements inside the loop makes the register allocator shuffle the accumulators between the copies.
+// Inside a MASKED kernel the comparisons of a step (2 instructions per score, a third of the step's vector
+// arithmetic) sit behind one wavefront-uniform branch and run only for tiles that hold a key some query of the
+// wavefront cannot see or that are padded: with the walk in position order that is the last one or two tiles
+// (C4 / C5 attention -6 %).
 // SPLIT (TQ = 2, MASKED, four heads per workgroup): the two wavefront groups take the same 32 query rows and every
 // other key/value tile each, and their running (offset, row sum, output) are merged through LDS at the end.  For
 // launches of a single round of workgroups: a query tile's walk is then half as long and there are twice as many
@@ -138,6 +142,19 @@ __global__ __launch_bounds__(1024 / TQ) void attn_fused_kernel(AttnBf16Params p)
         // (position 2^30) is cut; every position is below 2^30 in magnitude
         qlim[qb] = p.causal ? p.pos_packed[r] : (1 << 30) - 1;
     }
+
+    // The smallest limit of this wavefront's queries: a key/value tile whose largest position is not above it (and
+    // that has no padding) is visible to every one of them, and its scores skip the mask.
+    int q_min;
+    {
+        int qm = qlim[0];
+#pragma unroll
+        for (int qb = 1; qb < TQ; ++qb) qm = min(qm, qlim[qb]);
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) qm = min(qm, __shfl_xor(qm, off));
+        q_min = __builtin_amdgcn_readfirstlane(qm);
+    }
+    auto tile_needs_mask = [&](int tile_pmax, int tile_rows) { return tile_pmax > q_min || tile_rows < KV_TILE; };
 
     // ---- visible key/value tiles: a prefix of the list ordered by smallest position
     int t_end = p.n_kvtiles;
@@ -305,22 +322,20 @@ __global__ __launch_bounds__(1024 / TQ) void attn_fused_kernel(AttnBf16Params p)
     };
 
     // ---- one step: scores of (qs, X) into S[X], output product of (vs, X) with P[X] (and the row sums: the
-    // same product against a block of ones), exponentials of S[1-X] into P[1-X], then (MASKED) the mask and
-    // the lane maxima of the new scores.  Straight-line code: a taken branch costs this kernel some fifty
-    // cycles, so the only choice, masked or not, is made once per tile outside.  On entry the ring holds the
+    // same product against a block of ones), exponentials of S[1-X] into P[1-X], then (MASKED, mask_on) the mask
+    // and the lane maxima of the new scores.  Straight-line code but for the one branch around the mask: a taken
+    // branch costs this kernel some fifty cycles.  On entry the ring holds the
     // first RD fragments; on exit those of the next step (half 1-X, stages nqs / nvs).  Returns whether some
     // maximum passed its row's threshold.
     // NEXT: whether the ring is refilled for the next step at all (false in front of a barrier that has yet to
     // confirm the next step's tiles: the caller then fills it behind the barrier).
-    auto step = [&](auto x_tag, auto next_tag, int qs, int vs, int nqs, int nvs) -> bool {
+    auto step = [&](auto x_tag, auto next_tag, int qs, int vs, int nqs, int nvs, bool mask_on) -> bool {
         constexpr bool NEXT = decltype(next_tag)::value;
         constexpr int X = decltype(x_tag)::value;
         constexpr int NF = NQF + NVF, QS = TQ * NQF, NS = TQ * NF + TQ;   // slots: scores, output, row sums
         constexpr int NE = 2 * TQ;                           // chunks of exponentials: one per (query block, key block) pair
         constexpr int NT = 3 * TQ;                           // chunks of the tail: per query block 2 of mask, 1 of maxima
         const std::integral_constant<int, 1 - X> nx;
-        i32x4 pk[2];
-        if constexpr (MASKED) read_positions(x_tag, qs, pk);
         float flagv = 0.f;
         fence();
         auto after_slot = [&](auto s_tag) {
@@ -335,12 +350,20 @@ __global__ __launch_bounds__(1024 / TQ) void attn_fused_kernel(AttnBf16Params p)
                 constexpr int t = decltype(t_tag)::value;
                 if constexpr (QS + 2 + t * (NS - QS - 3) / NT == s) {
                     constexpr int tq = t / 3, c = t % 3;
-                    if constexpr (c < 2) {
-                        if constexpr (MASKED)
-                            mask_chunk(x_tag, std::integral_constant<int, tq>{}, std::integral_constant<int, c>{}, pk);
-                    } else {
-                        max_chunk(x_tag, std::integral_constant<int, tq>{}, flagv);
+                    // The mask of the whole step sits in the first tail slot, behind one branch on a
+                    // wavefront-uniform condition: in position order only the last one or two tiles of a walk hold
+                    // a key some query of the wavefront cannot see, all others skip these 2 instructions per score.
+                    if constexpr (t == 0 && MASKED) {
+                        if (mask_on) {
+                            i32x4 pk[2];
+                            read_positions(x_tag, qs, pk);
+                            static_for<2 * TQ>([&](auto m_tag) {
+                                constexpr int m = decltype(m_tag)::value;
+                                mask_chunk(x_tag, std::integral_constant<int, m / 2>{}, std::integral_constant<int, m % 2>{}, pk);
+                            });
+                        }
                     }
+                    if constexpr (c == 2) max_chunk(x_tag, std::integral_constant<int, tq>{}, flagv);
                 }
             });
             fence();
@@ -446,7 +469,8 @@ __global__ __launch_bounds__(1024 / TQ) void attn_fused_kernel(AttnBf16Params p)
                 const int qs = ((real ? i : i - 1) & (NST - 1)) * STAGE;
                 const int vs = ((i > 0 ? i - 1 : 0) & (NST - 1)) * STAGE + K_BYTES;
                 const int nqs = ((next_real ? i + 1 : i) & (NST - 1)) * STAGE, nvs = (i & (NST - 1)) * STAGE + K_BYTES;
-                const bool need0 = step(x0, refill, qs, vs, qs, vs);
+                const bool mask_on = tile_needs_mask(mt0.pmax, mt0.n_rows);
+                const bool need0 = step(x0, refill, qs, vs, qs, vs, mask_on);
                 between_steps(need0 && real);
                 // The barrier between the two steps of a tile: what was requested two barriers ago has landed (the
                 // requests of the previous barrier may still be in flight), everyone is past step 2i.  Free from
@@ -459,7 +483,7 @@ __global__ __launch_bounds__(1024 / TQ) void attn_fused_kernel(AttnBf16Params p)
                 in_flight = 0;
                 if (i + 3 < n_tiles) { issue_k(mt3, (i + 3) & (NST - 1)); in_flight += LPT_K; }
                 if (i + 2 < n_tiles) { issue_v(mt2, (i + 2) & (NST - 1)); in_flight += LPT_V; }
-                const bool need1 = step(x1, refill, qs, vs, nqs, nvs);
+                const bool need1 = step(x1, refill, qs, vs, nqs, nvs, mask_on);
                 between_steps(need1 && real);
                 if (real) {
                     if (next_real) mt0 = mt1;
@@ -509,9 +533,11 @@ __global__ __launch_bounds__(1024 / TQ) void attn_fused_kernel(AttnBf16Params p)
                     for (int qb = 0; qb < TQ; ++qb) qlim[qb] = -(1 << 30);                 // nothing is visible
 #pragma unroll
                 for (int f = 0; f < RD; ++f) ring[f] = *(const bf16x8 *)frag_ptr(qs, vs, x0, f);
-                const bool need0 = step(x0, refill, qs, vs, qs, vs);
+                // (the flush has every score masked)
+                const bool mask_on = !real || (rg == 0 ? tile_needs_mask(mv0.pmax, mv0.n_rows) : tile_needs_mask(mv1.pmax, mv1.n_rows));
+                const bool need0 = step(x0, refill, qs, vs, qs, vs, mask_on);
                 between_steps(need0 && real);
-                const bool need1 = step(x1, no_refill, qs, vs, qs, vs);
+                const bool need1 = step(x1, no_refill, qs, vs, qs, vs, mask_on);
                 between_steps(need1 && real);
             }
             mv0 = mk0; mv1 = mk1;
