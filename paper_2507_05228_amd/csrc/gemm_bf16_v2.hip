@@ -665,10 +665,6 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm2_kernel(Gemm2Params p) {
     };
 
     f32x4 acc[TM][TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     // operand fetch: lane -> tile row lane%16 of a 16-row block, chunk 4 ks + lane/16, swizzled
     const int frow = lane & 15, fch = lane >> 4, fsw = swz(lane & 15);
@@ -709,6 +705,12 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm2_kernel(Gemm2Params p) {
 #pragma unroll
     for (int s = 0; s < NST - 1; ++s)
         if (s < KT) issue_loads(s, s);
+    // (the accumulators are cleared while the first tile loads are in flight: up to 256 register writes)
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    __builtin_amdgcn_sched_barrier(0);
     // Software pipeline over k-steps: the LDS reads of a k-step are in flight while the MFMAs of the
     // previous k-step run, also across the tile boundary (the second k-step of tile kt is multiplied
     // after the barrier that opens tile kt+1, from registers).  It needs two operand register sets;
