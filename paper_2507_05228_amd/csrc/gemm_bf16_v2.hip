@@ -579,7 +579,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm2_kernel(Gemm2Params p) {
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm0 = (wave / WN) * WTM, wn0 = (wave % WN) * WTN;
 
-    // workgroup -> tile: contiguous run of tiles (m fastest) per XCD
+    // workgroup -> tile: a contiguous run of the tile list per XCD (see tile_coords for the order of the list)
     // One wavefront per SIMD: the workgroup is persistent.  The launch has one workgroup per CU (a multiple of 8)
     // and workgroup w takes the tiles that workgroups w, w + gridDim.x, ... of a launch with one workgroup per
     // tile would take: nothing waits for a workgroup's last stores to be acknowledged, for its registers and LDS
