@@ -137,10 +137,12 @@ def test_shard_gemm_swiglu_and_tanh(cas, dtype):
 
 # One shape per tile variant of the bf16 MFMA kernels (8 wavefronts at 192 / 224 / 256 columns, one wavefront per
 # SIMD at 192 / 224 and for SwiGLU at 224 / 256, the 256x128 ping-pong kernel), chosen with the launcher's own cost
-# rule on 256 CUs; ragged M and N, bias + GELU or residual, every output element against the oracle.
+# rule on 256 CUs; ragged M and N, bias + GELU or residual, every output element against the oracle.  The last three
+# shapes have 11 and 18 rows of tiles: the tile order then runs in groups of 8 rows of tiles with a shorter last group.
 @pytest.mark.parametrize("M,N,swiglu", [(700, 1000, False), (700, 1000, True), (700, 9600, True), (700, 13728, False),
                                         (1000, 12352, False), (1000, 14416, False), (1300, 10804, False),
-                                        (2000, 12352, False), (40, 448, True), (1, 1000, True), (3, 5000, False)])
+                                        (2000, 12352, False), (40, 448, True), (1, 1000, True), (3, 5000, False),
+                                        (2700, 6000, False), (2700, 9600, True), (4500, 2100, False)])
 @pytest.mark.parametrize("epi", ["plain", "bias_gelu", "residual"])
 def test_shard_gemm_every_mfma_tile_variant(cas, M, N, swiglu, epi):
     import torch
