@@ -89,3 +89,40 @@ def test_split_reduction_does_not_depend_on_what_the_workspace_held(cas):
     cas.cascade_layer_forward(plan, desc, wts, outs[0], second, ws)
     torch.cuda.synchronize()
     assert torch.equal(two, second)
+
+
+def test_layer_with_split_reduction_replays_from_a_hip_graph(cas):
+    """The exchange clears its flag words inside the captured work (a norm launch, no memset): replays, with eager
+    work and synchronisations in between and the scratch overwritten, reproduce the eager result bit for bit."""
+    import torch
+    cfg = SPLIT
+    a = make_assignment(cfg.assignment, cfg.seq_len, cfg.n_shards, 83)
+    w, h = make_layer_weights(cfg), make_hidden(cfg)
+    plan = cas.cascade_plan_create(cfg.batch, cfg.seq_len, cfg.n_shards, a)
+    desc = cas.make_layer_desc(cfg, cas.ATTN_FUSED)
+    t = {k: cas.to_device(v, cfg.dtype) for k, v in w.items()}
+    wts = cas.make_layer_weights(t)
+    h_in = cas.to_device(h, cfg.dtype)
+    h_out = torch.empty_like(h_in)
+    ws = cas.new_workspace(cas.cascade_layer_workspace_bytes(plan, desc))
+    step = lambda: cas.cascade_layer_forward(plan, desc, wts, h_in, h_out, ws)
+    step()
+    torch.cuda.synchronize()
+    ref = h_out.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()                                                     # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        step()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        h_out.fill_(7.0)
+        ws.fill_(0xA5 if rep % 2 else 0x00)                        # whatever the last replay left is gone
+        junk = torch.randn(256, 256, device="cuda") @ torch.randn(256, 256, device="cuda")   # eager work in between
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(h_out, ref), rep
