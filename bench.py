@@ -120,6 +120,34 @@ def measured_ceilings(cas):
     return out
 
 
+def vendor_gemm_reference(cfg):
+    """For scale only, never used by the product: the vendor library's plain bf16 GEMM (torch.matmul, weight as
+    [N, K]) on the four GEMM shapes of the layer, without the epilogues the shard GEMMs fuse (rotary, SwiGLU,
+    residual).  TFLOP/s per shape."""
+    import torch
+    T, D, f = cfg.batch * cfg.seq_len, cfg.d_model, cfg.d_ff
+    qw, hw = (cfg.n_heads + 2 * cfg.n_kv_heads) * cfg.head_dim, cfg.n_heads * cfg.head_dim
+    shapes = {"qkv_gemm": (T, qw, D), "o_proj": (T, D, hw), "ffn_up": (T, (2 if cfg.act == "swiglu" else 1) * f, D),
+              "ffn_down": (T, D, f)}
+    out = {}
+    for name, (m, n, k) in shapes.items():
+        x = torch.randn(m, k, device="cuda", dtype=torch.bfloat16)
+        w = torch.randn(n, k, device="cuda", dtype=torch.bfloat16)
+        fn = lambda: x @ w.t()
+        for _ in range(40):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(40):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / 40
+        out[name] = {"ms": ms, "tflops": 2.0 * m * n * k / (ms * 1e-3) / 1e12}
+        del x, w
+    return out
+
+
 class Workload:
     """Inputs, plan, descriptors and workspaces of one configuration, resident on the device."""
 
@@ -470,6 +498,7 @@ def main():
     extra = {}
     if bf16 and not args.no_ceilings:
         extra["measured_ceilings"] = measured_ceilings(cas)
+        extra["vendor_library_gemm_for_scale"] = vendor_gemm_reference(cfg)
     st = wl.staged(max(args.steps, 20))
     sec_m, stm, merge_alone = wl.materialised(max(5, args.steps // 4))
     if bf16 and not args.headline_only:
