@@ -63,6 +63,16 @@ __device__ __forceinline__ float block_sum_256(float v, float *scratch) {
 
 __device__ __forceinline__ int64_t map_row(const int32_t *map, int32_t seq_len, int32_t r) {
     if (!map) return r;
+    if (r < seq_len) return map[r];                        // the first (or only) sequence: no division
     int32_t b = r / seq_len;
     return (int64_t)b * seq_len + map[r - b * seq_len];
+}
+// The same for a row known to lie in or shortly behind sequence b_hint (the rows of a tile whose first row lies in
+// that sequence): a subtraction and a compare instead of an integer division by a run-time divisor, which costs
+// ~40 instructions per row and was most of the time of an epilogue that looks up 8 to 32 rows per lane.
+__device__ __forceinline__ int64_t map_row_near(const int32_t *map, int32_t seq_len, int32_t r, int32_t b_hint) {
+    if (!map) return r;
+    const int32_t off = r - b_hint * seq_len;
+    if ((uint32_t)off < (uint32_t)seq_len) return (int64_t)b_hint * seq_len + map[off];
+    return map_row(map, seq_len, r);
 }

@@ -89,12 +89,13 @@ struct ResidualAhead {
         const int m4 = (lane & 15) * 4, rsel = lane >> 4;
         const int wcol0 = SWIGLU ? nloc0 + (wn0 / WTN) * OW : nloc0 + wn0;
         const int gcol0 = p.seg_col0[seg];
+        const int b0 = m0 / p.seq_len;                     // sequence of the tile's first row (uniform)
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
                 const int gm = m0 + wm0 + 16 * i + 4 * t + rsel;
-                const bf16_t *rrow = p.residual + map_row(p.rmap, p.seq_len, gm < p.M ? gm : 0) * p.ldres + gcol0;
+                const bf16_t *rrow = p.residual + map_row_near(p.rmap, p.seq_len, gm < p.M ? gm : 0, b0) * p.ldres + gcol0;
 #pragma unroll
                 for (int cc = 0; cc < NCH; ++cc) {
                     const int c = wcol0 + 64 * cc + m4;
@@ -120,6 +121,7 @@ __device__ __forceinline__ void gemm_epilogue(const Gemm2Params &p, f32x4 (&acc)
     const int l16 = lane & 15, m4 = l16 * 4, rsel = lane >> 4;
     const int wcol0 = SWIGLU ? nloc0 + (wn0 / WTN) * OW : nloc0 + wn0;   // first output column (in segment)
     const int gcol0 = p.seg_col0[seg];
+    const int b0 = m0 / p.seq_len;                         // sequence of the tile's first row (uniform)
     const bf16_t *bias = (flags & CASCADE_EPI_BIAS) ? p.bias[seg] : nullptr;
     f32x4 bias_v[NCH];
 #pragma unroll
@@ -158,9 +160,9 @@ __device__ __forceinline__ void gemm_epilogue(const Gemm2Params &p, f32x4 (&acc)
             const int rl = 4 * t + rsel;
             const int gm = m0 + wm0 + 16 * i + rl;
             if (gm < p.M) {
-                bf16_t *yrow = p.Y + map_row(p.ymap, p.seq_len, gm) * p.ldy + gcol0;
+                bf16_t *yrow = p.Y + map_row_near(p.ymap, p.seq_len, gm, b0) * p.ldy + gcol0;
                 const bf16_t *rrow = (flags & CASCADE_EPI_RESIDUAL)
-                                         ? p.residual + map_row(p.rmap, p.seq_len, gm) * p.ldres + gcol0 : nullptr;
+                                         ? p.residual + map_row_near(p.rmap, p.seq_len, gm, b0) * p.ldres + gcol0 : nullptr;
 #pragma unroll
                 for (int cc = 0; cc < NCH; ++cc) {
                     const int c = wcol0 + 64 * cc + m4;
@@ -243,6 +245,7 @@ __device__ __forceinline__ void gemm_epilogue_tile_rope(const Gemm2Params &p, f3
     const int wp0 = (wn0 / WTN) * (WTN / 2);               // wavefront's first pair inside the tile
     const int lh = p.rope_lh, half = 1 << lh, n_pairs = seg_rows >> 1;
     const int gcol0 = p.seg_col0[seg];
+    const int b0 = m0 / p.seq_len;                         // sequence of the tile's first row (uniform)
     const bf16_t *bias = (p.flags & CASCADE_EPI_BIAS) ? p.bias[seg] : nullptr;
     f32x4 bias_a[TNO], bias_b[TNO];                        // of this lane's pairs, once
 #pragma unroll
@@ -301,7 +304,7 @@ __device__ __forceinline__ void gemm_epilogue_tile_rope(const Gemm2Params &p, f3
             y[g] = nullptr;
             if (g0 + g >= NPASS || !t_ok || row >= BM || (!rows_inside && gm >= p.M)) continue;
             v[g] = *(const bf16x8 *)(src + (g0 + g) * RPP * PITCH);
-            y[g] = p.Y + map_row(p.ymap, p.seq_len, gm) * p.ldy + gcol0 + c;
+            y[g] = p.Y + map_row_near(p.ymap, p.seq_len, gm, b0) * p.ldy + gcol0 + c;
         }
 #pragma unroll
         for (int g = 0; g < GRP; ++g) {
@@ -316,11 +319,16 @@ __device__ __forceinline__ void gemm_epilogue_tile_rope(const Gemm2Params &p, f3
     }
 }
 
-template <int BM, int NTHREADS, int TM, int TN, int WTN, bool SWIGLU, int BN_OUT, bool ACT_OK>
+// PARTNER (split reduction, the workgroup that finishes the tile): the other workgroup's accumulators, stored at
+// `part` as they lay in its registers, are added to this one's in stage 1; they are valid once the word at
+// `flag` reads `use`, which is waited for as late as possible, after the row lookups of stage 2 are on their way.
+template <int BM, int NTHREADS, int TM, int TN, int WTN, bool SWIGLU, int BN_OUT, bool ACT_OK, bool PARTNER = false>
 __device__ __forceinline__ void gemm_epilogue_tile(const Gemm2Params &p, f32x4 (&acc)[TM][TN], unsigned char *smem,
                                                    int tid, int m0, int wm0, int wn0, int nloc0, int seg,
-                                                   int seg_rows) {
+                                                   int seg_rows, const f32x4 *part = nullptr, uint32_t *flag = nullptr,
+                                                   uint32_t use = 0) {
     static_assert(!SWIGLU || TN % 2 == 0, "gate and up blocks pair up inside the wavefront tile");
+    static_assert(!PARTNER || !SWIGLU, "the split reduction runs plain GEMMs");
     constexpr int TNO = SWIGLU ? TN / 2 : TN;              // output blocks of the wavefront tile
     constexpr int OW = SWIGLU ? WTN / 2 : WTN;
     constexpr int PITCH = EpiTile<BN_OUT>::PITCH;
@@ -330,6 +338,7 @@ __device__ __forceinline__ void gemm_epilogue_tile(const Gemm2Params &p, f32x4 (
     const bf16_t *bias = (!SWIGLU && (flags & CASCADE_EPI_BIAS)) ? p.bias[seg] : nullptr;
     const bool act = ACT_OK && (flags & (CASCADE_EPI_GELU_ERF | CASCADE_EPI_GELU_TANH));
     const int gcol0 = p.seg_col0[seg];
+    const int b0 = m0 / p.seq_len;                         // sequence of the tile's first row (uniform)
     const bool has_res = flags & CASCADE_EPI_RESIDUAL;
     // 16-byte stores need the rows to start on 16-byte boundaries; otherwise two 8-byte halves
     const bool wide = ((p.ldy | gcol0) % 8 == 0) && ((uintptr_t)p.Y % 16 == 0);
@@ -339,17 +348,20 @@ __device__ __forceinline__ void gemm_epilogue_tile(const Gemm2Params &p, f32x4 (
     const bool interior = m0 + BM <= p.M && nloc0 + BN_OUT <= seg_rows && wide;
     // Stage 1, accumulators -> bf16 tile in LDS.  GENERAL: bias and activation code present.  INTERIOR: no range
     // checks.  RES: 0 no residual, 1 residual, 2 decided at run time.
-    // The residual of row block i + 1 is requested before row block i is worked on (two register sets), and the
-    // compiler may not move anything across the row-block boundaries: left alone it hoists the loads and the
-    // accumulator reads of all blocks to the top, which the 256-accumulator tile has no registers for.
+    // The residual of row block i + RES_AHEAD - 1 is requested before row block i is worked on (RES_AHEAD register
+    // sets of 2 TNO registers: the whole tile's residual costs about one memory latency, not one per row block;
+    // with two sets the second workgroup of a split reduction spent 46 k cycles in this epilogue, half of them
+    // waiting), and the compiler may not move anything across the row-block boundaries: left alone it hoists the
+    // loads and the accumulator reads of all blocks to the top, which the 256-accumulator tile has no registers for.
     auto to_lds = [&](auto general_tag, auto interior_tag, auto res_tag) {
     constexpr bool GENERAL = decltype(general_tag)::value, INTERIOR = decltype(interior_tag)::value;
     constexpr int RES = decltype(res_tag)::value;
     const bool res = RES == 2 ? has_res : RES == 1;
-    bf16x4 rv[2][TNO];
+    constexpr int RES_AHEAD = TM < 5 ? TM : 5;
+    bf16x4 rv[RES_AHEAD][TNO];
     auto load_res = [&](int i, int buf) {
         const int gm = m0 + wm0 + 16 * i + l16;
-        const bf16_t *rrow = p.residual + map_row(p.rmap, p.seq_len, INTERIOR || gm < p.M ? gm : 0) * p.ldres + gcol0 + nloc0;
+        const bf16_t *rrow = p.residual + map_row_near(p.rmap, p.seq_len, INTERIOR || gm < p.M ? gm : 0, b0) * p.ldres + gcol0 + nloc0;
 #pragma unroll
         for (int j = 0; j < TNO; ++j) {
             const int tc = wc0 + 16 * j + c4;
@@ -373,16 +385,31 @@ __device__ __forceinline__ void gemm_epilogue_tile(const Gemm2Params &p, f32x4 (
             }
         }
     }
-    if (res) load_res(0, 0);
+    // the partner's accumulators, three row blocks ahead like the residual
+    constexpr int P_AHEAD = PARTNER ? (TM < 3 ? TM : 3) : 1;
+    f32x4 pvv[P_AHEAD][PARTNER ? TNO : 1];
+    auto load_part = [&](int i) {
+        if constexpr (PARTNER)
+#pragma unroll
+            for (int j = 0; j < TNO; ++j) pvv[i % P_AHEAD][j] = __builtin_nontemporal_load(part + (i * TN + j) * NTHREADS);
+    };
+    if constexpr (PARTNER)
+#pragma unroll
+        for (int i = 0; i < P_AHEAD - 1 && i < TM; ++i) load_part(i);
+    if (res)
+#pragma unroll
+        for (int i = 0; i < RES_AHEAD - 1 && i < TM; ++i) load_res(i, i % RES_AHEAD);
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
         const int row = wm0 + 16 * i + l16;
-        if (res && i + 1 < TM) load_res(i + 1, (i + 1) & 1);
+        if (PARTNER && i + P_AHEAD - 1 < TM) load_part(i + P_AHEAD - 1);
+        if (res && i + RES_AHEAD - 1 < TM) load_res(i + RES_AHEAD - 1, (i + RES_AHEAD - 1) % RES_AHEAD);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int j = 0; j < TNO; ++j) {
             const int tc = wc0 + 16 * j + c4;              // column inside the tile
             f32x4 v = acc_load(acc[i][j]);
+            if constexpr (PARTNER) v += pvv[i % P_AHEAD][j];
             if constexpr (SWIGLU) {
                 const f32x4 up = acc_load(acc[i][j + TNO]);
 #pragma unroll
@@ -395,7 +422,7 @@ __device__ __forceinline__ void gemm_epilogue_tile(const Gemm2Params &p, f32x4 (
                         for (int x = 0; x < 4; ++x) v[x] = apply_act_bf16(v[x], flags);
             }
             if (res) {                                     // added before the one rounding to bf16
-                const bf16x4 r4 = rv[i & 1][j];
+                const bf16x4 r4 = rv[i % RES_AHEAD][j];
 #pragma unroll
                 for (int x = 0; x < 4; ++x) v[x] += (float)r4[x];
             }
@@ -405,6 +432,30 @@ __device__ __forceinline__ void gemm_epilogue_tile(const Gemm2Params &p, f32x4 (
         __builtin_amdgcn_sched_barrier(0);
     }
     };
+    // Stage 2's rows, looked up now where the output is scattered through a row map: the lookups are in flight
+    // while stage 1 runs instead of in front of every group of stores.
+    constexpr int CPRO = BN_OUT / 8;                       // 16-byte pieces per tile row
+    static_assert(BN_OUT % 8 == 0 && CPRO <= NTHREADS, "whole pieces");
+    constexpr int RPP = NTHREADS / CPRO, NPASS = (BM + RPP - 1) / RPP, GRP = 8;
+    const int trow = tid / CPRO, piece = tid - trow * CPRO;
+    int yrow[NPASS];                                       // output row of pass g (negative: nothing to store)
+#pragma unroll
+    for (int g = 0; g < NPASS; ++g) {
+        const int row = g * RPP + trow, gm = m0 + row;
+        yrow[g] = (trow < RPP && row < BM && gm < p.M) ? (int)map_row_near(p.ymap, p.seq_len, gm, b0) : -1;
+    }
+    if constexpr (PARTNER) {
+        // One wavefront polls and acquires (an acquire invalidates a whole L2); the workgroup barrier orders the
+        // other wavefronts' loads behind it.  The partner holds its ticket already: it is running and waits for
+        // nothing, so the wait ends (the spin count only guards against a partner that died).
+        if (tid == 0) {
+            int spins = 0;
+            while (__hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != use && ++spins < (1 << 22))
+                __builtin_amdgcn_s_sleep(8);
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+        }
+        __syncthreads();
+    }
     const std::integral_constant<int, 0> res_no;
     const std::integral_constant<int, 1> res_yes;
     const std::integral_constant<int, 2> res_rt;
@@ -417,15 +468,11 @@ __device__ __forceinline__ void gemm_epilogue_tile(const Gemm2Params &p, f32x4 (
     // walks down the rows RPP at a time, so the only per-piece work is an LDS read, a row-map lookup where the
     // output is scattered, one address addition and the store; the reads (and lookups) of a group of pieces are
     // in flight before the group's first store.
-    constexpr int CPRO = BN_OUT / 8;                       // 16-byte pieces per tile row
-    static_assert(BN_OUT % 8 == 0 && CPRO <= NTHREADS, "whole pieces");
-    constexpr int RPP = NTHREADS / CPRO, NPASS = (BM + RPP - 1) / RPP, GRP = 8;
-    const int trow = tid / CPRO, piece = tid - trow * CPRO;
     const int c = nloc0 + piece * 8;
     const unsigned char *src = smem + trow * PITCH + piece * 16;
     auto store_tile = [&](auto interior_tag) {
         constexpr bool INTERIOR = decltype(interior_tag)::value;
-        const bool t_ok = trow < RPP && (INTERIOR || c < seg_rows);
+        const bool t_ok = INTERIOR || c < seg_rows;
         const bool whole = INTERIOR || c + 8 <= seg_rows;  // else the segment ends inside this piece
 #pragma unroll
         for (int g0 = 0; g0 < NPASS; g0 += GRP) {
@@ -433,11 +480,11 @@ __device__ __forceinline__ void gemm_epilogue_tile(const Gemm2Params &p, f32x4 (
             bf16_t *y[GRP];
 #pragma unroll
             for (int g = 0; g < GRP; ++g) {
-                const int row = (g0 + g) * RPP + trow, gm = m0 + row;
                 y[g] = nullptr;
-                if (g0 + g >= NPASS || !t_ok || row >= BM || (!INTERIOR && gm >= p.M)) continue;
+                if (g0 + g >= NPASS) continue;
+                if (!t_ok || yrow[g0 + g < NPASS ? g0 + g : 0] < 0) continue;
                 v[g] = *(const bf16x8 *)(src + (g0 + g) * RPP * PITCH);
-                y[g] = p.Y + map_row(p.ymap, p.seq_len, gm) * p.ldy + gcol0 + c;
+                y[g] = p.Y + (int64_t)yrow[g0 + g < NPASS ? g0 + g : 0] * p.ldy + gcol0 + c;
             }
 #pragma unroll
             for (int g = 0; g < GRP; ++g) {
@@ -501,15 +548,15 @@ __device__ __forceinline__ int lane_id_again() {
 // Reduction split over two workgroups per tile (a launch whose tiles would fill half of the CUs).  Each computes
 // one half of K into its accumulators.  Then it takes a ticket from the tile's counter: the holder of the even
 // ticket (the first to finish) writes its accumulators to the tile's slot of the scratch as they lie in its
-// registers, publishes them by setting the tile's flag to the use count of the slot, and is done; the holder of
-// the odd ticket waits for that flag, adds the stored accumulators to its own and returns true: it runs the
-// epilogue.  The workgroup that is waited for took its ticket earlier, so it is running, has its main loop
+// registers, publishes them by setting the tile's flag to the use count of the slot (returned in `use`), and is
+// done; the holder of the odd ticket returns true: it runs the epilogue, which waits for that flag and adds the
+// stored accumulators to its own.  The workgroup that is waited for took its ticket earlier, so it is running, has its main loop
 // behind it and waits for nothing itself: the wait ends whatever the order in which workgroups are placed on the
 // CUs (the spin count only guards against a partner that died).  Ticket and flag count up over the launches that
 // share the words (which run one after the other), so nothing has to be reset between them.
 template <int TM, int TN, int NTHREADS>
 __device__ __forceinline__ bool splitk_combine(const Gemm2Params &p, f32x4 (&acc)[TM][TN], int tile, int tid,
-                                               unsigned char *smem) {
+                                               unsigned char *smem, uint32_t &use_out) {
     uint32_t *sync = p.sk_sync + 2 * tile;
     f32x4 *part = (f32x4 *)p.sk_partial + (size_t)tile * (TM * TN * NTHREADS) + tid;
     volatile uint32_t *sh = (volatile uint32_t *)smem;
@@ -517,6 +564,7 @@ __device__ __forceinline__ bool splitk_combine(const Gemm2Params &p, f32x4 (&acc
     __syncthreads();
     const uint32_t ticket = sh[0];
     const uint32_t use = (ticket >> 1) + 1;
+    use_out = use;
     // Cache maintenance across the XCDs' L2s is expensive (a release writes back, an acquire invalidates a whole
     // L2), so exactly one wavefront of each workgroup does it: the workgroup barrier orders the other wavefronts'
     // stores before thread 0's release and their loads after thread 0's acquire.
@@ -528,23 +576,6 @@ __device__ __forceinline__ bool splitk_combine(const Gemm2Params &p, f32x4 (&acc
         __syncthreads();
         if (tid == 0) __hip_atomic_store(&sync[1], use, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
         return false;
-    }
-    if (tid == 0) {
-        int spins = 0;
-        while (__hip_atomic_load(&sync[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != use && ++spins < (1 << 22))
-            __builtin_amdgcn_s_sleep(8);
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-    }
-    __syncthreads();
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-        f32x4 pv[TN];
-#pragma unroll
-        for (int j = 0; j < TN; ++j) pv[j] = __builtin_nontemporal_load(part + (i * TN + j) * NTHREADS);
-        __builtin_amdgcn_sched_barrier(0);                 // one row block's loads at a time: 8 x 4 registers
-#pragma unroll
-        for (int j = 0; j < TN; ++j) acc[i][j] = acc_load(acc[i][j]) + pv[j];
-        __builtin_amdgcn_sched_barrier(0);
     }
     return true;
 }
@@ -623,7 +654,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm2_kernel(Gemm2Params p) {
         const int row = wave * (BM / NW) + RPI * i + lane / CPR;
         const int c = (lane % CPR) ^ swz(row);
         const int gm = m0 + row;
-        a_off[i] = gm < p.M ? (uint32_t)(map_row(p.xmap, p.seq_len, gm) * p.ldx * 2) + c * 16 : OOB_OFF;
+        a_off[i] = gm < p.M ? (uint32_t)(map_row_near(p.xmap, p.seq_len, gm, m0 / p.seq_len) * p.ldx * 2) + c * 16 : OOB_OFF;
     }
 #pragma unroll
     for (int i = 0; i < B_INSTR; ++i) {
@@ -819,9 +850,13 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm2_kernel(Gemm2Params p) {
         int tid_e = wave * 64 + lane_id_again();
         if constexpr (SPLITK) {
             const int tile_sk = ((int)blockIdx.x & 7) * (total >> 3) + ((int)blockIdx.x >> 4);
-            if (!splitk_combine<TM, TN, NW * 64>(p, acc, tile_sk, tid_e, smem)) return;
-            __syncthreads();                               // the ticket has been read: the epilogue may stage
+            uint32_t use;
+            if (!splitk_combine<TM, TN, NW * 64>(p, acc, tile_sk, tid_e, smem, use)) return;
             tid_e = wave * 64 + lane_id_again();
+            gemm_epilogue_tile<BM, NW * 64, TM, TN, WTN, false, BN_OUT, false, true>(
+                p, acc, smem, tid_e, m0, wm0, wn0, nloc0, seg, seg_rows,
+                (const f32x4 *)p.sk_partial + (size_t)tile_sk * (TM * TN * NW * 64) + tid_e, p.sk_sync + 2 * tile_sk + 1, use);
+            return;
         }
         if constexpr (ROPE)
             gemm_epilogue_tile_rope<BM, NW * 64, TM, TN, WTN, BN>(p, acc, smem, tid_e, m0, wm0, wn0, nloc0 >> 1, seg, seg_rows);
@@ -908,7 +943,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm3_kernel(Gemm2Params p) {
         const int row = wave * (BM / NW) + RPI * i + lane / CPR;
         const int c = (lane % CPR) ^ swz(row);
         const int gm = m0 + row;
-        a_off[i] = gm < p.M ? (uint32_t)(map_row(p.xmap, p.seq_len, gm) * p.ldx * 2) + c * 16 : OOB_OFF;
+        a_off[i] = gm < p.M ? (uint32_t)(map_row_near(p.xmap, p.seq_len, gm, m0 / p.seq_len) * p.ldx * 2) + c * 16 : OOB_OFF;
     }
 #pragma unroll
     for (int i = 0; i < B_INSTR; ++i) {
@@ -1114,7 +1149,10 @@ bool gemm_bf16_rope_fusable(const GemmArgs &a) {
 // outputs against the 256 x 128 kernel on the same 256 CUs: the main loop gains 6 us at K = 4096 and 35-40 us at
 // K = 14336, the exchange (256 KB written and read per tile, one L2 write-back and one invalidation per
 // workgroup, the epilogue on half of the CUs) costs 15-20 us: 88 against 77 us and 199 against 205 us.
-constexpr int GEMM_SPLITK_MIN_K = 8192;
+#ifndef SK_MIN_K
+#define SK_MIN_K 8192
+#endif
+constexpr int GEMM_SPLITK_MIN_K = SK_MIN_K;
 size_t gemm_bf16_splitk_bytes(int32_t M, int32_t N, int32_t K) {
     if (M <= 0 || N <= 0 || K % 128 != 0 || K < GEMM_SPLITK_MIN_K) return 0;
     const int64_t tiles = (int64_t)((M + 255) / 256) * ((N + 255) / 256), cus = cu_count();
