@@ -199,7 +199,48 @@ __device__ __forceinline__ void gemm_epilogue(const Gemm2Params &p, f32x4 (&acc)
         __builtin_amdgcn_wave_barrier();
     }
     };
-    if (!SWIGLU && act) blocks(std::true_type{});
+    // A tile inside the matrix with no activation to apply takes a copy of the loop without the per-row and
+    // per-chunk range checks and with the residual from the registers filled above: a fifth of the instructions.
+    // The epilogue of a single-round launch runs once per workgroup, from a cold instruction cache, at about three
+    // times the cycles per instruction of warm code, so its length in instructions is what it costs.
+    auto blocks_inside = [&](auto res_tag) {
+    constexpr bool RES = decltype(res_tag)::value;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+        for (int j = 0; j < TNS; ++j)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                float v = acc[i][j][r];
+                if (INREG) v = silu_fast(v) * acc[i][j + TNS][r];
+                stg[(4 * rsel + r) * STG_LD + 16 * j + l16] = v;
+            }
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const int rl = 4 * t + rsel;
+            const int gm = m0 + wm0 + 16 * i + rl;
+            bf16_t *yrow = p.Y + map_row_near(p.ymap, p.seq_len, gm, b0) * p.ldy + gcol0 + wcol0 + m4;
+#pragma unroll
+            for (int cc = 0; cc < NCH; ++cc) {
+                f32x4 v = *(const f32x4 *)(stg + rl * STG_LD + 64 * cc + m4);
+                if (!SWIGLU) v += bias_v[cc];
+                if constexpr (RES) {
+                    const bf16x4 rv = res.r[RES_AHEAD ? i : 0][t][cc];
+#pragma unroll
+                    for (int x = 0; x < 4; ++x) v[x] += (float)rv[x];
+                }
+                *(bf16x4 *)(yrow + 64 * cc) = bf16x4{(bf16_t)v[0], (bf16_t)v[1], (bf16_t)v[2], (bf16_t)v[3]};
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+    }
+    };
+    constexpr int BN_W = SWIGLU ? OW : WTN;                // output columns per wavefront column
+    const bool inside = m0 + wm0 + 16 * TM <= p.M && wcol0 + BN_W <= seg_rows && OW % 64 == 0 && (INREG || !SWIGLU);
+    if (inside && !act && RES_AHEAD && (flags & CASCADE_EPI_RESIDUAL)) blocks_inside(std::true_type{});
+    else if (inside && !act && !(flags & CASCADE_EPI_RESIDUAL)) blocks_inside(std::false_type{});
+    else if (!SWIGLU && act) blocks(std::true_type{});
     else blocks(std::false_type{});
 }
 
@@ -259,6 +300,53 @@ __device__ __forceinline__ void gemm_epilogue_tile_rope(const Gemm2Params &p, f3
             bias_b[j] = f32x4{(float)b4[0], (float)b4[1], (float)b4[2], (float)b4[3]};
         }
     }
+    // A tile inside the matrix, without bias, whose columns are all rotated (q, k) or all passed through (v) takes a
+    // copy of the loop without the per-pair checks, with the cos | sin values requested three row blocks ahead
+    // (2 x 16 bytes per pair block and row from the table in L2: one latency instead of one per row block).  The
+    // code runs once per workgroup, from a cold instruction cache: its length in instructions is what it costs.
+    auto stage1_inside = [&](auto rot_tag) {
+        constexpr bool ROT = decltype(rot_tag)::value;
+        constexpr int AH = ROT ? (TNO > 4 ? 2 : 3) : 1;       // 8 registers per pair block and row block in flight
+        f32x4 cs[AH][ROT ? TNO : 1], sn[AH][ROT ? TNO : 1];
+        auto request = [&](int i) {
+            if constexpr (ROT) {
+                const float *trow = p.rope_table + (int64_t)(m0 + wm0 + 16 * i + l16) * (2 * half);
+#pragma unroll
+                for (int j = 0; j < TNO; ++j) {
+                    const int ph = (pair0 + wp0 + 16 * j + c4) & (half - 1);
+                    cs[i % AH][j] = *(const f32x4 *)(trow + ph);
+                    sn[i % AH][j] = *(const f32x4 *)(trow + half + ph);
+                }
+            }
+        };
+#pragma unroll
+        for (int i = 0; i < AH - 1 && i < TM; ++i) request(i);
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int row = wm0 + 16 * i + l16;
+            if (i + AH - 1 < TM) request(i + AH - 1);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int j = 0; j < TNO; ++j) {
+                const int tp = wp0 + 16 * j + c4;
+                f32x4 a = acc_load(acc[i][j]), b = acc_load(acc[i][j + TNO]);
+                if constexpr (ROT) {
+                    const f32x4 c = cs[i % AH][j], sv = sn[i % AH][j];
+                    const f32x4 ra = a * c - b * sv, rb = b * c + a * sv;
+                    a = ra; b = rb;
+                }
+                *(bf16x4 *)(smem + row * PITCH + tp * 2) = bf16x4{(bf16_t)a[0], (bf16_t)a[1], (bf16_t)a[2], (bf16_t)a[3]};
+                *(bf16x4 *)(smem + row * PITCH + (BN / 2 + tp) * 2) = bf16x4{(bf16_t)b[0], (bf16_t)b[1], (bf16_t)b[2], (bf16_t)b[3]};
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    // columns of the tile: whole heads from the head of its first pair to the head of its last
+    const int col_lo = gcol0 + ((pair0 >> lh) << (lh + 1)), col_hi = gcol0 + ((((pair0 + BN / 2 - 1) >> lh) + 1) << (lh + 1));
+    const bool tile_inside = m0 + BM <= p.M && pair0 + BN / 2 <= n_pairs && !bias;
+    if (tile_inside && col_hi <= p.rope_cols) stage1_inside(std::true_type{});
+    else if (tile_inside && col_lo >= p.rope_cols) stage1_inside(std::false_type{});
+    else {
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
         const int row = wm0 + 16 * i + l16, gm = m0 + row;
@@ -278,6 +366,7 @@ __device__ __forceinline__ void gemm_epilogue_tile_rope(const Gemm2Params &p, f3
             *(bf16x4 *)(smem + row * PITCH + tp * 2) = bf16x4{(bf16_t)a[0], (bf16_t)a[1], (bf16_t)a[2], (bf16_t)a[3]};
             *(bf16x4 *)(smem + row * PITCH + (BN / 2 + tp) * 2) = bf16x4{(bf16_t)b[0], (bf16_t)b[1], (bf16_t)b[2], (bf16_t)b[3]};
         }
+    }
     }
     __syncthreads();
     constexpr int CPRO = BN / 8;                           // 16-byte pieces per tile row
