@@ -658,10 +658,14 @@ __device__ __forceinline__ bool splitk_combine(const Gemm2Params &p, f32x4 (&acc
     // L2), so exactly one wavefront of each workgroup does it: the workgroup barrier orders the other wavefronts'
     // stores before thread 0's release and their loads after thread 0's acquire.
     if ((ticket & 1u) == 0u) {
+        // stored straight from the accumulation registers (a vector-memory instruction takes them as data): this
+        // runs once, on the path the other workgroup waits for, and 256 register moves less is a third of it
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
-            for (int j = 0; j < TN; ++j) part[(i * TN + j) * NTHREADS] = acc_load(acc[i][j]);
+            for (int j = 0; j < TN; ++j)
+                asm volatile("global_store_dwordx4 %0, %1, off" ::"v"(part + (i * TN + j) * NTHREADS), "a"(acc[i][j]) : "memory");
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the compiler does not count those stores
         __syncthreads();
         if (tid == 0) __hip_atomic_store(&sync[1], use, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
         return false;
