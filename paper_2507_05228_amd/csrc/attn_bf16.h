@@ -73,7 +73,17 @@ struct AttnBf16Params {
     const int32_t *o_rowmap;
     int32_t hpb;          // heads per workgroup (1, 2 or 4)
     int32_t gy;           // (batch, kv head, head block) combinations: blockIdx.x = query tile * gy + combination
+    // the same decomposition by multiplications (fused kernel): heads = kv heads x head blocks, rep = H / Hkv,
+    // hblocks = rep / hpb, and the reciprocals of div_magic() for gy, heads and hblocks
+    int32_t hpb_log2, rep, hblocks, heads;
+    uint64_t gy_magic, heads_magic, hblocks_magic;
 };
+
+// floor(n / d) as a multiplication: magic = ceil(2^40 / d); exact while n d < 2^40 (and n / d < 2^23, so that the
+// product stays inside 64 bits)
+static inline uint64_t div_magic(uint32_t d) { return ((1ull << 40) + d - 1) / d; }
+static inline bool div_magic_covers(uint64_t n_max, uint32_t d) { return n_max * d < (1ull << 40) && n_max / d < (1ull << 23); }
+__device__ __forceinline__ uint32_t div_by_magic(uint32_t n, uint64_t magic) { return (uint32_t)(((uint64_t)n * magic) >> 40); }
 
 
 

@@ -603,12 +603,16 @@ static int32_t launch_attn_cfg(const cascade_plan *p, const AttnArgs &a, hipStre
     const int64_t gy = (int64_t)a.B * a.Hkv * (rep / hpb);
     if (gy * ql.count > INT32_MAX || S > 65535) return CASCADE_EUNSUPPORTED;
     k.gy = (int32_t)gy;
+    for (k.hpb_log2 = 0; (1 << k.hpb_log2) < hpb; ++k.hpb_log2) {}
+    k.rep = rep; k.hblocks = rep / hpb; k.heads = a.Hkv * k.hblocks;
+    k.gy_magic = div_magic((uint32_t)gy); k.heads_magic = div_magic((uint32_t)k.heads); k.hblocks_magic = div_magic((uint32_t)k.hblocks);
     // fused mode with full-size query tiles: the software-pipelined kernel (same tiles, same parameters; its mask
     // forms "query position - key position" in 32 bits: positions below 2^30 in magnitude)
     if (a.fused && NWV == 8 && p->max_abs_pos < (1 << 30) && kvp->max_abs_pos < (1 << 30)) {
         bool all_visible = a.mask_kind != CASCADE_MASK_CAUSAL;
         for (int j = 0; j < kvp->n_shards && all_visible; ++j)
             all_visible = (kvp->offsets_h[j + 1] - kvp->offsets_h[j]) % KV_TILE == 0;
+        if (!div_magic_covers((uint64_t)gy * ql.count, (uint32_t)gy)) return CASCADE_EUNSUPPORTED;
         return launch_attn_fused(k, D, ql.count, all_visible, split, s);
     }
     if (split) return CASCADE_EINVAL;

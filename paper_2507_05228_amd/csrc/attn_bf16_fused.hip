@@ -116,69 +116,81 @@ __global__ __launch_bounds__(1024 / TQ) void attn_fused_kernel(AttnBf16Params p)
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l16 = lane & 15, g4 = lane >> 4;
-    const int hpb = p.hpb;
-    const int hsel = wave % hpb, rg = wave / hpb;
-    const int rep = p.H / p.Hkv;
-    const int hblocks = rep / hpb;
-    const int q_tile = blockIdx.x / p.gy, by = blockIdx.x % p.gy;
-    const int b = by / (p.Hkv * hblocks);
-    const int gh = by % (p.Hkv * hblocks);
-    const int g = gh / hblocks;
-    const int h = g * rep + (gh % hblocks) * hpb + hsel;
+    // workgroup -> (query tile, batch, kv head, head block): multiplications by reciprocals the launcher made
+    // (a division by a kernel argument is ~25 scalar instructions, and there were seven in front of the first load)
+    const int hpb_log2 = SPLIT ? 2 : p.hpb_log2, hpb = 1 << hpb_log2;
+    const int hsel = wave & (hpb - 1), rg = wave >> hpb_log2;
+    const int rep = p.rep, hblocks = p.hblocks;
+    const int q_tile = (int)div_by_magic(blockIdx.x, p.gy_magic), by = (int)blockIdx.x - q_tile * p.gy;
+    const int b = (int)div_by_magic((uint32_t)by, p.heads_magic), gh = by - b * p.heads;
+    const int g = (int)div_by_magic((uint32_t)gh, p.hblocks_magic);
+    const int h = g * rep + (gh - g * hblocks) * hpb + hsel;
 
     const tile_cptr kvtiles = (tile_cptr)p.kvtiles;
     const tile_cptr qtp = (tile_cptr)p.qtiles + q_tile;
     const int q_row_start = qtp->row_start, q_n_rows = qtp->n_rows, q_pmax = qtp->pmax;
     const int wrow0 = SPLIT ? 0 : rg * 16 * TQ;       // SPLIT: both wavefront groups hold the query tile's 32 rows
 
-    // ---- query fragments (B operand of S^T = K Q^T): lane holds row l16 of each 16-row block, head-dim
-    //      chunk 32 ks + 8 g4
-    bf16x8 Q[TQ][KS];
-    int qlim[TQ];
+    // ---- Everything below up to the first barrier is one chain of dependent accesses per workgroup (tile entry ->
+    // row map -> query rows; tile entry -> visible tiles -> their entries -> K rows), so the requests of a level go
+    // out together and nothing is waited for in between: rows and limits first, then the tile list's smallest
+    // positions, then the query rows.
+    int qlim[TQ], q_src[TQ];
     bool row_ok[TQ];
 #pragma unroll
     for (int qb = 0; qb < TQ; ++qb) {
         const int rloc = wrow0 + 16 * qb + l16;
         row_ok[qb] = rloc < q_n_rows;
         const int r = q_row_start + (row_ok[qb] ? rloc : q_n_rows - 1);
-        const bf16_t *qp = p.q + b * p.qs_b + h * p.qs_h + (int64_t)(p.q_rowmap ? p.q_rowmap[r] : r) * p.qs_n + g4 * 8;
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            // scaled by scale * log2(e) here, once, so that the score product comes out in log2 units
-            const bf16x8 raw = *(const bf16x8 *)(qp + ks * 32);
-#pragma unroll
-            for (int x = 0; x < 8; ++x) Q[qb][ks][x] = (bf16_t)((float)raw[x] * p.scale_log2);
-            // (in its accumulation registers here and now, not by moves right in front of the first MFMA that reads it)
-            asm volatile("" : "+a"(Q[qb][ks]));
-        }
+        q_src[qb] = p.q_rowmap ? p.q_rowmap[r] : r;
         // without a mask: the largest position the launcher accepts, so that only the padding of ragged tiles
         // (position 2^30) is cut; every position is below 2^30 in magnitude
         qlim[qb] = p.causal ? p.pos_packed[r] : (1 << 30) - 1;
     }
-
-    // The smallest limit of this wavefront's queries: a key/value tile whose largest position is not above it (and
-    // that has no padding) is visible to every one of them, and its scores skip the mask.
-    int q_min;
-    {
-        int qm = qlim[0];
+    // visible key/value tiles: a prefix of the list ordered by smallest position; four groups of 64 entries a time
+    constexpr int VIS = 4;
+    int pm_first[VIS];
+    if (p.causal) {
 #pragma unroll
-        for (int qb = 1; qb < TQ; ++qb) qm = min(qm, qlim[qb]);
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) qm = min(qm, __shfl_xor(qm, off));
-        q_min = __builtin_amdgcn_readfirstlane(qm);
+        for (int c = 0; c < VIS; ++c) {
+            const int t = 64 * c + lane;
+            pm_first[c] = t < p.n_kvtiles ? p.kvtiles[t].pmin : INT_MAX;
+        }
     }
-    auto tile_needs_mask = [&](int tile_pmax, int tile_rows) { return tile_pmax > q_min || tile_rows < KV_TILE; };
 
-    // ---- visible key/value tiles: a prefix of the list ordered by smallest position
+    // ---- query fragments (B operand of S^T = K Q^T): lane holds row l16 of each 16-row block, head-dim
+    //      chunk 32 ks + 8 g4
+    bf16x8 q_raw[TQ][KS];
+#pragma unroll
+    for (int qb = 0; qb < TQ; ++qb) {
+        const bf16_t *qp = p.q + b * p.qs_b + h * p.qs_h + (int64_t)q_src[qb] * p.qs_n + g4 * 8;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) q_raw[qb][ks] = *(const bf16x8 *)(qp + ks * 32);
+    }
+
     int t_end = p.n_kvtiles;
     if (p.causal) {
         int n = 0;
-        for (int base = 0; base < p.n_kvtiles; base += 64) {
+#pragma unroll
+        for (int c = 0; c < VIS; ++c) n += __popcll(__ballot(pm_first[c] <= q_pmax));
+        for (int base = 64 * VIS; base < p.n_kvtiles; base += 64) {
             const int t = base + lane;
             n += __popcll(__ballot(t < p.n_kvtiles && p.kvtiles[t].pmin <= q_pmax));
         }
         t_end = __builtin_amdgcn_readfirstlane(n);
     }
+
+    // The smallest limit of this wavefront's queries: a key/value tile whose largest position is not above it (and
+    // that has no padding) is visible to every one of them, and its scores skip the mask.  From the tile entry's
+    // 16-row minima (rows past the tile's end: INT_MAX; their lanes compute on the last row's limit and write nothing).
+    int q_min = (1 << 30) - 1;
+    if (p.causal) {
+        q_min = qtp->sub_min[wrow0 / 16];
+#pragma unroll
+        for (int qb = 1; qb < TQ; ++qb) q_min = min(q_min, qtp->sub_min[wrow0 / 16 + qb]);
+    }
+    auto tile_needs_mask = [&](int tile_pmax, int tile_rows) { return tile_pmax > q_min || tile_rows < KV_TILE; };
+
     const int n_tiles = t_end;
 
     struct TileMeta {
@@ -232,6 +244,40 @@ __global__ __launch_bounds__(1024 / TQ) void attn_fused_kernel(AttnBf16Params p)
         for (int i = 0; i < V_INSTR; ++i)
             load16_to_lds(rv, sv + (wave * V_INSTR + i) * 8 * 128, v_tile + v_lane[i]);
     };
+
+    // ---- the first tiles are requested here, ahead of the wait for the query rows.  The four entries are read
+    // whatever the number of visible tiles (the index is clamped), so that they do not wait for that number.
+    TileMeta mt0, mt1, mt2, mt3;                       // tiles i .. i+3 (split walk: j and j + 1 of either group)
+    auto first_tiles = [&]() {
+        const TileMeta none = {0, 0, 0, INT_MAX};
+        const int last = p.n_kvtiles - 1;
+        const TileMeta a0 = load_meta(0), a1 = load_meta(min(1, last)), a2 = load_meta(min(2, last)), a3 = load_meta(min(3, last));
+        mt0 = 0 < n_tiles ? a0 : none;
+        mt1 = 1 < n_tiles ? a1 : none;
+        mt2 = 2 < n_tiles ? a2 : none;
+        mt3 = 3 < n_tiles ? a3 : none;
+        if constexpr (SPLIT) {                         // tiles 0 and 1 are the first of the two wavefront groups
+            if (0 < n_tiles) issue_k(mt0, 0);
+            if (1 < n_tiles) issue_k(mt1, 2);
+        } else {
+            if (0 < n_tiles) { issue_k(mt0, 0); issue_v(mt0, 0); }
+            if (1 < n_tiles) { issue_k(mt1, 1); issue_v(mt1, 1); }
+            if (2 < n_tiles) issue_k(mt2, 2);
+        }
+    };
+    first_tiles();
+
+    bf16x8 Q[TQ][KS];
+#pragma unroll
+    for (int qb = 0; qb < TQ; ++qb)
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            // scaled by scale * log2(e) here, once, so that the score product comes out in log2 units
+#pragma unroll
+            for (int x = 0; x < 8; ++x) Q[qb][ks][x] = (bf16_t)((float)q_raw[qb][ks][x] * p.scale_log2);
+            // (in its accumulation registers here and now, not by moves right in front of the first MFMA that reads it)
+            asm volatile("" : "+a"(Q[qb][ks]));
+        }
 
     // ---- state
     f32x4 O[TQ][DB];                                   // accumulation registers
@@ -449,8 +495,9 @@ __global__ __launch_bounds__(1024 / TQ) void attn_fused_kernel(AttnBf16Params p)
     constexpr int LPT_K = K_INSTR + 1, LPT_V = V_INSTR;
     static_assert(NST == 4, "stage arithmetic");
     volatile int *redo_flags = (volatile int *)(smem + NST * STAGE);   // one word per wavefront
-    for (;;) {                                         // one pass, unless an exponent offset had to move late
+    for (int pass = 0;; ++pass) {                      // one pass, unless an exponent offset had to move late
         redo = false;
+        if (pass > 0) first_tiles();
 #pragma unroll
         for (int qb = 0; qb < TQ; ++qb) {
             P[0][qb] = P[1][qb] = u32x4{0u, 0u, 0u, 0u};
@@ -470,14 +517,6 @@ __global__ __launch_bounds__(1024 / TQ) void attn_fused_kernel(AttnBf16Params p)
         const std::true_type refill;
         const std::false_type no_refill;
         if constexpr (!SPLIT) {
-        TileMeta mt0 = {0, 0, 0, INT_MAX}, mt1 = mt0, mt2 = mt0, mt3 = mt0;     // tiles i .. i+3
-        if (0 < n_tiles) mt0 = load_meta(0);
-        if (1 < n_tiles) mt1 = load_meta(1);
-        if (2 < n_tiles) mt2 = load_meta(2);
-        if (3 < n_tiles) mt3 = load_meta(3);
-        if (0 < n_tiles) { issue_k(mt0, 0); issue_v(mt0, 0); }
-        if (1 < n_tiles) { issue_k(mt1, 1); issue_v(mt1, 1); }
-        if (2 < n_tiles) issue_k(mt2, 2);
         phase_barrier<0, false>();                     // everything requested so far is complete and visible
         if (n_tiles > 0) {
 #pragma unroll
@@ -528,13 +567,7 @@ __global__ __launch_bounds__(1024 / TQ) void attn_fused_kernel(AttnBf16Params p)
         }
         const int n_g0 = (n_tiles + 1) / 2, n_g1 = n_tiles / 2;     // tiles of the two groups; n_g0 >= n_g1
         const int n_mine = rg == 0 ? n_g0 : n_g1, gst = 2 * rg;
-        TileMeta mv0 = {0, 0, 0, INT_MAX}, mk0 = mv0, mv1 = mv0, mk1 = mv0;   // tiles j and j + 1 of group 0, of group 1
-        if (0 < n_g0) mv0 = load_meta(0);
-        if (0 < n_g1) mv1 = load_meta(1);
-        if (1 < n_g0) mk0 = load_meta(2);
-        if (1 < n_g1) mk1 = load_meta(3);
-        if (0 < n_g0) issue_k(mv0, 0);
-        if (0 < n_g1) issue_k(mv1, 2);
+        TileMeta &mv0 = mt0, &mv1 = mt1, &mk0 = mt2, &mk1 = mt3;        // tiles j and j + 1 of group 0, of group 1
         for (int j = 0; j <= n_g0; ++j) {
             __builtin_amdgcn_sched_barrier(0);
             asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
@@ -576,36 +609,55 @@ __global__ __launch_bounds__(1024 / TQ) void attn_fused_kernel(AttnBf16Params p)
         if (!__builtin_amdgcn_readfirstlane(any_redo)) break;
     }
 
-    // ---- split walk: the second group hands its offsets, row sums and outputs to the first through LDS (the tile
-    // stages are free: everyone is past the last barrier of the pass); the offsets are integers, so bringing both
-    // to the larger one is exact.
+    // ---- split walk: each group keeps half of the head's columns (group 0 the first D/2, group 1 the rest), hands
+    // the other half with its offsets and row sums to its partner through LDS (the tile stages are free: everyone is
+    // past the last barrier of the pass), merges and writes its half; the offsets are integers, so bringing both to
+    // the larger one is exact.  Both groups form the merged row sum from the same operands in the same order.
     if constexpr (SPLIT) {
-        float *xch = (float *)smem + (wave % (NWV / 2)) * ((TQ * DB * 4 + 2 * TQ) * 64) + lane;
-        if (rg == 1) {
+        constexpr int HB = DB / 2, XW = TQ * HB * 4 + 2 * TQ;      // floats a wavefront hands over per lane
+        int o_row[TQ];
+#pragma unroll
+        for (int qb = 0; qb < TQ; ++qb) {
+            const int r = q_row_start + 16 * qb + l16;
+            o_row[qb] = p.o_rowmap && row_ok[qb] ? p.o_rowmap[r] : r;
+        }
+        auto finish_half = [&](auto g_tag) {
+            constexpr int G = decltype(g_tag)::value, KEEP = G * HB, GIVE = (1 - G) * HB;
+            float *mine = (float *)smem + ((wave % (NWV / 2)) * 2 + G) * (XW * 64) + lane;
+            const float *theirs = (const float *)smem + ((wave % (NWV / 2)) * 2 + 1 - G) * (XW * 64) + lane;
 #pragma unroll
             for (int qb = 0; qb < TQ; ++qb) {
 #pragma unroll
-                for (int db = 0; db < DB; ++db)
+                for (int d = 0; d < HB; ++d)
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) xch[((qb * DB + db) * 4 + r) * 64] = O[qb][db][r];
-                xch[(TQ * DB * 4 + qb) * 64] = L[qb][0];
-                xch[(TQ * DB * 4 + TQ + qb) * 64] = m_run[qb];
+                    for (int r = 0; r < 4; ++r) mine[((qb * HB + d) * 4 + r) * 64] = O[qb][GIVE + d][r];
+                mine[(TQ * HB * 4 + qb) * 64] = L[qb][0];
+                mine[(TQ * HB * 4 + TQ + qb) * 64] = m_run[qb];
             }
-        }
-        phase_barrier<-1, true>();
-        if (rg == 1) return;
+            phase_barrier<-1, true>();
 #pragma unroll
-        for (int qb = 0; qb < TQ; ++qb) {
-            const float m1 = xch[(TQ * DB * 4 + TQ + qb) * 64], l1 = xch[(TQ * DB * 4 + qb) * 64];
-            const float m = fmaxf(m_run[qb], m1);
-            const float f0 = m_run[qb] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m_run[qb] - m);
-            const float f1 = m1 == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m1 - m);
-            L[qb][0] = L[qb][0] * f0 + l1 * f1;
+            for (int qb = 0; qb < TQ; ++qb) {
+                if (!row_ok[qb]) continue;
+                const float m1 = theirs[(TQ * HB * 4 + TQ + qb) * 64], l1 = theirs[(TQ * HB * 4 + qb) * 64];
+                const float m = fmaxf(m_run[qb], m1);
+                const float f0 = m_run[qb] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m_run[qb] - m);
+                const float f1 = m1 == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m1 - m);
+                const float l_tot = G == 0 ? __builtin_fmaf(l1, f1, L[qb][0] * f0) : __builtin_fmaf(L[qb][0], f0, l1 * f1);
+                const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
+                const float s0 = f0 * inv, s1 = f1 * inv;
+                bf16_t *op = p.o + ((int64_t)b * p.N + o_row[qb]) * p.o_ld + (int64_t)h * D + 16 * KEEP + 4 * g4;
 #pragma unroll
-            for (int db = 0; db < DB; ++db)
+                for (int d = 0; d < HB; ++d) {
+                    f32x4 v;
 #pragma unroll
-                for (int r = 0; r < 4; ++r) O[qb][db][r] = O[qb][db][r] * f0 + xch[((qb * DB + db) * 4 + r) * 64] * f1;
-        }
+                    for (int r = 0; r < 4; ++r) v[r] = O[qb][KEEP + d][r] * s0 + theirs[((qb * HB + d) * 4 + r) * 64] * s1;
+                    *(bf16x4 *)(op + 16 * d) = bf16x4{(bf16_t)v[0], (bf16_t)v[1], (bf16_t)v[2], (bf16_t)v[3]};
+                }
+            }
+        };
+        if (rg == 0) finish_half(std::integral_constant<int, 0>{});
+        else finish_half(std::integral_constant<int, 1>{});
+        return;
     }
 
     // ---- write-out.  O[qb][db][r]: query row 16 qb + l16, column 16 db + 4 g4 + r; every row of L[qb] holds the
