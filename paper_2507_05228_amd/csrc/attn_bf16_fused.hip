@@ -605,7 +605,7 @@ __global__ __launch_bounds__(1024 / TQ) void attn_fused_kernel(AttnBf16Params p)
         int any_redo = 0;
 #pragma unroll
         for (int w = 0; w < NWV; ++w) any_redo |= redo_flags[w];
-        phase_barrier<-1, true>();
+        // (no barrier behind the reads: a flag is written again only at the end of another pass, many barriers away)
         if (!__builtin_amdgcn_readfirstlane(any_redo)) break;
     }
 
@@ -643,7 +643,7 @@ __global__ __launch_bounds__(1024 / TQ) void attn_fused_kernel(AttnBf16Params p)
                 const float f0 = m_run[qb] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m_run[qb] - m);
                 const float f1 = m1 == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m1 - m);
                 const float l_tot = G == 0 ? __builtin_fmaf(l1, f1, L[qb][0] * f0) : __builtin_fmaf(L[qb][0], f0, l1 * f1);
-                const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
+                const float inv = l_tot > 0.f ? __builtin_amdgcn_rcpf(l_tot) : 0.f;
                 const float s0 = f0 * inv, s1 = f1 * inv;
                 bf16_t *op = p.o + ((int64_t)b * p.N + o_row[qb]) * p.o_ld + (int64_t)h * D + 16 * KEEP + 4 * g4;
 #pragma unroll
@@ -667,7 +667,7 @@ __global__ __launch_bounds__(1024 / TQ) void attn_fused_kernel(AttnBf16Params p)
         if (!row_ok[qb]) continue;
         const float l_tot = L[qb][0];
         const int r = q_row_start + wrow0 + 16 * qb + l16;
-        const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
+        const float inv = l_tot > 0.f ? __builtin_amdgcn_rcpf(l_tot) : 0.f;
         bf16_t *op = p.o + ((int64_t)b * p.N + (p.o_rowmap ? p.o_rowmap[r] : r)) * p.o_ld + (int64_t)h * D + 4 * g4;
 #pragma unroll
         for (int db = 0; db < DB; ++db) {

@@ -76,3 +76,29 @@ __device__ __forceinline__ int64_t map_row_near(const int32_t *map, int32_t seq_
     if ((uint32_t)off < (uint32_t)seq_len) return (int64_t)b_hint * seq_len + map[off];
     return map_row(map, seq_len, r);
 }
+// N rows of one tile at once (a negative r[i] passes through).  map_row_near has three ways out, so a sequence of
+// calls compiles to a branch, a load and a wait per row, one memory round trip each (16 rows: most of an epilogue
+// that runs once); here the lookups of a wavefront whose rows all lie in sequence b_hint go out back to back.
+template <int N>
+__device__ __forceinline__ void map_rows_near(const int32_t *map, int32_t seq_len, const int32_t (&r)[N], int32_t b_hint,
+                                              int32_t (&out)[N]) {
+    if (!map) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) out[i] = r[i];
+        return;
+    }
+    const int32_t base = b_hint * seq_len;
+    bool near = true;
+#pragma unroll
+    for (int i = 0; i < N; ++i) near &= r[i] < 0 || (uint32_t)(r[i] - base) < (uint32_t)seq_len;
+    if (__all(near)) {
+        int32_t v[N];
+#pragma unroll
+        for (int i = 0; i < N; ++i) v[i] = map[r[i] < 0 ? 0 : r[i] - base];
+#pragma unroll
+        for (int i = 0; i < N; ++i) out[i] = r[i] < 0 ? r[i] : base + v[i];
+    } else {
+#pragma unroll
+        for (int i = 0; i < N; ++i) out[i] = r[i] < 0 ? r[i] : (int32_t)map_row(map, seq_len, r[i]);
+    }
+}

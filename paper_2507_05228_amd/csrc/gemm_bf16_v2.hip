@@ -90,12 +90,21 @@ struct ResidualAhead {
         const int wcol0 = SWIGLU ? nloc0 + (wn0 / WTN) * OW : nloc0 + wn0;
         const int gcol0 = p.seg_col0[seg];
         const int b0 = m0 / p.seq_len;                     // sequence of the tile's first row (uniform)
+        int32_t rows[TM * 4], src[TM * 4];                 // every row's lookup goes out before the first residual load
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
                 const int gm = m0 + wm0 + 16 * i + 4 * t + rsel;
-                const bf16_t *rrow = p.residual + map_row_near(p.rmap, p.seq_len, gm < p.M ? gm : 0, b0) * p.ldres + gcol0;
+                rows[4 * i + t] = gm < p.M ? gm : m0;
+            }
+        map_rows_near(p.rmap, p.seq_len, rows, b0, src);
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const int gm = m0 + wm0 + 16 * i + 4 * t + rsel;
+                const bf16_t *rrow = p.residual + (int64_t)src[4 * i + t] * p.ldres + gcol0;
 #pragma unroll
                 for (int cc = 0; cc < NCH; ++cc) {
                     const int c = wcol0 + 64 * cc + m4;
