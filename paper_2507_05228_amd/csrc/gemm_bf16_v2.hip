@@ -1250,11 +1250,8 @@ bool gemm_bf16_rope_fusable(const GemmArgs &a) {
 // exchange (one segment of plain columns assumed: N is the output width).  Measured on MI355X at 2048 x 4096
 // outputs against the 256 x 128 kernel on the same 256 CUs: the main loop gains 6 us at K = 4096 and 35-40 us at
 // K = 14336, the exchange (256 KB written and read per tile, one L2 write-back and one invalidation per
-// workgroup, the epilogue on half of the CUs) costs 15-20 us: 88 against 77 us and 199 against 205 us.
-#ifndef SK_MIN_K
-#define SK_MIN_K 8192
-#endif
-constexpr int GEMM_SPLITK_MIN_K = SK_MIN_K;
+// workgroup, the epilogue on half of the CUs) costs 15-20 us: 81 against 70 us and 195 against 205 us.
+constexpr int GEMM_SPLITK_MIN_K = 8192;
 size_t gemm_bf16_splitk_bytes(int32_t M, int32_t N, int32_t K) {
     if (M <= 0 || N <= 0 || K % 128 != 0 || K < GEMM_SPLITK_MIN_K) return 0;
     const int64_t tiles = (int64_t)((M + 255) / 256) * ((N + 255) / 256), cus = cu_count();
