@@ -44,25 +44,39 @@ __global__ __launch_bounds__(256) void vtranspose_kernel(const bf16_t *__restric
     const int r0 = kvtiles[t].row_start, nr = kvtiles[t].n_rows;
     const bf16_t *vb = v + b * vs_b + g * vs_h;
     constexpr int CPR = D / 8;
+    // The tile's rows: every thread takes the same (row, 16-byte chunk) pairs of K and of V.  All row-map lookups go
+    // out first, then all loads: two memory round trips per workgroup instead of two per pair (a 16 MB pass that took
+    // 8 us with the lookups and loads of a pair chasing each other).
+    constexpr int IT = 64 * CPR / 256;
+    static_assert(64 * CPR % 256 == 0, "whole passes");
+    int rr_[IT], ch_[IT];
+    int64_t src[IT];
+#pragma unroll
+    for (int i = 0; i < IT; ++i) {
+        const int id = threadIdx.x + 256 * i;
+        rr_[i] = id / CPR; ch_[i] = id % CPR;
+        const int r = r0 + (rr_[i] < nr ? rr_[i] : 0);
+        src[i] = rowmap ? rowmap[r] : r;
+    }
     // On the side (kp given; k has v's strides): the tile's K rows into packed order, kp[b][g][r][D], for callers
     // whose K is in another row order, so that the attention kernel's tile loads never chase a row map.
+    bf16x8 kval[IT], vval[IT];
     if (kp) {
         const bf16_t *kb = k + b * vs_b + g * vs_h;
-        for (int id = threadIdx.x; id < nr * CPR; id += 256) {
-            const int rr = id / CPR, ch = id % CPR, r = r0 + rr;
-            *(bf16x8 *)(kp + (((int64_t)b * Hkv + g) * N + r) * D + ch * 8) =
-                *(const bf16x8 *)(kb + (int64_t)rowmap[r] * vs_n + ch * 8);
-        }
-    }
-    for (int id = threadIdx.x; id < 64 * CPR; id += 256) {
-        int rr = id / CPR, ch = id % CPR;
-        bf16x8 val = {0, 0, 0, 0, 0, 0, 0, 0};
-        if (rr < nr) {
-            int r = r0 + rr;
-            val = *(const bf16x8 *)(vb + (int64_t)(rowmap ? rowmap[r] : r) * vs_n + ch * 8);
-        }
 #pragma unroll
-        for (int i = 0; i < 8; ++i) tile[rr][ch * 8 + i] = val[i];
+        for (int i = 0; i < IT; ++i) kval[i] = *(const bf16x8 *)(kb + src[i] * vs_n + ch_[i] * 8);
+    }
+#pragma unroll
+    for (int i = 0; i < IT; ++i) vval[i] = *(const bf16x8 *)(vb + src[i] * vs_n + ch_[i] * 8);
+    if (kp) {
+#pragma unroll
+        for (int i = 0; i < IT; ++i)
+            if (rr_[i] < nr) *(bf16x8 *)(kp + (((int64_t)b * Hkv + g) * N + r0 + rr_[i]) * D + ch_[i] * 8) = kval[i];
+    }
+#pragma unroll
+    for (int i = 0; i < IT; ++i) {
+#pragma unroll
+        for (int x = 0; x < 8; ++x) tile[rr_[i]][ch_[i] * 8 + x] = rr_[i] < nr ? vval[i][x] : (bf16_t)0.f;
     }
     __syncthreads();
     bf16_t *ob = vt + ((int64_t)b * Hkv + g) * D * npad + (int64_t)t * 64;
