@@ -77,9 +77,12 @@ SMALL_GQA2 = CONFIGS["C3"].with_(name="fa-gqa2", d_model=256, n_heads=4, n_kv_he
                                  batch=2, seq_len=520, n_shards=9, index=43)
 SMALL_F32 = CONFIGS["C3"].with_(name="fa-f32", dtype="f32", d_model=96, n_heads=6, n_kv_heads=2, head_dim=16,
                                 d_ff=96, seq_len=200, n_shards=5, index=44)
+# four query heads per key/value head at head dimension 64, one round of workgroups: the split walk's 64-wide kernel
+SMALL64_GQA4 = CONFIGS["C3"].with_(name="fa-llama64-gqa4", d_model=512, n_heads=8, n_kv_heads=2, head_dim=64, d_ff=256,
+                                   batch=2, seq_len=600, n_shards=5, index=57)
 
 
-@pytest.mark.parametrize("cfg", [SMALL, SMALL64, SMALL_GQA2, SMALL_F32], ids=lambda c: c.name)
+@pytest.mark.parametrize("cfg", [SMALL, SMALL64, SMALL_GQA2, SMALL64_GQA4, SMALL_F32], ids=lambda c: c.name)
 @pytest.mark.parametrize("kind", ["perm", "contiguous", "roundrobin", "ragged"])
 @pytest.mark.parametrize("mode", ["fused", "materialised"])
 def test_attention_output_every_row_and_head(cas, cfg, kind, mode):
