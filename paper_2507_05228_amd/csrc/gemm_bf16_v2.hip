@@ -851,6 +851,11 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm2_kernel(Gemm2Params p) {
 #pragma unroll
     for (int s = 0; s < NST - 1; ++s)
         if (s < KT) issue_loads(s, s);
+    // One wavefront per SIMD: its A and B stages hold two tiles apart from the one being multiplied, so the second
+    // k-tile is requested right behind the first (requested only once the first had landed, its latency sat in
+    // front of the first barrier of every output tile).
+    if constexpr (SOLO)
+        if (1 < KT) issue_loads(1, 1);
     // (the accumulators are cleared while the first tile loads are in flight: up to 256 register writes)
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -863,7 +868,10 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm2_kernel(Gemm2Params p) {
     // the widest tile (256 columns: 128 accumulator + 96 operand registers) would spill with them and
     // keeps one k-step's reads directly ahead of its own MFMAs instead.
     constexpr bool PIPE = 4 * TM * TN + 8 * (TM + TN) <= 216;
-    tile_ready(0);
+    if constexpr (SOLO) {                                          // tile 0 has landed; tile 1 may be on its way
+        if (1 < KT) wait_loads_and_barrier<LPT>();
+        else wait_loads_and_barrier<0>();
+    } else tile_ready(0);
     if constexpr (SOLO) {
         // One wavefront per SIMD: nothing else covers this wavefront's waits, so every memory operation
         // is placed between two MFMAs of the k-step that runs meanwhile.  Tile kt, first k-step: its
