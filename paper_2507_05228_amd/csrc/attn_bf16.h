@@ -83,7 +83,7 @@ struct AttnBf16Params {
 // product stays inside 64 bits)
 static inline uint64_t div_magic(uint32_t d) { return ((1ull << 40) + d - 1) / d; }
 static inline bool div_magic_covers(uint64_t n_max, uint32_t d) { return n_max * d < (1ull << 40) && n_max / d < (1ull << 23); }
-__device__ __forceinline__ uint32_t div_by_magic(uint32_t n, uint64_t magic) { return (uint32_t)(((uint64_t)n * magic) >> 40); }
+__host__ __device__ __forceinline__ uint32_t div_by_magic(uint32_t n, uint64_t magic) { return (uint32_t)(((uint64_t)n * magic) >> 40); }
 
 
 

@@ -29,3 +29,21 @@ def test_plan_host_code_under_asan_and_ubsan(tmp_path):
     assert run.returncode == 0, (run.stdout[-2000:], run.stderr[-3000:])
     assert "HOST_SANITIZER_OK" in run.stdout
     assert "ERROR: AddressSanitizer" not in run.stderr and "runtime error" not in run.stderr
+
+
+def test_reciprocal_division_of_the_attention_launcher_is_exact(tmp_path):
+    """The fused attention kernel turns its workgroup index into (query tile, batch, head block) with multiplications
+    by reciprocals the launcher computes; the launcher refuses grids outside the range where that is exact.  Checked on
+    the host against the integer division, exhaustively for small indices and around every multiple of the divisor near
+    the admitted maximum."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    if not os.path.exists(hipcc):
+        pytest.skip("hipcc not available")
+    exe = tmp_path / "div_magic"
+    cmd = [hipcc, "--offload-arch=gfx950", "-x", "hip", "-O1", "-std=c++17",
+           os.path.join(HERE, "div_magic_main.cpp"), "-o", str(exe)]
+    build = subprocess.run(cmd, capture_output=True, text=True)
+    assert build.returncode == 0, build.stderr[-3000:]
+    run = subprocess.run([str(exe)], capture_output=True, text=True, timeout=300)
+    assert run.returncode == 0, (run.stdout[-2000:], run.stderr[-2000:])
+    assert "DIV_MAGIC_OK" in run.stdout
